@@ -1,0 +1,159 @@
+/*
+ * kmv — dense matrix-vector products for AMD Instinct MI355X (gfx950).
+ *
+ * C ABI of the library.  Every product is the BLAS level-2 operation of the
+ * paper's Section 5.2 ("Routines and APIs"):
+ *
+ *        y  <-  alpha * op(A) * x  +  beta * y
+ *
+ * with A general (GEMV; the non-transposed and transposed kernels of
+ * Section 6.1) or symmetric / Hermitian with ONE stored triangle (SYMV for
+ * s,d and HEMV for c,z; Sections 6.1, 6.5 and 7: only the upper or only the
+ * lower triangle is read).  The argument lists are the standard column-major
+ * BLAS ones, which the paper's routines follow (Section 5.2), followed by a
+ * caller-owned workspace and a stream (the paper's "_async" variants,
+ * Section 5.2, take the stream as an extra last argument as well).
+ *
+ * Memory and ownership
+ *   A, x, y, workspace : DEVICE pointers, owned by the caller, valid until
+ *                        the work enqueued on `stream` has completed.
+ *   alpha, beta        : HOST pointers, read before the call returns.
+ *   stream             : a hipStream_t passed as void* (NULL = null stream).
+ *   Calls only enqueue kernels: no allocation, no host synchronisation, no
+ *   hidden global state.  A and x must not overlap y or the workspace.
+ *   Concurrent calls must use distinct workspaces.
+ *
+ * Layout (Section 5.3, single-GPU routines)
+ *   A is column major: element (i,j) is A[i + j*lda], lda >= max(1, rows).
+ *   A may point anywhere inside a larger matrix (a sub-block at arbitrary
+ *   row / column offsets, Section 6.6): the kernels derive the 128-byte
+ *   alignment of the columns from the pointer value and lda, start their
+ *   row tiles on the aligned boundary and mask the leading rows, so no
+ *   separate "_offset" interface is needed.  No byte outside the m x n
+ *   block (GEMV) or outside the stored triangle (SYMV/HEMV) is ever read.
+ *   Complex numbers are interleaved (re, im) pairs.
+ *   Vectors: element k of a length-len vector with increment inc is
+ *   v[k*inc] for inc > 0 and v[(k-(len-1))*inc] for inc < 0 (reference BLAS).
+ *
+ * Semantics of special values (reference-BLAS conventions)
+ *   m == 0 or n == 0, or (alpha == 0 and beta == 1): nothing is enqueued.
+ *   alpha == 0 : A and x are not read,  y <- beta*y.
+ *   beta  == 0 : y is not read (NaN / Inf in y do not propagate).
+ *   HEMV ignores the imaginary part of the diagonal of A.
+ *
+ * Return value
+ *   0                    success (work enqueued)
+ *   -k                   the k-th BLAS argument is illegal, numbered as the
+ *                        reference BLAS numbers them
+ *                          GEMV     : trans 1, m 2, n 3, lda 6, incx 8, incy 11
+ *                          SYMV/HEMV: uplo 1, n 2, lda 5, incx 7, incy 10
+ *   KMV_ERR_WORKSPACE    workspace is NULL or smaller than the size the
+ *                        matching *_workspace_bytes call reports
+ *   KMV_ERR_NULL         A, x, y, alpha or beta is NULL
+ *   KMV_ERR_HIP + e      the HIP runtime reported error e at launch
+ *   On any error nothing is enqueued and y is untouched.
+ *
+ * Determinism: for fixed arguments (including the alignment of A modulo 128
+ * bytes) and fixed tuning values the result is bitwise reproducible; partial
+ * sums of different workgroups meet in a workspace and are added in a fixed
+ * order (no floating-point atomics).
+ */
+#ifndef KMV_H
+#define KMV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct { float re, im; } kmv_complex64;
+typedef struct { double re, im; } kmv_complex128;
+
+#define KMV_OK 0
+#define KMV_ERR_WORKSPACE 1001
+#define KMV_ERR_NULL 1002
+#define KMV_ERR_HIP 2000
+
+/* ---- GEMV: y <- alpha*op(A)*x + beta*y,  A is m x n (Section 6.1, kernels 1
+ * and 2; Algorithms "Non-transposed GEMV" and "Transposed GEMV").
+ * trans: 'N' op(A)=A (x has n, y has m elements); 'T' op(A)=A^T; 'C'
+ * op(A)=A^H (x has m, y has n elements); lower case accepted; for the real
+ * precisions 'C' is the same as 'T'. */
+int kmv_sgemv(char trans, int64_t m, int64_t n, const float* alpha, const float* A, int64_t lda,
+              const float* x, int64_t incx, const float* beta, float* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_dgemv(char trans, int64_t m, int64_t n, const double* alpha, const double* A, int64_t lda,
+              const double* x, int64_t incx, const double* beta, double* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_cgemv(char trans, int64_t m, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+              const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zgemv(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+              const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- SYMV (real symmetric) and HEMV (complex Hermitian): A is n x n and only
+ * its `uplo` triangle ('L' or 'U', lower case accepted) is read (Section 6.1
+ * kernel 3, Section 6.5 for the diagonal blocks, Algorithm "Upper/Lower
+ * SYMV/HEMV").  Each stored off-diagonal element is read once and used for
+ * both a_ij*x_j and op(a_ij)*x_i. */
+int kmv_ssymv(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda,
+              const float* x, int64_t incx, const float* beta, float* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_dsymv(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda,
+              const double* x, int64_t incx, const double* beta, double* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_chemv(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+              const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zhemv(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+              const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Workspace sizes (bytes; an upper bound valid for every pointer
+ * alignment, every increment and every tuning value).  prec is 's','d','c'
+ * or 'z'.  The workspace holds the packed copy of a strided x and the
+ * per-workgroup partial sums that the final pass adds in a fixed order (the
+ * deterministic replacement of the atomic accumulation of Section 6.2).
+ * The pointer passed as workspace must be 256-byte aligned.  Returns 0 for
+ * an unknown prec or a negative dimension. */
+size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n);
+size_t kmv_symv_workspace_bytes(char prec, char uplo, int64_t n);
+
+/* ---- Work partition of Section 6.2 (Eqs. local_workload and starting_point,
+ * read with W in place of the misprinted d): share `w` and first item `s` of
+ * worker `y` when `W` items are split over `Y` workers in contiguous,
+ * balanced pieces.  Host-only helper, exported so that its invariants
+ * (shares sum to W, pieces are contiguous, sizes differ by at most one) can
+ * be tested; the kernels use the same formula for their row / column /
+ * tile splits. */
+void kmv_partition(int64_t W, int64_t Y, int64_t y, int64_t* w, int64_t* s);
+
+/* ---- Bandwidth probe (the STREAM measurement of Section 7 that defines the
+ * sustained bandwidth of the roofline): enqueues one pass of
+ *   kind 0 "read"  : sum-reduce a[0..n)   (reads  n*8 bytes)
+ *   kind 1 "copy"  : b[i] = a[i]          (moves 2*n*8 bytes)
+ *   kind 2 "triad" : c[i] = a[i] + s*b[i] (moves 3*n*8 bytes)
+ * over n doubles.  a, b, c: device pointers to n doubles each (b, c may be
+ * NULL for kind 0; c for kind 1); `sink` a device pointer to at least 8192
+ * doubles (kind 0 writes per-workgroup sums there).  Returns 0 or an error
+ * code as above. */
+int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c, double* sink, void* stream);
+
+/* ---- Tuning values for sweeps (Section 9: the tuning parameters are kept
+ * apart from the kernel templates).  Keys are listed by kmv_tuning_keys()
+ * as a comma separated string; kmv_set_tuning returns 0, or -1 for an
+ * unknown key or a value outside the compiled set.  Process-wide; not
+ * thread safe against concurrent calls. */
+int kmv_set_tuning(const char* key, int64_t value);
+int64_t kmv_get_tuning(const char* key);
+const char* kmv_tuning_keys(void);
+
+const char* kmv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KMV_H */

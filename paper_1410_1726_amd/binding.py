@@ -1,0 +1,206 @@
+"""Thin ctypes binding of ``libkmv.so`` (argument marshalling only).
+
+Every function has the name and argument order of its C entry point in
+``include/kmv.h`` minus the ``kmv_`` prefix.  Matrices and vectors are torch
+tensors on the GPU (only ``data_ptr()`` is used, so views that point into the
+middle of a larger matrix work as sub-block pointers) or raw integer device
+addresses; the workspace and the stream come from torch as well.  No step of
+a product runs in Python or in torch: if the HIP library is missing the import
+of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkmv.so")
+
+ERR_WORKSPACE = 1001
+ERR_NULL = 1002
+ERR_HIP = 2000
+
+
+class KmvError(RuntimeError):
+    def __init__(self, name, code):
+        super().__init__(f"kmv_{name} returned {code}")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1410_1726_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ch, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_char, ctypes.c_int, ctypes.c_size_t
+    gemv_args = [ch, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64, vp, sz, vp]
+    symv_args = [ch, i64, vp, vp, i64, vp, i64, vp, vp, i64, vp, sz, vp]
+    for p in "sdcz":
+        f = getattr(lib, f"kmv_{p}gemv")
+        f.argtypes, f.restype = gemv_args, ci
+    for name in ("ssymv", "dsymv", "chemv", "zhemv"):
+        f = getattr(lib, f"kmv_{name}")
+        f.argtypes, f.restype = symv_args, ci
+    lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
+    lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
+    lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.kmv_partition.restype = None
+    lib.kmv_stream_probe.argtypes, lib.kmv_stream_probe.restype = [ci, i64, vp, vp, vp, vp, vp], ci
+    lib.kmv_set_tuning.argtypes, lib.kmv_set_tuning.restype = [ctypes.c_char_p, i64], ci
+    lib.kmv_get_tuning.argtypes, lib.kmv_get_tuning.restype = [ctypes.c_char_p], i64
+    lib.kmv_tuning_keys.restype = ctypes.c_char_p
+    lib.kmv_version.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+_CT = {"s": ctypes.c_float, "d": ctypes.c_double}
+_TORCH = {"s": torch.float32, "d": torch.float64, "c": torch.complex64, "z": torch.complex128}
+
+
+def _scalar(prec, v):
+    """Host storage of alpha / beta in the element type of the routine."""
+    if prec in "sd":
+        return (_CT[prec] * 1)(float(v))
+    v = complex(v)
+    return ((ctypes.c_float if prec == "c" else ctypes.c_double) * 2)(v.real, v.imag)
+
+
+def _ptr(t, prec=None):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if prec is not None and t.dtype != _TORCH[prec]:
+        raise TypeError(f"expected {_TORCH[prec]}, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError("kmv works on device memory only")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+_ws_cache: dict = {}
+
+
+def workspace(nbytes: int, device=None) -> torch.Tensor:
+    """Grow-only per-device byte buffer (torch owns the memory)."""
+    dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+    buf = _ws_cache.get(dev)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
+        _ws_cache[dev] = buf
+    return buf
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+def gemv_workspace_bytes(prec, trans, m, n) -> int:
+    return int(lib.kmv_gemv_workspace_bytes(prec.encode(), trans.encode(), m, n))
+
+
+def symv_workspace_bytes(prec, uplo, n) -> int:
+    return int(lib.kmv_symv_workspace_bytes(prec.encode(), uplo.encode(), n))
+
+
+def _ws_args(workspace_, need, y):
+    """(pointer, bytes) of the workspace: None -> cached torch buffer of `need()`
+    bytes, a tensor -> its storage, a (pointer, bytes) tuple -> as given."""
+    if workspace_ is None:
+        workspace_ = workspace(need(), None if isinstance(y, int) else y.device)
+    if isinstance(workspace_, tuple):
+        return workspace_
+    return workspace_.data_ptr(), workspace_.numel() * workspace_.element_size()
+
+
+def _gemv(prec, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace_=None, stream=None, check=True):
+    wsp, wsb = _ws_args(workspace_, lambda: gemv_workspace_bytes(
+        prec, trans if trans in tuple("NnTtCc") else "N", max(m, 0), max(n, 0)), y)
+    al, be = _scalar(prec, alpha), _scalar(prec, beta)
+    rc = getattr(lib, f"kmv_{prec}gemv")(trans.encode(), m, n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be,
+                                         _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
+    if check and rc != 0:
+        raise KmvError(f"{prec}gemv", rc)
+    return rc
+
+
+def _symv(name, prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace_=None, stream=None, check=True):
+    wsp, wsb = _ws_args(workspace_, lambda: symv_workspace_bytes(
+        prec, uplo if uplo in tuple("LlUu") else "L", max(n, 0)), y)
+    al, be = _scalar(prec, alpha), _scalar(prec, beta)
+    rc = getattr(lib, f"kmv_{name}")(uplo.encode(), n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be,
+                                     _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
+    if check and rc != 0:
+        raise KmvError(name, rc)
+    return rc
+
+
+def sgemv(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _gemv("s", trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def dgemv(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _gemv("d", trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def cgemv(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _gemv("c", trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def zgemv(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _gemv("z", trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def ssymv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _symv("ssymv", "s", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def dsymv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _symv("dsymv", "d", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def chemv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _symv("chemv", "c", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def zhemv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _symv("zhemv", "z", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+GEMV = {"s": sgemv, "d": dgemv, "c": cgemv, "z": zgemv}
+SYMV = {"s": ssymv, "d": dsymv, "c": chemv, "z": zhemv}   # HEMV for the complex precisions
+
+
+def partition(W, Y, y):
+    w, s = ctypes.c_int64(), ctypes.c_int64()
+    lib.kmv_partition(W, Y, y, ctypes.byref(w), ctypes.byref(s))
+    return w.value, s.value
+
+
+def stream_probe(kind, n, a, b=None, c=None, sink=None, stream=None):
+    rc = lib.kmv_stream_probe(kind, n, _ptr(a), _ptr(b), _ptr(c), _ptr(sink), _stream(stream))
+    if rc != 0:
+        raise KmvError("stream_probe", rc)
+
+
+def set_tuning(key, value):
+    if lib.kmv_set_tuning(key.encode(), int(value)) != 0:
+        raise ValueError(f"bad tuning {key}={value}")
+
+
+def get_tuning(key):
+    return int(lib.kmv_get_tuning(key.encode()))
+
+
+def tuning_keys():
+    return lib.kmv_tuning_keys().decode().split(",")
+
+
+def version():
+    return lib.kmv_version().decode()

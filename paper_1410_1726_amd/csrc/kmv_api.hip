@@ -1,0 +1,227 @@
+// C ABI of the kmv library: argument checks, quick returns, workspace layout
+// and the choice of kernels.  Nothing here synchronises with the device or
+// allocates memory; every call only enqueues kernels on the caller's stream.
+// The routines follow the standard BLAS argument lists, as the paper's
+// routines do (Section 5.2), with the stream of its "_async" variants.
+#include <string.h>
+
+#include "../../include/kmv.h"
+#include "kmv_launch.hpp"
+
+namespace kmv {
+
+Tuning& tuning() {
+    static Tuning t;
+    return t;
+}
+
+namespace {
+
+inline int hip_code(hipError_t e) { return e == hipSuccess ? KMV_OK : KMV_ERR_HIP + (int)e; }
+
+// first storage position of a strided vector (reference-BLAS rule for inc < 0)
+template <class T> inline T* vec_base(T* v, int64_t len, int64_t inc) {
+    return inc >= 0 ? v : v + (1 - len) * inc;
+}
+
+template <class T>
+int gemv_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x, int64_t incx,
+               const T* beta, T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream) {
+    const bool notrans = (trans == 'N' || trans == 'n');
+    const bool tr = (trans == 'T' || trans == 't');
+    const bool ct = (trans == 'C' || trans == 'c');
+    if (!notrans && !tr && !ct) return -1;
+    if (m < 0) return -2;
+    if (n < 0) return -3;
+    if (lda < (m > 1 ? m : 1)) return -6;
+    if (incx == 0) return -8;
+    if (incy == 0) return -11;
+    if (!alpha || !beta) return KMV_ERR_NULL;
+    const T al = *alpha, be = *beta;
+    if (m == 0 || n == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    if (!A || !x || !y) return KMV_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t leny = notrans ? m : n, lenx = notrans ? n : m;
+    T* yb = vec_base(y, leny, incy);
+    if (is_zero(al)) return hip_code(launch_scal<T>(leny, be, yb, incy, s));
+
+    const GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, A, lda);
+    const bool need_ws = (incx != 1) || plan.splits > 1;
+    if (need_ws && (!workspace || workspace_bytes < plan.total_bytes || ((uintptr_t)workspace % WS_ALIGN) != 0))
+        return KMV_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    GemvArgs<T> a;
+    a.m = m; a.n = n; a.lda = lda; a.A = A;
+    a.y = yb; a.incy = incy; a.alpha = al; a.beta = be;
+    a.partial = plan.splits > 1 ? reinterpret_cast<T*>(ws + plan.partial_off) : nullptr;
+    a.plan = plan;
+    if (incx != 1) {
+        T* xp = reinterpret_cast<T*>(ws + plan.xpack_off);
+        hipError_t e = launch_pack<T>(vec_base(x, lenx, incx), incx, lenx, xp, s);
+        if (e != hipSuccess) return hip_code(e);
+        a.x = xp;
+    } else {
+        a.x = x;
+    }
+    return hip_code(notrans ? launch_gemv_n<T>(a, s) : launch_gemv_t<T>(a, ct, s));
+}
+
+template <class T>
+int symv_entry(char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x, int64_t incx, const T* beta,
+               T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream) {
+    const bool lower = (uplo == 'L' || uplo == 'l');
+    const bool upper = (uplo == 'U' || uplo == 'u');
+    if (!lower && !upper) return -1;
+    if (n < 0) return -2;
+    if (lda < (n > 1 ? n : 1)) return -5;
+    if (incx == 0) return -7;
+    if (incy == 0) return -10;
+    if (!alpha || !beta) return KMV_ERR_NULL;
+    const T al = *alpha, be = *beta;
+    if (n == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    if (!A || !x || !y) return KMV_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    T* yb = vec_base(y, n, incy);
+    if (is_zero(al)) return hip_code(launch_scal<T>(n, be, yb, incy, s));
+
+    const SymvPlan<T> plan = plan_symv<T>(lower, n, A, lda);
+    if (!workspace || workspace_bytes < plan.total_bytes || ((uintptr_t)workspace % WS_ALIGN) != 0)
+        return KMV_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    SymvArgs<T> a;
+    a.n = n; a.lda = lda; a.A = A;
+    a.y = yb; a.incy = incy; a.alpha = al; a.beta = be;
+    a.wsn = reinterpret_cast<T*>(ws + plan.wsn_off);
+    a.wst = reinterpret_cast<T*>(ws + plan.wst_off);
+    a.plan = plan;
+    if (incx != 1) {
+        T* xp = reinterpret_cast<T*>(ws + plan.xpack_off);
+        hipError_t e = launch_pack<T>(vec_base(x, n, incx), incx, n, xp, s);
+        if (e != hipSuccess) return hip_code(e);
+        a.x = xp;
+    } else {
+        a.x = x;
+    }
+    return hip_code(launch_symv<T>(a, lower, s));
+}
+
+template <class T> size_t gemv_ws(char trans, int64_t m, int64_t n) {
+    const bool notrans = (trans == 'N' || trans == 'n');
+    if (m < 0 || n < 0) return 0;
+    return plan_gemv<T>(notrans, m, n, nullptr, 0).total_bytes;
+}
+template <class T> size_t symv_ws(char uplo, int64_t n) {
+    if (n < 0) return 0;
+    return plan_symv<T>(uplo == 'L' || uplo == 'l', n, nullptr, 0).total_bytes;
+}
+
+struct Key { const char* name; int64_t Tuning::*field; int64_t lo, hi; };
+const Key KEYS[] = {
+    {"gemv_n_splits", &Tuning::gemv_n_splits, 0, 256},
+    {"gemv_t_splits", &Tuning::gemv_t_splits, 0, 256},
+    {"symv_chunk_tiles", &Tuning::symv_chunk_tiles, 0, 64},
+    {"wg_target", &Tuning::wg_target, 0, 1 << 20},
+};
+
+}  // namespace
+}  // namespace kmv
+
+using namespace kmv;
+
+extern "C" {
+
+int kmv_sgemv(char trans, int64_t m, int64_t n, const float* alpha, const float* A, int64_t lda, const float* x,
+              int64_t incx, const float* beta, float* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+    return gemv_entry<float>(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
+}
+int kmv_dgemv(char trans, int64_t m, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x,
+              int64_t incx, const double* beta, double* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+    return gemv_entry<double>(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
+}
+int kmv_cgemv(char trans, int64_t m, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+              const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
+              void* ws, size_t wsb, void* stream) {
+    return gemv_entry<cf32>(trans, m, n, (const cf32*)alpha, (const cf32*)A, lda, (const cf32*)x, incx,
+                            (const cf32*)beta, (cf32*)y, incy, ws, wsb, stream);
+}
+int kmv_zgemv(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+              const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
+              void* ws, size_t wsb, void* stream) {
+    return gemv_entry<cf64>(trans, m, n, (const cf64*)alpha, (const cf64*)A, lda, (const cf64*)x, incx,
+                            (const cf64*)beta, (cf64*)y, incy, ws, wsb, stream);
+}
+
+int kmv_ssymv(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda, const float* x, int64_t incx,
+              const float* beta, float* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+    return symv_entry<float>(uplo, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
+}
+int kmv_dsymv(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x, int64_t incx,
+              const double* beta, double* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+    return symv_entry<double>(uplo, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
+}
+int kmv_chemv(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+              const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
+              void* ws, size_t wsb, void* stream) {
+    return symv_entry<cf32>(uplo, n, (const cf32*)alpha, (const cf32*)A, lda, (const cf32*)x, incx, (const cf32*)beta,
+                            (cf32*)y, incy, ws, wsb, stream);
+}
+int kmv_zhemv(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+              const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
+              void* ws, size_t wsb, void* stream) {
+    return symv_entry<cf64>(uplo, n, (const cf64*)alpha, (const cf64*)A, lda, (const cf64*)x, incx, (const cf64*)beta,
+                            (cf64*)y, incy, ws, wsb, stream);
+}
+
+size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n) {
+    switch (prec) {
+        case 's': return gemv_ws<float>(trans, m, n);
+        case 'd': return gemv_ws<double>(trans, m, n);
+        case 'c': return gemv_ws<cf32>(trans, m, n);
+        case 'z': return gemv_ws<cf64>(trans, m, n);
+    }
+    return 0;
+}
+size_t kmv_symv_workspace_bytes(char prec, char uplo, int64_t n) {
+    switch (prec) {
+        case 's': return symv_ws<float>(uplo, n);
+        case 'd': return symv_ws<double>(uplo, n);
+        case 'c': return symv_ws<cf32>(uplo, n);
+        case 'z': return symv_ws<cf64>(uplo, n);
+    }
+    return 0;
+}
+
+void kmv_partition(int64_t W, int64_t Y, int64_t y, int64_t* w, int64_t* s) {
+    int64_t ww = 0, ss = 0;
+    if (Y > 0 && y >= 0 && y < Y && W >= 0) partition(W, Y, y, ww, ss);
+    if (w) *w = ww;
+    if (s) *s = ss;
+}
+
+int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c, double* sink, void* stream) {
+    if (kind < 0 || kind > 2 || n < 0) return -1;
+    if (!a || (kind == 0 && !sink) || (kind >= 1 && !b) || (kind == 2 && !c)) return KMV_ERR_NULL;
+    return hip_code(launch_stream_probe(kind, n, a, b, c, sink, static_cast<hipStream_t>(stream)));
+}
+
+int kmv_set_tuning(const char* key, int64_t value) {
+    if (!key) return -1;
+    for (const Key& k : KEYS)
+        if (strcmp(k.name, key) == 0) {
+            if (value < k.lo || value > k.hi) return -1;
+            tuning().*(k.field) = value;
+            return 0;
+        }
+    return -1;
+}
+int64_t kmv_get_tuning(const char* key) {
+    if (!key) return -1;
+    for (const Key& k : KEYS)
+        if (strcmp(k.name, key) == 0) return tuning().*(k.field);
+    return -1;
+}
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,symv_chunk_tiles,wg_target"; }
+
+const char* kmv_version(void) { return "kmv 0.1 (gfx950)"; }
+
+}  // extern "C"

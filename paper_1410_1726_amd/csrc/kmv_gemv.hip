@@ -1,0 +1,280 @@
+// GEMV kernels for gfx950: y <- alpha*op(A)*x + beta*y, A column major.
+//
+// The paper's two general kernels (Section 6.1, kernels 1 and 2; Algorithms
+// "Non-transposed GEMV" and "Transposed GEMV") walk the matrix in blocks with
+// a register double buffer (Section 6.3), reduce once at the end and add the
+// result into y with atomics (Section 6.2).  What is kept here: the traversal
+// directions, one reduction per workgroup at the very end, the prefetch of the
+// next block into a second register buffer, and the balanced split of a block
+// row / block column over several workgroups (Eqs. local_workload and
+// starting_point).  What is different: lanes map to 16-byte row vectors so a
+// wave64 streams 1 KiB of a column per instruction; partial results of
+// different workgroups go to a workspace and are added in a fixed order by a
+// second tiny kernel (no atomics, so results are reproducible and beta is
+// applied in the same pass instead of a separate SCAL launch, Section 6.4);
+// row tiles start on the 128-byte boundary below the first element and the
+// leading slots are masked (Section 6.6) without a separate interface.
+#include "kmv_launch.hpp"
+
+namespace kmv {
+
+// ------------------------------------------------------------------ GEMV-N --
+// grid.x : blocks of NW row tiles (one tile = 64*VEC rows per wave)
+// grid.y : column splits; each workgroup walks its column range horizontally.
+// Lanes own rows, so no cross-lane reduction is needed; x_j is wave uniform
+// and comes through scalar loads.
+template <class T, int NW, int U>
+__global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int TR = WAVE * VEC;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int64_t t = (int64_t)blockIdx.x * NW + w;
+    if (t >= a.plan.ntiles) return;
+
+    int64_t cw, c0;
+    partition(a.n, a.plan.splits, blockIdx.y, cw, c0);
+    const int64_t r0 = t * TR - a.plan.shift;   // first row slot of the tile, may be negative
+    const int64_t r = r0 + (int64_t)lane * VEC;
+    const int64_t lda = a.lda;
+    const T* __restrict__ x = a.x;
+
+    T acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = zero_of<T>();
+
+    const bool interior = (r0 >= 0) && (r0 + TR <= a.m);
+    if (interior) {
+        const T* __restrict__ p = a.A + r;
+        Vec<T> b0[U], b1[U];
+        auto load_blk = [&](Vec<T>(&buf)[U], int64_t j) {
+            const T* q = p + j * lda;
+#pragma unroll
+            for (int u = 0; u < U; ++u) buf[u] = load_stream(q + (int64_t)u * lda);
+        };
+        auto compute_blk = [&](const Vec<T>(&buf)[U], int64_t j) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const T xj = x[j + u];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) fma_acc(acc[v], buf[u].e[v], xj);
+            }
+        };
+        const int64_t nblk = cw / U;
+        if (nblk > 0) load_blk(b0, c0);
+        for (int64_t b = 0; b < nblk; b += 2) {
+            const int64_t j = c0 + b * U;
+            if (b + 1 < nblk) load_blk(b1, j + U);
+            compute_blk(b0, j);
+            if (b + 1 < nblk) {
+                if (b + 2 < nblk) load_blk(b0, j + 2 * U);
+                compute_blk(b1, j + U);
+            }
+        }
+        for (int64_t j = c0 + nblk * U; j < c0 + cw; ++j) {
+            const Vec<T> av = load_stream(p + j * lda);
+            const T xj = x[j];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) fma_acc(acc[v], av.e[v], xj);
+        }
+    } else {
+        // edge tile: element-wise, only elements inside the m x n block are read
+        for (int64_t j = c0; j < c0 + cw; ++j) {
+            const T xj = x[j];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                const int64_t row = r + v;
+                if (row >= 0 && row < a.m) fma_acc(acc[v], load_elem_stream(a.A + row + j * lda), xj);
+            }
+        }
+    }
+
+    if (a.plan.splits == 1) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const int64_t row = r + v;
+            if (row >= 0 && row < a.m) {
+                T* yp = a.y + row * a.incy;
+                *yp = epilogue(a.alpha, acc[v], a.beta, yp);
+            }
+        }
+    } else {
+        Vec<T> out;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) out.e[v] = acc[v];
+        store_vec(a.partial + (int64_t)blockIdx.y * a.plan.part_stride + (r + a.plan.shift), out);
+    }
+}
+
+// ------------------------------------------------------------------ GEMV-T --
+// grid.x : groups of NC columns; grid.y : row splits.  The NW waves of a
+// workgroup take row tiles round robin and walk down their columns; each lane
+// keeps one accumulator per column; one wave reduction per column and one LDS
+// step across the waves at the very end.
+template <class T, bool CONJ, int NC, int NW>
+__global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int TR = WAVE * VEC;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int64_t j0 = (int64_t)blockIdx.x * NC;
+    const int64_t ntiles = a.plan.ntiles;
+    const int shift = a.plan.shift;
+    const T* __restrict__ x = a.x;
+
+    int64_t tw, ts;
+    partition(ntiles, a.plan.splits, blockIdx.y, tw, ts);
+
+    // columns past n-1 are clamped: they read legitimate data that is dropped
+    const T* __restrict__ col[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int64_t j = (j0 + c < a.n) ? (j0 + c) : (a.n - 1);
+        col[c] = a.A + j * a.lda;
+    }
+    T acc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[c] = zero_of<T>();
+
+    auto is_interior = [&](int64_t t) { return (t * TR - shift >= 0) && ((t + 1) * TR - shift <= a.m); };
+    auto masked_tile = [&](int64_t t) {
+        const int64_t r = t * TR - shift + (int64_t)lane * VEC;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const int64_t row = r + v;
+            if (row >= 0 && row < a.m) {
+                const T xv = x[row];
+#pragma unroll
+                for (int c = 0; c < NC; ++c) fma_op<CONJ>(acc[c], load_elem_stream(col[c] + row), xv);
+            }
+        }
+    };
+
+    int64_t tb = ts + w;              // this wave: tiles tb, tb+NW, ... < te
+    const int64_t te = ts + tw;
+    if (tb < te && tb == 0 && !is_interior(0)) {
+        masked_tile(0);
+        tb += NW;
+    }
+    int64_t cnt = tb < te ? (te - tb + NW - 1) / NW : 0;
+    const bool last_edge = cnt > 0 && (tb + (cnt - 1) * NW == ntiles - 1) && !is_interior(ntiles - 1);
+    if (last_edge) --cnt;
+
+    {
+        Vec<T> x0, x1, b0[NC], b1[NC];
+        auto load_tile = [&](Vec<T>& xv, Vec<T>(&buf)[NC], int64_t k) {
+            const int64_t r = (tb + k * NW) * TR - shift + (int64_t)lane * VEC;
+            xv = load_cached(x + r);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) buf[c] = load_stream(col[c] + r);
+        };
+        auto compute_tile = [&](const Vec<T>& xv, const Vec<T>(&buf)[NC]) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) fma_op<CONJ>(acc[c], buf[c].e[v], xv.e[v]);
+        };
+        if (cnt > 0) load_tile(x0, b0, 0);
+        for (int64_t k = 0; k < cnt; k += 2) {
+            if (k + 1 < cnt) load_tile(x1, b1, k + 1);
+            compute_tile(x0, b0);
+            if (k + 1 < cnt) {
+                if (k + 2 < cnt) load_tile(x0, b0, k + 2);
+                compute_tile(x1, b1);
+            }
+        }
+    }
+    if (last_edge) masked_tile(ntiles - 1);
+
+    __shared__ T red[NW][NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const T s = wave_sum(acc[c]);
+        if (lane == 0) red[w][c] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x < NC) {
+        const int c = threadIdx.x;
+        const int64_t j = j0 + c;
+        if (j < a.n) {
+            T s = red[0][c];
+            for (int ww = 1; ww < NW; ++ww) s = add_of(s, red[ww][c]);
+            if (a.plan.splits == 1) {
+                T* yp = a.y + j * a.incy;
+                *yp = epilogue(a.alpha, s, a.beta, yp);
+            } else {
+                a.partial[(int64_t)blockIdx.y * a.plan.part_stride + j] = s;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------- host side ----
+namespace {
+constexpr int GN_NW = 4, GN_U = 8;      // GEMV-N: waves per workgroup, columns per prefetch block
+constexpr int GT_NC = 8, GT_NW = 4;     // GEMV-T: columns per workgroup, waves per workgroup
+constexpr int64_t MAX_SPLITS = 256;
+constexpr int64_t DEFAULT_WG_TARGET = 2048;   // about 8 workgroups per compute unit
+}  // namespace
+
+template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda) {
+    constexpr int TR = tile_rows<T>();
+    GemvPlan<T> p;
+    const bool sizing = (A == nullptr);
+    p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
+    p.ntiles = ceil_div(m + p.shift, TR);
+    const int64_t target = tuning().wg_target > 0 ? tuning().wg_target : DEFAULT_WG_TARGET;
+    int64_t s;
+    if (notrans) {
+        const int64_t rb = ceil_div(p.ntiles, GN_NW);
+        s = tuning().gemv_n_splits > 0 ? tuning().gemv_n_splits : ceil_div(target, rb);
+        const int64_t cap = n / (4 * GN_U) > 1 ? n / (4 * GN_U) : 1;   // at least 32 columns per split
+        if (s > cap) s = cap;
+        p.part_stride = p.ntiles * TR;
+    } else {
+        const int64_t g = ceil_div(n, GT_NC);
+        s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits : ceil_div(target, g);
+        const int64_t cap = p.ntiles / (2 * GT_NW) > 1 ? p.ntiles / (2 * GT_NW) : 1;   // two tiles per wave at least
+        if (s > cap) s = cap;
+        p.part_stride = (int64_t)round_up((size_t)n, 32);
+    }
+    if (s > MAX_SPLITS) s = MAX_SPLITS;
+    if (s < 1) s = 1;
+    p.splits = s;
+    const int64_t lenx = notrans ? n : m;
+    p.xpack_off = 0;
+    p.partial_off = round_up((size_t)lenx * sizeof(T), WS_ALIGN);
+    const int64_t size_splits = sizing ? MAX_SPLITS : (s > 1 ? s : 0);
+    p.total_bytes = p.partial_off + round_up((size_t)size_splits * p.part_stride * sizeof(T), WS_ALIGN);
+    return p;
+}
+
+template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s) {
+    const dim3 grid((unsigned)ceil_div(a.plan.ntiles, GN_NW), (unsigned)a.plan.splits);
+    hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_U>), grid, dim3(GN_NW * WAVE), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.plan.splits == 1) return e;
+    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.y, a.incy, s);
+}
+
+template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s) {
+    const dim3 grid((unsigned)ceil_div(a.n, GT_NC), (unsigned)a.plan.splits);
+    if (conj && Traits<T>::cplx)
+        hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW>), grid, dim3(GT_NW * WAVE), 0, s, a);
+    else
+        hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW>), grid, dim3(GT_NW * WAVE), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.plan.splits == 1) return e;
+    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, 0, a.n, a.alpha, a.beta, a.y, a.incy, s);
+}
+
+#define KMV_INSTANTIATE_GEMV(T)                                                              \
+    template GemvPlan<T> plan_gemv<T>(bool, int64_t, int64_t, const void*, int64_t);         \
+    template hipError_t launch_gemv_n<T>(const GemvArgs<T>&, hipStream_t);                   \
+    template hipError_t launch_gemv_t<T>(const GemvArgs<T>&, bool, hipStream_t);
+KMV_INSTANTIATE_GEMV(float)
+KMV_INSTANTIATE_GEMV(double)
+KMV_INSTANTIATE_GEMV(cf32)
+KMV_INSTANTIATE_GEMV(cf64)
+
+}  // namespace kmv

@@ -1,0 +1,98 @@
+// Host-side contracts between the C-ABI layer (kmv_api.hip) and the kernel
+// translation units.  Plain structs of pointers and sizes; every launcher
+// only enqueues kernels on the given stream and returns the HIP error code.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "kmv_common.hpp"
+
+namespace kmv {
+
+// Process-wide tuning values (0 = choose automatically).
+struct Tuning {
+    int64_t gemv_n_splits = 0;     // column splits of GEMV-N
+    int64_t gemv_t_splits = 0;     // row splits of GEMV-T
+    int64_t symv_chunk_tiles = 0;  // row tiles per SYMV workgroup
+    int64_t wg_target = 0;         // workgroups the heuristics aim for
+};
+Tuning& tuning();
+
+constexpr int64_t WS_ALIGN = 256;
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Row tiles start on the 128-byte boundary below the first element when every
+// column has the same misalignment (lda*sizeof(T) multiple of 128); `shift` is
+// the number of leading, masked element slots of tile 0 (Section 6.6: start at
+// the aligned address and ignore the extra rows).
+template <class T> inline int row_shift(const void* A, int64_t lda) {
+    const uint64_t b = sizeof(T);
+    if ((uint64_t)lda * b % 128 != 0) return 0;
+    return (int)(((uint64_t)(uintptr_t)A % 128) / b);
+}
+template <class T> constexpr int max_row_shift() { return 128 / (int)sizeof(T) - 1; }
+
+// ---------------------------------------------------------------- GEMV ----
+template <class T> struct GemvPlan {
+    int shift;            // masked leading slots of row tile 0
+    int64_t ntiles;       // row tiles of tile_rows<T>() rows covering [-shift, m)
+    int64_t splits;       // N: column splits; T: row splits
+    int64_t part_stride;  // elements between consecutive partial vectors
+    size_t xpack_off, partial_off, total_bytes;   // workspace layout
+};
+// plan for a concrete call (A != nullptr) or the worst case over alignments
+template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda);
+
+template <class T> struct GemvArgs {
+    int64_t m, n, lda;
+    const T* A;
+    const T* x;       // contiguous x (packed copy when incx != 1)
+    T* y;             // element k of y is y[k*incy] (base already moved for incy < 0)
+    int64_t incy;
+    T alpha, beta;
+    T* partial;       // [splits][part_stride]
+    GemvPlan<T> plan;
+};
+template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s);
+template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s);
+
+// ----------------------------------------------------------- SYMV/HEMV ----
+template <class T> struct SymvPlan {
+    int shift;
+    int64_t ntiles;        // row tiles covering [-shift, n)
+    int64_t npanels;       // column panels of panel_cols<T>() columns
+    int64_t chunk_tiles;   // row tiles per workgroup
+    int64_t max_chunks;    // workgroups per panel (grid x)
+    int64_t rows_padded;   // ntiles * tile_rows
+    size_t xpack_off, wsn_off, wst_off, total_bytes;
+};
+template <class T> int panel_cols();
+template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
+
+template <class T> struct SymvArgs {
+    int64_t n, lda;
+    const T* A;
+    const T* x;       // contiguous
+    T* y;
+    int64_t incy;
+    T alpha, beta;
+    T* wsn;           // [npanels][rows_padded]  row sums of each panel ("N part")
+    T* wst;           // [npanels][max_chunks][panel_cols]  column sums ("T part")
+    SymvPlan<T> plan;
+};
+template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s);
+
+// ------------------------------------------------------------ auxiliary ----
+// dst[k] = element k of the strided vector src (base already moved for inc < 0)
+template <class T> hipError_t launch_pack(const T* src, int64_t inc, int64_t len, T* dst, hipStream_t s);
+// y[k*incy] = beta * y[k*incy]   (alpha == 0 path; beta == 0 stores zeros)
+template <class T> hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s);
+// y[k*incy] = alpha * sum_s partial[s*stride + off + k] + beta*y[k*incy], s ascending
+template <class T> hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off,
+                                            int64_t len, T alpha, T beta, T* y, int64_t incy, hipStream_t s);
+
+hipError_t launch_stream_probe(int kind, int64_t n, const double* a, double* b, double* c, double* sink, hipStream_t s);
+
+}  // namespace kmv

@@ -1,0 +1,119 @@
+"""C-ABI checks that need no GPU: the library loads, exports every function the
+header declares, rejects illegal arguments with the reference-BLAS argument
+numbers before touching the device, and its host-side helpers (work partition,
+workspace sizes, tuning keys) behave."""
+import os
+import re
+
+import pytest
+
+from paper_1410_1726_amd import binding as kmv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+DUMMY = 0x1000   # a non-null "device address" that is never dereferenced on error paths
+NOWS = (0, 0)
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "kmv.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(kmv_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(kmv.lib, n), f"{n} is declared in include/kmv.h but not exported"
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+def test_gemv_argument_errors(prec):
+    f = kmv.GEMV[prec]
+
+    def call(trans="N", m=4, n=4, lda=4, incx=1, incy=1, A=DUMMY, x=DUMMY, y=DUMMY):
+        return f(trans, m, n, 1.0, A, lda, x, incx, 0.0, y, incy, workspace=NOWS, stream=0, check=False)
+
+    assert call(trans="X") == -1
+    assert call(m=-1) == -2
+    assert call(n=-1) == -3
+    assert call(lda=3) == -6
+    assert call(m=0, lda=0) == -6
+    assert call(incx=0) == -8
+    assert call(incy=0) == -11
+    assert call(A=None) == kmv.ERR_NULL
+    # quick returns enqueue nothing and need no device
+    assert call(m=0, lda=1) == 0
+    assert call(n=0) == 0
+    assert f("T", 4, 4, 0.0, DUMMY, 4, DUMMY, 1, 1.0, DUMMY, 1, workspace=NOWS, stream=0, check=False) == 0
+    # a strided x needs the workspace: missing -> error before any launch
+    assert call(incx=2) == kmv.ERR_WORKSPACE
+    with pytest.raises(kmv.KmvError):
+        f("Q", 4, 4, 1.0, DUMMY, 4, DUMMY, 1, 0.0, DUMMY, 1, workspace=NOWS, stream=0)
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+def test_symv_argument_errors(prec):
+    f = kmv.SYMV[prec]
+
+    def call(uplo="L", n=4, lda=4, incx=1, incy=1, A=DUMMY):
+        return f(uplo, n, 1.0, A, lda, DUMMY, incx, 0.0, DUMMY, incy, workspace=NOWS, stream=0, check=False)
+
+    assert call(uplo="N") == -1
+    assert call(n=-1) == -2
+    assert call(lda=3) == -5
+    assert call(incx=0) == -7
+    assert call(incy=0) == -10
+    assert call(A=None) == kmv.ERR_NULL
+    assert call(n=0, lda=1) == 0
+    assert call() == kmv.ERR_WORKSPACE          # SYMV always needs its workspace
+    assert f("u", 4, 0.0, DUMMY, 4, DUMMY, 1, 1.0, DUMMY, 1, workspace=NOWS, stream=0, check=False) == 0
+
+
+def test_partition_invariants():
+    # Section 6.2: shares are balanced (differ by at most one), contiguous, and
+    # tile [0, W); workers beyond W get nothing
+    for W in (0, 1, 5, 64, 1000, 4099):
+        for Y in (1, 2, 3, 7, 16, 100, 5000):
+            pos, sizes = 0, []
+            for y in range(Y):
+                w, s = kmv.partition(W, Y, y)
+                assert s == pos and w >= 0
+                pos += w
+                sizes.append(w)
+            assert pos == W
+            assert max(sizes) - min(sizes) <= 1
+            assert sizes == sorted(sizes, reverse=True)
+    assert kmv.partition(10, 3, 0) == (4, 0)
+    assert kmv.partition(10, 3, 1) == (3, 4)
+    assert kmv.partition(10, 3, 2) == (3, 7)
+
+
+def test_workspace_sizes():
+    for prec, b in (("s", 4), ("d", 8), ("c", 8), ("z", 16)):
+        assert kmv.gemv_workspace_bytes(prec, "N", 0, 0) >= 0
+        small = kmv.gemv_workspace_bytes(prec, "N", 1024, 1024)
+        big = kmv.gemv_workspace_bytes(prec, "N", 4096, 4096)
+        assert 0 < small <= big
+        assert small >= 1024 * b                      # room for a packed x
+        n = 2048
+        s = kmv.symv_workspace_bytes(prec, "L", n)
+        assert s >= n * b and s == kmv.symv_workspace_bytes(prec, "U", n)
+        assert s < 0.2 * n * n * b                    # partial sums stay a small share of the matrix
+    assert kmv.gemv_workspace_bytes("q", "N", 8, 8) == 0
+    assert kmv.symv_workspace_bytes("d", "L", -1) == 0
+
+
+def test_tuning_keys_roundtrip():
+    keys = kmv.tuning_keys()
+    assert "symv_chunk_tiles" in keys
+    for k in keys:
+        old = kmv.get_tuning(k)
+        kmv.set_tuning(k, 4)
+        assert kmv.get_tuning(k) == 4
+        kmv.set_tuning(k, old)
+    with pytest.raises(ValueError):
+        kmv.set_tuning("no_such_key", 1)
+    with pytest.raises(ValueError):
+        kmv.set_tuning("gemv_n_splits", 100000)
+    assert "kmv" in kmv.version()
