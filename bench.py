@@ -1,0 +1,302 @@
+#!/usr/bin/env python3
+"""Benchmark of the kmv hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--table FILE]
+
+One "step" is one pass of the whole hot path over one batch of synthetic
+inputs.  The default workload is the size sweep the headline metric is quoted
+on: SGEMV / DGEMV (N and T) and DSYMV / ZHEMV (L and U) on square matrices,
+n = 1024..32768 in steps of 1024 plus n = 1000, 4099, 17001 for GEMV, lda = n,
+entries U[-1,1], seed 0 (268 products per step).  All inputs are resident in
+HBM before the timed region starts.
+
+The metric follows the paper's performance model (Section 7): algorithmic
+bytes (matrix once, x once, y read and written once; one triangle for the
+symmetric products) divided by time, in GB/s, as a fraction of the HBM peak;
+Gflop/s with the paper's flop counts are reported alongside.
+
+Prints ONE JSON line on stdout.  `--table FILE` additionally writes one JSON
+line per (routine, n) with GB/s, % of peak and Gflop/s (the "vs n" curves).
+Only the `cpu_baseline` leg touches the CPU oracle.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "tiny"])
+    ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
+    return ap.parse_args()
+
+
+# --------------------------------------------------------------- workloads ----
+def products(workload):
+    """List of dicts describing the products of one step."""
+    out = []
+    if workload == "sweep":
+        sizes = [1024 * k for k in range(1, 33)]
+        for prec in "sd":
+            for trans in "NT":
+                for n in sizes + [1000, 4099, 17001]:
+                    out.append(dict(kind="gemv", prec=prec, mode=trans, n=n, lda=n, alpha=1.0, beta=1.0))
+        for prec in "dz":
+            for uplo in "LU":
+                for n in sizes:
+                    out.append(dict(kind="symv", prec=prec, mode=uplo, n=n, lda=n, alpha=1.0, beta=0.0))
+    elif workload == "target16k":
+        for prec in "sdcz":
+            for n in (16384, 32768):
+                for trans in "NT":
+                    out.append(dict(kind="gemv", prec=prec, mode=trans, n=n, lda=n, alpha=1.0, beta=1.0))
+                for uplo in "LU":
+                    out.append(dict(kind="symv", prec=prec, mode=uplo, n=n, lda=n, alpha=1.0, beta=0.0))
+    elif workload == "large":      # lda = n + 32, normal entries, alpha 0.7, beta 0.3, incx 1 and 2
+        for prec in "sdcz":
+            n = 49152 if prec in "sc" else 40960
+            for incx in (1, 2):
+                for trans in "NT":
+                    out.append(dict(kind="gemv", prec=prec, mode=trans, n=n, lda=n + 32, alpha=0.7, beta=0.3,
+                                    incx=incx, dist="normal"))
+                for uplo in "LU":
+                    out.append(dict(kind="symv", prec=prec, mode=uplo, n=n, lda=n + 32, alpha=0.7, beta=0.3,
+                                    incx=incx, dist="normal"))
+    elif workload == "subblock":   # blocks of a 20000 x 20000 fp64 parent at (o, o)
+        for o in (1, 17, 63, 1000):
+            for n in (2048, 8192, 19000 - o):
+                for trans in "NT":
+                    out.append(dict(kind="gemv", prec="d", mode=trans, n=n, lda=20000, off=o, parent=20000,
+                                    alpha=-1.0, beta=1.0))
+                out.append(dict(kind="symv", prec="d", mode="L", n=n, lda=20000, off=o, parent=20000,
+                                alpha=-1.0, beta=1.0))
+    elif workload == "tiny":       # DGEMV N, m = n = lda = 1024, alpha 1.5, beta 0.5
+        out.append(dict(kind="gemv", prec="d", mode="N", n=1024, lda=1024, alpha=1.5, beta=0.5))
+    return out
+
+
+def op_name(p):
+    if p["kind"] == "gemv":
+        return "gemv_" + p["mode"].lower()
+    return ("hemv_" if p["prec"] in "cz" else "symv_") + p["mode"].lower()
+
+
+def routine_name(p):
+    if p["kind"] == "gemv":
+        return f"{p['prec']}gemv_{p['mode']}"
+    return f"{p['prec']}{'hemv' if p['prec'] in 'cz' else 'symv'}_{p['mode']}"
+
+
+def kernel_name(p):
+    """main device kernel of a product (what rocprofv3 lists)"""
+    t = {"s": "float", "d": "double", "c": "kmv::cf32", "z": "kmv::cf64"}[p["prec"]]
+    if p["kind"] == "gemv":
+        return f"gemv_{'n' if p['mode'] == 'N' else 't'}_kernel<{t}>"
+    return f"symv_kernel<{t}>"
+
+
+class Inputs:
+    """Device buffers: per (precision, distribution) one flat matrix buffer as large
+    as the largest product needs (each product views it with its own lda) and one
+    x / y pair.  Filled once, before anything is timed.  The unreferenced triangle
+    of the symmetric products holds ordinary random numbers here: it is never
+    loaded, so its content cannot change the timing (the parity tests run the same
+    shapes with that triangle set to NaN)."""
+
+    def __init__(self, prods, torch, wl):
+        need, vlen = {}, {}
+        for p in prods:
+            key = (p["prec"], p.get("dist", "uniform"))
+            cols = p.get("parent", 0) or p["n"]
+            need[key] = max(need.get(key, 0), p["lda"] * cols)
+            vlen[key] = max(vlen.get(key, 0), 1 + (p["n"] - 1) * abs(p.get("incx", 1)))
+        self.mat, self.vec = {}, {}
+        for key, elems in need.items():
+            prec, dist = key
+            flat = torch.empty(elems, dtype=wl.TORCH_DTYPES[prec], device="cuda")
+            g = torch.Generator(device="cuda")
+            g.manual_seed(0)
+            wl.fill_random(flat, dist, g)
+            self.mat[key] = flat
+            self.vec[key] = (wl.vector(prec, vlen[key], 1, dist=dist, seed=0, which=1, device="cuda"),
+                             wl.vector(prec, vlen[key], 1, dist=dist, seed=0, which=2, device="cuda"))
+
+    def views(self, p):
+        key = (p["prec"], p.get("dist", "uniform"))
+        n, lda, off = p["n"], p["lda"], p.get("off", 0)
+        cols = p.get("parent", 0) or n
+        A2 = self.mat[key][: lda * cols].view(cols, lda)
+        A = A2[off:, off:] if off else A2
+        x, y = self.vec[key]
+        return A, x, y
+
+
+def make_call(p, k, A, x, y):
+    n, lda, incx = p["n"], p["lda"], p.get("incx", 1)
+    if p["kind"] == "gemv":
+        f = k.GEMV[p["prec"]]
+        return lambda: f(p["mode"], n, n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
+    f = k.SYMV[p["prec"]]
+    return lambda: f(p["mode"], n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
+
+
+# ------------------------------------------------------------ CPU baseline ----
+def cpu_baseline(acc, wl):
+    """The oracle as it stands (working-precision mode, OpenMP over outputs) on a
+    bounded sample of the sweep: one product per routine family at one size."""
+    import oracle
+
+    n = 16384
+    sample = [("gemv", "s", "N"), ("gemv", "s", "T"), ("gemv", "d", "N"), ("gemv", "d", "T"),
+              ("symv", "d", "L"), ("symv", "d", "U"), ("symv", "z", "L"), ("symv", "z", "U")]
+    tot_b, tot_t = 0, 0.0
+    oracle.build()
+    for kind, prec, mode in sample:
+        A = wl.matrix(prec, n, n, n, seed=0).numpy().reshape(-1)
+        x = wl.vector(prec, n, seed=0, which=1).numpy()
+        y = wl.vector(prec, n, seed=0, which=2).numpy()
+        t0 = time.perf_counter()
+        if kind == "gemv":
+            oracle.gemv(prec, mode, n, n, 1.0, A, x, 1.0, y, lda=n, mode=oracle.MODE_W)
+            op = "gemv_" + mode.lower()
+        else:
+            oracle.symv(prec, mode, n, 1.0, A, x, 0.0, y, lda=n, mode=oracle.MODE_W)
+            op = "symv_" + mode.lower()
+        tot_t += time.perf_counter() - t0
+        tot_b += acc.algorithmic_bytes(op, prec, n, n)
+        del A
+    return {"value": round(tot_b / tot_t / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"sgemv/dgemv N,T + dsymv/zhemv L,U at n={n}, working-precision oracle, one run each",
+            "seconds": round(tot_t, 2)}
+
+
+# --------------------------------------------------------------------- main ----
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build is single-GPU by design (no multi-GPU layer); --gpus {args.gpus} is not supported, "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_1410_1726_amd import accounting as acc
+    from paper_1410_1726_amd import binding as k
+    from paper_1410_1726_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the kmv library has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    for kv in args.tuning:
+        key, v = kv.split("=")
+        k.set_tuning(key, int(v))
+
+    # largest products first: the host runs ahead of the device, so the short
+    # products at the end of a step are already queued when their turn comes
+    prods = sorted(products(args.workload), key=lambda p: -p["n"])
+    inputs = Inputs(prods, torch, wl)
+    stream = torch.cuda.current_stream()
+    calls = [make_call(p, k, *inputs.views(p)) for p in prods]
+    nprod = len(prods)
+    per = [dict(bytes=acc.algorithmic_bytes(op_name(p), p["prec"], p["n"], p["n"]),
+                flops=acc.flops(op_name(p), p["prec"], p["n"], p["n"]), ms=0.0) for p in prods]
+
+    for _ in range(args.warmup):
+        for call in calls:
+            call()
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in prods]
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    # timed region: exactly `steps` passes, inputs already resident in HBM; HIP
+    # events on the launch stream bracket every product for the breakdown
+    t0 = time.perf_counter()
+    for step in range(args.steps):
+        for call, (e0, e1) in zip(calls, events[step]):
+            e0.record(stream)
+            call()
+            e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for step in range(args.steps):
+        for rec, (e0, e1) in zip(per, events[step]):
+            rec["ms"] += e0.elapsed_time(e1) / args.steps
+
+    step_ms = wall / args.steps * 1e3          # wall clock between the two synchronisations
+    device_ms = sum(r["ms"] for r in per)       # sum of the per-product event brackets
+    tot_bytes = sum(r["bytes"] for r in per)
+    tot_flops = sum(r["flops"] for r in per)
+    value = tot_bytes / (step_ms * 1e-3) / 1e9
+
+    # dominant kernel = the main kernel with the largest share of the step time
+    by_kernel = {}
+    for p, r in zip(prods, per):
+        d = by_kernel.setdefault(kernel_name(p), dict(ms=0.0, bytes=0, launches=0))
+        d["ms"] += r["ms"]
+        d["bytes"] += r["bytes"]
+        d["launches"] += 1
+    dom, dd = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dd["bytes"] / (dd["ms"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "launches_per_step": dd["launches"],
+                "avg_launch_us": round(dd["ms"] * 1e3 / dd["launches"], 2),
+                "avg_algorithmic_bytes_per_launch": dd["bytes"] // dd["launches"]}
+
+    # fraction of peak per routine over the graded region n >= 16384
+    graded = {}
+    for p, r in zip(prods, per):
+        if p["n"] >= 16384:
+            g = graded.setdefault(routine_name(p), [0, 0.0])
+            g[0] += r["bytes"]
+            g[1] += r["ms"]
+    graded = {name: round(b / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for name, (b, m) in graded.items()}
+
+    if args.table:
+        with open(args.table, "w") as f:
+            for p, r in zip(prods, per):
+                gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9
+                f.write(json.dumps({"routine": routine_name(p), "n": p["n"], "lda": p["lda"], "off": p.get("off", 0),
+                                    "incx": p.get("incx", 1), "us": round(r["ms"] * 1e3, 2), "gbs": round(gbs, 1),
+                                    "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                                    "gflops": round(r["flops"] / (r["ms"] * 1e-3) / 1e9, 1)}) + "\n")
+
+    out = {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32+f64+c128" if args.workload == "sweep" else "f32+f64+c64+c128", "data": "synthetic",
+        "config": {"workload": {
+            "sweep": "configs[1]+configs[2]: SGEMV/DGEMV N,T n=1024..32768 step 1024 + {1000,4099,17001}; "
+                     "DSYMV/ZHEMV L,U n=1024..32768 step 1024 (other triangle NaN, beta=0); lda=n, U[-1,1], seed 0",
+            "target16k": "all 16 precision x routine products at n=16384 and 32768, lda=n",
+            "large": "configs[4]: n=49152 (s,c) / 40960 (d,z), lda=n+32, N(0,1), alpha=0.7, beta=0.3, incx 1 and 2",
+            "subblock": "configs[3]: blocks of a 20000x20000 fp64 parent at offsets 1,17,63,1000",
+            "tiny": "configs[0]: DGEMV N m=n=lda=1024",
+        }[args.workload], "products_per_step": nprod},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "gflops": round(tot_flops / (step_ms * 1e-3) / 1e9, 1),
+        "frac_hbm_peak_n_ge_16384": graded,
+        "device_ms_per_step": round(device_ms, 3),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(acc, wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -119,7 +119,9 @@ struct Key { const char* name; int64_t Tuning::*field; int64_t lo, hi; };
 const Key KEYS[] = {
     {"gemv_n_splits", &Tuning::gemv_n_splits, 0, 256},
     {"gemv_t_splits", &Tuning::gemv_t_splits, 0, 256},
-    {"symv_chunk_tiles", &Tuning::symv_chunk_tiles, 0, 64},
+    {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
+    {"symv_panel_cols", &Tuning::symv_panel_cols, 0, 128},
+    {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
 };
 
@@ -209,6 +211,8 @@ int kmv_set_tuning(const char* key, int64_t value) {
     for (const Key& k : KEYS)
         if (strcmp(k.name, key) == 0) {
             if (value < k.lo || value > k.hi) return -1;
+            if (k.field == &Tuning::gemv_n_row_tiles && value == 3) return -1;
+            if (k.field == &Tuning::symv_panel_cols && value != 0 && value != 64 && value != 128) return -1;
             tuning().*(k.field) = value;
             return 0;
         }
@@ -220,7 +224,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,symv_chunk_tiles,wg_target"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,wg_target"; }
 
 const char* kmv_version(void) { return "kmv 0.1 (gfx950)"; }
 

@@ -20,16 +20,32 @@ template <class T> __global__ void scal_kernel(int64_t len, T beta, T* y, int64_
     }
 }
 
+// blockDim = 256 = 32 outputs x 8 groups: group g adds the partial vectors
+// g, g+8, ... in ascending order, the eight group sums meet in LDS and are
+// added in group order, so the result does not depend on scheduling.
+constexpr int RD_OUT = 32, RD_GRP = 8;
 template <class T>
-__global__ void reduce_kernel(const T* __restrict__ partial, int64_t splits, int64_t stride, int64_t off,
-                              int64_t len, T alpha, T beta, T* y, int64_t incy) {
-    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= len) return;
-    const T* p = partial + off + k;
-    T s = p[0];
-    for (int64_t i = 1; i < splits; ++i) s = add_of(s, p[i * stride]);
-    T* yp = y + k * incy;
-    *yp = epilogue(alpha, s, beta, yp);
+__global__ __launch_bounds__(RD_OUT * RD_GRP) void reduce_kernel(const T* __restrict__ partial, int64_t splits,
+                                                                  int64_t stride, int64_t off, int64_t len, T alpha,
+                                                                  T beta, T* y, int64_t incy) {
+    const int lx = threadIdx.x % RD_OUT, g = threadIdx.x / RD_OUT;
+    const int64_t k = (int64_t)blockIdx.x * RD_OUT + lx;
+    __shared__ T part[RD_GRP][RD_OUT];
+    T s = zero_of<T>();
+    if (k < len) {
+        const T* p = partial + off + k;
+#pragma unroll 4
+        for (int64_t i = g; i < splits; i += RD_GRP) s = add_of(s, p[i * stride]);
+    }
+    part[g][lx] = s;
+    __syncthreads();
+    if (g == 0 && k < len) {
+        T tot = part[0][lx];
+#pragma unroll
+        for (int gg = 1; gg < RD_GRP; ++gg) tot = add_of(tot, part[gg][lx]);
+        T* yp = y + k * incy;
+        *yp = epilogue(alpha, tot, beta, yp);
+    }
 }
 
 template <class T> hipError_t launch_pack(const T* src, int64_t inc, int64_t len, T* dst, hipStream_t s) {
@@ -46,8 +62,8 @@ template <class T>
 hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off, int64_t len, T alpha, T beta,
                          T* y, int64_t incy, hipStream_t s) {
     if (len <= 0) return hipSuccess;
-    hipLaunchKernelGGL((reduce_kernel<T>), dim3((unsigned)ceil_div(len, 128)), dim3(128), 0, s, partial, splits,
-                       stride, off, len, alpha, beta, y, incy);
+    hipLaunchKernelGGL((reduce_kernel<T>), dim3((unsigned)ceil_div(len, RD_OUT)), dim3(RD_OUT * RD_GRP), 0, s, partial,
+                       splits, stride, off, len, alpha, beta, y, incy);
     return hipGetLastError();
 }
 

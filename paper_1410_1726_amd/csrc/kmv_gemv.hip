@@ -19,90 +19,123 @@
 namespace kmv {
 
 // ------------------------------------------------------------------ GEMV-N --
-// grid.x : blocks of NW row tiles (one tile = 64*VEC rows per wave)
+// grid.x : blocks of NW*RT row tiles (one tile = 64*VEC rows); a wave owns RT
+//          tiles that lie NW tiles apart, so that for every column the NW waves
+//          of a workgroup read NW consecutive KiB, RT times
 // grid.y : column splits; each workgroup walks its column range horizontally.
 // Lanes own rows, so no cross-lane reduction is needed; x_j is wave uniform
-// and comes through scalar loads.
-template <class T, int NW, int U>
+// and comes through scalar loads.  A block = U columns x RT tiles of 16-byte
+// row vectors plus the U x values, fetched one block ahead of its use.
+// Edge tiles (rows before the first or after the last row) run the same
+// pipeline with element loads whose row index is clamped into the matrix: the
+// clamped lanes compute sums of rows that do not exist, which are dropped.
+template <class T, bool EDGE> __device__ __forceinline__ Vec<T> load_rows(const T* __restrict__ colp, int64_t r, int64_t m) {
+    if (!EDGE) return load_stream(colp + r);
+    Vec<T> v;
+#pragma unroll
+    for (int e = 0; e < Traits<T>::VEC; ++e) {
+        int64_t row = r + e;
+        row = row < 0 ? 0 : (row >= m ? m - 1 : row);
+        v.e[e] = load_elem_stream(colp + row);
+    }
+    return v;
+}
+
+template <class T, int U, int RT, int NW, bool EDGE>
+__device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t (&r)[RT], int64_t c0, int64_t cw,
+                                            T (&acc)[RT][Traits<T>::VEC]) {
+    constexpr int VEC = Traits<T>::VEC;
+    const int64_t lda = a.lda;
+    const T* __restrict__ x = a.x;
+    const T* __restrict__ A = a.A;
+    Vec<T> b0[U][RT], b1[U][RT];
+    T xb0[U], xb1[U];
+    auto load_blk = [&](Vec<T>(&buf)[U][RT], T(&xb)[U], int64_t j) {
+        const T* q = A + j * lda;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < RT; ++t) buf[u][t] = load_rows<T, EDGE>(q + (int64_t)u * lda, r[t], a.m);
+#pragma unroll
+        for (int u = 0; u < U; ++u) xb[u] = x[j + u];
+    };
+    auto compute_blk = [&](const Vec<T>(&buf)[U][RT], const T(&xb)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) fma_acc(acc[t][v], buf[u][t].e[v], xb[u]);
+    };
+    const int64_t nblk = cw / U;
+    if (nblk > 0) load_blk(b0, xb0, c0);
+    for (int64_t b = 0; b < nblk; b += 2) {
+        const int64_t j = c0 + b * U;
+        if (b + 1 < nblk) load_blk(b1, xb1, j + U);
+        compute_blk(b0, xb0);
+        if (b + 1 < nblk) {
+            if (b + 2 < nblk) load_blk(b0, xb0, j + 2 * U);
+            compute_blk(b1, xb1);
+        }
+    }
+    for (int64_t j = c0 + nblk * U; j < c0 + cw; ++j) {
+        Vec<T> av[RT];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) av[t] = load_rows<T, EDGE>(A + j * lda, r[t], a.m);
+        const T xj = x[j];
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) fma_acc(acc[t][v], av[t].e[v], xj);
+    }
+}
+
+template <class T, int NW, int U, int RT>
 __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     const int lane = threadIdx.x & (WAVE - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
-    const int64_t t = (int64_t)blockIdx.x * NW + w;
-    if (t >= a.plan.ntiles) return;
+    const int64_t tbase = (int64_t)blockIdx.x * (NW * RT) + w;   // tiles tbase + NW*t, t < RT
+    if (tbase >= a.plan.ntiles) return;
 
     int64_t cw, c0;
     partition(a.n, a.plan.splits, blockIdx.y, cw, c0);
-    const int64_t r0 = t * TR - a.plan.shift;   // first row slot of the tile, may be negative
-    const int64_t r = r0 + (int64_t)lane * VEC;
-    const int64_t lda = a.lda;
-    const T* __restrict__ x = a.x;
+    int64_t r[RT];          // first row slot of this lane in each tile (may be outside [0, m))
+    bool interior = true;   // all RT tiles fully inside the matrix (wave uniform)
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int64_t r0 = (tbase + (int64_t)NW * t) * TR - a.plan.shift;
+        r[t] = r0 + (int64_t)lane * VEC;
+        interior = interior && (r0 >= 0) && (r0 + TR <= a.m);
+    }
+    T acc[RT][VEC];
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[t][v] = zero_of<T>();
 
-    T acc[VEC];
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[v] = zero_of<T>();
+    if (interior) gemv_n_walk<T, U, RT, NW, false>(a, r, c0, cw, acc);
+    else gemv_n_walk<T, U, RT, NW, true>(a, r, c0, cw, acc);
 
-    const bool interior = (r0 >= 0) && (r0 + TR <= a.m);
-    if (interior) {
-        const T* __restrict__ p = a.A + r;
-        Vec<T> b0[U], b1[U];
-        auto load_blk = [&](Vec<T>(&buf)[U], int64_t j) {
-            const T* q = p + j * lda;
 #pragma unroll
-            for (int u = 0; u < U; ++u) buf[u] = load_stream(q + (int64_t)u * lda);
-        };
-        auto compute_blk = [&](const Vec<T>(&buf)[U], int64_t j) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const T xj = x[j + u];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) fma_acc(acc[v], buf[u].e[v], xj);
-            }
-        };
-        const int64_t nblk = cw / U;
-        if (nblk > 0) load_blk(b0, c0);
-        for (int64_t b = 0; b < nblk; b += 2) {
-            const int64_t j = c0 + b * U;
-            if (b + 1 < nblk) load_blk(b1, j + U);
-            compute_blk(b0, j);
-            if (b + 1 < nblk) {
-                if (b + 2 < nblk) load_blk(b0, j + 2 * U);
-                compute_blk(b1, j + U);
-            }
-        }
-        for (int64_t j = c0 + nblk * U; j < c0 + cw; ++j) {
-            const Vec<T> av = load_stream(p + j * lda);
-            const T xj = x[j];
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) fma_acc(acc[v], av.e[v], xj);
-        }
-    } else {
-        // edge tile: element-wise, only elements inside the m x n block are read
-        for (int64_t j = c0; j < c0 + cw; ++j) {
-            const T xj = x[j];
+    for (int t = 0; t < RT; ++t) {
+        if (tbase + (int64_t)NW * t >= a.plan.ntiles) continue;   // tile beyond the matrix: nothing to store
+        if (a.plan.splits == 1) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                const int64_t row = r + v;
-                if (row >= 0 && row < a.m) fma_acc(acc[v], load_elem_stream(a.A + row + j * lda), xj);
+                const int64_t row = r[t] + v;
+                if (row >= 0 && row < a.m) {
+                    T* yp = a.y + row * a.incy;
+                    *yp = epilogue(a.alpha, acc[t][v], a.beta, yp);
+                }
             }
-        }
-    }
-
-    if (a.plan.splits == 1) {
+        } else {
+            Vec<T> out;
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            const int64_t row = r + v;
-            if (row >= 0 && row < a.m) {
-                T* yp = a.y + row * a.incy;
-                *yp = epilogue(a.alpha, acc[v], a.beta, yp);
-            }
+            for (int v = 0; v < VEC; ++v) out.e[v] = acc[t][v];
+            store_vec(a.partial + (int64_t)blockIdx.y * a.plan.part_stride + (r[t] + a.plan.shift), out);
         }
-    } else {
-        Vec<T> out;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) out.e[v] = acc[v];
-        store_vec(a.partial + (int64_t)blockIdx.y * a.plan.part_stride + (r + a.plan.shift), out);
     }
 }
 
@@ -137,17 +170,29 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     for (int c = 0; c < NC; ++c) acc[c] = zero_of<T>();
 
     auto is_interior = [&](int64_t t) { return (t * TR - shift >= 0) && ((t + 1) * TR - shift <= a.m); };
+    // edge tile: element loads with the row index clamped into the matrix (all
+    // issued before the first use), rows that do not exist are then skipped
     auto masked_tile = [&](int64_t t) {
         const int64_t r = t * TR - shift + (int64_t)lane * VEC;
+        T xv[VEC], av[NC][VEC];
+        bool ok[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-            const int64_t row = r + v;
-            if (row >= 0 && row < a.m) {
-                const T xv = x[row];
+            int64_t row = r + v;
+            ok[v] = row >= 0 && row < a.m;
+            row = row < 0 ? 0 : (row >= a.m ? a.m - 1 : row);
+            xv[v] = x[row];
 #pragma unroll
-                for (int c = 0; c < NC; ++c) fma_op<CONJ>(acc[c], load_elem_stream(col[c] + row), xv);
-            }
+            for (int c = 0; c < NC; ++c) av[c][v] = load_elem_stream(col[c] + row);
         }
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                T nacc = acc[c];
+                fma_op<CONJ>(nacc, av[c][v], xv[v]);
+                acc[c] = ok[v] ? nacc : acc[c];
+            }
     };
 
     int64_t tb = ts + w;              // this wave: tiles tb, tb+NW, ... < te
@@ -211,32 +256,36 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
 
 // ------------------------------------------------------------- host side ----
 namespace {
-constexpr int GN_NW = 4, GN_U = 8;      // GEMV-N: waves per workgroup, columns per prefetch block
+constexpr int GN_NW = 4;                // GEMV-N: waves per workgroup
+constexpr int GN_LOADS = 8;             // GEMV-N: 16-byte loads per lane and prefetch block (columns x tiles)
 constexpr int GT_NC = 8, GT_NW = 4;     // GEMV-T: columns per workgroup, waves per workgroup
 constexpr int64_t MAX_SPLITS = 256;
 constexpr int64_t DEFAULT_WG_TARGET = 2048;   // about 8 workgroups per compute unit
+constexpr int64_t DEFAULT_GN_ROW_TILES = 1;
 }  // namespace
 
 template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda) {
     constexpr int TR = tile_rows<T>();
     GemvPlan<T> p;
+    p.row_tiles = 1;
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(m + p.shift, TR);
     const int64_t target = tuning().wg_target > 0 ? tuning().wg_target : DEFAULT_WG_TARGET;
     int64_t s;
     if (notrans) {
-        const int64_t rb = ceil_div(p.ntiles, GN_NW);
+        p.row_tiles = tuning().gemv_n_row_tiles > 0 ? tuning().gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
+        const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
         s = tuning().gemv_n_splits > 0 ? tuning().gemv_n_splits : ceil_div(target, rb);
-        const int64_t cap = n / (4 * GN_U) > 1 ? n / (4 * GN_U) : 1;   // at least 32 columns per split
+        const int64_t cap = n / 32 > 1 ? n / 32 : 1;   // at least 32 columns per split
         if (s > cap) s = cap;
-        p.part_stride = p.ntiles * TR;
+        p.part_stride = partial_stride<T>(p.ntiles * TR);
     } else {
         const int64_t g = ceil_div(n, GT_NC);
         s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits : ceil_div(target, g);
         const int64_t cap = p.ntiles / (2 * GT_NW) > 1 ? p.ntiles / (2 * GT_NW) : 1;   // two tiles per wave at least
         if (s > cap) s = cap;
-        p.part_stride = (int64_t)round_up((size_t)n, 32);
+        p.part_stride = partial_stride<T>(n);
     }
     if (s > MAX_SPLITS) s = MAX_SPLITS;
     if (s < 1) s = 1;
@@ -250,8 +299,13 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
 }
 
 template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s) {
-    const dim3 grid((unsigned)ceil_div(a.plan.ntiles, GN_NW), (unsigned)a.plan.splits);
-    hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_U>), grid, dim3(GN_NW * WAVE), 0, s, a);
+    const int64_t rt = a.plan.row_tiles;
+    const dim3 grid((unsigned)ceil_div(a.plan.ntiles, GN_NW * rt), (unsigned)a.plan.splits);
+    const dim3 block(GN_NW * WAVE);
+    if (rt == 1) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS, 1>), grid, block, 0, s, a);
+    else if (rt == 2) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS / 2, 2>), grid, block, 0, s, a);
+    else if (rt == 4) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS / 4, 4>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.plan.splits == 1) return e;
     return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.y, a.incy, s);

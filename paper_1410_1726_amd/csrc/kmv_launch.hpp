@@ -15,13 +15,24 @@ namespace kmv {
 struct Tuning {
     int64_t gemv_n_splits = 0;     // column splits of GEMV-N
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
-    int64_t symv_chunk_tiles = 0;  // row tiles per SYMV workgroup
+    int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
+    int64_t symv_panel_cols = 0;      // SYMV panel width: 64 or 128 columns
+    int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave and task: 1 or 2
     int64_t wg_target = 0;         // workgroups the heuristics aim for
 };
 Tuning& tuning();
 
 constexpr int64_t WS_ALIGN = 256;
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// Distance (in elements) between consecutive partial vectors of `elems` elements:
+// a whole number of 256-byte units, and an odd one, so that the vectors of
+// different workgroups that hold the same rows do not all fall on one memory
+// channel the way a power-of-two distance would make them.
+template <class T> inline int64_t partial_stride(int64_t elems) {
+    size_t units = round_up((size_t)elems * sizeof(T), 256) / 256;
+    if (units % 2 == 0) ++units;
+    return (int64_t)(units * 256 / sizeof(T));
+}
 
 // Row tiles start on the 128-byte boundary below the first element when every
 // column has the same misalignment (lda*sizeof(T) multiple of 128); `shift` is
@@ -39,6 +50,7 @@ template <class T> struct GemvPlan {
     int shift;            // masked leading slots of row tile 0
     int64_t ntiles;       // row tiles of tile_rows<T>() rows covering [-shift, m)
     int64_t splits;       // N: column splits; T: row splits
+    int64_t row_tiles;    // N: row tiles per wave
     int64_t part_stride;  // elements between consecutive partial vectors
     size_t xpack_off, partial_off, total_bytes;   // workspace layout
 };
@@ -62,13 +74,13 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
 template <class T> struct SymvPlan {
     int shift;
     int64_t ntiles;        // row tiles covering [-shift, n)
-    int64_t npanels;       // column panels of panel_cols<T>() columns
+    int64_t panel_cols;    // columns per panel
+    int64_t npanels;       // column panels
     int64_t chunk_tiles;   // row tiles per workgroup
     int64_t max_chunks;    // workgroups per panel (grid x)
-    int64_t rows_padded;   // ntiles * tile_rows
+    int64_t rows_padded;   // distance between the row-sum vectors of two panels (>= ntiles * tile_rows)
     size_t xpack_off, wsn_off, wst_off, total_bytes;
 };
-template <class T> int panel_cols();
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
 
 template <class T> struct SymvArgs {

@@ -11,16 +11,28 @@
 // to a separate kernel that mirrors them in shared memory (Section 6.5).
 //
 // Kept: the vertical walk of a column panel, the dual use of each element, the
-// register accumulators for the transposed part, the register double buffer.
-// Different: lanes map to 16-byte row vectors (wave64 streams 1 KiB of a
-// column per instruction); the waves of a workgroup share the rows and split
-// the panel's columns, their non-transposed row sums meet in LDS and are
-// flushed every KT row tiles to a workspace indexed [panel][row] (one barrier
-// per KT tiles instead of two per block, and no atomics); the diagonal tiles
-// are handled in the same kernel by predicated element loads that never touch
-// the other triangle, so the mirrored copy of Section 6.5 is never built; the
-// triangle is cut into (panel, chunk of row tiles) workgroups of bounded size
-// instead of a fixed (X, Y) grid, which balances the triangular workload.
+// register double buffer.  Different, to fit wave64 and the HBM behaviour of
+// the MI355X (a workgroup that touches many columns at the same row offset
+// loses bandwidth, a workgroup that reads a few columns over several KiB of
+// consecutive rows does not):
+//  * lanes map to 16-byte row vectors, a wave streams 1 KiB of a column per
+//    instruction;
+//  * a workgroup owns (panel of C columns) x (chunk of NW*KTW row tiles); each
+//    wave owns KTW of those row tiles for the whole task and sweeps the panel
+//    in groups of NC columns, so at any moment the workgroup reads NC columns
+//    over NW consecutive KiB;
+//  * the non-transposed row sums of a wave's tiles therefore stay in registers
+//    for the whole panel width and are stored once per task into a workspace
+//    indexed [panel][row] - no shared memory, no barrier and no atomics in the
+//    loop (the paper needs a sync-and-reduce per block);
+//  * the transposed column sums are reduced across the wave once per column
+//    group (DPP), meet the other waves' in LDS and go to a second workspace
+//    indexed [panel][chunk][column];
+//  * diagonal tiles are handled in the same kernel by predicated element loads
+//    that never touch the other triangle, so the mirrored copy of Section 6.5
+//    is never built;
+//  * the triangle is cut into bounded (panel, chunk) tasks instead of a fixed
+//    (X, Y) grid, which balances the triangular workload.
 // A second kernel adds, in a fixed order, all row sums and column sums that
 // belong to y_i and applies alpha and beta.
 #include "kmv_launch.hpp"
@@ -29,14 +41,11 @@ namespace kmv {
 
 namespace {
 constexpr int SY_NW = 4;    // waves per workgroup
-constexpr int SY_CW = 16;   // columns per wave  -> panel of 64 columns
-constexpr int SY_KT = 4;    // row tiles between two flushes of the row sums
-constexpr int64_t DEFAULT_CHUNK_TILES = 8;
-constexpr int64_t MAX_CHUNK_TILES = 64;
-constexpr int RED_ROWS = 64, RED_PARTS = 4;
+constexpr int SY_NC = 8;    // columns per column group
+constexpr int DEFAULT_PANEL_COLS = 64;
+constexpr int DEFAULT_TILES_PER_WAVE = 2;
+constexpr int RED_ROWS = 32, RED_PARTS = 8;
 }  // namespace
-
-template <class T> int panel_cols() { return SY_NW * SY_CW; }
 
 // first / one-past-last row tile that a panel's stored part touches
 template <bool LOWER>
@@ -52,11 +61,12 @@ __host__ __device__ __forceinline__ void panel_tiles(int64_t J0, int64_t C, int6
     }
 }
 
-template <class T, bool HERM, bool LOWER, int CW, int NW, int KT>
+template <class T, bool HERM, bool LOWER, int NC, int CGS, int KTW, int NW>
 __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
-    constexpr int C = CW * NW;
+    constexpr int C = NC * CGS;
+    constexpr int CT = NW * KTW;
     const int lane = threadIdx.x & (WAVE - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int64_t n = a.n, lda = a.lda;
@@ -68,135 +78,148 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
     const int64_t J0 = p * C;
     int64_t tlo, thi;
     panel_tiles<LOWER>(J0, C, n, shift, TR, a.plan.ntiles, tlo, thi);
-    const int64_t tbeg = tlo + (int64_t)blockIdx.x * a.plan.chunk_tiles;
-    int64_t tend = tbeg + a.plan.chunk_tiles;
+    const int64_t tbeg = tlo + (int64_t)blockIdx.x * CT;
+    int64_t tend = tbeg + CT;
     if (tend > thi) tend = thi;
     if (tbeg >= tend) return;   // whole workgroup leaves together, before any barrier
 
-    const int64_t jw = J0 + (int64_t)w * CW;   // first column of this wave
     const bool ragged_panel = (J0 + C > n);
-    T xj[CW];
-    const T* __restrict__ col[CW];
-#pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const bool ok = jw + c < n;
-        xj[c] = ok ? x[jw + c] : zero_of<T>();
-        col[c] = a.A + (ok ? (jw + c) : (n - 1)) * lda;
-    }
-    T accT[CW];
-#pragma unroll
-    for (int c = 0; c < CW; ++c) accT[c] = zero_of<T>();
-
-    __shared__ Vec<T> nbuf[2][NW][KT][WAVE];
-    int q = 0, buf = 0;
-    int64_t gstart = tbeg;
-    T* __restrict__ wsn = a.wsn + p * a.plan.rows_padded;
-
-    // hand the row sums of tile t to LDS; every KT tiles (and after the last
-    // tile) add the NW waves' contributions in wave order and store them.
-    auto emit = [&](const T(&accN)[VEC], int64_t t) {
-        Vec<T> o;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) o.e[v] = accN[v];
-        nbuf[buf][w][q][lane] = o;
-        ++q;
-        if (q == KT || t == tend - 1) {
-            __syncthreads();
-            for (int e = threadIdx.x; e < q * WAVE; e += NW * WAVE) {
-                const int qt = e / WAVE, ln = e % WAVE;
-                Vec<T> s = nbuf[buf][0][qt][ln];
-#pragma unroll
-                for (int ww = 1; ww < NW; ++ww) {
-                    const Vec<T> o2 = nbuf[buf][ww][qt][ln];
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) s.e[v] = add_of(s.e[v], o2.e[v]);
-                }
-                store_vec(wsn + (gstart + qt) * TR + (int64_t)ln * VEC, s);
-            }
-            buf ^= 1;
-            gstart += q;
-            q = 0;
-        }
-    };
-
-    // a tile is interior when all its rows exist, the panel is full width and
-    // every (row, column) pair lies strictly inside the stored triangle
+    // a tile is "fast" when all its rows exist, the panel is full width and every
+    // (row, column) pair of the panel lies strictly inside the stored triangle
     auto is_interior = [&](int64_t t) {
         const int64_t r0 = t * TR - shift;
         if (ragged_panel || r0 < 0 || r0 + TR > n) return false;
         return LOWER ? (r0 > J0 + C - 1) : (r0 + TR - 1 < J0);
     };
-    auto masked_tile = [&](int64_t t) {
-        const int64_t r = t * TR - shift + (int64_t)lane * VEC;
-        T accN[VEC];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            accN[v] = zero_of<T>();
-            const int64_t row = r + v;
-            const bool rowok = row >= 0 && row < n;
-            const T xi = rowok ? x[row] : zero_of<T>();
-#pragma unroll
-            for (int c = 0; c < CW; ++c) {
-                const int64_t j = jw + c;
-                const bool inside = rowok && j < n && (LOWER ? row >= j : row <= j);
-                if (inside) {
-                    T av = load_elem_stream(col[c] + row);
-                    if (row == j) {
-                        if (HERM) av = real_part_only(av);
-                        fma_acc(accN[v], av, xj[c]);
-                    } else {
-                        fma_acc(accN[v], av, xj[c]);
-                        fma_op<HERM>(accT[c], av, xi);
-                    }
-                }
-            }
-        }
-        emit(accN, t);
-    };
 
-    Vec<T> xi0, xi1, b0[CW], b1[CW];
-    auto load_tile = [&](Vec<T>& xi, Vec<T>(&bb)[CW], int64_t t) {
-        const int64_t r = t * TR - shift + (int64_t)lane * VEC;
-        xi = load_cached(x + r);
+    // this wave's row tiles, their x segment and their row-sum accumulators
+    int64_t rq[KTW];
+    bool valid[KTW], fast[KTW];
+    Vec<T> xi[KTW];
+    T accN[KTW][VEC];
 #pragma unroll
-        for (int c = 0; c < CW; ++c) bb[c] = load_stream(col[c] + r);
-    };
-    auto compute_tile = [&](const Vec<T>& xi, const Vec<T>(&bb)[CW], int64_t t) {
-        T accN[VEC];
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) accN[v] = zero_of<T>();
-#pragma unroll
-        for (int c = 0; c < CW; ++c)
+    for (int q = 0; q < KTW; ++q) {
+        const int64_t t = tbeg + w + (int64_t)NW * q;
+        valid[q] = t < tend;
+        fast[q] = valid[q] && is_interior(t);
+        rq[q] = t * TR - shift + (int64_t)lane * VEC;
+        if (fast[q]) {
+            xi[q] = load_cached(x + rq[q]);
+        } else {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                fma_acc(accN[v], bb[c].e[v], xj[c]);
-                fma_op<HERM>(accT[c], bb[c].e[v], xi.e[v]);
+                const int64_t row = rq[q] + v;
+                xi[q].e[v] = (valid[q] && row >= 0 && row < n) ? x[row] : zero_of<T>();
             }
-        emit(accN, t);
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) accN[q][v] = zero_of<T>();
+    }
+
+    __shared__ T tpart[NW][C];
+    const T* __restrict__ colbase = a.A + J0 * lda;
+
+    // one unit of work = one column group (NC columns) over all KTW tiles of the
+    // wave; the next unit's matrix vectors and x_j scalars are in flight while
+    // the current one is being used
+    Vec<T> b0[KTW][NC], b1[KTW][NC];
+    T xj0[NC], xj1[NC];
+    auto load_cg = [&](Vec<T>(&buf)[KTW][NC], T(&xjb)[NC], int cg) {
+        const int64_t jg = J0 + (int64_t)cg * NC;
+#pragma unroll
+        for (int q = 0; q < KTW; ++q) {
+            if (fast[q]) {
+                const T* src = colbase + (int64_t)cg * NC * lda + rq[q];
+#pragma unroll
+                for (int c = 0; c < NC; ++c) buf[q][c] = load_stream(src + (int64_t)c * lda);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) xjb[c] = (jg + c < n) ? x[jg + c] : zero_of<T>();
+    };
+    auto compute_cg = [&](const Vec<T>(&buf)[KTW][NC], const T(&xjb)[NC], int cg) {
+        const int64_t jg = J0 + (int64_t)cg * NC;
+        T accT[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) accT[c] = zero_of<T>();
+#pragma unroll
+        for (int q = 0; q < KTW; ++q) {
+            if (fast[q]) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        fma_acc(accN[q][v], buf[q][c].e[v], xjb[c]);
+                        fma_op<HERM>(accT[c], buf[q][c].e[v], xi[q].e[v]);
+                    }
+            } else if (valid[q]) {
+                // edge / diagonal tile: element loads, all issued before the first
+                // use; a pair outside the stored triangle loads the (always
+                // stored) diagonal element of its column instead and is skipped
+                T av[VEC][NC];
+                bool ins[VEC][NC], dia[VEC][NC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const int64_t row = rq[q] + v;
+                    const bool rowok = row >= 0 && row < n;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const int64_t j = jg + c;
+                        const int64_t jc = j < n ? j : n - 1;
+                        ins[v][c] = rowok && j < n && (LOWER ? row >= j : row <= j);
+                        dia[v][c] = (row == j);
+                        av[v][c] = load_elem_stream(a.A + (ins[v][c] ? row : jc) + jc * lda);
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const T an = (HERM && dia[v][c]) ? real_part_only(av[v][c]) : av[v][c];
+                        T nn = accN[q][v], nt = accT[c];
+                        fma_acc(nn, an, xjb[c]);
+                        fma_op<HERM>(nt, av[v][c], xi[q].e[v]);
+                        accN[q][v] = ins[v][c] ? nn : accN[q][v];
+                        accT[c] = (ins[v][c] && !dia[v][c]) ? nt : accT[c];
+                    }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const T s = wave_sum(accT[c]);
+            if (lane == 0) tpart[w][cg * NC + c] = s;
+        }
     };
 
-    // masked prefix, interior run (register double buffer), masked suffix
-    int64_t t = tbeg;
-    while (t < tend && !is_interior(t)) { masked_tile(t); ++t; }
-    int64_t tin_end = t;
-    while (tin_end < tend && is_interior(tin_end)) ++tin_end;
-    if (t < tin_end) load_tile(xi0, b0, t);
-    for (; t < tin_end; t += 2) {
-        if (t + 1 < tin_end) load_tile(xi1, b1, t + 1);
-        compute_tile(xi0, b0, t);
-        if (t + 1 < tin_end) {
-            if (t + 2 < tin_end) load_tile(xi0, b0, t + 2);
-            compute_tile(xi1, b1, t + 1);
+    load_cg(b0, xj0, 0);
+    for (int cg = 0; cg < CGS; cg += 2) {
+        if (cg + 1 < CGS) load_cg(b1, xj1, cg + 1);
+        compute_cg(b0, xj0, cg);
+        if (cg + 1 < CGS) {
+            if (cg + 2 < CGS) load_cg(b0, xj0, cg + 2);
+            compute_cg(b1, xj1, cg + 1);
         }
     }
-    for (t = tin_end; t < tend; ++t) masked_tile(t);
 
-    // transposed part: one wave reduction per column, this wave owns its columns
-    T* __restrict__ wst = a.wst + (p * a.plan.max_chunks + (int64_t)blockIdx.x) * C + (int64_t)w * CW;
+    // row sums: one 16-byte store per lane and tile into wsn[panel][row slot]
+    T* __restrict__ wsn = a.wsn + p * a.plan.rows_padded + a.plan.shift;
 #pragma unroll
-    for (int c = 0; c < CW; ++c) {
-        const T s = wave_sum(accT[c]);
-        if (lane == 0) wst[c] = s;
+    for (int q = 0; q < KTW; ++q) {
+        if (valid[q]) {
+            Vec<T> o;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) o.e[v] = accN[q][v];
+            store_vec(wsn + rq[q], o);
+        }
+    }
+    // column sums of the NW waves meet in LDS and are added in wave order
+    __syncthreads();
+    if (threadIdx.x < C) {
+        const int c = threadIdx.x;
+        T s = tpart[0][c];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) s = add_of(s, tpart[ww][c]);
+        a.wst[(p * a.plan.max_chunks + (int64_t)blockIdx.x) * C + c] = s;
     }
 }
 
@@ -226,6 +249,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
             pend = a.plan.npanels;
         }
         const T* __restrict__ wsn = a.wsn + slot;
+#pragma unroll 4
         for (int64_t p = pbeg + g; p < pend; p += RED_PARTS) s = add_of(s, wsn[p * a.plan.rows_padded]);
     }
     part[g][lx] = s;
@@ -249,49 +273,59 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda) {
     (void)lower;
     constexpr int TR = tile_rows<T>();
-    const int64_t C = panel_cols<T>();
     SymvPlan<T> p;
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
+    // sizing takes the settings that need the most room: narrow panels, one tile per wave
+    int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
+    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave : DEFAULT_TILES_PER_WAVE;
+    if (sizing) { C = 64; ktw = 1; }
+    p.panel_cols = C;
     p.npanels = ceil_div(n, C);
-    int64_t ct = tuning().symv_chunk_tiles > 0 ? tuning().symv_chunk_tiles : DEFAULT_CHUNK_TILES;
-    if (ct > MAX_CHUNK_TILES) ct = MAX_CHUNK_TILES;
-    p.chunk_tiles = ct;
-    p.max_chunks = ceil_div(p.ntiles, ct);
-    p.rows_padded = p.ntiles * TR;
+    p.chunk_tiles = SY_NW * ktw;
+    p.max_chunks = ceil_div(p.ntiles, p.chunk_tiles);
+    p.rows_padded = partial_stride<T>(p.ntiles * TR);
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
     p.wst_off = p.wsn_off + round_up((size_t)p.npanels * p.rows_padded * sizeof(T), WS_ALIGN);
-    // sizing: one chunk per tile is the largest column-sum area any tuning needs
-    const int64_t size_chunks = sizing ? p.ntiles : p.max_chunks;
-    p.total_bytes = p.wst_off + round_up((size_t)p.npanels * size_chunks * C * sizeof(T), WS_ALIGN);
+    p.total_bytes = p.wst_off + round_up((size_t)p.npanels * p.max_chunks * C * sizeof(T), WS_ALIGN);
     return p;
 }
 
-template <class T, bool HERM> static hipError_t launch_symv_impl(const SymvArgs<T>& a, bool lower, hipStream_t s) {
+namespace {
+template <class T, bool HERM, bool LOWER, int CGS, int KTW>
+void launch_main(const SymvArgs<T>& a, hipStream_t s) {
     const dim3 grid((unsigned)a.plan.max_chunks, (unsigned)a.plan.npanels);
-    if (lower)
-        hipLaunchKernelGGL((symv_kernel<T, HERM, true, SY_CW, SY_NW, SY_KT>), grid, dim3(SY_NW * WAVE), 0, s, a);
-    else
-        hipLaunchKernelGGL((symv_kernel<T, HERM, false, SY_CW, SY_NW, SY_KT>), grid, dim3(SY_NW * WAVE), 0, s, a);
+    hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, SY_NC, CGS, KTW, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
+}
+template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
+    const int cgs = (int)(a.plan.panel_cols / SY_NC), ktw = (int)(a.plan.chunk_tiles / SY_NW);
+    if (cgs == 8 && ktw == 1) launch_main<T, HERM, LOWER, 8, 1>(a, s);
+    else if (cgs == 8 && ktw == 2) launch_main<T, HERM, LOWER, 8, 2>(a, s);
+    else if (cgs == 16 && ktw == 1) launch_main<T, HERM, LOWER, 16, 1>(a, s);
+    else if (cgs == 16 && ktw == 2) launch_main<T, HERM, LOWER, 16, 2>(a, s);
+    else return false;
+    return true;
+}
+}  // namespace
+
+template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s) {
+    constexpr bool HERM = Traits<T>::cplx;
+    const bool ok = lower ? dispatch_main<T, HERM, true>(a, s) : dispatch_main<T, HERM, false>(a, s);
+    if (!ok) return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 rgrid((unsigned)ceil_div(a.n, RED_ROWS));
     const dim3 rblock(RED_ROWS, RED_PARTS);
     if (lower)
-        hipLaunchKernelGGL((symv_reduce_kernel<T, true>), rgrid, rblock, 0, s, a, (int)panel_cols<T>());
+        hipLaunchKernelGGL((symv_reduce_kernel<T, true>), rgrid, rblock, 0, s, a, (int)a.plan.panel_cols);
     else
-        hipLaunchKernelGGL((symv_reduce_kernel<T, false>), rgrid, rblock, 0, s, a, (int)panel_cols<T>());
+        hipLaunchKernelGGL((symv_reduce_kernel<T, false>), rgrid, rblock, 0, s, a, (int)a.plan.panel_cols);
     return hipGetLastError();
 }
 
-template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s) {
-    return launch_symv_impl<T, Traits<T>::cplx>(a, lower, s);
-}
-
 #define KMV_INSTANTIATE_SYMV(T)                                                       \
-    template int panel_cols<T>();                                                     \
     template SymvPlan<T> plan_symv<T>(bool, int64_t, const void*, int64_t);           \
     template hipError_t launch_symv<T>(const SymvArgs<T>&, bool, hipStream_t);
 KMV_INSTANTIATE_SYMV(float)

@@ -1,0 +1,167 @@
+"""Helpers of the GPU parity tests: run one product through the C ABI and through
+the CPU oracle on the same bytes, and measure the error the way the tolerance
+is stated (normwise relative, plus the componentwise n-scaled bound)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_1410_1726_amd import workloads as wl
+
+# tolerances of the target: normwise relative error against the extended-
+# accumulation oracle
+NORMWISE_TOL = {"s": 1e-5, "c": 1e-5, "d": 1e-13, "z": 1e-13}
+UNIT_ROUNDOFF = {"s": 2.0 ** -24, "c": 2.0 ** -24, "d": 2.0 ** -53, "z": 2.0 ** -53}
+NP_DTYPES = oracle.DTYPES
+DEV = "cuda"
+
+
+def kmv():
+    from paper_1410_1726_amd import binding
+    return binding
+
+
+def gamma(k: int, prec: str) -> float:
+    """Deterministic rounding bound gamma_k = k*u / (1 - k*u) for a length-k sum in
+    ANY order; complex products carry a small constant factor (sqrt(2)*gamma_2
+    per product), covered by doubling k + 4."""
+    u = UNIT_ROUNDOFF[prec]
+    k = 2 * (k + 4) if prec in "cz" else (k + 2)
+    return k * u / (1 - k * u)
+
+
+def logical(buf, n, inc):
+    v = buf[:: abs(inc)][:n]
+    return v if inc > 0 else v[::-1]
+
+
+class Errors:
+    def __init__(self, normwise, componentwise, bound):
+        self.normwise, self.componentwise, self.bound = normwise, componentwise, bound
+
+    def __repr__(self):
+        return f"normwise={self.normwise:.3e} componentwise={self.componentwise:.3e} (gamma bound {self.bound:.3e})"
+
+
+def errors(prec, got, want_x, denom, lenx) -> Errors:
+    """got: GPU result (working precision), want_x: MODE_X oracle result, denom:
+    MODE_ABS oracle result, all logical (unstrided) vectors of the same outputs."""
+    got = got.astype(want_x.dtype)
+    diff = np.abs(got - want_x)
+    nrm = np.linalg.norm(want_x)
+    normwise = float(np.linalg.norm(got - want_x) / nrm) if nrm > 0 else float(np.linalg.norm(got - want_x))
+    ok = denom > 0
+    comp = float(np.max(diff[ok] / denom[ok])) if np.any(ok) else 0.0
+    if np.any(~ok):
+        assert np.all(diff[~ok] == 0)
+    return Errors(normwise, comp, gamma(lenx, prec))
+
+
+def check(prec, err: Errors, what=""):
+    assert np.isfinite(err.normwise), f"{what}: non-finite result"
+    assert err.normwise <= NORMWISE_TOL[prec], f"{what}: {err}"
+    # final rounding of alpha*sum + beta*y adds a few u on top of the sum bound
+    assert err.componentwise <= err.bound + 4 * UNIT_ROUNDOFF[prec], f"{what}: {err}"
+
+
+def gemv_case(prec, trans, m, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uniform", seed=0,
+              row_off=0, col_off=0, parent=None, sample=None, poison_outside=True):
+    """Run kmv_<prec>gemv and the oracle on one seeded problem.
+
+    The matrix is the m x n block at (row_off, col_off) of a parent stored with
+    leading dimension lda; everything of the parent outside the block is NaN
+    when poison_outside.  Returns (y_gpu_logical, Errors, extras)."""
+    k = kmv()
+    lda = (m + row_off if lda is None else lda)
+    lda = max(lda, 1)
+    if parent is None:
+        parent = wl.matrix(prec, m + row_off, n + col_off, lda, dist=dist, seed=seed, device=DEV)
+    if poison_outside and (row_off or col_off or parent.shape[0] > n + col_off):
+        keep = parent[col_off:col_off + n, row_off:row_off + m].clone()
+        parent.fill_(float("nan"))
+        parent[col_off:col_off + n, row_off:row_off + m] = keep
+        del keep
+    A = parent[col_off:, row_off:] if (row_off or col_off) else parent
+    leny, lenx = (m, n) if trans.upper() == "N" else (n, m)
+    x = wl.vector(prec, lenx, incx, dist=dist, seed=seed, which=1, device=DEV, gap_value=float("nan"))
+    y0 = wl.vector(prec, leny, incy, dist=dist, seed=seed, which=2, device=DEV, gap_value=float("nan"))
+    y = y0.clone()
+    k.GEMV[prec](trans, m, n, alpha, A, lda, x, incx, beta, y, incy)
+    torch.cuda.synchronize()
+    yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
+    # positions of y that are not outputs must be bit-unchanged (NaN canaries)
+    if abs(incy) > 1 and leny:
+        gaps = np.ones(yh.size, dtype=bool)
+        gaps[:: abs(incy)] = False
+        assert np.array_equal(yh[gaps].view(np.uint8), y0h[gaps].view(np.uint8)), "wrote between the elements of y"
+    got = logical(yh, leny, incy)
+    if sample is None:
+        Ah = parent[: col_off + n].cpu().numpy().reshape(-1)[col_off * lda + row_off:]
+        kw = dict(lda=lda, incx=incx, incy=incy)
+        want = logical(oracle.gemv(prec, trans, m, n, alpha, Ah, xh, beta, y0h, mode=oracle.MODE_X, **kw), leny, incy)
+        den = logical(oracle.gemv(prec, trans, m, n, alpha, Ah, xh, beta, y0h, mode=oracle.MODE_ABS, **kw), leny, incy)
+        idx = slice(None)
+    else:
+        # only the sampled outputs: gather the rows (N) or columns (T/C) they need
+        # into a compact matrix on the device, then run the oracle on that
+        idx = np.asarray(sample)
+        it = torch.as_tensor(idx, device=DEV)
+        if trans.upper() == "N":
+            As = A[:n, :].index_select(1, it).contiguous().cpu().numpy().reshape(-1)   # |S| x n, lda = |S|
+            ms, ns, ld = idx.size, n, max(idx.size, 1)
+        else:
+            As = A.index_select(0, it)[:, :m].contiguous().cpu().numpy().reshape(-1)   # m x |S|, lda = m
+            ms, ns, ld = m, idx.size, max(m, 1)
+        ys = np.ascontiguousarray(logical(y0h, leny, incy)[idx])
+        want = oracle.gemv(prec, trans, ms, ns, alpha, As, logical(xh, lenx, incx).copy(), beta, ys, lda=ld, mode=oracle.MODE_X)
+        den = oracle.gemv(prec, trans, ms, ns, alpha, As, logical(xh, lenx, incx).copy(), beta, ys, lda=ld, mode=oracle.MODE_ABS)
+        got = got[idx]
+    err = errors(prec, got, want, den, lenx)
+    return got, err, dict(want=want, y_full=logical(yh, leny, incy))
+
+
+def symv_case(prec, uplo, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uniform", seed=0,
+              off=0, sample=None, nan_imag_diag=False, parent=None, parent_host=None, poison=True):
+    """Run kmv symv/hemv and the oracle; with `poison` the unreferenced triangle
+    and everything outside the block of the parent are NaN on the device (the
+    host copy handed to the oracle is taken before: the oracle indexes the
+    stored triangle only)."""
+    k = kmv()
+    lda = max(n + off if lda is None else lda, 1)
+    if parent is None:
+        parent = wl.matrix(prec, n + off, n + off, lda, dist=dist, seed=seed, device=DEV)
+    if parent_host is None:
+        parent_host = parent.cpu().numpy().reshape(-1)     # before poisoning: the oracle reads only the triangle
+    A = parent[off:, off:] if off else parent
+    if poison:
+        if off or parent.shape[0] > n + off:
+            keep = A[:n, :n].clone()
+            parent.fill_(float("nan"))
+            A[:n, :n] = keep
+            del keep
+        wl.poison_triangle(A, n, uplo, real_diag=False)
+    if nan_imag_diag and prec in "cz":
+        d = torch.arange(n, device=DEV)
+        torch.view_as_real(A)[d, d, 1] = float("nan")
+    x = wl.vector(prec, n, incx, dist=dist, seed=seed, which=1, device=DEV, gap_value=float("nan"))
+    y0 = wl.vector(prec, n, incy, dist=dist, seed=seed, which=2, device=DEV, gap_value=float("nan"))
+    if beta == 0:
+        y0.fill_(float("nan"))      # beta = 0: y must not be read
+    y = y0.clone()
+    k.SYMV[prec](uplo, n, alpha, A, lda, x, incx, beta, y, incy)
+    torch.cuda.synchronize()
+    yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
+    if abs(incy) > 1 and n:
+        gaps = np.ones(yh.size, dtype=bool)
+        gaps[:: abs(incy)] = False
+        assert np.array_equal(yh[gaps].view(np.uint8), y0h[gaps].view(np.uint8)), "wrote between the elements of y"
+    got = logical(yh, n, incy)
+    Ah = parent_host[off * lda + off:]
+    y0o = np.zeros_like(y0h) if beta == 0 else y0h
+    kw = dict(lda=lda, incx=incx, incy=incy, sample=sample)
+    want = logical(oracle.symv(prec, uplo, n, alpha, Ah, xh, beta, y0o, mode=oracle.MODE_X, **kw), n, incy)
+    den = logical(oracle.symv(prec, uplo, n, alpha, Ah, xh, beta, y0o, mode=oracle.MODE_ABS, **kw), n, incy)
+    idx = slice(None) if sample is None else np.asarray(sample)
+    err = errors(prec, got[idx], want[idx], den[idx], n)
+    return got, err, dict(want=want, parent_host=parent_host)

@@ -106,14 +106,17 @@ def test_workspace_sizes():
 
 def test_tuning_keys_roundtrip():
     keys = kmv.tuning_keys()
-    assert "symv_chunk_tiles" in keys
+    assert "symv_panel_cols" in keys
     for k in keys:
         old = kmv.get_tuning(k)
-        kmv.set_tuning(k, 4)
-        assert kmv.get_tuning(k) == 4
+        val = 64 if k == "symv_panel_cols" else 2
+        kmv.set_tuning(k, val)
+        assert kmv.get_tuning(k) == val
         kmv.set_tuning(k, old)
     with pytest.raises(ValueError):
         kmv.set_tuning("no_such_key", 1)
     with pytest.raises(ValueError):
         kmv.set_tuning("gemv_n_splits", 100000)
+    with pytest.raises(ValueError):
+        kmv.set_tuning("symv_panel_cols", 96)
     assert "kmv" in kmv.version()

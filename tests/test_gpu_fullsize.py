@@ -1,0 +1,112 @@
+"""Parity at the full benchmark sizes, in the launch configuration the benchmark
+times (default tuning): the oracle computes a sample of output elements one by
+one (both ends, tile-boundary neighbourhoods, seeded random picks) and every
+sampled element must meet the normwise tolerance and the componentwise bound.
+Inputs follow the benchmark configurations: the size sweep (lda = n, U[-1,1]),
+the symmetric sweep with the unreferenced triangle set to NaN, sub-blocks of a
+20000 x 20000 fp64 parent at unaligned offsets, and the largest shapes with
+lda = n + 32, N(0,1) entries and a strided x."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1410_1726_amd import workloads as wl
+
+from gpu_util import DEV, check, gemv_case, symv_case
+
+pytestmark = pytest.mark.gpu
+
+NSAMPLE = 48
+
+
+def samples(n, seed):
+    return wl.sample_indices(n, NSAMPLE, seed).numpy()
+
+
+def free():
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+# ---- size sweep: SGEMV / DGEMV, N and T, lda = n, alpha = beta = 1 ------------
+@pytest.mark.parametrize("prec", "sd")
+@pytest.mark.parametrize("n", [16384, 17001, 32768])
+def test_gemv_sweep_sizes(prec, n):
+    parent = wl.matrix(prec, n, n, n, seed=0, device=DEV)
+    for trans in "NT":
+        _, err, _ = gemv_case(prec, trans, n, n, 1.0, 1.0, lda=n, seed=0, parent=parent, sample=samples(n, 1),
+                              poison_outside=False)
+        check(prec, err, f"{prec}gemv {trans} n={n}")
+    del parent
+    free()
+
+
+# ---- symmetric sweep: DSYMV / ZHEMV, L and U, other triangle NaN, beta = 0 -----
+@pytest.mark.parametrize("prec", "dz")
+def test_symv_sweep_largest(prec):
+    n = 32768
+    host = None
+    for uplo in "LU":
+        parent = wl.matrix(prec, n, n, n, seed=0, device=DEV)      # regenerated: the run poisons it
+        _, err, ex = symv_case(prec, uplo, n, 1.0, 0.0, lda=n, seed=0, parent=parent, parent_host=host,
+                               sample=samples(n, 2), nan_imag_diag=True)
+        host = ex["parent_host"]
+        check(prec, err, f"symv/hemv {prec} {uplo} n={n}")
+        del parent
+        free()
+
+
+# ---- sub-blocks of a 20000 x 20000 fp64 parent, alpha = -1, beta = 1 -----------
+PARENT_N = 20000
+_parent_host = {}
+
+
+def parent20k():
+    p = wl.matrix("d", PARENT_N, PARENT_N, PARENT_N, seed=4, device=DEV)
+    if "h" not in _parent_host:
+        _parent_host["h"] = p.cpu().numpy().reshape(-1)
+    return p, _parent_host["h"]
+
+
+@pytest.mark.parametrize("off", [1, 17, 63, 1000])
+def test_subblocks_of_20000_parent(off):
+    for n in (2048, 8192, 19000 - off):
+        for trans in "NT":
+            parent, _ = parent20k()
+            _, err, _ = gemv_case("d", trans, n, n, -1.0, 1.0, lda=PARENT_N, row_off=off, col_off=off, seed=4,
+                                  parent=parent, sample=samples(n, 3))
+            check("d", err, f"dgemv {trans} block n={n} at offset {off}")
+            del parent
+        parent, host = parent20k()
+        _, err, _ = symv_case("d", "L", n, -1.0, 1.0, lda=PARENT_N, off=off, seed=4, parent=parent,
+                              parent_host=host, sample=samples(n, 3))
+        check("d", err, f"dsymv L block n={n} at offset {off}")
+        del parent
+        free()
+
+
+def test_release_parent_host_copy():
+    _parent_host.clear()
+    free()
+
+
+# ---- largest shapes: lda = n + 32, N(0,1), alpha 0.7, beta 0.3, incx 1 and 2 ---
+@pytest.mark.parametrize("prec", "sdcz")
+def test_largest_shapes(prec):
+    n = 49152 if prec in "sc" else 40960
+    lda = n + 32
+    parent = wl.matrix(prec, n, n, lda, dist="normal", seed=5, device=DEV, pad_nan=True)
+    host = parent.cpu().numpy().reshape(-1)
+    for incx in (1, 2):
+        for trans in "NT":
+            _, err, _ = gemv_case(prec, trans, n, n, 0.7, 0.3, lda=lda, incx=incx, dist="normal", seed=5,
+                                  parent=parent, sample=samples(n, 4), poison_outside=False)
+            check(prec, err, f"{prec}gemv {trans} n={n} incx={incx}")
+        for uplo in "LU":
+            _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, lda=lda, incx=incx, dist="normal", seed=5,
+                                  parent=parent, parent_host=host, sample=samples(n, 4), poison=False)
+            check(prec, err, f"symv/hemv {prec} {uplo} n={n} incx={incx}")
+    del parent, host
+    free()

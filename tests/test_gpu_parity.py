@@ -1,0 +1,273 @@
+"""GPU parity tests: every product goes through the C ABI (ctypes binding) and is
+compared with the CPU oracle on the same seeded inputs.
+
+Bars: integer-valued inputs (every summation order is exact) must match
+bitwise; random inputs must match the extended-accumulation oracle within a
+normwise relative error of 1e-5 (s, c) / 1e-13 (d, z), and every component
+within the order-independent bound gamma_{n+2} * (|alpha||A||x| + |beta||y|).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1410_1726_amd import workloads as wl
+
+from gpu_util import DEV, check, gemv_case, kmv, logical, symv_case
+
+pytestmark = pytest.mark.gpu
+
+PRECS = "sdcz"
+TINY = [1, 2, 3, 5, 8, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257]
+
+
+def scalars(prec, a, b):
+    """complex routines get scalars with an imaginary part"""
+    if prec in "cz":
+        return complex(a, 0.25 * a), complex(b, -0.5 * b)
+    return a, b
+
+
+# ------------------------------------------------------------------ GEMV ----
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "NTC")
+def test_gemv_tiny_shapes_bitwise(prec, trans):
+    """small integers: exact in any order, so GPU == oracle bit for bit; covers
+    every combination of head / tail / single-tile shapes"""
+    alpha, beta = scalars(prec, 2, -3)
+    for i, m in enumerate(TINY):
+        for n in TINY[i % 3:: 3]:
+            got, err, ex = gemv_case(prec, trans, m, n, alpha, beta, dist="smallint", seed=m * 7 + n, lda=m + (n % 4))
+            assert np.array_equal(got.astype(ex["want"].dtype), ex["want"]), (m, n, err)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "NT")
+@pytest.mark.parametrize("m,n", [(1024, 1024), (1000, 1000), (4099, 4099), (2500, 700), (700, 2500), (5000, 33), (33, 5000)])
+def test_gemv_medium_full_oracle(prec, trans, m, n):
+    """several tiles, ragged tails, lda == m (per-column alignment drift for the odd sizes)"""
+    alpha, beta = scalars(prec, 1.0, 1.0)
+    _, err, _ = gemv_case(prec, trans, m, n, alpha, beta, seed=1)
+    check(prec, err, f"{prec}gemv {trans} {m}x{n}")
+
+
+def test_dgemv_config1():
+    """DGEMV N, m = n = lda = 1024, U[-1,1], alpha 1.5, beta 0.5, seed 0"""
+    _, err, _ = gemv_case("d", "N", 1024, 1024, 1.5, 0.5, seed=0)
+    check("d", err, "config 1")
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "NC")
+@pytest.mark.parametrize("incx,incy", [(2, 1), (1, 2), (-1, -1), (-3, 2)])
+def test_gemv_strides(prec, trans, incx, incy):
+    alpha, beta = scalars(prec, 0.7, 0.3)
+    _, err, _ = gemv_case(prec, trans, 777, 1301, alpha, beta, incx=incx, incy=incy, lda=800, seed=2)
+    check(prec, err, f"{prec}gemv {trans} inc {incx},{incy}")
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "NT")
+@pytest.mark.parametrize("off", [1, 17, 63, 1000])
+def test_gemv_subblock_offsets(prec, trans, off):
+    """sub-block at (off, off) of a parent whose lda keeps columns 128-byte
+    aligned; everything outside the block is NaN"""
+    m, n, lda = 1500, 900, 2560
+    alpha, beta = scalars(prec, -1.0, 1.0)
+    _, err, _ = gemv_case(prec, trans, m, n, alpha, beta, lda=lda, row_off=off, col_off=off, seed=3)
+    check(prec, err, f"{prec}gemv {trans} offset {off}")
+    # and with a leading dimension that drifts the alignment column by column
+    _, err, _ = gemv_case(prec, trans, 600, 500, alpha, beta, lda=600 + off + 3, row_off=off, col_off=2, seed=4)
+    check(prec, err, f"{prec}gemv {trans} offset {off} odd lda")
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_gemv_alpha_beta_special_cases(prec):
+    k = kmv()
+    m, n = 300, 200
+    dt = wl.TORCH_DTYPES[prec]
+    nan = float("nan")
+    A = torch.full((n, m), nan, dtype=dt, device=DEV)
+    x = torch.full((n,), nan, dtype=dt, device=DEV)
+    y0 = wl.vector(prec, m, seed=5, which=2, device=DEV)
+    # alpha = 0: A and x (all NaN) are not read, y = beta*y exactly
+    y = y0.clone()
+    k.GEMV[prec]("N", m, n, 0.0, A, m, x, 1, 0.5, y, 1)
+    assert torch.equal(y, y0 * 0.5)
+    # alpha = 0 and beta = 0: zeros even from a NaN y
+    y = torch.full((m,), nan, dtype=dt, device=DEV)
+    k.GEMV[prec]("N", m, n, 0.0, A, m, x, 1, 0.0, y, 1)
+    assert torch.equal(y, torch.zeros_like(y))
+    # alpha = 0 and beta = 1: y untouched
+    y = y0.clone()
+    k.GEMV[prec]("T", n, m, 0.0, A, n, x, 1, 1.0, y, 1)
+    assert torch.equal(y, y0)
+    # beta = 0: a NaN y is overwritten, never read (both the direct and the split path)
+    for (mm, nn, trans) in [(300, 200, "N"), (300, 200, "T"), (64, 5000, "N"), (5000, 64, "T")]:
+        Ar = wl.matrix(prec, mm, nn, seed=6, device=DEV)
+        lenx, leny = (nn, mm) if trans == "N" else (mm, nn)
+        xr = wl.vector(prec, lenx, seed=6, device=DEV)
+        ynan = torch.full((leny,), nan, dtype=dt, device=DEV)
+        yzero = torch.zeros((leny,), dtype=dt, device=DEV)
+        k.GEMV[prec](trans, mm, nn, 1.0, Ar, mm, xr, 1, 0.0, ynan, 1)
+        k.GEMV[prec](trans, mm, nn, 1.0, Ar, mm, xr, 1, 0.0, yzero, 1)
+        assert torch.isfinite(torch.view_as_real(ynan) if ynan.is_complex() else ynan).all()
+        assert torch.equal(ynan, yzero)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_identity_and_ones_closed_forms(prec):
+    """A = I gives alpha*x + beta*y exactly; A = ones with integer x gives
+    alpha*sum(x) + beta*y exactly, in every precision and summation order"""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    n = 1300
+    I = torch.eye(n, dtype=dt, device=DEV)
+    x = wl.vector(prec, n, seed=7, device=DEV)
+    y0 = wl.vector(prec, n, seed=7, which=2, device=DEV)
+    want = 2.0 * x + 0.5 * y0
+    for trans in "NTC":
+        y = y0.clone()
+        k.GEMV[prec](trans, n, n, 2.0, I, n, x, 1, 0.5, y, 1)
+        assert torch.equal(y, want)
+    for uplo in "LU":
+        y = y0.clone()
+        k.SYMV[prec](uplo, n, 2.0, wl.poison_triangle(I.clone(), n, uplo), n, x, 1, 0.5, y, 1)
+        assert torch.equal(y, want)
+    m = 2100
+    ones = torch.ones((n, m), dtype=dt, device=DEV)          # m x n matrix of ones
+    xi = wl.vector(prec, n, dist="smallint", seed=8, device=DEV)
+    yi = wl.vector(prec, m, dist="smallint", seed=8, which=2, device=DEV)
+    y = yi.clone()
+    k.GEMV[prec]("N", m, n, 2.0, ones, m, xi, 1, 4.0, y, 1)
+    assert torch.equal(y, 2.0 * xi.sum() + 4.0 * yi)
+    xt = wl.vector(prec, m, dist="smallint", seed=9, device=DEV)
+    yt = wl.vector(prec, n, dist="smallint", seed=9, which=2, device=DEV)
+    y = yt.clone()
+    k.GEMV[prec]("T", m, n, 2.0, ones, m, xt, 1, 4.0, y, 1)
+    assert torch.equal(y, 2.0 * xt.sum() + 4.0 * yt)
+    sq = torch.ones((n, n), dtype=dt, device=DEV)
+    for uplo in "LU":
+        y = torch.zeros(n, dtype=dt, device=DEV)
+        k.SYMV[prec](uplo, n, 2.0, wl.poison_triangle(sq.clone(), n, uplo), n, xi, 1, 0.0, y, 1)
+        assert torch.equal(y, (2.0 * xi.sum()).expand(n))
+
+
+# ------------------------------------------------------------- SYMV / HEMV ----
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+def test_symv_tiny_shapes_bitwise(prec, uplo):
+    alpha, beta = scalars(prec, 2, -3)
+    for n in TINY + [300, 513]:
+        got, err, ex = symv_case(prec, uplo, n, alpha, beta, dist="smallint", seed=n, lda=n + (n % 5),
+                                 nan_imag_diag=True)
+        assert np.array_equal(got.astype(ex["want"].dtype), ex["want"]), (n, err)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+@pytest.mark.parametrize("n", [1024, 1000, 2048, 4099])
+def test_symv_medium_full_oracle(prec, uplo, n):
+    """config 3 shape: referenced triangle random, other triangle NaN, beta = 0
+    with a NaN y; n = 1000 / 4099 add ragged panels and alignment drift"""
+    _, err, _ = symv_case(prec, uplo, n, 1.0, 0.0, seed=10, nan_imag_diag=True)
+    check(prec, err, f"symv {prec} {uplo} n={n}")
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+@pytest.mark.parametrize("incx,incy", [(2, 1), (-1, 3), (1, -2)])
+def test_symv_strides_and_scalars(prec, uplo, incx, incy):
+    alpha, beta = scalars(prec, 0.7, 0.3)
+    _, err, _ = symv_case(prec, uplo, 1237, alpha, beta, incx=incx, incy=incy, lda=1300, seed=11)
+    check(prec, err, f"symv {prec} {uplo} inc {incx},{incy}")
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+@pytest.mark.parametrize("off", [1, 17, 63, 1000])
+def test_symv_subblock_offsets(prec, uplo, off):
+    alpha, beta = scalars(prec, -1.0, 1.0)
+    _, err, _ = symv_case(prec, uplo, 1100, alpha, beta, lda=2304, off=off, seed=12)
+    check(prec, err, f"symv {prec} {uplo} offset {off}")
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_symv_alpha_zero(prec):
+    k = kmv()
+    n = 500
+    dt = wl.TORCH_DTYPES[prec]
+    A = torch.full((n, n), float("nan"), dtype=dt, device=DEV)
+    x = torch.full((n,), float("nan"), dtype=dt, device=DEV)
+    y0 = wl.vector(prec, n, seed=13, which=2, device=DEV)
+    y = y0.clone()
+    k.SYMV[prec]("L", n, 0.0, A, n, x, 1, 0.5, y, 1)
+    assert torch.equal(y, y0 * 0.5)
+
+
+# ------------------------------------------------------------ determinism ----
+@pytest.mark.parametrize("prec", PRECS)
+def test_bitwise_reproducible(prec):
+    """partial sums meet in a workspace in a fixed order: repeated calls agree bit for bit"""
+    k = kmv()
+    n = 3000
+    A = wl.matrix(prec, n, n, seed=14, device=DEV)
+    x = wl.vector(prec, n, seed=14, device=DEV)
+    y0 = wl.vector(prec, n, seed=14, which=2, device=DEV)
+    for call in (lambda y: k.GEMV[prec]("N", n, n, 0.7, A, n, x, 1, 0.3, y, 1),
+                 lambda y: k.GEMV[prec]("T", n, n, 0.7, A, n, x, 1, 0.3, y, 1),
+                 lambda y: k.SYMV[prec]("L", n, 0.7, A, n, x, 1, 0.3, y, 1),
+                 lambda y: k.SYMV[prec]("U", n, 0.7, A, n, x, 1, 0.3, y, 1)):
+        ref = y0.clone()
+        call(ref)
+        for _ in range(5):
+            y = y0.clone()
+            call(y)
+            assert torch.equal(y, ref)
+
+
+def test_split_variants_agree_with_oracle():
+    """every cross-workgroup split count goes through the same fixed-order reduction"""
+    k = kmv()
+    try:
+        for key, trans in (("gemv_n_splits", "N"), ("gemv_t_splits", "T")):
+            for s in (1, 2, 3, 7, 16):
+                k.set_tuning(key, s)
+                _, err, _ = gemv_case("d", trans, 2100, 1900, 0.7, 0.3, seed=15)
+                check("d", err, f"{key}={s}")
+        for cols in (64, 128):
+            for tpw in (1, 2):
+                k.set_tuning("symv_panel_cols", cols)
+                k.set_tuning("symv_tiles_per_wave", tpw)
+                for prec, n in (("z", 1500), ("s", 2300)):
+                    for uplo in "LU":
+                        _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, seed=16)
+                        check(prec, err, f"symv panel_cols={cols} tiles_per_wave={tpw} {prec} {uplo}")
+    finally:
+        for key in k.tuning_keys():
+            k.set_tuning(key, 0)
+
+
+def test_runs_on_a_side_stream_with_explicit_workspace():
+    k = kmv()
+    n = 2000
+    A = wl.matrix("d", n, n, seed=17, device=DEV)
+    x = wl.vector("d", n, seed=17, device=DEV)
+    y0 = wl.vector("d", n, seed=17, which=2, device=DEV)
+    ref = y0.clone()
+    k.dgemv("N", n, n, 1.0, A, n, x, 1, 1.0, ref, 1)
+    ws = torch.empty(k.gemv_workspace_bytes("d", "N", n, n), dtype=torch.uint8, device=DEV)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    y = y0.clone()
+    torch.cuda.synchronize()
+    k.dgemv("N", n, n, 1.0, A, n, x, 1, 1.0, y, 1, workspace=ws, stream=st)
+    st.synchronize()
+    assert torch.equal(y, ref)
+    # a workspace that is too small is refused before anything is enqueued
+    k.set_tuning("gemv_n_splits", 8)
+    try:
+        rc = k.dgemv("N", n, n, 1.0, A, n, x, 1, 1.0, y, 1, workspace=ws[:512], check=False)
+    finally:
+        k.set_tuning("gemv_n_splits", 0)
+    assert rc == k.ERR_WORKSPACE and torch.equal(y, ref)
