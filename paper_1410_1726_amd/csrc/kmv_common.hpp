@@ -14,6 +14,7 @@ struct cf32 { float re, im; };
 struct cf64 { double re, im; };
 
 constexpr int WAVE = 64;
+constexpr int XCDS = 8;   // accelerator dies; consecutive workgroup ids go to consecutive XCDs
 
 template <class T> struct Traits;
 template <> struct Traits<float>  { typedef float real;  static constexpr int VEC = 4; static constexpr bool cplx = false; };
@@ -77,6 +78,12 @@ __device__ __forceinline__ float mul_of(float a, float b) { return a * b; }
 __device__ __forceinline__ double mul_of(double a, double b) { return a * b; }
 __device__ __forceinline__ cf32 mul_of(cf32 a, cf32 b) { cf32 r = zero_of<cf32>(); fma_acc(r, a, b); return r; }
 __device__ __forceinline__ cf64 mul_of(cf64 a, cf64 b) { cf64 r = zero_of<cf64>(); fma_acc(r, a, b); return r; }
+
+// c ? a : b, member by member (keeps complex values in registers)
+__device__ __forceinline__ float select_of(bool c, float a, float b) { return c ? a : b; }
+__device__ __forceinline__ double select_of(bool c, double a, double b) { return c ? a : b; }
+__device__ __forceinline__ cf32 select_of(bool c, cf32 a, cf32 b) { return cf32{c ? a.re : b.re, c ? a.im : b.im}; }
+__device__ __forceinline__ cf64 select_of(bool c, cf64 a, cf64 b) { return cf64{c ? a.re : b.re, c ? a.im : b.im}; }
 
 // HEMV uses only the real part of a diagonal element
 __device__ __forceinline__ float real_part_only(float a) { return a; }

@@ -96,11 +96,13 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     constexpr int TR = WAVE * VEC;
     const int lane = threadIdx.x & (WAVE - 1);
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
-    const int64_t tbase = (int64_t)blockIdx.x * (NW * RT) + w;   // tiles tbase + NW*t, t < RT
+    // grid.x = column split (fastest: consecutive ids, i.e. different XCDs, share
+    // the rows and differ in the columns), grid.y = block of row tiles
+    const int64_t tbase = (int64_t)blockIdx.y * (NW * RT) + w;   // tiles tbase + NW*t, t < RT
     if (tbase >= a.plan.ntiles) return;
 
     int64_t cw, c0;
-    partition(a.n, a.plan.splits, blockIdx.y, cw, c0);
+    partition(a.n, a.plan.splits, blockIdx.x, cw, c0);
     int64_t r[RT];          // first row slot of this lane in each tile (may be outside [0, m))
     bool interior = true;   // all RT tiles fully inside the matrix (wave uniform)
 #pragma unroll
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
             Vec<T> out;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) out.e[v] = acc[t][v];
-            store_vec(a.partial + (int64_t)blockIdx.y * a.plan.part_stride + (r[t] + a.plan.shift), out);
+            store_vec(a.partial + (int64_t)blockIdx.x * a.plan.part_stride + (r[t] + a.plan.shift), out);
         }
     }
 }
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
             for (int v = 0; v < VEC; ++v) {
                 T nacc = acc[c];
                 fma_op<CONJ>(nacc, av[c][v], xv[v]);
-                acc[c] = ok[v] ? nacc : acc[c];
+                acc[c] = select_of(ok[v], nacc, acc[c]);
             }
     };
 
@@ -300,7 +302,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
 
 template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s) {
     const int64_t rt = a.plan.row_tiles;
-    const dim3 grid((unsigned)ceil_div(a.plan.ntiles, GN_NW * rt), (unsigned)a.plan.splits);
+    const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt));
     const dim3 block(GN_NW * WAVE);
     if (rt == 1) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS, 1>), grid, block, 0, s, a);
     else if (rt == 2) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS / 2, 2>), grid, block, 0, s, a);

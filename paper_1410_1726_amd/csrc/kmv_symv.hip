@@ -73,12 +73,21 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
     const int shift = a.plan.shift;
     const T* __restrict__ x = a.x;
 
-    // long panels first: panel 0 is the longest for 'L', the last one for 'U'
-    const int64_t p = LOWER ? (int64_t)blockIdx.y : (a.plan.npanels - 1 - (int64_t)blockIdx.y);
+    // Workgroup ids are dealt round robin to the 8 XCDs, each with its own L2.
+    // All chunks of a panel go to one XCD (panel index = XCD modulo 8), so every
+    // L2 sees the whole range of row offsets: with a power-of-two leading
+    // dimension the lines of one row range in all columns share few L2 sets.
+    // Long panels first: panel 0 is the longest for 'L', the last one for 'U'.
+    const int64_t lin = blockIdx.x;
+    const int64_t slot = lin / XCDS, xcd = lin % XCDS;
+    const int64_t pord = (slot / a.plan.max_chunks) * XCDS + xcd;
+    const int64_t chunk = slot % a.plan.max_chunks;
+    if (pord >= a.plan.npanels) return;
+    const int64_t p = LOWER ? pord : (a.plan.npanels - 1 - pord);
     const int64_t J0 = p * C;
     int64_t tlo, thi;
     panel_tiles<LOWER>(J0, C, n, shift, TR, a.plan.ntiles, tlo, thi);
-    const int64_t tbeg = tlo + (int64_t)blockIdx.x * CT;
+    const int64_t tbeg = tlo + chunk * CT;
     int64_t tend = tbeg + CT;
     if (tend > thi) tend = thi;
     if (tbeg >= tend) return;   // whole workgroup leaves together, before any barrier
@@ -109,7 +118,8 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const int64_t row = rq[q] + v;
-                xi[q].e[v] = (valid[q] && row >= 0 && row < n) ? x[row] : zero_of<T>();
+                const int64_t rc = row < 0 ? 0 : (row >= n ? n - 1 : row);
+                xi[q].e[v] = select_of(valid[q] && row >= 0 && row < n, x[rc], zero_of<T>());
             }
         }
 #pragma unroll
@@ -135,7 +145,7 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
             }
         }
 #pragma unroll
-        for (int c = 0; c < NC; ++c) xjb[c] = (jg + c < n) ? x[jg + c] : zero_of<T>();
+        for (int c = 0; c < NC; ++c) xjb[c] = select_of(jg + c < n, x[jg + c < n ? jg + c : n - 1], zero_of<T>());
     };
     auto compute_cg = [&](const Vec<T>(&buf)[KTW][NC], const T(&xjb)[NC], int cg) {
         const int64_t jg = J0 + (int64_t)cg * NC;
@@ -175,12 +185,12 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
                 for (int v = 0; v < VEC; ++v)
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
-                        const T an = (HERM && dia[v][c]) ? real_part_only(av[v][c]) : av[v][c];
+                        const T an = select_of(HERM && dia[v][c], real_part_only(av[v][c]), av[v][c]);
                         T nn = accN[q][v], nt = accT[c];
                         fma_acc(nn, an, xjb[c]);
                         fma_op<HERM>(nt, av[v][c], xi[q].e[v]);
-                        accN[q][v] = ins[v][c] ? nn : accN[q][v];
-                        accT[c] = (ins[v][c] && !dia[v][c]) ? nt : accT[c];
+                        accN[q][v] = select_of(ins[v][c], nn, accN[q][v]);
+                        accT[c] = select_of(ins[v][c] && !dia[v][c], nt, accT[c]);
                     }
             }
         }
@@ -219,7 +229,7 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
         T s = tpart[0][c];
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) s = add_of(s, tpart[ww][c]);
-        a.wst[(p * a.plan.max_chunks + (int64_t)blockIdx.x) * C + c] = s;
+        a.wst[(p * a.plan.max_chunks + chunk) * C + c] = s;
     }
 }
 
@@ -279,7 +289,9 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.ntiles = ceil_div(n + p.shift, TR);
     // sizing takes the settings that need the most room: narrow panels, one tile per wave
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
-    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave : DEFAULT_TILES_PER_WAVE;
+    // 16-byte elements: one tile per wave keeps the kernel at three waves per SIMD
+    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
+                                                   : (sizeof(T) == 16 ? 1 : DEFAULT_TILES_PER_WAVE);
     if (sizing) { C = 64; ktw = 1; }
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
@@ -296,7 +308,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
 namespace {
 template <class T, bool HERM, bool LOWER, int CGS, int KTW>
 void launch_main(const SymvArgs<T>& a, hipStream_t s) {
-    const dim3 grid((unsigned)a.plan.max_chunks, (unsigned)a.plan.npanels);
+    const dim3 grid((unsigned)(ceil_div(a.plan.npanels, XCDS) * XCDS * a.plan.max_chunks));
     hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, SY_NC, CGS, KTW, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
