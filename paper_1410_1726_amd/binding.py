@@ -16,7 +16,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkmv.so")
+# KMV_LIBRARY selects another build of the same library (tuning experiments)
+LIB_PATH = os.environ.get("KMV_LIBRARY") or os.path.join(_HERE, "libkmv.so")
 
 ERR_WORKSPACE = 1001
 ERR_NULL = 1002

@@ -35,8 +35,10 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found: the kmv library needs the ROCm toolchain")
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every source (always, even when a library exists) and link."""
+def build_library(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
+    """Compile every source (always, even when a library exists) and link.
+    `extra_flags` / `out` build a variant next to the default library."""
+    out = out or LIB
     os.makedirs(BUILD, exist_ok=True)
     hipcc = _hipcc()
 
@@ -52,14 +54,21 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    tmp = LIB + ".tmp"
+    tmp = out + ".tmp"
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    # python -m paper_1410_1726_amd.build [-DFLAG ...] [-o variant.so]
+    args = sys.argv[1:]
+    target = None
+    if "-o" in args:
+        i = args.index("-o")
+        target = os.path.abspath(args[i + 1])
+        del args[i:i + 2]
+    print(build_library(verbose=True, extra_flags=tuple(args), out=target))

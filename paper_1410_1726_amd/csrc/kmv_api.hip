@@ -122,6 +122,7 @@ const Key KEYS[] = {
     {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
     {"symv_panel_cols", &Tuning::symv_panel_cols, 0, 128},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
+    {"symv_classes", &Tuning::symv_classes, 0, 256},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
 };
 
@@ -224,7 +225,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,wg_target"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,symv_classes,wg_target"; }
 
 const char* kmv_version(void) { return "kmv 0.1 (gfx950)"; }
 

@@ -124,6 +124,12 @@ template <class T> __device__ __forceinline__ void store_vec(T* p, const Vec<T>&
     __builtin_memcpy(&raw, &v, 16);
     *reinterpret_cast<u32x4_a4*>(p) = raw;
 }
+// streaming store (written once, read once by a later kernel)
+template <class T> __device__ __forceinline__ void store_vec_stream(T* p, const Vec<T>& v) {
+    u32x4 raw;
+    __builtin_memcpy(&raw, &v, 16);
+    __builtin_nontemporal_store(raw, reinterpret_cast<u32x4_a4*>(p));
+}
 template <class T> __device__ __forceinline__ T load_elem_stream(const T* p) {
     return __builtin_nontemporal_load(p);
 }

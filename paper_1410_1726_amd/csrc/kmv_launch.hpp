@@ -17,7 +17,8 @@ struct Tuning {
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
     int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
     int64_t symv_panel_cols = 0;      // SYMV panel width: 64 or 128 columns
-    int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave and task: 1 or 2
+    int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave: 1 or 2
+    int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
     int64_t wg_target = 0;         // workgroups the heuristics aim for
 };
 Tuning& tuning();
@@ -77,8 +78,9 @@ template <class T> struct SymvPlan {
     int64_t panel_cols;    // columns per panel
     int64_t npanels;       // column panels
     int64_t chunk_tiles;   // row tiles per workgroup
-    int64_t max_chunks;    // workgroups per panel (grid x)
-    int64_t rows_padded;   // distance between the row-sum vectors of two panels (>= ntiles * tile_rows)
+    int64_t nchunks;       // row chunks
+    int64_t classes;       // a chain takes every classes-th panel of its row chunk
+    int64_t rows_padded;   // distance between the row-sum vectors of two classes (>= ntiles * tile_rows)
     size_t xpack_off, wsn_off, wst_off, total_bytes;
 };
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
@@ -90,8 +92,8 @@ template <class T> struct SymvArgs {
     T* y;
     int64_t incy;
     T alpha, beta;
-    T* wsn;           // [npanels][rows_padded]  row sums of each panel ("N part")
-    T* wst;           // [npanels][max_chunks][panel_cols]  column sums ("T part")
+    T* wsn;           // [classes][rows_padded]  row sums of each chain ("N part")
+    T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
     SymvPlan<T> plan;
 };
 template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s);

@@ -10,31 +10,33 @@
 // every block because they belong to different pieces of y; diagonal blocks go
 // to a separate kernel that mirrors them in shared memory (Section 6.5).
 //
-// Kept: the vertical walk of a column panel, the dual use of each element, the
-// register double buffer.  Different, to fit wave64 and the HBM behaviour of
-// the MI355X (a workgroup that touches many columns at the same row offset
-// loses bandwidth, a workgroup that reads a few columns over several KiB of
-// consecutive rows does not):
+// Kept: the dual use of each element, the register double buffer, blocks of
+// the stored triangle as the unit of work.  Different, to fit wave64 and what
+// was measured on the MI355X (small writes scattered through a read stream
+// cost far more than their bytes; a workgroup that reads a few columns over
+// several KiB of consecutive rows streams at full speed; each of the 8 XCDs
+// has its own L2):
 //  * lanes map to 16-byte row vectors, a wave streams 1 KiB of a column per
 //    instruction;
-//  * a workgroup owns (panel of C columns) x (chunk of NW*KTW row tiles); each
-//    wave owns KTW of those row tiles for the whole task and sweeps the panel
-//    in groups of NC columns, so at any moment the workgroup reads NC columns
-//    over NW consecutive KiB;
-//  * the non-transposed row sums of a wave's tiles therefore stay in registers
-//    for the whole panel width and are stored once per task into a workspace
-//    indexed [panel][row] - no shared memory, no barrier and no atomics in the
-//    loop (the paper needs a sync-and-reduce per block);
+//  * a workgroup owns a chunk of NW*KTW row tiles and walks HORIZONTALLY over
+//    a chain of column panels (every Q-th panel that the chunk's rows touch),
+//    each wave keeping the non-transposed row sums of its own KTW tiles in
+//    registers for the whole chain: they are stored once per chain into a
+//    workspace indexed [class][row], instead of once per block;
+//  * inside a panel the workgroup sweeps groups of NC columns, so at any
+//    moment it reads NC columns over NW consecutive KiB; the next group is in
+//    flight (registers) while the current one is used, across panel borders;
 //  * the transposed column sums are reduced across the wave once per column
-//    group (DPP), meet the other waves' in LDS and go to a second workspace
-//    indexed [panel][chunk][column];
-//  * diagonal tiles are handled in the same kernel by predicated element loads
+//    group (DPP), meet the other waves' in LDS once per panel (one barrier per
+//    panel, none inside) and go to a workspace indexed [panel][chunk][column];
+//  * diagonal and edge tiles are handled in the same kernel by element loads
 //    that never touch the other triangle, so the mirrored copy of Section 6.5
 //    is never built;
-//  * the triangle is cut into bounded (panel, chunk) tasks instead of a fixed
-//    (X, Y) grid, which balances the triangular workload.
+//  * consecutive workgroup ids differ in the class, so every XCD sees all row
+//    offsets (with a power-of-two leading dimension the lines of one row range
+//    in all columns share few L2 sets), and long chains are dispatched first.
 // A second kernel adds, in a fixed order, all row sums and column sums that
-// belong to y_i and applies alpha and beta.
+// belong to y_i and applies alpha and beta (no atomics anywhere).
 #include "kmv_launch.hpp"
 
 namespace kmv {
@@ -44,6 +46,8 @@ constexpr int SY_NW = 4;    // waves per workgroup
 constexpr int SY_NC = 8;    // columns per column group
 constexpr int DEFAULT_PANEL_COLS = 64;
 constexpr int DEFAULT_TILES_PER_WAVE = 2;
+constexpr int DEFAULT_CLASSES = 64;
+constexpr int MAX_CLASSES = 256;
 constexpr int RED_ROWS = 32, RED_PARTS = 8;
 }  // namespace
 
@@ -60,6 +64,20 @@ __host__ __device__ __forceinline__ void panel_tiles(int64_t J0, int64_t C, int6
         thi = (jend - 1 + shift) / TR + 1;
     }
 }
+// first / one-past-last panel whose stored part touches the row tiles [tbeg, tend)
+template <bool LOWER>
+__host__ __device__ __forceinline__ void chunk_panels(int64_t tbeg, int64_t tend, int64_t C, int shift, int64_t TR,
+                                                      int64_t npanels, int64_t& plo, int64_t& phi) {
+    if (LOWER) {   // panels with tlo(p) < tend
+        plo = 0;
+        phi = (tend * TR - shift - 1) / C + 1;
+        if (phi > npanels) phi = npanels;
+    } else {       // panels with thi(p) > tbeg  <=>  (p+1)*C >= tbeg*TR - shift + 1
+        const int64_t need = tbeg * TR - shift + 1;
+        plo = need > 0 ? (need + C - 1) / C - 1 : 0;
+        phi = npanels;
+    }
+}
 
 template <class T, bool HERM, bool LOWER, int NC, int CGS, int KTW, int NW>
 __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
@@ -71,75 +89,81 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int64_t n = a.n, lda = a.lda;
     const int shift = a.plan.shift;
+    const int64_t ntiles = a.plan.ntiles;
     const T* __restrict__ x = a.x;
 
-    // Workgroup ids are dealt round robin to the 8 XCDs, each with its own L2.
-    // All chunks of a panel go to one XCD (panel index = XCD modulo 8), so every
-    // L2 sees the whole range of row offsets: with a power-of-two leading
-    // dimension the lines of one row range in all columns share few L2 sets.
-    // Long panels first: panel 0 is the longest for 'L', the last one for 'U'.
-    const int64_t lin = blockIdx.x;
-    const int64_t slot = lin / XCDS, xcd = lin % XCDS;
-    const int64_t pord = (slot / a.plan.max_chunks) * XCDS + xcd;
-    const int64_t chunk = slot % a.plan.max_chunks;
-    if (pord >= a.plan.npanels) return;
-    const int64_t p = LOWER ? pord : (a.plan.npanels - 1 - pord);
-    const int64_t J0 = p * C;
-    int64_t tlo, thi;
-    panel_tiles<LOWER>(J0, C, n, shift, TR, a.plan.ntiles, tlo, thi);
-    const int64_t tbeg = tlo + chunk * CT;
+    // chain = (chunk k, class cls); long chains first: the bottom chunks for
+    // 'L', the top chunks for 'U'
+    const int64_t Q = a.plan.classes;
+    const int64_t cls = (int64_t)blockIdx.x % Q, kord = (int64_t)blockIdx.x / Q;
+    const int64_t k = LOWER ? (a.plan.nchunks - 1 - kord) : kord;
+    const int64_t tbeg = k * CT;
     int64_t tend = tbeg + CT;
-    if (tend > thi) tend = thi;
-    if (tbeg >= tend) return;   // whole workgroup leaves together, before any barrier
-
-    const bool ragged_panel = (J0 + C > n);
-    // a tile is "fast" when all its rows exist, the panel is full width and every
-    // (row, column) pair of the panel lies strictly inside the stored triangle
-    auto is_interior = [&](int64_t t) {
-        const int64_t r0 = t * TR - shift;
-        if (ragged_panel || r0 < 0 || r0 + TR > n) return false;
-        return LOWER ? (r0 > J0 + C - 1) : (r0 + TR - 1 < J0);
-    };
+    if (tend > ntiles) tend = ntiles;
+    int64_t plo, phi;
+    chunk_panels<LOWER>(tbeg, tend, C, shift, TR, a.plan.npanels, plo, phi);
+    const int64_t p0 = plo + ((cls - plo) % Q + Q) % Q;            // first panel of the class
+    const int64_t np = p0 < phi ? (phi - p0 + Q - 1) / Q : 0;      // panels of this chain
+    const int64_t units = np * CGS;
 
     // this wave's row tiles, their x segment and their row-sum accumulators
-    int64_t rq[KTW];
-    bool valid[KTW], fast[KTW];
+    int64_t tq[KTW], rq[KTW];
+    bool inrange[KTW], rowfull[KTW];
     Vec<T> xi[KTW];
     T accN[KTW][VEC];
 #pragma unroll
     for (int q = 0; q < KTW; ++q) {
-        const int64_t t = tbeg + w + (int64_t)NW * q;
-        valid[q] = t < tend;
-        fast[q] = valid[q] && is_interior(t);
-        rq[q] = t * TR - shift + (int64_t)lane * VEC;
-        if (fast[q]) {
+        tq[q] = tbeg + w + (int64_t)NW * q;
+        inrange[q] = tq[q] < tend;
+        const int64_t r0 = tq[q] * TR - shift;
+        rowfull[q] = inrange[q] && r0 >= 0 && r0 + TR <= n;
+        rq[q] = r0 + (int64_t)lane * VEC;
+        if (rowfull[q]) {
             xi[q] = load_cached(x + rq[q]);
         } else {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 const int64_t row = rq[q] + v;
                 const int64_t rc = row < 0 ? 0 : (row >= n ? n - 1 : row);
-                xi[q].e[v] = select_of(valid[q] && row >= 0 && row < n, x[rc], zero_of<T>());
+                xi[q].e[v] = select_of(inrange[q] && row >= 0 && row < n, x[rc], zero_of<T>());
             }
         }
 #pragma unroll
         for (int v = 0; v < VEC; ++v) accN[q][v] = zero_of<T>();
     }
 
-    __shared__ T tpart[NW][C];
-    const T* __restrict__ colbase = a.A + J0 * lda;
+    __shared__ T tpart[2][NW][C];
 
-    // one unit of work = one column group (NC columns) over all KTW tiles of the
-    // wave; the next unit's matrix vectors and x_j scalars are in flight while
-    // the current one is being used
+    // per panel: which of this wave's tiles carry stored elements at all (valid)
+    // and which are "fast": all rows exist, the panel is full width and every
+    // (row, column) pair lies strictly inside the stored triangle
+    auto tile_flags = [&](int64_t p, bool(&valid)[KTW], bool(&fast)[KTW]) {
+        const int64_t J0 = p * C;
+        int64_t tlo, thi;
+        panel_tiles<LOWER>(J0, C, n, shift, TR, ntiles, tlo, thi);
+        const bool ragged = (J0 + C > n);
+#pragma unroll
+        for (int q = 0; q < KTW; ++q) {
+            const int64_t r0 = tq[q] * TR - shift;
+            valid[q] = inrange[q] && tq[q] >= tlo && tq[q] < thi;
+            fast[q] = valid[q] && rowfull[q] && !ragged && (LOWER ? (r0 > J0 + C - 1) : (r0 + TR - 1 < J0));
+        }
+    };
+
+    // one unit of work = one column group (NC columns) of one panel over all KTW
+    // tiles of the wave; the next unit's matrix vectors and x_j scalars are in
+    // flight while the current one is being used
     Vec<T> b0[KTW][NC], b1[KTW][NC];
     T xj0[NC], xj1[NC];
-    auto load_cg = [&](Vec<T>(&buf)[KTW][NC], T(&xjb)[NC], int cg) {
-        const int64_t jg = J0 + (int64_t)cg * NC;
+    auto load_unit = [&](Vec<T>(&buf)[KTW][NC], T(&xjb)[NC], int64_t u) {
+        const int64_t p = p0 + Q * (u / CGS);
+        const int64_t jg = p * C + (u % CGS) * NC;
+        bool valid[KTW], fast[KTW];
+        tile_flags(p, valid, fast);
 #pragma unroll
         for (int q = 0; q < KTW; ++q) {
             if (fast[q]) {
-                const T* src = colbase + (int64_t)cg * NC * lda + rq[q];
+                const T* src = a.A + jg * lda + rq[q];
 #pragma unroll
                 for (int c = 0; c < NC; ++c) buf[q][c] = load_stream(src + (int64_t)c * lda);
             }
@@ -147,8 +171,13 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) xjb[c] = select_of(jg + c < n, x[jg + c < n ? jg + c : n - 1], zero_of<T>());
     };
-    auto compute_cg = [&](const Vec<T>(&buf)[KTW][NC], const T(&xjb)[NC], int cg) {
-        const int64_t jg = J0 + (int64_t)cg * NC;
+    auto compute_unit = [&](const Vec<T>(&buf)[KTW][NC], const T(&xjb)[NC], int64_t u) {
+        const int64_t pi = u / CGS;
+        const int cg = (int)(u % CGS);
+        const int64_t p = p0 + Q * pi;
+        const int64_t jg = p * C + (int64_t)cg * NC;
+        bool valid[KTW], fast[KTW];
+        tile_flags(p, valid, fast);
         T accT[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) accT[c] = zero_of<T>();
@@ -194,73 +223,77 @@ __global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
                     }
             }
         }
+        T(&tp)[NW][C] = tpart[pi & 1];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const T s = wave_sum(accT[c]);
-            if (lane == 0) tpart[w][cg * NC + c] = s;
+            if (lane == 0) tp[w][cg * NC + c] = s;
+        }
+        if (cg == CGS - 1) {
+            // panel finished: the column sums of the NW waves meet in LDS and are
+            // added in wave order.  tpart alternates between two copies, so one
+            // barrier per panel is enough.
+            __syncthreads();
+            if (threadIdx.x < C) {
+                const int c = threadIdx.x;
+                T s = tp[0][c];
+#pragma unroll
+                for (int ww = 1; ww < NW; ++ww) s = add_of(s, tp[ww][c]);
+                a.wst[(p * a.plan.nchunks + k) * C + c] = s;
+            }
         }
     };
 
-    load_cg(b0, xj0, 0);
-    for (int cg = 0; cg < CGS; cg += 2) {
-        if (cg + 1 < CGS) load_cg(b1, xj1, cg + 1);
-        compute_cg(b0, xj0, cg);
-        if (cg + 1 < CGS) {
-            if (cg + 2 < CGS) load_cg(b0, xj0, cg + 2);
-            compute_cg(b1, xj1, cg + 1);
+    if (units > 0) load_unit(b0, xj0, 0);
+    for (int64_t u = 0; u < units; u += 2) {
+        if (u + 1 < units) load_unit(b1, xj1, u + 1);
+        compute_unit(b0, xj0, u);
+        if (u + 1 < units) {
+            if (u + 2 < units) load_unit(b0, xj0, u + 2);
+            compute_unit(b1, xj1, u + 1);
         }
     }
 
-    // row sums: one 16-byte store per lane and tile into wsn[panel][row slot]
-    T* __restrict__ wsn = a.wsn + p * a.plan.rows_padded + a.plan.shift;
+    // row sums of the whole chain: one 16-byte store per lane and tile into
+    // wsn[class][row slot] (zeros where the chain had nothing to add)
+    T* __restrict__ wsn = a.wsn + cls * a.plan.rows_padded + shift;
 #pragma unroll
     for (int q = 0; q < KTW; ++q) {
-        if (valid[q]) {
+        if (inrange[q]) {
             Vec<T> o;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) o.e[v] = accN[q][v];
-            store_vec(wsn + rq[q], o);
+            store_vec_stream(wsn + rq[q], o);
         }
-    }
-    // column sums of the NW waves meet in LDS and are added in wave order
-    __syncthreads();
-    if (threadIdx.x < C) {
-        const int c = threadIdx.x;
-        T s = tpart[0][c];
-#pragma unroll
-        for (int ww = 1; ww < NW; ++ww) s = add_of(s, tpart[ww][c]);
-        a.wst[(p * a.plan.max_chunks + chunk) * C + c] = s;
     }
 }
 
-// y_i = alpha * ( sum over panels of wsn[panel][i] + sum over chunks of
-// wst[panel(i)][chunk][i] ) + beta*y_i, every sum in ascending index order.
-// blockDim = (RED_ROWS, RED_PARTS): the panel range of a row is cut into
-// RED_PARTS interleaved parts that meet in LDS in part order.
+// y_i = alpha * ( sum over classes of wsn[class][i] + sum over chunks of
+// wst[panel(i)][chunk][i] ) + beta*y_i.  blockDim = (RED_ROWS, RED_PARTS): part g
+// adds the classes g, g+RED_PARTS, ... and then the chunks kbeg+g, kbeg+g+
+// RED_PARTS, ... in ascending order; the parts meet in LDS and are added in
+// part order, so the result does not depend on scheduling.
 template <class T, bool LOWER>
-__global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a, int C) {
+__global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a) {
     constexpr int TR = tile_rows<T>();
     const int lx = threadIdx.x, g = threadIdx.y;
     const int64_t i = (int64_t)blockIdx.x * RED_ROWS + lx;
     const int shift = a.plan.shift;
+    const int64_t C = a.plan.panel_cols;
     __shared__ T part[RED_PARTS][RED_ROWS];
     T s = zero_of<T>();
     if (i < a.n) {
-        const int64_t slot = i + shift;
-        const int64_t ti = slot / TR;
-        int64_t pbeg, pend;   // panels whose tile range contains tile ti
-        if (LOWER) {
-            pbeg = 0;
-            pend = ((ti + 1) * TR - shift - 1) / C + 1;
-            if (pend > a.plan.npanels) pend = a.plan.npanels;
-        } else {
-            const int64_t need = ti * TR - shift + 1;   // panels with (p+1)*C >= need
-            pbeg = need > 0 ? (need + C - 1) / C - 1 : 0;
-            pend = a.plan.npanels;
-        }
-        const T* __restrict__ wsn = a.wsn + slot;
+        const T* __restrict__ wsn = a.wsn + i + shift;
 #pragma unroll 4
-        for (int64_t p = pbeg + g; p < pend; p += RED_PARTS) s = add_of(s, wsn[p * a.plan.rows_padded]);
+        for (int64_t q = g; q < a.plan.classes; q += RED_PARTS) s = add_of(s, wsn[q * a.plan.rows_padded]);
+        // chunks whose row tiles intersect the tile range of the panel of column i
+        const int64_t pi = i / C;
+        int64_t tlo, thi;
+        panel_tiles<LOWER>(pi * C, C, a.n, shift, TR, a.plan.ntiles, tlo, thi);
+        const int64_t kbeg = tlo / a.plan.chunk_tiles, kend = (thi - 1) / a.plan.chunk_tiles + 1;
+        const T* __restrict__ wst = a.wst + pi * a.plan.nchunks * C + (i - pi * C);
+#pragma unroll 4
+        for (int64_t k = kbeg + g; k < kend; k += RED_PARTS) s = add_of(s, wst[k * C]);
     }
     part[g][lx] = s;
     __syncthreads();
@@ -268,12 +301,6 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
         T tot = part[0][lx];
 #pragma unroll
         for (int gg = 1; gg < RED_PARTS; ++gg) tot = add_of(tot, part[gg][lx]);
-        const int64_t pi = i / C;
-        int64_t tlo, thi;
-        panel_tiles<LOWER>(pi * C, C, a.n, shift, TR, a.plan.ntiles, tlo, thi);
-        const int64_t nch = ceil_div(thi - tlo, a.plan.chunk_tiles);
-        const T* __restrict__ wst = a.wst + pi * a.plan.max_chunks * C + (i - pi * C);
-        for (int64_t k = 0; k < nch; ++k) tot = add_of(tot, wst[k * C]);
         T* yp = a.y + i * a.incy;
         *yp = epilogue(a.alpha, tot, a.beta, yp);
     }
@@ -287,28 +314,31 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
-    // sizing takes the settings that need the most room: narrow panels, one tile per wave
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
     // 16-byte elements: one tile per wave keeps the kernel at three waves per SIMD
     int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
                                                    : (sizeof(T) == 16 ? 1 : DEFAULT_TILES_PER_WAVE);
-    if (sizing) { C = 64; ktw = 1; }
+    int64_t Q = tuning().symv_classes > 0 ? tuning().symv_classes : DEFAULT_CLASSES;
+    // sizing takes the settings that need the most room
+    if (sizing) { C = 64; ktw = 1; Q = MAX_CLASSES; }
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
+    if (Q > p.npanels && !sizing) Q = p.npanels;
+    p.classes = Q;
     p.chunk_tiles = SY_NW * ktw;
-    p.max_chunks = ceil_div(p.ntiles, p.chunk_tiles);
+    p.nchunks = ceil_div(p.ntiles, p.chunk_tiles);
     p.rows_padded = partial_stride<T>(p.ntiles * TR);
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
-    p.wst_off = p.wsn_off + round_up((size_t)p.npanels * p.rows_padded * sizeof(T), WS_ALIGN);
-    p.total_bytes = p.wst_off + round_up((size_t)p.npanels * p.max_chunks * C * sizeof(T), WS_ALIGN);
+    p.wst_off = p.wsn_off + round_up((size_t)Q * p.rows_padded * sizeof(T), WS_ALIGN);
+    p.total_bytes = p.wst_off + round_up((size_t)p.npanels * p.nchunks * C * sizeof(T), WS_ALIGN);
     return p;
 }
 
 namespace {
 template <class T, bool HERM, bool LOWER, int CGS, int KTW>
 void launch_main(const SymvArgs<T>& a, hipStream_t s) {
-    const dim3 grid((unsigned)(ceil_div(a.plan.npanels, XCDS) * XCDS * a.plan.max_chunks));
+    const dim3 grid((unsigned)(a.plan.nchunks * a.plan.classes));
     hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, SY_NC, CGS, KTW, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
@@ -331,9 +361,9 @@ template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipS
     const dim3 rgrid((unsigned)ceil_div(a.n, RED_ROWS));
     const dim3 rblock(RED_ROWS, RED_PARTS);
     if (lower)
-        hipLaunchKernelGGL((symv_reduce_kernel<T, true>), rgrid, rblock, 0, s, a, (int)a.plan.panel_cols);
+        hipLaunchKernelGGL((symv_reduce_kernel<T, true>), rgrid, rblock, 0, s, a);
     else
-        hipLaunchKernelGGL((symv_reduce_kernel<T, false>), rgrid, rblock, 0, s, a, (int)a.plan.panel_cols);
+        hipLaunchKernelGGL((symv_reduce_kernel<T, false>), rgrid, rblock, 0, s, a);
     return hipGetLastError();
 }
 

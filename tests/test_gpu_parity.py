@@ -235,14 +235,14 @@ def test_split_variants_agree_with_oracle():
                 k.set_tuning(key, s)
                 _, err, _ = gemv_case("d", trans, 2100, 1900, 0.7, 0.3, seed=15)
                 check("d", err, f"{key}={s}")
-        for cols in (64, 128):
-            for tpw in (1, 2):
-                k.set_tuning("symv_panel_cols", cols)
-                k.set_tuning("symv_tiles_per_wave", tpw)
-                for prec, n in (("z", 1500), ("s", 2300)):
-                    for uplo in "LU":
-                        _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, seed=16)
-                        check(prec, err, f"symv panel_cols={cols} tiles_per_wave={tpw} {prec} {uplo}")
+        for cols, tpw, classes in ((64, 1, 1), (64, 2, 3), (128, 1, 8), (128, 2, 5), (64, 2, 256), (64, 1, 16)):
+            k.set_tuning("symv_panel_cols", cols)
+            k.set_tuning("symv_tiles_per_wave", tpw)
+            k.set_tuning("symv_classes", classes)
+            for prec, n in (("z", 1500), ("s", 2300), ("d", 3001)):
+                for uplo in "LU":
+                    _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, seed=16)
+                    check(prec, err, f"symv panel_cols={cols} tiles_per_wave={tpw} classes={classes} {prec} {uplo}")
     finally:
         for key in k.tuning_keys():
             k.set_tuning(key, 0)
