@@ -43,7 +43,8 @@ namespace kmv {
 
 namespace {
 constexpr int SY_NW = 4;    // waves per workgroup
-constexpr int SY_NC = 8;    // columns per column group
+// columns per column group: 8 columns of 16-byte vectors, 4 for 16-byte elements
+template <class T> constexpr int sy_nc() { return sizeof(T) == 16 ? 4 : 8; }
 constexpr int DEFAULT_PANEL_COLS = 64;
 constexpr int DEFAULT_TILES_PER_WAVE = 2;
 constexpr int DEFAULT_CLASSES = 64;
@@ -80,7 +81,7 @@ __host__ __device__ __forceinline__ void chunk_panels(int64_t tbeg, int64_t tend
 }
 
 template <class T, bool HERM, bool LOWER, int NC, int CGS, int KTW, int NW>
-__global__ __launch_bounds__(NW * WAVE) void symv_kernel(SymvArgs<T> a) {
+__global__ __launch_bounds__(NW * WAVE, (sizeof(T) == 16 ? 3 : 2)) void symv_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     constexpr int C = NC * CGS;
@@ -315,9 +316,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
-    // 16-byte elements: one tile per wave keeps the kernel at three waves per SIMD
-    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
-                                                   : (sizeof(T) == 16 ? 1 : DEFAULT_TILES_PER_WAVE);
+    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave : DEFAULT_TILES_PER_WAVE;
     int64_t Q = tuning().symv_classes > 0 ? tuning().symv_classes : DEFAULT_CLASSES;
     // sizing takes the settings that need the most room
     if (sizing) { C = 64; ktw = 1; Q = MAX_CLASSES; }
@@ -336,17 +335,18 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
 }
 
 namespace {
-template <class T, bool HERM, bool LOWER, int CGS, int KTW>
+template <class T, bool HERM, bool LOWER, int C, int KTW>
 void launch_main(const SymvArgs<T>& a, hipStream_t s) {
     const dim3 grid((unsigned)(a.plan.nchunks * a.plan.classes));
-    hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, SY_NC, CGS, KTW, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
+    hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, sy_nc<T>(), C / sy_nc<T>(), KTW, SY_NW>), grid, dim3(SY_NW * WAVE),
+                       0, s, a);
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
-    const int cgs = (int)(a.plan.panel_cols / SY_NC), ktw = (int)(a.plan.chunk_tiles / SY_NW);
-    if (cgs == 8 && ktw == 1) launch_main<T, HERM, LOWER, 8, 1>(a, s);
-    else if (cgs == 8 && ktw == 2) launch_main<T, HERM, LOWER, 8, 2>(a, s);
-    else if (cgs == 16 && ktw == 1) launch_main<T, HERM, LOWER, 16, 1>(a, s);
-    else if (cgs == 16 && ktw == 2) launch_main<T, HERM, LOWER, 16, 2>(a, s);
+    const int cols = (int)a.plan.panel_cols, ktw = (int)(a.plan.chunk_tiles / SY_NW);
+    if (cols == 64 && ktw == 1) launch_main<T, HERM, LOWER, 64, 1>(a, s);
+    else if (cols == 64 && ktw == 2) launch_main<T, HERM, LOWER, 64, 2>(a, s);
+    else if (cols == 128 && ktw == 1) launch_main<T, HERM, LOWER, 128, 1>(a, s);
+    else if (cols == 128 && ktw == 2) launch_main<T, HERM, LOWER, 128, 2>(a, s);
     else return false;
     return true;
 }
