@@ -32,6 +32,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes (read + written) per launch of the main kernels in the default sweep,
+# from the two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE, each scaled by the
+# reading of the library's copy kernel) summarised in profiles/sweep_hbm_traffic.txt
+MEASURED_TRAFFIC_SWEEP = {
+    "gemv_n_kernel<float>": 1416224892, "gemv_t_kernel<float>": 1409503148,
+    "gemv_n_kernel<double>": 2826688281, "gemv_t_kernel<double>": 2818770359,
+    "symv_kernel<double>": 1512791034, "symv_kernel<kmv::cf64>": 3031874126,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -184,6 +193,31 @@ def cpu_baseline(acc, wl):
             "seconds": round(tot_t, 2)}
 
 
+def stream_probe(k, torch):
+    """Sustained bandwidth of the device measured the way the paper defines the
+    roofline's bandwidth (Section 7: STREAM-style kernels): read, copy and triad
+    over 2 GiB per array with the library's own probe kernels."""
+    n = 1 << 28
+    a = torch.zeros(n, dtype=torch.float64, device="cuda")
+    b = torch.empty_like(a)
+    c = torch.empty_like(a)
+    sink = torch.zeros(8192, dtype=torch.float64, device="cuda")
+    out = {}
+    for kind, name, arrays in ((0, "read", 1), (1, "copy", 2), (2, "triad", 3)):
+        for _ in range(2):
+            k.stream_probe(kind, n, a, b, c, sink)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            k.stream_probe(kind, n, a, b, c, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_gbs"] = round(arrays * n * 8 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del a, b, c
+    torch.cuda.empty_cache()
+    return out
+
+
 # --------------------------------------------------------------------- main ----
 def main():
     args = parse()
@@ -207,6 +241,7 @@ def main():
 
     # largest products first: the host runs ahead of the device, so the short
     # products at the end of a step are already queued when their turn comes
+    probe = stream_probe(k, torch)
     prods = sorted(products(args.workload), key=lambda p: -p["n"])
     inputs = Inputs(prods, torch, wl)
     stream = torch.cuda.current_stream()
@@ -250,8 +285,10 @@ def main():
         d["launches"] += 1
     dom, dd = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
     achieved = dd["bytes"] / (dd["ms"] * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_SWEEP.get(dom) if args.workload == "sweep" and not args.tuning else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": "profiles/sweep_hbm_traffic.txt (bytes per launch, read + written)" if traffic else None,
                 "launches_per_step": dd["launches"],
                 "avg_launch_us": round(dd["ms"] * 1e3 / dd["launches"], 2),
                 "avg_algorithmic_bytes_per_launch": dd["bytes"] // dd["launches"]}
@@ -291,6 +328,8 @@ def main():
         "gflops": round(tot_flops / (step_ms * 1e-3) / 1e9, 1),
         "frac_hbm_peak_n_ge_16384": graded,
         "device_ms_per_step": round(device_ms, 3),
+        "stream_probe": probe,
+        "frac_of_stream_read": round(value / probe["read_gbs"], 4),
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
