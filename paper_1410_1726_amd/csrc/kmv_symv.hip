@@ -43,8 +43,9 @@ namespace kmv {
 
 namespace {
 constexpr int SY_NW = 4;    // waves per workgroup
-// columns per column group: 8 columns of 16-byte vectors, 4 for 16-byte elements
-template <class T> constexpr int sy_nc() { return sizeof(T) == 16 ? 4 : 8; }
+// columns per column group (with two tiles per wave: 8 loads in flight per lane
+// and buffer, three workgroups per compute unit)
+template <class T> constexpr int sy_nc() { return 4; }
 constexpr int DEFAULT_PANEL_COLS = 64;
 constexpr int DEFAULT_TILES_PER_WAVE = 2;
 constexpr int DEFAULT_CLASSES = 64;
@@ -81,7 +82,7 @@ __host__ __device__ __forceinline__ void chunk_panels(int64_t tbeg, int64_t tend
 }
 
 template <class T, bool HERM, bool LOWER, int NC, int CGS, int KTW, int NW>
-__global__ __launch_bounds__(NW * WAVE, (sizeof(T) == 16 ? 3 : 2)) void symv_kernel(SymvArgs<T> a) {
+__global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     constexpr int C = NC * CGS;
@@ -316,7 +317,9 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
-    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave : DEFAULT_TILES_PER_WAVE;
+    // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
+    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
+                                                   : (sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE);
     int64_t Q = tuning().symv_classes > 0 ? tuning().symv_classes : DEFAULT_CLASSES;
     // sizing takes the settings that need the most room
     if (sizing) { C = 64; ktw = 1; Q = MAX_CLASSES; }
