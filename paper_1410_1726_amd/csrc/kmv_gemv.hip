@@ -266,6 +266,46 @@ constexpr int64_t DEFAULT_WG_TARGET = 2048;   // about 8 workgroups per compute 
 constexpr int64_t DEFAULT_GN_ROW_TILES = 1;
 }  // namespace
 
+// Workgroups of gemv_n_kernel<T, ., ., rt> that the device keeps resident at
+// once (compute units x occupancy), queried once per instance.  A compute
+// unit's share of the HBM bandwidth is capped, so the kernel is fastest when
+// every compute unit holds the same number of equally long workgroups.
+template <class T> int64_t gemv_n_slots(int64_t rt) {
+    static int64_t cache[5] = {0, 0, 0, 0, 0};
+    if (rt < 1 || rt > 4) return 0;
+    if (cache[rt] == 0) {
+        int dev = 0, cus = 0, nb = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) {
+            if (rt == 1) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gemv_n_kernel<T, GN_NW, GN_LOADS, 1>, GN_NW * WAVE, 0);
+            else if (rt == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gemv_n_kernel<T, GN_NW, GN_LOADS / 2, 2>, GN_NW * WAVE, 0);
+            else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gemv_n_kernel<T, GN_NW, GN_LOADS / 4, 4>, GN_NW * WAVE, 0);
+        }
+        cache[rt] = (e == hipSuccess && cus > 0 && nb > 0) ? (int64_t)cus * nb : -1;
+        (void)hipGetLastError();
+    }
+    return cache[rt];
+}
+
+// Column splits for `rb` row blocks: the largest count that still fits one
+// resident round (rb*s <= slots), or two rounds when one round would leave
+// more than a tenth of the slots empty and two rounds fill better.
+inline int64_t choose_splits(int64_t rb, int64_t slots, int64_t cap) {
+    if (slots <= 0) return 0;
+    int64_t best = 1;
+    double best_eff = 0.0;
+    for (int rounds = 1; rounds <= 2; ++rounds) {
+        int64_t s = rounds * slots / rb;
+        if (s < 1) s = 1;
+        if (s > cap) s = cap;
+        const int64_t w = rb * s;
+        const double eff = (double)w / (double)(ceil_div(w, slots) * slots);
+        if (eff > best_eff + 0.1 || (rounds == 1)) { best = s; best_eff = eff; }
+    }
+    return best;
+}
+
 template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda) {
     constexpr int TR = tile_rows<T>();
     GemvPlan<T> p;
@@ -278,8 +318,11 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     if (notrans) {
         p.row_tiles = tuning().gemv_n_row_tiles > 0 ? tuning().gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
         const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
-        s = tuning().gemv_n_splits > 0 ? tuning().gemv_n_splits : ceil_div(target, rb);
-        const int64_t cap = n / 32 > 1 ? n / 32 : 1;   // at least 32 columns per split
+        int64_t cap = n / 32 > 1 ? n / 32 : 1;   // at least 32 columns per split
+        if (cap > MAX_SPLITS) cap = MAX_SPLITS;
+        s = tuning().gemv_n_splits;
+        if (s <= 0 && tuning().wg_target <= 0 && !sizing) s = choose_splits(rb, gemv_n_slots<T>(p.row_tiles), cap);
+        if (s <= 0) s = ceil_div(target, rb);
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(p.ntiles * TR);
     } else {
