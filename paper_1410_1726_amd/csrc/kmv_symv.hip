@@ -50,7 +50,7 @@ constexpr int DEFAULT_PANEL_COLS = 64;
 constexpr int DEFAULT_TILES_PER_WAVE = 2;
 constexpr int DEFAULT_CLASSES = 64;
 constexpr int MAX_CLASSES = 256;
-constexpr int RED_ROWS = 32, RED_PARTS = 8;
+constexpr int RED_ROWS = 16, RED_PARTS = 16;
 }  // namespace
 
 // first / one-past-last row tile that a panel's stored part touches
