@@ -27,18 +27,19 @@ namespace kmv {
 // and comes through scalar loads.  A block = U columns x RT tiles of 16-byte
 // row vectors plus the U x values, fetched one block ahead of its use.
 // Edge tiles (rows before the first or after the last row) run the same
-// pipeline with element loads whose row index is clamped into the matrix: the
-// clamped lanes compute sums of rows that do not exist, which are dropped.
-template <class T, bool EDGE> __device__ __forceinline__ Vec<T> load_rows(const T* __restrict__ colp, int64_t r, int64_t m) {
-    if (!EDGE) return load_stream(colp + r);
-    Vec<T> v;
+// pipeline with the lanes' load positions clamped into the column: the lanes
+// outside compute sums of rows that do not exist, which are dropped.
+// element e of the result = element e + d of v (lanes of an edge tile whose
+// vector was loaded at a clamped position; elements that fall outside belong to
+// rows that do not exist and may hold anything)
+template <class T> __device__ __forceinline__ Vec<T> shift_elems(const Vec<T>& v, int d) {
+    constexpr int VEC = Traits<T>::VEC;
+    Vec<T> o = v;
 #pragma unroll
-    for (int e = 0; e < Traits<T>::VEC; ++e) {
-        int64_t row = r + e;
-        row = row < 0 ? 0 : (row >= m ? m - 1 : row);
-        v.e[e] = load_elem_stream(colp + row);
-    }
-    return v;
+    for (int e = 0; e < VEC; ++e)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) o.e[e] = select_of(e + d == k, v.e[k], o.e[e]);
+    return o;
 }
 
 template <class T, int U, int RT, int NW, bool EDGE>
@@ -48,6 +49,20 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
     const int64_t lda = a.lda;
     const T* __restrict__ x = a.x;
     const T* __restrict__ A = a.A;
+    // edge tile: every lane loads its 16 bytes from a position clamped into the
+    // column (no branch, same loads as an interior tile); at use the elements are
+    // moved to where the lane's existing rows expect them
+    int64_t rl[RT];
+    int dsh[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        rl[t] = r[t];
+        dsh[t] = 0;
+        if (EDGE) {
+            rl[t] = r[t] < 0 ? 0 : (r[t] + VEC > a.m ? a.m - VEC : r[t]);
+            dsh[t] = (int)(r[t] - rl[t]);
+        }
+    }
     Vec<T> b0[U][RT], b1[U][RT];
     T xb0[U], xb1[U];
     auto load_blk = [&](Vec<T>(&buf)[U][RT], T(&xb)[U], int64_t j) {
@@ -55,7 +70,7 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int t = 0; t < RT; ++t) buf[u][t] = load_rows<T, EDGE>(q + (int64_t)u * lda, r[t], a.m);
+            for (int t = 0; t < RT; ++t) buf[u][t] = load_stream(q + (int64_t)u * lda + rl[t]);
 #pragma unroll
         for (int u = 0; u < U; ++u) xb[u] = x[j + u];
     };
@@ -63,9 +78,11 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int t = 0; t < RT; ++t)
+            for (int t = 0; t < RT; ++t) {
+                const Vec<T> v = EDGE ? shift_elems(buf[u][t], dsh[t]) : buf[u][t];
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) fma_acc(acc[t][v], buf[u][t].e[v], xb[u]);
+                for (int e = 0; e < VEC; ++e) fma_acc(acc[t][e], v.e[e], xb[u]);
+            }
     };
     const int64_t nblk = cw / U;
     if (nblk > 0) load_blk(b0, xb0, c0);
@@ -79,14 +96,32 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
         }
     }
     for (int64_t j = c0 + nblk * U; j < c0 + cw; ++j) {
-        Vec<T> av[RT];
-#pragma unroll
-        for (int t = 0; t < RT; ++t) av[t] = load_rows<T, EDGE>(A + j * lda, r[t], a.m);
         const T xj = x[j];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            Vec<T> v = load_stream(A + j * lda + rl[t]);
+            if (EDGE) v = shift_elems(v, dsh[t]);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) fma_acc(acc[t][e], v.e[e], xj);
+        }
+    }
+}
+
+// fewer rows than one 16-byte vector: plain element loop (m <= 3)
+template <class T, int RT>
+__device__ __forceinline__ void gemv_n_few_rows(const GemvArgs<T>& a, const int64_t (&r)[RT], int64_t c0, int64_t cw,
+                                                T (&acc)[RT][Traits<T>::VEC]) {
+    constexpr int VEC = Traits<T>::VEC;
+    for (int64_t j = c0; j < c0 + cw; ++j) {
+        const T xj = a.x[j];
 #pragma unroll
         for (int t = 0; t < RT; ++t)
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) fma_acc(acc[t][v], av[t].e[v], xj);
+            for (int e = 0; e < VEC; ++e) {
+                int64_t row = r[t] + e;
+                row = row < 0 ? 0 : (row >= a.m ? a.m - 1 : row);
+                fma_acc(acc[t][e], a.A[row + j * a.lda], xj);
+            }
     }
 }
 
@@ -118,7 +153,8 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
         for (int v = 0; v < VEC; ++v) acc[t][v] = zero_of<T>();
 
     if (interior) gemv_n_walk<T, U, RT, NW, false>(a, r, c0, cw, acc);
-    else gemv_n_walk<T, U, RT, NW, true>(a, r, c0, cw, acc);
+    else if (a.m >= VEC) gemv_n_walk<T, U, RT, NW, true>(a, r, c0, cw, acc);
+    else gemv_n_few_rows<T, RT>(a, r, c0, cw, acc);
 
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
