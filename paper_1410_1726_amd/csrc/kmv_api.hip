@@ -213,7 +213,9 @@ int kmv_set_tuning(const char* key, int64_t value) {
         if (strcmp(k.name, key) == 0) {
             if (value < k.lo || value > k.hi) return -1;
             if (k.field == &Tuning::gemv_n_row_tiles && value == 3) return -1;
-            if (k.field == &Tuning::symv_panel_cols && value != 0 && value != 64 && value != 128) return -1;
+            if (k.field == &Tuning::symv_panel_cols && value != 0 && value != 16 && value != 32 && value != 64 &&
+                value != 128)
+                return -1;
             tuning().*(k.field) = value;
             return 0;
         }

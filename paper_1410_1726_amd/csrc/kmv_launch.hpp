@@ -16,7 +16,7 @@ struct Tuning {
     int64_t gemv_n_splits = 0;     // column splits of GEMV-N
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
     int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
-    int64_t symv_panel_cols = 0;      // SYMV panel width: 64 or 128 columns
+    int64_t symv_panel_cols = 0;      // SYMV panel width: 16, 32, 64 or 128 columns
     int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave: 1 or 2
     int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
     int64_t wg_target = 0;         // workgroups the heuristics aim for

@@ -29,9 +29,9 @@
 //  * the transposed column sums are reduced across the wave once per column
 //    group (DPP), meet the other waves' in LDS once per panel (one barrier per
 //    panel, none inside) and go to a workspace indexed [panel][chunk][column];
-//  * diagonal and edge tiles are handled in the same kernel by element loads
-//    that never touch the other triangle, so the mirrored copy of Section 6.5
-//    is never built;
+//  * diagonal and edge tiles are handled in the same kernel and the same
+//    prefetch pipeline by element loads that never touch the other triangle,
+//    so the mirrored copy of Section 6.5 is never built;
 //  * consecutive workgroup ids differ in the class, so every XCD sees all row
 //    offsets (with a power-of-two leading dimension the lines of one row range
 //    in all columns share few L2 sets), and long chains are dispatched first.
@@ -46,9 +46,9 @@ constexpr int SY_NW = 4;    // waves per workgroup
 // columns per column group (with two tiles per wave: 8 loads in flight per lane
 // and buffer, three workgroups per compute unit)
 template <class T> constexpr int sy_nc() { return 4; }
-constexpr int DEFAULT_PANEL_COLS = 64;
+constexpr int DEFAULT_PANEL_COLS = 16;
+constexpr int64_t TARGET_CHAINS = 2048;   // chains (workgroups) the class count aims at
 constexpr int DEFAULT_TILES_PER_WAVE = 2;
-constexpr int DEFAULT_CLASSES = 64;
 constexpr int MAX_CLASSES = 256;
 constexpr int RED_ROWS = 16, RED_PARTS = 16;
 }  // namespace
@@ -168,6 +168,22 @@ __global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
                 const T* src = a.A + jg * lda + rq[q];
 #pragma unroll
                 for (int c = 0; c < NC; ++c) buf[q][c] = load_stream(src + (int64_t)c * lda);
+            } else if (valid[q]) {
+                // edge / diagonal tile: element loads into the same buffer; a pair
+                // outside the stored triangle loads the (always stored) diagonal
+                // element of its column instead and is skipped at use
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const int64_t row = rq[q] + v;
+                    const bool rowok = row >= 0 && row < n;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const int64_t j = jg + c;
+                        const int64_t jc = j < n ? j : n - 1;
+                        const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
+                        buf[q][c].e[v] = load_elem_stream(a.A + (ins ? row : jc) + jc * lda);
+                    }
+                }
             }
         }
 #pragma unroll
@@ -194,11 +210,9 @@ __global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
                         fma_op<HERM>(accT[c], buf[q][c].e[v], xi[q].e[v]);
                     }
             } else if (valid[q]) {
-                // edge / diagonal tile: element loads, all issued before the first
-                // use; a pair outside the stored triangle loads the (always
-                // stored) diagonal element of its column instead and is skipped
-                T av[VEC][NC];
-                bool ins[VEC][NC], dia[VEC][NC];
+                // edge / diagonal tile (element-loaded above): pairs outside the
+                // stored triangle are skipped, the diagonal feeds only the row sum
+                // and HEMV takes its real part
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
                     const int64_t row = rq[q] + v;
@@ -206,23 +220,17 @@ __global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
 #pragma unroll
                     for (int c = 0; c < NC; ++c) {
                         const int64_t j = jg + c;
-                        const int64_t jc = j < n ? j : n - 1;
-                        ins[v][c] = rowok && j < n && (LOWER ? row >= j : row <= j);
-                        dia[v][c] = (row == j);
-                        av[v][c] = load_elem_stream(a.A + (ins[v][c] ? row : jc) + jc * lda);
-                    }
-                }
-#pragma unroll
-                for (int v = 0; v < VEC; ++v)
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        const T an = select_of(HERM && dia[v][c], real_part_only(av[v][c]), av[v][c]);
+                        const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
+                        const bool dia = (row == j);
+                        const T av = buf[q][c].e[v];
+                        const T an = select_of(HERM && dia, real_part_only(av), av);
                         T nn = accN[q][v], nt = accT[c];
                         fma_acc(nn, an, xjb[c]);
-                        fma_op<HERM>(nt, av[v][c], xi[q].e[v]);
-                        accN[q][v] = select_of(ins[v][c], nn, accN[q][v]);
-                        accT[c] = select_of(ins[v][c] && !dia[v][c], nt, accT[c]);
+                        fma_op<HERM>(nt, av, xi[q].e[v]);
+                        accN[q][v] = select_of(ins, nn, accN[q][v]);
+                        accT[c] = select_of(ins && !dia, nt, accT[c]);
                     }
+                }
             }
         }
         T(&tp)[NW][C] = tpart[pi & 1];
@@ -320,15 +328,22 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
     int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
                                                    : (sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE);
-    int64_t Q = tuning().symv_classes > 0 ? tuning().symv_classes : DEFAULT_CLASSES;
-    // sizing takes the settings that need the most room
-    if (sizing) { C = 64; ktw = 1; Q = MAX_CLASSES; }
+    if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
-    if (Q > p.npanels && !sizing) Q = p.npanels;
-    p.classes = Q;
     p.chunk_tiles = SY_NW * ktw;
     p.nchunks = ceil_div(p.ntiles, p.chunk_tiles);
+    // classes: a power of two between 32 and 128 that gives about TARGET_CHAINS
+    // chains (measured: fewer chains leave compute units idle at the end, more
+    // only add row-sum vectors), never more than there are panels
+    int64_t Q = tuning().symv_classes;
+    if (Q <= 0) {
+        Q = 32;
+        while (Q < 128 && Q * p.nchunks < TARGET_CHAINS) Q *= 2;
+    }
+    if (sizing) Q = MAX_CLASSES;
+    else if (Q > p.npanels) Q = p.npanels;
+    p.classes = Q;
     p.rows_padded = partial_stride<T>(p.ntiles * TR);
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
@@ -346,7 +361,11 @@ void launch_main(const SymvArgs<T>& a, hipStream_t s) {
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
     const int cols = (int)a.plan.panel_cols, ktw = (int)(a.plan.chunk_tiles / SY_NW);
-    if (cols == 64 && ktw == 1) launch_main<T, HERM, LOWER, 64, 1>(a, s);
+    if (cols == 16 && ktw == 1) launch_main<T, HERM, LOWER, 16, 1>(a, s);
+    else if (cols == 16 && ktw == 2) launch_main<T, HERM, LOWER, 16, 2>(a, s);
+    else if (cols == 32 && ktw == 1) launch_main<T, HERM, LOWER, 32, 1>(a, s);
+    else if (cols == 32 && ktw == 2) launch_main<T, HERM, LOWER, 32, 2>(a, s);
+    else if (cols == 64 && ktw == 1) launch_main<T, HERM, LOWER, 64, 1>(a, s);
     else if (cols == 64 && ktw == 2) launch_main<T, HERM, LOWER, 64, 2>(a, s);
     else if (cols == 128 && ktw == 1) launch_main<T, HERM, LOWER, 128, 1>(a, s);
     else if (cols == 128 && ktw == 2) launch_main<T, HERM, LOWER, 128, 2>(a, s);
