@@ -233,20 +233,30 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
             }
     };
 
-    int64_t tb = ts + w;              // this wave: tiles tb, tb+NW, ... < te
-    const int64_t te = ts + tw;
-    if (tb < te && tb == 0 && !is_interior(0)) {
-        masked_tile(0);
-        tb += NW;
-    }
-    int64_t cnt = tb < te ? (te - tb + NW - 1) / NW : 0;
-    const bool last_edge = cnt > 0 && (tb + (cnt - 1) * NW == ntiles - 1) && !is_interior(ntiles - 1);
-    if (last_edge) --cnt;
+    // interior tiles [ilo, ihi) of this split; an edge tile at either end is done
+    // by wave 0 / wave NW-1 on its own
+    int64_t ilo = ts, ihi = ts + tw;
+    const bool first_edge = tw > 0 && ilo == 0 && !is_interior(0);
+    if (first_edge) ++ilo;
+    const bool last_edge = ihi > ilo && ihi == ntiles && !is_interior(ntiles - 1);
+    if (last_edge) --ihi;
+    const int64_t ni = ihi - ilo;
+    if (first_edge && w == 0) masked_tile(0);
+    if (last_edge && w == NW - 1) masked_tile(ntiles - 1);
 
+    // The waves take the interior tiles round robin, starting at a tile that
+    // depends on the column group: workgroups that run at the same time then
+    // sit at different row offsets (with a power-of-two leading dimension equal
+    // row offsets of different columns share few L2 sets).  The rotation depends
+    // only on the arguments, so results stay reproducible.
+    const int64_t rot = ni > 0 ? ((int64_t)blockIdx.x * 37) % ni : 0;
+    const int64_t cnt = ni > w ? (ni - w + NW - 1) / NW : 0;   // tiles of this wave
     {
         Vec<T> x0, x1, b0[NC], b1[NC];
         auto load_tile = [&](Vec<T>& xv, Vec<T>(&buf)[NC], int64_t k) {
-            const int64_t r = (tb + k * NW) * TR - shift + (int64_t)lane * VEC;
+            int64_t i = w + k * NW + rot;
+            if (i >= ni) i -= ni;
+            const int64_t r = (ilo + i) * TR - shift + (int64_t)lane * VEC;
             xv = load_cached(x + r);
 #pragma unroll
             for (int c = 0; c < NC; ++c) buf[c] = load_stream(col[c] + r);
@@ -267,7 +277,6 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
             }
         }
     }
-    if (last_edge) masked_tile(ntiles - 1);
 
     __shared__ T red[NW][NC];
 #pragma unroll
