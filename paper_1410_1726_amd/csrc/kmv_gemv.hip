@@ -372,7 +372,11 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
         p.part_stride = partial_stride<T>(p.ntiles * TR);
     } else {
         const int64_t g = ceil_div(n, GT_NC);
-        s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits : ceil_div(target, g);
+        // row splits only when there are too few column groups to occupy the device:
+        // from about 512 groups on, one workgroup per group with the epilogue fused
+        // (no second kernel) is faster
+        const int64_t ttarget = tuning().wg_target > 0 ? tuning().wg_target : 512;
+        s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits : ceil_div(ttarget, g);
         const int64_t cap = p.ntiles / (2 * GT_NW) > 1 ? p.ntiles / (2 * GT_NW) : 1;   // two tiles per wave at least
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(n);
