@@ -115,7 +115,11 @@ def kernel_name(p):
     t = {"s": "float", "d": "double", "c": "kmv::cf32", "z": "kmv::cf64"}[p["prec"]]
     if p["kind"] == "gemv":
         return f"gemv_{'n' if p['mode'] == 'N' else 't'}_kernel<{t}>"
-    return f"symv_kernel<{t}>"
+    from paper_1410_1726_amd import binding as k
+    esize = {"s": 4, "d": 8, "c": 8, "z": 16}[p["prec"]]
+    # only the alignment of A matters to the choice: the bench buffers are 256-byte aligned
+    variant = k.symv_kernel_variant(p["prec"], p["mode"], p["n"], 256 + (p.get("off", 0) * (p["lda"] + 1)) * esize, p["lda"])
+    return f"{'symv_balanced_kernel' if variant == 2 else 'symv_kernel'}<{t}>"
 
 
 class Inputs:

@@ -145,11 +145,28 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
 /* ---- Tuning values for sweeps (Section 9: the tuning parameters are kept
  * apart from the kernel templates).  Keys are listed by kmv_tuning_keys()
  * as a comma separated string; kmv_set_tuning returns 0, or -1 for an
- * unknown key or a value outside the compiled set.  Process-wide; not
- * thread safe against concurrent calls. */
+ * unknown key or a value outside the compiled set; value 0 = choose
+ * automatically.  Process-wide; not thread safe against concurrent calls.
+ *   gemv_n_splits, gemv_t_splits  column / row splits of the GEMV kernels
+ *   gemv_n_row_tiles              row tiles per wave of GEMV-N (1, 2, 4)
+ *   symv_variant                  SYMV/HEMV main kernel, see below (1, 2)
+ *   symv_panel_cols               panel width of variant 1 (16, 32, 64, 128)
+ *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)
+ *   symv_classes                  variant 1: chains per row chunk (1..256)
+ *   wg_target                     workgroups the split heuristics aim for; for
+ *                                 SYMV variant 2 the number of workgroups */
 int kmv_set_tuning(const char* key, int64_t value);
 int64_t kmv_get_tuning(const char* key);
 const char* kmv_tuning_keys(void);
+
+/* Which main kernel a kmv_<prec>symv / hemv call with these arguments would
+ * launch under the current tuning values: 1 = chains of column panels per row
+ * chunk, 2 = balanced shares of (row chunk, panel) pieces (the balanced
+ * partition of Section 6.2 applied to the stored triangle).  Only the address
+ * of A is used (its alignment decides), nothing is read or launched.  Returns
+ * 0 for an unknown prec or uplo, n < 0 or lda < max(1, n).  For benchmarks
+ * and profiles that have to name the kernel they time. */
+int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda);
 
 const char* kmv_version(void);
 

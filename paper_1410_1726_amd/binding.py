@@ -53,6 +53,8 @@ def _load() -> ctypes.CDLL:
     lib.kmv_set_tuning.argtypes, lib.kmv_set_tuning.restype = [ctypes.c_char_p, i64], ci
     lib.kmv_get_tuning.argtypes, lib.kmv_get_tuning.restype = [ctypes.c_char_p], i64
     lib.kmv_tuning_keys.restype = ctypes.c_char_p
+    lib.kmv_symv_kernel_variant.argtypes = [ctypes.c_char, ctypes.c_char, i64, ctypes.c_void_p, i64]
+    lib.kmv_symv_kernel_variant.restype = ctypes.c_int
     lib.kmv_version.restype = ctypes.c_char_p
     return lib
 
@@ -201,6 +203,13 @@ def get_tuning(key):
 
 def tuning_keys():
     return lib.kmv_tuning_keys().decode().split(",")
+
+
+def symv_kernel_variant(prec, uplo, n, A, lda):
+    """1 (chains) or 2 (balanced shares): the main kernel a symv/hemv call with these
+    arguments launches; A may be a tensor or an integer address"""
+    addr = A if isinstance(A, int) else A.data_ptr()
+    return int(lib.kmv_symv_kernel_variant(prec.encode(), uplo.encode(), n, ctypes.c_void_p(addr), lda))
 
 
 def version():

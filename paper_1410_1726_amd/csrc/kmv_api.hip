@@ -123,6 +123,7 @@ const Key KEYS[] = {
     {"symv_panel_cols", &Tuning::symv_panel_cols, 0, 128},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
     {"symv_classes", &Tuning::symv_classes, 0, 256},
+    {"symv_variant", &Tuning::symv_variant, 0, 2},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
 };
 
@@ -227,7 +228,21 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,symv_classes,wg_target"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,wg_target"; }
+
+int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
+    const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
+    if ((!lower && !upper) || n < 0 || lda < (n > 1 ? n : 1)) return 0;
+    // a null A would ask the planner for the workspace bound instead of a launch plan
+    const void* base = A ? A : reinterpret_cast<const void*>(uintptr_t(WS_ALIGN));
+    switch (prec) {
+        case 's': return plan_symv<float>(lower, n, base, lda).variant;
+        case 'd': return plan_symv<double>(lower, n, base, lda).variant;
+        case 'c': return plan_symv<cf32>(lower, n, base, lda).variant;
+        case 'z': return plan_symv<cf64>(lower, n, base, lda).variant;
+    }
+    return 0;
+}
 
 const char* kmv_version(void) { return "kmv 0.1 (gfx950)"; }
 

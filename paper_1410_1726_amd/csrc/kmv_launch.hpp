@@ -19,6 +19,7 @@ struct Tuning {
     int64_t symv_panel_cols = 0;      // SYMV panel width: 16, 32, 64 or 128 columns
     int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave: 1 or 2
     int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
+    int64_t symv_variant = 0;         // SYMV main kernel: 1 = chains, 2 = balanced shares
     int64_t wg_target = 0;         // workgroups the heuristics aim for
 };
 Tuning& tuning();
@@ -74,13 +75,16 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
 // ----------------------------------------------------------- SYMV/HEMV ----
 template <class T> struct SymvPlan {
     int shift;
+    int variant;           // main kernel: 1 = chains of panels per row chunk, 2 = balanced shares of pieces
     int64_t ntiles;        // row tiles covering [-shift, n)
     int64_t panel_cols;    // columns per panel
     int64_t npanels;       // column panels
     int64_t chunk_tiles;   // row tiles per workgroup
     int64_t nchunks;       // row chunks
     int64_t classes;       // a chain takes every classes-th panel of its row chunk
-    int64_t rows_padded;   // distance between the row-sum vectors of two classes (>= ntiles * tile_rows)
+    int64_t rows_padded;   // distance between two row-sum vectors (variant 1: >= ntiles * tile_rows; 2: >= chunk rows)
+    int64_t work;          // variant 2: length of the work line (row tiles x panels that hold stored elements)
+    int64_t workers;       // variant 2: workgroups of the main kernel
     size_t xpack_off, wsn_off, wst_off, total_bytes;
 };
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
@@ -92,7 +96,7 @@ template <class T> struct SymvArgs {
     T* y;
     int64_t incy;
     T alpha, beta;
-    T* wsn;           // [classes][rows_padded]  row sums of each chain ("N part")
+    T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
     SymvPlan<T> plan;
 };

@@ -278,12 +278,275 @@ __global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
     }
 }
 
+// panels whose stored part touches row chunk k (chunks of CT tiles): first panel
+// plo and their number; tk = row tiles of the chunk (the last chunk may be short)
+template <bool LOWER>
+__host__ __device__ __forceinline__ int64_t chunk_pieces(int64_t k, int64_t CT, int64_t C, int shift, int64_t TR,
+                                                         int64_t ntiles, int64_t npanels, int64_t& plo, int64_t& tk) {
+    const int64_t tbeg = k * CT;
+    const int64_t tend = tbeg + CT < ntiles ? tbeg + CT : ntiles;
+    int64_t phi;
+    chunk_panels<LOWER>(tbeg, tend, C, shift, TR, npanels, plo, phi);
+    tk = tend - tbeg;
+    return phi > plo ? phi - plo : 0;
+}
+// worker that owns item s when `partition` deals P items to Y workers
+__host__ __device__ __forceinline__ int64_t partition_owner(int64_t P, int64_t Y, int64_t s) {
+    const int64_t q = P / Y, r = P % Y, thr = r * (q + 1);
+    return s < thr ? s / (q + 1) : r + (s - thr) / q;
+}
+
+// Balanced form: the pieces (row chunk k, panel p) of the stored triangle are
+// laid chunk by chunk on a work line that is dealt to the workgroups in equal
+// contiguous shares by the partition of Section 6.2, and the grid is exactly
+// one resident round (compute units x occupancy): every workgroup starts at
+// once, reads about the same number of bytes and ends at once, and at any
+// moment the resident workgroups cover all row chunks, so the load on memory
+// channels does not depend on the leading dimension.  A workgroup's share lies
+// in one chunk, rarely two or more.  (Pieces count alike: measured, a piece of
+// a short last chunk costs nearly as much as a full one.)
+// Inside a piece wave w owns the columns [w*NC, (w+1)*NC) of the panel over ALL
+// CT = KT*G row tiles (G units of KT tiles, visited in a per-wave rotated order
+// so that the waves read different KiB of their columns at any moment).  The
+// transposed column sums are private to the wave: one DPP reduction per column
+// and panel, no barrier inside the walk, and the diagonal tiles' element-wise
+// work is spread over all waves.  The row sums of a wave live in a wave-private
+// LDS array (each lane touches only its own slots, no synchronisation) and meet
+// the other waves' when the share leaves a chunk: one row-sum vector per
+// (workgroup, chunk), stored at index workgroup + chunk.  x over the chunk's
+// rows is staged in LDS.
+template <class T, bool HERM, bool LOWER, int NC, int KT, int G, int NW>
+__global__ __launch_bounds__(NW * WAVE, 3) void symv_balanced_kernel(SymvArgs<T> a) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int TR = WAVE * VEC;
+    constexpr int C = NC * NW;
+    constexpr int CT = KT * G;
+    constexpr int R = CT * TR;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    // row, column, tile and panel numbers are kept in 32 bits (the host uses this
+    // kernel only while n + 2*CT*TR < 2^31); only addresses are 64-bit
+    const int n = (int)a.n;
+    const int64_t lda = a.lda;
+    const int shift = a.plan.shift;
+    const int ntiles = (int)a.plan.ntiles, nchunks = (int)a.plan.nchunks, npanels = (int)a.plan.npanels;
+    const T* __restrict__ x = a.x;
+
+    __shared__ __align__(16) T xs[R];       // x over the chunk's rows (zeros outside [0, n))
+    __shared__ __align__(16) T rs[NW][R];   // row sums of each wave
+
+    // this workgroup's share [wlo, whi) of the work line
+    int64_t wlo, whi;
+    {
+        int64_t wcnt;
+        partition(a.plan.work, (int64_t)gridDim.x, (int64_t)blockIdx.x, wcnt, wlo);
+        if (wcnt <= 0) return;
+        whi = wlo + wcnt;
+    }
+
+    Vec<T> b0[KT][NC], b1[KT][NC];
+    T xj0[NC], xj1[NC];
+    T accT[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) accT[c] = zero_of<T>();
+
+    int64_t wb = 0;   // work before chunk k
+    for (int k = 0; k < nchunks && wb < whi; ++k) {
+        int64_t plo64, tk, len;
+        len = chunk_pieces<LOWER>(k, CT, C, shift, TR, ntiles, npanels, plo64, tk);
+        const int64_t wb0 = wb;
+        wb += len;
+        if (wb <= wlo) continue;   // the share starts in a later chunk
+        // pieces of this chunk that lie in the share
+        const int64_t lo = (wlo > wb0 ? wlo : wb0) - wb0, hi = (whi < wb ? whi : wb) - wb0;
+        const int j0 = (int)lo, j1 = (int)hi;
+        // piece, panel and unit counts fit 32 bits (n < 2^31 * 16 columns)
+        const int pfirst = (int)plo64 + j0;
+        const int gk = ((int)tk + KT - 1) / KT;   // units per piece: a short last chunk has fewer
+        const int units = (j1 - j0) * gk;
+        const int tbeg = k * CT;
+        const int tend = tbeg + CT < ntiles ? tbeg + CT : ntiles;
+        const int row0 = tbeg * TR - shift;   // row of slot 0 of the chunk
+
+        // flags of row tile tt (0..CT-1 inside the chunk) against the wave's column
+        // group starting at column jg: valid = holds stored elements, fast = all rows
+        // exist, all NC columns exist, every pair strictly inside the triangle
+        auto tile_flags = [&](int jg, int tt, bool& valid, bool& fast) {
+            const int t = tbeg + tt;
+            const int r0 = t * TR - shift;
+            const bool inrange = t < tend && jg < n;
+            const bool rowfull = r0 >= 0 && r0 + TR <= n;
+            const int jl = (jg + NC < n ? jg + NC : n) - 1;   // last existing column
+            valid = inrange && (LOWER ? (r0 + TR - 1 >= jg) : (r0 <= jl));
+            fast = valid && rowfull && jg + NC <= n && (LOWER ? (r0 >= jg + NC) : (r0 + TR - 1 < jg));
+        };
+        // one unit = the wave's NC columns of one panel over KT row tiles; the next
+        // unit's matrix vectors and x_j scalars are in flight while this one is used
+        // (pp, g) = (piece of the share, group of KT row tiles); the waves take the
+        // groups in rotated order so that they read different KiB at any moment
+        auto load_unit = [&](Vec<T>(&b)[KT][NC], T(&xjb)[NC], int pp, int g) {
+            const int jg = (pfirst + pp) * C + w * NC;
+#pragma unroll
+            for (int q = 0; q < KT; ++q) {
+                bool valid, fast;
+                tile_flags(jg, g * KT + q, valid, fast);
+                const int rq = row0 + (g * KT + q) * TR + lane * VEC;
+                if (fast) {
+                    const T* src = a.A + (int64_t)jg * lda + rq;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) b[q][c] = load_stream(src + (int64_t)c * lda);
+                } else if (valid) {
+                    // edge / diagonal tile: element loads into the same buffer; a pair
+                    // outside the stored triangle loads the (always stored) diagonal
+                    // element of its column instead and is skipped at use
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const int row = rq + v;
+                        const bool rowok = row >= 0 && row < n;
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) {
+                            const int j = jg + c;
+                            const int jc = j < n ? j : n - 1;
+                            const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
+                            b[q][c].e[v] = load_elem_stream(a.A + (ins ? row : jc) + (int64_t)jc * lda);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                xjb[c] = select_of(jg + c < n, x[jg + c < n ? jg + c : n - 1], zero_of<T>());
+        };
+        auto compute_unit = [&](const Vec<T>(&b)[KT][NC], const T(&xjb)[NC], int pp, int g, bool last) {
+            const int p = pfirst + pp;
+            const int jg = p * C + w * NC;
+#pragma unroll
+            for (int q = 0; q < KT; ++q) {
+                bool valid, fast;
+                tile_flags(jg, g * KT + q, valid, fast);
+                if (!valid) continue;
+                const int slot = (g * KT + q) * TR + lane * VEC;
+                Vec<T> xi, an;
+                __builtin_memcpy(&xi, &xs[slot], sizeof(xi));
+                __builtin_memcpy(&an, &rs[w][slot], sizeof(an));
+                if (fast) {
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            fma_acc(an.e[v], b[q][c].e[v], xjb[c]);
+                            fma_op<HERM>(accT[c], b[q][c].e[v], xi.e[v]);
+                        }
+                } else {
+                    // pairs outside the stored triangle are skipped, the diagonal feeds
+                    // only the row sum and HEMV takes its real part
+                    const int rq = row0 + slot;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const int row = rq + v;
+                        const bool rowok = row >= 0 && row < n;
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) {
+                            const int j = jg + c;
+                            const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
+                            const bool dia = (row == j);
+                            const T av = b[q][c].e[v];
+                            const T ad = select_of(HERM && dia, real_part_only(av), av);
+                            T nn = an.e[v], nt = accT[c];
+                            fma_acc(nn, ad, xjb[c]);
+                            fma_op<HERM>(nt, av, xi.e[v]);
+                            an.e[v] = select_of(ins, nn, an.e[v]);
+                            accT[c] = select_of(ins && !dia, nt, accT[c]);
+                        }
+                    }
+                }
+                __builtin_memcpy(&rs[w][slot], &an, sizeof(an));
+            }
+            if (last) {
+                // panel finished: column sums of this wave's NC columns, lane c keeps column c
+                T mine = zero_of<T>();
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const T sum = wave_sum(accT[c]);
+                    mine = select_of(lane == c, sum, mine);
+                    accT[c] = zero_of<T>();
+                }
+                if (lane < NC) a.wst[((int64_t)p * nchunks + k) * C + w * NC + lane] = mine;
+            }
+        };
+
+        // the first matrix vectors are on their way while x is staged
+        // next unit to load / to use: piece, step inside the piece, rotated tile group
+        const int g0 = w % gk;
+        int lp = 0, ls = 0, lg = g0, cp = 0, cs = 0, cg = g0;
+        auto step = [&](int& pp, int& ss, int& gg) {
+            if (++gg == gk) gg = 0;
+            if (++ss == gk) {
+                ss = 0;
+                ++pp;
+            }
+        };
+        if (units > 0) {
+            load_unit(b0, xj0, lp, lg);
+            step(lp, ls, lg);
+        }
+        for (int i = threadIdx.x; i < R; i += NW * WAVE) {
+            const int row = row0 + i;
+            const int rc = row < 0 ? 0 : (row >= n ? n - 1 : row);
+            xs[i] = select_of(row >= 0 && row < n, x[rc], zero_of<T>());
+        }
+        {
+            Vec<T> z;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) z.e[v] = zero_of<T>();
+#pragma unroll
+            for (int t = 0; t < CT; ++t) __builtin_memcpy(&rs[w][t * TR + lane * VEC], &z, sizeof(z));
+        }
+        __syncthreads();
+        for (int u = 0; u < units; u += 2) {
+            if (u + 1 < units) {
+                load_unit(b1, xj1, lp, lg);
+                step(lp, ls, lg);
+            }
+            compute_unit(b0, xj0, cp, cg, cs == gk - 1);
+            step(cp, cs, cg);
+            if (u + 1 < units) {
+                if (u + 2 < units) {
+                    load_unit(b0, xj0, lp, lg);
+                    step(lp, ls, lg);
+                }
+                compute_unit(b1, xj1, cp, cg, cs == gk - 1);
+                step(cp, cs, cg);
+            }
+        }
+
+        // leaving the chunk: the NW waves' row sums are added in wave order and
+        // stored as row-sum vector number workgroup + chunk
+        __syncthreads();
+        T* __restrict__ wsn = a.wsn + ((int64_t)blockIdx.x + k) * a.plan.rows_padded;
+        const int nvec = (int)(tend - tbeg) * WAVE;   // 16-byte row vectors of this chunk
+        for (int vi = threadIdx.x; vi < nvec; vi += NW * WAVE) {
+            Vec<T> sum;
+            __builtin_memcpy(&sum, &rs[0][vi * VEC], sizeof(sum));
+#pragma unroll
+            for (int ww = 1; ww < NW; ++ww) {
+                Vec<T> o;
+                __builtin_memcpy(&o, &rs[ww][vi * VEC], sizeof(o));
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sum.e[v] = add_of(sum.e[v], o.e[v]);
+            }
+            store_vec_stream(wsn + (int64_t)vi * VEC, sum);
+        }
+        __syncthreads();   // before xs and rs are reused for the next chunk
+    }
+}
+
 // y_i = alpha * ( sum over classes of wsn[class][i] + sum over chunks of
 // wst[panel(i)][chunk][i] ) + beta*y_i.  blockDim = (RED_ROWS, RED_PARTS): part g
 // adds the classes g, g+RED_PARTS, ... and then the chunks kbeg+g, kbeg+g+
 // RED_PARTS, ... in ascending order; the parts meet in LDS and are added in
 // part order, so the result does not depend on scheduling.
-template <class T, bool LOWER>
+template <class T, bool LOWER, bool BAL>
 __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a) {
     constexpr int TR = tile_rows<T>();
     const int lx = threadIdx.x, g = threadIdx.y;
@@ -293,9 +556,28 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
     __shared__ T part[RED_PARTS][RED_ROWS];
     T s = zero_of<T>();
     if (i < a.n) {
-        const T* __restrict__ wsn = a.wsn + i + shift;
+        if (BAL) {
+            // row-sum vectors of the workgroups whose share touches the chunk of row i
+            const int64_t CT = a.plan.chunk_tiles, slot = i + shift;
+            const int64_t k = slot / (CT * TR);
+            int64_t before = 0, plo, tk = 0, len = 0;
+            for (int64_t kk = 0; kk <= k; ++kk) {
+                before += len;
+                len = chunk_pieces<LOWER>(kk, CT, C, shift, TR, a.plan.ntiles, a.plan.npanels, plo, tk);
+            }
+            if (len > 0) {
+                // every workgroup whose share meets the chunk's stretch of the work line wrote a vector
+                const int64_t ylo = partition_owner(a.plan.work, a.plan.workers, before);
+                const int64_t yhi = partition_owner(a.plan.work, a.plan.workers, before + len - 1);
+                const T* __restrict__ wsn = a.wsn + (slot - k * CT * TR);
 #pragma unroll 4
-        for (int64_t q = g; q < a.plan.classes; q += RED_PARTS) s = add_of(s, wsn[q * a.plan.rows_padded]);
+                for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
+            }
+        } else {
+            const T* __restrict__ wsn = a.wsn + i + shift;
+#pragma unroll 4
+            for (int64_t q = g; q < a.plan.classes; q += RED_PARTS) s = add_of(s, wsn[q * a.plan.rows_padded]);
+        }
         // chunks whose row tiles intersect the tile range of the panel of column i
         const int64_t pi = i / C;
         int64_t tlo, thi;
@@ -317,17 +599,61 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 }
 
 // ------------------------------------------------------------- host side ----
+namespace {
+// balanced kernel: columns per wave, and row tiles per unit (two where the
+// registers allow eight 16-byte loads per lane and buffer without spilling and
+// the rate gains from it: 8-byte elements)
+constexpr int BAL_NC = 4;
+template <class T> constexpr int bal_kt() { return sizeof(T) == 8 ? 2 : 1; }
+constexpr int64_t MAX_WORKERS = 2048;
+// workgroups of the balanced kernel that are resident at once (compute units x
+// occupancy), queried once per element type and chunk height
+template <class T, bool LOWER, int G> int64_t balanced_slots_of() {
+    constexpr bool HERM = Traits<T>::cplx;
+    int dev = 0, cus = 0, nb = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &nb, symv_balanced_kernel<T, HERM, LOWER, BAL_NC, bal_kt<T>(), G, SY_NW>, SY_NW * WAVE, 0);
+    (void)hipGetLastError();
+    return (e == hipSuccess && cus > 0 && nb > 0) ? (int64_t)cus * nb : -1;
+}
+template <class T> int64_t balanced_slots(bool lower, int ktw) {
+    static int64_t cache[2][3] = {{0, 0, 0}, {0, 0, 0}};
+    if (ktw < 1 || ktw > 2) return -1;
+    int64_t& c = cache[lower ? 1 : 0][ktw];
+    if (c == 0) {
+        constexpr int G1 = SY_NW / bal_kt<T>(), G2 = 2 * SY_NW / bal_kt<T>();
+        if (lower) c = ktw == 1 ? balanced_slots_of<T, true, G1>() : balanced_slots_of<T, true, G2>();
+        else c = ktw == 1 ? balanced_slots_of<T, false, G1>() : balanced_slots_of<T, false, G2>();
+    }
+    return c;
+}
+}  // namespace
+
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda) {
-    (void)lower;
     constexpr int TR = tile_rows<T>();
     SymvPlan<T> p;
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
+    // Main kernel.  Measured: the balanced kernel wins for 16-byte elements from a
+    // few thousand rows on, and for the upper triangle when all columns start at
+    // the same offset inside an 8 KiB stretch (the chain kernel then loads the
+    // memory channels unevenly); otherwise the chain kernel is 2-5% faster.
+    p.variant = (int)tuning().symv_variant;
+    if (p.variant <= 0) {
+        const bool wide = sizeof(T) == 16 && n >= 3000;
+        const bool aliased = !lower && n >= 12000 && ((uint64_t)lda * sizeof(T)) % 8192 == 0;
+        p.variant = (wide || aliased) ? 2 : 1;
+    }
+    if (n > (int64_t)1 << 30) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
+    if (p.variant == 2) C = BAL_NC * SY_NW;
     // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
     int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
-                                                   : (sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE);
+                                                   : (sizeof(T) == 4 && p.variant == 1 ? 1 : DEFAULT_TILES_PER_WAVE);
     if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
@@ -344,10 +670,56 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     if (sizing) Q = MAX_CLASSES;
     else if (Q > p.npanels) Q = p.npanels;
     p.classes = Q;
-    p.rows_padded = partial_stride<T>(p.ntiles * TR);
+    p.work = 0;
+    p.workers = 0;
+    size_t wsn_bytes;
+    if (sizing) {
+        // room for either variant: MAX_CLASSES row-sum vectors of all rows, or one
+        // vector of the tallest chunk per workgroup and chunk
+        p.rows_padded = partial_stride<T>(p.ntiles * TR);
+        const size_t chains = (size_t)Q * p.rows_padded * sizeof(T);
+        // workgroups <= pieces: the largest piece count over both triangles, both
+        // chunk heights and all alignments
+        int64_t entries = 0;
+        const int64_t C2 = BAL_NC * SY_NW;
+        for (int64_t kt = 1; kt <= 2; ++kt)
+            for (int sh = 0; sh <= max_row_shift<T>(); ++sh) {
+                const int64_t nt = ceil_div(n + sh, TR), ct = SY_NW * kt, nc = ceil_div(nt, ct), npan = ceil_div(n, C2);
+                int64_t lo = 0, up = 0, plo, tk;
+                for (int64_t k = 0; k < nc; ++k) {
+                    lo += chunk_pieces<true>(k, ct, C2, sh, TR, nt, npan, plo, tk);
+                    up += chunk_pieces<false>(k, ct, C2, sh, TR, nt, npan, plo, tk);
+                }
+                if (lo > entries) entries = lo;
+                if (up > entries) entries = up;
+            }
+        if (entries > MAX_WORKERS) entries = MAX_WORKERS;
+        entries += p.nchunks + 1;
+        const size_t balanced = (size_t)entries * partial_stride<T>(2 * SY_NW * TR) * sizeof(T);
+        wsn_bytes = chains > balanced ? chains : balanced;
+    } else if (p.variant == 2) {
+        int64_t plo, tk, pieces = 0;
+        for (int64_t k = 0; k < p.nchunks; ++k) {
+            const int64_t len = lower ? chunk_pieces<true>(k, p.chunk_tiles, C, p.shift, TR, p.ntiles, p.npanels, plo, tk)
+                                      : chunk_pieces<false>(k, p.chunk_tiles, C, p.shift, TR, p.ntiles, p.npanels, plo, tk);
+            pieces += len;
+            p.work += len;
+        }
+        int64_t Y = tuning().wg_target > 0 ? tuning().wg_target : balanced_slots<T>(lower, (int)ktw);
+        if (Y <= 0) Y = 768;
+        if (Y > MAX_WORKERS) Y = MAX_WORKERS;
+        if (Y > pieces) Y = pieces;
+        if (Y < 1) Y = 1;
+        p.workers = Y;
+        p.rows_padded = partial_stride<T>(p.chunk_tiles * TR);
+        wsn_bytes = (size_t)(Y + p.nchunks) * p.rows_padded * sizeof(T);
+    } else {
+        p.rows_padded = partial_stride<T>(p.ntiles * TR);
+        wsn_bytes = (size_t)Q * p.rows_padded * sizeof(T);
+    }
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
-    p.wst_off = p.wsn_off + round_up((size_t)Q * p.rows_padded * sizeof(T), WS_ALIGN);
+    p.wst_off = p.wsn_off + round_up(wsn_bytes, WS_ALIGN);
     p.total_bytes = p.wst_off + round_up((size_t)p.npanels * p.nchunks * C * sizeof(T), WS_ALIGN);
     return p;
 }
@@ -359,8 +731,21 @@ void launch_main(const SymvArgs<T>& a, hipStream_t s) {
     hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, sy_nc<T>(), C / sy_nc<T>(), KTW, SY_NW>), grid, dim3(SY_NW * WAVE),
                        0, s, a);
 }
+template <class T, bool HERM, bool LOWER, int G>
+void launch_balanced(const SymvArgs<T>& a, hipStream_t s) {
+    const dim3 grid((unsigned)a.plan.workers);
+    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, bal_kt<T>(), G, SY_NW>), grid, dim3(SY_NW * WAVE), 0,
+                       s, a);
+}
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
     const int cols = (int)a.plan.panel_cols, ktw = (int)(a.plan.chunk_tiles / SY_NW);
+    if (a.plan.variant == 2) {
+        if (cols != BAL_NC * SY_NW || a.plan.workers < 1) return false;
+        if (ktw == 1) launch_balanced<T, HERM, LOWER, SY_NW / bal_kt<T>()>(a, s);
+        else if (ktw == 2) launch_balanced<T, HERM, LOWER, 2 * SY_NW / bal_kt<T>()>(a, s);
+        else return false;
+        return true;
+    }
     if (cols == 16 && ktw == 1) launch_main<T, HERM, LOWER, 16, 1>(a, s);
     else if (cols == 16 && ktw == 2) launch_main<T, HERM, LOWER, 16, 2>(a, s);
     else if (cols == 32 && ktw == 1) launch_main<T, HERM, LOWER, 32, 1>(a, s);
@@ -382,10 +767,13 @@ template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipS
     if (e != hipSuccess) return e;
     const dim3 rgrid((unsigned)ceil_div(a.n, RED_ROWS));
     const dim3 rblock(RED_ROWS, RED_PARTS);
-    if (lower)
-        hipLaunchKernelGGL((symv_reduce_kernel<T, true>), rgrid, rblock, 0, s, a);
-    else
-        hipLaunchKernelGGL((symv_reduce_kernel<T, false>), rgrid, rblock, 0, s, a);
+    if (a.plan.variant == 2) {
+        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, true, true>), rgrid, rblock, 0, s, a);
+        else hipLaunchKernelGGL((symv_reduce_kernel<T, false, true>), rgrid, rblock, 0, s, a);
+    } else {
+        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, true, false>), rgrid, rblock, 0, s, a);
+        else hipLaunchKernelGGL((symv_reduce_kernel<T, false, false>), rgrid, rblock, 0, s, a);
+    }
     return hipGetLastError();
 }
 

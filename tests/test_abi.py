@@ -120,3 +120,19 @@ def test_tuning_keys_roundtrip():
     with pytest.raises(ValueError):
         kmv.set_tuning("symv_panel_cols", 96)
     assert "kmv" in kmv.version()
+
+
+def test_symv_kernel_variant_query():
+    """host-only: names the main kernel without reading or launching anything"""
+    assert kmv.symv_kernel_variant("d", "X", 100, DUMMY, 100) == 0
+    assert kmv.symv_kernel_variant("q", "L", 100, DUMMY, 100) == 0
+    assert kmv.symv_kernel_variant("d", "L", 100, DUMMY, 99) == 0
+    for prec in "sdcz":
+        for uplo in "LU":
+            assert kmv.symv_kernel_variant(prec, uplo, 5000, DUMMY, 5000) in (1, 2)
+    try:
+        for v in (1, 2):
+            kmv.set_tuning("symv_variant", v)
+            assert kmv.symv_kernel_variant("s", "L", 5000, DUMMY, 5000) == v
+    finally:
+        kmv.set_tuning("symv_variant", 0)
