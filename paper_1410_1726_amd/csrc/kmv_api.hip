@@ -93,6 +93,7 @@ int symv_entry(char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, co
     a.y = yb; a.incy = incy; a.alpha = al; a.beta = be;
     a.wsn = reinterpret_cast<T*>(ws + plan.wsn_off);
     a.wst = reinterpret_cast<T*>(ws + plan.wst_off);
+    a.wtab = reinterpret_cast<int*>(ws + plan.tab_off);
     a.plan = plan;
     if (incx != 1) {
         T* xp = reinterpret_cast<T*>(ws + plan.xpack_off);

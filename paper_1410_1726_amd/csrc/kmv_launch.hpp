@@ -85,7 +85,7 @@ template <class T> struct SymvPlan {
     int64_t rows_padded;   // distance between two row-sum vectors (variant 1: >= ntiles * tile_rows; 2: >= chunk rows)
     int64_t work;          // variant 2: length of the work line (row tiles x panels that hold stored elements)
     int64_t workers;       // variant 2: workgroups of the main kernel
-    size_t xpack_off, wsn_off, wst_off, total_bytes;
+    size_t xpack_off, wsn_off, wst_off, tab_off, total_bytes;
 };
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
 
@@ -98,6 +98,7 @@ template <class T> struct SymvArgs {
     T alpha, beta;
     T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
+    int* wtab;        // variant 2: [nchunks][2] first and last workgroup whose share touches the chunk
     SymvPlan<T> plan;
 };
 template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s);

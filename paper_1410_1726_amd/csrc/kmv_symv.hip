@@ -290,21 +290,22 @@ __host__ __device__ __forceinline__ int64_t chunk_pieces(int64_t k, int64_t CT, 
     tk = tend - tbeg;
     return phi > plo ? phi - plo : 0;
 }
-// worker that owns item s when `partition` deals P items to Y workers
-__host__ __device__ __forceinline__ int64_t partition_owner(int64_t P, int64_t Y, int64_t s) {
-    const int64_t q = P / Y, r = P % Y, thr = r * (q + 1);
-    return s < thr ? s / (q + 1) : r + (s - thr) / q;
-}
+// Length of a piece on the work line: its row tiles plus a fixed part (measured:
+// a piece of a short last chunk costs clearly more than its share of the rows).
+#ifndef KMV_PIECE_FIXED
+#define KMV_PIECE_FIXED 3
+#endif
+__host__ __device__ __forceinline__ int64_t piece_weight(int64_t tk) { return tk + KMV_PIECE_FIXED; }
 
 // Balanced form: the pieces (row chunk k, panel p) of the stored triangle are
-// laid chunk by chunk on a work line that is dealt to the workgroups in equal
-// contiguous shares by the partition of Section 6.2, and the grid is exactly
+// laid chunk by chunk on a work line (piece_weight units each) that is dealt to
+// the workgroups in equal contiguous shares by the partition of Section 6.2 (a
+// piece goes to the share that holds its first unit), and the grid is exactly
 // one resident round (compute units x occupancy): every workgroup starts at
 // once, reads about the same number of bytes and ends at once, and at any
 // moment the resident workgroups cover all row chunks, so the load on memory
 // channels does not depend on the leading dimension.  A workgroup's share lies
-// in one chunk, rarely two or more.  (Pieces count alike: measured, a piece of
-// a short last chunk costs nearly as much as a full one.)
+// in one chunk, rarely two or more.
 // Inside a piece wave w owns the columns [w*NC, (w+1)*NC) of the panel over ALL
 // CT = KT*G row tiles (G units of KT tiles, visited in a per-wave rotated order
 // so that the waves read different KiB of their columns at any moment).  The
@@ -313,8 +314,9 @@ __host__ __device__ __forceinline__ int64_t partition_owner(int64_t P, int64_t Y
 // work is spread over all waves.  The row sums of a wave live in a wave-private
 // LDS array (each lane touches only its own slots, no synchronisation) and meet
 // the other waves' when the share leaves a chunk: one row-sum vector per
-// (workgroup, chunk), stored at index workgroup + chunk.  x over the chunk's
-// rows is staged in LDS.
+// (workgroup, chunk), stored at index workgroup + chunk; the owners of a
+// chunk's first and last piece leave their numbers in a small table for the
+// final pass.  x over the chunk's rows is staged in LDS.
 template <class T, bool HERM, bool LOWER, int NC, int KT, int G, int NW>
 __global__ __launch_bounds__(NW * WAVE, 3) void symv_balanced_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
@@ -354,12 +356,19 @@ __global__ __launch_bounds__(NW * WAVE, 3) void symv_balanced_kernel(SymvArgs<T>
     for (int k = 0; k < nchunks && wb < whi; ++k) {
         int64_t plo64, tk, len;
         len = chunk_pieces<LOWER>(k, CT, C, shift, TR, ntiles, npanels, plo64, tk);
-        const int64_t wb0 = wb;
-        wb += len;
+        const int64_t wb0 = wb, pw = piece_weight(tk);
+        wb += len * pw;
         if (wb <= wlo) continue;   // the share starts in a later chunk
-        // pieces of this chunk that lie in the share
+        // pieces of this chunk whose first unit of the line lies in the share (there
+        // may be none: the row-sum vector is then all zeros)
         const int64_t lo = (wlo > wb0 ? wlo : wb0) - wb0, hi = (whi < wb ? whi : wb) - wb0;
-        const int j0 = (int)lo, j1 = (int)hi;
+        const int j0 = (int)((lo + pw - 1) / pw), j1 = (int)((hi + pw - 1) / pw);
+        // the owners of a chunk's first and last piece tell the final pass which
+        // row-sum vectors exist for the chunk
+        if (threadIdx.x == 0 && j1 > j0) {
+            if (j0 == 0) a.wtab[2 * k] = (int)blockIdx.x;
+            if (j1 == (int)len) a.wtab[2 * k + 1] = (int)blockIdx.x;
+        }
         // piece, panel and unit counts fit 32 bits (n < 2^31 * 16 columns)
         const int pfirst = (int)plo64 + j0;
         const int gk = ((int)tk + KT - 1) / KT;   // units per piece: a short last chunk has fewer
@@ -557,22 +566,16 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
     T s = zero_of<T>();
     if (i < a.n) {
         if (BAL) {
-            // row-sum vectors of the workgroups whose share touches the chunk of row i
+            // row-sum vectors of the workgroups whose share touches the chunk of row i:
+            // numbers ylo..yhi (left by the main kernel), vector y + k each
             const int64_t CT = a.plan.chunk_tiles, slot = i + shift;
             const int64_t k = slot / (CT * TR);
-            int64_t before = 0, plo, tk = 0, len = 0;
-            for (int64_t kk = 0; kk <= k; ++kk) {
-                before += len;
-                len = chunk_pieces<LOWER>(kk, CT, C, shift, TR, a.plan.ntiles, a.plan.npanels, plo, tk);
-            }
-            if (len > 0) {
-                // every workgroup whose share meets the chunk's stretch of the work line wrote a vector
-                const int64_t ylo = partition_owner(a.plan.work, a.plan.workers, before);
-                const int64_t yhi = partition_owner(a.plan.work, a.plan.workers, before + len - 1);
-                const T* __restrict__ wsn = a.wsn + (slot - k * CT * TR);
+            int64_t ylo = a.wtab[2 * k], yhi = a.wtab[2 * k + 1];
+            if (ylo < 0) ylo = 0;
+            if (yhi >= a.plan.workers) yhi = a.plan.workers - 1;
+            const T* __restrict__ wsn = a.wsn + (slot - k * CT * TR);
 #pragma unroll 4
-                for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
-            }
+            for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
         } else {
             const T* __restrict__ wsn = a.wsn + i + shift;
 #pragma unroll 4
@@ -703,7 +706,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             const int64_t len = lower ? chunk_pieces<true>(k, p.chunk_tiles, C, p.shift, TR, p.ntiles, p.npanels, plo, tk)
                                       : chunk_pieces<false>(k, p.chunk_tiles, C, p.shift, TR, p.ntiles, p.npanels, plo, tk);
             pieces += len;
-            p.work += len;
+            p.work += len * piece_weight(tk);
         }
         int64_t Y = tuning().wg_target > 0 ? tuning().wg_target : balanced_slots<T>(lower, (int)ktw);
         if (Y <= 0) Y = 768;
@@ -720,7 +723,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
     p.wst_off = p.wsn_off + round_up(wsn_bytes, WS_ALIGN);
-    p.total_bytes = p.wst_off + round_up((size_t)p.npanels * p.nchunks * C * sizeof(T), WS_ALIGN);
+    p.tab_off = p.wst_off + round_up((size_t)p.npanels * p.nchunks * C * sizeof(T), WS_ALIGN);
+    p.total_bytes = p.tab_off + round_up((size_t)p.nchunks * 2 * sizeof(int), WS_ALIGN);
     return p;
 }
 
