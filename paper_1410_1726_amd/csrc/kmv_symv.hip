@@ -642,21 +642,24 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
     // Main kernel.  Measured: the balanced kernel wins for 16-byte elements from a
-    // few thousand rows on, and for the upper triangle when all columns start at
-    // the same offset inside an 8 KiB stretch (the chain kernel then loads the
-    // memory channels unevenly); otherwise the chain kernel is 2-5% faster.
+    // few thousand rows on, and whenever all columns start at the same offset
+    // inside an 8 KiB stretch (the chain kernel then loads the memory channels
+    // unevenly); otherwise the chain kernel is 2-5% faster.
     p.variant = (int)tuning().symv_variant;
     if (p.variant <= 0) {
         const bool wide = sizeof(T) == 16 && n >= 3000;
-        const bool aliased = !lower && n >= 12000 && ((uint64_t)lda * sizeof(T)) % 8192 == 0;
+        const bool aliased = n >= 4096 && ((uint64_t)lda * sizeof(T)) % 8192 == 0;
         p.variant = (wide || aliased) ? 2 : 1;
     }
     if (n > (int64_t)1 << 30) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
     if (p.variant == 2) C = BAL_NC * SY_NW;
     // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
-    int64_t ktw = tuning().symv_tiles_per_wave > 0 ? tuning().symv_tiles_per_wave
-                                                   : (sizeof(T) == 4 && p.variant == 1 ? 1 : DEFAULT_TILES_PER_WAVE);
+    int64_t ktw = tuning().symv_tiles_per_wave;
+    if (ktw <= 0) {
+        if (p.variant == 1) ktw = sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE;
+        else ktw = (sizeof(T) < 16 && n <= 16384) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay up to there
+    }
     if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
