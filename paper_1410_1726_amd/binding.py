@@ -98,18 +98,32 @@ def workspace(nbytes: int, device=None) -> torch.Tensor:
     return buf
 
 
+_cached_workspace = workspace   # the wrappers below take a parameter called `workspace`
+
+
 def _stream(stream):
     if stream is None:
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
 
 
+_ws_bytes_cache: dict = {}
+
+
 def gemv_workspace_bytes(prec, trans, m, n) -> int:
-    return int(lib.kmv_gemv_workspace_bytes(prec.encode(), trans.encode(), m, n))
+    key = ("g", prec, trans, m, n)
+    v = _ws_bytes_cache.get(key)
+    if v is None:
+        v = _ws_bytes_cache[key] = int(lib.kmv_gemv_workspace_bytes(prec.encode(), trans.encode(), m, n))
+    return v
 
 
 def symv_workspace_bytes(prec, uplo, n) -> int:
-    return int(lib.kmv_symv_workspace_bytes(prec.encode(), uplo.encode(), n))
+    key = ("s", prec, uplo, n)
+    v = _ws_bytes_cache.get(key)
+    if v is None:
+        v = _ws_bytes_cache[key] = int(lib.kmv_symv_workspace_bytes(prec.encode(), uplo.encode(), n))
+    return v
 
 
 def _ws_args(workspace_, need, y):
@@ -174,6 +188,47 @@ def chemv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream
 
 def zhemv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
     return _symv("zhemv", "z", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+class Prepared:
+    """One routine call with every argument already marshalled: calling the object
+    only makes the foreign call (for loops that repeat a product, where the
+    per-call Python work of the plain wrappers would exceed the kernel time).
+    Holds references to the tensors (and the workspace) so that the addresses stay
+    valid; the stream is fixed at preparation time."""
+
+    __slots__ = ("_fn", "_args", "_keep", "name")
+
+    def __init__(self, name, fn, args, keep):
+        self.name, self._fn, self._args, self._keep = name, fn, args, keep
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != 0:
+            raise KmvError(self.name, rc)
+
+
+def prepare_gemv(prec, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None) -> Prepared:
+    if workspace is None:
+        workspace = _cached_workspace(gemv_workspace_bytes(prec, trans, max(m, 0), max(n, 0)),
+                                           None if isinstance(y, int) else y.device)
+    wsp, wsb = _ws_args(workspace, None, y)
+    al, be = _scalar(prec, alpha), _scalar(prec, beta)
+    args = (trans.encode(), m, n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be, _ptr(y, prec), incy,
+            ctypes.c_void_p(wsp), wsb, _stream(stream))
+    return Prepared(f"{prec}gemv", getattr(lib, f"kmv_{prec}gemv"), args, (A, x, y, workspace))
+
+
+def prepare_symv(prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None) -> Prepared:
+    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}"
+    if workspace is None:
+        workspace = _cached_workspace(symv_workspace_bytes(prec, uplo, max(n, 0)),
+                                           None if isinstance(y, int) else y.device)
+    wsp, wsb = _ws_args(workspace, None, y)
+    al, be = _scalar(prec, alpha), _scalar(prec, beta)
+    args = (uplo.encode(), n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be, _ptr(y, prec), incy,
+            ctypes.c_void_p(wsp), wsb, _stream(stream))
+    return Prepared(name, getattr(lib, f"kmv_{name}"), args, (A, x, y, workspace))
 
 
 GEMV = {"s": sgemv, "d": dgemv, "c": cgemv, "z": zgemv}

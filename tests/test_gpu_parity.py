@@ -295,3 +295,29 @@ def test_runs_on_a_side_stream_with_explicit_workspace():
     finally:
         k.set_tuning("gemv_n_splits", 0)
     assert rc == k.ERR_WORKSPACE and torch.equal(y, ref)
+
+
+def test_prepared_calls_match_plain_calls():
+    """a prepared call (arguments marshalled once) gives the bits of the plain wrapper"""
+    k = kmv()
+    n = 1500
+    A = wl.matrix("d", n, n, seed=21, device=DEV)
+    x = wl.vector("d", n, seed=21, device=DEV)
+    y0 = wl.vector("d", n, seed=21, which=2, device=DEV)
+    for make, plain in ((lambda y: k.prepare_gemv("d", "N", n, n, 0.7, A, n, x, 1, 0.3, y, 1),
+                         lambda y: k.dgemv("N", n, n, 0.7, A, n, x, 1, 0.3, y, 1)),
+                        (lambda y: k.prepare_gemv("d", "T", n, n, 0.7, A, n, x, 1, 0.3, y, 1),
+                         lambda y: k.dgemv("T", n, n, 0.7, A, n, x, 1, 0.3, y, 1)),
+                        (lambda y: k.prepare_symv("d", "U", n, 0.7, A, n, x, 1, 0.3, y, 1),
+                         lambda y: k.dsymv("U", n, 0.7, A, n, x, 1, 0.3, y, 1))):
+        ref = y0.clone()
+        plain(ref)
+        y = y0.clone()
+        call = make(y)
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref)
+        y.copy_(y0)
+        call()                       # a prepared call can be repeated
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref)
