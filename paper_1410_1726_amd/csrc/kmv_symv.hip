@@ -318,7 +318,13 @@ __host__ __device__ __forceinline__ int64_t piece_weight(int64_t tk) { return tk
 // chunk's first and last piece leave their numbers in a small table for the
 // final pass.  x over the chunk's rows is staged in LDS.
 template <class T, bool HERM, bool LOWER, int NC, int KT, int G, int NW>
-__global__ __launch_bounds__(NW * WAVE, 3) void symv_balanced_kernel(SymvArgs<T> a) {
+#ifndef KMV_BAL_MINB
+#define KMV_BAL_MINB 3
+#endif
+#ifndef KMV_BAL_KT16
+#define KMV_BAL_KT16 1
+#endif
+__global__ __launch_bounds__(NW * WAVE, KMV_BAL_MINB) void symv_balanced_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     constexpr int C = NC * NW;
@@ -607,7 +613,7 @@ namespace {
 // registers allow eight 16-byte loads per lane and buffer without spilling and
 // the rate gains from it: 8-byte elements)
 constexpr int BAL_NC = 4;
-template <class T> constexpr int bal_kt() { return sizeof(T) == 8 ? 2 : 1; }
+template <class T> constexpr int bal_kt() { return sizeof(T) == 8 ? 2 : (sizeof(T) == 16 ? KMV_BAL_KT16 : 1); }
 constexpr int64_t MAX_WORKERS = 2048;
 // workgroups of the balanced kernel that are resident at once (compute units x
 // occupancy), queried once per element type and chunk height
@@ -641,15 +647,15 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
-    // Main kernel.  Measured: the balanced kernel wins for 16-byte elements from a
-    // few thousand rows on, and whenever all columns start at the same offset
-    // inside an 8 KiB stretch (the chain kernel then loads the memory channels
-    // unevenly); otherwise the chain kernel is 2-5% faster.
+    // Main kernel.  Measured with the two kernels alternating in one process: the
+    // balanced kernel is faster (by up to 10-30% below n = 8192 and for 16-byte
+    // elements, 3-8% when all columns start at the same offset inside an 8 KiB
+    // stretch) or equal, except for large matrices whose columns are not 16-byte
+    // aligned, where the chain kernel's longer runs per column win 2-3%.
     p.variant = (int)tuning().symv_variant;
     if (p.variant <= 0) {
-        const bool wide = sizeof(T) == 16 && n >= 3000;
-        const bool aliased = n >= 4096 && ((uint64_t)lda * sizeof(T)) % 8192 == 0;
-        p.variant = (wide || aliased) ? 2 : 1;
+        const bool drifting = n >= 12000 && ((uint64_t)lda * sizeof(T)) % 16 != 0;
+        p.variant = drifting ? 1 : 2;
     }
     if (n > (int64_t)1 << 30) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
@@ -658,7 +664,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     int64_t ktw = tuning().symv_tiles_per_wave;
     if (ktw <= 0) {
         if (p.variant == 1) ktw = sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE;
-        else ktw = (sizeof(T) < 16 && n <= 16384) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay up to there
+        else ktw = n <= (sizeof(T) < 16 ? 16384 : 8192) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay up to there
     }
     if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
     p.panel_cols = C;
