@@ -153,6 +153,7 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *   symv_panel_cols               panel width of variant 1 (16, 32, 64, 128)
  *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)
  *   symv_classes                  variant 1: chains per row chunk (1..256)
+ *   symv_unit_tiles               variant 2: row tiles per prefetch unit (1, 2)
  *   wg_target                     workgroups the split heuristics aim for; for
  *                                 SYMV variant 2 the number of workgroups */
 int kmv_set_tuning(const char* key, int64_t value);

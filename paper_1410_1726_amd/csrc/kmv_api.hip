@@ -125,6 +125,7 @@ const Key KEYS[] = {
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
     {"symv_classes", &Tuning::symv_classes, 0, 256},
     {"symv_variant", &Tuning::symv_variant, 0, 2},
+    {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
 };
 
@@ -229,7 +230,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,wg_target"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

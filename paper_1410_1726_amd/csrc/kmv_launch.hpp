@@ -20,6 +20,7 @@ struct Tuning {
     int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave: 1 or 2
     int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
     int64_t symv_variant = 0;         // SYMV main kernel: 1 = chains, 2 = balanced shares
+    int64_t symv_unit_tiles = 0;      // balanced kernel: row tiles per prefetch unit (1 or 2)
     int64_t wg_target = 0;         // workgroups the heuristics aim for
 };
 Tuning& tuning();
@@ -76,6 +77,7 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
 template <class T> struct SymvPlan {
     int shift;
     int variant;           // main kernel: 1 = chains of panels per row chunk, 2 = balanced shares of pieces
+    int unit_tiles;        // variant 2: row tiles per prefetch unit
     int64_t ntiles;        // row tiles covering [-shift, n)
     int64_t panel_cols;    // columns per panel
     int64_t npanels;       // column panels

@@ -318,13 +318,7 @@ __host__ __device__ __forceinline__ int64_t piece_weight(int64_t tk) { return tk
 // chunk's first and last piece leave their numbers in a small table for the
 // final pass.  x over the chunk's rows is staged in LDS.
 template <class T, bool HERM, bool LOWER, int NC, int KT, int G, int NW>
-#ifndef KMV_BAL_MINB
-#define KMV_BAL_MINB 3
-#endif
-#ifndef KMV_BAL_KT16
-#define KMV_BAL_KT16 1
-#endif
-__global__ __launch_bounds__(NW * WAVE, KMV_BAL_MINB) void symv_balanced_kernel(SymvArgs<T> a) {
+__global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     constexpr int C = NC * NW;
@@ -609,33 +603,40 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 
 // ------------------------------------------------------------- host side ----
 namespace {
-// balanced kernel: columns per wave, and row tiles per unit (two where the
-// registers allow eight 16-byte loads per lane and buffer without spilling and
-// the rate gains from it: 8-byte elements)
-constexpr int BAL_NC = 4;
-template <class T> constexpr int bal_kt() { return sizeof(T) == 8 ? 2 : (sizeof(T) == 16 ? KMV_BAL_KT16 : 1); }
+constexpr int BAL_NC = 4;   // balanced kernel: columns per wave
+// Row tiles per unit (KT) and workgroups per compute unit that go with it, measured
+// with the settings alternating in one process: two tiles (8 loads per lane and
+// buffer) with two workgroups per compute unit for 8- and 16-byte elements from
+// n = 16384 on (1-3% faster there, 3-5% slower at n = 8192), otherwise one tile
+// (4 loads) with three workgroups per compute unit.
+template <class T> inline int default_unit_tiles(int64_t n) { return (sizeof(T) >= 8 && n >= 16384) ? 2 : 1; }
+inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }
 constexpr int64_t MAX_WORKERS = 2048;
-// workgroups of the balanced kernel that are resident at once (compute units x
-// occupancy), queried once per element type and chunk height
-template <class T, bool LOWER, int G> int64_t balanced_slots_of() {
+// compute units x min(occupancy, wanted workgroups per compute unit), queried once per instance
+template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     constexpr bool HERM = Traits<T>::cplx;
     int dev = 0, cus = 0, nb = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &nb, symv_balanced_kernel<T, HERM, LOWER, BAL_NC, bal_kt<T>(), G, SY_NW>, SY_NW * WAVE, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>,
+                                                         SY_NW * WAVE, 0);
     (void)hipGetLastError();
-    return (e == hipSuccess && cus > 0 && nb > 0) ? (int64_t)cus * nb : -1;
+    if (e != hipSuccess || cus <= 0 || nb <= 0) return -1;
+    return (int64_t)cus * (nb < wgs_per_cu(KT) ? nb : wgs_per_cu(KT));
 }
-template <class T> int64_t balanced_slots(bool lower, int ktw) {
-    static int64_t cache[2][3] = {{0, 0, 0}, {0, 0, 0}};
-    if (ktw < 1 || ktw > 2) return -1;
-    int64_t& c = cache[lower ? 1 : 0][ktw];
+template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
+    static int64_t cache[2][3][3] = {};
+    if (ktw < 1 || ktw > 2 || kt < 1 || kt > 2) return -1;
+    int64_t& c = cache[lower ? 1 : 0][ktw][kt];
     if (c == 0) {
-        constexpr int G1 = SY_NW / bal_kt<T>(), G2 = 2 * SY_NW / bal_kt<T>();
-        if (lower) c = ktw == 1 ? balanced_slots_of<T, true, G1>() : balanced_slots_of<T, true, G2>();
-        else c = ktw == 1 ? balanced_slots_of<T, false, G1>() : balanced_slots_of<T, false, G2>();
+        if (lower) {
+            if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, true, 1, SY_NW>() : balanced_slots_of<T, true, 1, 2 * SY_NW>();
+            else c = ktw == 1 ? balanced_slots_of<T, true, 2, SY_NW / 2>() : balanced_slots_of<T, true, 2, SY_NW>();
+        } else {
+            if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, false, 1, SY_NW>() : balanced_slots_of<T, false, 1, 2 * SY_NW>();
+            else c = ktw == 1 ? balanced_slots_of<T, false, 2, SY_NW / 2>() : balanced_slots_of<T, false, 2, SY_NW>();
+        }
     }
     return c;
 }
@@ -683,6 +684,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     else if (Q > p.npanels) Q = p.npanels;
     p.classes = Q;
     p.work = 0;
+    p.unit_tiles = 1;
     p.workers = 0;
     size_t wsn_bytes;
     if (sizing) {
@@ -717,8 +719,9 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             pieces += len;
             p.work += len * piece_weight(tk);
         }
-        int64_t Y = tuning().wg_target > 0 ? tuning().wg_target : balanced_slots<T>(lower, (int)ktw);
-        if (Y <= 0) Y = 768;
+        p.unit_tiles = tuning().symv_unit_tiles > 0 ? (int)tuning().symv_unit_tiles : default_unit_tiles<T>(n);
+        int64_t Y = tuning().wg_target > 0 ? tuning().wg_target : balanced_slots<T>(lower, (int)ktw, p.unit_tiles);
+        if (Y <= 0) Y = 256 * wgs_per_cu(p.unit_tiles);
         if (Y > MAX_WORKERS) Y = MAX_WORKERS;
         if (Y > pieces) Y = pieces;
         if (Y < 1) Y = 1;
@@ -744,18 +747,20 @@ void launch_main(const SymvArgs<T>& a, hipStream_t s) {
     hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, sy_nc<T>(), C / sy_nc<T>(), KTW, SY_NW>), grid, dim3(SY_NW * WAVE),
                        0, s, a);
 }
-template <class T, bool HERM, bool LOWER, int G>
+template <class T, bool HERM, bool LOWER, int KT, int G>
 void launch_balanced(const SymvArgs<T>& a, hipStream_t s) {
     const dim3 grid((unsigned)a.plan.workers);
-    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, bal_kt<T>(), G, SY_NW>), grid, dim3(SY_NW * WAVE), 0,
-                       s, a);
+    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
     const int cols = (int)a.plan.panel_cols, ktw = (int)(a.plan.chunk_tiles / SY_NW);
     if (a.plan.variant == 2) {
+        const int kt = a.plan.unit_tiles;
         if (cols != BAL_NC * SY_NW || a.plan.workers < 1) return false;
-        if (ktw == 1) launch_balanced<T, HERM, LOWER, SY_NW / bal_kt<T>()>(a, s);
-        else if (ktw == 2) launch_balanced<T, HERM, LOWER, 2 * SY_NW / bal_kt<T>()>(a, s);
+        if (ktw == 1 && kt == 1) launch_balanced<T, HERM, LOWER, 1, SY_NW>(a, s);
+        else if (ktw == 2 && kt == 1) launch_balanced<T, HERM, LOWER, 1, 2 * SY_NW>(a, s);
+        else if (ktw == 1 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW / 2>(a, s);
+        else if (ktw == 2 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW>(a, s);
         else return false;
         return true;
     }

@@ -257,16 +257,17 @@ def test_symv_main_kernel_variants(prec, variant):
     k = kmv()
     try:
         k.set_tuning("symv_variant", variant)
-        for tpw, target in ((0, 0), (1, 3), (2, 1), (1, 256), (2, 7)):
+        for tpw, target, unit in ((0, 0, 0), (1, 3, 1), (2, 1, 2), (1, 256, 2), (2, 7, 1)):
             k.set_tuning("symv_tiles_per_wave", tpw)
             k.set_tuning("symv_classes", target)
             k.set_tuning("wg_target", target)
+            k.set_tuning("symv_unit_tiles", unit)
             for n, off, lda in ((1, 0, None), (63, 0, None), (257, 0, 300), (1500, 17, 1792), (2048, 0, 2048),
                                 (3001, 0, 3008), (4099, 1, 4112)):
                 for uplo in "LU":
                     beta = 0.0 if (n + off) % 2 else 0.3
                     _, err, _ = symv_case(prec, uplo, n, 0.7, beta, lda=lda, off=off, seed=n + off, nan_imag_diag=True)
-                    check(prec, err, f"variant={variant} tiles_per_wave={tpw} target={target} {prec} {uplo} n={n} off={off}")
+                    check(prec, err, f"variant={variant} tiles_per_wave={tpw} target={target} unit={unit} {prec} {uplo} n={n} off={off}")
     finally:
         for key in k.tuning_keys():
             k.set_tuning(key, 0)
