@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "tiny"])
+    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "rect", "tiny"])
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
@@ -94,6 +94,13 @@ def products(workload):
                                     alpha=-1.0, beta=1.0))
                 out.append(dict(kind="symv", prec="d", mode="L", n=n, lda=20000, off=o, parent=20000,
                                 alpha=-1.0, beta=1.0))
+    elif workload == "rect":       # panels as in blocked reductions: tall-skinny and short-wide, d and s, N and T
+        shapes = [(65536, 32), (65536, 128), (65536, 512), (16384, 64), (16384, 256), (16384, 1024), (16384, 4096),
+                  (32, 65536), (128, 65536), (512, 65536), (64, 16384), (256, 16384), (1024, 16384), (4096, 16384)]
+        for prec in "ds":
+            for m, n in shapes:
+                for trans in "NT":
+                    out.append(dict(kind="gemv", prec=prec, mode=trans, m=m, n=n, lda=m, alpha=1.0, beta=1.0))
     elif workload == "tiny":       # DGEMV N, m = n = lda = 1024, alpha 1.5, beta 0.5
         out.append(dict(kind="gemv", prec="d", mode="N", n=1024, lda=1024, alpha=1.5, beta=0.5))
     return out
@@ -137,7 +144,7 @@ class Inputs:
             key = (p["prec"], p.get("dist", "uniform"))
             cols = p.get("parent", 0) or p["n"]
             need[key] = max(need.get(key, 0), p["lda"] * cols)
-            vlen[key] = max(vlen.get(key, 0), 1 + (p["n"] - 1) * abs(p.get("incx", 1)))
+            vlen[key] = max(vlen.get(key, 0), 1 + (max(p["n"], p.get("m", 0)) - 1) * abs(p.get("incx", 1)))
         self.mat, self.vec = {}, {}
         for key, elems in need.items():
             prec, dist = key
@@ -163,7 +170,7 @@ def make_call(p, k, A, x, y):
     n, lda, incx = p["n"], p["lda"], p.get("incx", 1)
     # arguments are marshalled once, outside the timed region; a call is then one foreign call
     if p["kind"] == "gemv":
-        return k.prepare_gemv(p["prec"], p["mode"], n, n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
+        return k.prepare_gemv(p["prec"], p["mode"], p.get("m", n), n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
     return k.prepare_symv(p["prec"], p["mode"], n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
 
 
@@ -246,13 +253,13 @@ def main():
     # largest products first: the host runs ahead of the device, so the short
     # products at the end of a step are already queued when their turn comes
     probe = stream_probe(k, torch)
-    prods = sorted(products(args.workload), key=lambda p: -p["n"])
+    prods = sorted(products(args.workload), key=lambda p: -p["n"] * p.get("m", p["n"]))
     inputs = Inputs(prods, torch, wl)
     stream = torch.cuda.current_stream()
     calls = [make_call(p, k, *inputs.views(p)) for p in prods]
     nprod = len(prods)
-    per = [dict(bytes=acc.algorithmic_bytes(op_name(p), p["prec"], p["n"], p["n"]),
-                flops=acc.flops(op_name(p), p["prec"], p["n"], p["n"]), ms=0.0) for p in prods]
+    per = [dict(bytes=acc.algorithmic_bytes(op_name(p), p["prec"], p.get("m", p["n"]), p["n"]),
+                flops=acc.flops(op_name(p), p["prec"], p.get("m", p["n"]), p["n"]), ms=0.0) for p in prods]
 
     for _ in range(args.warmup):
         for call in calls:
@@ -310,7 +317,7 @@ def main():
         with open(args.table, "w") as f:
             for p, r in zip(prods, per):
                 gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9
-                f.write(json.dumps({"routine": routine_name(p), "n": p["n"], "lda": p["lda"], "off": p.get("off", 0),
+                f.write(json.dumps({"routine": routine_name(p), "m": p.get("m", p["n"]), "n": p["n"], "lda": p["lda"], "off": p.get("off", 0),
                                     "incx": p.get("incx", 1), "us": round(r["ms"] * 1e3, 2), "gbs": round(gbs, 1),
                                     "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                                     "gflops": round(r["flops"] / (r["ms"] * 1e-3) / 1e9, 1)}) + "\n")
@@ -326,6 +333,7 @@ def main():
             "target16k": "all 16 precision x routine products at n=16384 and 32768, lda=n",
             "large": "configs[4]: n=49152 (s,c) / 40960 (d,z), lda=n+32, N(0,1), alpha=0.7, beta=0.3, incx 1 and 2",
             "subblock": "configs[3]: blocks of a 20000x20000 fp64 parent at offsets 1,17,63,1000",
+            "rect": "S/DGEMV N,T on tall-skinny and short-wide panels (65536x32 .. 4096x16384 and transposes), lda=m",
             "tiny": "configs[0]: DGEMV N m=n=lda=1024",
         }[args.workload], "products_per_step": nprod},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),

@@ -149,6 +149,8 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  * automatically.  Process-wide; not thread safe against concurrent calls.
  *   gemv_n_splits, gemv_t_splits  column / row splits of the GEMV kernels
  *   gemv_n_row_tiles              row tiles per wave of GEMV-N (1, 2, 4)
+ *   gemv_short                    kernels for matrices of a few row tiles:
+ *                                 1 = never, 2 = whenever they apply
  *   symv_variant                  SYMV/HEMV main kernel, see below (1, 2)
  *   symv_panel_cols               panel width of variant 1 (16, 32, 64, 128)
  *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)

@@ -121,6 +121,7 @@ const Key KEYS[] = {
     {"gemv_n_splits", &Tuning::gemv_n_splits, 0, 256},
     {"gemv_t_splits", &Tuning::gemv_t_splits, 0, 256},
     {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
+    {"gemv_short", &Tuning::gemv_short, 0, 2},
     {"symv_panel_cols", &Tuning::symv_panel_cols, 0, 128},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
     {"symv_classes", &Tuning::symv_classes, 0, 256},
@@ -230,7 +231,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

@@ -177,18 +177,77 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     }
 }
 
+// Short matrices (one or two row tiles in all): the NW waves of a workgroup would
+// mostly idle in the kernel above, so here NW/tiles waves share a row tile and
+// split the workgroup's column slice once more; their row sums meet in LDS and
+// are added in wave order.  grid.x = column splits.
+template <class T, int NW, int U>
+__global__ __launch_bounds__(NW * WAVE) void gemv_n_short_kernel(GemvArgs<T> a) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int TR = WAVE * VEC;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int nt = (int)a.plan.ntiles;   // 1 or 2 (the launcher checks)
+    const int ws = NW / nt;              // waves per row tile
+    const int tile = w / ws, sub = w % ws;
+
+    int64_t cw, c0, cws, c0s;
+    partition(a.n, a.plan.splits, blockIdx.x, cw, c0);
+    partition(cw, ws, sub, cws, c0s);
+    int64_t r[1];
+    const int64_t r0 = (int64_t)tile * TR - a.plan.shift;
+    r[0] = r0 + (int64_t)lane * VEC;
+    const bool interior = (r0 >= 0) && (r0 + TR <= a.m);
+    T acc[1][VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[0][v] = zero_of<T>();
+    if (interior) gemv_n_walk<T, U, 1, NW, false>(a, r, c0 + c0s, cws, acc);
+    else if (a.m >= VEC) gemv_n_walk<T, U, 1, NW, true>(a, r, c0 + c0s, cws, acc);
+    else gemv_n_few_rows<T, 1>(a, r, c0 + c0s, cws, acc);
+
+    __shared__ T red[NW][TR];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) red[w][lane * VEC + v] = acc[0][v];
+    __syncthreads();
+    if (sub != 0) return;
+    Vec<T> out;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        T sum = red[w][lane * VEC + v];
+        for (int k = 1; k < ws; ++k) sum = add_of(sum, red[w + k][lane * VEC + v]);
+        out.e[v] = sum;
+    }
+    if (a.plan.splits == 1) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const int64_t row = r[0] + v;
+            if (row >= 0 && row < a.m) {
+                T* yp = a.y + row * a.incy;
+                *yp = epilogue(a.alpha, out.e[v], a.beta, yp);
+            }
+        }
+    } else {
+        store_vec(a.partial + (int64_t)blockIdx.x * a.plan.part_stride + (r[0] + a.plan.shift), out);
+    }
+}
+
 // ------------------------------------------------------------------ GEMV-T --
 // grid.x : groups of NC columns; grid.y : row splits.  The NW waves of a
 // workgroup take row tiles round robin and walk down their columns; each lane
 // keeps one accumulator per column; one wave reduction per column and one LDS
 // step across the waves at the very end.
-template <class T, bool CONJ, int NC, int NW>
-__global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
+// WCOLS (short matrices, a few row tiles only): every wave owns NC columns of its
+// own and walks all tiles of the split alone; nothing crosses waves.
+template <class T, bool CONJ, int NC, int NW_, bool WCOLS>
+__global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
+    constexpr int NW = WCOLS ? 1 : NW_;   // waves that share the tiles of a column group
     const int lane = threadIdx.x & (WAVE - 1);
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
-    const int64_t j0 = (int64_t)blockIdx.x * NC;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int w = WCOLS ? 0 : wv;
+    const int64_t j0 = WCOLS ? ((int64_t)blockIdx.x * NW_ + wv) * NC : (int64_t)blockIdx.x * NC;
+    if (WCOLS && j0 >= a.n) return;   // a whole wave past the last column (no barrier in this form)
     const int64_t ntiles = a.plan.ntiles;
     const int shift = a.plan.shift;
     const T* __restrict__ x = a.x;
@@ -249,7 +308,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     // sit at different row offsets (with a power-of-two leading dimension equal
     // row offsets of different columns share few L2 sets).  The rotation depends
     // only on the arguments, so results stay reproducible.
-    const int64_t rot = ni > 0 ? ((int64_t)blockIdx.x * 37) % ni : 0;
+    const int64_t rot = (ni > 0 && !WCOLS) ? ((int64_t)blockIdx.x * 37) % ni : 0;
     const int64_t cnt = ni > w ? (ni - w + NW - 1) / NW : 0;   // tiles of this wave
     {
         Vec<T> x0, x1, b0[NC], b1[NC];
@@ -279,17 +338,19 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     }
 
     __shared__ T red[NW][NC];
+    T mine = zero_of<T>();
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const T s = wave_sum(acc[c]);
-        if (lane == 0) red[w][c] = s;
+        if (WCOLS) mine = select_of(lane == c, s, mine);
+        else if (lane == 0) red[w][c] = s;
     }
-    __syncthreads();
-    if (threadIdx.x < NC) {
-        const int c = threadIdx.x;
+    if (!WCOLS) __syncthreads();
+    if (WCOLS ? lane < NC : threadIdx.x < NC) {
+        const int c = WCOLS ? lane : threadIdx.x;
         const int64_t j = j0 + c;
         if (j < a.n) {
-            T s = red[0][c];
+            T s = WCOLS ? mine : red[0][c];
             for (int ww = 1; ww < NW; ++ww) s = add_of(s, red[ww][c]);
             if (a.plan.splits == 1) {
                 T* yp = a.y + j * a.incy;
@@ -307,6 +368,7 @@ constexpr int GN_NW = 4;                // GEMV-N: waves per workgroup
 constexpr int GN_LOADS = 8;             // GEMV-N: 16-byte loads per lane and prefetch block (columns x tiles)
 constexpr int GT_NC = 8, GT_NW = 4;     // GEMV-T: columns per workgroup, waves per workgroup
 constexpr int64_t MAX_SPLITS = 256;
+constexpr int64_t SHORT_T_TILES = 2;         // GEMV-T: up to this many row tiles every wave owns its columns
 constexpr int64_t DEFAULT_WG_TARGET = 2048;   // about 8 workgroups per compute unit
 constexpr int64_t DEFAULT_GN_ROW_TILES = 1;
 }  // namespace
@@ -360,7 +422,23 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     p.ntiles = ceil_div(m + p.shift, TR);
     const int64_t target = tuning().wg_target > 0 ? tuning().wg_target : DEFAULT_WG_TARGET;
     int64_t s;
-    if (notrans) {
+    const int64_t max_splits = MAX_SPLITS;
+    p.short_form = 0;
+    const int64_t short_mode = tuning().gemv_short;   // 0 = automatic, 1 = never, 2 = whenever the kernels allow
+    if (notrans && !sizing && short_mode != 1 && p.ntiles <= 2) {
+        // one or two row tiles: NW/ntiles waves per tile split the columns once more
+        p.short_form = 1;
+        const int64_t ws = GN_NW / p.ntiles;
+        int64_t cap = n / (GN_LOADS * ws) > 1 ? n / (GN_LOADS * ws) : 1;   // a block of columns per wave at least
+        s = tuning().gemv_n_splits > 0 ? tuning().gemv_n_splits : (tuning().wg_target > 0 ? tuning().wg_target : 256);   // measured best
+        if (s > cap) s = cap;
+        p.part_stride = partial_stride<T>(p.ntiles * TR);
+    } else if (!notrans && !sizing && short_mode != 1 && (p.ntiles <= SHORT_T_TILES || (short_mode == 2 && p.ntiles <= 64))) {
+        // a few row tiles: every wave takes 8 columns of its own through all tiles, one launch
+        p.short_form = 1;
+        s = 1;
+        p.part_stride = partial_stride<T>(n);
+    } else if (notrans) {
         p.row_tiles = tuning().gemv_n_row_tiles > 0 ? tuning().gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
         const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
         int64_t cap = n / 32 > 1 ? n / 32 : 1;   // at least 32 columns per split
@@ -381,7 +459,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(n);
     }
-    if (s > MAX_SPLITS) s = MAX_SPLITS;
+    if (s > max_splits) s = max_splits;
     if (s < 1) s = 1;
     p.splits = s;
     const int64_t lenx = notrans ? n : m;
@@ -393,6 +471,13 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
 }
 
 template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s) {
+    if (a.plan.short_form) {
+        if (a.plan.ntiles < 1 || a.plan.ntiles > 2) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemv_n_short_kernel<T, GN_NW, GN_LOADS>), dim3((unsigned)a.plan.splits), dim3(GN_NW * WAVE), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess || a.plan.splits == 1) return e;
+        return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.y, a.incy, s);
+    }
     const int64_t rt = a.plan.row_tiles;
     const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt));
     const dim3 block(GN_NW * WAVE);
@@ -406,11 +491,19 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s)
 }
 
 template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s) {
-    const dim3 grid((unsigned)ceil_div(a.n, GT_NC), (unsigned)a.plan.splits);
-    if (conj && Traits<T>::cplx)
-        hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW>), grid, dim3(GT_NW * WAVE), 0, s, a);
-    else
-        hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW>), grid, dim3(GT_NW * WAVE), 0, s, a);
+    if (a.plan.short_form) {
+        const dim3 grid((unsigned)ceil_div(a.n, GT_NC * GT_NW), (unsigned)a.plan.splits);
+        if (conj && Traits<T>::cplx)
+            hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        else
+            hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+    } else {
+        const dim3 grid((unsigned)ceil_div(a.n, GT_NC), (unsigned)a.plan.splits);
+        if (conj && Traits<T>::cplx)
+            hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        else
+            hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.plan.splits == 1) return e;
     return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, 0, a.n, a.alpha, a.beta, a.y, a.incy, s);

@@ -16,6 +16,7 @@ struct Tuning {
     int64_t gemv_n_splits = 0;     // column splits of GEMV-N
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
     int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
+    int64_t gemv_short = 0;        // kernels for matrices of a few row tiles: 1 = never, 2 = whenever possible
     int64_t symv_panel_cols = 0;      // SYMV panel width: 16, 32, 64 or 128 columns
     int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave: 1 or 2
     int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
@@ -54,6 +55,7 @@ template <class T> struct GemvPlan {
     int64_t ntiles;       // row tiles of tile_rows<T>() rows covering [-shift, m)
     int64_t splits;       // N: column splits; T: row splits
     int64_t row_tiles;    // N: row tiles per wave
+    int short_form;       // kernels for matrices of a few row tiles (waves split columns instead of rows)
     int64_t part_stride;  // elements between consecutive partial vectors
     size_t xpack_off, partial_off, total_bytes;   // workspace layout
 };

@@ -665,7 +665,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     int64_t ktw = tuning().symv_tiles_per_wave;
     if (ktw <= 0) {
         if (p.variant == 1) ktw = sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE;
-        else ktw = n <= (sizeof(T) < 16 ? 16384 : 8192) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay up to there
+        else ktw = n < (sizeof(T) < 16 ? 16384 : 10000) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay below that
     }
     if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
     p.panel_cols = C;

@@ -322,3 +322,21 @@ def test_prepared_calls_match_plain_calls():
         call()                       # a prepared call can be repeated
         torch.cuda.synchronize()
         assert torch.equal(y, ref)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_gemv_short_matrix_kernels(prec):
+    """matrices of a few row tiles: the kernels in which waves split columns, forced on
+    (2) and off (1), with sub-block offsets that move the tile grid, against the oracle"""
+    k = kmv()
+    alpha, beta = scalars(prec, 0.7, 0.3)
+    try:
+        for mode in (1, 2):
+            k.set_tuning("gemv_short", mode)
+            for m, n, off, lda in ((100, 9000, 0, None), (200, 3000, 3, 256), (64, 70000, 0, 64), (500, 5000, 1, 512),
+                                   (1000, 4100, 17, 1024), (3, 1000, 0, None), (130, 37, 5, 144)):
+                for trans in "NTC":
+                    _, err, _ = gemv_case(prec, trans, m, n, alpha, beta, lda=lda, row_off=off, col_off=off, seed=31)
+                    check(prec, err, f"gemv_short={mode} {prec}gemv {trans} {m}x{n} off={off}")
+    finally:
+        k.set_tuning("gemv_short", 0)
