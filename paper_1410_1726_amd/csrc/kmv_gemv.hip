@@ -366,6 +366,7 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
 namespace {
 constexpr int GN_NW = 4;                // GEMV-N: waves per workgroup
 constexpr int GN_LOADS = 8;             // GEMV-N: 16-byte loads per lane and prefetch block (columns x tiles)
+constexpr int GN_WGS_PER_CU = 2;        // GEMV-N: workgroups per compute unit the column split aims at
 constexpr int GT_NC = 8, GT_NW = 4;     // GEMV-T: columns per workgroup, waves per workgroup
 constexpr int64_t MAX_SPLITS = 256;
 constexpr int64_t SHORT_T_TILES = 2;         // GEMV-T: up to this many row tiles every wave owns its columns
@@ -373,10 +374,13 @@ constexpr int64_t DEFAULT_WG_TARGET = 2048;   // about 8 workgroups per compute 
 constexpr int64_t DEFAULT_GN_ROW_TILES = 1;
 }  // namespace
 
-// Workgroups of gemv_n_kernel<T, ., ., rt> that the device keeps resident at
-// once (compute units x occupancy), queried once per instance.  A compute
-// unit's share of the HBM bandwidth is capped, so the kernel is fastest when
-// every compute unit holds the same number of equally long workgroups.
+// Workgroups of gemv_n_kernel<T, ., ., rt> that one round should hold: compute
+// units x min(occupancy, 2), queried once per instance.  A compute unit's share
+// of the HBM bandwidth is capped, so the kernel is fastest when every compute
+// unit holds the same number of equally long workgroups; measured with the split
+// counts alternating in one process, two workgroups (8 waves with 8-16 loads in
+// flight each) per compute unit beat the full occupancy of four by 1-12%, most
+// below n = 8192 where fewer, longer workgroups also mean fewer partial sums.
 template <class T> int64_t gemv_n_slots(int64_t rt) {
     static int64_t cache[5] = {0, 0, 0, 0, 0};
     if (rt < 1 || rt > 4) return 0;
@@ -389,7 +393,7 @@ template <class T> int64_t gemv_n_slots(int64_t rt) {
             else if (rt == 2) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gemv_n_kernel<T, GN_NW, GN_LOADS / 2, 2>, GN_NW * WAVE, 0);
             else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, gemv_n_kernel<T, GN_NW, GN_LOADS / 4, 4>, GN_NW * WAVE, 0);
         }
-        cache[rt] = (e == hipSuccess && cus > 0 && nb > 0) ? (int64_t)cus * nb : -1;
+        cache[rt] = (e == hipSuccess && cus > 0 && nb > 0) ? (int64_t)cus * (nb < GN_WGS_PER_CU ? nb : GN_WGS_PER_CU) : -1;
         (void)hipGetLastError();
     }
     return cache[rt];
