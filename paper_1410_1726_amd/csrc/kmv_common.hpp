@@ -142,6 +142,19 @@ template <> __device__ __forceinline__ cf64 load_elem_stream<cf64>(const cf64* p
     return cf64{__builtin_nontemporal_load(q), __builtin_nontemporal_load(q + 1)};
 }
 
+// element e of the result = element e + d of v (lanes of an edge tile whose
+// vector was loaded at a clamped position; elements that fall outside belong to
+// rows that do not exist or are not stored, and may hold anything)
+template <class T> __device__ __forceinline__ Vec<T> shift_elems(const Vec<T>& v, int d) {
+    constexpr int VEC = Traits<T>::VEC;
+    Vec<T> o = v;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) o.e[e] = select_of(e + d == k, v.e[k], o.e[e]);
+    return o;
+}
+
 // ---- wave64 sum: DPP inside each row of 16 lanes, then the four row sums are
 // read in lane order 0,16,32,48 and added left to right (a fixed order). The
 // result is wave-uniform.

@@ -29,19 +29,6 @@ namespace kmv {
 // Edge tiles (rows before the first or after the last row) run the same
 // pipeline with the lanes' load positions clamped into the column: the lanes
 // outside compute sums of rows that do not exist, which are dropped.
-// element e of the result = element e + d of v (lanes of an edge tile whose
-// vector was loaded at a clamped position; elements that fall outside belong to
-// rows that do not exist and may hold anything)
-template <class T> __device__ __forceinline__ Vec<T> shift_elems(const Vec<T>& v, int d) {
-    constexpr int VEC = Traits<T>::VEC;
-    Vec<T> o = v;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e)
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) o.e[e] = select_of(e + d == k, v.e[k], o.e[e]);
-    return o;
-}
-
 template <class T, int U, int RT, int NW, bool EDGE>
 __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t (&r)[RT], int64_t c0, int64_t cw,
                                             T (&acc)[RT][Traits<T>::VEC]) {
