@@ -36,10 +36,9 @@ HBM_PEAK_GBS = 8000.0
 # from the two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE, each scaled by the
 # reading of the library's copy kernel) summarised in profiles/sweep_hbm_traffic.txt
 MEASURED_TRAFFIC_SWEEP = {
-    "gemv_n_kernel<float>": 1412921845, "gemv_t_kernel<float>": 1409912374,
-    "gemv_n_kernel<double>": 2822567625, "gemv_t_kernel<double>": 2819287857,
-    "symv_kernel<double>": 1183122068, "symv_balanced_kernel<double>": 2196934422,
-    "symv_kernel<kmv::cf64>": 24696384, "symv_balanced_kernel<kmv::cf64>": 3214074971,
+    "gemv_n_kernel<float>": 1411605686, "gemv_t_kernel<float>": 1410082161,
+    "gemv_n_kernel<double>": 2821472987, "gemv_t_kernel<double>": 2819225620,
+    "symv_balanced_kernel<double>": 1507340043, "symv_balanced_kernel<kmv::cf64>": 3013031357,
 }
 
 
