@@ -110,3 +110,42 @@ def test_largest_shapes(prec):
             check(prec, err, f"symv/hemv {prec} {uplo} n={n} incx={incx}")
     del parent, host
     free()
+
+
+# ---- panels of the rectangular benchmark workload (tall-skinny, short-wide) ------
+@pytest.mark.parametrize("prec", "ds")
+def test_rectangular_panels(prec):
+    for m, n in ((65536, 512), (16384, 64), (128, 65536), (512, 65536), (4096, 16384)):
+        for trans in "NT":
+            leny = m if trans == "N" else n
+            _, err, _ = gemv_case(prec, trans, m, n, 1.0, 1.0, lda=m, seed=6, sample=samples(leny, 6),
+                                  poison_outside=False)
+            check(prec, err, f"{prec}gemv {trans} {m}x{n}")
+        free()
+
+
+# ---- the chain kernel (chosen only for large matrices with drifting column alignment
+# by default) at a large size, forced through the tuning key, and the size that selects it
+def test_symv_chain_kernel_large():
+    from paper_1410_1726_amd import binding as k
+    n = 24576
+    host = None
+    try:
+        k.set_tuning("symv_variant", 1)
+        for uplo in "LU":
+            parent = wl.matrix("d", n, n, n, seed=7, device=DEV)
+            _, err, ex = symv_case("d", uplo, n, 1.0, 0.0, lda=n, seed=7, parent=parent, parent_host=host,
+                                   sample=samples(n, 7))
+            host = ex["parent_host"]
+            check("d", err, f"dsymv {uplo} n={n} chain kernel")
+            del parent
+            free()
+    finally:
+        k.set_tuning("symv_variant", 0)
+    del host
+    n = 17001   # lda = n: columns not 16-byte aligned, the default picks the chain kernel
+    assert k.symv_kernel_variant("d", "L", n, 256, n) == 1
+    for uplo in "LU":
+        _, err, _ = symv_case("d", uplo, n, 1.0, 0.0, lda=n, seed=8, sample=samples(n, 8))
+        check("d", err, f"dsymv {uplo} n={n}")
+        free()

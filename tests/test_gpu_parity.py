@@ -340,3 +340,27 @@ def test_gemv_short_matrix_kernels(prec):
                     check(prec, err, f"gemv_short={mode} {prec}gemv {trans} {m}x{n} off={off}")
     finally:
         k.set_tuning("gemv_short", 0)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_random_shapes_against_oracle(prec):
+    """seeded random shapes, leading dimensions, offsets, increments and scalars for every
+    routine: whatever combination of kernels and edge cases they hit must match the oracle"""
+    rng = np.random.default_rng({"s": 11, "d": 12, "c": 13, "z": 14}[prec])
+    incs = (1, 1, 1, 2, -1, 3, -2)
+    for case in range(24):
+        m = int(rng.choice([1, 7, 64, 300, 1000, 2500]) + rng.integers(0, 130))
+        n = int(rng.choice([1, 5, 96, 500, 1500, 3000]) + rng.integers(0, 130))
+        off = int(rng.choice([0, 0, 1, 3, 16, 33]))
+        pad = int(rng.choice([0, 1, 7, 32]))
+        alpha, beta = scalars(prec, float(rng.choice([1.0, -0.5, 0.7])), float(rng.choice([0.0, 1.0, 0.3])))
+        incx, incy = int(rng.choice(incs)), int(rng.choice(incs))
+        trans = "NTC"[case % 3]
+        _, err, _ = gemv_case(prec, trans, m, n, alpha, beta, lda=m + off + pad, row_off=off, col_off=off, incx=incx,
+                              incy=incy, seed=100 + case)
+        check(prec, err, f"case {case}: {prec}gemv {trans} {m}x{n} off={off} pad={pad} inc={incx},{incy}")
+        uplo = "LU"[case % 2]
+        beta_s = beta if case % 4 else 0.0
+        _, err, _ = symv_case(prec, uplo, n, alpha, beta_s, lda=n + off + pad, off=off, incx=incx, incy=incy,
+                              seed=200 + case, nan_imag_diag=True)
+        check(prec, err, f"case {case}: symv/hemv {prec} {uplo} n={n} off={off} pad={pad} inc={incx},{incy}")
