@@ -1,0 +1,95 @@
+"""Tuning sweeps: time one routine under several settings of the library's tuning
+keys, with the settings ALTERNATING inside one process.
+
+The paper keeps tuning parameters apart from the kernel templates and sweeps them
+coarse to fine (Section 9).  Here the template instances are compiled in and the
+keys of kmv_set_tuning pick among them at run time, so a sweep is a loop over
+settings.  Alternating matters on this hardware: the device slows by a few per cent
+over a minute-long run, so two back-to-back series are not comparable, while
+interleaved rounds are (the defaults in the planners were chosen this way).
+
+  python -m paper_1410_1726_amd.tune dsymv_L 16384 symv_unit_tiles=1,2 wg_target=512,768
+  python -m paper_1410_1726_amd.tune sgemv_N 8192x65536 gemv_n_splits=0,32,64,128
+
+A value 0 means "let the library choose".  Prints the median time of every
+combination (microseconds, GB/s of algorithmic bytes) and marks the fastest.
+"""
+from __future__ import annotations
+
+import itertools
+import statistics
+import sys
+
+import torch
+
+from . import accounting as acc
+from . import binding as k
+from . import workloads as wl
+
+
+def _time(call, reps, warm=2):
+    for _ in range(warm):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e3
+
+
+def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int = 10):
+    """routine like 'dgemv_T', 'zhemv_U', 'ssymv_L'; grid: {key: [values]}.  Returns
+    [(settings dict, median microseconds)], in grid order."""
+    prec, name, mode = routine[0], routine[1:5], routine[-1]
+    sym = name in ("symv", "hemv")
+    A = wl.matrix(prec, m, n, m, device="cuda")
+    lenx, leny = (n, n) if sym else ((n, m) if mode == "N" else (m, n))
+    x = wl.vector(prec, lenx, device="cuda")
+    y = wl.vector(prec, leny, which=2, device="cuda")
+    keys = list(grid)
+    combos = [dict(zip(keys, vals)) for vals in itertools.product(*(grid[key] for key in keys))] or [{}]
+    times = [[] for _ in combos]
+    saved = {key: k.get_tuning(key) for key in k.tuning_keys()}
+    try:
+        for _ in range(rounds):
+            for i, combo in enumerate(combos):
+                for key in k.tuning_keys():
+                    k.set_tuning(key, 0)
+                for key, v in combo.items():
+                    k.set_tuning(key, v)
+                # the plan (kernel, splits, workspace layout) is fixed when the call is prepared
+                call = (k.prepare_symv(prec, mode, n, 1.0, A, m, x, 1, 0.0, y, 1) if sym
+                        else k.prepare_gemv(prec, mode, m, n, 1.0, A, m, x, 1, 1.0, y, 1))
+                times[i].append(_time(call, reps))
+    finally:
+        for key, v in saved.items():
+            k.set_tuning(key, v)
+    return [(combo, statistics.median(t)) for combo, t in zip(combos, times)]
+
+
+def main(argv):
+    if len(argv) < 2:
+        print(__doc__)
+        return 2
+    routine, shape = argv[0], argv[1]
+    m, n = (int(v) for v in shape.split("x")) if "x" in shape else (int(shape), int(shape))
+    grid = {}
+    for spec in argv[2:]:
+        key, vals = spec.split("=")
+        grid[key] = [int(v) for v in vals.split(",")]
+    res = sweep(routine, m, n, grid)
+    op = {"gemv": "gemv_" + routine[-1].lower(), "symv": "symv_l", "hemv": "hemv_l"}[routine[1:5]]
+    nbytes = acc.algorithmic_bytes(op, routine[0], m, n)
+    best = min(us for _, us in res)
+    print(f"{routine} {m}x{n} on {torch.cuda.get_device_name(0)}")
+    for combo, us in res:
+        text = " ".join(f"{key}={v}" for key, v in combo.items()) or "(defaults)"
+        print(f"  {text:50s} {us:10.1f} us {nbytes / us / 1e3:9.1f} GB/s{'  <- fastest' if us == best else ''}")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))

@@ -136,3 +136,8 @@ def test_symv_kernel_variant_query():
             assert kmv.symv_kernel_variant("s", "L", 5000, DUMMY, 5000) == v
     finally:
         kmv.set_tuning("symv_variant", 0)
+
+
+def test_tuning_sweep_tool_is_importable():
+    from paper_1410_1726_amd import tune
+    assert tune.main([]) == 2          # prints its usage, touches no device
