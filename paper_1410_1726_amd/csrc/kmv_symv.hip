@@ -606,10 +606,12 @@ namespace {
 constexpr int BAL_NC = 4;   // balanced kernel: columns per wave
 // Row tiles per unit (KT) and workgroups per compute unit that go with it, measured
 // with the settings alternating in one process: two tiles (8 loads per lane and
-// buffer) with two workgroups per compute unit for 8- and 16-byte elements from
-// n = 16384 on (1-3% faster there, 3-5% slower at n = 8192), otherwise one tile
-// (4 loads) with three workgroups per compute unit.
-template <class T> inline int default_unit_tiles(int64_t n) { return (sizeof(T) >= 8 && n >= 16384) ? 2 : 1; }
+// buffer) with two workgroups per compute unit for 16-byte elements from n = 16384
+// and 8-byte elements from n = 28672 on (1-3% faster there, 3-5% slower at
+// n = 8192), otherwise one tile (4 loads) with three workgroups per compute unit.
+template <class T> inline int default_unit_tiles(int64_t n) {
+    return (sizeof(T) == 16 && n >= 16384) || (sizeof(T) == 8 && n >= 28672) ? 2 : 1;
+}
 inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }
 constexpr int64_t MAX_WORKERS = 2048;
 // compute units x min(occupancy, wanted workgroups per compute unit), queried once per instance
