@@ -126,7 +126,7 @@ def kernel_name(p):
     esize = {"s": 4, "d": 8, "c": 8, "z": 16}[p["prec"]]
     # only the alignment of A matters to the choice: the bench buffers are 256-byte aligned
     variant = k.symv_kernel_variant(p["prec"], p["mode"], p["n"], 256 + (p.get("off", 0) * (p["lda"] + 1)) * esize, p["lda"])
-    return f"{'symv_balanced_kernel' if variant == 2 else 'symv_kernel'}<{t}>"
+    return f"{ {1: 'symv_kernel', 2: 'symv_balanced_kernel', 3: 'symv_small_kernel'}[variant] }<{t}>"
 
 
 class Inputs:

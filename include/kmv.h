@@ -151,7 +151,7 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *   gemv_n_row_tiles              row tiles per wave of GEMV-N (1, 2, 4)
  *   gemv_short                    kernels for matrices of a few row tiles:
  *                                 1 = never, 2 = whenever they apply
- *   symv_variant                  SYMV/HEMV main kernel, see below (1, 2)
+ *   symv_variant                  SYMV/HEMV main kernel, see below (1, 2, 3)
  *   symv_panel_cols               panel width of variant 1 (16, 32, 64, 128)
  *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)
  *   symv_classes                  variant 1: chains per row chunk (1..256)
@@ -165,7 +165,9 @@ const char* kmv_tuning_keys(void);
 /* Which main kernel a kmv_<prec>symv / hemv call with these arguments would
  * launch under the current tuning values: 1 = chains of column panels per row
  * chunk, 2 = balanced shares of (row chunk, panel) pieces (the balanced
- * partition of Section 6.2 applied to the stored triangle).  Only the address
+ * partition of Section 6.2 applied to the stored triangle), 3 = the
+ * single-launch kernel for small matrices (no workspace traffic, every stored
+ * element read twice).  Only the address
  * of A is used (its alignment decides), nothing is read or launched.  Returns
  * 0 for an unknown prec or uplo, n < 0 or lda < max(1, n).  For benchmarks
  * and profiles that have to name the kernel they time. */

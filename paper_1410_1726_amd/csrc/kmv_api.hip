@@ -125,7 +125,7 @@ const Key KEYS[] = {
     {"symv_panel_cols", &Tuning::symv_panel_cols, 0, 128},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
     {"symv_classes", &Tuning::symv_classes, 0, 256},
-    {"symv_variant", &Tuning::symv_variant, 0, 2},
+    {"symv_variant", &Tuning::symv_variant, 0, 3},
     {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
 };

@@ -550,6 +550,138 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
     }
 }
 
+// Small matrices, one launch: a workgroup owns NC consecutive outputs y_j
+// (j0 <= j < j0+NC) and forms the whole rows j of the symmetric matrix from the
+// stored triangle: the part of row j that is stored as column j (a dot product
+// down the column, conjugated for HEMV), the part that is stored as row j (NC
+// consecutive elements of every column on the other side of the diagonal block,
+// one column per lane) and the NC x NC diagonal block (one stored pair per lane,
+// used for both of its outputs).  Every stored element is read twice, which is
+// affordable while the triangle stays in cache, and there is no workspace and
+// no second kernel: below a few thousand rows the two launches of the kernels
+// above cost more than the traffic.
+template <class T, bool HERM, bool LOWER, int NC, int NW>
+__global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int TR = WAVE * VEC;
+    static_assert(NC * NC == WAVE && NC % VEC == 0, "one lane per pair of the diagonal block");
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int64_t n = a.n, lda = a.lda;
+    const int shift = a.plan.shift;
+    const int64_t j0 = (int64_t)blockIdx.x * NC;
+    const int64_t jend = j0 + NC < n ? j0 + NC : n;   // one past the last existing output
+    const T* __restrict__ x = a.x;
+    const T* __restrict__ A = a.A;
+    T acc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[c] = zero_of<T>();
+
+    // ---- stored as columns: rows below (lower) / above (upper) the diagonal block
+    {
+        const int64_t rlo = LOWER ? jend : 0, rhi = LOWER ? n : j0;   // rows [rlo, rhi)
+        const T* __restrict__ col[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) col[c] = A + (j0 + c < n ? j0 + c : n - 1) * lda;
+        if (rhi > rlo) {
+            const int64_t tlo = (rlo + shift) / TR, thi = (rhi - 1 + shift) / TR + 1;
+            for (int64_t t = tlo + w; t < thi; t += NW) {
+                const int64_t r0 = t * TR - shift, r = r0 + (int64_t)lane * VEC;
+                if (r0 >= rlo && r0 + TR <= rhi) {
+                    const Vec<T> xv = load_cached(x + r);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const Vec<T> v = load_cached(col[c] + r);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) fma_op<HERM>(acc[c], v.e[e], xv.e[e]);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const int64_t row = r + e;
+                        const bool ok = row >= rlo && row < rhi;
+                        const int64_t rc = ok ? row : rlo;   // rlo is a stored row of every column of the group
+                        const T xi = x[rc];
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) {
+                            T nt = acc[c];
+                            fma_op<HERM>(nt, col[c][rc], xi);
+                            acc[c] = select_of(ok, nt, acc[c]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    // ---- stored as rows: columns left (lower) / right (upper) of the diagonal block,
+    // one column per lane, NC consecutive rows of it
+    {
+        const int64_t ilo = LOWER ? 0 : jend, ihi = LOWER ? j0 : n;
+        const bool whole = (j0 + NC <= n);   // all NC rows exist: 16-byte loads
+        for (int64_t ib = ilo + (int64_t)w * WAVE; ib < ihi; ib += NW * WAVE) {
+            const int64_t i = ib + lane;
+            const bool ok = i < ihi;
+            const int64_t ic = ok ? i : ihi - 1;
+            const T xi = x[ic];
+            const T* __restrict__ seg = A + j0 + ic * lda;
+            if (whole) {
+#pragma unroll
+                for (int cv = 0; cv < NC / VEC; ++cv) {
+                    const Vec<T> v = load_cached(seg + cv * VEC);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        T nt = acc[cv * VEC + e];
+                        fma_acc(nt, v.e[e], xi);
+                        acc[cv * VEC + e] = select_of(ok, nt, acc[cv * VEC + e]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const bool rok = j0 + c < n;
+                    T nt = acc[c];
+                    fma_acc(nt, seg[rok ? c : 0], xi);
+                    acc[c] = select_of(rok && ok, nt, acc[c]);
+                }
+            }
+        }
+    }
+    // ---- diagonal block: lane (r, c) holds the pair (j0+r, j0+c) if it is stored
+    if (w == 0) {
+        const int r = lane / NC, c = lane % NC;
+        const int64_t row = j0 + r, colj = j0 + c;
+        const bool stored = row < n && colj < n && (LOWER ? r >= c : r <= c);
+        const T av = A[(stored ? row : j0) + (stored ? colj : j0) * lda];   // (j0, j0) is always stored
+        const T xr = x[stored ? row : j0], xc = x[stored ? colj : j0];
+        // a(row, col) * x_col goes to output row; off the diagonal its mirror image
+        // op(a) * x_row goes to output col
+        T to_row = zero_of<T>(), to_col = zero_of<T>();
+        fma_acc(to_row, select_of(HERM && r == c, real_part_only(av), av), xc);
+        fma_op<HERM>(to_col, av, xr);
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            acc[k] = select_of(stored && r == k, add_of(acc[k], to_row), acc[k]);
+            acc[k] = select_of(stored && c == k && r != c, add_of(acc[k], to_col), acc[k]);
+        }
+    }
+
+    __shared__ T red[NW][NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const T sum = wave_sum(acc[c]);
+        if (lane == 0) red[w][c] = sum;
+    }
+    __syncthreads();
+    if (threadIdx.x < NC && j0 + threadIdx.x < n) {
+        const int c = threadIdx.x;
+        T sum = red[0][c];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) sum = add_of(sum, red[ww][c]);
+        T* yp = a.y + (j0 + c) * a.incy;
+        *yp = epilogue(a.alpha, sum, a.beta, yp);
+    }
+}
+
 // y_i = alpha * ( sum over classes of wsn[class][i] + sum over chunks of
 // wst[panel(i)][chunk][i] ) + beta*y_i.  blockDim = (RED_ROWS, RED_PARTS): part g
 // adds the classes g, g+RED_PARTS, ... and then the chunks kbeg+g, kbeg+g+
@@ -604,6 +736,8 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 // ------------------------------------------------------------- host side ----
 namespace {
 constexpr int BAL_NC = 4;   // balanced kernel: columns per wave
+constexpr int SMALL_NC = 8;            // small-matrix kernel: outputs per workgroup
+constexpr int64_t SMALL_N = 1536;      // largest n the small-matrix kernel is chosen for
 // Row tiles per unit (KT) and workgroups per compute unit that go with it, measured
 // with the settings alternating in one process: two tiles (8 loads per lane and
 // buffer) with two workgroups per compute unit for 16-byte elements from n = 16384
@@ -658,9 +792,9 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.variant = (int)tuning().symv_variant;
     if (p.variant <= 0) {
         const bool drifting = n >= 12000 && ((uint64_t)lda * sizeof(T)) % 16 != 0;
-        p.variant = drifting ? 1 : 2;
+        p.variant = n <= SMALL_N ? 3 : (drifting ? 1 : 2);
     }
-    if (n > (int64_t)1 << 30) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
+    if (n > (int64_t)1 << 30 && p.variant == 2) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
     if (p.variant == 2) C = BAL_NC * SY_NW;
     // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
@@ -781,6 +915,12 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
 
 template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s) {
     constexpr bool HERM = Traits<T>::cplx;
+    if (a.plan.variant == 3) {   // one launch, no workspace
+        const dim3 grid((unsigned)ceil_div(a.n, SMALL_NC));
+        if (lower) hipLaunchKernelGGL((symv_small_kernel<T, HERM, true, SMALL_NC, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
+        else hipLaunchKernelGGL((symv_small_kernel<T, HERM, false, SMALL_NC, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
+        return hipGetLastError();
+    }
     const bool ok = lower ? dispatch_main<T, HERM, true>(a, s) : dispatch_main<T, HERM, false>(a, s);
     if (!ok) return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();

@@ -130,8 +130,9 @@ def test_symv_kernel_variant_query():
     for prec in "sdcz":
         for uplo in "LU":
             assert kmv.symv_kernel_variant(prec, uplo, 5000, DUMMY, 5000) in (1, 2)
+            assert kmv.symv_kernel_variant(prec, uplo, 500, DUMMY, 500) == 3
     try:
-        for v in (1, 2):
+        for v in (1, 2, 3):
             kmv.set_tuning("symv_variant", v)
             assert kmv.symv_kernel_variant("s", "L", 5000, DUMMY, 5000) == v
     finally:

@@ -248,10 +248,10 @@ def test_split_variants_agree_with_oracle():
             k.set_tuning(key, 0)
 
 
-@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("prec", list("sdcz"))
 def test_symv_main_kernel_variants(prec, variant):
-    """both SYMV/HEMV main kernels (chains of panels; balanced shares of pieces), forced
+    """the SYMV/HEMV main kernels (chains of panels; balanced shares of pieces; one launch for small matrices), forced
     through the tuning key, over ragged sizes, sub-block offsets, chunk heights and
     workgroup counts that make one share span several row chunks"""
     k = kmv()
@@ -364,3 +364,37 @@ def test_random_shapes_against_oracle(prec):
         _, err, _ = symv_case(prec, uplo, n, alpha, beta_s, lda=n + off + pad, off=off, incx=incx, incy=incy,
                               seed=200 + case, nan_imag_diag=True)
         check(prec, err, f"case {case}: symv/hemv {prec} {uplo} n={n} off={off} pad={pad} inc={incx},{incy}")
+
+
+def test_calls_can_be_captured_in_a_graph():
+    """the entry points only enqueue kernels (no allocation, no memset, no host
+    synchronisation), so a sequence of calls can be recorded once and replayed;
+    every replay, with new vector contents and eager work in between, must give
+    the bits of the eager calls"""
+    k = kmv()
+    n = 1800
+    A = wl.matrix("d", n, n, seed=41, device=DEV)
+    x = wl.vector("d", n, seed=41, device=DEV)
+    y1, y2, y3 = (torch.zeros(n, dtype=torch.float64, device=DEV) for _ in range(3))
+    ws = torch.empty(max(k.gemv_workspace_bytes("d", "N", n, n), k.symv_workspace_bytes("d", "L", n)),
+                     dtype=torch.uint8, device=DEV)
+
+    def run():
+        k.dgemv("N", n, n, 0.7, A, n, x, 1, 0.0, y1, 1, workspace=ws)
+        k.dgemv("T", n, n, 1.0, A, n, y1, 1, 0.0, y2, 1, workspace=ws)
+        k.dsymv("L", n, -0.5, A, n, y2, 1, 0.0, y3, 1, workspace=ws)
+
+    run()                                   # warm up outside the capture (occupancy queries, module load)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for rep in range(4):
+        x.copy_(wl.vector("d", n, seed=50 + rep, device=DEV))
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (y1, y2, y3)]
+        run()
+        torch.cuda.synchronize()
+        for a_, b_ in zip(got, (y1, y2, y3)):
+            assert torch.equal(a_, b_), f"replay {rep} differs from the eager calls"
