@@ -11,11 +11,16 @@
 // to a separate kernel that mirrors them in shared memory (Section 6.5).
 //
 // Kept: the dual use of each element, the register double buffer, blocks of
-// the stored triangle as the unit of work.  Different, to fit wave64 and what
-// was measured on the MI355X (small writes scattered through a read stream
-// cost far more than their bytes; a workgroup that reads a few columns over
-// several KiB of consecutive rows streams at full speed; each of the 8 XCDs
-// has its own L2):
+// the stored triangle as the unit of work.  Three main kernels follow, each
+// with its own description: symv_kernel (chains of panels per row chunk, the
+// first design, still chosen for large matrices whose columns are not 16-byte
+// aligned), symv_balanced_kernel (equal shares of the triangle's pieces for one
+// resident round of workgroups, the default) and symv_small_kernel (one launch,
+// no workspace, for small matrices).  What the first one does differently from
+// the paper, to fit wave64 and what was measured on the MI355X (small writes
+// scattered through a read stream cost far more than their bytes; a workgroup
+// that reads a few columns over several KiB of consecutive rows streams at full
+// speed; each of the 8 XCDs has its own L2):
 //  * lanes map to 16-byte row vectors, a wave streams 1 KiB of a column per
 //    instruction;
 //  * a workgroup owns a chunk of NW*KTW row tiles and walks HORIZONTALLY over
