@@ -19,8 +19,10 @@
  *                        the work enqueued on `stream` has completed.
  *   alpha, beta        : HOST pointers, read before the call returns.
  *   stream             : a hipStream_t passed as void* (NULL = null stream).
- *   Calls only enqueue kernels: no allocation, no host synchronisation, no
- *   hidden global state.  A and x must not overlap y or the workspace.
+ *   Calls only enqueue kernels: no allocation, no memset, no host
+ *   synchronisation, no hidden global state, so a sequence of calls can be
+ *   recorded into a HIP graph and replayed.  A and x must not overlap y or
+ *   the workspace.
  *   Concurrent calls must use distinct workspaces.
  *
  * Layout (Section 5.3, single-GPU routines)

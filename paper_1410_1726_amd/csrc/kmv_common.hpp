@@ -14,7 +14,6 @@ struct cf32 { float re, im; };
 struct cf64 { double re, im; };
 
 constexpr int WAVE = 64;
-constexpr int XCDS = 8;   // accelerator dies; consecutive workgroup ids go to consecutive XCDs
 
 template <class T> struct Traits;
 template <> struct Traits<float>  { typedef float real;  static constexpr int VEC = 4; static constexpr bool cplx = false; };
