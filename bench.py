@@ -173,6 +173,32 @@ def make_call(p, k, A, x, y):
     return k.prepare_symv(p["prec"], p["mode"], n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
 
 
+def tiny_latency(k, torch, wl):
+    """DGEMV N 1024 x 1024: microseconds per call with the matrix resident in cache (the
+    same buffers every call) and cold (96 distinct matrices in rotation, 768 MiB, more
+    than the last-level cache), both as a back-to-back series between two events."""
+    n, copies = 1024, 96
+    As = [wl.matrix("d", n, n, n, seed=s, device="cuda") for s in range(copies)]
+    x = wl.vector("d", n, seed=0, which=1, device="cuda")
+    y = wl.vector("d", n, seed=0, which=2, device="cuda")
+    calls = [k.prepare_gemv("d", "N", n, n, 1.5, A, n, x, 1, 0.5, y, 1) for A in As]
+
+    def series(seq, reps):
+        for c in seq[:4]:
+            c()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            for c in seq:
+                c()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * len(seq))
+
+    return {"warm": round(series(calls[:1] * copies, 5), 2), "cold": round(series(calls, 5), 2)}
+
+
 # ------------------------------------------------------------ CPU baseline ----
 def cpu_baseline(acc, wl):
     """The oracle as it stands (working-precision mode, OpenMP over outputs) on a
@@ -343,6 +369,8 @@ def main():
         "frac_of_stream_read": round(value / probe["read_gbs"], 4),
         "roofline": roofline,
     }
+    if args.workload == "tiny":
+        out["latency_us"] = tiny_latency(k, torch, wl)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(acc, wl)
     print(json.dumps(out))
