@@ -304,7 +304,9 @@ def main():
     wall = time.perf_counter() - t0
     for step in range(args.steps):
         for rec, (e0, e1) in zip(per, events[step]):
-            rec["ms"] += e0.elapsed_time(e1) / args.steps
+            t = e0.elapsed_time(e1)
+            rec["ms"] += t / args.steps
+            rec.setdefault("all_ms", []).append(t)
 
     step_ms = wall / args.steps * 1e3          # wall clock between the two synchronisations
     device_ms = sum(r["ms"] for r in per)       # sum of the per-product event brackets
@@ -343,7 +345,10 @@ def main():
             for p, r in zip(prods, per):
                 gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9
                 f.write(json.dumps({"routine": routine_name(p), "m": p.get("m", p["n"]), "n": p["n"], "lda": p["lda"], "off": p.get("off", 0),
-                                    "incx": p.get("incx", 1), "us": round(r["ms"] * 1e3, 2), "gbs": round(gbs, 1),
+                                    "incx": p.get("incx", 1), "us": round(r["ms"] * 1e3, 2),
+                                    "us_min": round(min(r["all_ms"]) * 1e3, 2),
+                                    "us_median": round(sorted(r["all_ms"])[len(r["all_ms"]) // 2] * 1e3, 2),
+                                    "gbs": round(gbs, 1),
                                     "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
                                     "gflops": round(r["flops"] / (r["ms"] * 1e-3) / 1e9, 1)}) + "\n")
 
