@@ -398,3 +398,27 @@ def test_calls_can_be_captured_in_a_graph():
         torch.cuda.synchronize()
         for a_, b_ in zip(got, (y1, y2, y3)):
             assert torch.equal(a_, b_), f"replay {rep} differs from the eager calls"
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_shrinking_trailing_blocks(prec):
+    """the trailing blocks A[o:, o:] of one parent for consecutive offsets o, as the panel
+    loop of a blocked reduction visits them: every misalignment of the block's first column
+    (0..127 bytes), with the rest of the parent set to NaN, for GEMV N/T and SYMV/HEMV L/U"""
+    alpha, beta = scalars(prec, -1.0, 1.0)
+    N, lda = 900, 1024           # lda*sizeof(T) is a multiple of 128: one shift for all columns
+    per_line = 128 // {"s": 4, "d": 8, "c": 8, "z": 16}[prec]
+    offsets = list(range(0, per_line + 2)) + [per_line * 3 + 1, 333]
+    for o in offsets:
+        n = N - o
+        for trans in "NT":
+            _, err, _ = gemv_case(prec, trans, n, n - 7, alpha, beta, lda=lda, row_off=o, col_off=o, seed=70 + o % 5)
+            check(prec, err, f"{prec}gemv {trans} trailing block at {o}")
+        for variant in (0, 2):       # default (the small-matrix kernel at this size) and the balanced kernel
+            kmv().set_tuning("symv_variant", variant)
+            try:
+                for uplo in "LU":
+                    _, err, _ = symv_case(prec, uplo, n, alpha, beta, lda=lda, off=o, seed=80 + o % 5)
+                    check(prec, err, f"symv/hemv {prec} {uplo} trailing block at {o}, variant {variant}")
+            finally:
+                kmv().set_tuning("symv_variant", 0)
