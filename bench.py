@@ -205,7 +205,7 @@ def cpu_baseline(acc, wl):
     bounded sample of the sweep: one product per routine family at one size."""
     import oracle
 
-    n = 16384
+    n, reps = 16384, 8      # about ten seconds of CPU work on 16 cores
     sample = [("gemv", "s", "N"), ("gemv", "s", "T"), ("gemv", "d", "N"), ("gemv", "d", "T"),
               ("symv", "d", "L"), ("symv", "d", "U"), ("symv", "z", "L"), ("symv", "z", "U")]
     tot_b, tot_t = 0, 0.0
@@ -215,17 +215,18 @@ def cpu_baseline(acc, wl):
         x = wl.vector(prec, n, seed=0, which=1).numpy()
         y = wl.vector(prec, n, seed=0, which=2).numpy()
         t0 = time.perf_counter()
-        if kind == "gemv":
-            oracle.gemv(prec, mode, n, n, 1.0, A, x, 1.0, y, lda=n, mode=oracle.MODE_W)
-            op = "gemv_" + mode.lower()
-        else:
-            oracle.symv(prec, mode, n, 1.0, A, x, 0.0, y, lda=n, mode=oracle.MODE_W)
-            op = "symv_" + mode.lower()
+        for _ in range(reps):
+            if kind == "gemv":
+                oracle.gemv(prec, mode, n, n, 1.0, A, x, 1.0, y, lda=n, mode=oracle.MODE_W)
+                op = "gemv_" + mode.lower()
+            else:
+                oracle.symv(prec, mode, n, 1.0, A, x, 0.0, y, lda=n, mode=oracle.MODE_W)
+                op = "symv_" + mode.lower()
         tot_t += time.perf_counter() - t0
-        tot_b += acc.algorithmic_bytes(op, prec, n, n)
+        tot_b += reps * acc.algorithmic_bytes(op, prec, n, n)
         del A
     return {"value": round(tot_b / tot_t / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"sgemv/dgemv N,T + dsymv/zhemv L,U at n={n}, working-precision oracle, one run each",
+            "sample": f"sgemv/dgemv N,T + dsymv/zhemv L,U at n={n}, working-precision oracle, {reps} runs each",
             "seconds": round(tot_t, 2)}
 
 
