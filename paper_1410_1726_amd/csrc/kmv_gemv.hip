@@ -369,8 +369,10 @@ constexpr int64_t DEFAULT_GN_ROW_TILES = 1;
 // flight each) per compute unit beat the full occupancy of four by 1-12%, most
 // below n = 8192 where fewer, longer workgroups also mean fewer partial sums.
 template <class T> int64_t gemv_n_slots(int64_t rt) {
-    static int64_t cache[5] = {0, 0, 0, 0, 0};
-    if (rt < 1 || rt > 4) return 0;
+    static int64_t caches[MAX_CACHED_DEVICES][5] = {};
+    const int di = cached_device_index();
+    if (rt < 1 || rt > 4 || di < 0) return 0;
+    int64_t(&cache)[5] = caches[di];
     if (cache[rt] == 0) {
         int dev = 0, cus = 0, nb = 0;
         hipError_t e = hipGetDevice(&dev);

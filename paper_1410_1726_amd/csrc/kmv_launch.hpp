@@ -26,6 +26,19 @@ struct Tuning {
 };
 Tuning& tuning();
 
+// Index of the current device for the per-device caches of the planners
+// (occupancy and compute-unit counts differ between devices), -1 if it cannot
+// be found or lies beyond the cached range: the planners then use defaults.
+constexpr int MAX_CACHED_DEVICES = 64;
+inline int cached_device_index() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    return (dev >= 0 && dev < MAX_CACHED_DEVICES) ? dev : -1;
+}
+
 constexpr int64_t WS_ALIGN = 256;
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Distance (in elements) between consecutive partial vectors of `elems` elements:

@@ -767,9 +767,10 @@ template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     return (int64_t)cus * (nb < wgs_per_cu(KT) ? nb : wgs_per_cu(KT));
 }
 template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
-    static int64_t cache[2][3][3] = {};
-    if (ktw < 1 || ktw > 2 || kt < 1 || kt > 2) return -1;
-    int64_t& c = cache[lower ? 1 : 0][ktw][kt];
+    static int64_t cache[MAX_CACHED_DEVICES][2][3][3] = {};
+    const int di = cached_device_index();
+    if (ktw < 1 || ktw > 2 || kt < 1 || kt > 2 || di < 0) return -1;
+    int64_t& c = cache[di][lower ? 1 : 0][ktw][kt];
     if (c == 0) {
         if (lower) {
             if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, true, 1, SY_NW>() : balanced_slots_of<T, true, 1, 2 * SY_NW>();
