@@ -59,6 +59,8 @@ def _load():
         lib.mvo_gemv.restype = ci
         lib.mvo_symv.argtypes = [ch, ci, ch, i64, vp, vp, i64, vp, i64, vp, vp, i64, vp, vp, i64]
         lib.mvo_symv.restype = ci
+        lib.mvo_symv_complex_symmetric.argtypes = lib.mvo_symv.argtypes
+        lib.mvo_symv_complex_symmetric.restype = ci
         lib.mvo_num_threads.restype = ci
         lib.mvo_set_num_threads.argtypes = [ci]
         _lib = lib
@@ -140,9 +142,16 @@ def gemv(prec, trans, m, n, alpha, A, x, beta, y, *, lda=None, incx=1, incy=1,
 
 
 def symv(prec, uplo, n, alpha, A, x, beta, y, *, lda=None, incx=1, incy=1,
-         mode=MODE_X, sample=None):
-    """SYMV (prec s,d) or HEMV (prec c,z) reading only the ``uplo`` triangle."""
+         mode=MODE_X, sample=None, complex_symmetric=False):
+    """SYMV (prec s,d) or HEMV (prec c,z) reading only the ``uplo`` triangle.
+
+    ``complex_symmetric=True`` (prec c,z only) gives the complex symmetric
+    product instead of the Hermitian one: no conjugation, diagonal as stored.
+    """
     lib = _load()
+    if complex_symmetric and prec not in "cz":
+        raise ValueError("complex_symmetric needs prec 'c' or 'z'")
+    fn = lib.mvo_symv_complex_symmetric if complex_symmetric else lib.mvo_symv
     dt = DTYPES[prec]
     A, lda = _prep(prec, A, lda, n, n)
     x = np.ascontiguousarray(x, dtype=dt)
@@ -156,11 +165,16 @@ def symv(prec, uplo, n, alpha, A, x, beta, y, *, lda=None, incx=1, incy=1,
         sp, ns = _ptr(sample), sample.size
     else:
         sp, ns = None, 0
-    rc = lib.mvo_symv(prec.encode(), mode, uplo.upper().encode(), n, _ptr(al), _ptr(A), lda,
-                      _ptr(x), incx, _ptr(be), _ptr(y), incy, _ptr(out), sp, ns)
+    rc = fn(prec.encode(), mode, uplo.upper().encode(), n, _ptr(al), _ptr(A), lda,
+            _ptr(x), incx, _ptr(be), _ptr(y), incy, _ptr(out), sp, ns)
     if rc != 0:
         raise RuntimeError(f"mvo_symv failed: {rc}")
     return out
 
 
 hemv = symv
+
+
+def csymv(prec, uplo, n, alpha, A, x, beta, y, **kw):
+    """Complex symmetric SYMV (prec c,z)."""
+    return symv(prec, uplo, n, alpha, A, x, beta, y, complex_symmetric=True, **kw)

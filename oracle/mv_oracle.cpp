@@ -16,6 +16,10 @@
 //              (i,j) lies in the stored triangle, a_ji otherwise
 //   HEMV    :  same with s_ij = conj(a_ji) outside the stored triangle and
 //              s_ii = Re(a_ii)
+//   The paper's routine table lists SYMV for s,d and HEMV for c,z; the
+//   complex *symmetric* product (no conjugation anywhere, the diagonal taken
+//   as stored) is the same definition with the s,d rule applied to c,z and is
+//   offered through mvo_symv_complex_symmetric.
 //
 // A is column major with leading dimension lda (Section 5.3, single-GPU
 // layout): a_ij = A[i + j*lda].  Vectors follow the reference-BLAS increment
@@ -184,7 +188,7 @@ void symv_loops(bool herm, char uplo, int64_t n, T alpha, const T* A, int64_t ld
 }
 
 template <class T>
-void symv_abs(char uplo, int64_t n, T alpha, const T* A, int64_t lda,
+void symv_abs(bool herm, char uplo, int64_t n, T alpha, const T* A, int64_t lda,
               const T* x, int64_t incx, T beta, const T* yin, int64_t incy,
               double* yout, const int64_t* sample, int64_t nsample) {
     const bool lower = (uplo == 'L' || uplo == 'l');
@@ -198,7 +202,7 @@ void symv_abs(char uplo, int64_t n, T alpha, const T* A, int64_t lda,
                 const bool stored = (j == i) || (lower ? (i > j) : (i < j));
                 const T s = stored ? A[i + j * lda] : A[j + i * lda];
                 // HEMV uses only the real part of the diagonal
-                const double as = (j == i && is_cplx<T>::value) ? absval(real_only(s)) : absval(s);
+                const double as = (j == i && herm) ? absval(real_only(s)) : absval(s);
                 sum += as * absval(x[vpos(j, n, incx)]);
             }
         }
@@ -231,7 +235,7 @@ int symv_any(int mode, bool herm, char uplo, int64_t n, const void* alpha, const
     const T *a = static_cast<const T*>(A), *xv = static_cast<const T*>(x), *yi = static_cast<const T*>(yin);
     if (mode == MODE_W) symv_loops<T, T, T>(herm, uplo, n, al, a, lda, xv, incx, be, yi, incy, static_cast<T*>(yout), sample, nsample);
     else if (mode == MODE_X) symv_loops<T, XT, XO>(herm, uplo, n, al, a, lda, xv, incx, be, yi, incy, static_cast<XO*>(yout), sample, nsample);
-    else if (mode == MODE_ABS) symv_abs<T>(uplo, n, al, a, lda, xv, incx, be, yi, incy, static_cast<double*>(yout), sample, nsample);
+    else if (mode == MODE_ABS) symv_abs<T>(herm, uplo, n, al, a, lda, xv, incx, be, yi, incy, static_cast<double*>(yout), sample, nsample);
     else return -100;
     return 0;
 }
@@ -273,6 +277,18 @@ extern "C" int mvo_symv(char prec, int mode, char uplo, int64_t n, const void* a
         case 'd': return symv_any<double, long double, double>(mode, false, uplo, n, alpha, A, lda, x, incx, beta, yin, incy, yout, sample, nsample);
         case 'c': return symv_any<cf, cd, cd>(mode, true, uplo, n, alpha, A, lda, x, incx, beta, yin, incy, yout, sample, nsample);
         case 'z': return symv_any<cd, cl, cd>(mode, true, uplo, n, alpha, A, lda, x, incx, beta, yin, incy, yout, sample, nsample);
+    }
+    return -101;
+}
+
+// Complex symmetric SYMV (prec 'c','z'): the SYMV rule without any conjugation.
+extern "C" int mvo_symv_complex_symmetric(char prec, int mode, char uplo, int64_t n, const void* alpha,
+                                          const void* A, int64_t lda, const void* x, int64_t incx, const void* beta,
+                                          const void* yin, int64_t incy, void* yout, const int64_t* sample,
+                                          int64_t nsample) {
+    switch (prec) {
+        case 'c': return symv_any<cf, cd, cd>(mode, false, uplo, n, alpha, A, lda, x, incx, beta, yin, incy, yout, sample, nsample);
+        case 'z': return symv_any<cd, cl, cd>(mode, false, uplo, n, alpha, A, lda, x, incx, beta, yin, incy, yout, sample, nsample);
     }
     return -101;
 }

@@ -392,3 +392,98 @@ def test_abs_mode_and_sampling(prec):
     fulls = oracle.symv(prec, "L", m, alpha, colmajor(poison(S, "L"))[0], xs, beta, y, lda=m, mode=MODE_X)
     parts = oracle.symv(prec, "L", m, alpha, colmajor(poison(S, "L"))[0], xs, beta, y, lda=m, mode=MODE_X, sample=idx)
     assert np.array_equal(parts[idx], fulls[idx])
+
+
+# --------------------------------------------------------------------------
+# 8. complex symmetric SYMV (prec c,z): the s,d rule applied to complex data.
+#    Pinned apart from HEMV so that a conjugation left in, or the diagonal's
+#    imaginary part dropped, fails.
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("prec", "cz")
+@pytest.mark.parametrize("uplo", "LU")
+def test_complex_symmetric_exact_rational(prec, uplo):
+    rng = np.random.default_rng(21)
+    n = 6
+    A = rnd_int(rng, prec, (n, n))
+    x, y = rnd_int(rng, prec, n), rnd_int(rng, prec, n)
+    alpha, beta = 2 - 1j, -1 + 3j
+    want = []
+    for i in range(n):
+        acc = (Fraction(0), Fraction(0))
+        for j in range(n):
+            stored = (i == j) or ((i > j) if uplo == "L" else (i < j))
+            acc = cadd(acc, cmul(frac(A[i, j] if stored else A[j, i]), frac(x[j])))
+        r = cadd(cmul(frac(alpha), acc), cmul(frac(beta), frac(y[i])))
+        want.append(complex(float(r[0]), float(r[1])))
+    want = np.array(want)
+    Af, lda = colmajor(poison(A, uplo), lda=n + 3)
+    for mode in (MODE_W, MODE_X):
+        got = oracle.csymv(prec, uplo, n, alpha, Af, x, beta, y, lda=lda, mode=mode)
+        assert np.array_equal(got, as_dtype(want, got.dtype))
+    herm = oracle.symv(prec, uplo, n, alpha, Af, x, beta, y, lda=lda, mode=MODE_X)
+    assert not np.array_equal(herm, want), "inputs do not tell the two products apart"
+
+
+@pytest.mark.parametrize("prec", "cz")
+@pytest.mark.parametrize("uplo", "LU")
+@pytest.mark.parametrize("n", [1, 2, 5, 64, 65, 200])
+def test_complex_symmetric_vs_numpy_and_gemv(prec, uplo, n):
+    rng = np.random.default_rng(100 + n)
+    A = rnd(rng, prec, (n, n))
+    x, y = rnd(rng, prec, n), rnd(rng, prec, n)
+    alpha, beta = 0.7 + 0.1j, 0.3 - 0.2j
+    S = complete(A.astype(np.complex128), uplo, herm=False)
+    assert np.array_equal(S, S.T) and (n == 1 or not np.array_equal(S, S.conj().T))
+    al, be = oracle.DTYPES[prec].type(alpha), oracle.DTYPES[prec].type(beta)
+    want = np.complex128(al) * (S @ x.astype(np.complex128)) + np.complex128(be) * y.astype(np.complex128)
+    for incx, incy, lda in [(1, 1, None), (-2, 3, n + 5)]:
+        Af, ld = colmajor(poison(A, uplo), lda=lda)
+        got = oracle.csymv(prec, uplo, n, alpha, Af, strided(x, incx), beta, strided(y, incy),
+                           lda=ld, incx=incx, incy=incy, mode=MODE_X)
+        g = logical(got, n, incy)
+        assert np.all(np.isfinite(g)), "the poisoned triangle or padding was read"
+        assert np.linalg.norm(g - want) <= XTOL[prec] * np.linalg.norm(want)
+    Sf, _ = colmajor(S.astype(oracle.DTYPES[prec]))
+    via_gemv = oracle.gemv(prec, "N", n, n, alpha, Sf, x, beta, y, lda=n, mode=MODE_W)
+    via_symv = oracle.csymv(prec, uplo, n, alpha, colmajor(poison(A, uplo))[0], x, beta, y, lda=n, mode=MODE_W)
+    assert np.array_equal(via_gemv, via_symv)
+    # the transposed product of a symmetric matrix is the same sum in the same order
+    via_gemv_t = oracle.gemv(prec, "T", n, n, alpha, Sf, x, beta, y, lda=n, mode=MODE_W)
+    assert np.array_equal(via_gemv_t, via_symv)
+
+
+@pytest.mark.parametrize("prec", "cz")
+def test_complex_symmetric_bilinear_form_and_diagonal(prec):
+    rng = np.random.default_rng(31)
+    n = 83
+    A = rnd(rng, prec, (n, n))
+    x1, x2 = rnd(rng, prec, n), rnd(rng, prec, n)
+    zero = np.zeros(n, dtype=A.dtype)
+    Af = colmajor(poison(A, "L"))[0]
+    # x1^T (S x2) == x2^T (S x1) without any conjugation
+    a = np.dot(x1.astype(np.complex128), oracle.csymv(prec, "L", n, 1.0, Af, x2, 0, zero, lda=n))
+    b = np.dot(x2.astype(np.complex128), oracle.csymv(prec, "L", n, 1.0, Af, x1, 0, zero, lda=n))
+    assert abs(a - b) <= 1e-12 * max(abs(a), 1.0)
+    # the imaginary part of the diagonal takes part: changing it changes exactly y_k by i*d*x_k
+    B = A.copy()
+    k = 17
+    B[k, k] += 0.5j
+    ya = oracle.csymv(prec, "L", n, 1.0, Af, x1, 0, zero, lda=n)
+    yb = oracle.csymv(prec, "L", n, 1.0, colmajor(poison(B, "L"))[0], x1, 0, zero, lda=n)
+    diff = yb - ya
+    assert np.count_nonzero(diff) == 1
+    assert abs(diff[k] - 0.5j * np.complex128(x1[k])) <= 1e-13
+    # ABS mode uses |a_kk| of the full diagonal entry, not of its real part
+    C = np.zeros((n, n), dtype=A.dtype)
+    C[k, k] = 3 + 4j
+    ones = np.ones(n, dtype=A.dtype)
+    ab = oracle.csymv(prec, "L", n, 1.0, colmajor(C)[0], ones, 0, zero, lda=n, mode=MODE_ABS)
+    assert ab[k] == 5.0 and np.count_nonzero(ab) == 1
+    ab_h = oracle.symv(prec, "L", n, 1.0, colmajor(C)[0], ones, 0, zero, lda=n, mode=MODE_ABS)
+    assert ab_h[k] == 3.0
+
+
+def test_complex_symmetric_rejects_real_precisions():
+    z = np.zeros(1, dtype=np.float64)
+    with pytest.raises(ValueError):
+        oracle.csymv("d", "L", 1, 1.0, z, z, 0.0, z, lda=1)
