@@ -47,7 +47,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "rect", "tiny"])
+    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "csymv", "rect", "tiny"])
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
@@ -93,6 +93,21 @@ def products(workload):
                                     alpha=-1.0, beta=1.0))
                 out.append(dict(kind="symv", prec="d", mode="L", n=n, lda=20000, off=o, parent=20000,
                                 alpha=-1.0, beta=1.0))
+    elif workload == "panel":      # the products of one 64-column panel of the two-sided reductions (Section 10):
+        # column j of the panel multiplies by the trailing block that starts at j or j+1 of a 16384 x 16384 parent
+        for j in range(64):
+            out.append(dict(kind="symv", prec="d", mode="L", n=16384 - (j + 1), lda=16384, off=j + 1, parent=16384,
+                            alpha=1.0, beta=0.0))
+            out.append(dict(kind="gemv", prec="d", mode="T", n=16384 - j, lda=16384, off=j, parent=16384,
+                            alpha=1.0, beta=0.0))
+            out.append(dict(kind="gemv", prec="d", mode="N", n=16384 - (j + 1), lda=16384, off=j + 1, parent=16384,
+                            alpha=1.0, beta=0.0))
+    elif workload == "csymv":      # complex symmetric SYMV beside HEMV, same shapes
+        for prec in "cz":
+            for n in (16384, 32768):
+                for uplo in "LU":
+                    out.append(dict(kind="symv", prec=prec, mode=uplo, n=n, lda=n, alpha=1.0, beta=0.0, csym=True))
+                    out.append(dict(kind="symv", prec=prec, mode=uplo, n=n, lda=n, alpha=1.0, beta=0.0))
     elif workload == "rect":       # panels as in blocked reductions: tall-skinny and short-wide, d and s, N and T
         shapes = [(65536, 32), (65536, 128), (65536, 512), (16384, 64), (16384, 256), (16384, 1024), (16384, 4096),
                   (32, 65536), (128, 65536), (512, 65536), (64, 16384), (256, 16384), (1024, 16384), (4096, 16384)]
@@ -114,7 +129,7 @@ def op_name(p):
 def routine_name(p):
     if p["kind"] == "gemv":
         return f"{p['prec']}gemv_{p['mode']}"
-    return f"{p['prec']}{'hemv' if p['prec'] in 'cz' else 'symv'}_{p['mode']}"
+    return f"{p['prec']}{'hemv' if p['prec'] in 'cz' and not p.get('csym') else 'symv'}_{p['mode']}"
 
 
 def kernel_name(p):
@@ -170,7 +185,8 @@ def make_call(p, k, A, x, y):
     # arguments are marshalled once, outside the timed region; a call is then one foreign call
     if p["kind"] == "gemv":
         return k.prepare_gemv(p["prec"], p["mode"], p.get("m", n), n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
-    return k.prepare_symv(p["prec"], p["mode"], n, p["alpha"], A, lda, x, incx, p["beta"], y, 1)
+    return k.prepare_symv(p["prec"], p["mode"], n, p["alpha"], A, lda, x, incx, p["beta"], y, 1,
+                          complex_symmetric=bool(p.get("csym")))
 
 
 def tiny_latency(k, torch, wl):
@@ -364,6 +380,9 @@ def main():
             "target16k": "all 16 precision x routine products at n=16384 and 32768, lda=n",
             "large": "configs[4]: n=49152 (s,c) / 40960 (d,z), lda=n+32, N(0,1), alpha=0.7, beta=0.3, incx 1 and 2",
             "subblock": "configs[3]: blocks of a 20000x20000 fp64 parent at offsets 1,17,63,1000",
+            "panel": "DSYMV L, DGEMV T, DGEMV N on the trailing blocks at offsets 0..64 of a 16384x16384 fp64 parent "
+                     "(one 64-column panel of a two-sided reduction), beta=0",
+            "csymv": "CSYMV/ZSYMV (complex symmetric) beside CHEMV/ZHEMV, L and U, n=16384 and 32768, lda=n",
             "rect": "S/DGEMV N,T on tall-skinny and short-wide panels (65536x32 .. 4096x16384 and transposes), lda=m",
             "tiny": "configs[0]: DGEMV N m=n=lda=1024",
         }[args.workload], "products_per_step": nprod},

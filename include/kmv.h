@@ -114,13 +114,70 @@ int kmv_zhemv(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_compl
               const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
               void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- SYMV for complex symmetric matrices (A = A^T, no conjugation, the
+ * diagonal taken as stored).  The routine table of Section 5.2 lists SYMV for
+ * s,d and HEMV for c,z only; these two complete the set of the standard BLAS
+ * extension and run the HEMV kernels with the conjugation switched off.
+ * Arguments, workspace (kmv_symv_workspace_bytes with prec 'c' / 'z') and
+ * errors as for kmv_chemv / kmv_zhemv. */
+int kmv_csymv(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+              const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zsymv(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+              const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Sub-block calls that name the parent matrix (Section 6.6, "Multiplication
+ * by a Submatrix"; the GEMV-OFFSET / SYMV-OFFSET / HEMV-OFFSET rows
+ * of the routine table in Section 5.2).  A, m, n (and x, y) describe the
+ * PARENT; the product is taken with the block of its rows offset_r..m-1 and
+ * columns offset_c..n-1 (SYMV/HEMV: the trailing diagonal block from `offset`
+ * on).  x and y are the parent's vectors: of a vector with increment inc the
+ * logical elements from the offset on take part, the others are neither read
+ * nor written ('N': x from offset_c, y from offset_r; 'T','C': x from
+ * offset_r, y from offset_c).  The paper does not print the argument list;
+ * this one is the standard list followed by the offsets.
+ * The call equals the standard call on the pointer A + offset_r + offset_c*lda
+ * with the reduced sizes: the standard calls here already derive the tile grid
+ * from the pointer's misalignment, and, unlike the paper's kernels, neither
+ * form loads parent elements outside the block.  Workspace: the size for the
+ * block's dimensions (m - offset_r, n - offset_c; n - offset).  Errors as for
+ * the standard calls; an offset below 0 or beyond the dimension returns the
+ * negated number of that argument (-12 / -13 for GEMV, -11 for SYMV/HEMV). */
+int kmv_sgemv_offset(char trans, int64_t m, int64_t n, const float* alpha, const float* A, int64_t lda,
+                     const float* x, int64_t incx, const float* beta, float* y, int64_t incy,
+                     int64_t offset_r, int64_t offset_c, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_dgemv_offset(char trans, int64_t m, int64_t n, const double* alpha, const double* A, int64_t lda,
+                     const double* x, int64_t incx, const double* beta, double* y, int64_t incy,
+                     int64_t offset_r, int64_t offset_c, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_cgemv_offset(char trans, int64_t m, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A,
+                     int64_t lda, const kmv_complex64* x, int64_t incx, const kmv_complex64* beta,
+                     kmv_complex64* y, int64_t incy, int64_t offset_r, int64_t offset_c, void* workspace,
+                     size_t workspace_bytes, void* stream);
+int kmv_zgemv_offset(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A,
+                     int64_t lda, const kmv_complex128* x, int64_t incx, const kmv_complex128* beta,
+                     kmv_complex128* y, int64_t incy, int64_t offset_r, int64_t offset_c, void* workspace,
+                     size_t workspace_bytes, void* stream);
+int kmv_ssymv_offset(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda, const float* x,
+                     int64_t incx, const float* beta, float* y, int64_t incy, int64_t offset, void* workspace,
+                     size_t workspace_bytes, void* stream);
+int kmv_dsymv_offset(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x,
+                     int64_t incx, const double* beta, double* y, int64_t incy, int64_t offset, void* workspace,
+                     size_t workspace_bytes, void* stream);
+int kmv_chemv_offset(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+                     const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y,
+                     int64_t incy, int64_t offset, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zhemv_offset(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+                     const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
+                     int64_t incy, int64_t offset, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- Workspace sizes (bytes; an upper bound valid for every pointer
  * alignment, every increment and every tuning value).  prec is 's','d','c'
  * or 'z'.  The workspace holds the packed copy of a strided x and the
  * per-workgroup partial sums that the final pass adds in a fixed order (the
  * deterministic replacement of the atomic accumulation of Section 6.2).
  * The pointer passed as workspace must be 256-byte aligned.  Returns 0 for
- * an unknown prec or a negative dimension. */
+ * an unknown prec, a negative dimension or an empty product. */
 size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n);
 size_t kmv_symv_workspace_bytes(char prec, char uplo, int64_t n);
 

@@ -42,9 +42,16 @@ def _load() -> ctypes.CDLL:
     for p in "sdcz":
         f = getattr(lib, f"kmv_{p}gemv")
         f.argtypes, f.restype = gemv_args, ci
-    for name in ("ssymv", "dsymv", "chemv", "zhemv"):
+    for name in ("ssymv", "dsymv", "chemv", "zhemv", "csymv", "zsymv"):
         f = getattr(lib, f"kmv_{name}")
         f.argtypes, f.restype = symv_args, ci
+    gemv_off_args = gemv_args[:11] + [i64, i64] + gemv_args[11:]
+    symv_off_args = symv_args[:10] + [i64] + symv_args[10:]
+    for p_ in "sdcz":
+        f = getattr(lib, f"kmv_{p_}gemv_offset")
+        f.argtypes, f.restype = gemv_off_args, ci
+        f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_offset")
+        f.argtypes, f.restype = symv_off_args, ci
     lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
     lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
     lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -219,8 +226,12 @@ def prepare_gemv(prec, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, works
     return Prepared(f"{prec}gemv", getattr(lib, f"kmv_{prec}gemv"), args, (A, x, y, workspace))
 
 
-def prepare_symv(prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None) -> Prepared:
-    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}"
+def prepare_symv(prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None,
+                 complex_symmetric=False) -> Prepared:
+    """`complex_symmetric` (prec c,z) prepares csymv / zsymv instead of chemv / zhemv."""
+    if complex_symmetric and prec not in "cz":
+        raise ValueError("complex_symmetric needs prec 'c' or 'z'")
+    name = f"{prec}{'hemv' if prec in 'cz' and not complex_symmetric else 'symv'}"
     if workspace is None:
         workspace = _cached_workspace(symv_workspace_bytes(prec, uplo, max(n, 0)),
                                            None if isinstance(y, int) else y.device)
@@ -231,8 +242,55 @@ def prepare_symv(prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace
     return Prepared(name, getattr(lib, f"kmv_{name}"), args, (A, x, y, workspace))
 
 
+def csymv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _symv("csymv", "c", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def zsymv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+    return _symv("zsymv", "z", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def _gemv_offset(prec):
+    def call(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, offset_r, offset_c, workspace=None, stream=None,
+             check=True):
+        wsp, wsb = _ws_args(workspace, lambda: gemv_workspace_bytes(
+            prec, trans if trans in tuple("NnTtCc") else "N", max(m - offset_r, 0), max(n - offset_c, 0)), y)
+        rc = getattr(lib, f"kmv_{prec}gemv_offset")(
+            trans.encode(), m, n, _scalar(prec, alpha), _ptr(A, prec), lda, _ptr(x, prec), incx, _scalar(prec, beta),
+            _ptr(y, prec), incy, offset_r, offset_c, ctypes.c_void_p(wsp), wsb, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(f"{prec}gemv_offset", rc)
+        return rc
+    call.__name__ = f"{prec}gemv_offset"
+    call.__doc__ = "GEMV with the block of the parent A (m x n) from row offset_r and column offset_c on."
+    return call
+
+
+def _symv_offset(prec):
+    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}_offset"
+
+    def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, offset, workspace=None, stream=None, check=True):
+        wsp, wsb = _ws_args(workspace, lambda: symv_workspace_bytes(
+            prec, uplo if uplo in tuple("LlUu") else "L", max(n - offset, 0)), y)
+        rc = getattr(lib, f"kmv_{name}")(
+            uplo.encode(), n, _scalar(prec, alpha), _ptr(A, prec), lda, _ptr(x, prec), incx, _scalar(prec, beta),
+            _ptr(y, prec), incy, offset, ctypes.c_void_p(wsp), wsb, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(name, rc)
+        return rc
+    call.__name__ = name
+    call.__doc__ = "SYMV / HEMV with the trailing diagonal block of the parent A (n x n) from `offset` on."
+    return call
+
+
+sgemv_offset, dgemv_offset, cgemv_offset, zgemv_offset = (_gemv_offset(p_) for p_ in "sdcz")
+ssymv_offset, dsymv_offset, chemv_offset, zhemv_offset = (_symv_offset(p_) for p_ in "sdcz")
+GEMV_OFFSET = {"s": sgemv_offset, "d": dgemv_offset, "c": cgemv_offset, "z": zgemv_offset}
+SYMV_OFFSET = {"s": ssymv_offset, "d": dsymv_offset, "c": chemv_offset, "z": zhemv_offset}
+
 GEMV = {"s": sgemv, "d": dgemv, "c": cgemv, "z": zgemv}
 SYMV = {"s": ssymv, "d": dsymv, "c": chemv, "z": zhemv}   # HEMV for the complex precisions
+CSYMV = {"c": csymv, "z": zsymv}                          # complex symmetric
 
 
 def partition(W, Y, y):

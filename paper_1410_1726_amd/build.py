@@ -17,7 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkmv.so")
-SOURCES = ["kmv_api.hip", "kmv_gemv.hip", "kmv_symv.hip", "kmv_aux.hip"]
+SOURCES = ["kmv_symv_real.hip", "kmv_symv_herm.hip", "kmv_symv_csym.hip", "kmv_gemv.hip", "kmv_api.hip",
+           "kmv_aux.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -52,7 +53,7 @@ def build_library(verbose: bool = False, extra_flags=(), out: str | None = None)
             print(r.stderr, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     tmp = out + ".tmp"
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],

@@ -67,7 +67,7 @@ int gemv_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int
 }
 
 template <class T>
-int symv_entry(char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x, int64_t incx, const T* beta,
+int symv_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x, int64_t incx, const T* beta,
                T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream) {
     const bool lower = (uplo == 'L' || uplo == 'l');
     const bool upper = (uplo == 'U' || uplo == 'u');
@@ -103,16 +103,51 @@ int symv_entry(char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, co
     } else {
         a.x = x;
     }
-    return hip_code(launch_symv<T>(a, lower, s));
+    return hip_code(launch_symv<T>(a, lower, herm, s));
+}
+
+// Sub-block calls that name the parent matrix (Section 6.6).  Logical elements off..len-1 of a
+// strided parent vector start `off` increments further on when the increment is positive and
+// at the same address when it is negative (the shorter vector ends where the parent's does).
+template <class T> inline T* vec_from(T* v, int64_t off, int64_t inc) {
+    return (v && inc > 0) ? v + off * inc : v;
+}
+template <class T>
+int gemv_offset_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x,
+                      int64_t incx, const T* beta, T* y, int64_t incy, int64_t offset_r, int64_t offset_c,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    const bool notrans = (trans == 'N' || trans == 'n');
+    if (!notrans && trans != 'T' && trans != 't' && trans != 'C' && trans != 'c') return -1;
+    if (m < 0) return -2;
+    if (n < 0) return -3;
+    if (lda < (m > 1 ? m : 1)) return -6;
+    if (offset_r < 0 || offset_r > m) return -12;
+    if (offset_c < 0 || offset_c > n) return -13;
+    const int64_t offx = notrans ? offset_c : offset_r, offy = notrans ? offset_r : offset_c;
+    return gemv_entry<T>(trans, m - offset_r, n - offset_c, alpha, A ? A + offset_r + offset_c * lda : A, lda,
+                         vec_from(x, offx, incx), incx, beta, vec_from(y, offy, incy), incy, workspace,
+                         workspace_bytes, stream);
+}
+template <class T>
+int symv_offset_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x,
+                      int64_t incx, const T* beta, T* y, int64_t incy, int64_t offset, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (uplo != 'L' && uplo != 'l' && uplo != 'U' && uplo != 'u') return -1;
+    if (n < 0) return -2;
+    if (lda < (n > 1 ? n : 1)) return -5;
+    if (offset < 0 || offset > n) return -11;
+    return symv_entry<T>(herm, uplo, n - offset, alpha, A ? A + offset + offset * lda : A, lda,
+                         vec_from(x, offset, incx), incx, beta, vec_from(y, offset, incy), incy, workspace,
+                         workspace_bytes, stream);
 }
 
 template <class T> size_t gemv_ws(char trans, int64_t m, int64_t n) {
     const bool notrans = (trans == 'N' || trans == 'n');
-    if (m < 0 || n < 0) return 0;
+    if (m <= 0 || n <= 0) return 0;   // an empty product returns before it would use a workspace
     return plan_gemv<T>(notrans, m, n, nullptr, 0).total_bytes;
 }
 template <class T> size_t symv_ws(char uplo, int64_t n) {
-    if (n < 0) return 0;
+    if (n <= 0) return 0;
     return plan_symv<T>(uplo == 'L' || uplo == 'l', n, nullptr, 0).total_bytes;
 }
 
@@ -160,24 +195,61 @@ int kmv_zgemv(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, con
 
 int kmv_ssymv(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda, const float* x, int64_t incx,
               const float* beta, float* y, int64_t incy, void* ws, size_t wsb, void* stream) {
-    return symv_entry<float>(uplo, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
+    return symv_entry<float>(false, uplo, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
 }
 int kmv_dsymv(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x, int64_t incx,
               const double* beta, double* y, int64_t incy, void* ws, size_t wsb, void* stream) {
-    return symv_entry<double>(uplo, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
+    return symv_entry<double>(false, uplo, n, alpha, A, lda, x, incx, beta, y, incy, ws, wsb, stream);
 }
 int kmv_chemv(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
               const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
               void* ws, size_t wsb, void* stream) {
-    return symv_entry<cf32>(uplo, n, (const cf32*)alpha, (const cf32*)A, lda, (const cf32*)x, incx, (const cf32*)beta,
+    return symv_entry<cf32>(true, uplo, n, (const cf32*)alpha, (const cf32*)A, lda, (const cf32*)x, incx, (const cf32*)beta,
                             (cf32*)y, incy, ws, wsb, stream);
 }
 int kmv_zhemv(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
               const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
               void* ws, size_t wsb, void* stream) {
-    return symv_entry<cf64>(uplo, n, (const cf64*)alpha, (const cf64*)A, lda, (const cf64*)x, incx, (const cf64*)beta,
+    return symv_entry<cf64>(true, uplo, n, (const cf64*)alpha, (const cf64*)A, lda, (const cf64*)x, incx, (const cf64*)beta,
                             (cf64*)y, incy, ws, wsb, stream);
 }
+int kmv_csymv(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+              const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y, int64_t incy,
+              void* ws, size_t wsb, void* stream) {
+    return symv_entry<cf32>(false, uplo, n, (const cf32*)alpha, (const cf32*)A, lda, (const cf32*)x, incx,
+                            (const cf32*)beta, (cf32*)y, incy, ws, wsb, stream);
+}
+int kmv_zsymv(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+              const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y, int64_t incy,
+              void* ws, size_t wsb, void* stream) {
+    return symv_entry<cf64>(false, uplo, n, (const cf64*)alpha, (const cf64*)A, lda, (const cf64*)x, incx,
+                            (const cf64*)beta, (cf64*)y, incy, ws, wsb, stream);
+}
+
+#define KMV_GEMV_OFFSET(NAME, CT, T)                                                                              \
+    int NAME(char trans, int64_t m, int64_t n, const CT* alpha, const CT* A, int64_t lda, const CT* x,            \
+             int64_t incx, const CT* beta, CT* y, int64_t incy, int64_t offset_r, int64_t offset_c, void* ws,     \
+             size_t wsb, void* stream) {                                                                          \
+        return gemv_offset_entry<T>(trans, m, n, (const T*)alpha, (const T*)A, lda, (const T*)x, incx,            \
+                                    (const T*)beta, (T*)y, incy, offset_r, offset_c, ws, wsb, stream);            \
+    }
+KMV_GEMV_OFFSET(kmv_sgemv_offset, float, float)
+KMV_GEMV_OFFSET(kmv_dgemv_offset, double, double)
+KMV_GEMV_OFFSET(kmv_cgemv_offset, kmv_complex64, cf32)
+KMV_GEMV_OFFSET(kmv_zgemv_offset, kmv_complex128, cf64)
+#undef KMV_GEMV_OFFSET
+
+#define KMV_SYMV_OFFSET(NAME, CT, T, HERM)                                                                        \
+    int NAME(char uplo, int64_t n, const CT* alpha, const CT* A, int64_t lda, const CT* x, int64_t incx,          \
+             const CT* beta, CT* y, int64_t incy, int64_t offset, void* ws, size_t wsb, void* stream) {           \
+        return symv_offset_entry<T>(HERM, uplo, n, (const T*)alpha, (const T*)A, lda, (const T*)x, incx,          \
+                                    (const T*)beta, (T*)y, incy, offset, ws, wsb, stream);                        \
+    }
+KMV_SYMV_OFFSET(kmv_ssymv_offset, float, float, false)
+KMV_SYMV_OFFSET(kmv_dsymv_offset, double, double, false)
+KMV_SYMV_OFFSET(kmv_chemv_offset, kmv_complex64, cf32, true)
+KMV_SYMV_OFFSET(kmv_zhemv_offset, kmv_complex128, cf64, true)
+#undef KMV_SYMV_OFFSET
 
 size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n) {
     switch (prec) {

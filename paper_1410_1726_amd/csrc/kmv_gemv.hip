@@ -442,7 +442,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(p.ntiles * TR);
     } else {
-        const int64_t g = ceil_div(n, GT_NC);
+        const int64_t g = n > 0 ? ceil_div(n, GT_NC) : 1;
         // row splits only when there are too few column groups to occupy the device:
         // from about 512 groups on, one workgroup per group with the epilogue fused
         // (no second kernel) is faster

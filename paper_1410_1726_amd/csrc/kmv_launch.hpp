@@ -118,7 +118,15 @@ template <class T> struct SymvArgs {
     int* wtab;        // variant 2: [nchunks][2] first and last workgroup whose share touches the chunk
     SymvPlan<T> plan;
 };
-template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s);
+// HERM selects the Hermitian rule (conjugated mirror image, real diagonal); it exists for
+// complex T only.  Each (T, HERM) pair is instantiated in exactly one translation unit.
+template <class T, bool HERM> hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s);
+template <class T> inline hipError_t launch_symv(const SymvArgs<T>& a, bool lower, bool herm, hipStream_t s) {
+    if constexpr (Traits<T>::cplx) {
+        if (herm) return launch_symv_kind<T, true>(a, lower, s);
+    }
+    return launch_symv_kind<T, false>(a, lower, s);
+}
 
 // ------------------------------------------------------------ auxiliary ----
 // dst[k] = element k of the strided vector src (base already moved for inc < 0)

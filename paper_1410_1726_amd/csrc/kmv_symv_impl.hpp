@@ -42,6 +42,12 @@
 //    in all columns share few L2 sets), and long chains are dispatched first.
 // A second kernel adds, in a fixed order, all row sums and column sums that
 // belong to y_i and applies alpha and beta (no atomics anywhere).
+//
+// This header holds the kernels and their host side as templates; the
+// translation units kmv_symv_real.hip (s, d), kmv_symv_herm.hip (c, z
+// Hermitian) and kmv_symv_csym.hip (c, z symmetric) instantiate them, so that
+// the three groups compile side by side.
+#pragma once
 #include "kmv_launch.hpp"
 
 namespace kmv {
@@ -919,8 +925,10 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
 }
 }  // namespace
 
-template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipStream_t s) {
-    constexpr bool HERM = Traits<T>::cplx;
+// HERM: conjugate the mirrored triangle and take the real part of the diagonal
+// (complex Hermitian); false for real symmetric and complex symmetric matrices.
+template <class T, bool HERM> hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s) {
+    static_assert(!HERM || Traits<T>::cplx, "Hermitian kernels exist for complex types only");
     if (a.plan.variant == 3) {   // one launch, no workspace
         const dim3 grid((unsigned)ceil_div(a.n, SMALL_NC));
         if (lower) hipLaunchKernelGGL((symv_small_kernel<T, HERM, true, SMALL_NC, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
@@ -942,13 +950,5 @@ template <class T> hipError_t launch_symv(const SymvArgs<T>& a, bool lower, hipS
     }
     return hipGetLastError();
 }
-
-#define KMV_INSTANTIATE_SYMV(T)                                                       \
-    template SymvPlan<T> plan_symv<T>(bool, int64_t, const void*, int64_t);           \
-    template hipError_t launch_symv<T>(const SymvArgs<T>&, bool, hipStream_t);
-KMV_INSTANTIATE_SYMV(float)
-KMV_INSTANTIATE_SYMV(double)
-KMV_INSTANTIATE_SYMV(cf32)
-KMV_INSTANTIATE_SYMV(cf64)
 
 }  // namespace kmv

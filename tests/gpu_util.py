@@ -122,8 +122,9 @@ def gemv_case(prec, trans, m, n, alpha, beta, *, lda=None, incx=1, incy=1, dist=
 
 
 def symv_case(prec, uplo, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uniform", seed=0,
-              off=0, sample=None, nan_imag_diag=False, parent=None, parent_host=None, poison=True):
-    """Run kmv symv/hemv and the oracle; with `poison` the unreferenced triangle
+              off=0, sample=None, nan_imag_diag=False, parent=None, parent_host=None, poison=True,
+              complex_symmetric=False):
+    """Run kmv symv/hemv (csymv/zsymv with `complex_symmetric`) and the oracle; with `poison` the unreferenced triangle
     and everything outside the block of the parent are NaN on the device (the
     host copy handed to the oracle is taken before: the oracle indexes the
     stored triangle only)."""
@@ -149,7 +150,8 @@ def symv_case(prec, uplo, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uni
     if beta == 0:
         y0.fill_(float("nan"))      # beta = 0: y must not be read
     y = y0.clone()
-    k.SYMV[prec](uplo, n, alpha, A, lda, x, incx, beta, y, incy)
+    assert not (complex_symmetric and nan_imag_diag), "the symmetric product uses the whole diagonal entry"
+    (k.CSYMV if complex_symmetric else k.SYMV)[prec](uplo, n, alpha, A, lda, x, incx, beta, y, incy)
     torch.cuda.synchronize()
     yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
     if abs(incy) > 1 and n:
@@ -159,7 +161,7 @@ def symv_case(prec, uplo, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uni
     got = logical(yh, n, incy)
     Ah = parent_host[off * lda + off:]
     y0o = np.zeros_like(y0h) if beta == 0 else y0h
-    kw = dict(lda=lda, incx=incx, incy=incy, sample=sample)
+    kw = dict(lda=lda, incx=incx, incy=incy, sample=sample, complex_symmetric=complex_symmetric)
     want = logical(oracle.symv(prec, uplo, n, alpha, Ah, xh, beta, y0o, mode=oracle.MODE_X, **kw), n, incy)
     den = logical(oracle.symv(prec, uplo, n, alpha, Ah, xh, beta, y0o, mode=oracle.MODE_ABS, **kw), n, incy)
     idx = slice(None) if sample is None else np.asarray(sample)

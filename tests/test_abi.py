@@ -52,9 +52,9 @@ def test_gemv_argument_errors(prec):
         f("Q", 4, 4, 1.0, DUMMY, 4, DUMMY, 1, 0.0, DUMMY, 1, workspace=NOWS, stream=0)
 
 
-@pytest.mark.parametrize("prec", "sdcz")
+@pytest.mark.parametrize("prec", ["s", "d", "c", "z", "c-symmetric", "z-symmetric"])
 def test_symv_argument_errors(prec):
-    f = kmv.SYMV[prec]
+    f = kmv.CSYMV[prec[0]] if prec.endswith("symmetric") else kmv.SYMV[prec]
 
     def call(uplo="L", n=4, lda=4, incx=1, incy=1, A=DUMMY):
         return f(uplo, n, 1.0, A, lda, DUMMY, incx, 0.0, DUMMY, incy, workspace=NOWS, stream=0, check=False)
@@ -91,7 +91,10 @@ def test_partition_invariants():
 
 def test_workspace_sizes():
     for prec, b in (("s", 4), ("d", 8), ("c", 8), ("z", 16)):
-        assert kmv.gemv_workspace_bytes(prec, "N", 0, 0) >= 0
+        for trans in "NTC":                           # empty products need no workspace (and no division by zero)
+            for m, n in ((0, 0), (0, 7), (7, 0)):
+                assert kmv.gemv_workspace_bytes(prec, trans, m, n) == 0
+        assert kmv.symv_workspace_bytes(prec, "L", 0) == 0
         small = kmv.gemv_workspace_bytes(prec, "N", 1024, 1024)
         big = kmv.gemv_workspace_bytes(prec, "N", 4096, 4096)
         assert 0 < small <= big
@@ -142,3 +145,28 @@ def test_symv_kernel_variant_query():
 def test_tuning_sweep_tool_is_importable():
     from paper_1410_1726_amd import tune
     assert tune.main([]) == 2          # prints its usage, touches no device
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+def test_offset_argument_errors(prec):
+    g, f = kmv.GEMV_OFFSET[prec], kmv.SYMV_OFFSET[prec]
+
+    def gemv(trans="N", m=8, n=6, lda=8, offr=0, offc=0, incx=1, A=DUMMY):
+        return g(trans, m, n, 1.0, A, lda, DUMMY, incx, 0.0, DUMMY, 1, offr, offc, workspace=NOWS, stream=0, check=False)
+
+    def symv(uplo="L", n=8, lda=8, off=0, A=DUMMY):
+        return f(uplo, n, 1.0, A, lda, DUMMY, 1, 0.0, DUMMY, 1, off, workspace=NOWS, stream=0, check=False)
+
+    assert gemv(trans="X") == -1 and gemv(m=-1) == -2 and gemv(n=-1) == -3
+    assert gemv(lda=7) == -6                    # the leading dimension is checked against the parent
+    assert gemv(lda=7, offr=4) == -6
+    assert gemv(offr=-1) == -12 and gemv(offr=9) == -12
+    assert gemv(offc=-1) == -13 and gemv(offc=7) == -13
+    assert gemv(incx=0) == -8
+    assert gemv(offr=8) == 0 and gemv(offc=6) == 0          # empty block: nothing to do
+    assert gemv(A=None) == kmv.ERR_NULL
+    assert symv(uplo="N") == -1 and symv(n=-1) == -2 and symv(lda=7) == -5
+    assert symv(off=-1) == -11 and symv(off=9) == -11
+    assert symv(off=8) == 0
+    assert symv(A=None) == kmv.ERR_NULL
+    assert symv() == kmv.ERR_WORKSPACE

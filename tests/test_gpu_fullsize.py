@@ -108,6 +108,10 @@ def test_largest_shapes(prec):
             _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, lda=lda, incx=incx, dist="normal", seed=5,
                                   parent=parent, parent_host=host, sample=samples(n, 4), poison=False)
             check(prec, err, f"symv/hemv {prec} {uplo} n={n} incx={incx}")
+            if prec in "cz" and incx == 1:
+                _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, lda=lda, dist="normal", seed=5, parent=parent,
+                                      parent_host=host, sample=samples(n, 4), poison=False, complex_symmetric=True)
+                check(prec, err, f"complex symmetric symv {prec} {uplo} n={n}")
     del parent, host
     free()
 

@@ -13,7 +13,7 @@ import torch
 import oracle
 from paper_1410_1726_amd import workloads as wl
 
-from gpu_util import DEV, check, gemv_case, kmv, logical, symv_case
+from gpu_util import DEV, check, errors, gemv_case, kmv, logical, symv_case
 
 pytestmark = pytest.mark.gpu
 
@@ -271,6 +271,117 @@ def test_symv_main_kernel_variants(prec, variant):
     finally:
         for key in k.tuning_keys():
             k.set_tuning(key, 0)
+
+
+@pytest.mark.parametrize("prec", "cz")
+@pytest.mark.parametrize("uplo", "LU")
+def test_complex_symmetric_symv(prec, uplo):
+    """csymv / zsymv: the HEMV kernels without conjugation and with the diagonal as stored; integer data
+    bitwise, then every main kernel on ragged sizes, sub-block offsets, strides and complex scalars"""
+    k = kmv()
+    for n in TINY + [300, 513]:
+        got, err, ex = symv_case(prec, uplo, n, 2 - 1j, -3 + 2j, dist="smallint", seed=n, lda=n + (n % 5),
+                                 complex_symmetric=True)
+        assert np.array_equal(got.astype(ex["want"].dtype), ex["want"]), (n, err)
+    # the inputs tell the two products apart: the Hermitian call gives another result
+    got_s, _, ex = symv_case(prec, uplo, 300, 1.0, 0.0, dist="smallint", seed=5, complex_symmetric=True)
+    got_h, _, _ = symv_case(prec, uplo, 300, 1.0, 0.0, dist="smallint", seed=5)
+    assert not np.array_equal(got_s, got_h)
+    try:
+        for variant, unit in ((0, 0), (1, 0), (2, 1), (2, 2), (3, 0)):
+            k.set_tuning("symv_variant", variant)
+            k.set_tuning("symv_unit_tiles", unit)
+            for n, off, lda, incx, incy in ((1000, 0, None, 1, 1), (1500, 17, 1792, -2, 1), (2048, 0, 2048, 1, 3),
+                                            (4099, 1, 4112, 1, 1)):
+                beta = 0.0 if n % 2 else 0.3 - 0.2j
+                _, err, _ = symv_case(prec, uplo, n, 0.7 + 0.1j, beta, lda=lda, off=off, incx=incx, incy=incy,
+                                      seed=n + off, complex_symmetric=True)
+                check(prec, err, f"complex symmetric variant={variant} unit={unit} {prec} {uplo} n={n} off={off}")
+    finally:
+        for key in k.tuning_keys():
+            k.set_tuning(key, 0)
+
+
+def _bits(a):
+    return np.ascontiguousarray(a).view(np.uint8)
+
+
+def _sub_vector(buf, off, inc):
+    """storage of the logical elements off.. of a strided parent vector (BLAS rule)"""
+    return buf[off * inc:] if inc > 0 else buf[: buf.size - off * (-inc)] if off else buf
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_offset_calls_name_the_parent(prec):
+    """GEMV/SYMV/HEMV `_offset` entry points: parent matrix and parent vectors plus offsets.  The oracle
+    computes the product with the block; parent elements outside the block are NaN, the vector elements
+    before the offsets are NaN in x and must stay bit-unchanged in y."""
+    k = kmv()
+    alpha, beta = scalars(prec, 0.7, -0.4)
+    M, N, lda = 1400, 1100, 1536
+    for trans, offr, offc, incx, incy in (("N", 1, 17, 1, 1), ("T", 63, 5, 2, 1), ("C", 100, 1000, -1, -2),
+                                          ("N", 0, 0, 1, 1), ("N", M, 3, 1, 1), ("T", 7, N, 1, 1)):
+        parent = wl.matrix(prec, M, N, lda, seed=41, device=DEV)
+        keep = parent[offc:, offr:M].clone()
+        parent.fill_(float("nan"))
+        parent[offc:, offr:M] = keep
+        lenx, leny, offx, offy = (N, M, offc, offr) if trans == "N" else (M, N, offr, offc)
+        x = wl.vector(prec, lenx, incx, seed=41, which=1, device=DEV, gap_value=float("nan"))
+        y0 = wl.vector(prec, leny, incy, seed=41, which=2, device=DEV, gap_value=float("nan"))
+        xl = x[:: abs(incx)]
+        (xl[:offx] if incx > 0 else xl[lenx - offx:]).fill_(float("nan"))      # logical elements before the offset
+        y = y0.clone()
+        k.GEMV_OFFSET[prec](trans, M, N, alpha, parent, lda, x, incx, beta, y, incy, offr, offc)
+        torch.cuda.synchronize()
+        yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
+        m, n = M - offr, N - offc
+        got_all, y0_all = logical(yh, leny, incy), logical(y0h, leny, incy)
+        assert np.array_equal(_bits(got_all[:offy]), _bits(y0_all[:offy])), "wrote before the offset"
+        untouched = np.ones(yh.size, dtype=bool)
+        untouched[:: abs(incy)] = False
+        assert np.array_equal(yh[untouched].view(np.uint8), y0h[untouched].view(np.uint8))
+        if m == 0 or n == 0:
+            assert np.array_equal(yh.view(np.uint8), y0h.view(np.uint8))
+            continue
+        Ah = parent.cpu().numpy().reshape(-1)[offc * lda + offr:]
+        xs, ys = _sub_vector(xh, offx, incx), _sub_vector(y0h, offy, incy)
+        kw = dict(lda=lda, incx=incx, incy=incy)
+        lo, lx = (m, n) if trans == "N" else (n, m)
+        want = logical(oracle.gemv(prec, trans, m, n, alpha, Ah, xs, beta, ys, mode=oracle.MODE_X, **kw), lo, incy)
+        den = logical(oracle.gemv(prec, trans, m, n, alpha, Ah, xs, beta, ys, mode=oracle.MODE_ABS, **kw), lo, incy)
+        check(prec, errors(prec, got_all[offy:], want, den, lx), f"{prec}gemv_offset {trans} ({offr},{offc})")
+    n, lda = 1300, 1408
+    for uplo, off, incx, incy in (("L", 1, 1, 1), ("U", 63, -1, 2), ("L", 1000, 2, -1), ("U", 0, 1, 1), ("L", n, 1, 1)):
+        parent = wl.matrix(prec, n, n, lda, seed=42, device=DEV)
+        keep = parent[off:, off:n].clone()
+        parent.fill_(float("nan"))
+        parent[off:, off:n] = keep
+        host = parent.cpu().numpy().reshape(-1)
+        if n - off:
+            wl.poison_triangle(parent[off:, off:], n - off, uplo, real_diag=False)
+        x = wl.vector(prec, n, incx, seed=42, which=1, device=DEV, gap_value=float("nan"))
+        y0 = wl.vector(prec, n, incy, seed=42, which=2, device=DEV, gap_value=float("nan"))
+        xl = x[:: abs(incx)]
+        (xl[:off] if incx > 0 else xl[n - off:]).fill_(float("nan"))
+        y = y0.clone()
+        k.SYMV_OFFSET[prec](uplo, n, alpha, parent, lda, x, incx, beta, y, incy, off)
+        torch.cuda.synchronize()
+        yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
+        got_all, y0_all = logical(yh, n, incy), logical(y0h, n, incy)
+        assert np.array_equal(_bits(got_all[:off]), _bits(y0_all[:off])), "wrote before the offset"
+        untouched = np.ones(yh.size, dtype=bool)
+        untouched[:: abs(incy)] = False
+        assert np.array_equal(yh[untouched].view(np.uint8), y0h[untouched].view(np.uint8))
+        nb = n - off
+        if nb == 0:
+            assert np.array_equal(yh.view(np.uint8), y0h.view(np.uint8))
+            continue
+        Ah = host[off * lda + off:]
+        xs, ys = _sub_vector(xh, off, incx), _sub_vector(y0h, off, incy)
+        kw = dict(lda=lda, incx=incx, incy=incy)
+        want = logical(oracle.symv(prec, uplo, nb, alpha, Ah, xs, beta, ys, mode=oracle.MODE_X, **kw), nb, incy)
+        den = logical(oracle.symv(prec, uplo, nb, alpha, Ah, xs, beta, ys, mode=oracle.MODE_ABS, **kw), nb, incy)
+        check(prec, errors(prec, got_all[off:], want, den, nb), f"symv/hemv_offset {prec} {uplo} offset {off}")
 
 
 def test_runs_on_a_side_stream_with_explicit_workspace():
