@@ -171,6 +171,40 @@ int kmv_zhemv_offset(char uplo, int64_t n, const kmv_complex128* alpha, const km
                      const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
                      int64_t incy, int64_t offset, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- The same products with alpha and beta in DEVICE memory (one element
+ * each, read by the kernels when they run, so a scalar that an earlier kernel
+ * on the stream computes needs no host synchronisation; the paper's routines
+ * take host scalars only, Section 5.2).  Everything else as for the standard
+ * calls, except that nothing can depend on the scalars' values at enqueue
+ * time: alpha == 0 still yields beta*y exactly (A and x are read, their
+ * values - NaN, Inf - do not enter), beta == 0 still means y is not read,
+ * alpha == 0 with beta == 1 rewrites y with its own values.  The scalars must
+ * not be written while the call is in flight. */
+int kmv_sgemv_devscalars(char trans, int64_t m, int64_t n, const float* alpha, const float* A, int64_t lda,
+                         const float* x, int64_t incx, const float* beta, float* y, int64_t incy,
+                         void* workspace, size_t workspace_bytes, void* stream);
+int kmv_dgemv_devscalars(char trans, int64_t m, int64_t n, const double* alpha, const double* A, int64_t lda,
+                         const double* x, int64_t incx, const double* beta, double* y, int64_t incy,
+                         void* workspace, size_t workspace_bytes, void* stream);
+int kmv_cgemv_devscalars(char trans, int64_t m, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A,
+                         int64_t lda, const kmv_complex64* x, int64_t incx, const kmv_complex64* beta,
+                         kmv_complex64* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zgemv_devscalars(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A,
+                         int64_t lda, const kmv_complex128* x, int64_t incx, const kmv_complex128* beta,
+                         kmv_complex128* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_ssymv_devscalars(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda, const float* x,
+                         int64_t incx, const float* beta, float* y, int64_t incy, void* workspace,
+                         size_t workspace_bytes, void* stream);
+int kmv_dsymv_devscalars(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x,
+                         int64_t incx, const double* beta, double* y, int64_t incy, void* workspace,
+                         size_t workspace_bytes, void* stream);
+int kmv_chemv_devscalars(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+                         const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y,
+                         int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zhemv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+                         const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
+                         int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- Workspace sizes (bytes; an upper bound valid for every pointer
  * alignment, every increment and every tuning value).  prec is 's','d','c'
  * or 'z'.  The workspace holds the packed copy of a strided x and the

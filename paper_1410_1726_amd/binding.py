@@ -52,6 +52,11 @@ def _load() -> ctypes.CDLL:
         f.argtypes, f.restype = gemv_off_args, ci
         f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_offset")
         f.argtypes, f.restype = symv_off_args, ci
+    for p_ in "sdcz":
+        f = getattr(lib, f"kmv_{p_}gemv_devscalars")
+        f.argtypes, f.restype = gemv_args, ci
+        f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_devscalars")
+        f.argtypes, f.restype = symv_args, ci
     lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
     lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
     lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -283,6 +288,42 @@ def _symv_offset(prec):
     return call
 
 
+def _gemv_devscalars(prec):
+    def call(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+        wsp, wsb = _ws_args(workspace, lambda: gemv_workspace_bytes(
+            prec, trans if trans in tuple("NnTtCc") else "N", max(m, 0), max(n, 0)), y)
+        rc = getattr(lib, f"kmv_{prec}gemv_devscalars")(
+            trans.encode(), m, n, _ptr(alpha, prec), _ptr(A, prec), lda, _ptr(x, prec), incx, _ptr(beta, prec),
+            _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(f"{prec}gemv_devscalars", rc)
+        return rc
+    call.__name__ = f"{prec}gemv_devscalars"
+    call.__doc__ = "GEMV with alpha and beta given as one-element device tensors (or device addresses)."
+    return call
+
+
+def _symv_devscalars(prec):
+    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}_devscalars"
+
+    def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
+        wsp, wsb = _ws_args(workspace, lambda: symv_workspace_bytes(
+            prec, uplo if uplo in tuple("LlUu") else "L", max(n, 0)), y)
+        rc = getattr(lib, f"kmv_{name}")(
+            uplo.encode(), n, _ptr(alpha, prec), _ptr(A, prec), lda, _ptr(x, prec), incx, _ptr(beta, prec),
+            _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(name, rc)
+        return rc
+    call.__name__ = name
+    call.__doc__ = "SYMV / HEMV with alpha and beta given as one-element device tensors (or device addresses)."
+    return call
+
+
+GEMV_DEVSCALARS = {p_: _gemv_devscalars(p_) for p_ in "sdcz"}
+SYMV_DEVSCALARS = {p_: _symv_devscalars(p_) for p_ in "sdcz"}
+sgemv_devscalars, dgemv_devscalars, cgemv_devscalars, zgemv_devscalars = (GEMV_DEVSCALARS[p_] for p_ in "sdcz")
+ssymv_devscalars, dsymv_devscalars, chemv_devscalars, zhemv_devscalars = (SYMV_DEVSCALARS[p_] for p_ in "sdcz")
 sgemv_offset, dgemv_offset, cgemv_offset, zgemv_offset = (_gemv_offset(p_) for p_ in "sdcz")
 ssymv_offset, dsymv_offset, chemv_offset, zhemv_offset = (_symv_offset(p_) for p_ in "sdcz")
 GEMV_OFFSET = {"s": sgemv_offset, "d": dgemv_offset, "c": cgemv_offset, "z": zgemv_offset}

@@ -26,7 +26,8 @@ template <class T> inline T* vec_base(T* v, int64_t len, int64_t inc) {
 
 template <class T>
 int gemv_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x, int64_t incx,
-               const T* beta, T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream) {
+               const T* beta, T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream,
+               bool dev_scalars = false) {
     const bool notrans = (trans == 'N' || trans == 'n');
     const bool tr = (trans == 'T' || trans == 't');
     const bool ct = (trans == 'C' || trans == 'c');
@@ -37,13 +38,15 @@ int gemv_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int
     if (incx == 0) return -8;
     if (incy == 0) return -11;
     if (!alpha || !beta) return KMV_ERR_NULL;
-    const T al = *alpha, be = *beta;
-    if (m == 0 || n == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    // scalars in device memory are not looked at here: the quick returns that depend on their
+    // values do not apply, the epilogue kernels read them when they run
+    const T al = dev_scalars ? zero_of<T>() : *alpha, be = dev_scalars ? zero_of<T>() : *beta;
+    if (m == 0 || n == 0 || (!dev_scalars && is_zero(al) && is_one(be))) return KMV_OK;
     if (!A || !x || !y) return KMV_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t leny = notrans ? m : n, lenx = notrans ? n : m;
     T* yb = vec_base(y, leny, incy);
-    if (is_zero(al)) return hip_code(launch_scal<T>(leny, be, yb, incy, s));
+    if (!dev_scalars && is_zero(al)) return hip_code(launch_scal<T>(leny, be, yb, incy, s));
 
     const GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, A, lda);
     const bool need_ws = (incx != 1) || plan.splits > 1;
@@ -53,6 +56,7 @@ int gemv_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int
     GemvArgs<T> a;
     a.m = m; a.n = n; a.lda = lda; a.A = A;
     a.y = yb; a.incy = incy; a.alpha = al; a.beta = be;
+    if (dev_scalars) { a.alpha_dev = alpha; a.beta_dev = beta; }
     a.partial = plan.splits > 1 ? reinterpret_cast<T*>(ws + plan.partial_off) : nullptr;
     a.plan = plan;
     if (incx != 1) {
@@ -68,7 +72,7 @@ int gemv_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int
 
 template <class T>
 int symv_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, const T* x, int64_t incx, const T* beta,
-               T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream) {
+               T* y, int64_t incy, void* workspace, size_t workspace_bytes, void* stream, bool dev_scalars = false) {
     const bool lower = (uplo == 'L' || uplo == 'l');
     const bool upper = (uplo == 'U' || uplo == 'u');
     if (!lower && !upper) return -1;
@@ -77,12 +81,12 @@ int symv_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int6
     if (incx == 0) return -7;
     if (incy == 0) return -10;
     if (!alpha || !beta) return KMV_ERR_NULL;
-    const T al = *alpha, be = *beta;
-    if (n == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    const T al = dev_scalars ? zero_of<T>() : *alpha, be = dev_scalars ? zero_of<T>() : *beta;
+    if (n == 0 || (!dev_scalars && is_zero(al) && is_one(be))) return KMV_OK;
     if (!A || !x || !y) return KMV_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     T* yb = vec_base(y, n, incy);
-    if (is_zero(al)) return hip_code(launch_scal<T>(n, be, yb, incy, s));
+    if (!dev_scalars && is_zero(al)) return hip_code(launch_scal<T>(n, be, yb, incy, s));
 
     const SymvPlan<T> plan = plan_symv<T>(lower, n, A, lda);
     if (!workspace || workspace_bytes < plan.total_bytes || ((uintptr_t)workspace % WS_ALIGN) != 0)
@@ -91,6 +95,7 @@ int symv_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int6
     SymvArgs<T> a;
     a.n = n; a.lda = lda; a.A = A;
     a.y = yb; a.incy = incy; a.alpha = al; a.beta = be;
+    if (dev_scalars) { a.alpha_dev = alpha; a.beta_dev = beta; }
     a.wsn = reinterpret_cast<T*>(ws + plan.wsn_off);
     a.wst = reinterpret_cast<T*>(ws + plan.wst_off);
     a.wtab = reinterpret_cast<int*>(ws + plan.tab_off);
@@ -250,6 +255,31 @@ KMV_SYMV_OFFSET(kmv_dsymv_offset, double, double, false)
 KMV_SYMV_OFFSET(kmv_chemv_offset, kmv_complex64, cf32, true)
 KMV_SYMV_OFFSET(kmv_zhemv_offset, kmv_complex128, cf64, true)
 #undef KMV_SYMV_OFFSET
+
+// alpha and beta in device memory
+#define KMV_GEMV_DEVSCALARS(NAME, CT, T)                                                                          \
+    int NAME(char trans, int64_t m, int64_t n, const CT* alpha, const CT* A, int64_t lda, const CT* x,            \
+             int64_t incx, const CT* beta, CT* y, int64_t incy, void* ws, size_t wsb, void* stream) {             \
+        return gemv_entry<T>(trans, m, n, (const T*)alpha, (const T*)A, lda, (const T*)x, incx, (const T*)beta,   \
+                             (T*)y, incy, ws, wsb, stream, true);                                                 \
+    }
+KMV_GEMV_DEVSCALARS(kmv_sgemv_devscalars, float, float)
+KMV_GEMV_DEVSCALARS(kmv_dgemv_devscalars, double, double)
+KMV_GEMV_DEVSCALARS(kmv_cgemv_devscalars, kmv_complex64, cf32)
+KMV_GEMV_DEVSCALARS(kmv_zgemv_devscalars, kmv_complex128, cf64)
+#undef KMV_GEMV_DEVSCALARS
+
+#define KMV_SYMV_DEVSCALARS(NAME, CT, T, HERM)                                                                    \
+    int NAME(char uplo, int64_t n, const CT* alpha, const CT* A, int64_t lda, const CT* x, int64_t incx,          \
+             const CT* beta, CT* y, int64_t incy, void* ws, size_t wsb, void* stream) {                           \
+        return symv_entry<T>(HERM, uplo, n, (const T*)alpha, (const T*)A, lda, (const T*)x, incx, (const T*)beta, \
+                             (T*)y, incy, ws, wsb, stream, true);                                                 \
+    }
+KMV_SYMV_DEVSCALARS(kmv_ssymv_devscalars, float, float, false)
+KMV_SYMV_DEVSCALARS(kmv_dsymv_devscalars, double, double, false)
+KMV_SYMV_DEVSCALARS(kmv_chemv_devscalars, kmv_complex64, cf32, true)
+KMV_SYMV_DEVSCALARS(kmv_zhemv_devscalars, kmv_complex128, cf64, true)
+#undef KMV_SYMV_DEVSCALARS
 
 size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n) {
     switch (prec) {

@@ -27,7 +27,8 @@ constexpr int RD_OUT = 32, RD_GRP = 8;
 template <class T>
 __global__ __launch_bounds__(RD_OUT * RD_GRP) void reduce_kernel(const T* __restrict__ partial, int64_t splits,
                                                                   int64_t stride, int64_t off, int64_t len, T alpha,
-                                                                  T beta, T* y, int64_t incy) {
+                                                                  T beta, const T* alpha_dev, const T* beta_dev,
+                                                                  T* y, int64_t incy) {
     const int lx = threadIdx.x % RD_OUT, g = threadIdx.x / RD_OUT;
     const int64_t k = (int64_t)blockIdx.x * RD_OUT + lx;
     __shared__ T part[RD_GRP][RD_OUT];
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(RD_OUT * RD_GRP) void reduce_kernel(const T* __rest
 #pragma unroll
         for (int gg = 1; gg < RD_GRP; ++gg) tot = add_of(tot, part[gg][lx]);
         T* yp = y + k * incy;
-        *yp = epilogue(alpha, tot, beta, yp);
+        *yp = epilogue(scalar_of(alpha, alpha_dev), tot, scalar_of(beta, beta_dev), yp);
     }
 }
 
@@ -60,17 +61,18 @@ template <class T> hipError_t launch_scal(int64_t len, T beta, T* y, int64_t inc
 }
 template <class T>
 hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off, int64_t len, T alpha, T beta,
-                         T* y, int64_t incy, hipStream_t s) {
+                         const T* alpha_dev, const T* beta_dev, T* y, int64_t incy, hipStream_t s) {
     if (len <= 0) return hipSuccess;
     hipLaunchKernelGGL((reduce_kernel<T>), dim3((unsigned)ceil_div(len, RD_OUT)), dim3(RD_OUT * RD_GRP), 0, s, partial,
-                       splits, stride, off, len, alpha, beta, y, incy);
+                       splits, stride, off, len, alpha, beta, alpha_dev, beta_dev, y, incy);
     return hipGetLastError();
 }
 
 #define KMV_INSTANTIATE_AUX(T)                                                                              \
     template hipError_t launch_pack<T>(const T*, int64_t, int64_t, T*, hipStream_t);                        \
     template hipError_t launch_scal<T>(int64_t, T, T*, int64_t, hipStream_t);                               \
-    template hipError_t launch_reduce<T>(const T*, int64_t, int64_t, int64_t, int64_t, T, T, T*, int64_t, hipStream_t);
+    template hipError_t launch_reduce<T>(const T*, int64_t, int64_t, int64_t, int64_t, T, T, const T*, const T*, T*, \
+                                         int64_t, hipStream_t);
 KMV_INSTANTIATE_AUX(float)
 KMV_INSTANTIATE_AUX(double)
 KMV_INSTANTIATE_AUX(cf32)

@@ -90,9 +90,15 @@ __device__ __forceinline__ double real_part_only(double a) { return a; }
 __device__ __forceinline__ cf32 real_part_only(cf32 a) { return cf32{a.re, 0.f}; }
 __device__ __forceinline__ cf64 real_part_only(cf64 a) { return cf64{a.re, 0.0}; }
 
-// alpha*sum (+ beta*yold when beta != 0; yold is not read otherwise)
+// A scalar of the call: the value copied at enqueue time, or, when the caller keeps its scalars
+// in device memory, the value found there when the kernel runs (a wave-uniform load).
+template <class T> __device__ __forceinline__ T scalar_of(T value, const T* dev) { return dev ? *dev : value; }
+
+// alpha*sum (+ beta*yold when beta != 0; yold is not read otherwise).  alpha == 0 can only arrive
+// through a device-resident scalar (the host path returns earlier); the sum then does not count,
+// whatever it holds.
 template <class T> __device__ __forceinline__ T epilogue(T alpha, T sum, T beta, const T* yold) {
-    T r = mul_of(alpha, sum);
+    T r = is_zero(alpha) ? zero_of<T>() : mul_of(alpha, sum);
     if (!is_zero(beta)) r = add_of(r, mul_of(beta, *yold));
     return r;
 }

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
                 const int64_t row = r[t] + v;
                 if (row >= 0 && row < a.m) {
                     T* yp = a.y + row * a.incy;
-                    *yp = epilogue(a.alpha, acc[t][v], a.beta, yp);
+                    *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), acc[t][v], scalar_of(a.beta, a.beta_dev), yp);
                 }
             }
         } else {
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_short_kernel(GemvArgs<T> a) 
             const int64_t row = r[0] + v;
             if (row >= 0 && row < a.m) {
                 T* yp = a.y + row * a.incy;
-                *yp = epilogue(a.alpha, out.e[v], a.beta, yp);
+                *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), out.e[v], scalar_of(a.beta, a.beta_dev), yp);
             }
         }
     } else {
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
             for (int ww = 1; ww < NW; ++ww) s = add_of(s, red[ww][c]);
             if (a.plan.splits == 1) {
                 T* yp = a.y + j * a.incy;
-                *yp = epilogue(a.alpha, s, a.beta, yp);
+                *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), s, scalar_of(a.beta, a.beta_dev), yp);
             } else {
                 a.partial[(int64_t)blockIdx.y * a.plan.part_stride + j] = s;
             }
@@ -469,7 +469,7 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s)
         hipLaunchKernelGGL((gemv_n_short_kernel<T, GN_NW, GN_LOADS>), dim3((unsigned)a.plan.splits), dim3(GN_NW * WAVE), 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess || a.plan.splits == 1) return e;
-        return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.y, a.incy, s);
+        return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
     }
     const int64_t rt = a.plan.row_tiles;
     const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt));
@@ -480,7 +480,7 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s)
     else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.plan.splits == 1) return e;
-    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.y, a.incy, s);
+    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
 }
 
 template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s) {
@@ -499,7 +499,7 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.plan.splits == 1) return e;
-    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, 0, a.n, a.alpha, a.beta, a.y, a.incy, s);
+    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, 0, a.n, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
 }
 
 #define KMV_INSTANTIATE_GEMV(T)                                                              \

@@ -82,6 +82,8 @@ template <class T> struct GemvArgs {
     T* y;             // element k of y is y[k*incy] (base already moved for incy < 0)
     int64_t incy;
     T alpha, beta;
+    const T* alpha_dev = nullptr;   // non-null: alpha / beta are read from device memory by the epilogue
+    const T* beta_dev = nullptr;
     T* partial;       // [splits][part_stride]
     GemvPlan<T> plan;
 };
@@ -113,6 +115,8 @@ template <class T> struct SymvArgs {
     T* y;
     int64_t incy;
     T alpha, beta;
+    const T* alpha_dev = nullptr;   // non-null: alpha / beta are read from device memory by the epilogue
+    const T* beta_dev = nullptr;
     T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
     int* wtab;        // variant 2: [nchunks][2] first and last workgroup whose share touches the chunk
@@ -135,7 +139,8 @@ template <class T> hipError_t launch_pack(const T* src, int64_t inc, int64_t len
 template <class T> hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s);
 // y[k*incy] = alpha * sum_s partial[s*stride + off + k] + beta*y[k*incy], s ascending
 template <class T> hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off,
-                                            int64_t len, T alpha, T beta, T* y, int64_t incy, hipStream_t s);
+                                            int64_t len, T alpha, T beta, const T* alpha_dev, const T* beta_dev, T* y,
+                                            int64_t incy, hipStream_t s);
 
 hipError_t launch_stream_probe(int kind, int64_t n, const double* a, double* b, double* c, double* sink, hipStream_t s);
 

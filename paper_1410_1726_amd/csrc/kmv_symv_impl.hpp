@@ -689,7 +689,7 @@ __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) sum = add_of(sum, red[ww][c]);
         T* yp = a.y + (j0 + c) * a.incy;
-        *yp = epilogue(a.alpha, sum, a.beta, yp);
+        *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), sum, scalar_of(a.beta, a.beta_dev), yp);
     }
 }
 
@@ -740,7 +740,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 #pragma unroll
         for (int gg = 1; gg < RED_PARTS; ++gg) tot = add_of(tot, part[gg][lx]);
         T* yp = a.y + i * a.incy;
-        *yp = epilogue(a.alpha, tot, a.beta, yp);
+        *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), tot, scalar_of(a.beta, a.beta_dev), yp);
     }
 }
 

@@ -170,3 +170,26 @@ def test_offset_argument_errors(prec):
     assert symv(off=8) == 0
     assert symv(A=None) == kmv.ERR_NULL
     assert symv() == kmv.ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+def test_devscalars_argument_errors(prec):
+    """argument checks come before anything is read or enqueued; the scalars are device addresses here and
+    are never dereferenced on the host"""
+    g, f = kmv.GEMV_DEVSCALARS[prec], kmv.SYMV_DEVSCALARS[prec]
+
+    def gemv(trans="N", m=8, n=6, lda=8, incx=1, incy=1, alpha=DUMMY, beta=DUMMY, A=DUMMY):
+        return g(trans, m, n, alpha, A, lda, DUMMY, incx, beta, DUMMY, incy, workspace=NOWS, stream=0, check=False)
+
+    def symv(uplo="L", n=8, lda=8, incx=1, alpha=DUMMY, beta=DUMMY, A=DUMMY):
+        return f(uplo, n, alpha, A, lda, DUMMY, incx, beta, DUMMY, 1, workspace=NOWS, stream=0, check=False)
+
+    assert gemv(trans="X") == -1 and gemv(m=-1) == -2 and gemv(n=-1) == -3 and gemv(lda=7) == -6
+    assert gemv(incx=0) == -8 and gemv(incy=0) == -11
+    assert gemv(alpha=None) == kmv.ERR_NULL and gemv(beta=None) == kmv.ERR_NULL and gemv(A=None) == kmv.ERR_NULL
+    assert gemv(m=0) == 0 and gemv(n=0) == 0
+    assert gemv(incx=2) == kmv.ERR_WORKSPACE
+    assert symv(uplo="N") == -1 and symv(n=-1) == -2 and symv(lda=7) == -5 and symv(incx=0) == -7
+    assert symv(alpha=None) == kmv.ERR_NULL and symv(A=None) == kmv.ERR_NULL
+    assert symv(n=0, lda=1) == 0
+    assert symv() == kmv.ERR_WORKSPACE

@@ -384,6 +384,100 @@ def test_offset_calls_name_the_parent(prec):
         check(prec, errors(prec, got_all[off:], want, den, nb), f"symv/hemv_offset {prec} {uplo} offset {off}")
 
 
+@pytest.mark.parametrize("prec", PRECS)
+def test_scalars_in_device_memory(prec):
+    """`_devscalars` entry points: alpha and beta are read from device memory by every kernel that ends a
+    product (fused epilogues of the GEMV-N, short GEMV-N, GEMV-T and small SYMV kernels, the GEMV and SYMV
+    final passes).  Same kernels and arithmetic as the host-scalar calls, so results are compared bitwise
+    with those (which the other tests hold against the oracle); the value-dependent cases alpha = 0 and
+    beta = 0 are checked against their definition."""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    al_v, be_v = scalars(prec, 0.7, -0.3)
+    al = torch.tensor([al_v], dtype=dt, device=DEV)
+    be = torch.tensor([be_v], dtype=dt, device=DEV)
+    zero = torch.zeros(1, dtype=dt, device=DEV)
+    one = torch.ones(1, dtype=dt, device=DEV)
+    nan = float("nan")
+
+    def has_nan(t):
+        return bool(torch.isnan(torch.view_as_real(t) if t.is_complex() else t).any())
+
+    try:
+        # (tuning, trans, m, n): every way a GEMV ends
+        for tune, trans, m, n in (({}, "N", 3000, 2000), ({"gemv_n_splits": 1}, "N", 1500, 700), ({}, "N", 64, 9000),
+                                  ({"gemv_n_splits": 1}, "N", 64, 3000),
+                                  ({}, "T", 2000, 3000), ({}, "C", 5000, 40), ({}, "T", 100, 5000)):
+            for key, v in tune.items():
+                k.set_tuning(key, v)
+            A = wl.matrix(prec, m, n, m + 3, seed=7, device=DEV)
+            lenx, leny = (n, m) if trans == "N" else (m, n)
+            x = wl.vector(prec, lenx, 1, seed=7, which=1, device=DEV)
+            y0 = wl.vector(prec, leny, 2, seed=7, which=2, device=DEV, gap_value=nan)
+            want, got = y0.clone(), y0.clone()
+            k.GEMV[prec](trans, m, n, al_v, A, m + 3, x, 1, be_v, want, 2)
+            k.GEMV_DEVSCALARS[prec](trans, m, n, al, A, m + 3, x, 1, be, got, 2)
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), (trans, m, n, tune)
+            # alpha = 0 on the device: beta*y exactly, although A and x hold NaN
+            An, xn = torch.full_like(A, nan), torch.full_like(x, nan)
+            got = y0.clone()
+            k.GEMV_DEVSCALARS[prec](trans, m, n, zero, An, m + 3, xn, 1, be, got, 2)
+            want = y0.clone()
+            k.GEMV[prec](trans, m, n, 0.0, An, m + 3, xn, 1, be_v, want, 2)
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+            assert not has_nan(got[::2])
+            # beta = 0 on the device: y is not read
+            got = torch.full_like(y0, nan)
+            want = torch.full_like(y0, nan)
+            k.GEMV_DEVSCALARS[prec](trans, m, n, al, A, m + 3, x, 1, zero, got, 2)
+            k.GEMV[prec](trans, m, n, al_v, A, m + 3, x, 1, 0.0, want, 2)
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+            assert not has_nan(got[::2])
+            # alpha = 0, beta = 1: y keeps its values
+            got = y0.clone()
+            k.GEMV_DEVSCALARS[prec](trans, m, n, zero, An, m + 3, xn, 1, one, got, 2)
+            assert torch.equal(got.view(torch.uint8), y0.view(torch.uint8))
+            for key in tune:
+                k.set_tuning(key, 0)
+        for variant, n in ((3, 700), (2, 2500), (1, 2500)):
+            k.set_tuning("symv_variant", variant)
+            for uplo in "LU":
+                A = wl.poison_triangle(wl.matrix(prec, n, n, n + 5, seed=8, device=DEV), n, uplo)
+                x = wl.vector(prec, n, 1, seed=8, which=1, device=DEV)
+                y0 = wl.vector(prec, n, 1, seed=8, which=2, device=DEV)
+                want, got = y0.clone(), y0.clone()
+                k.SYMV[prec](uplo, n, al_v, A, n + 5, x, 1, be_v, want, 1)
+                k.SYMV_DEVSCALARS[prec](uplo, n, al, A, n + 5, x, 1, be, got, 1)
+                assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), (variant, uplo)
+                assert not has_nan(got)
+                got = y0.clone()
+                k.SYMV_DEVSCALARS[prec](uplo, n, zero, torch.full_like(A, nan), n + 5, torch.full_like(x, nan), 1, be, got, 1)
+                want = y0.clone()
+                k.SYMV[prec](uplo, n, 0.0, A, n + 5, x, 1, be_v, want, 1)
+                assert torch.equal(got, want)
+                got = torch.full_like(y0, nan)
+                want = torch.full_like(y0, nan)
+                k.SYMV_DEVSCALARS[prec](uplo, n, al, A, n + 5, x, 1, zero, got, 1)
+                k.SYMV[prec](uplo, n, al_v, A, n + 5, x, 1, 0.0, want, 1)
+                assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+        # a scalar produced by an earlier kernel on the stream is seen without a host synchronisation
+        k.set_tuning("symv_variant", 0)
+        n = 1000
+        A = wl.matrix(prec, n, n, n, seed=9, device=DEV)
+        x = wl.vector(prec, n, 1, seed=9, which=1, device=DEV)
+        y0 = wl.vector(prec, n, 1, seed=9, which=2, device=DEV)
+        dyn = torch.zeros(1, dtype=dt, device=DEV)
+        got = y0.clone()
+        dyn.copy_(x[:1] * 2)                 # device-side producer
+        k.GEMV_DEVSCALARS[prec]("N", n, n, dyn, A, n, x, 1, one, got, 1)
+        want = y0.clone()
+        k.GEMV[prec]("N", n, n, complex(dyn.cpu()[0]) if dt.is_complex else float(dyn.cpu()[0]), A, n, x, 1, 1.0, want, 1)
+        assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+    finally:
+        for key in k.tuning_keys():
+            k.set_tuning(key, 0)
+
+
 def test_runs_on_a_side_stream_with_explicit_workspace():
     k = kmv()
     n = 2000
