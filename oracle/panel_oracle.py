@@ -1,0 +1,95 @@
+"""CPU oracle for the panel step of the symmetric tridiagonal reduction (test
+infrastructure, never the product path).
+
+The paper's Section 10 speeds up the two-sided reductions by replacing their
+matrix-vector products: the tridiagonal reduction calls SYMV on the trailing
+block once per column and GEMV on the tall panels of reflectors that have
+accumulated so far.  The paper does not print that algorithm; this file writes
+out the published one (the "latrd" panel step of the blocked Householder
+tridiagonalisation, lower storage), column by column, with plain numpy
+products in extended precision and nothing blocked or fused:
+
+for column i of the first nb columns of the symmetric n x n matrix A (lower
+triangle referenced), with V = the reflector vectors and W the companion
+vectors of the columns before i:
+
+  1. bring column i up to date:   a = A[i:, i] - V[i:, :i] W[i, :i]^T - W[i:, :i] V[i, :i]^T
+     (the diagonal entry d_i = a[0] is final)
+  2. reflector for a[1:]:  alpha = a[1], x = a[2:], xnorm = ||x||_2;
+       xnorm == 0:  tau = 0, beta = alpha
+       else:        beta = -sign(alpha) * sqrt(alpha^2 + xnorm^2), tau = (beta - alpha) / beta,
+                    x <- x / (alpha - beta)
+     e_i = beta; v = [1, x] is stored in A[i+1:, i]  (the leading one explicitly)
+  3. w = A[i+1:, i+1:] v                        (the symmetric product with the ORIGINAL trailing block)
+     w <- w - V[i+1:, :i] (W[i+1:, :i]^T v) - W[i+1:, :i] (V[i+1:, :i]^T v)
+     w <- tau * w;   w <- w - (tau/2) (w^T v) v
+     W[i+1:, i] = w, W[:i, i] holds the last small product V[i+1:, :i]^T v (scratch, as in the published routine)
+
+so that after the panel  A - V W^T - W V^T  restricted to the trailing block is
+the orthogonally transformed trailing block, and the first nb columns are
+tridiagonal with diagonal d and subdiagonal e.  No rescaling against underflow
+of xnorm is done (inputs here are O(1)).
+
+V lives in A below the diagonal of the first nb columns: V[:, j] has zeros in
+rows 0..j, a one in row j+1 and the scaled x below.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_WIDE = {np.dtype(np.float32): np.float64, np.dtype(np.float64): np.longdouble}
+
+
+def sytrd_panel(A, nb, *, wide=True):
+    """Panel step on a copy of the symmetric matrix whose lower triangle is in
+    ``A`` (n x n numpy array; the strict upper triangle is never read).
+
+    Returns ``dict(A=..., e=..., tau=..., W=...)``: ``A`` with the first ``nb``
+    columns overwritten (diagonal d, ones on the subdiagonal, reflector tails
+    below), ``e`` and ``tau`` of length ``nb``, ``W`` of shape ``(n, nb)``.
+    With ``wide`` all arithmetic runs in the next wider type (float64 for
+    float32 input, long double for float64) and the results stay in it.
+    """
+    A = np.asarray(A)
+    n = A.shape[0]
+    assert A.shape == (n, n) and 0 <= nb <= n
+    dt = _WIDE[A.dtype] if wide else A.dtype.type
+    # only the lower triangle is taken from the input; work on the completed matrix so that
+    # the trailing symmetric product is a plain matrix-vector product
+    L = np.tril(A).astype(dt)
+    S = L + np.tril(L, -1).T
+    out = L.copy()
+    V = np.zeros((n, nb), dtype=dt)
+    W = np.zeros((n, nb), dtype=dt)
+    e = np.zeros(nb, dtype=dt)
+    tau = np.zeros(nb, dtype=dt)
+    for i in range(nb):
+        a = S[i:, i].copy()
+        if i:
+            a = a - V[i:, :i] @ W[i, :i] - W[i:, :i] @ V[i, :i]
+        out[i:, i] = a
+        if i >= n - 1:
+            continue
+        alpha = a[1]
+        x = a[2:].copy()
+        xnorm = np.sqrt(np.sum(x * x)) if x.size else dt(0)
+        if xnorm == 0:
+            beta, t = alpha, dt(0)
+        else:
+            beta = -np.copysign(np.sqrt(alpha * alpha + xnorm * xnorm), alpha)
+            t = (beta - alpha) / beta
+            x = x / (alpha - beta)
+        e[i], tau[i] = beta, t
+        v = np.concatenate(([dt(1)], x))
+        V[i + 1:, i] = v
+        out[i + 1:, i] = v
+        w = S[i + 1:, i + 1:] @ v
+        if i:
+            W[:i, i] = W[i + 1:, :i].T @ v
+            w = w - V[i + 1:, :i] @ W[:i, i]
+            W[:i, i] = V[i + 1:, :i].T @ v
+            w = w - W[i + 1:, :i] @ W[:i, i]
+        w = t * w
+        w = w - (t / 2) * (w @ v) * v
+        W[i + 1:, i] = w
+    return dict(A=out, e=e, tau=tau, W=W)

@@ -1,0 +1,117 @@
+"""Pins of the panel-step oracle (`oracle/panel_oracle.py`) against things it does not compute itself:
+a hand-worked 3 x 3 case, and numpy linear algebra on the explicitly formed reflectors (orthogonality,
+tridiagonal leading columns, the trailing-block identity, eigenvalues of a full reduction)."""
+import numpy as np
+import pytest
+
+from oracle import panel_oracle as po
+
+
+def sym_lower(rng, n, dtype=np.float64):
+    """random symmetric matrix given by its lower triangle; the strict upper triangle is NaN"""
+    A = rng.uniform(-1, 1, (n, n)).astype(dtype)
+    A[np.triu_indices(n, 1)] = np.nan
+    return A
+
+
+def completed(A):
+    L = np.tril(A).astype(np.float64)
+    return L + np.tril(L, -1).T
+
+
+def reflectors(res, n, nb):
+    """V (n x nb, zero above the leading ones) from the panel result"""
+    V = np.zeros((n, nb))
+    for j in range(min(nb, n - 1)):
+        V[j + 1:, j] = np.asarray(res["A"][j + 1:, j], dtype=np.float64)
+    return V
+
+
+def q_of(V, tau):
+    n, nb = V.shape
+    Q = np.eye(n)
+    for j in range(nb):
+        Q = Q @ (np.eye(n) - float(tau[j]) * np.outer(V[:, j], V[:, j]))
+    return Q
+
+
+def test_hand_worked_three_by_three():
+    # a = (4,3,4): alpha = 3, x = (4), beta = -5, tau = 8/5, v = (1, 1/2);
+    # S22 v = (5/2, 7/2), times tau = (4, 28/5), w.v = 34/5, w - (4/5)(34/5) v = (-36/25, 72/25)
+    A = np.array([[4.0, np.nan, np.nan], [3.0, 2.0, np.nan], [4.0, 1.0, 5.0]])
+    r = po.sytrd_panel(A, 1)
+    assert float(r["e"][0]) == -5.0 and abs(float(r["tau"][0]) - 1.6) < 1e-18
+    assert float(r["A"][0, 0]) == 4.0 and float(r["A"][1, 0]) == 1.0 and float(r["A"][2, 0]) == 0.5
+    assert np.allclose(np.asarray(r["W"][:, 0], dtype=np.float64), [0.0, -1.44, 2.88], rtol=0, atol=1e-15)
+    # the untouched trailing columns keep their input values
+    assert float(r["A"][1, 1]) == 2.0 and float(r["A"][2, 1]) == 1.0 and float(r["A"][2, 2]) == 5.0
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("n,nb", [(2, 1), (5, 2), (40, 8), (97, 32), (64, 64), (33, 33)])
+def test_similarity_transform_identities(dtype, n, nb):
+    rng = np.random.default_rng(n * 100 + nb)
+    A = sym_lower(rng, n, dtype)
+    S = completed(A)
+    r = po.sytrd_panel(A, nb)
+    assert np.all(np.isfinite(np.asarray(r["W"], dtype=np.float64))), "the NaN triangle was read"
+    V = reflectors(r, n, nb)
+    tau = np.asarray(r["tau"], dtype=np.float64)
+    W = np.asarray(r["W"], dtype=np.float64).copy()
+    for j in range(nb):
+        W[: j + 1, j] = 0.0                   # rows 0..j of column j are scratch / not part of w_j
+        vv = V[:, j] @ V[:, j]
+        assert tau[j] == 0 or abs(tau[j] * vv - 2.0) < 1e-13, "H_j is not orthogonal"
+        if j < n - 1:
+            assert V[j + 1, j] == 1.0
+    Q = q_of(V, tau)
+    assert np.allclose(Q.T @ Q, np.eye(n), atol=1e-13)
+    T = Q.T @ S @ Q
+    d = np.asarray(np.diag(r["A"]), dtype=np.float64)
+    e = np.asarray(r["e"], dtype=np.float64)
+    scale = np.linalg.norm(S)
+    for j in range(nb):
+        assert abs(T[j, j] - d[j]) < 1e-13 * scale
+        if j < n - 1:
+            assert abs(T[j + 1, j] - e[j]) < 1e-13 * scale
+            assert np.all(np.abs(T[j + 2:, j]) < 1e-13 * scale), "column is not reduced"
+    # trailing block: A - V W^T - W V^T equals the transformed matrix there
+    upd = S - V @ W.T - W @ V.T
+    assert np.allclose(upd[nb:, nb:], T[nb:, nb:], atol=1e-12 * scale)
+
+
+def test_full_reduction_keeps_eigenvalues():
+    rng = np.random.default_rng(5)
+    n = 48
+    A = sym_lower(rng, n)
+    r = po.sytrd_panel(A, n)
+    d = np.asarray(np.diag(r["A"]), dtype=np.float64)
+    e = np.asarray(r["e"], dtype=np.float64)[: n - 1]
+    T = np.diag(d) + np.diag(e, -1) + np.diag(e, 1)
+    assert np.allclose(np.linalg.eigvalsh(T), np.linalg.eigvalsh(completed(A)), atol=1e-12)
+
+
+def test_already_reduced_inputs():
+    n = 12
+    rng = np.random.default_rng(6)
+    # diagonal matrix: nothing to annihilate, alpha = 0: tau = 0, e = 0
+    D = np.diag(rng.uniform(1, 2, n))
+    r = po.sytrd_panel(D, 5)
+    assert np.all(np.asarray(r["tau"], dtype=np.float64) == 0) and np.all(np.asarray(r["e"], dtype=np.float64) == 0)
+    # tridiagonal matrix: tau = 0 and e is the subdiagonal, d the diagonal
+    sub = rng.uniform(1, 2, n - 1)
+    T = D + np.diag(sub, -1)
+    r = po.sytrd_panel(T, 6)
+    assert np.all(np.asarray(r["tau"], dtype=np.float64) == 0)
+    assert np.array_equal(np.asarray(r["e"], dtype=np.float64), sub[:6])
+    assert np.array_equal(np.asarray(np.diag(r["A"]), dtype=np.float64)[:6], np.diag(D)[:6])
+    assert np.all(np.asarray(r["W"], dtype=np.float64) == 0)
+
+
+def test_working_precision_mode_is_close_to_the_wide_one():
+    rng = np.random.default_rng(7)
+    A = sym_lower(rng, 60, np.float32)
+    a = po.sytrd_panel(A, 16, wide=False)
+    b = po.sytrd_panel(A, 16, wide=True)
+    assert a["W"].dtype == np.float32 and b["W"].dtype == np.float64
+    assert np.linalg.norm(a["W"] - b["W"]) < 1e-5 * np.linalg.norm(b["W"])
