@@ -47,7 +47,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "csymv", "rect", "tiny"])
+    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "csymv", "rect", "tiny"])
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
@@ -216,6 +216,63 @@ def tiny_latency(k, torch, wl):
 
 
 # ------------------------------------------------------------ CPU baseline ----
+def sytrd_panel_bench(args, k, torch, wl, acc):
+    """One step = the panel step of the tridiagonal reduction (kmv_dsytrd_panel) on the first 64 columns of a
+    16384 x 16384 fp64 matrix: per column one DSYMV on the trailing block, two DGEMV-N with strided x, two
+    DGEMV-T and two DGEMV-N on the reflector panels and two small vector kernels, all enqueued without a host
+    round trip.  The matrix is restored from a copy before every step, outside the timed brackets."""
+    n, nb, prec = 16384, 64, "d"
+    A0 = wl.matrix(prec, n, n, n, seed=0, device="cuda")
+    A = A0.clone()
+    dt = wl.TORCH_DTYPES[prec]
+    W = torch.zeros((nb, n), dtype=dt, device="cuda")
+    e = torch.zeros(nb, dtype=dt, device="cuda")
+    tau = torch.zeros(nb, dtype=dt, device="cuda")
+    ws = k.workspace(k.sytrd_panel_workspace_bytes(prec, n, nb))
+    stream = torch.cuda.current_stream()
+    nbytes = nflops = 0
+    for i in range(nb):
+        ops = [("gemv_n", n - i, i)] * 2 if i else []
+        m = n - i - 1
+        ops += [("symv_l", m, m)] + ([("gemv_t", m, i), ("gemv_n", m, i)] * 2 if i else [])
+        for op, mm, nn in ops:
+            nbytes += acc.algorithmic_bytes(op, prec, mm, nn)
+            nflops += acc.flops(op, prec, mm, nn)
+        nbytes += 6 * m * 8            # the two vector kernels: v read and written, then w and v read, w written
+    times = []
+    for step in range(args.warmup + args.steps):
+        A.copy_(A0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        k.dsytrd_panel("L", n, nb, A, n, e, tau, W, n, workspace=ws)
+        e1.record(stream)
+        host_ms = (time.perf_counter() - t0) * 1e3
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        if step >= args.warmup:
+            times.append((wall_ms, e0.elapsed_time(e1), host_ms))
+    step_ms = sum(t[0] for t in times) / len(times)
+    value = nbytes / (step_ms * 1e-3) / 1e9
+    symv_bytes = sum(acc.algorithmic_bytes("symv_l", prec, n - i - 1, n - i - 1) for i in range(nb))
+    return {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "panel step of the tridiagonal reduction (kmv_dsytrd_panel), n=16384, nb=64, lda=n, "
+                               "U[-1,1]: 64 DSYMV on trailing blocks + 378 DGEMV on reflector panels + 128 vector kernels",
+                   "products_per_step": nb + 6 * (nb - 1)},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "gflops": round(nflops / (step_ms * 1e-3) / 1e9, 1),
+        "device_ms_per_step": round(sum(t[1] for t in times) / len(times), 3),
+        "host_enqueue_ms_per_step": round(sum(t[2] for t in times) / len(times), 3),
+        "symv_share_of_bytes": round(symv_bytes / nbytes, 4),
+        "roofline": None,
+    }
+
+
 def cpu_baseline(acc, wl):
     """The oracle as it stands (working-precision mode, OpenMP over outputs) on a
     bounded sample of the sweep: one product per routine family at one size."""
@@ -291,6 +348,10 @@ def main():
     for kv in args.tuning:
         key, v = kv.split("=")
         k.set_tuning(key, int(v))
+
+    if args.workload == "sytrd":
+        print(json.dumps(sytrd_panel_bench(args, k, torch, wl, acc)))
+        return
 
     # largest products first: the host runs ahead of the device, so the short
     # products at the end of a step are already queued when their turn comes

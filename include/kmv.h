@@ -205,6 +205,35 @@ int kmv_zhemv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, cons
                          const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
                          int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Panel step of the symmetric tridiagonal reduction (Section 10: the
+ * two-sided reductions are where these products are spent; SYMV on the
+ * trailing block and GEMV on the reflector panels, all on sub-blocks at
+ * arbitrary offsets, Section 6.6).  A second workload built on the entry
+ * points above, for s and d, lower storage only (uplo 'L').
+ * For the first nb columns of the symmetric n x n matrix A (device, lower
+ * triangle referenced, never the strict upper one): column i is brought up to
+ * date with the reflectors before it, a Householder reflector H_i = I - tau_i
+ * v_i v_i^T annihilates its entries below the subdiagonal, and w_i is formed so
+ * that A - V W^T - W V^T on the trailing block is the transformed block.
+ * On exit (all device memory): A[i][i] = d_i; A[i+1][i] = 1 and A[i+2..][i] =
+ * the rest of v_i; e[i] the subdiagonal entry, tau[i]; W (n x nb, leading
+ * dimension ldw >= n) holds w_i in W[i+1..n-1][i] (rows 0..i of column i are
+ * scratch).  Columns nb..n-1 of A are not modified.  A column without entries
+ * below the subdiagonal gets tau = 0 (e = the subdiagonal entry as it stands;
+ * both 0 for the last column of the matrix).  Norms are formed without
+ * rescaling against underflow or overflow.
+ * Only enqueues kernels on `stream` (about nine per column; tau and the inner
+ * products stay on the device), so a panel can be captured in a graph.
+ * Workspace: kmv_sytrd_panel_workspace_bytes(prec, n, nb), 256-byte aligned.
+ * Errors: negated argument number (uplo 1, n 2, nb 3 (0 <= nb <= min(n, 1024)), lda 5,
+ * ldw 9), KMV_ERR_NULL, KMV_ERR_WORKSPACE, or the code of a failing launch,
+ * in which case the columns before it are done and A is left in between. */
+int kmv_ssytrd_panel(char uplo, int64_t n, int64_t nb, float* A, int64_t lda, float* e, float* tau, float* W,
+                     int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_dsytrd_panel(char uplo, int64_t n, int64_t nb, double* A, int64_t lda, double* e, double* tau, double* W,
+                     int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
+size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
+
 /* ---- Workspace sizes (bytes; an upper bound valid for every pointer
  * alignment, every increment and every tuning value).  prec is 's','d','c'
  * or 'z'.  The workspace holds the packed copy of a strided x and the

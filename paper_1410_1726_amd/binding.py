@@ -57,6 +57,10 @@ def _load() -> ctypes.CDLL:
         f.argtypes, f.restype = gemv_args, ci
         f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_devscalars")
         f.argtypes, f.restype = symv_args, ci
+    for p_ in "sd":
+        f = getattr(lib, f"kmv_{p_}sytrd_panel")
+        f.argtypes, f.restype = [ch, i64, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp], ci
+    lib.kmv_sytrd_panel_workspace_bytes.argtypes, lib.kmv_sytrd_panel_workspace_bytes.restype = [ch, i64, i64], sz
     lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
     lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
     lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -320,6 +324,26 @@ def _symv_devscalars(prec):
     return call
 
 
+def sytrd_panel_workspace_bytes(prec, n, nb) -> int:
+    return int(lib.kmv_sytrd_panel_workspace_bytes(prec.encode(), n, nb))
+
+
+def _sytrd_panel(prec):
+    def call(uplo, n, nb, A, lda, e, tau, W, ldw, workspace=None, stream=None, check=True):
+        wsp, wsb = _ws_args(workspace, lambda: sytrd_panel_workspace_bytes(prec, max(n, 0), max(min(nb, n), 0)), A)
+        rc = getattr(lib, f"kmv_{prec}sytrd_panel")(
+            uplo.encode(), n, nb, _ptr(A, prec), lda, _ptr(e, prec), _ptr(tau, prec), _ptr(W, prec), ldw,
+            ctypes.c_void_p(wsp), wsb, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(f"{prec}sytrd_panel", rc)
+        return rc
+    call.__name__ = f"{prec}sytrd_panel"
+    call.__doc__ = "Panel step of the symmetric tridiagonal reduction on device tensors (see include/kmv.h)."
+    return call
+
+
+SYTRD_PANEL = {p_: _sytrd_panel(p_) for p_ in "sd"}
+ssytrd_panel, dsytrd_panel = SYTRD_PANEL["s"], SYTRD_PANEL["d"]
 GEMV_DEVSCALARS = {p_: _gemv_devscalars(p_) for p_ in "sdcz"}
 SYMV_DEVSCALARS = {p_: _symv_devscalars(p_) for p_ in "sdcz"}
 sgemv_devscalars, dgemv_devscalars, cgemv_devscalars, zgemv_devscalars = (GEMV_DEVSCALARS[p_] for p_ in "sdcz")

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkmv.so")
 SOURCES = ["kmv_symv_real.hip", "kmv_symv_herm.hip", "kmv_symv_csym.hip", "kmv_gemv.hip", "kmv_api.hip",
-           "kmv_aux.hip"]
+           "kmv_aux.hip", "kmv_panel.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -1,0 +1,256 @@
+// Panel step of the symmetric tridiagonal reduction, built on the library's own
+// SYMV and GEMV calls (paper, Section 10: the two-sided reductions spend their
+// memory-bound time in exactly these products - SYMV on the trailing block once
+// per column, GEMV on the tall panels of accumulated reflectors - and always on
+// sub-blocks that start at arbitrary offsets inside the matrix, Section 6.6).
+//
+// The step is the published "latrd" panel of the blocked Householder
+// tridiagonalisation, lower storage, written from its definition:
+//   column i:  a  = A[i:,i] - V[i:,:i] W[i,:i]^T - W[i:,:i] V[i,:i]^T        (2 GEMV-N, strided x)
+//              reflector (beta, tau, v) that annihilates a[2:]                (one small kernel)
+//              w  = A[i+1:,i+1:] v                                            (SYMV, trailing block)
+//              w -= V[i+1:,:i] (W[i+1:,:i]^T v) + W[i+1:,:i] (V[i+1:,:i]^T v) (2 GEMV-T, 2 GEMV-N)
+//              w  = tau w;  w -= (tau/2)(w.v) v                               (one small kernel)
+// Everything stays on the device and on the caller's stream: tau and the dot
+// product never visit the host, so a whole panel is one uninterrupted sequence of
+// launches (and can be captured in a graph).  The matrix-vector products go
+// through the public entry points, i.e. through the same argument checks,
+// planners and kernels as any other caller's.
+#include "../../include/kmv.h"
+#include "kmv_common.hpp"
+
+namespace kmv {
+namespace {
+
+constexpr int PT = 1024;   // threads of the two single-workgroup vector kernels
+
+// Sum over the workgroup in a fixed order: lanes by DPP, then the waves' sums in wave order.
+template <class T> __device__ __forceinline__ T block_sum(T v, T* red) {
+    const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE;
+    const T s = wave_sum(v);
+    __syncthreads();             // red may still be read from an earlier call
+    if (lane == 0) red[w] = s;
+    __syncthreads();
+    T tot = red[0];
+#pragma unroll
+    for (int k = 1; k < PT / WAVE; ++k) tot += red[k];
+    return tot;
+}
+
+// The two vector kernels run in one workgroup (their sums need no second launch then); each thread
+// keeps PU independent loads in flight per pass, which is what their time depends on.
+constexpr int PU = 8;
+
+// Householder reflector for the vector (alpha, x) stored in col[0..m-1]: on exit col = (1, x / (alpha - beta)),
+// *e = beta = -sign(alpha) * ||(alpha, x)||, *tau = (beta - alpha) / beta; a zero x gives tau = 0, beta = alpha.
+template <class T> __global__ __launch_bounds__(PT) void reflector_kernel(int64_t m, T* col, T* e, T* tau) {
+    __shared__ T red[PT / WAVE];
+    const T alpha = col[0];
+    T ss = 0;
+    for (int64_t base = 1 + threadIdx.x; base < m; base += (int64_t)PU * PT) {
+        T x[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            x[u] = k < m ? col[k] : T(0);
+        }
+#pragma unroll
+        for (int u = 0; u < PU; ++u) ss += x[u] * x[u];
+    }
+    const T xnorm = sqrt(block_sum(ss, red));    // every thread has read col[0] once this returns
+    T beta = alpha, t = 0;
+    if (xnorm != 0) {
+        beta = -copysign(sqrt(alpha * alpha + xnorm * xnorm), alpha);
+        t = (beta - alpha) / beta;
+        const T scale = T(1) / (alpha - beta);
+        for (int64_t base = 1 + threadIdx.x; base < m; base += (int64_t)PU * PT) {
+            T x[PU];
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                const int64_t k = base + (int64_t)u * PT;
+                x[u] = k < m ? col[k] : T(0);
+            }
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                const int64_t k = base + (int64_t)u * PT;
+                if (k < m) col[k] = x[u] * scale;
+            }
+        }
+    }
+    if (threadIdx.x == 0) {
+        col[0] = 1;
+        *e = beta;
+        *tau = t;
+    }
+}
+
+// w <- tau w - (tau/2) ((tau w).v) v.  Then, for the next column's update, the first `cnt` entries of the
+// next row of W and of V (element j at wnext[j*ldw], vnext[j*ldv]; the last one of W is w[0], just written)
+// are copied to the contiguous wrow / vrow, which spares that column two launches for packing strided rows.
+template <class T>
+__global__ __launch_bounds__(PT) void finish_w_kernel(int64_t m, const T* tau, const T* v, T* w, const T* wnext,
+                                                      int64_t ldw, const T* vnext, int64_t ldv, int cnt, T* wrow,
+                                                      T* vrow) {
+    __shared__ T red[PT / WAVE];
+    const T t = *tau;
+    T part = 0;
+    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
+        T wv[PU], vv[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            wv[u] = k < m ? w[k] : T(0);
+            vv[u] = k < m ? v[k] : T(0);
+        }
+#pragma unroll
+        for (int u = 0; u < PU; ++u) part += (t * wv[u]) * vv[u];
+    }
+    const T c = T(-0.5) * t * block_sum(part, red);
+    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
+        T wv[PU], vv[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            wv[u] = k < m ? w[k] : T(0);
+            vv[u] = k < m ? v[k] : T(0);
+        }
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            if (k < m) w[k] = t * wv[u] + c * vv[u];
+        }
+    }
+    __syncthreads();     // w[0] is in place for every thread of the workgroup
+    if ((int)threadIdx.x < cnt) {
+        wrow[threadIdx.x] = wnext[threadIdx.x * ldw];
+        vrow[threadIdx.x] = vnext[threadIdx.x * ldv];
+    }
+}
+
+// e and tau of a column that has no reflector (a fill kernel rather than a memset node, so that a
+// captured panel holds kernels only)
+template <class T> __global__ void no_reflector_kernel(T* e, T* tau) {
+    *e = 0;
+    *tau = 0;
+}
+
+template <class T> struct Calls;
+template <> struct Calls<float> {
+    static constexpr char prec = 's';
+    static constexpr auto gemv = kmv_sgemv;
+    static constexpr auto symv = kmv_ssymv;
+};
+template <> struct Calls<double> {
+    static constexpr char prec = 'd';
+    static constexpr auto gemv = kmv_dgemv;
+    static constexpr auto symv = kmv_dsymv;
+};
+
+inline size_t max_of(size_t a, size_t b) { return a > b ? a : b; }
+
+// bytes at the front of the workspace for the two packed rows (nb elements each)
+template <class T> size_t rows_bytes(int64_t nb) {
+    return (size_t)((2 * nb * sizeof(T) + 255) / 256) * 256;
+}
+
+// the packed rows plus the largest workspace any product of the panel asks for
+template <class T> size_t panel_workspace(int64_t n, int64_t nb) {
+    if (n <= 0 || nb <= 0) return 0;
+    if (nb > n) nb = n;
+    size_t need = 0;
+    for (int64_t i = 0; i < nb; ++i) {
+        need = max_of(need, kmv_gemv_workspace_bytes(Calls<T>::prec, 'N', n - i, i));
+        if (i < n - 1) {
+            need = max_of(need, kmv_symv_workspace_bytes(Calls<T>::prec, 'L', n - i - 1));
+            need = max_of(need, kmv_gemv_workspace_bytes(Calls<T>::prec, 'T', n - i - 1, i));
+            need = max_of(need, kmv_gemv_workspace_bytes(Calls<T>::prec, 'N', n - i - 1, i));
+        }
+    }
+    return rows_bytes<T>(nb) + need;
+}
+
+template <class T>
+int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* tau, T* W, int64_t ldw, void* ws,
+                size_t wsb, void* stream) {
+    if (uplo != 'L' && uplo != 'l') return -1;      // lower storage only
+    if (n < 0) return -2;
+    if (nb < 0 || nb > n) return -3;
+    if (lda < (n > 1 ? n : 1)) return -5;
+    if (ldw < (n > 1 ? n : 1)) return -9;
+    if (n == 0 || nb == 0) return KMV_OK;
+    if (!A || !e || !tau || !W) return KMV_ERR_NULL;
+    if (!ws || wsb < panel_workspace<T>(n, nb) || ((uintptr_t)ws % 256) != 0) return KMV_ERR_WORKSPACE;
+    static_assert(PT >= 1024, "the row copy at the end of finish_w_kernel uses one thread per column of the panel");
+    if (nb > PT) return -3;
+    T* wrow = static_cast<T*>(ws);           // row i of W and of V, packed by the column before
+    T* vrow = wrow + nb;
+    ws = static_cast<char*>(ws) + rows_bytes<T>(nb);
+    wsb -= rows_bytes<T>(nb);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const T one = 1, zero = 0, minus = -1;
+    const auto gemv = Calls<T>::gemv;
+    const auto symv = Calls<T>::symv;
+    int rc = KMV_OK;
+    for (int64_t i = 0; i < nb; ++i) {
+        T* col = A + i + i * lda;               // A[i:, i]
+        if (i > 0) {
+            // column i catches up with the reflectors before it; x is row i of W, then row i of V (= of A),
+            // both packed by the last kernel of column i-1
+            rc = gemv('N', n - i, i, &minus, A + i, lda, wrow, 1, &one, col, 1, ws, wsb, stream);
+            if (rc) return rc;
+            rc = gemv('N', n - i, i, &minus, W + i, ldw, vrow, 1, &one, col, 1, ws, wsb, stream);
+            if (rc) return rc;
+        }
+        if (i >= n - 1) {   // last column of the matrix: no reflector; its slots are defined all the same
+            hipLaunchKernelGGL((no_reflector_kernel<T>), dim3(1), dim3(1), 0, s, e + i, tau + i);
+            const hipError_t he = hipGetLastError();
+            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+            continue;
+        }
+        const int64_t m = n - i - 1;
+        T* v = col + 1;                         // A[i+1:, i]
+        T* w = W + (i + 1) + i * ldw;           // W[i+1:, i]
+        T* small = W + i * ldw;                 // W[:i, i]: the i-vector of the corrections
+        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, v, e + i, tau + i);
+        hipError_t he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        rc = symv('L', m, &one, A + (i + 1) + (i + 1) * lda, lda, v, 1, &zero, w, 1, ws, wsb, stream);
+        if (rc) return rc;
+        if (i > 0) {
+            rc = gemv('T', m, i, &one, W + i + 1, ldw, v, 1, &zero, small, 1, ws, wsb, stream);
+            if (rc) return rc;
+            rc = gemv('N', m, i, &minus, A + i + 1, lda, small, 1, &one, w, 1, ws, wsb, stream);
+            if (rc) return rc;
+            rc = gemv('T', m, i, &one, A + i + 1, lda, v, 1, &zero, small, 1, ws, wsb, stream);
+            if (rc) return rc;
+            rc = gemv('N', m, i, &minus, W + i + 1, ldw, small, 1, &one, w, 1, ws, wsb, stream);
+            if (rc) return rc;
+        }
+        hipLaunchKernelGGL((finish_w_kernel<T>), dim3(1), dim3(PT), 0, s, m, tau + i, v, w, W + (i + 1), ldw,
+                           A + (i + 1), lda, (int)(i + 1), wrow, vrow);
+        he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+    }
+    return KMV_OK;
+}
+
+}  // namespace
+}  // namespace kmv
+
+extern "C" {
+
+int kmv_ssytrd_panel(char uplo, int64_t n, int64_t nb, float* A, int64_t lda, float* e, float* tau, float* W,
+                     int64_t ldw, void* workspace, size_t workspace_bytes, void* stream) {
+    return kmv::sytrd_panel<float>(uplo, n, nb, A, lda, e, tau, W, ldw, workspace, workspace_bytes, stream);
+}
+int kmv_dsytrd_panel(char uplo, int64_t n, int64_t nb, double* A, int64_t lda, double* e, double* tau, double* W,
+                     int64_t ldw, void* workspace, size_t workspace_bytes, void* stream) {
+    return kmv::sytrd_panel<double>(uplo, n, nb, A, lda, e, tau, W, ldw, workspace, workspace_bytes, stream);
+}
+size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb) {
+    if (prec == 's') return kmv::panel_workspace<float>(n, nb);
+    if (prec == 'd') return kmv::panel_workspace<double>(n, nb);
+    return 0;
+}
+
+}  // extern "C"

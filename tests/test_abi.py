@@ -193,3 +193,23 @@ def test_devscalars_argument_errors(prec):
     assert symv(alpha=None) == kmv.ERR_NULL and symv(A=None) == kmv.ERR_NULL
     assert symv(n=0, lda=1) == 0
     assert symv() == kmv.ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("prec", "sd")
+def test_sytrd_panel_argument_errors(prec):
+    f = kmv.SYTRD_PANEL[prec]
+
+    def call(uplo="L", n=8, nb=4, lda=8, ldw=8, A=DUMMY, W=DUMMY):
+        return f(uplo, n, nb, A, lda, DUMMY, DUMMY, W, ldw, workspace=NOWS, stream=0, check=False)
+
+    assert call(uplo="U") == -1                 # lower storage only
+    assert call(n=-1) == -2
+    assert call(nb=-1) == -3 and call(nb=9) == -3
+    assert call(lda=7) == -5 and call(ldw=7) == -9
+    assert call(n=0, nb=0, lda=1, ldw=1) == 0 and call(nb=0) == 0
+    assert call(A=None) == kmv.ERR_NULL and call(W=None) == kmv.ERR_NULL
+    assert call() == kmv.ERR_WORKSPACE
+    need = kmv.sytrd_panel_workspace_bytes(prec, 4096, 64)
+    assert need >= kmv.symv_workspace_bytes(prec, "L", 4095)
+    assert need >= kmv.gemv_workspace_bytes(prec, "N", 4095, 63)
+    assert kmv.sytrd_panel_workspace_bytes("z", 64, 8) == 0 and kmv.sytrd_panel_workspace_bytes(prec, 0, 0) == 0

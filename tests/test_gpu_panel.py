@@ -1,0 +1,136 @@
+"""Panel step of the symmetric tridiagonal reduction (kmv_{s,d}sytrd_panel) against the numpy oracle:
+the reflectors, tau, e, the diagonal and W, on matrices that span several tiles, with ragged sizes, padded
+leading dimensions and sub-block pointers; the strict upper triangle is NaN and must stay unread and
+unwritten, the trailing columns must stay bit-unchanged."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import panel_oracle as po
+from paper_1410_1726_amd import workloads as wl
+
+from gpu_util import DEV, kmv
+
+pytestmark = pytest.mark.gpu
+
+# normwise tolerance of a panel: nb columns that depend on each other, each a handful of length-n sums
+TOL = {"s": 1e-5, "d": 1e-12}
+
+
+def run_panel(prec, n, nb, lda, ldw, off=0, seed=0):
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    parent = wl.matrix(prec, n + off, n + off, lda, seed=seed, device=DEV)
+    A = parent[off:, off:] if off else parent
+    wl.poison_triangle(A, n, "L")
+    before = parent.clone()
+    W = torch.full((nb, ldw), float("nan"), dtype=dt, device=DEV)      # column major n x nb, leading dimension ldw
+    e = torch.full((nb,), float("nan"), dtype=dt, device=DEV)
+    tau = torch.full((nb,), float("nan"), dtype=dt, device=DEV)
+    k.SYTRD_PANEL[prec]("L", n, nb, A, lda, e, tau, W, ldw)
+    torch.cuda.synchronize()
+    return parent, before, W, e, tau
+
+
+def host_matrix(parent, off, n):
+    """n x n numpy array (row index first) of the block that starts at (off, off)"""
+    return parent[off:off + n, off:off + n].cpu().numpy().T.copy()
+
+
+def rel(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    nrm = np.linalg.norm(want)
+    return float(np.linalg.norm(np.asarray(got, dtype=np.float64) - want) / (nrm if nrm else 1.0))
+
+
+@pytest.mark.parametrize("prec", "sd")
+@pytest.mark.parametrize("n,nb,pad,off", [(1, 1, 0, 0), (2, 2, 0, 0), (3, 1, 1, 0), (100, 16, 0, 0), (700, 32, 36, 0),
+                                          (1500, 64, 0, 0), (1100, 24, 52, 17), (300, 300, 4, 1)])
+def test_panel_against_oracle(prec, n, nb, pad, off):
+    lda, ldw = n + off + pad, n + (pad // 2)
+    parent, before, W, e, tau = run_panel(prec, n, nb, lda, ldw, off, seed=n + nb)
+    A0 = host_matrix(before, off, n)
+    want = po.sytrd_panel(A0, nb)
+    A1 = host_matrix(parent, off, n)
+    tol = TOL[prec]
+    low = np.tril(np.ones((n, n), dtype=bool))[:, :nb]
+    for i in range(min(nb, n - 1)):
+        assert A1[i + 1, i] == 1.0
+    Wh = W.cpu().numpy().T[:n]                       # n x nb
+    defined = np.zeros((n, nb), dtype=bool)
+    for i in range(nb):
+        defined[i + 1:, i] = True
+    assert np.all(np.isfinite(Wh[defined]))
+    if nb <= 64:
+        # element by element: the first nb columns (diagonal, leading ones, reflector tails), e, tau, W
+        assert rel(A1[:, :nb][low], np.asarray(want["A"])[:, :nb][low]) <= tol
+        assert rel(e.cpu().numpy(), want["e"]) <= tol
+        assert rel(tau.cpu().numpy(), want["tau"]) <= tol
+        assert rel(Wh[defined], np.asarray(want["W"])[defined]) <= tol
+    else:
+        # A long chain of dependent columns: single reflector entries are not determined to working accuracy
+        # any more (the late columns see a matrix that carries all earlier rounding), but the factorisation
+        # as a whole is: with the GPU's own reflectors Q, Q^T S Q is tridiagonal with the GPU's d and e, and
+        # d, e agree with the oracle's as a tridiagonal matrix with the same eigenvalues.
+        S = np.tril(A0).astype(np.float64)
+        S = S + np.tril(S, -1).T
+        V = np.zeros((n, nb))
+        for j in range(min(nb, n - 1)):
+            V[j + 1:, j] = A1[j + 1:, j]
+        Q = np.eye(n)
+        th = tau.cpu().numpy().astype(np.float64)
+        for j in range(nb):
+            Q = Q @ (np.eye(n) - th[j] * np.outer(V[:, j], V[:, j]))
+        assert np.linalg.norm(Q.T @ Q - np.eye(n)) <= 50 * tol
+        T = Q.T @ S @ Q
+        d, eh = np.diag(A1).astype(np.float64), e.cpu().numpy().astype(np.float64)
+        Tg = np.diag(d[:nb]) + np.diag(eh[: nb - 1], -1) + np.diag(eh[: nb - 1], 1)
+        assert np.linalg.norm(T[:nb, :nb] - Tg) <= 50 * tol * np.linalg.norm(S)
+        assert np.allclose(np.linalg.eigvalsh(Tg), np.linalg.eigvalsh(S), atol=50 * tol * np.linalg.norm(S, 2))
+        assert rel(d[:nb], np.diag(np.asarray(want["A"], dtype=np.float64))[:nb]) <= 1e3 * tol
+    # untouched: everything of the parent outside the first nb columns of the block's lower triangle
+    pb, pa = before.cpu().numpy(), parent.cpu().numpy()          # (cols, lda)
+    touched = np.zeros(pb.shape, dtype=bool)
+    for i in range(nb):
+        touched[off + i, off + i:off + n] = True
+    assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
+    # rows of W beyond n (the padding of ldw) were not written
+    assert np.all(np.isnan(W.cpu().numpy()[:, n:]))
+
+
+@pytest.mark.parametrize("prec", "sd")
+def test_panel_is_deterministic_and_capturable(prec):
+    """the whole panel is a sequence of kernel launches with no host round trip: captured in a graph and
+    replayed on restored inputs, every replay reproduces the eager result bit for bit"""
+    k = kmv()
+    n, nb = 900, 32
+    dt = wl.TORCH_DTYPES[prec]
+    A0 = wl.poison_triangle(wl.matrix(prec, n, n, n, seed=3, device=DEV), n, "L")
+    A = A0.clone()
+    W = torch.zeros((nb, n), dtype=dt, device=DEV)
+    e = torch.zeros(nb, dtype=dt, device=DEV)
+    tau = torch.zeros(nb, dtype=dt, device=DEV)
+    ws = k.workspace(k.sytrd_panel_workspace_bytes(prec, n, nb))
+    k.SYTRD_PANEL[prec]("L", n, nb, A, n, e, tau, W, n, workspace=ws)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (A, W, e, tau)]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    A.copy_(A0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            k.SYTRD_PANEL[prec]("L", n, nb, A, n, e, tau, W, n, workspace=ws, stream=side)
+    for _ in range(3):
+        A.copy_(A0)
+        for t in (W, e, tau):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((A, e, tau), (ref[0], ref[2], ref[3])):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+        rows = torch.arange(n, device=DEV).unsqueeze(0)
+        cols = torch.arange(nb, device=DEV).unsqueeze(1)
+        defined = rows > cols
+        assert torch.equal(W[defined], ref[1][defined])
