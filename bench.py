@@ -47,7 +47,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "csymv", "rect", "tiny"])
+    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "batched", "csymv", "rect", "tiny"])
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
@@ -273,6 +273,81 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
     }
 
 
+def batched_bench(args, k, torch, wl, acc):
+    """One step = strided batches of small fp64 products, 1 GiB of matrices per batch: DGEMV N and T and DSYMV L at
+    n = 64 .. 1024, one call (one launch) per batch.  For comparison the same products as a loop of single calls
+    (prepared, so a call is one foreign call) are timed on the first 256 members."""
+    dt = wl.TORCH_DTYPES["d"]
+    total = 1 << 27                      # elements of matrix storage per batch (1 GiB)
+    flat = torch.empty(total, dtype=dt, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(0)
+    wl.fill_random(flat, "uniform", g)
+    stream = torch.cuda.current_stream()
+    rows, tot_bytes, tot_ms = [], 0, 0.0
+    t_all0 = None
+    cases = [(kind, n) for n in (64, 128, 256, 512, 1024) for kind in ("gemv_n", "gemv_t", "symv_l")]
+    xs = wl.vector("d", total // 64, 1, seed=0, which=1, device="cuda")
+    ys = wl.vector("d", total // 64, 1, seed=0, which=2, device="cuda")
+
+    def run(kind, n, batch):
+        if kind == "symv_l":
+            k.dsymv_strided_batched("L", n, 1.0, flat, n, n * n, xs, 1, n, 0.0, ys, 1, n, batch)
+        else:
+            k.dgemv_strided_batched("N" if kind == "gemv_n" else "T", n, n, 1.0, flat, n, n * n, xs, 1, n, 1.0, ys, 1, n, batch)
+
+    for kind, n in cases:
+        batch = total // (n * n)
+        nbytes = batch * acc.algorithmic_bytes(kind, "d", n, n)
+        for _ in range(args.warmup):
+            run(kind, n, batch)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(args.steps):
+            run(kind, n, batch)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        # the same members one call at a time (first 256 only)
+        nloop = min(batch, 256)
+        if kind == "symv_l":
+            calls = [k.prepare_symv("d", "L", n, 1.0, flat[b * n * n:], n, xs[b * n:], 1, 0.0, ys[b * n:], 1) for b in range(nloop)]
+        else:
+            calls = [k.prepare_gemv("d", "N" if kind == "gemv_n" else "T", n, n, 1.0, flat[b * n * n:], n, xs[b * n:], 1, 1.0,
+                                    ys[b * n:], 1) for b in range(nloop)]
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        loop_us = (time.perf_counter() - t0) * 1e6 / nloop
+        rows.append({"routine": "d" + kind, "n": n, "batch": batch, "ms": round(ms, 4),
+                     "us_per_member": round(ms * 1e3 / batch, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "single_call_loop_us_per_member": round(loop_us, 3)})
+        tot_bytes += nbytes
+        tot_ms += ms
+    if args.table:
+        with open(args.table, "w") as f:
+            for r in rows:
+                f.write(json.dumps(r) + "\n")
+    value = tot_bytes / (tot_ms * 1e-3) / 1e9
+    return {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(tot_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "strided batches of DGEMV N,T and DSYMV L, n = 64..1024, 1 GiB of fp64 matrices per batch "
+                               "(32768 .. 128 members), one call per batch", "products_per_step": len(cases)},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "per_shape": rows,
+        "roofline": None,
+    }
+
+
 def cpu_baseline(acc, wl):
     """The oracle as it stands (working-precision mode, OpenMP over outputs) on a
     bounded sample of the sweep: one product per routine family at one size."""
@@ -349,6 +424,9 @@ def main():
         key, v = kv.split("=")
         k.set_tuning(key, int(v))
 
+    if args.workload == "batched":
+        print(json.dumps(batched_bench(args, k, torch, wl, acc)))
+        return
     if args.workload == "sytrd":
         print(json.dumps(sytrd_panel_bench(args, k, torch, wl, acc)))
         return

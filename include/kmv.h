@@ -234,6 +234,45 @@ int kmv_dsytrd_panel(char uplo, int64_t n, int64_t nb, double* A, int64_t lda, d
                      int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
 size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
 
+/* ---- Strided batches: `batch` products of one shape in one call; member b
+ * uses A + b*strideA, x + b*stridex, y + b*stridey (strides in elements, >= 0;
+ * 0 shares an input among the members; the outputs of two members must not
+ * overlap: stridey >= 1 + (len(y)-1)*|incy| when batch > 1).  alpha and beta
+ * (host) are common to all members.  The paper has no batched routines; these
+ * serve the many-small-matrices case, where a launch per product would cost
+ * more than the product: one launch covers the whole batch (65535 members per
+ * launch, more are split), each member runs the single-launch form of the
+ * kernels (GEMV without column or row splits, the small-matrix SYMV/HEMV
+ * kernel), so no workspace is needed and member results do not depend on the
+ * batch size.  Restriction: incx must be 1.  Errors: negated argument number
+ * (GEMV: trans 1, m 2, n 3, lda 6, strideA 7, incx 9, stridex 10, incy 13,
+ * stridey 14, batch 15; SYMV/HEMV: uplo 1, n 2, lda 5, strideA 6, incx 8,
+ * stridex 9, incy 12, stridey 13, batch 14), KMV_ERR_NULL, KMV_ERR_HIP + code. */
+int kmv_sgemv_strided_batched(char trans, int64_t m, int64_t n, const float* alpha, const float* A, int64_t lda,
+                              int64_t strideA, const float* x, int64_t incx, int64_t stridex, const float* beta,
+                              float* y, int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_dgemv_strided_batched(char trans, int64_t m, int64_t n, const double* alpha, const double* A, int64_t lda,
+                              int64_t strideA, const double* x, int64_t incx, int64_t stridex, const double* beta,
+                              double* y, int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_cgemv_strided_batched(char trans, int64_t m, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+                              int64_t strideA, const kmv_complex64* x, int64_t incx, int64_t stridex, const kmv_complex64* beta,
+                              kmv_complex64* y, int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_zgemv_strided_batched(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+                              int64_t strideA, const kmv_complex128* x, int64_t incx, int64_t stridex, const kmv_complex128* beta,
+                              kmv_complex128* y, int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_ssymv_strided_batched(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda, int64_t strideA,
+                              const float* x, int64_t incx, int64_t stridex, const float* beta, float* y,
+                              int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_dsymv_strided_batched(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, int64_t strideA,
+                              const double* x, int64_t incx, int64_t stridex, const double* beta, double* y,
+                              int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_chemv_strided_batched(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda, int64_t strideA,
+                              const kmv_complex64* x, int64_t incx, int64_t stridex, const kmv_complex64* beta, kmv_complex64* y,
+                              int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_zhemv_strided_batched(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda, int64_t strideA,
+                              const kmv_complex128* x, int64_t incx, int64_t stridex, const kmv_complex128* beta, kmv_complex128* y,
+                              int64_t incy, int64_t stridey, int64_t batch, void* stream);
+
 /* ---- Workspace sizes (bytes; an upper bound valid for every pointer
  * alignment, every increment and every tuning value).  prec is 's','d','c'
  * or 'z'.  The workspace holds the packed copy of a strided x and the

@@ -61,6 +61,13 @@ def _load() -> ctypes.CDLL:
         f = getattr(lib, f"kmv_{p_}sytrd_panel")
         f.argtypes, f.restype = [ch, i64, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp], ci
     lib.kmv_sytrd_panel_workspace_bytes.argtypes, lib.kmv_sytrd_panel_workspace_bytes.restype = [ch, i64, i64], sz
+    gemv_b_args = [ch, i64, i64, vp, vp, i64, i64, vp, i64, i64, vp, vp, i64, i64, i64, vp]
+    symv_b_args = [ch, i64, vp, vp, i64, i64, vp, i64, i64, vp, vp, i64, i64, i64, vp]
+    for p_ in "sdcz":
+        f = getattr(lib, f"kmv_{p_}gemv_strided_batched")
+        f.argtypes, f.restype = gemv_b_args, ci
+        f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_strided_batched")
+        f.argtypes, f.restype = symv_b_args, ci
     lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
     lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
     lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -322,6 +329,44 @@ def _symv_devscalars(prec):
     call.__name__ = name
     call.__doc__ = "SYMV / HEMV with alpha and beta given as one-element device tensors (or device addresses)."
     return call
+
+
+def _gemv_strided_batched(prec):
+    def call(trans, m, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch, stream=None,
+             check=True):
+        rc = getattr(lib, f"kmv_{prec}gemv_strided_batched")(
+            trans.encode(), m, n, _scalar(prec, alpha), _ptr(A, prec), lda, strideA, _ptr(x, prec), incx, stridex,
+            _scalar(prec, beta), _ptr(y, prec), incy, stridey, batch, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(f"{prec}gemv_strided_batched", rc)
+        return rc
+    call.__name__ = f"{prec}gemv_strided_batched"
+    call.__doc__ = "`batch` GEMVs of one shape; member b uses A + b*strideA, x + b*stridex, y + b*stridey."
+    return call
+
+
+def _symv_strided_batched(prec):
+    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}_strided_batched"
+
+    def call(uplo, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch, stream=None,
+             check=True):
+        rc = getattr(lib, f"kmv_{name}")(
+            uplo.encode(), n, _scalar(prec, alpha), _ptr(A, prec), lda, strideA, _ptr(x, prec), incx, stridex,
+            _scalar(prec, beta), _ptr(y, prec), incy, stridey, batch, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(name, rc)
+        return rc
+    call.__name__ = name
+    call.__doc__ = "`batch` SYMV / HEMV products of one shape; member b uses A + b*strideA, x + b*stridex, y + b*stridey."
+    return call
+
+
+GEMV_STRIDED_BATCHED = {p_: _gemv_strided_batched(p_) for p_ in "sdcz"}
+SYMV_STRIDED_BATCHED = {p_: _symv_strided_batched(p_) for p_ in "sdcz"}
+sgemv_strided_batched, dgemv_strided_batched, cgemv_strided_batched, zgemv_strided_batched = (
+    GEMV_STRIDED_BATCHED[p_] for p_ in "sdcz")
+ssymv_strided_batched, dsymv_strided_batched, chemv_strided_batched, zhemv_strided_batched = (
+    SYMV_STRIDED_BATCHED[p_] for p_ in "sdcz")
 
 
 def sytrd_panel_workspace_bytes(prec, n, nb) -> int:

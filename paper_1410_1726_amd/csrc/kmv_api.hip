@@ -146,6 +146,113 @@ int symv_offset_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* 
                          workspace_bytes, stream);
 }
 
+// Strided batches: `batch` products of one shape, operand b at base + b*stride.  One launch per
+// product type covers the whole batch (grid z / y = member), with the single-launch forms of the
+// kernels (no column or row splits, small-matrix SYMV kernel), so no workspace is involved.
+constexpr int64_t MAX_GRID_BATCH = 65535;
+
+template <class T>
+int gemv_batched_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* A, int64_t lda, int64_t strideA,
+                       const T* x, int64_t incx, int64_t stridex, const T* beta, T* y, int64_t incy, int64_t stridey,
+                       int64_t batch, void* stream) {
+    const bool notrans = (trans == 'N' || trans == 'n');
+    const bool tr = (trans == 'T' || trans == 't');
+    const bool ct = (trans == 'C' || trans == 'c');
+    if (!notrans && !tr && !ct) return -1;
+    if (m < 0) return -2;
+    if (n < 0) return -3;
+    if (lda < (m > 1 ? m : 1)) return -6;
+    if (strideA < 0) return -7;
+    if (incx != 1) return -9;              // a strided x would need packing space per member
+    if (stridex < 0) return -10;
+    if (incy == 0) return -13;
+    const int64_t leny = notrans ? m : n;
+    const int64_t exty = leny > 0 ? 1 + (leny - 1) * (incy < 0 ? -incy : incy) : 0;
+    if (stridey < 0 || (batch > 1 && stridey < exty)) return -14;   // outputs of two members must not overlap
+    if (batch < 0) return -15;
+    if (!alpha || !beta) return KMV_ERR_NULL;
+    const T al = *alpha, be = *beta;
+    if (m == 0 || n == 0 || batch == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    if (!y || (!is_zero(al) && (!A || !x))) return KMV_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    T* yb = vec_base(y, leny, incy);
+    GemvArgs<T> a;
+    a.m = m; a.n = n; a.lda = lda;
+    a.incy = incy; a.alpha = al; a.beta = be;
+    a.partial = nullptr;
+    a.batch_A = strideA; a.batch_x = stridex; a.batch_y = stridey;
+    for (int64_t b0 = 0; b0 < batch; b0 += MAX_GRID_BATCH) {
+        const int64_t nb = batch - b0 < MAX_GRID_BATCH ? batch - b0 : MAX_GRID_BATCH;
+        if (is_zero(al)) {   // y <- beta*y, A and x not referenced
+            const hipError_t e = launch_scal<T>(leny, be, yb + b0 * stridey, incy, s, nb, stridey);
+            if (e != hipSuccess) return hip_code(e);
+            continue;
+        }
+        a.A = A + b0 * strideA; a.x = x + b0 * stridex; a.y = yb + b0 * stridey;
+        GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, a.A, lda);
+        // the members share one tile grid: keep the pointer's alignment shift only if every member has it
+        if (nb > 1 && ((uint64_t)strideA * sizeof(T)) % 128 != 0) {
+            plan.shift = 0;
+            plan.ntiles = ceil_div(m, (int64_t)tile_rows<T>());
+        }
+        plan.splits = 1;
+        // transposed products of one or two row tiles: every wave takes columns of its own
+        plan.short_form = (!notrans && plan.ntiles <= 2) ? 1 : 0;
+        plan.row_tiles = 1;
+        a.plan = plan;
+        const hipError_t e = notrans ? launch_gemv_n<T>(a, s, nb) : launch_gemv_t<T>(a, ct, s, nb);
+        if (e != hipSuccess) return hip_code(e);
+    }
+    return KMV_OK;
+}
+
+template <class T>
+int symv_batched_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int64_t lda, int64_t strideA,
+                       const T* x, int64_t incx, int64_t stridex, const T* beta, T* y, int64_t incy, int64_t stridey,
+                       int64_t batch, void* stream) {
+    const bool lower = (uplo == 'L' || uplo == 'l');
+    const bool upper = (uplo == 'U' || uplo == 'u');
+    if (!lower && !upper) return -1;
+    if (n < 0) return -2;
+    if (lda < (n > 1 ? n : 1)) return -5;
+    if (strideA < 0) return -6;
+    if (incx != 1) return -8;
+    if (stridex < 0) return -9;
+    if (incy == 0) return -12;
+    const int64_t exty = n > 0 ? 1 + (n - 1) * (incy < 0 ? -incy : incy) : 0;
+    if (stridey < 0 || (batch > 1 && stridey < exty)) return -13;
+    if (batch < 0) return -14;
+    if (!alpha || !beta) return KMV_ERR_NULL;
+    const T al = *alpha, be = *beta;
+    if (n == 0 || batch == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    if (!y || (!is_zero(al) && (!A || !x))) return KMV_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    T* yb = vec_base(y, n, incy);
+    SymvArgs<T> a;
+    a.n = n; a.lda = lda;
+    a.incy = incy; a.alpha = al; a.beta = be;
+    a.wsn = nullptr; a.wst = nullptr; a.wtab = nullptr;
+    a.batch_A = strideA; a.batch_x = stridex; a.batch_y = stridey;
+    for (int64_t b0 = 0; b0 < batch; b0 += MAX_GRID_BATCH) {
+        const int64_t nb = batch - b0 < MAX_GRID_BATCH ? batch - b0 : MAX_GRID_BATCH;
+        if (is_zero(al)) {
+            const hipError_t e = launch_scal<T>(n, be, yb + b0 * stridey, incy, s, nb, stridey);
+            if (e != hipSuccess) return hip_code(e);
+            continue;
+        }
+        a.A = A + b0 * strideA; a.x = x + b0 * stridex; a.y = yb + b0 * stridey;
+        SymvPlan<T> plan = plan_symv<T>(lower, n, a.A, lda);
+        if (nb > 1 && ((uint64_t)strideA * sizeof(T)) % 128 != 0) plan.shift = 0;
+        // one workgroup per member up to 512 rows, else the one-launch kernel for small matrices with the
+        // member in the grid's second dimension
+        plan.variant = ceil_div(n, (int64_t)tile_rows<T>()) <= member_max_tiles<T>() ? 4 : 3;
+        a.plan = plan;
+        const hipError_t e = launch_symv<T>(a, lower, herm, s, nb);
+        if (e != hipSuccess) return hip_code(e);
+    }
+    return KMV_OK;
+}
+
 template <class T> size_t gemv_ws(char trans, int64_t m, int64_t n) {
     const bool notrans = (trans == 'N' || trans == 'n');
     if (m <= 0 || n <= 0) return 0;   // an empty product returns before it would use a workspace
@@ -280,6 +387,33 @@ KMV_SYMV_DEVSCALARS(kmv_dsymv_devscalars, double, double, false)
 KMV_SYMV_DEVSCALARS(kmv_chemv_devscalars, kmv_complex64, cf32, true)
 KMV_SYMV_DEVSCALARS(kmv_zhemv_devscalars, kmv_complex128, cf64, true)
 #undef KMV_SYMV_DEVSCALARS
+
+// strided batches
+#define KMV_GEMV_BATCHED(NAME, CT, T)                                                                             \
+    int NAME(char trans, int64_t m, int64_t n, const CT* alpha, const CT* A, int64_t lda, int64_t strideA,        \
+             const CT* x, int64_t incx, int64_t stridex, const CT* beta, CT* y, int64_t incy, int64_t stridey,    \
+             int64_t batch, void* stream) {                                                                       \
+        return gemv_batched_entry<T>(trans, m, n, (const T*)alpha, (const T*)A, lda, strideA, (const T*)x, incx,  \
+                                     stridex, (const T*)beta, (T*)y, incy, stridey, batch, stream);               \
+    }
+KMV_GEMV_BATCHED(kmv_sgemv_strided_batched, float, float)
+KMV_GEMV_BATCHED(kmv_dgemv_strided_batched, double, double)
+KMV_GEMV_BATCHED(kmv_cgemv_strided_batched, kmv_complex64, cf32)
+KMV_GEMV_BATCHED(kmv_zgemv_strided_batched, kmv_complex128, cf64)
+#undef KMV_GEMV_BATCHED
+
+#define KMV_SYMV_BATCHED(NAME, CT, T, HERM)                                                                       \
+    int NAME(char uplo, int64_t n, const CT* alpha, const CT* A, int64_t lda, int64_t strideA, const CT* x,       \
+             int64_t incx, int64_t stridex, const CT* beta, CT* y, int64_t incy, int64_t stridey, int64_t batch,  \
+             void* stream) {                                                                                      \
+        return symv_batched_entry<T>(HERM, uplo, n, (const T*)alpha, (const T*)A, lda, strideA, (const T*)x,      \
+                                     incx, stridex, (const T*)beta, (T*)y, incy, stridey, batch, stream);         \
+    }
+KMV_SYMV_BATCHED(kmv_ssymv_strided_batched, float, float, false)
+KMV_SYMV_BATCHED(kmv_dsymv_strided_batched, double, double, false)
+KMV_SYMV_BATCHED(kmv_chemv_strided_batched, kmv_complex64, cf32, true)
+KMV_SYMV_BATCHED(kmv_zhemv_strided_batched, kmv_complex128, cf64, true)
+#undef KMV_SYMV_BATCHED
 
 size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n) {
     switch (prec) {

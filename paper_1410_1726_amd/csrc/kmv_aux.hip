@@ -12,10 +12,10 @@ template <class T> __global__ void pack_kernel(const T* __restrict__ src, int64_
     if (k < len) dst[k] = src[k * inc];
 }
 
-template <class T> __global__ void scal_kernel(int64_t len, T beta, T* y, int64_t incy) {
+template <class T> __global__ void scal_kernel(int64_t len, T beta, T* y, int64_t incy, int64_t stride) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k < len) {
-        T* yp = y + k * incy;
+        T* yp = y + (int64_t)blockIdx.y * stride + k * incy;
         *yp = is_zero(beta) ? zero_of<T>() : mul_of(beta, *yp);
     }
 }
@@ -54,9 +54,12 @@ template <class T> hipError_t launch_pack(const T* src, int64_t inc, int64_t len
     hipLaunchKernelGGL((pack_kernel<T>), dim3((unsigned)ceil_div(len, 256)), dim3(256), 0, s, src, inc, len, dst);
     return hipGetLastError();
 }
-template <class T> hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s) {
-    if (len <= 0) return hipSuccess;
-    hipLaunchKernelGGL((scal_kernel<T>), dim3((unsigned)ceil_div(len, 256)), dim3(256), 0, s, len, beta, y, incy);
+template <class T>
+hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s, int64_t batch, int64_t stride) {
+    if (len <= 0 || batch <= 0) return hipSuccess;
+    if (batch > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((scal_kernel<T>), dim3((unsigned)ceil_div(len, 256), (unsigned)batch), dim3(256), 0, s, len, beta,
+                       y, incy, stride);
     return hipGetLastError();
 }
 template <class T>
@@ -70,7 +73,7 @@ hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64
 
 #define KMV_INSTANTIATE_AUX(T)                                                                              \
     template hipError_t launch_pack<T>(const T*, int64_t, int64_t, T*, hipStream_t);                        \
-    template hipError_t launch_scal<T>(int64_t, T, T*, int64_t, hipStream_t);                               \
+    template hipError_t launch_scal<T>(int64_t, T, T*, int64_t, hipStream_t, int64_t, int64_t);             \
     template hipError_t launch_reduce<T>(const T*, int64_t, int64_t, int64_t, int64_t, T, T, const T*, const T*, T*, \
                                          int64_t, hipStream_t);
 KMV_INSTANTIATE_AUX(float)

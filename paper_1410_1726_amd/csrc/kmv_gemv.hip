@@ -122,6 +122,9 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     // the rows and differ in the columns), grid.y = block of row tiles
     const int64_t tbase = (int64_t)blockIdx.y * (NW * RT) + w;   // tiles tbase + NW*t, t < RT
     if (tbase >= a.plan.ntiles) return;
+    a.A += (int64_t)blockIdx.z * a.batch_A;   // member of a strided batch (all zero otherwise)
+    a.x += (int64_t)blockIdx.z * a.batch_x;
+    a.y += (int64_t)blockIdx.z * a.batch_y;
 
     int64_t cw, c0;
     partition(a.n, a.plan.splits, blockIdx.x, cw, c0);
@@ -237,7 +240,9 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     if (WCOLS && j0 >= a.n) return;   // a whole wave past the last column (no barrier in this form)
     const int64_t ntiles = a.plan.ntiles;
     const int shift = a.plan.shift;
-    const T* __restrict__ x = a.x;
+    a.A += (int64_t)blockIdx.z * a.batch_A;   // member of a strided batch (all zero otherwise)
+    a.y += (int64_t)blockIdx.z * a.batch_y;
+    const T* __restrict__ x = a.x + (int64_t)blockIdx.z * a.batch_x;
 
     int64_t tw, ts;
     partition(ntiles, a.plan.splits, blockIdx.y, tw, ts);
@@ -463,7 +468,8 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     return p;
 }
 
-template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s) {
+template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s, int64_t batch) {
+    if (batch < 1 || batch > 65535 || (batch > 1 && (a.plan.splits != 1 || a.plan.short_form))) return hipErrorInvalidValue;
     if (a.plan.short_form) {
         if (a.plan.ntiles < 1 || a.plan.ntiles > 2) return hipErrorInvalidValue;
         hipLaunchKernelGGL((gemv_n_short_kernel<T, GN_NW, GN_LOADS>), dim3((unsigned)a.plan.splits), dim3(GN_NW * WAVE), 0, s, a);
@@ -472,7 +478,7 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s)
         return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
     }
     const int64_t rt = a.plan.row_tiles;
-    const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt));
+    const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt), (unsigned)batch);
     const dim3 block(GN_NW * WAVE);
     if (rt == 1) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS, 1>), grid, block, 0, s, a);
     else if (rt == 2) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS / 2, 2>), grid, block, 0, s, a);
@@ -483,15 +489,16 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s)
     return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
 }
 
-template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s) {
+template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s, int64_t batch) {
+    if (batch < 1 || batch > 65535 || (batch > 1 && a.plan.splits != 1)) return hipErrorInvalidValue;
     if (a.plan.short_form) {
-        const dim3 grid((unsigned)ceil_div(a.n, GT_NC * GT_NW), (unsigned)a.plan.splits);
+        const dim3 grid((unsigned)ceil_div(a.n, GT_NC * GT_NW), (unsigned)a.plan.splits, (unsigned)batch);
         if (conj && Traits<T>::cplx)
             hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
         else
             hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
     } else {
-        const dim3 grid((unsigned)ceil_div(a.n, GT_NC), (unsigned)a.plan.splits);
+        const dim3 grid((unsigned)ceil_div(a.n, GT_NC), (unsigned)a.plan.splits, (unsigned)batch);
         if (conj && Traits<T>::cplx)
             hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
         else
@@ -504,8 +511,8 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
 
 #define KMV_INSTANTIATE_GEMV(T)                                                              \
     template GemvPlan<T> plan_gemv<T>(bool, int64_t, int64_t, const void*, int64_t);         \
-    template hipError_t launch_gemv_n<T>(const GemvArgs<T>&, hipStream_t);                   \
-    template hipError_t launch_gemv_t<T>(const GemvArgs<T>&, bool, hipStream_t);
+    template hipError_t launch_gemv_n<T>(const GemvArgs<T>&, hipStream_t, int64_t);          \
+    template hipError_t launch_gemv_t<T>(const GemvArgs<T>&, bool, hipStream_t, int64_t);
 KMV_INSTANTIATE_GEMV(float)
 KMV_INSTANTIATE_GEMV(double)
 KMV_INSTANTIATE_GEMV(cf32)

@@ -84,11 +84,15 @@ template <class T> struct GemvArgs {
     T alpha, beta;
     const T* alpha_dev = nullptr;   // non-null: alpha / beta are read from device memory by the epilogue
     const T* beta_dev = nullptr;
+    // strided batches: workgroups with blockIdx.z = b work on A + b*batch_A, x + b*batch_x, y + b*batch_y
+    // (elements); all zero for a single product
+    int64_t batch_A = 0, batch_x = 0, batch_y = 0;
     T* partial;       // [splits][part_stride]
     GemvPlan<T> plan;
 };
-template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s);
-template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s);
+// batch > 1: a strided batch in one launch (requires plan.splits == 1 and the general kernels)
+template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s, int64_t batch = 1);
+template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s, int64_t batch = 1);
 
 // ----------------------------------------------------------- SYMV/HEMV ----
 template <class T> struct SymvPlan {
@@ -117,6 +121,9 @@ template <class T> struct SymvArgs {
     T alpha, beta;
     const T* alpha_dev = nullptr;   // non-null: alpha / beta are read from device memory by the epilogue
     const T* beta_dev = nullptr;
+    // strided batches: workgroups with blockIdx.z = b work on A + b*batch_A, x + b*batch_x, y + b*batch_y
+    // (elements); all zero for a single product
+    int64_t batch_A = 0, batch_x = 0, batch_y = 0;
     T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
     int* wtab;        // variant 2: [nchunks][2] first and last workgroup whose share touches the chunk
@@ -124,19 +131,28 @@ template <class T> struct SymvArgs {
 };
 // HERM selects the Hermitian rule (conjugated mirror image, real diagonal); it exists for
 // complex T only.  Each (T, HERM) pair is instantiated in exactly one translation unit.
-template <class T, bool HERM> hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s);
-template <class T> inline hipError_t launch_symv(const SymvArgs<T>& a, bool lower, bool herm, hipStream_t s) {
+// Row tiles of the largest matrix the one-workgroup-per-member kernel (plan.variant == 4, batches only)
+// takes: 512 rows in every precision.  Its row sums and x live in registers (MAXT * VEC values per lane),
+// and a member is streamed by a single compute unit: measured on fp64 batches of 1 GiB it beats the
+// small-matrix kernel up to n = 512 (3.6x at n = 64, 2.7x at 256, 1.1x at 512) and loses beyond.
+template <class T> constexpr int member_max_tiles() { return 512 / tile_rows<T>(); }
+// batch > 1: a strided batch in one launch (requires plan.variant == 3 or 4)
+template <class T, bool HERM> hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int64_t batch);
+template <class T>
+inline hipError_t launch_symv(const SymvArgs<T>& a, bool lower, bool herm, hipStream_t s, int64_t batch = 1) {
     if constexpr (Traits<T>::cplx) {
-        if (herm) return launch_symv_kind<T, true>(a, lower, s);
+        if (herm) return launch_symv_kind<T, true>(a, lower, s, batch);
     }
-    return launch_symv_kind<T, false>(a, lower, s);
+    return launch_symv_kind<T, false>(a, lower, s, batch);
 }
 
 // ------------------------------------------------------------ auxiliary ----
 // dst[k] = element k of the strided vector src (base already moved for inc < 0)
 template <class T> hipError_t launch_pack(const T* src, int64_t inc, int64_t len, T* dst, hipStream_t s);
 // y[k*incy] = beta * y[k*incy]   (alpha == 0 path; beta == 0 stores zeros)
-template <class T> hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s);
+// (`batch` vectors, `stride` elements apart)
+template <class T>
+hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s, int64_t batch = 1, int64_t stride = 0);
 // y[k*incy] = alpha * sum_s partial[s*stride + off + k] + beta*y[k*incy], s ascending
 template <class T> hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off,
                                             int64_t len, T alpha, T beta, const T* alpha_dev, const T* beta_dev, T* y,

@@ -582,8 +582,9 @@ __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
     const int shift = a.plan.shift;
     const int64_t j0 = (int64_t)blockIdx.x * NC;
     const int64_t jend = j0 + NC < n ? j0 + NC : n;   // one past the last existing output
-    const T* __restrict__ x = a.x;
-    const T* __restrict__ A = a.A;
+    const T* __restrict__ x = a.x + (int64_t)blockIdx.y * a.batch_x;   // member of a strided batch (all zero otherwise)
+    const T* __restrict__ A = a.A + (int64_t)blockIdx.y * a.batch_A;
+    a.y += (int64_t)blockIdx.y * a.batch_y;
     T acc[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) acc[c] = zero_of<T>();
@@ -690,6 +691,102 @@ __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
         for (int ww = 1; ww < NW; ++ww) sum = add_of(sum, red[ww][c]);
         T* yp = a.y + (j0 + c) * a.incy;
         *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), sum, scalar_of(a.beta, a.beta_dev), yp);
+    }
+}
+
+// Members of a batch, one workgroup per matrix (n <= MAXT row tiles): the whole product stays on one
+// compute unit, so every stored element is loaded once and nothing crosses workgroups.  Wave w takes the
+// columns j = w, w + NW, ... (a balanced share of the triangle).  Lanes own rows as everywhere else: for
+// column j a lane loads the stored part of its rows, adds a_ij x_j to its row sums (registers, one set per
+// wave) and collects op(a_ij) x_i for the column sum, which one wave reduction per column turns into the
+// "transposed" part of y_j (LDS, each column written by exactly one wave).  At the end the waves add their
+// row sums into one LDS vector in wave order and the epilogue runs.  A lane whose VEC rows are all stored
+// takes them with one 16-byte load; the lane that straddles the diagonal or the last row loads its stored
+// elements one by one, so the other triangle is never loaded here either.
+template <class T, bool HERM, bool LOWER, int MAXT, int NW>
+__global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int TR = WAVE * VEC;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    const int n = (int)a.n;
+    const int64_t lda = a.lda;
+    const T* __restrict__ x = a.x + (int64_t)blockIdx.x * a.batch_x;
+    const T* __restrict__ A = a.A + (int64_t)blockIdx.x * a.batch_A;
+    T* y = a.y + (int64_t)blockIdx.x * a.batch_y;
+    const int ntiles = (n + TR - 1) / TR;
+
+    __shared__ T rowsum[MAXT * TR];   // N parts, all waves
+    __shared__ T colsum[MAXT * TR];   // T parts, one writer per column
+
+    T xr[MAXT][VEC], acc[MAXT][VEC];
+#pragma unroll
+    for (int t = 0; t < MAXT; ++t)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const int row = t * TR + lane * VEC + e;
+            xr[t][e] = x[row < n ? row : 0];
+            acc[t][e] = zero_of<T>();
+        }
+
+    for (int j = w; j < n; j += NW) {
+        const T* __restrict__ col = A + (int64_t)j * lda;
+        const T xj = x[j];
+        const int tlo = LOWER ? j / TR : 0, thi = LOWER ? ntiles : j / TR + 1;   // tiles that hold stored rows
+        T tsum = zero_of<T>();
+#pragma unroll
+        for (int t = 0; t < MAXT; ++t) {
+            if (t < tlo || t >= thi) continue;     // wave uniform
+            const int r = t * TR + lane * VEC;
+            const bool full = (LOWER ? r >= j : r + VEC - 1 <= j) && r + VEC <= n;
+            Vec<T> v;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v.e[e] = zero_of<T>();
+            if (full) v = load_stream(col + r);
+            if (!full) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int row = r + e;
+                    if (row < n && (LOWER ? row >= j : row <= j)) v.e[e] = col[row];
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int row = r + e;
+                const bool stored = row < n && (LOWER ? row >= j : row <= j);
+                const bool dia = row == j;
+                const T av = v.e[e];
+                // a_ij x_j for y_i (the diagonal element takes part here, as a real number for HEMV)
+                T nt = acc[t][e];
+                fma_acc(nt, select_of(HERM && dia, real_part_only(av), av), xj);
+                acc[t][e] = select_of(stored, nt, acc[t][e]);
+                // op(a_ij) x_i for y_j
+                T tt = tsum;
+                fma_op<HERM>(tt, av, xr[t][e]);
+                tsum = select_of(stored && !dia, tt, tsum);
+            }
+        }
+        const T cs = wave_sum(tsum);
+        if (lane == 0) colsum[j] = cs;
+    }
+
+    // row sums of the waves, added in wave order
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int t = 0; t < MAXT; ++t)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int row = t * TR + lane * VEC + e;
+                    if (row < n) rowsum[row] = ww == 0 ? acc[t][e] : add_of(rowsum[row], acc[t][e]);
+                }
+        }
+        __syncthreads();
+    }
+    const T alpha = scalar_of(a.alpha, a.alpha_dev), beta = scalar_of(a.beta, a.beta_dev);
+    for (int i = threadIdx.x; i < n; i += NW * WAVE) {
+        T* yp = y + (int64_t)i * a.incy;
+        *yp = epilogue(alpha, add_of(rowsum[i], colsum[i]), beta, yp);
     }
 }
 
@@ -925,12 +1022,32 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
 }
 }  // namespace
 
+namespace {
+template <class T, bool HERM, int MAXT>
+void launch_member(const SymvArgs<T>& a, bool lower, dim3 grid, dim3 block, hipStream_t s) {
+    if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, SY_NW>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, SY_NW>), grid, block, 0, s, a);
+}
+}  // namespace
+
 // HERM: conjugate the mirrored triangle and take the real part of the diagonal
 // (complex Hermitian); false for real symmetric and complex symmetric matrices.
-template <class T, bool HERM> hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s) {
+template <class T, bool HERM>
+hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int64_t batch) {
     static_assert(!HERM || Traits<T>::cplx, "Hermitian kernels exist for complex types only");
+    if (batch < 1 || batch > 65535 || (batch > 1 && a.plan.variant < 3)) return hipErrorInvalidValue;
+    if (a.plan.variant == 4) {   // members of a batch: one workgroup per matrix
+        const int64_t tiles = ceil_div(a.n, (int64_t)tile_rows<T>());
+        const dim3 grid((unsigned)batch), block(SY_NW * WAVE);
+        if (tiles < 1 || tiles > member_max_tiles<T>()) return hipErrorInvalidValue;
+        if (tiles <= 1) launch_member<T, HERM, 1>(a, lower, grid, block, s);
+        else if (tiles <= 2) launch_member<T, HERM, 2>(a, lower, grid, block, s);
+        else if (tiles <= 4) launch_member<T, HERM, (member_max_tiles<T>() < 4 ? member_max_tiles<T>() : 4)>(a, lower, grid, block, s);
+        else launch_member<T, HERM, member_max_tiles<T>()>(a, lower, grid, block, s);
+        return hipGetLastError();
+    }
     if (a.plan.variant == 3) {   // one launch, no workspace
-        const dim3 grid((unsigned)ceil_div(a.n, SMALL_NC));
+        const dim3 grid((unsigned)ceil_div(a.n, SMALL_NC), (unsigned)batch);
         if (lower) hipLaunchKernelGGL((symv_small_kernel<T, HERM, true, SMALL_NC, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
         else hipLaunchKernelGGL((symv_small_kernel<T, HERM, false, SMALL_NC, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
         return hipGetLastError();

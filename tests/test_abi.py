@@ -213,3 +213,25 @@ def test_sytrd_panel_argument_errors(prec):
     assert need >= kmv.symv_workspace_bytes(prec, "L", 4095)
     assert need >= kmv.gemv_workspace_bytes(prec, "N", 4095, 63)
     assert kmv.sytrd_panel_workspace_bytes("z", 64, 8) == 0 and kmv.sytrd_panel_workspace_bytes(prec, 0, 0) == 0
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+def test_strided_batched_argument_errors(prec):
+    g, f = kmv.GEMV_STRIDED_BATCHED[prec], kmv.SYMV_STRIDED_BATCHED[prec]
+
+    def gemv(trans="N", m=8, n=6, lda=8, sA=48, incx=1, sx=6, incy=1, sy=8, batch=3, A=DUMMY):
+        return g(trans, m, n, 1.0, A, lda, sA, DUMMY, incx, sx, 0.0, DUMMY, incy, sy, batch, stream=0, check=False)
+
+    def symv(uplo="L", n=8, lda=8, sA=64, incx=1, sx=8, incy=1, sy=8, batch=3, A=DUMMY):
+        return f(uplo, n, 1.0, A, lda, sA, DUMMY, incx, sx, 0.0, DUMMY, incy, sy, batch, stream=0, check=False)
+
+    assert gemv(trans="Q") == -1 and gemv(m=-1) == -2 and gemv(n=-1) == -3 and gemv(lda=7) == -6
+    assert gemv(sA=-1) == -7 and gemv(incx=2) == -9 and gemv(sx=-1) == -10 and gemv(incy=0) == -13
+    assert gemv(sy=7) == -14 and gemv(incy=2, sy=14) == -14 and gemv(sy=-8) == -14
+    assert gemv(sy=0, batch=1, A=None) == kmv.ERR_NULL       # a single member may have any stride
+    assert gemv(batch=-1) == -15 and gemv(batch=0) == 0 and gemv(m=0) == 0
+    assert gemv(A=None) == kmv.ERR_NULL
+    assert symv(uplo="X") == -1 and symv(n=-1) == -2 and symv(lda=7) == -5 and symv(sA=-1) == -6
+    assert symv(incx=-1) == -8 and symv(sx=-1) == -9 and symv(incy=0) == -12 and symv(sy=7) == -13
+    assert symv(batch=-1) == -14 and symv(batch=0) == 0 and symv(n=0, lda=1) == 0
+    assert symv(A=None) == kmv.ERR_NULL

@@ -1,0 +1,143 @@
+"""Strided-batched GEMV / SYMV / HEMV against the oracle, member by member: shapes around the tile sizes,
+member strides that keep and that break the 128-byte alignment of the members, shared inputs (stride 0),
+strided and reversed y, NaN canaries between the outputs, the other triangle NaN, and a batch longer than one
+launch can hold."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1410_1726_amd import workloads as wl
+
+from gpu_util import DEV, check, errors, kmv, logical
+
+pytestmark = pytest.mark.gpu
+PRECS = "sdcz"
+NAN = float("nan")
+
+
+def scal(prec, a, b):
+    return (complex(a, 0.25), complex(b, -0.5)) if prec in "cz" else (a, b)
+
+
+def rand(prec, count, seed):
+    t = torch.empty(count, dtype=wl.TORCH_DTYPES[prec], device=DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    return wl.fill_random(t, "uniform", g)
+
+
+def y_buffer(prec, leny, incy, stridey, batch, seed):
+    """batch strided vectors, NaN in every position that is not an element of one of them"""
+    y = torch.full((max(batch * stridey, 1),), NAN, dtype=wl.TORCH_DTYPES[prec], device=DEV)
+    vals = rand(prec, batch * leny, seed).view(batch, leny)
+    for b in range(batch):
+        y[b * stridey: b * stridey + 1 + (leny - 1) * abs(incy): abs(incy)] = vals[b]
+    return y
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "NTC")
+def test_gemv_strided_batched(prec, trans):
+    k = kmv()
+    alpha, beta = scal(prec, 0.7, -0.3)
+    cases = [(1, 1, 1, 0, 1), (7, 5, 3, 1, 1), (64, 64, 4, 0, 2), (100, 300, 5, 3, -1), (513, 129, 17, 0, 1),
+             (1000, 40, 2, 8, 1), (300, 700, 3, 16, -2)]
+    for m, n, batch, pad, incy in cases:
+        lda = m + (pad % 5)
+        strideA = lda * n + pad                       # pad = 0 or 16: members equally aligned; else not
+        lenx, leny = (n, m) if trans == "N" else (m, n)
+        stridex = 0 if batch % 2 else lenx + 3        # odd batches share one x
+        exty = 1 + (leny - 1) * abs(incy)
+        stridey = exty + 2
+        A = rand(prec, (batch - 1) * strideA + lda * n, 11 + m)
+        x = rand(prec, (batch - 1) * stridex + lenx, 12 + m)
+        y0 = y_buffer(prec, leny, incy, stridey, batch, 13 + m)
+        y = y0.clone()
+        k.GEMV_STRIDED_BATCHED[prec](trans, m, n, alpha, A, lda, strideA, x, 1, stridex, beta, y, incy, stridey, batch)
+        torch.cuda.synchronize()
+        Ah, xh, yh, y0h = A.cpu().numpy(), x.cpu().numpy(), y.cpu().numpy(), y0.cpu().numpy()
+        is_out = np.zeros(yh.size, dtype=bool)
+        for b in range(batch):
+            sl = slice(b * stridey, b * stridey + exty)
+            is_out[b * stridey: b * stridey + exty: abs(incy)] = True
+            kw = dict(lda=lda, incy=incy)
+            want = oracle.gemv(prec, trans, m, n, alpha, Ah[b * strideA:], xh[b * stridex: b * stridex + lenx], beta,
+                               y0h[sl], mode=oracle.MODE_X, **kw)
+            den = oracle.gemv(prec, trans, m, n, alpha, Ah[b * strideA:], xh[b * stridex: b * stridex + lenx], beta,
+                              y0h[sl], mode=oracle.MODE_ABS, **kw)
+            err = errors(prec, logical(yh[sl], leny, incy), logical(want, leny, incy), logical(den, leny, incy), lenx)
+            check(prec, err, f"{prec}gemv_strided_batched {trans} {m}x{n} member {b}/{batch}")
+        assert np.array_equal(yh[~is_out].view(np.uint8), y0h[~is_out].view(np.uint8)), "wrote between outputs"
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+def test_symv_strided_batched(prec, uplo):
+    k = kmv()
+    alpha, beta = scal(prec, -1.1, 0.4)
+    for n, batch, pad, incy in [(1, 1, 0, 1), (8, 4, 0, 1), (9, 3, 1, -1), (63, 5, 16, 2), (64, 2, 0, 1), (65, 3, 2, 1),
+                                 (129, 4, 0, -2), (200, 6, 3, 1), (257, 2, 5, 1), (511, 2, 0, 1), (512, 3, 0, 1),
+                                 (513, 2, 1, 1), (777, 2, 0, 1), (1100, 3, 0, 1)]:   # up to 512: one workgroup per member; beyond: small-matrix kernel
+        lda = n + (pad % 4)
+        strideA = lda * n + pad
+        stridex = 0 if batch % 2 else n + 1
+        exty = 1 + (n - 1) * abs(incy)
+        stridey = exty + 1
+        A = rand(prec, (batch - 1) * strideA + lda * n, 21 + n)
+        host = A.cpu().numpy()                         # the oracle reads the stored triangle only
+        for b in range(batch):
+            blk = A[b * strideA: b * strideA + lda * n].view(n, lda)
+            wl.poison_triangle(blk, n, uplo, real_diag=False)
+            if prec in "cz":
+                d = torch.arange(n, device=DEV)
+                torch.view_as_real(blk)[d, d, 1] = NAN      # HEMV ignores the diagonal's imaginary part
+        x = rand(prec, (batch - 1) * stridex + n, 22 + n)
+        y0 = y_buffer(prec, n, incy, stridey, batch, 23 + n)
+        y = y0.clone()
+        k.SYMV_STRIDED_BATCHED[prec](uplo, n, alpha, A, lda, strideA, x, 1, stridex, beta, y, incy, stridey, batch)
+        torch.cuda.synchronize()
+        xh, yh, y0h = x.cpu().numpy(), y.cpu().numpy(), y0.cpu().numpy()
+        is_out = np.zeros(yh.size, dtype=bool)
+        for b in range(batch):
+            sl = slice(b * stridey, b * stridey + exty)
+            is_out[b * stridey: b * stridey + exty: abs(incy)] = True
+            args = (prec, uplo, n, alpha, host[b * strideA:], xh[b * stridex: b * stridex + n], beta, y0h[sl])
+            want = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_X)
+            den = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_ABS)
+            err = errors(prec, logical(yh[sl], n, incy), logical(want, n, incy), logical(den, n, incy), n)
+            check(prec, err, f"symv/hemv_strided_batched {prec} {uplo} n={n} member {b}/{batch}")
+        assert np.array_equal(yh[~is_out].view(np.uint8), y0h[~is_out].view(np.uint8)), "wrote between outputs"
+
+
+def test_batch_longer_than_one_launch_and_special_scalars():
+    k = kmv()
+    m, n, batch = 4, 3, 70000                           # 65535 members per launch: two launches
+    A = rand("d", batch * m * n, 1)
+    x = rand("d", batch * n, 2)
+    y0 = rand("d", batch * m, 3)
+    y = y0.clone()
+    k.dgemv_strided_batched("N", m, n, 2.0, A, m, m * n, x, 1, n, -1.0, y, 1, m, batch)
+    torch.cuda.synchronize()
+    Ah = A.cpu().numpy().reshape(batch, n, m)           # member, column, row
+    want = 2.0 * np.einsum("bji,bj->bi", Ah, x.cpu().numpy().reshape(batch, n)) - y0.cpu().numpy().reshape(batch, m)
+    got = y.cpu().numpy().reshape(batch, m)
+    assert np.max(np.abs(got - want)) <= 1e-14
+    for b in (0, 65534, 65535, 65536, batch - 1):       # around the launch boundary, through the oracle
+        w = oracle.gemv("d", "N", m, n, 2.0, A.cpu().numpy()[b * m * n:], x.cpu().numpy()[b * n: b * n + n], -1.0,
+                        y0.cpu().numpy()[b * m: b * m + m], lda=m, mode=oracle.MODE_X)
+        assert np.max(np.abs(got[b] - w)) <= 1e-14
+    # alpha = 0: y <- beta*y, A and x (NaN here) are not referenced; beta = 0 with NaN in y
+    y = y0.clone()
+    k.dgemv_strided_batched("T", n, m, 0.0, torch.full_like(A, NAN), n, m * n, torch.full_like(x, NAN), 1, n, 3.0, y, 1, m, batch)
+    assert torch.equal(y, 3.0 * y0)
+    y = torch.full_like(y0, NAN)
+    k.dgemv_strided_batched("N", m, n, 2.0, A, m, m * n, x, 1, n, 0.0, y, 1, m, batch)
+    torch.cuda.synchronize()
+    want0 = 2.0 * np.einsum("bji,bj->bi", Ah, x.cpu().numpy().reshape(batch, n))
+    assert np.max(np.abs(y.cpu().numpy().reshape(batch, m) - want0)) <= 1e-14
+    # batch = 0 and alpha = 0, beta = 1: nothing happens
+    y = y0.clone()
+    k.dgemv_strided_batched("N", m, n, 2.0, A, m, m * n, x, 1, n, 0.5, y, 1, m, 0)
+    k.dsymv_strided_batched("L", 3, 0.0, A, 3, 9, x, 1, 3, 1.0, y, 1, 3, 100)
+    assert torch.equal(y, y0)
