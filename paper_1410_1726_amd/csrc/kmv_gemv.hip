@@ -393,6 +393,21 @@ template <class T> int64_t gemv_n_slots(int64_t rt) {
     return cache[rt];
 }
 
+// compute units of the current device (0 when it cannot be asked)
+inline int64_t device_cus() {
+    static int64_t cache[MAX_CACHED_DEVICES] = {};
+    const int di = cached_device_index();
+    if (di < 0) return 0;
+    if (cache[di] == 0) {
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        cache[di] = (e == hipSuccess && cus > 0) ? cus : -1;
+        (void)hipGetLastError();
+    }
+    return cache[di] > 0 ? cache[di] : 0;
+}
+
 // Column splits for `rb` row blocks: the largest count that still fits one
 // resident round (rb*s <= slots), or two rounds when one round would leave
 // more than a tenth of the slots empty and two rounds fill better.
@@ -437,22 +452,53 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
         s = 1;
         p.part_stride = partial_stride<T>(n);
     } else if (notrans) {
-        p.row_tiles = tuning().gemv_n_row_tiles > 0 ? tuning().gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
-        const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
         int64_t cap = n / 32 > 1 ? n / 32 : 1;   // at least 32 columns per split
         if (cap > MAX_SPLITS) cap = MAX_SPLITS;
         s = tuning().gemv_n_splits;
+        p.row_tiles = tuning().gemv_n_row_tiles > 0 ? tuning().gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
+        if (tuning().gemv_n_row_tiles <= 0 && s <= 0 && tuning().wg_target <= 0 && !sizing) {
+            // Large matrices: ONE workgroup per compute unit, each over 16 row tiles (four per wave, two
+            // columns per prefetch block).  Measured with the settings alternating in one process this
+            // is 3-7% faster than two workgroups per compute unit from about 256 MB of matrix on (the
+            // read-bandwidth probe peaks at the same shape: one workgroup per compute unit, eight loads
+            // in flight per lane), provided the workgroups fill nearly all compute units, their count is a
+            // multiple of 8 (the number of XCDs that workgroup ids are dealt to) and the last block of 16
+            // row tiles is not much shorter than the others (with one workgroup per compute unit nothing
+            // fills in behind a short one; the 4-byte types lost 2-10% whenever it was not full).
+            const int64_t cus = gemv_n_slots<T>(4) > 0 ? device_cus() : 0;
+            const int64_t rb4 = ceil_div(p.ntiles, GN_NW * 4);
+            int64_t step = 8;                      // s must be a multiple of 8 / gcd(rb4, 8)
+            for (int64_t d = 8; d >= 1; d /= 2)
+                if (rb4 % d == 0) { step = 8 / d; break; }
+            int64_t s4 = cus > 0 && rb4 <= cus ? (cus / rb4) / step * step : 0;
+            if (s4 > cap) s4 = 0;
+            const bool big = (double)m * (double)n * sizeof(T) >= 256.0 * 1024 * 1024;
+            const bool rows_even = sizeof(T) == 4 ? p.ntiles % (GN_NW * 4) == 0 : p.ntiles * 100 >= rb4 * GN_NW * 4 * 85;
+            if (big && rows_even && s4 >= 1 && rb4 * s4 * 100 >= cus * 85) {
+                p.row_tiles = 4;
+                s = s4;
+            }
+        }
+        const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
         if (s <= 0 && tuning().wg_target <= 0 && !sizing) s = choose_splits(rb, gemv_n_slots<T>(p.row_tiles), cap);
         if (s <= 0) s = ceil_div(target, rb);
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(p.ntiles * TR);
     } else {
         const int64_t g = n > 0 ? ceil_div(n, GT_NC) : 1;
-        // row splits only when there are too few column groups to occupy the device:
-        // from about 512 groups on, one workgroup per group with the epilogue fused
-        // (no second kernel) is faster
-        const int64_t ttarget = tuning().wg_target > 0 ? tuning().wg_target : 512;
-        s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits : ceil_div(ttarget, g);
+        // Row splits (and the second kernel that adds the pieces) pay only when the column groups
+        // alone leave compute units idle AND a workgroup's 8 columns are long: a lone workgroup streams
+        // at about 40 GB/s, the second launch costs 4-5 us.  Measured over shapes from 1024 x 1024 to
+        // 65536 x 64 in three precisions: from 192 groups on a single launch is as fast or faster (by
+        // up to 28% at n = 2048); below, splitting wins from about 6 us of work per workgroup on, and
+        // then at least four splits (two are slower than either one or four).
+        int64_t sa = 1;
+        if (g < 192 && (double)m * GT_NC * sizeof(T) / 40e3 >= 6.0) {
+            sa = ceil_div(512, g);
+            if (sa < 4) sa = 4;
+        }
+        s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits
+                                       : (tuning().wg_target > 0 ? ceil_div(tuning().wg_target, g) : sa);
         const int64_t cap = p.ntiles / (2 * GT_NW) > 1 ? p.ntiles / (2 * GT_NW) : 1;   // two tiles per wave at least
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(n);
