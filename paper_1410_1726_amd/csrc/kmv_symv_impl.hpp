@@ -845,7 +845,9 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 namespace {
 constexpr int BAL_NC = 4;   // balanced kernel: columns per wave
 constexpr int SMALL_NC = 8;            // small-matrix kernel: outputs per workgroup
-constexpr int64_t SMALL_N = 1536;      // largest n the small-matrix kernel is chosen for
+// largest n the small-matrix kernel is chosen for (measured against the two-launch path at n = 1280 .. 3072:
+// it wins up to 2048 in s and d, up to about 1792 in c and z, and loses by 20-50% from 2560 on)
+template <class T> constexpr int64_t small_n() { return Traits<T>::cplx ? 1792 : 2048; }
 // Row tiles per unit (KT) and workgroups per compute unit that go with it, measured
 // with the settings alternating in one process: two tiles (8 loads per lane and
 // buffer) with two workgroups per compute unit for 16-byte elements from n = 16384
@@ -901,7 +903,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.variant = (int)tuning().symv_variant;
     if (p.variant <= 0) {
         const bool drifting = n >= 12000 && ((uint64_t)lda * sizeof(T)) % 16 != 0;
-        p.variant = n <= SMALL_N ? 3 : (drifting ? 1 : 2);
+        p.variant = n <= small_n<T>() ? 3 : (drifting ? 1 : 2);
     }
     if (n > (int64_t)1 << 30 && p.variant == 2) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
