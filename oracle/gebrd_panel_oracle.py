@@ -1,0 +1,100 @@
+"""CPU oracle for the panel step of the bidiagonal reduction (test infrastructure,
+never the product path).
+
+The paper's Section 10 names the bidiagonal reduction as the consumer of GEMV on
+sub-blocks: every column of a panel multiplies the trailing block once from the
+left (transposed) and once from the right, and several tall or wide panels of
+accumulated vectors besides.  The paper prints no algorithm; this file writes out
+the published "labrd" panel step (m >= n, upper bidiagonal) from its definition,
+column by column, with plain numpy products in extended precision:
+
+for i = 0 .. nb-1, with V, U the reflector vectors so far and X, Y the companion
+panels (A is m x n; everything not yet reduced keeps its input values):
+
+  1. column i up to date:   a = A[i:, i] - V[i:, :i] Y[i, :i]^T - X[i:, :i] Ubar[:i, i]
+     where V[i:, :i] lives in A[i:, :i] and Ubar[:i, i] = A[:i, i] (the rows 0..i-1 of column i, which
+     hold the row reflectors' entries)
+  2. column reflector for a:  alpha = a[0], x = a[1:];  beta = -sign(alpha) ||a||,  tauq = (beta - alpha)/beta,
+     v = [1, x / (alpha - beta)];  d_i = beta   (x = 0 gives tauq = 0, beta = alpha)
+  3. if i < n-1:
+       y = A[i:, i+1:]^T v                                  (trailing block, transposed)
+       y -= Y[i+1:, :i] (A[i:, :i]^T v) + A[:i, i+1:]^T (X[i:, :i]^T v);   y *= tauq
+       row i up to date:    r = A[i, i+1:] - Y[i+1:, :i+1] A[i, :i+1]^T - A[:i, i+1:]^T X[i, :i]^T
+       row reflector for r: taup, u = [1, ...], e_i = beta
+       x = A[i+1:, i+1:] u                                  (trailing block)
+       x -= A[i+1:, :i+1] (Y[i+1:, :i+1]^T u) + X[i+1:, :i] (A[:i, i+1:] u);   x *= taup
+     Y[i+1:, i] = y,  X[i+1:, i] = x
+
+so that afterwards  A - V Y^T - X U^T  on the trailing block equals Q^T A P there, and the leading nb
+rows and columns of Q^T A P are upper bidiagonal with diagonal d and superdiagonal e.  V is stored in
+A on and below the diagonal of the first nb columns (leading ones explicit), U in A right of the diagonal
+of the first nb rows (leading ones explicit, at column i+1).  No rescaling of the norms.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_WIDE = {np.dtype(np.float32): np.float64, np.dtype(np.float64): np.longdouble}
+
+
+def _reflector(alpha, x, dt):
+    xnorm = np.sqrt(np.sum(x * x)) if x.size else dt(0)
+    if xnorm == 0:
+        return alpha, dt(0), x
+    beta = -np.copysign(np.sqrt(alpha * alpha + xnorm * xnorm), alpha)
+    return beta, (beta - alpha) / beta, x / (alpha - beta)
+
+
+def gebrd_panel(A, nb, *, wide=True):
+    """Panel step on a copy of the m x n matrix ``A`` (m >= n, 0 <= nb <= n).
+
+    Returns ``dict(A=..., d=..., e=..., tauq=..., taup=..., X=..., Y=...)``: ``A`` with the first nb
+    columns and rows overwritten by the reflector vectors (ones explicit), ``X`` (m x nb) and ``Y``
+    (n x nb) with rows 0..i of column i zero (scratch in the device routine).
+    """
+    A = np.asarray(A)
+    m, n = A.shape
+    assert m >= n and 0 <= nb <= n
+    dt = _WIDE[A.dtype] if wide else A.dtype.type
+    W = A.astype(dt).copy()
+    X = np.zeros((m, nb), dtype=dt)
+    Y = np.zeros((n, nb), dtype=dt)
+    d = np.zeros(nb, dtype=dt)
+    e = np.zeros(nb, dtype=dt)
+    tauq = np.zeros(nb, dtype=dt)
+    taup = np.zeros(nb, dtype=dt)
+    for i in range(nb):
+        # 1. column i
+        a = W[i:, i].copy()
+        if i:
+            a = a - W[i:, :i] @ Y[i, :i] - X[i:, :i] @ W[:i, i]
+        # 2. column reflector
+        beta, tq, tail = _reflector(a[0], a[1:].copy(), dt)
+        d[i], tauq[i] = beta, tq
+        v = np.concatenate(([dt(1)], tail))
+        W[i:, i] = v
+        if i >= n - 1:
+            continue
+        # 3. y
+        y = W[i:, i + 1:].T @ v
+        if i:
+            y = y - Y[i + 1:, :i] @ (W[i:, :i].T @ v) - W[:i, i + 1:].T @ (X[i:, :i].T @ v)
+        y = tq * y
+        Y[i + 1:, i] = y
+        # row i
+        r = W[i, i + 1:].copy()
+        r = r - Y[i + 1:, :i + 1] @ W[i, :i + 1]
+        if i:
+            r = r - W[:i, i + 1:].T @ X[i, :i]
+        beta, tp, tail = _reflector(r[0], r[1:].copy(), dt)
+        e[i], taup[i] = beta, tp
+        u = np.concatenate(([dt(1)], tail))
+        W[i, i + 1:] = u
+        # x
+        x = W[i + 1:, i + 1:] @ u
+        x = x - W[i + 1:, :i + 1] @ (Y[i + 1:, :i + 1].T @ u)
+        if i:
+            x = x - X[i + 1:, :i] @ (W[:i, i + 1:] @ u)
+        x = tp * x
+        X[i + 1:, i] = x
+    return dict(A=W, d=d, e=e, tauq=tauq, taup=taup, X=X, Y=Y)

@@ -1,0 +1,88 @@
+"""Pins of the bidiagonal panel oracle (`oracle/gebrd_panel_oracle.py`) against numpy linear algebra on the
+explicitly formed reflectors: orthogonality, the bidiagonal leading rows and columns of Q^T A P, the
+trailing-block identity A - V Y^T - X U^T = Q^T A P, singular values of a full reduction, and a 2 x 2 case
+worked by hand."""
+import numpy as np
+import pytest
+
+from oracle import gebrd_panel_oracle as go
+
+
+def reflectors(res, m, n, nb):
+    A = np.asarray(res["A"], dtype=np.float64)
+    V = np.zeros((m, nb))
+    U = np.zeros((n, nb))
+    for i in range(nb):
+        V[i:, i] = A[i:, i]
+        if i < n - 1:
+            U[i + 1:, i] = A[i, i + 1:]
+    return V, U
+
+
+def products(V, U, tauq, taup):
+    m, n, nb = V.shape[0], U.shape[0], V.shape[1]
+    Q, P = np.eye(m), np.eye(n)
+    for i in range(nb):
+        Q = Q @ (np.eye(m) - tauq[i] * np.outer(V[:, i], V[:, i]))
+        P = P @ (np.eye(n) - taup[i] * np.outer(U[:, i], U[:, i]))
+    return Q, P
+
+
+def test_hand_worked_two_by_two():
+    # column (3, 4): beta = -5, tauq = 8/5, v = (1, 1/2);  y = tauq * (row of A^T v) = 1.6 * (1*1 + 2*0.5) = 3.2
+    # row 0 right of the diagonal: 1 - y * 1 = -2.2: a single entry, nothing to annihilate: taup = 0, e = -2.2
+    A = np.array([[3.0, 1.0], [4.0, 2.0]])
+    r = go.gebrd_panel(A, 1)
+    assert float(r["d"][0]) == -5.0 and abs(float(r["tauq"][0]) - 1.6) < 1e-18
+    assert float(r["A"][0, 0]) == 1.0 and float(r["A"][1, 0]) == 0.5
+    assert abs(float(r["Y"][1, 0]) - 3.2) < 1e-15
+    assert abs(float(r["e"][0]) + 2.2) < 1e-15 and float(r["taup"][0]) == 0.0 and float(r["A"][0, 1]) == 1.0
+    # x = taup * (...) = 0
+    assert float(r["X"][1, 0]) == 0.0
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("m,n,nb", [(2, 2, 1), (5, 3, 2), (40, 40, 8), (97, 61, 32), (64, 64, 64), (50, 33, 33)])
+def test_two_sided_identities(dtype, m, n, nb):
+    rng = np.random.default_rng(m * 1000 + n * 10 + nb)
+    A0 = rng.uniform(-1, 1, (m, n)).astype(dtype)
+    r = go.gebrd_panel(A0, nb)
+    A64 = A0.astype(np.float64)
+    V, U = reflectors(r, m, n, nb)
+    tauq = np.asarray(r["tauq"], dtype=np.float64)
+    taup = np.asarray(r["taup"], dtype=np.float64)
+    d = np.asarray(r["d"], dtype=np.float64)
+    e = np.asarray(r["e"], dtype=np.float64)
+    X = np.asarray(r["X"], dtype=np.float64)
+    Y = np.asarray(r["Y"], dtype=np.float64)
+    for i in range(nb):
+        assert V[i, i] == 1.0 and np.all(V[:i, i] == 0)
+        assert tauq[i] == 0 or abs(tauq[i] * (V[:, i] @ V[:, i]) - 2) < 1e-13
+        if i < n - 1:
+            assert U[i + 1, i] == 1.0 and np.all(U[:i + 1, i] == 0)
+            assert taup[i] == 0 or abs(taup[i] * (U[:, i] @ U[:, i]) - 2) < 1e-13
+    Q, P = products(V, U, tauq, taup)
+    B = Q.T @ A64 @ P
+    scale = np.linalg.norm(A64)
+    for i in range(nb):
+        assert abs(B[i, i] - d[i]) < 1e-13 * scale
+        assert np.all(np.abs(B[i + 1:, i]) < 1e-13 * scale), "column not reduced"
+        if i < n - 1:
+            assert abs(B[i, i + 1] - e[i]) < 1e-13 * scale
+            assert np.all(np.abs(B[i, i + 2:]) < 1e-13 * scale), "row not reduced"
+        assert np.all(np.abs(B[i, :i]) < 1e-13 * scale)
+    upd = A64 - V @ Y.T - X @ U.T
+    assert np.allclose(upd[nb:, nb:], B[nb:, nb:], atol=1e-12 * scale)
+    # everything outside the first nb rows and columns keeps its input values
+    assert np.array_equal(np.asarray(r["A"])[nb:, nb:].astype(np.float64), A64[nb:, nb:])
+
+
+def test_full_reduction_keeps_singular_values():
+    rng = np.random.default_rng(3)
+    m, n = 45, 30
+    A0 = rng.uniform(-1, 1, (m, n))
+    r = go.gebrd_panel(A0, n)
+    d = np.asarray(r["d"], dtype=np.float64)
+    e = np.asarray(r["e"], dtype=np.float64)[: n - 1]
+    B = np.diag(d) + np.diag(e, 1)
+    assert np.allclose(np.linalg.svd(B, compute_uv=False), np.linalg.svd(A0, compute_uv=False), atol=1e-12)
