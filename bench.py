@@ -47,7 +47,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "batched", "csymv", "rect", "tiny"])
+    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "gebrd", "batched", "csymv", "rect", "tiny"])
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
@@ -273,6 +273,65 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
     }
 
 
+def gebrd_panel_bench(args, k, torch, wl, acc):
+    """One step = the panel step of the bidiagonal reduction (kmv_dgebrd_panel) on the first 64 columns and rows of
+    a 16384 x 16384 fp64 matrix: per column DGEMV-T and DGEMV-N on the whole trailing block (the latter with a
+    strided x, a row of A) and eleven DGEMV on the accumulated panels, two reflectors, two scalings."""
+    m = n = 16384
+    nb, prec = 64, "d"
+    A0 = wl.matrix(prec, m, n, m, seed=0, device="cuda")
+    A = A0.clone()
+    dt = wl.TORCH_DTYPES[prec]
+    X = torch.zeros((nb, m), dtype=dt, device="cuda")
+    Y = torch.zeros((nb, n), dtype=dt, device="cuda")
+    d, e, tauq, taup = (torch.zeros(nb, dtype=dt, device="cuda") for _ in range(4))
+    ws = k.workspace(k.gebrd_panel_workspace_bytes(prec, m, n, nb))
+    stream = torch.cuda.current_stream()
+    nbytes = nflops = big = 0
+    for i in range(nb):
+        mi, ni = m - i, n - i - 1
+        ops = [("gemv_n", mi, i)] * 2 if i else []
+        ops += [("gemv_t", mi, ni), ("gemv_n", ni, i + 1), ("gemv_n", mi - 1, ni), ("gemv_t", ni, i + 1), ("gemv_n", mi - 1, i + 1)]
+        if i:
+            ops += [("gemv_t", mi, i), ("gemv_n", ni, i), ("gemv_t", mi, i), ("gemv_t", i, ni), ("gemv_t", i, ni),
+                    ("gemv_n", i, ni), ("gemv_n", mi - 1, i)]
+        for op, mm, nn in ops:
+            nbytes += acc.algorithmic_bytes(op, prec, mm, nn)
+            nflops += acc.flops(op, prec, mm, nn)
+        big += acc.algorithmic_bytes("gemv_t", prec, mi, ni) + acc.algorithmic_bytes("gemv_n", prec, mi - 1, ni)
+    times = []
+    for step in range(args.warmup + args.steps):
+        A.copy_(A0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        k.dgebrd_panel(m, n, nb, A, m, d, e, tauq, taup, X, m, Y, n, workspace=ws)
+        e1.record(stream)
+        host_ms = (time.perf_counter() - t0) * 1e3
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        if step >= args.warmup:
+            times.append((wall_ms, e0.elapsed_time(e1), host_ms))
+    step_ms = sum(t[0] for t in times) / len(times)
+    value = nbytes / (step_ms * 1e-3) / 1e9
+    return {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "panel step of the bidiagonal reduction (kmv_dgebrd_panel), m=n=16384, nb=64, lda=m, "
+                               "U[-1,1]: 128 DGEMV on trailing blocks + about 690 DGEMV on the panels",
+                   "products_per_step": 2 * nb + 11 * (nb - 1)},
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "gflops": round(nflops / (step_ms * 1e-3) / 1e9, 1),
+        "device_ms_per_step": round(sum(t[1] for t in times) / len(times), 3),
+        "host_enqueue_ms_per_step": round(sum(t[2] for t in times) / len(times), 3),
+        "trailing_block_share_of_bytes": round(big / nbytes, 4),
+        "roofline": None,
+    }
+
+
 def batched_bench(args, k, torch, wl, acc):
     """One step = strided batches of small fp64 products, 1 GiB of matrices per batch: DGEMV N and T and DSYMV L at
     n = 64 .. 1024, one call (one launch) per batch.  For comparison the same products as a loop of single calls
@@ -426,6 +485,9 @@ def main():
 
     if args.workload == "batched":
         print(json.dumps(batched_bench(args, k, torch, wl, acc)))
+        return
+    if args.workload == "gebrd":
+        print(json.dumps(gebrd_panel_bench(args, k, torch, wl, acc)))
         return
     if args.workload == "sytrd":
         print(json.dumps(sytrd_panel_bench(args, k, torch, wl, acc)))

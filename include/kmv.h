@@ -234,6 +234,36 @@ int kmv_dsytrd_panel(char uplo, int64_t n, int64_t nb, double* A, int64_t lda, d
                      int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
 size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
 
+/* ---- Panel step of the bidiagonal reduction (Section 10: GEMV on the trailing
+ * block and on the accumulated panels, on sub-blocks at arbitrary row and
+ * column offsets, with strided vectors).  For s and d, m >= n, upper
+ * bidiagonal.  For the first nb columns and rows of the m x n matrix A
+ * (device): column i is brought up to date, a reflector H_i = I - tauq_i v_i
+ * v_i^T annihilates it below the diagonal, y_i is formed from the trailing
+ * block (transposed product); row i is brought up to date, a reflector G_i =
+ * I - taup_i u_i u_i^T annihilates it right of the superdiagonal, x_i is
+ * formed from the trailing block; so that A - V Y^T - X U^T on the trailing
+ * block is Q^T A P there.
+ * On exit (all device memory): A[i..m-1][i] = v_i with A[i][i] = 1, A[i][i+1..
+ * n-1] = u_i with A[i][i+1] = 1; d[i] the diagonal and e[i] the superdiagonal
+ * entry of the bidiagonal form, tauq[i], taup[i]; X (m x nb, ldx >= m) holds
+ * x_i in X[i+1..m-1][i], Y (n x nb, ldy >= n) holds y_i in Y[i+1..n-1][i]
+ * (rows 0..i of column i of X and Y are scratch).  Rows and columns nb.. of A
+ * beyond the panel are not modified.  The last column of the matrix has no
+ * row reflector (e = taup = 0).  Norms are formed without rescaling.
+ * Only enqueues kernels on `stream` (about twenty per column), capturable.
+ * Workspace: kmv_gebrd_panel_workspace_bytes(prec, m, n, nb), 256-byte
+ * aligned.  Errors: negated argument number (m 1, n 2 (0 <= n <= m), nb 3
+ * (0 <= nb <= n), lda 5, ldx 11, ldy 13), KMV_ERR_NULL, KMV_ERR_WORKSPACE, or
+ * the code of a failing launch (the columns before it are done). */
+int kmv_sgebrd_panel(int64_t m, int64_t n, int64_t nb, float* A, int64_t lda, float* d, float* e, float* tauq,
+                     float* taup, float* X, int64_t ldx, float* Y, int64_t ldy, void* workspace,
+                     size_t workspace_bytes, void* stream);
+int kmv_dgebrd_panel(int64_t m, int64_t n, int64_t nb, double* A, int64_t lda, double* d, double* e, double* tauq,
+                     double* taup, double* X, int64_t ldx, double* Y, int64_t ldy, void* workspace,
+                     size_t workspace_bytes, void* stream);
+size_t kmv_gebrd_panel_workspace_bytes(char prec, int64_t m, int64_t n, int64_t nb);
+
 /* ---- Strided batches: `batch` products of one shape in one call; member b
  * uses A + b*strideA, x + b*stridex, y + b*stridey (strides in elements, >= 0;
  * 0 shares an input among the members; the outputs of two members must not

@@ -60,6 +60,10 @@ def _load() -> ctypes.CDLL:
     for p_ in "sd":
         f = getattr(lib, f"kmv_{p_}sytrd_panel")
         f.argtypes, f.restype = [ch, i64, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp], ci
+    for p_ in "sd":
+        f = getattr(lib, f"kmv_{p_}gebrd_panel")
+        f.argtypes, f.restype = [i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, i64, vp, i64, vp, sz, vp], ci
+    lib.kmv_gebrd_panel_workspace_bytes.argtypes, lib.kmv_gebrd_panel_workspace_bytes.restype = [ch, i64, i64, i64], sz
     lib.kmv_sytrd_panel_workspace_bytes.argtypes, lib.kmv_sytrd_panel_workspace_bytes.restype = [ch, i64, i64], sz
     gemv_b_args = [ch, i64, i64, vp, vp, i64, i64, vp, i64, i64, vp, vp, i64, i64, i64, vp]
     symv_b_args = [ch, i64, vp, vp, i64, i64, vp, i64, i64, vp, vp, i64, i64, i64, vp]
@@ -387,6 +391,26 @@ def _sytrd_panel(prec):
     return call
 
 
+def gebrd_panel_workspace_bytes(prec, m, n, nb) -> int:
+    return int(lib.kmv_gebrd_panel_workspace_bytes(prec.encode(), m, n, nb))
+
+
+def _gebrd_panel(prec):
+    def call(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, workspace=None, stream=None, check=True):
+        wsp, wsb = _ws_args(workspace, lambda: gebrd_panel_workspace_bytes(prec, max(m, 0), max(n, 0), max(nb, 0)), A)
+        rc = getattr(lib, f"kmv_{prec}gebrd_panel")(
+            m, n, nb, _ptr(A, prec), lda, _ptr(d, prec), _ptr(e, prec), _ptr(tauq, prec), _ptr(taup, prec),
+            _ptr(X, prec), ldx, _ptr(Y, prec), ldy, ctypes.c_void_p(wsp), wsb, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(f"{prec}gebrd_panel", rc)
+        return rc
+    call.__name__ = f"{prec}gebrd_panel"
+    call.__doc__ = "Panel step of the bidiagonal reduction on device tensors (see include/kmv.h)."
+    return call
+
+
+GEBRD_PANEL = {p_: _gebrd_panel(p_) for p_ in "sd"}
+sgebrd_panel, dgebrd_panel = GEBRD_PANEL["s"], GEBRD_PANEL["d"]
 SYTRD_PANEL = {p_: _sytrd_panel(p_) for p_ in "sd"}
 ssytrd_panel, dsytrd_panel = SYTRD_PANEL["s"], SYTRD_PANEL["d"]
 GEMV_DEVSCALARS = {p_: _gemv_devscalars(p_) for p_ in "sdcz"}

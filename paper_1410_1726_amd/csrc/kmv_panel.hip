@@ -1,4 +1,5 @@
-// Panel step of the symmetric tridiagonal reduction, built on the library's own
+// Panel steps of the two-sided reductions - symmetric tridiagonal (below) and
+// bidiagonal (further down) - built on the library's own
 // SYMV and GEMV calls (paper, Section 10: the two-sided reductions spend their
 // memory-bound time in exactly these products - SYMV on the trailing block once
 // per column, GEMV on the tall panels of accumulated reflectors - and always on
@@ -41,47 +42,61 @@ template <class T> __device__ __forceinline__ T block_sum(T v, T* red) {
 // keeps PU independent loads in flight per pass, which is what their time depends on.
 constexpr int PU = 8;
 
-// Householder reflector for the vector (alpha, x) stored in col[0..m-1]: on exit col = (1, x / (alpha - beta)),
-// *e = beta = -sign(alpha) * ||(alpha, x)||, *tau = (beta - alpha) / beta; a zero x gives tau = 0, beta = alpha.
-template <class T> __global__ __launch_bounds__(PT) void reflector_kernel(int64_t m, T* col, T* e, T* tau) {
+// Householder reflector for the vector (alpha, x): alpha at *head, the m-1 elements of x at tail[k*inc].
+// On exit *head = 1, x <- x / (alpha - beta), *e = beta = -sign(alpha) * ||(alpha, x)||,
+// *tau = (beta - alpha) / beta; a zero x gives tau = 0, beta = alpha.
+template <class T>
+__global__ __launch_bounds__(PT) void reflector_kernel(int64_t m, T* head, T* tail, int64_t inc, T* e, T* tau) {
     __shared__ T red[PT / WAVE];
-    const T alpha = col[0];
+    const T alpha = *head;
     T ss = 0;
-    for (int64_t base = 1 + threadIdx.x; base < m; base += (int64_t)PU * PT) {
+    for (int64_t base = threadIdx.x; base < m - 1; base += (int64_t)PU * PT) {
         T x[PU];
 #pragma unroll
         for (int u = 0; u < PU; ++u) {
             const int64_t k = base + (int64_t)u * PT;
-            x[u] = k < m ? col[k] : T(0);
+            x[u] = k < m - 1 ? tail[k * inc] : T(0);
         }
 #pragma unroll
         for (int u = 0; u < PU; ++u) ss += x[u] * x[u];
     }
-    const T xnorm = sqrt(block_sum(ss, red));    // every thread has read col[0] once this returns
+    const T xnorm = sqrt(block_sum(ss, red));    // every thread has read *head once this returns
     T beta = alpha, t = 0;
     if (xnorm != 0) {
         beta = -copysign(sqrt(alpha * alpha + xnorm * xnorm), alpha);
         t = (beta - alpha) / beta;
         const T scale = T(1) / (alpha - beta);
-        for (int64_t base = 1 + threadIdx.x; base < m; base += (int64_t)PU * PT) {
+        for (int64_t base = threadIdx.x; base < m - 1; base += (int64_t)PU * PT) {
             T x[PU];
 #pragma unroll
             for (int u = 0; u < PU; ++u) {
                 const int64_t k = base + (int64_t)u * PT;
-                x[u] = k < m ? col[k] : T(0);
+                x[u] = k < m - 1 ? tail[k * inc] : T(0);
             }
 #pragma unroll
             for (int u = 0; u < PU; ++u) {
                 const int64_t k = base + (int64_t)u * PT;
-                if (k < m) col[k] = x[u] * scale;
+                if (k < m - 1) tail[k * inc] = x[u] * scale;
             }
         }
     }
     if (threadIdx.x == 0) {
-        col[0] = 1;
+        *head = 1;
         *e = beta;
         *tau = t;
     }
+}
+
+// dst[k*dinc] = src[k*sinc]: a row of a column-major matrix to a contiguous vector and back
+template <class T> __global__ void strided_copy_kernel(int64_t len, const T* src, int64_t sinc, T* dst, int64_t dinc) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < len) dst[k * dinc] = src[k * sinc];
+}
+
+// v <- (*s) v, the scalar in device memory
+template <class T> __global__ void scale_kernel(int64_t len, const T* s, T* v) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < len) v[k] *= *s;
 }
 
 // w <- tau w - (tau/2) ((tau w).v) v.  Then, for the next column's update, the first `cnt` entries of the
@@ -211,7 +226,7 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* ta
         T* v = col + 1;                         // A[i+1:, i]
         T* w = W + (i + 1) + i * ldw;           // W[i+1:, i]
         T* small = W + i * ldw;                 // W[:i, i]: the i-vector of the corrections
-        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, v, e + i, tau + i);
+        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, v, v + 1, (int64_t)1, e + i, tau + i);
         hipError_t he = hipGetLastError();
         if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
         rc = symv('L', m, &one, A + (i + 1) + (i + 1) * lda, lda, v, 1, &zero, w, 1, ws, wsb, stream);
@@ -234,6 +249,123 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* ta
     return KMV_OK;
 }
 
+// bytes at the front of the workspace for the contiguous copy of the current row
+template <class T> size_t row_bytes(int64_t n) { return (size_t)((n * sizeof(T) + 255) / 256) * 256; }
+
+// the row copy plus the largest workspace any product of the bidiagonal panel asks for
+template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
+    if (m <= 0 || n <= 0 || nb <= 0 || m < n) return 0;
+    if (nb > n) nb = n;
+    const char p = Calls<T>::prec;
+    size_t need = 0;
+    for (int64_t i = 0; i < nb; ++i) {
+        const int64_t mi = m - i, ni = n - i - 1;
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi, i));
+        if (ni <= 0) continue;
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', mi, ni));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', mi, i));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', ni, i + 1));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', i, ni));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi - 1, ni));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', ni, i + 1));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi - 1, i + 1));
+        need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', i, ni));
+    }
+    return row_bytes<T>(n) + need;
+}
+
+// Panel step of the bidiagonal reduction (m >= n, upper bidiagonal): the published "labrd" step written
+// from its definition on top of the GEMV entry points.  Per column two products with the whole trailing
+// block (transposed from the left, plain from the right, the latter with a strided x: a row of A) and
+// eleven with the tall or wide panels of vectors accumulated so far, two reflectors and two scalings by
+// tau; everything on the device and on the caller's stream.  The row that becomes u_i is worked on in a
+// contiguous copy (one strided gather before, one scatter after): a reflector along a row of stride lda took
+// 36 us on average at n = 16384, and the three products that take u_i as x need no packing this way.
+template <class T>
+int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, T* d, T* e, T* tauq, T* taup, T* X, int64_t ldx,
+                T* Y, int64_t ldy, void* ws, size_t wsb, void* stream) {
+    if (m < 0) return -1;
+    if (n < 0 || n > m) return -2;
+    if (nb < 0 || nb > n) return -3;
+    if (lda < (m > 1 ? m : 1)) return -5;
+    if (ldx < (m > 1 ? m : 1)) return -11;
+    if (ldy < (n > 1 ? n : 1)) return -13;
+    if (n == 0 || nb == 0) return KMV_OK;
+    if (!A || !d || !e || !tauq || !taup || !X || !Y) return KMV_ERR_NULL;
+    if (!ws || wsb < gebrd_workspace<T>(m, n, nb) || ((uintptr_t)ws % 256) != 0) return KMV_ERR_WORKSPACE;
+    T* urow = static_cast<T*>(ws);            // row i right of the diagonal, contiguous
+    ws = static_cast<char*>(ws) + row_bytes<T>(n);
+    wsb -= row_bytes<T>(n);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const T one = 1, zero = 0, minus = -1;
+    const auto gemv = Calls<T>::gemv;
+    auto a_ = [&](int64_t i, int64_t j) { return A + i + j * lda; };
+    auto x_ = [&](int64_t i, int64_t j) { return X + i + j * ldx; };
+    auto y_ = [&](int64_t i, int64_t j) { return Y + i + j * ldy; };
+    int rc = KMV_OK;
+#define KMV_GEMV(...)                                   \
+    do {                                                \
+        rc = gemv(__VA_ARGS__, ws, wsb, stream);        \
+        if (rc) return rc;                              \
+    } while (0)
+    for (int64_t i = 0; i < nb; ++i) {
+        const int64_t mi = m - i, ni = n - i - 1;
+        if (i > 0) {   // column i catches up with the panels
+            KMV_GEMV('N', mi, i, &minus, a_(i, 0), lda, y_(i, 0), ldy, &one, a_(i, i), (int64_t)1);
+            KMV_GEMV('N', mi, i, &minus, x_(i, 0), ldx, a_(0, i), (int64_t)1, &one, a_(i, i), (int64_t)1);
+        }
+        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, mi, a_(i, i), a_(i, i) + 1, (int64_t)1,
+                           d + i, tauq + i);
+        hipError_t he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        if (ni <= 0) {     // last column of the matrix: no row reflector
+            hipLaunchKernelGGL((no_reflector_kernel<T>), dim3(1), dim3(1), 0, s, e + i, taup + i);
+            he = hipGetLastError();
+            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+            continue;
+        }
+        // y = tauq * (trailing block^T v - corrections)
+        KMV_GEMV('T', mi, ni, &one, a_(i, i + 1), lda, a_(i, i), (int64_t)1, &zero, y_(i + 1, i), (int64_t)1);
+        if (i > 0) {
+            KMV_GEMV('T', mi, i, &one, a_(i, 0), lda, a_(i, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
+            KMV_GEMV('N', ni, i, &minus, y_(i + 1, 0), ldy, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
+            KMV_GEMV('T', mi, i, &one, x_(i, 0), ldx, a_(i, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
+            KMV_GEMV('T', i, ni, &minus, a_(0, i + 1), lda, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
+        }
+        hipLaunchKernelGGL((scale_kernel<T>), dim3((unsigned)ceil_div(ni, (int64_t)256)), dim3(256), 0, s, ni, tauq + i,
+                           y_(i + 1, i));
+        he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        // row i catches up and gets its reflector, in a contiguous copy that then goes back into the row
+        const dim3 cgrid((unsigned)ceil_div(ni, (int64_t)256));
+        hipLaunchKernelGGL((strided_copy_kernel<T>), cgrid, dim3(256), 0, s, ni, a_(i, i + 1), lda, urow, (int64_t)1);
+        he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        KMV_GEMV('N', ni, i + 1, &minus, y_(i + 1, 0), ldy, a_(i, 0), lda, &one, urow, (int64_t)1);
+        if (i > 0) KMV_GEMV('T', i, ni, &minus, a_(0, i + 1), lda, x_(i, 0), ldx, &one, urow, (int64_t)1);
+        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, ni, urow, urow + 1, (int64_t)1, e + i, taup + i);
+        he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        hipLaunchKernelGGL((strided_copy_kernel<T>), cgrid, dim3(256), 0, s, ni, urow, (int64_t)1, a_(i, i + 1), lda);
+        he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        // x = taup * (trailing block u - corrections)
+        KMV_GEMV('N', mi - 1, ni, &one, a_(i + 1, i + 1), lda, urow, (int64_t)1, &zero, x_(i + 1, i), (int64_t)1);
+        KMV_GEMV('T', ni, i + 1, &one, y_(i + 1, 0), ldy, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
+        KMV_GEMV('N', mi - 1, i + 1, &minus, a_(i + 1, 0), lda, x_(0, i), (int64_t)1, &one, x_(i + 1, i), (int64_t)1);
+        if (i > 0) {
+            KMV_GEMV('N', i, ni, &one, a_(0, i + 1), lda, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
+            KMV_GEMV('N', mi - 1, i, &minus, x_(i + 1, 0), ldx, x_(0, i), (int64_t)1, &one, x_(i + 1, i), (int64_t)1);
+        }
+        hipLaunchKernelGGL((scale_kernel<T>), dim3((unsigned)ceil_div(mi - 1, (int64_t)256)), dim3(256), 0, s, mi - 1,
+                           taup + i, x_(i + 1, i));
+        he = hipGetLastError();
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+    }
+#undef KMV_GEMV
+    return KMV_OK;
+}
+
 }  // namespace
 }  // namespace kmv
 
@@ -246,6 +378,21 @@ int kmv_ssytrd_panel(char uplo, int64_t n, int64_t nb, float* A, int64_t lda, fl
 int kmv_dsytrd_panel(char uplo, int64_t n, int64_t nb, double* A, int64_t lda, double* e, double* tau, double* W,
                      int64_t ldw, void* workspace, size_t workspace_bytes, void* stream) {
     return kmv::sytrd_panel<double>(uplo, n, nb, A, lda, e, tau, W, ldw, workspace, workspace_bytes, stream);
+}
+int kmv_sgebrd_panel(int64_t m, int64_t n, int64_t nb, float* A, int64_t lda, float* d, float* e, float* tauq, float* taup,
+                     float* X, int64_t ldx, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    return kmv::gebrd_panel<float>(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, workspace, workspace_bytes, stream);
+}
+int kmv_dgebrd_panel(int64_t m, int64_t n, int64_t nb, double* A, int64_t lda, double* d, double* e, double* tauq,
+                     double* taup, double* X, int64_t ldx, double* Y, int64_t ldy, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    return kmv::gebrd_panel<double>(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, workspace, workspace_bytes, stream);
+}
+size_t kmv_gebrd_panel_workspace_bytes(char prec, int64_t m, int64_t n, int64_t nb) {
+    if (prec == 's') return kmv::gebrd_workspace<float>(m, n, nb);
+    if (prec == 'd') return kmv::gebrd_workspace<double>(m, n, nb);
+    return 0;
 }
 size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb) {
     if (prec == 's') return kmv::panel_workspace<float>(n, nb);

@@ -238,3 +238,22 @@ def test_strided_batched_argument_errors(prec):
     assert symv(incx=-1) == -8 and symv(sx=-1) == -9 and symv(incy=0) == -12 and symv(sy=7) == -13
     assert symv(batch=-1) == -14 and symv(batch=0) == 0 and symv(n=0, lda=1) == 0
     assert symv(A=None) == kmv.ERR_NULL
+
+
+@pytest.mark.parametrize("prec", "sd")
+def test_gebrd_panel_argument_errors(prec):
+    f = kmv.GEBRD_PANEL[prec]
+
+    def call(m=8, n=6, nb=4, lda=8, ldx=8, ldy=6, A=DUMMY, X=DUMMY):
+        return f(m, n, nb, A, lda, DUMMY, DUMMY, DUMMY, DUMMY, X, ldx, DUMMY, ldy, workspace=NOWS, stream=0, check=False)
+
+    assert call(m=-1) == -1
+    assert call(n=-1) == -2 and call(n=9) == -2            # m >= n only
+    assert call(nb=-1) == -3 and call(nb=7) == -3
+    assert call(lda=7) == -5 and call(ldx=7) == -11 and call(ldy=5) == -13
+    assert call(nb=0) == 0 and call(m=0, n=0, nb=0, lda=1, ldx=1, ldy=1) == 0
+    assert call(A=None) == kmv.ERR_NULL and call(X=None) == kmv.ERR_NULL
+    assert call() == kmv.ERR_WORKSPACE
+    need = kmv.gebrd_panel_workspace_bytes(prec, 4096, 4096, 64)
+    assert need >= kmv.gemv_workspace_bytes(prec, "T", 4096, 4095)
+    assert kmv.gebrd_panel_workspace_bytes("c", 64, 64, 8) == 0 and kmv.gebrd_panel_workspace_bytes(prec, 8, 9, 2) == 0

@@ -134,3 +134,55 @@ def test_panel_is_deterministic_and_capturable(prec):
         cols = torch.arange(nb, device=DEV).unsqueeze(1)
         defined = rows > cols
         assert torch.equal(W[defined], ref[1][defined])
+
+
+# ------------------------------------------------------------ bidiagonal panel ----
+from oracle import gebrd_panel_oracle as go   # noqa: E402
+
+
+@pytest.mark.parametrize("prec", "sd")
+@pytest.mark.parametrize("m,n,nb,pad,off", [(1, 1, 1, 0, 0), (2, 2, 2, 0, 0), (5, 3, 3, 1, 0), (100, 100, 16, 0, 0),
+                                            (700, 500, 32, 36, 0), (1500, 1500, 64, 0, 0), (1300, 900, 24, 52, 17),
+                                            (900, 1500 - 700, 8, 3, 1)])
+def test_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
+    """kmv_{s,d}gebrd_panel on a block at (off, off) of a parent with padded leading dimension: reflector
+    vectors, d, e, tauq, taup, X and Y element by element; everything outside the first nb rows and columns
+    of the block bit-unchanged"""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    lda, ldx, ldy = m + off + pad, m + pad // 2, n + pad // 3
+    parent = wl.matrix(prec, m + off, n + off, lda, seed=m + n + nb, device=DEV)
+    before = parent.clone()
+    A = parent[off:, off:] if off else parent
+    nanv = float("nan")
+    X = torch.full((nb, ldx), nanv, dtype=dt, device=DEV)
+    Y = torch.full((nb, ldy), nanv, dtype=dt, device=DEV)
+    d, e, tauq, taup = (torch.full((nb,), nanv, dtype=dt, device=DEV) for _ in range(4))
+    k.GEBRD_PANEL[prec](m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy)
+    torch.cuda.synchronize()
+    A0 = before[off:off + n, off:off + m].cpu().numpy().T.copy()
+    A1 = parent[off:off + n, off:off + m].cpu().numpy().T.copy()
+    want = go.gebrd_panel(A0, nb)
+    tol = TOL[prec]
+    panel = np.zeros((m, n), dtype=bool)       # first nb columns (column reflectors) and first nb rows (row reflectors)
+    panel[:, :nb] = True
+    panel[:nb, :] = True
+    assert rel(A1[panel], np.asarray(want["A"])[panel]) <= tol
+    for name, got in (("d", d), ("e", e), ("tauq", tauq), ("taup", taup)):
+        assert rel(got.cpu().numpy(), want[name]) <= tol, name
+    Xh, Yh = X.cpu().numpy().T[:m], Y.cpu().numpy().T[:n]
+    dx = np.zeros((m, nb), dtype=bool)
+    dy = np.zeros((n, nb), dtype=bool)
+    for i in range(min(nb, n - 1)):
+        dx[i + 1:, i] = True
+        dy[i + 1:, i] = True
+    assert np.all(np.isfinite(Xh[dx])) and np.all(np.isfinite(Yh[dy]))
+    assert rel(Xh[dx], np.asarray(want["X"])[dx]) <= tol
+    assert rel(Yh[dy], np.asarray(want["Y"])[dy]) <= tol
+    # untouched: the parent outside the block, the padding, and the block beyond the panel
+    pb, pa = before.cpu().numpy(), parent.cpu().numpy()           # (cols, lda)
+    touched = np.zeros(pb.shape, dtype=bool)
+    touched[off:off + nb, off:off + m] = True                      # first nb columns of the block
+    touched[off:off + n, off:off + nb] = True                      # first nb rows of the block
+    assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
+    assert np.all(np.isnan(X.cpu().numpy()[:, m:])) and np.all(np.isnan(Y.cpu().numpy()[:, n:]))
