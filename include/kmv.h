@@ -30,8 +30,9 @@
  *   A may point anywhere inside a larger matrix (a sub-block at arbitrary
  *   row / column offsets, Section 6.6): the kernels derive the 128-byte
  *   alignment of the columns from the pointer value and lda, start their
- *   row tiles on the aligned boundary and mask the leading rows, so no
- *   separate "_offset" interface is needed.  No byte outside the m x n
+ *   row tiles on the aligned boundary and mask the leading rows, so the
+ *   "_offset" entry points further down are a convenience, not a faster
+ *   path.  No byte outside the m x n
  *   block (GEMV) or outside the stored triangle (SYMV/HEMV) is ever read.
  *   Complex numbers are interleaved (re, im) pairs.
  *   Vectors: element k of a length-len vector with increment inc is
@@ -54,6 +55,12 @@
  *   KMV_ERR_NULL         A, x, y, alpha or beta is NULL
  *   KMV_ERR_HIP + e      the HIP runtime reported error e at launch
  *   On any error nothing is enqueued and y is untouched.
+ *
+ * Families declared below, in this order: GEMV; SYMV / HEMV; complex
+ * symmetric SYMV; the "_offset" forms that name the parent matrix; the
+ * "_devscalars" forms (alpha, beta in device memory); panel steps of the
+ * tridiagonal and the bidiagonal reduction built on these calls; strided
+ * batches; workspace sizes; the work partition; the bandwidth probe; tuning.
  *
  * Determinism: for fixed arguments (including the alignment of A modulo 128
  * bytes) and fixed tuning values the result is bitwise reproducible; partial
