@@ -259,16 +259,38 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     for (int c = 0; c < NC; ++c) acc[c] = zero_of<T>();
 
     auto is_interior = [&](int64_t t) { return (t * TR - shift >= 0) && ((t + 1) * TR - shift <= a.m); };
-    // edge tile: element loads with the row index clamped into the matrix (all
-    // issued before the first use), rows that do not exist are then skipped
+    // edge tile: the same 16-byte loads as an interior tile, taken at a position clamped into the
+    // column (all issued before the first use); at use the elements are moved to where the lane's
+    // rows expect them and rows that do not exist are skipped.  Fewer rows than one vector: element
+    // loads with the row index clamped.
     auto masked_tile = [&](int64_t t) {
         const int64_t r = t * TR - shift + (int64_t)lane * VEC;
-        T xv[VEC], av[NC][VEC];
         bool ok[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) ok[v] = r + v >= 0 && r + v < a.m;
+        if (a.m >= VEC) {     // wave uniform
+            const int64_t rc = r < 0 ? 0 : (r + VEC > a.m ? a.m - VEC : r);
+            const int dsh = (int)(r - rc);
+            Vec<T> xv = load_cached(x + rc), av[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) av[c] = load_stream(col[c] + rc);
+            xv = shift_elems(xv, dsh);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const Vec<T> sv = shift_elems(av[c], dsh);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    T nacc = acc[c];
+                    fma_op<CONJ>(nacc, sv.e[v], xv.e[v]);
+                    acc[c] = select_of(ok[v], nacc, acc[c]);
+                }
+            }
+            return;
+        }
+        T xv[VEC], av[NC][VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             int64_t row = r + v;
-            ok[v] = row >= 0 && row < a.m;
             row = row < 0 ? 0 : (row >= a.m ? a.m - 1 : row);
             xv[v] = x[row];
 #pragma unroll
