@@ -580,14 +580,22 @@ def test_calls_can_be_captured_in_a_graph():
     n = 1800
     A = wl.matrix("d", n, n, seed=41, device=DEV)
     x = wl.vector("d", n, seed=41, device=DEV)
-    y1, y2, y3 = (torch.zeros(n, dtype=torch.float64, device=DEV) for _ in range(3))
+    y1, y2, y3, y4, y5, y6 = (torch.zeros(n, dtype=torch.float64, device=DEV) for _ in range(6))
     ws = torch.empty(max(k.gemv_workspace_bytes("d", "N", n, n), k.symv_workspace_bytes("d", "L", n)),
                      dtype=torch.uint8, device=DEV)
+    dev_alpha = torch.zeros(1, dtype=torch.float64, device=DEV)
+    dev_beta = torch.zeros(1, dtype=torch.float64, device=DEV)
+    nb, bn = 9, 200                              # a batch of nine 200 x 200 blocks inside A's buffer
 
     def run():
         k.dgemv("N", n, n, 0.7, A, n, x, 1, 0.0, y1, 1, workspace=ws)
         k.dgemv("T", n, n, 1.0, A, n, y1, 1, 0.0, y2, 1, workspace=ws)
         k.dsymv("L", n, -0.5, A, n, y2, 1, 0.0, y3, 1, workspace=ws)
+        # the other families: offsets, scalars written by a kernel of the same capture, a strided batch
+        k.dgemv_offset("N", n, n, 1.0, A, n, x, 1, 0.0, y4, 1, 17, 5, workspace=ws)
+        dev_alpha.copy_(y1[:1])                  # device-side producer of alpha
+        k.dsymv_devscalars("U", n, dev_alpha, A, n, x, 1, dev_beta, y5, 1, workspace=ws)
+        k.dgemv_strided_batched("T", bn, bn, 1.0, A, bn, bn * bn, x, 1, bn, 0.0, y6, 1, bn, nb)
 
     run()                                   # warm up outside the capture (occupancy queries, module load)
     torch.cuda.synchronize()
@@ -598,10 +606,11 @@ def test_calls_can_be_captured_in_a_graph():
         x.copy_(wl.vector("d", n, seed=50 + rep, device=DEV))
         g.replay()
         torch.cuda.synchronize()
-        got = [t.clone() for t in (y1, y2, y3)]
+        got = [t.clone() for t in (y1, y2, y3, y4, y5, y6)]
         run()
         torch.cuda.synchronize()
-        for a_, b_ in zip(got, (y1, y2, y3)):
+        assert float(y5.abs().sum()) > 0 and float(y6.abs().sum()) > 0
+        for a_, b_ in zip(got, (y1, y2, y3, y4, y5, y6)):
             assert torch.equal(a_, b_), f"replay {rep} differs from the eager calls"
 
 
