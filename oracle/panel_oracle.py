@@ -37,7 +37,8 @@ from __future__ import annotations
 
 import numpy as np
 
-_WIDE = {np.dtype(np.float32): np.float64, np.dtype(np.float64): np.longdouble}
+_WIDE = {np.dtype(np.float32): np.float64, np.dtype(np.float64): np.longdouble,
+         np.dtype(np.complex64): np.complex128, np.dtype(np.complex128): np.clongdouble}
 
 
 def sytrd_panel(A, nb, *, wide=True):
@@ -91,5 +92,59 @@ def sytrd_panel(A, nb, *, wide=True):
             w = w - W[i + 1:, :i] @ W[:i, i]
         w = t * w
         w = w - (t / 2) * (w @ v) * v
+        W[i + 1:, i] = w
+    return dict(A=out, e=e, tau=tau, W=W)
+
+
+def hetrd_panel(A, nb, *, wide=True):
+    """The same panel step for a complex Hermitian matrix (lower triangle referenced, the imaginary part of
+    the diagonal ignored): H_i = I - tau_i v_i v_i^H with the published complex reflector (beta real:
+    beta = -sign(Re alpha) ||(alpha, x)||, tau = (beta - alpha) / beta, v = [1, x / (alpha - beta)]; tau = 0 when
+    x = 0 and alpha is real), column update  a = A[i:, i] - V[i:, :i] conj(W[i, :i]) - W[i:, :i] conj(V[i, :i]),
+    w = tau (A22 v - V (W^H v) - W (V^H v)),  w <- w - (tau/2) (w^H v) v,  so that  A - V W^H - W V^H  on the
+    trailing block is Q^H A Q there, with d and e real.  Returns the same dictionary; ``e`` is real.
+    """
+    A = np.asarray(A)
+    n = A.shape[0]
+    assert A.shape == (n, n) and 0 <= nb <= n and np.iscomplexobj(A)
+    dt = _WIDE[A.dtype] if wide else A.dtype.type
+    rt = np.real(dt(0)).dtype.type
+    L = np.tril(A).astype(dt)
+    L[np.arange(n), np.arange(n)] = L[np.arange(n), np.arange(n)].real
+    S = L + np.conj(np.tril(L, -1)).T
+    out = L.copy()
+    V = np.zeros((n, nb), dtype=dt)
+    W = np.zeros((n, nb), dtype=dt)
+    e = np.zeros(nb, dtype=rt)
+    tau = np.zeros(nb, dtype=dt)
+    for i in range(nb):
+        a = S[i:, i].copy()
+        if i:
+            a = a - V[i:, :i] @ np.conj(W[i, :i]) - W[i:, :i] @ np.conj(V[i, :i])
+        a[0] = a[0].real
+        out[i:, i] = a
+        if i >= n - 1:
+            continue
+        alpha = a[1]
+        x = a[2:].copy()
+        xnorm = np.sqrt(np.sum(x.real * x.real + x.imag * x.imag)) if x.size else rt(0)
+        if xnorm == 0 and alpha.imag == 0:
+            beta, t = alpha.real, dt(0)
+        else:
+            beta = -np.copysign(np.sqrt(alpha.real * alpha.real + alpha.imag * alpha.imag + xnorm * xnorm), alpha.real)
+            t = dt((beta - alpha.real) / beta + 1j * (-alpha.imag / beta))
+            x = x / (alpha - beta)
+        e[i], tau[i] = beta, t
+        v = np.concatenate(([dt(1)], x))
+        V[i + 1:, i] = v
+        out[i + 1:, i] = v
+        w = S[i + 1:, i + 1:] @ v
+        if i:
+            W[:i, i] = np.conj(W[i + 1:, :i]).T @ v
+            w = w - V[i + 1:, :i] @ W[:i, i]
+            W[:i, i] = np.conj(V[i + 1:, :i]).T @ v
+            w = w - W[i + 1:, :i] @ W[:i, i]
+        w = t * w
+        w = w - (t / 2) * (np.conj(w) @ v) * v
         W[i + 1:, i] = w
     return dict(A=out, e=e, tau=tau, W=W)

@@ -115,3 +115,67 @@ def test_working_precision_mode_is_close_to_the_wide_one():
     b = po.sytrd_panel(A, 16, wide=True)
     assert a["W"].dtype == np.float32 and b["W"].dtype == np.float64
     assert np.linalg.norm(a["W"] - b["W"]) < 1e-5 * np.linalg.norm(b["W"])
+
+
+# ---------------------------------------------------------------- complex Hermitian ----
+def herm_lower(rng, n, dtype=np.complex128):
+    A = (rng.uniform(-1, 1, (n, n)) + 1j * rng.uniform(-1, 1, (n, n))).astype(dtype)
+    A[np.triu_indices(n, 1)] = np.nan       # never read; the diagonal keeps a garbage imaginary part
+    return A
+
+
+def completed_h(A):
+    L = np.tril(A).astype(np.complex128)
+    L[np.arange(len(L)), np.arange(len(L))] = L.diagonal().real
+    return L + np.conj(np.tril(L, -1)).T
+
+
+def test_hermitian_hand_worked_two_by_two():
+    # n = 2: column 0 has nothing below the subdiagonal: x is empty, alpha = 3 + 4i is not real, so the
+    # reflector is a phase: beta = -|alpha| = -5, tau = (beta - alpha)/beta = 1.6 + 0.8i, v = (1)
+    A = np.array([[2.0 + 9j, np.nan], [3.0 + 4j, 7.0 - 5j]])
+    r = po.hetrd_panel(A, 1)
+    assert float(r["e"][0]) == -5.0
+    assert abs(complex(r["tau"][0]) - (1.6 + 0.8j)) < 1e-15
+    assert complex(r["A"][0, 0]) == 2.0 and complex(r["A"][1, 0]) == 1.0
+    # w = tau * 7 * 1 - (tau/2) * conj(tau * 7) * 1 ... evaluated directly
+    t = 1.6 + 0.8j
+    w = t * 7.0
+    w = w - (t / 2) * np.conj(w)
+    assert abs(complex(r["W"][1, 0]) - w) < 1e-14
+
+
+@pytest.mark.parametrize("dtype", [np.complex64, np.complex128])
+@pytest.mark.parametrize("n,nb", [(2, 1), (5, 2), (40, 8), (97, 32), (48, 48)])
+def test_hermitian_similarity_identities(dtype, n, nb):
+    rng = np.random.default_rng(n * 7 + nb)
+    A = herm_lower(rng, n, dtype)
+    S = completed_h(A)
+    r = po.hetrd_panel(A, nb)
+    W = np.asarray(r["W"], dtype=np.complex128).copy()
+    assert np.all(np.isfinite(W)), "the NaN triangle was read"
+    tau = np.asarray(r["tau"], dtype=np.complex128)
+    e = np.asarray(r["e"], dtype=np.float64)
+    V = np.zeros((n, nb), dtype=np.complex128)
+    for j in range(min(nb, n - 1)):
+        V[j + 1:, j] = np.asarray(r["A"][j + 1:, j], dtype=np.complex128)
+        assert V[j + 1, j] == 1.0
+    Q = np.eye(n, dtype=np.complex128)
+    for j in range(nb):
+        W[: j + 1, j] = 0.0
+        H = np.eye(n) - tau[j] * np.outer(V[:, j], np.conj(V[:, j]))
+        assert np.allclose(np.conj(H).T @ H, np.eye(n), atol=1e-13), "H_j is not unitary"
+        Q = Q @ H
+    T = np.conj(Q).T @ S @ Q
+    d = np.asarray(np.diag(r["A"]), dtype=np.complex128)
+    scale = np.linalg.norm(S)
+    for j in range(nb):
+        assert d[j].imag == 0 and abs(T[j, j] - d[j]) < 1e-13 * scale
+        if j < n - 1:
+            assert abs(T[j + 1, j] - e[j]) < 1e-13 * scale, "subdiagonal is not the real e"
+            assert np.all(np.abs(T[j + 2:, j]) < 1e-13 * scale), "column is not reduced"
+    upd = S - V @ np.conj(W).T - W @ np.conj(V).T
+    assert np.allclose(upd[nb:, nb:], T[nb:, nb:], atol=1e-12 * scale)
+    if nb == n:
+        Tm = np.diag(d.real) + np.diag(e[: n - 1], -1) + np.diag(e[: n - 1], 1)
+        assert np.allclose(np.linalg.eigvalsh(Tm), np.linalg.eigvalsh(S), atol=1e-12)
