@@ -216,7 +216,8 @@ int kmv_zhemv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, cons
  * two-sided reductions are where these products are spent; SYMV on the
  * trailing block and GEMV on the reflector panels, all on sub-blocks at
  * arbitrary offsets, Section 6.6).  A second workload built on the entry
- * points above, for s and d, lower storage only (uplo 'L').
+ * points above, for s and d (and c, z: see the Hermitian form below), lower
+ * storage only (uplo 'L').
  * For the first nb columns of the symmetric n x n matrix A (device, lower
  * triangle referenced, never the strict upper one): column i is brought up to
  * date with the reflectors before it, a Householder reflector H_i = I - tau_i
@@ -239,6 +240,14 @@ int kmv_ssytrd_panel(char uplo, int64_t n, int64_t nb, float* A, int64_t lda, fl
                      int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
 int kmv_dsytrd_panel(char uplo, int64_t n, int64_t nb, double* A, int64_t lda, double* e, double* tau, double* W,
                      int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
+/* The same step for a complex Hermitian matrix (HETRD): H_i = I - tau_i v_i v_i^H with a real e_i and a
+ * complex tau_i, A - V W^H - W V^H on the trailing block; the diagonal entries d_i come out real (their
+ * imaginary parts, never used, are set to zero for the panel's columns).  e is a REAL array. */
+int kmv_chetrd_panel(char uplo, int64_t n, int64_t nb, kmv_complex64* A, int64_t lda, float* e, kmv_complex64* tau,
+                     kmv_complex64* W, int64_t ldw, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zhetrd_panel(char uplo, int64_t n, int64_t nb, kmv_complex128* A, int64_t lda, double* e,
+                     kmv_complex128* tau, kmv_complex128* W, int64_t ldw, void* workspace, size_t workspace_bytes,
+                     void* stream);
 size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
 
 /* ---- Panel step of the bidiagonal reduction (Section 10: GEMV on the trailing

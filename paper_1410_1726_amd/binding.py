@@ -57,8 +57,8 @@ def _load() -> ctypes.CDLL:
         f.argtypes, f.restype = gemv_args, ci
         f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_devscalars")
         f.argtypes, f.restype = symv_args, ci
-    for p_ in "sd":
-        f = getattr(lib, f"kmv_{p_}sytrd_panel")
+    for name in ("ssytrd_panel", "dsytrd_panel", "chetrd_panel", "zhetrd_panel"):
+        f = getattr(lib, f"kmv_{name}")
         f.argtypes, f.restype = [ch, i64, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp], ci
     for p_ in "sd":
         f = getattr(lib, f"kmv_{p_}gebrd_panel")
@@ -378,15 +378,18 @@ def sytrd_panel_workspace_bytes(prec, n, nb) -> int:
 
 
 def _sytrd_panel(prec):
+    name = f"{prec}{'hetrd' if prec in 'cz' else 'sytrd'}_panel"
+    eprec = {"s": "s", "d": "d", "c": "s", "z": "d"}[prec]      # e is real
+
     def call(uplo, n, nb, A, lda, e, tau, W, ldw, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: sytrd_panel_workspace_bytes(prec, max(n, 0), max(min(nb, n), 0)), A)
-        rc = getattr(lib, f"kmv_{prec}sytrd_panel")(
-            uplo.encode(), n, nb, _ptr(A, prec), lda, _ptr(e, prec), _ptr(tau, prec), _ptr(W, prec), ldw,
+        rc = getattr(lib, f"kmv_{name}")(
+            uplo.encode(), n, nb, _ptr(A, prec), lda, _ptr(e, eprec), _ptr(tau, prec), _ptr(W, prec), ldw,
             ctypes.c_void_p(wsp), wsb, _stream(stream))
         if check and rc != 0:
-            raise KmvError(f"{prec}sytrd_panel", rc)
+            raise KmvError(name, rc)
         return rc
-    call.__name__ = f"{prec}sytrd_panel"
+    call.__name__ = name
     call.__doc__ = "Panel step of the symmetric tridiagonal reduction on device tensors (see include/kmv.h)."
     return call
 
@@ -411,8 +414,8 @@ def _gebrd_panel(prec):
 
 GEBRD_PANEL = {p_: _gebrd_panel(p_) for p_ in "sd"}
 sgebrd_panel, dgebrd_panel = GEBRD_PANEL["s"], GEBRD_PANEL["d"]
-SYTRD_PANEL = {p_: _sytrd_panel(p_) for p_ in "sd"}
-ssytrd_panel, dsytrd_panel = SYTRD_PANEL["s"], SYTRD_PANEL["d"]
+SYTRD_PANEL = {p_: _sytrd_panel(p_) for p_ in "sdcz"}      # HETRD for the complex precisions
+ssytrd_panel, dsytrd_panel, chetrd_panel, zhetrd_panel = (SYTRD_PANEL[p_] for p_ in "sdcz")
 GEMV_DEVSCALARS = {p_: _gemv_devscalars(p_) for p_ in "sdcz"}
 SYMV_DEVSCALARS = {p_: _symv_devscalars(p_) for p_ in "sdcz"}
 sgemv_devscalars, dgemv_devscalars, cgemv_devscalars, zgemv_devscalars = (GEMV_DEVSCALARS[p_] for p_ in "sdcz")

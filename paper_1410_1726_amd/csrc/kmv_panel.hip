@@ -142,11 +142,128 @@ __global__ __launch_bounds__(PT) void finish_w_kernel(int64_t m, const T* tau, c
     }
 }
 
+// ---- the same two kernels for complex vectors (C = cf32 / cf64, R its real type) ----
+// Reflector for (alpha, x), alpha at *head, x at tail[0..m-2]: beta = -sign(Re alpha) ||(alpha, x)|| is real,
+// tau = (beta - alpha) / beta, x <- x / (alpha - beta), *head = 1; x = 0 with a real alpha gives tau = 0,
+// beta = alpha.  The diagonal element above the head (*diag, the d_i of this column) loses its imaginary
+// part here: it is real for a Hermitian matrix and was only carried along by the column update.
+template <class C, class R>
+__global__ __launch_bounds__(PT) void reflector_kernel_c(int64_t m, C* diag, C* head, C* tail, R* e, C* tau) {
+    __shared__ R red[PT / WAVE];
+    const C alpha = *head;
+    R ss = 0;
+    for (int64_t base = threadIdx.x; base < m - 1; base += (int64_t)PU * PT) {
+        C x[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            x[u] = k < m - 1 ? tail[k] : C{0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < PU; ++u) ss += x[u].re * x[u].re + x[u].im * x[u].im;
+    }
+    const R xnorm = sqrt(block_sum(ss, red));
+    R beta = alpha.re;
+    C t{0, 0};
+    if (xnorm != 0 || alpha.im != 0) {
+        beta = -copysign(sqrt(alpha.re * alpha.re + alpha.im * alpha.im + xnorm * xnorm), alpha.re);
+        t = C{(beta - alpha.re) / beta, -alpha.im / beta};
+        // 1 / (alpha - beta)
+        const R dr = alpha.re - beta, di = alpha.im, den = dr * dr + di * di;
+        const C scale{dr / den, -di / den};
+        for (int64_t base = threadIdx.x; base < m - 1; base += (int64_t)PU * PT) {
+            C x[PU];
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                const int64_t k = base + (int64_t)u * PT;
+                x[u] = k < m - 1 ? tail[k] : C{0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                const int64_t k = base + (int64_t)u * PT;
+                if (k < m - 1) tail[k] = C{x[u].re * scale.re - x[u].im * scale.im, x[u].re * scale.im + x[u].im * scale.re};
+            }
+        }
+    }
+    if (threadIdx.x == 0) {
+        *head = C{1, 0};
+        diag->im = 0;
+        *e = beta;
+        *tau = t;
+    }
+}
+
+// w <- tau w - (tau/2) ((tau w)^H v) v, then the conjugated next rows of W and V packed for the next column.
+// The next diagonal element (*diag_next) loses its imaginary part before that column's update reads it: the
+// caller need not have set it, and a product with it would carry whatever it holds into the real part
+// (null for the last column of the panel: the element after it is not the panel's).
+template <class C, class R>
+__global__ __launch_bounds__(PT) void finish_w_kernel_c(int64_t m, const C* tau, const C* v, C* w, const C* wnext,
+                                                        int64_t ldw, const C* vnext, int64_t ldv, int cnt, C* wrow,
+                                                        C* vrow, C* diag_next) {
+    __shared__ R red[PT / WAVE];
+    const C t = *tau;
+    R pr = 0, pi = 0;       // sum of conj(t w_k) v_k
+    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
+        C wv[PU], vv[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            wv[u] = k < m ? w[k] : C{0, 0};
+            vv[u] = k < m ? v[k] : C{0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const R sr = t.re * wv[u].re - t.im * wv[u].im, si = t.re * wv[u].im + t.im * wv[u].re;   // t w
+            pr += sr * vv[u].re + si * vv[u].im;
+            pi += sr * vv[u].im - si * vv[u].re;
+        }
+    }
+    const R dr = block_sum(pr, red), di = block_sum(pi, red);
+    // c = -(t/2) * dot
+    const C c{R(-0.5) * (t.re * dr - t.im * di), R(-0.5) * (t.re * di + t.im * dr)};
+    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
+        C wv[PU], vv[PU];
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            wv[u] = k < m ? w[k] : C{0, 0};
+            vv[u] = k < m ? v[k] : C{0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+            const int64_t k = base + (int64_t)u * PT;
+            if (k < m)
+                w[k] = C{t.re * wv[u].re - t.im * wv[u].im + c.re * vv[u].re - c.im * vv[u].im,
+                         t.re * wv[u].im + t.im * wv[u].re + c.re * vv[u].im + c.im * vv[u].re};
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < cnt) {
+        const C a = wnext[threadIdx.x * ldw], b = vnext[threadIdx.x * ldv];
+        wrow[threadIdx.x] = C{a.re, -a.im};
+        vrow[threadIdx.x] = C{b.re, -b.im};
+    }
+    if (threadIdx.x == 0 && diag_next) diag_next->im = 0;
+}
+
+// a column without a reflector: e = tau = 0, the diagonal element real
+template <class C, class R> __global__ void no_reflector_kernel_c(C* diag, R* e, C* tau) {
+    diag->im = 0;
+    *e = 0;
+    *tau = C{0, 0};
+}
+
 // e and tau of a column that has no reflector (a fill kernel rather than a memset node, so that a
 // captured panel holds kernels only)
 template <class T> __global__ void no_reflector_kernel(T* e, T* tau) {
     *e = 0;
     *tau = 0;
+}
+
+template <class T> inline T from_real(double v) {
+    if constexpr (Traits<T>::cplx) return T{(typename Traits<T>::real)v, 0};
+    else return (T)v;
 }
 
 template <class T> struct Calls;
@@ -159,6 +276,33 @@ template <> struct Calls<double> {
     static constexpr char prec = 'd';
     static constexpr auto gemv = kmv_dgemv;
     static constexpr auto symv = kmv_dsymv;
+};
+
+template <> struct Calls<cf32> {
+    static constexpr char prec = 'c';
+    static int gemv(char trans, int64_t m, int64_t n, const cf32* alpha, const cf32* A, int64_t lda, const cf32* x,
+                    int64_t incx, const cf32* beta, cf32* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+        return kmv_cgemv(trans, m, n, (const kmv_complex64*)alpha, (const kmv_complex64*)A, lda, (const kmv_complex64*)x, incx,
+                         (const kmv_complex64*)beta, (kmv_complex64*)y, incy, ws, wsb, stream);
+    }
+    static int symv(char uplo, int64_t n, const cf32* alpha, const cf32* A, int64_t lda, const cf32* x, int64_t incx,
+                    const cf32* beta, cf32* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+        return kmv_chemv(uplo, n, (const kmv_complex64*)alpha, (const kmv_complex64*)A, lda, (const kmv_complex64*)x, incx,
+                         (const kmv_complex64*)beta, (kmv_complex64*)y, incy, ws, wsb, stream);
+    }
+};
+template <> struct Calls<cf64> {
+    static constexpr char prec = 'z';
+    static int gemv(char trans, int64_t m, int64_t n, const cf64* alpha, const cf64* A, int64_t lda, const cf64* x,
+                    int64_t incx, const cf64* beta, cf64* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+        return kmv_zgemv(trans, m, n, (const kmv_complex128*)alpha, (const kmv_complex128*)A, lda, (const kmv_complex128*)x,
+                         incx, (const kmv_complex128*)beta, (kmv_complex128*)y, incy, ws, wsb, stream);
+    }
+    static int symv(char uplo, int64_t n, const cf64* alpha, const cf64* A, int64_t lda, const cf64* x, int64_t incx,
+                    const cf64* beta, cf64* y, int64_t incy, void* ws, size_t wsb, void* stream) {
+        return kmv_zhemv(uplo, n, (const kmv_complex128*)alpha, (const kmv_complex128*)A, lda, (const kmv_complex128*)x, incx,
+                         (const kmv_complex128*)beta, (kmv_complex128*)y, incy, ws, wsb, stream);
+    }
 };
 
 inline size_t max_of(size_t a, size_t b) { return a > b ? a : b; }
@@ -184,9 +328,13 @@ template <class T> size_t panel_workspace(int64_t n, int64_t nb) {
     return rows_bytes<T>(nb) + need;
 }
 
+// T real: SYTRD panel; T complex (cf32 / cf64): HETRD panel, e real, transposes conjugated
 template <class T>
-int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* tau, T* W, int64_t ldw, void* ws,
-                size_t wsb, void* stream) {
+int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Traits<T>::real* e, T* tau, T* W,
+                int64_t ldw, void* ws, size_t wsb, void* stream) {
+    using R = typename Traits<T>::real;
+    constexpr bool CPLX = Traits<T>::cplx;
+    constexpr char TC = CPLX ? 'C' : 'T';
     if (uplo != 'L' && uplo != 'l') return -1;      // lower storage only
     if (n < 0) return -2;
     if (nb < 0 || nb > n) return -3;
@@ -202,7 +350,7 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* ta
     ws = static_cast<char*>(ws) + rows_bytes<T>(nb);
     wsb -= rows_bytes<T>(nb);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const T one = 1, zero = 0, minus = -1;
+    const T one = from_real<T>(1), zero = from_real<T>(0), minus = from_real<T>(-1);
     const auto gemv = Calls<T>::gemv;
     const auto symv = Calls<T>::symv;
     int rc = KMV_OK;
@@ -210,14 +358,15 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* ta
         T* col = A + i + i * lda;               // A[i:, i]
         if (i > 0) {
             // column i catches up with the reflectors before it; x is row i of W, then row i of V (= of A),
-            // both packed by the last kernel of column i-1
+            // both packed (and conjugated in the complex case) by the last kernel of column i-1
             rc = gemv('N', n - i, i, &minus, A + i, lda, wrow, 1, &one, col, 1, ws, wsb, stream);
             if (rc) return rc;
             rc = gemv('N', n - i, i, &minus, W + i, ldw, vrow, 1, &one, col, 1, ws, wsb, stream);
             if (rc) return rc;
         }
         if (i >= n - 1) {   // last column of the matrix: no reflector; its slots are defined all the same
-            hipLaunchKernelGGL((no_reflector_kernel<T>), dim3(1), dim3(1), 0, s, e + i, tau + i);
+            if constexpr (CPLX) hipLaunchKernelGGL((no_reflector_kernel_c<T, R>), dim3(1), dim3(1), 0, s, col, e + i, tau + i);
+            else hipLaunchKernelGGL((no_reflector_kernel<T>), dim3(1), dim3(1), 0, s, e + i, tau + i);
             const hipError_t he = hipGetLastError();
             if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
             continue;
@@ -226,23 +375,29 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, T* e, T* ta
         T* v = col + 1;                         // A[i+1:, i]
         T* w = W + (i + 1) + i * ldw;           // W[i+1:, i]
         T* small = W + i * ldw;                 // W[:i, i]: the i-vector of the corrections
-        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, v, v + 1, (int64_t)1, e + i, tau + i);
+        if constexpr (CPLX) hipLaunchKernelGGL((reflector_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, col, v, v + 1, e + i, tau + i);
+        else hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, v, v + 1, (int64_t)1, e + i, tau + i);
         hipError_t he = hipGetLastError();
         if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
         rc = symv('L', m, &one, A + (i + 1) + (i + 1) * lda, lda, v, 1, &zero, w, 1, ws, wsb, stream);
         if (rc) return rc;
         if (i > 0) {
-            rc = gemv('T', m, i, &one, W + i + 1, ldw, v, 1, &zero, small, 1, ws, wsb, stream);
+            rc = gemv(TC, m, i, &one, W + i + 1, ldw, v, 1, &zero, small, 1, ws, wsb, stream);
             if (rc) return rc;
             rc = gemv('N', m, i, &minus, A + i + 1, lda, small, 1, &one, w, 1, ws, wsb, stream);
             if (rc) return rc;
-            rc = gemv('T', m, i, &one, A + i + 1, lda, v, 1, &zero, small, 1, ws, wsb, stream);
+            rc = gemv(TC, m, i, &one, A + i + 1, lda, v, 1, &zero, small, 1, ws, wsb, stream);
             if (rc) return rc;
             rc = gemv('N', m, i, &minus, W + i + 1, ldw, small, 1, &one, w, 1, ws, wsb, stream);
             if (rc) return rc;
         }
-        hipLaunchKernelGGL((finish_w_kernel<T>), dim3(1), dim3(PT), 0, s, m, tau + i, v, w, W + (i + 1), ldw,
-                           A + (i + 1), lda, (int)(i + 1), wrow, vrow);
+        if constexpr (CPLX)
+            hipLaunchKernelGGL((finish_w_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, tau + i, v, w, W + (i + 1), ldw,
+                               A + (i + 1), lda, (int)(i + 1), wrow, vrow,
+                               i + 1 < nb ? A + (i + 1) + (i + 1) * lda : (T*)nullptr);
+        else
+            hipLaunchKernelGGL((finish_w_kernel<T>), dim3(1), dim3(PT), 0, s, m, tau + i, v, w, W + (i + 1), ldw,
+                               A + (i + 1), lda, (int)(i + 1), wrow, vrow);
         he = hipGetLastError();
         if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
     }
@@ -394,9 +549,21 @@ size_t kmv_gebrd_panel_workspace_bytes(char prec, int64_t m, int64_t n, int64_t 
     if (prec == 'd') return kmv::gebrd_workspace<double>(m, n, nb);
     return 0;
 }
+int kmv_chetrd_panel(char uplo, int64_t n, int64_t nb, kmv_complex64* A, int64_t lda, float* e, kmv_complex64* tau,
+                     kmv_complex64* W, int64_t ldw, void* workspace, size_t workspace_bytes, void* stream) {
+    return kmv::sytrd_panel<kmv::cf32>(uplo, n, nb, (kmv::cf32*)A, lda, e, (kmv::cf32*)tau, (kmv::cf32*)W, ldw, workspace,
+                                       workspace_bytes, stream);
+}
+int kmv_zhetrd_panel(char uplo, int64_t n, int64_t nb, kmv_complex128* A, int64_t lda, double* e, kmv_complex128* tau,
+                     kmv_complex128* W, int64_t ldw, void* workspace, size_t workspace_bytes, void* stream) {
+    return kmv::sytrd_panel<kmv::cf64>(uplo, n, nb, (kmv::cf64*)A, lda, e, (kmv::cf64*)tau, (kmv::cf64*)W, ldw, workspace,
+                                       workspace_bytes, stream);
+}
 size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb) {
     if (prec == 's') return kmv::panel_workspace<float>(n, nb);
     if (prec == 'd') return kmv::panel_workspace<double>(n, nb);
+    if (prec == 'c') return kmv::panel_workspace<kmv::cf32>(n, nb);
+    if (prec == 'z') return kmv::panel_workspace<kmv::cf64>(n, nb);
     return 0;
 }
 

@@ -198,7 +198,7 @@ def test_devscalars_argument_errors(prec):
     assert symv() == kmv.ERR_WORKSPACE
 
 
-@pytest.mark.parametrize("prec", "sd")
+@pytest.mark.parametrize("prec", "sdcz")
 def test_sytrd_panel_argument_errors(prec):
     f = kmv.SYTRD_PANEL[prec]
 
@@ -215,7 +215,7 @@ def test_sytrd_panel_argument_errors(prec):
     need = kmv.sytrd_panel_workspace_bytes(prec, 4096, 64)
     assert need >= kmv.symv_workspace_bytes(prec, "L", 4095)
     assert need >= kmv.gemv_workspace_bytes(prec, "N", 4095, 63)
-    assert kmv.sytrd_panel_workspace_bytes("z", 64, 8) == 0 and kmv.sytrd_panel_workspace_bytes(prec, 0, 0) == 0
+    assert kmv.sytrd_panel_workspace_bytes("q", 64, 8) == 0 and kmv.sytrd_panel_workspace_bytes(prec, 0, 0) == 0
 
 
 @pytest.mark.parametrize("prec", "sdcz")

@@ -136,6 +136,68 @@ def test_panel_is_deterministic_and_capturable(prec):
         assert torch.equal(W[defined], ref[1][defined])
 
 
+TOLC = {"c": 1e-5, "z": 1e-12}
+
+
+@pytest.mark.parametrize("prec", "cz")
+@pytest.mark.parametrize("n,nb,pad,off", [(1, 1, 0, 0), (2, 2, 0, 0), (3, 1, 1, 0), (100, 16, 0, 0), (700, 32, 36, 0),
+                                          (1500, 64, 0, 0), (1100, 24, 52, 17)])
+def test_hermitian_panel_against_oracle(prec, n, nb, pad, off):
+    """kmv_{c,z}hetrd_panel: reflectors, the real e, the complex tau, W and the real diagonal element by element;
+    the strict upper triangle and the imaginary parts of the diagonal are NaN on entry"""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    rdt = torch.float32 if prec == "c" else torch.float64
+    lda, ldw = n + off + pad, n + (pad // 2)
+    parent = wl.matrix(prec, n + off, n + off, lda, seed=n + nb, device=DEV)
+    A = parent[off:, off:] if off else parent
+    wl.poison_triangle(A, n, "L", real_diag=False)
+    host0 = parent.clone()                               # the oracle ignores the diagonal's imaginary part
+    dd = torch.arange(n, device=DEV)
+    torch.view_as_real(A)[dd, dd, 1] = float("nan")      # ... which is NaN for the device
+    before = parent.clone()
+    nanv = float("nan")
+    W = torch.full((nb, ldw), nanv, dtype=dt, device=DEV)
+    e = torch.full((nb,), nanv, dtype=rdt, device=DEV)
+    tau = torch.full((nb,), nanv, dtype=dt, device=DEV)
+    k.SYTRD_PANEL[prec]("L", n, nb, A, lda, e, tau, W, ldw)
+    torch.cuda.synchronize()
+    A0 = host_matrix(host0, off, n)
+    want = po.hetrd_panel(A0, nb)
+    A1 = host_matrix(parent, off, n)
+    tol = TOLC[prec]
+    low = np.tril(np.ones((n, n), dtype=bool))[:, :nb]
+    got_cols, want_cols = A1[:, :nb][low], np.asarray(want["A"], dtype=np.complex128)[:, :nb][low]
+    assert np.all(np.isfinite(got_cols.view(np.float32 if prec == "c" else np.float64))), "a NaN was read"
+    assert np.linalg.norm(got_cols - want_cols) <= tol * np.linalg.norm(want_cols)
+    for i in range(nb):
+        assert A1[i, i].imag == 0
+        if i < n - 1:
+            assert A1[i + 1, i] == 1.0
+    assert rel(e.cpu().numpy(), want["e"]) <= tol
+
+    def relc(got, ref):
+        ref = np.asarray(ref, dtype=np.complex128)
+        nrm = np.linalg.norm(ref)
+        return float(np.linalg.norm(np.asarray(got, dtype=np.complex128) - ref) / (nrm if nrm else 1.0))
+
+    assert relc(tau.cpu().numpy(), want["tau"]) <= tol
+    Wh = W.cpu().numpy().T[:n]
+    defined = np.zeros((n, nb), dtype=bool)
+    for i in range(nb):
+        defined[i + 1:, i] = True
+    assert relc(Wh[defined], np.asarray(want["W"])[defined]) <= tol
+    pb, pa = before.cpu().numpy(), parent.cpu().numpy()
+    touched = np.zeros(pb.shape, dtype=bool)
+    for i in range(nb):
+        touched[off + i, off + i:off + n] = True
+    keep = ~touched
+    assert np.array_equal(pb[keep].view(np.uint8), pa[keep].view(np.uint8)), "wrote outside the panel"
+    # the diagonal beyond the panel keeps its real part and its (NaN) imaginary part
+    for i in range(nb, n):
+        assert A1[i, i].real == A0[i, i].real and np.isnan(A1[i, i].imag)
+
+
 # ------------------------------------------------------------ bidiagonal panel ----
 from oracle import gebrd_panel_oracle as go   # noqa: E402
 
