@@ -13,6 +13,14 @@ interleaved rounds are (the defaults in the planners were chosen this way).
 
 A value 0 means "let the library choose".  Prints the median time of every
 combination (microseconds, GB/s of algorithmic bytes) and marks the fastest.
+
+  python -m paper_1410_1726_amd.tune auto dgemv_N 16384 [--save best.json]
+
+runs the paper's two stages for one routine and shape without a hand-written
+grid: a coarse stage over the routine's kernel-shape keys, then a fine stage
+around the best coarse point over its split / workgroup counts, and reports
+the best setting next to the library's own choice (optionally as JSON that
+`apply(json.load(...))` turns back into tuning values).
 """
 from __future__ import annotations
 
@@ -70,10 +78,86 @@ def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int =
     return [(combo, statistics.median(t)) for combo, t in zip(combos, times)]
 
 
+def apply(settings: dict) -> None:
+    """Set the tuning keys of a saved result (all other keys back to automatic)."""
+    for key in k.tuning_keys():
+        k.set_tuning(key, 0)
+    for key, v in settings.items():
+        k.set_tuning(key, int(v))
+
+
+def _coarse_grid(routine: str, m: int, n: int) -> dict:
+    name, mode = routine[1:5], routine[-1]
+    if name == "gemv" and mode == "N":
+        return {"gemv_n_row_tiles": [1, 2, 4], "gemv_n_splits": [0, 8, 32, 128]}
+    if name == "gemv":
+        return {"gemv_t_splits": [0, 1, 2, 4, 8, 16]}
+    variants = [1, 2] + ([3] if n <= 4096 else [])
+    return {"symv_variant": variants, "symv_tiles_per_wave": [1, 2], "symv_unit_tiles": [1, 2]}
+
+
+def _fine_grid(routine: str, best: dict) -> dict:
+    name, mode = routine[1:5], routine[-1]
+    fixed = {key: [v] for key, v in best.items()}
+    if name == "gemv" and mode == "N":
+        s0 = best.get("gemv_n_splits", 0)
+        if s0 <= 0:
+            return {}
+        around = sorted({max(1, min(256, int(round(s0 * f)))) for f in (0.5, 0.75, 0.875, 1.0, 1.125, 1.25, 1.5, 2.0)})
+        fixed["gemv_n_splits"] = around
+        return fixed
+    if name == "gemv":
+        return {}
+    if best.get("symv_variant") == 2:
+        fixed["wg_target"] = [0, 512, 768, 1024]
+        return fixed
+    if best.get("symv_variant") == 1:
+        fixed["symv_classes"] = [0, 32, 64, 128]
+        return fixed
+    return {}
+
+
+def auto(routine: str, m: int, n: int, rounds: int = 3, reps: int = 8):
+    """Coarse stage, then a fine stage around its best point.  Returns (best settings, microseconds,
+    microseconds of the library's own choice)."""
+    default_us = sweep(routine, m, n, {}, rounds, reps)[0][1]
+    coarse = sweep(routine, m, n, _coarse_grid(routine, m, n), rounds, reps)
+    best, best_us = min(coarse, key=lambda r: r[1])
+    stages = [("coarse", coarse)]
+    fine_grid = _fine_grid(routine, best)
+    if fine_grid:
+        fine = sweep(routine, m, n, fine_grid, rounds, reps)
+        stages.append(("fine", fine))
+        fb, fus = min(fine, key=lambda r: r[1])
+        if fus < best_us:
+            best, best_us = fb, fus
+    return best, best_us, default_us, stages
+
+
 def main(argv):
     if len(argv) < 2:
         print(__doc__)
         return 2
+    if argv[0] == "auto":
+        save = None
+        if "--save" in argv:
+            i = argv.index("--save")
+            save = argv[i + 1]
+            del argv[i:i + 2]
+        routine, shape = argv[1], argv[2]
+        m, n = (int(v) for v in shape.split("x")) if "x" in shape else (int(shape), int(shape))
+        best, best_us, default_us, stages = auto(routine, m, n)
+        for label, res in stages:
+            print(f"{label} stage:")
+            for combo, us in res:
+                print("  " + " ".join(f"{key}={v}" for key, v in combo.items()) + f"   {us:.1f} us")
+        gain = 100 * (default_us / best_us - 1)
+        print(f"{routine} {m}x{n}: library's choice {default_us:.1f} us; best found {best_us:.1f} us ({gain:+.1f}%) with {best}")
+        if save:
+            import json
+            with open(save, "w") as f:
+                json.dump({"routine": routine, "m": m, "n": n, "settings": best, "us": best_us, "default_us": default_us}, f)
+        return 0
     routine, shape = argv[0], argv[1]
     m, n = (int(v) for v in shape.split("x")) if "x" in shape else (int(shape), int(shape))
     grid = {}

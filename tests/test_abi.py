@@ -145,6 +145,30 @@ def test_symv_kernel_variant_query():
         kmv.set_tuning("symv_variant", 0)
 
 
+def test_tuning_tool_grids_and_apply():
+    """host-only parts of the tuning tool: the coarse and fine grids name valid keys and values, and a saved
+    setting round-trips through apply()"""
+    from paper_1410_1726_amd import tune
+    keys = set(kmv.tuning_keys())
+    for routine, m, n in (("dgemv_N", 4096, 4096), ("sgemv_T", 512, 9000), ("zhemv_L", 2048, 2048), ("dsymv_U", 20000, 20000)):
+        coarse = tune._coarse_grid(routine, m, n)
+        assert coarse and set(coarse) <= keys
+        first = {key: vals[-1] for key, vals in coarse.items()}
+        fine = tune._fine_grid(routine, first)
+        assert set(fine) <= keys
+        try:
+            for grid in (coarse, fine):
+                for key, vals in grid.items():
+                    for v in vals:
+                        kmv.set_tuning(key, v)          # raises on an illegal value
+            tune.apply(first)
+            assert all(kmv.get_tuning(key) == v for key, v in first.items())
+            assert all(kmv.get_tuning(key) == 0 for key in keys - set(first))
+        finally:
+            for key in keys:
+                kmv.set_tuning(key, 0)
+
+
 def test_tuning_sweep_tool_is_importable():
     from paper_1410_1726_amd import tune
     assert tune.main([]) == 2          # prints its usage, touches no device
