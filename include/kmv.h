@@ -364,7 +364,10 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *   symv_classes                  variant 1: chains per row chunk (1..256)
  *   symv_unit_tiles               variant 2: row tiles per prefetch unit (1, 2)
  *   wg_target                     workgroups the split heuristics aim for; for
- *                                 SYMV variant 2 the number of workgroups */
+ *                                 SYMV variant 2 the number of workgroups
+ *   symv_member_rows              strided batches: largest n that gets one
+ *                                 workgroup per member (up to 1024; 512 for z)
+ *   symv_member_waves             waves of that workgroup (4, 8) */
 int kmv_set_tuning(const char* key, int64_t value);
 int64_t kmv_get_tuning(const char* key);
 const char* kmv_tuning_keys(void);

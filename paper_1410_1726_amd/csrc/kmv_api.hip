@@ -243,9 +243,9 @@ int symv_batched_entry(bool herm, char uplo, int64_t n, const T* alpha, const T*
         a.A = A + b0 * strideA; a.x = x + b0 * stridex; a.y = yb + b0 * stridey;
         SymvPlan<T> plan = plan_symv<T>(lower, n, a.A, lda);
         if (nb > 1 && ((uint64_t)strideA * sizeof(T)) % 128 != 0) plan.shift = 0;
-        // one workgroup per member up to 512 rows, else the one-launch kernel for small matrices with the
-        // member in the grid's second dimension
-        plan.variant = ceil_div(n, (int64_t)tile_rows<T>()) <= member_max_tiles<T>() ? 4 : 3;
+        // one workgroup per member for small members, else the one-launch kernel for small matrices with
+        // the member in the grid's second dimension
+        plan.variant = n <= member_rows<T>() ? 4 : 3;
         a.plan = plan;
         const hipError_t e = launch_symv<T>(a, lower, herm, s, nb);
         if (e != hipSuccess) return hip_code(e);
@@ -275,6 +275,8 @@ const Key KEYS[] = {
     {"symv_variant", &Tuning::symv_variant, 0, 3},
     {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
+    {"symv_member_rows", &Tuning::symv_member_rows, 0, 1024},
+    {"symv_member_waves", &Tuning::symv_member_waves, 0, 8},
 };
 
 }  // namespace
@@ -453,6 +455,7 @@ int kmv_set_tuning(const char* key, int64_t value) {
         if (strcmp(k.name, key) == 0) {
             if (value < k.lo || value > k.hi) return -1;
             if (k.field == &Tuning::gemv_n_row_tiles && value == 3) return -1;
+            if (k.field == &Tuning::symv_member_waves && value != 0 && value != 4 && value != 8) return -1;
             if (k.field == &Tuning::symv_panel_cols && value != 0 && value != 16 && value != 32 && value != 64 &&
                 value != 128)
                 return -1;
@@ -467,7 +470,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target,symv_member_rows,symv_member_waves"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

@@ -23,6 +23,8 @@ struct Tuning {
     int64_t symv_variant = 0;         // SYMV main kernel: 1 = chains, 2 = balanced shares
     int64_t symv_unit_tiles = 0;      // balanced kernel: row tiles per prefetch unit (1 or 2)
     int64_t wg_target = 0;         // workgroups the heuristics aim for
+    int64_t symv_member_rows = 0;     // batches: largest n for the one-workgroup-per-member kernel
+    int64_t symv_member_waves = 0;    // batches: waves of that kernel's workgroup (4 or 8)
 };
 Tuning& tuning();
 
@@ -132,10 +134,16 @@ template <class T> struct SymvArgs {
 // HERM selects the Hermitian rule (conjugated mirror image, real diagonal); it exists for
 // complex T only.  Each (T, HERM) pair is instantiated in exactly one translation unit.
 // Row tiles of the largest matrix the one-workgroup-per-member kernel (plan.variant == 4, batches only)
-// takes: 512 rows in every precision.  Its row sums and x live in registers (MAXT * VEC values per lane),
-// and a member is streamed by a single compute unit: measured on fp64 batches of 1 GiB it beats the
-// small-matrix kernel up to n = 512 (3.6x at n = 64, 2.7x at 256, 1.1x at 512) and loses beyond.
-template <class T> constexpr int member_max_tiles() { return 512 / tile_rows<T>(); }
+// is compiled for: its row sums, x and two columns of matrix data live in registers (4 * MAXT vectors
+// per lane), which allows 8 tiles (1024 rows of 8-byte elements, 512 of 16-byte ones; 1024 rows are
+// 4 tiles of 4-byte elements).
+template <class T> constexpr int member_max_tiles() { return 1024 / tile_rows<T>() < 8 ? 1024 / tile_rows<T>() : 8; }
+// Largest n that kernel is chosen for (a member is streamed by a single compute unit).
+template <class T> inline int64_t member_rows() {
+    const int64_t cap = (int64_t)member_max_tiles<T>() * tile_rows<T>();
+    const int64_t want = tuning().symv_member_rows > 0 ? tuning().symv_member_rows : cap;
+    return want < cap ? want : cap;
+}
 // batch > 1: a strided batch in one launch (requires plan.variant == 3 or 4)
 template <class T, bool HERM> hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int64_t batch);
 template <class T>

@@ -700,9 +700,13 @@ __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
 // column j a lane loads the stored part of its rows, adds a_ij x_j to its row sums (registers, one set per
 // wave) and collects op(a_ij) x_i for the column sum, which one wave reduction per column turns into the
 // "transposed" part of y_j (LDS, each column written by exactly one wave).  At the end the waves add their
-// row sums into one LDS vector in wave order and the epilogue runs.  A lane whose VEC rows are all stored
-// takes them with one 16-byte load; the lane that straddles the diagonal or the last row loads its stored
-// elements one by one, so the other triangle is never loaded here either.
+// row sums into one LDS vector in wave order and the epilogue runs.
+// The loads of a column are issued without any branch, one to three columns ahead of the arithmetic: a tile that
+// holds no stored row of the column loads one vector of the stored part (the same for all lanes), and a
+// lane whose VEC rows straddle the diagonal or the last row loads its vector at the nearest position that
+// lies inside the stored part and moves the elements into place afterwards, so the other triangle is never
+// loaded here either.  That needs VEC stored rows in the column; the VEC - 1 columns at the short end of
+// the triangle (at most 6 elements) are left to the epilogue, which adds them to the outputs they belong to.
 template <class T, bool HERM, bool LOWER, int MAXT, int NW>
 __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
@@ -729,45 +733,81 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
             acc[t][e] = zero_of<T>();
         }
 
-    for (int j = w; j < n; j += NW) {
-        const T* __restrict__ col = A + (int64_t)j * lda;
-        const T xj = x[j];
-        const int tlo = LOWER ? j / TR : 0, thi = LOWER ? ntiles : j / TR + 1;   // tiles that hold stored rows
-        T tsum = zero_of<T>();
+    // columns with at least VEC stored rows: [jlo, jhi)
+    const int jlo = LOWER ? 0 : VEC - 1;
+    const int jhi = LOWER ? n - VEC + 1 : n;
+    if (jhi > jlo) {
+        const int ncols = jhi - jlo;
+        const int cnt = ncols > w ? (ncols - w + NW - 1) / NW : 0;   // columns of this wave
+        // k-th column of this wave; past the end the last column of the range (loaded, not used)
+        auto column = [&](int k) {
+            const int j = jlo + w + k * NW;
+            return j < jhi ? j : jhi - 1;
+        };
+        // position of the lane's vector in tile t of column j: the stored rows are [slo, shi)
+        auto vec_row = [&](int t, int j) {
+            const int slo = LOWER ? j : 0, shi = LOWER ? n : j + 1;
+            const int tlo = slo / TR, thi = (shi - 1) / TR + 1;
+            const int r = (t >= tlo && t < thi) ? t * TR + lane * VEC : slo;
+            const int rc = r < slo ? slo : r;
+            return rc > shi - VEC ? shi - VEC : rc;
+        };
+        auto load_col = [&](Vec<T>(&buf)[MAXT], int j) {
+            const T* __restrict__ col = A + (int64_t)j * lda;
 #pragma unroll
-        for (int t = 0; t < MAXT; ++t) {
-            if (t < tlo || t >= thi) continue;     // wave uniform
-            const int r = t * TR + lane * VEC;
-            const bool full = (LOWER ? r >= j : r + VEC - 1 <= j) && r + VEC <= n;
-            Vec<T> v;
+            for (int t = 0; t < MAXT; ++t) buf[t] = load_stream(col + vec_row(t, j));
+        };
+        auto compute_col = [&](const Vec<T>(&buf)[MAXT], int j) {
+            const T xj = x[j];
+            const int slo = LOWER ? j : 0, shi = LOWER ? n : j + 1;
+            const int tlo = slo / TR, thi = (shi - 1) / TR + 1;
+            T tsum = zero_of<T>();
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) v.e[e] = zero_of<T>();
-            if (full) v = load_stream(col + r);
-            if (!full) {
+            for (int t = 0; t < MAXT; ++t) {
+                if (t < tlo || t >= thi) continue;     // wave uniform
+                const int r = t * TR + lane * VEC;
+                if (t * TR >= slo && (t + 1) * TR <= shi - (LOWER ? 0 : 1) && (!LOWER || t * TR > j)) {
+                    // every row of the tile is stored and none is the diagonal
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    const int row = r + e;
-                    if (row < n && (LOWER ? row >= j : row <= j)) v.e[e] = col[row];
+                    for (int e = 0; e < VEC; ++e) {
+                        fma_acc(acc[t][e], buf[t].e[e], xj);
+                        fma_op<HERM>(tsum, buf[t].e[e], xr[t][e]);
+                    }
+                } else {
+                    const Vec<T> sv = shift_elems(buf[t], r - vec_row(t, j));
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        const int row = r + e;
+                        const bool stored = row >= slo && row < shi;
+                        const bool dia = row == j;
+                        const T av = sv.e[e];
+                        // a_ij x_j for y_i (the diagonal element takes part here, as a real number for HEMV)
+                        T nt = acc[t][e];
+                        fma_acc(nt, select_of(HERM && dia, real_part_only(av), av), xj);
+                        acc[t][e] = select_of(stored, nt, acc[t][e]);
+                        // op(a_ij) x_i for y_j
+                        T tt = tsum;
+                        fma_op<HERM>(tt, av, xr[t][e]);
+                        tsum = select_of(stored && !dia, tt, tsum);
+                    }
                 }
             }
+            const T cs = wave_sum(tsum);
+            if (lane == 0) colsum[j] = cs;
+        };
+        // DEPTH column buffers, DEPTH - 1 columns in flight while one is worked on (more for the
+        // small members, whose columns are short; deeper settings measured the same or 1-4% slower)
+        constexpr int DEPTH = MAXT == 1 ? 4 : (MAXT == 2 ? 3 : 2);
+        Vec<T> b[DEPTH][MAXT];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const int row = r + e;
-                const bool stored = row < n && (LOWER ? row >= j : row <= j);
-                const bool dia = row == j;
-                const T av = v.e[e];
-                // a_ij x_j for y_i (the diagonal element takes part here, as a real number for HEMV)
-                T nt = acc[t][e];
-                fma_acc(nt, select_of(HERM && dia, real_part_only(av), av), xj);
-                acc[t][e] = select_of(stored, nt, acc[t][e]);
-                // op(a_ij) x_i for y_j
-                T tt = tsum;
-                fma_op<HERM>(tt, av, xr[t][e]);
-                tsum = select_of(stored && !dia, tt, tsum);
+        for (int d = 0; d < DEPTH - 1; ++d) load_col(b[d], column(d));
+        for (int k = 0; k < cnt; k += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                load_col(b[(d + DEPTH - 1) % DEPTH], column(k + d + DEPTH - 1));
+                if (k + d < cnt) compute_col(b[d], jlo + w + (k + d) * NW);
             }
         }
-        const T cs = wave_sum(tsum);
-        if (lane == 0) colsum[j] = cs;
     }
 
     // row sums of the waves, added in wave order
@@ -784,9 +824,21 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
         __syncthreads();
     }
     const T alpha = scalar_of(a.alpha, a.alpha_dev), beta = scalar_of(a.beta, a.beta_dev);
+    // the short columns left out above: indices [clo, chi)
+    const int clo = LOWER ? (jhi > 0 ? jhi : 0) : 0, chi = LOWER ? n : (jlo < n ? jlo : n);
     for (int i = threadIdx.x; i < n; i += NW * WAVE) {
+        T sum = rowsum[i];
+        if (i >= jlo && i < jhi) sum = add_of(sum, colsum[i]);
+        if (VEC > 1 && i >= clo && i < chi) {
+            for (int k = clo; k < chi; ++k) {
+                const bool own = LOWER ? i >= k : i <= k;      // a_ik itself is stored (else a_ki)
+                const T av = own ? A[i + (int64_t)k * lda] : A[k + (int64_t)i * lda];
+                if (own) fma_acc(sum, select_of(HERM && i == k, real_part_only(av), av), x[k]);
+                else fma_op<HERM>(sum, av, x[k]);
+            }
+        }
         T* yp = y + (int64_t)i * a.incy;
-        *yp = epilogue(alpha, add_of(rowsum[i], colsum[i]), beta, yp);
+        *yp = epilogue(alpha, sum, beta, yp);
     }
 }
 
@@ -1026,9 +1078,18 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
 
 namespace {
 template <class T, bool HERM, int MAXT>
-void launch_member(const SymvArgs<T>& a, bool lower, dim3 grid, dim3 block, hipStream_t s) {
-    if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, SY_NW>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, SY_NW>), grid, block, 0, s, a);
+void launch_member(const SymvArgs<T>& a, bool lower, unsigned batch, hipStream_t s) {
+    const dim3 grid(batch);
+    // eight waves from 2 KB per column on (measured on 1 GiB batches: 3-10% faster there, up to 45% for the
+    // largest members, 3-10% slower below)
+    const bool eight = tuning().symv_member_waves ? tuning().symv_member_waves == 8 : a.n * (int64_t)sizeof(T) >= 2048;
+    if (eight) {
+        if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, 8>), grid, dim3(8 * WAVE), 0, s, a);
+        else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, 8>), grid, dim3(8 * WAVE), 0, s, a);
+    } else {
+        if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, 4>), grid, dim3(4 * WAVE), 0, s, a);
+        else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, 4>), grid, dim3(4 * WAVE), 0, s, a);
+    }
 }
 }  // namespace
 
@@ -1040,12 +1101,14 @@ hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int
     if (batch < 1 || batch > 65535 || (batch > 1 && a.plan.variant < 3)) return hipErrorInvalidValue;
     if (a.plan.variant == 4) {   // members of a batch: one workgroup per matrix
         const int64_t tiles = ceil_div(a.n, (int64_t)tile_rows<T>());
-        const dim3 grid((unsigned)batch), block(SY_NW * WAVE);
-        if (tiles < 1 || tiles > member_max_tiles<T>()) return hipErrorInvalidValue;
-        if (tiles <= 1) launch_member<T, HERM, 1>(a, lower, grid, block, s);
-        else if (tiles <= 2) launch_member<T, HERM, 2>(a, lower, grid, block, s);
-        else if (tiles <= 4) launch_member<T, HERM, (member_max_tiles<T>() < 4 ? member_max_tiles<T>() : 4)>(a, lower, grid, block, s);
-        else launch_member<T, HERM, member_max_tiles<T>()>(a, lower, grid, block, s);
+        constexpr int M = member_max_tiles<T>();
+        if (tiles < 1 || tiles > M) return hipErrorInvalidValue;
+        if (tiles <= 1) launch_member<T, HERM, 1>(a, lower, (unsigned)batch, s);
+        else if (tiles <= 2) launch_member<T, HERM, 2>(a, lower, (unsigned)batch, s);
+        else if (tiles <= 3) launch_member<T, HERM, (M < 3 ? M : 3)>(a, lower, (unsigned)batch, s);
+        else if (tiles <= 4) launch_member<T, HERM, (M < 4 ? M : 4)>(a, lower, (unsigned)batch, s);
+        else if (tiles <= 6) launch_member<T, HERM, (M < 6 ? M : 6)>(a, lower, (unsigned)batch, s);
+        else launch_member<T, HERM, M>(a, lower, (unsigned)batch, s);
         return hipGetLastError();
     }
     if (a.plan.variant == 3) {   // one launch, no workspace

@@ -112,7 +112,7 @@ def test_tuning_keys_roundtrip():
     assert "symv_panel_cols" in keys
     for k in keys:
         old = kmv.get_tuning(k)
-        val = 64 if k == "symv_panel_cols" else 2
+        val = {"symv_panel_cols": 64, "symv_member_waves": 8}.get(k, 2)
         kmv.set_tuning(k, val)
         assert kmv.get_tuning(k) == val
         kmv.set_tuning(k, old)
@@ -122,6 +122,8 @@ def test_tuning_keys_roundtrip():
         kmv.set_tuning("gemv_n_splits", 100000)
     with pytest.raises(ValueError):
         kmv.set_tuning("symv_panel_cols", 96)
+    with pytest.raises(ValueError):
+        kmv.set_tuning("symv_member_waves", 6)
     assert "kmv" in kmv.version()
 
 
