@@ -58,7 +58,8 @@
  *
  * Families declared below, in this order: GEMV; SYMV / HEMV; complex
  * symmetric SYMV; the "_offset" forms that name the parent matrix; the
- * "_devscalars" forms (alpha, beta in device memory); panel steps of the
+ * "_devscalars" forms (alpha, beta in device memory) - both also for the
+ * complex symmetric product (kmv_csymv_*, kmv_zsymv_*); panel steps of the
  * tridiagonal and the bidiagonal reduction built on these calls; strided
  * batches; workspace sizes; the work partition; the bandwidth probe; tuning.
  *
@@ -177,6 +178,12 @@ int kmv_chemv_offset(char uplo, int64_t n, const kmv_complex64* alpha, const kmv
 int kmv_zhemv_offset(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
                      const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
                      int64_t incy, int64_t offset, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_csymv_offset(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+                     const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y,
+                     int64_t incy, int64_t offset, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zsymv_offset(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+                     const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
+                     int64_t incy, int64_t offset, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- The same products with alpha and beta in DEVICE memory (one element
  * each, read by the kernels when they run, so a scalar that an earlier kernel
@@ -209,6 +216,12 @@ int kmv_chemv_devscalars(char uplo, int64_t n, const kmv_complex64* alpha, const
                          const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y,
                          int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
 int kmv_zhemv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
+                         const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
+                         int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_csymv_devscalars(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda,
+                         const kmv_complex64* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* y,
+                         int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zsymv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda,
                          const kmv_complex128* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* y,
                          int64_t incy, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -287,10 +300,12 @@ size_t kmv_gebrd_panel_workspace_bytes(char prec, int64_t m, int64_t n, int64_t 
  * (host) are common to all members.  The paper has no batched routines; these
  * serve the many-small-matrices case, where a launch per product would cost
  * more than the product: one launch covers the whole batch (65535 members per
- * launch, more are split), each member runs the single-launch form of the
- * kernels (GEMV without column or row splits, the small-matrix SYMV/HEMV
- * kernel), so no workspace is needed and member results do not depend on the
- * batch size.  Restriction: incx must be 1.  Errors: negated argument number
+ * launch, more are split), each member runs a single-launch form of the
+ * kernels (GEMV without column or row splits; SYMV/HEMV with one workgroup
+ * per member up to n = 1024, 512 for z, and the small-matrix kernel beyond),
+ * so no workspace is needed and member results do not depend on the batch
+ * size.  kmv_csymv_ / kmv_zsymv_strided_batched are the complex symmetric
+ * products.  Restriction: incx must be 1.  Errors: negated argument number
  * (GEMV: trans 1, m 2, n 3, lda 6, strideA 7, incx 9, stridex 10, incy 13,
  * stridey 14, batch 15; SYMV/HEMV: uplo 1, n 2, lda 5, strideA 6, incx 8,
  * stridex 9, incy 12, stridey 13, batch 14), KMV_ERR_NULL, KMV_ERR_HIP + code. */
@@ -316,6 +331,12 @@ int kmv_chemv_strided_batched(char uplo, int64_t n, const kmv_complex64* alpha, 
                               const kmv_complex64* x, int64_t incx, int64_t stridex, const kmv_complex64* beta, kmv_complex64* y,
                               int64_t incy, int64_t stridey, int64_t batch, void* stream);
 int kmv_zhemv_strided_batched(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda, int64_t strideA,
+                              const kmv_complex128* x, int64_t incx, int64_t stridex, const kmv_complex128* beta, kmv_complex128* y,
+                              int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_csymv_strided_batched(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* A, int64_t lda, int64_t strideA,
+                              const kmv_complex64* x, int64_t incx, int64_t stridex, const kmv_complex64* beta, kmv_complex64* y,
+                              int64_t incy, int64_t stridey, int64_t batch, void* stream);
+int kmv_zsymv_strided_batched(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda, int64_t strideA,
                               const kmv_complex128* x, int64_t incx, int64_t stridex, const kmv_complex128* beta, kmv_complex128* y,
                               int64_t incy, int64_t stridey, int64_t batch, void* stream);
 

@@ -52,6 +52,11 @@ def _load() -> ctypes.CDLL:
         f.argtypes, f.restype = gemv_off_args, ci
         f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_offset")
         f.argtypes, f.restype = symv_off_args, ci
+    for p_ in "cz":                      # complex symmetric forms
+        getattr(lib, f"kmv_{p_}symv_offset").argtypes = symv_off_args
+        getattr(lib, f"kmv_{p_}symv_devscalars").argtypes = symv_args
+        for suffix in ("offset", "devscalars", "strided_batched"):
+            getattr(lib, f"kmv_{p_}symv_{suffix}").restype = ci
     for p_ in "sdcz":
         f = getattr(lib, f"kmv_{p_}gemv_devscalars")
         f.argtypes, f.restype = gemv_args, ci
@@ -72,6 +77,8 @@ def _load() -> ctypes.CDLL:
         f.argtypes, f.restype = gemv_b_args, ci
         f = getattr(lib, f"kmv_{p_}{'hemv' if p_ in 'cz' else 'symv'}_strided_batched")
         f.argtypes, f.restype = symv_b_args, ci
+    for p_ in "cz":
+        getattr(lib, f"kmv_{p_}symv_strided_batched").argtypes = symv_b_args
     lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
     lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
     lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -286,8 +293,8 @@ def _gemv_offset(prec):
     return call
 
 
-def _symv_offset(prec):
-    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}_offset"
+def _symv_offset(prec, complex_symmetric=False):
+    name = f"{prec}{'hemv' if prec in 'cz' and not complex_symmetric else 'symv'}_offset"
 
     def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, offset, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: symv_workspace_bytes(
@@ -318,8 +325,8 @@ def _gemv_devscalars(prec):
     return call
 
 
-def _symv_devscalars(prec):
-    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}_devscalars"
+def _symv_devscalars(prec, complex_symmetric=False):
+    name = f"{prec}{'hemv' if prec in 'cz' and not complex_symmetric else 'symv'}_devscalars"
 
     def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: symv_workspace_bytes(
@@ -349,8 +356,8 @@ def _gemv_strided_batched(prec):
     return call
 
 
-def _symv_strided_batched(prec):
-    name = f"{prec}{'hemv' if prec in 'cz' else 'symv'}_strided_batched"
+def _symv_strided_batched(prec, complex_symmetric=False):
+    name = f"{prec}{'hemv' if prec in 'cz' and not complex_symmetric else 'symv'}_strided_batched"
 
     def call(uplo, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch, stream=None,
              check=True):
@@ -428,6 +435,12 @@ SYMV_OFFSET = {"s": ssymv_offset, "d": dsymv_offset, "c": chemv_offset, "z": zhe
 GEMV = {"s": sgemv, "d": dgemv, "c": cgemv, "z": zgemv}
 SYMV = {"s": ssymv, "d": dsymv, "c": chemv, "z": zhemv}   # HEMV for the complex precisions
 CSYMV = {"c": csymv, "z": zsymv}                          # complex symmetric
+CSYMV_OFFSET = {p_: _symv_offset(p_, True) for p_ in "cz"}
+CSYMV_DEVSCALARS = {p_: _symv_devscalars(p_, True) for p_ in "cz"}
+CSYMV_STRIDED_BATCHED = {p_: _symv_strided_batched(p_, True) for p_ in "cz"}
+csymv_offset, zsymv_offset = (CSYMV_OFFSET[p_] for p_ in "cz")
+csymv_devscalars, zsymv_devscalars = (CSYMV_DEVSCALARS[p_] for p_ in "cz")
+csymv_strided_batched, zsymv_strided_batched = (CSYMV_STRIDED_BATCHED[p_] for p_ in "cz")
 
 
 def partition(W, Y, y):

@@ -363,6 +363,8 @@ KMV_SYMV_OFFSET(kmv_ssymv_offset, float, float, false)
 KMV_SYMV_OFFSET(kmv_dsymv_offset, double, double, false)
 KMV_SYMV_OFFSET(kmv_chemv_offset, kmv_complex64, cf32, true)
 KMV_SYMV_OFFSET(kmv_zhemv_offset, kmv_complex128, cf64, true)
+KMV_SYMV_OFFSET(kmv_csymv_offset, kmv_complex64, cf32, false)
+KMV_SYMV_OFFSET(kmv_zsymv_offset, kmv_complex128, cf64, false)
 #undef KMV_SYMV_OFFSET
 
 // alpha and beta in device memory
@@ -388,6 +390,8 @@ KMV_SYMV_DEVSCALARS(kmv_ssymv_devscalars, float, float, false)
 KMV_SYMV_DEVSCALARS(kmv_dsymv_devscalars, double, double, false)
 KMV_SYMV_DEVSCALARS(kmv_chemv_devscalars, kmv_complex64, cf32, true)
 KMV_SYMV_DEVSCALARS(kmv_zhemv_devscalars, kmv_complex128, cf64, true)
+KMV_SYMV_DEVSCALARS(kmv_csymv_devscalars, kmv_complex64, cf32, false)
+KMV_SYMV_DEVSCALARS(kmv_zsymv_devscalars, kmv_complex128, cf64, false)
 #undef KMV_SYMV_DEVSCALARS
 
 // strided batches
@@ -415,6 +419,8 @@ KMV_SYMV_BATCHED(kmv_ssymv_strided_batched, float, float, false)
 KMV_SYMV_BATCHED(kmv_dsymv_strided_batched, double, double, false)
 KMV_SYMV_BATCHED(kmv_chemv_strided_batched, kmv_complex64, cf32, true)
 KMV_SYMV_BATCHED(kmv_zhemv_strided_batched, kmv_complex128, cf64, true)
+KMV_SYMV_BATCHED(kmv_csymv_strided_batched, kmv_complex64, cf32, false)
+KMV_SYMV_BATCHED(kmv_zsymv_strided_batched, kmv_complex128, cf64, false)
 #undef KMV_SYMV_BATCHED
 
 size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n) {

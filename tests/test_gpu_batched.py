@@ -74,6 +74,17 @@ def test_gemv_strided_batched(prec, trans):
 @pytest.mark.parametrize("prec", PRECS)
 @pytest.mark.parametrize("uplo", "LU")
 def test_symv_strided_batched(prec, uplo):
+    _symv_batched_case(prec, uplo, False)
+
+
+@pytest.mark.parametrize("prec", "cz")
+@pytest.mark.parametrize("uplo", "LU")
+def test_complex_symmetric_strided_batched(prec, uplo):
+    """csymv / zsymv batches: no conjugation, the diagonal as stored"""
+    _symv_batched_case(prec, uplo, True)
+
+
+def _symv_batched_case(prec, uplo, csym):
     k = kmv()
     alpha, beta = scal(prec, -1.1, 0.4)
     for n, batch, pad, incy in [(1, 1, 0, 1), (2, 3, 0, 1), (3, 2, 1, 1), (4, 2, 0, -1), (5, 2, 2, 1), (8, 4, 0, 1), (9, 3, 1, -1), (63, 5, 16, 2), (64, 2, 0, 1), (65, 3, 2, 1),
@@ -89,13 +100,14 @@ def test_symv_strided_batched(prec, uplo):
         for b in range(batch):
             blk = A[b * strideA: b * strideA + lda * n].view(n, lda)
             wl.poison_triangle(blk, n, uplo, real_diag=False)
-            if prec in "cz":
+            if prec in "cz" and not csym:
                 d = torch.arange(n, device=DEV)
                 torch.view_as_real(blk)[d, d, 1] = NAN      # HEMV ignores the diagonal's imaginary part
         x = rand(prec, (batch - 1) * stridex + n, 22 + n)
         y0 = y_buffer(prec, n, incy, stridey, batch, 23 + n)
         y = y0.clone()
-        k.SYMV_STRIDED_BATCHED[prec](uplo, n, alpha, A, lda, strideA, x, 1, stridex, beta, y, incy, stridey, batch)
+        (k.CSYMV_STRIDED_BATCHED if csym else k.SYMV_STRIDED_BATCHED)[prec](
+            uplo, n, alpha, A, lda, strideA, x, 1, stridex, beta, y, incy, stridey, batch)
         torch.cuda.synchronize()
         xh, yh, y0h = x.cpu().numpy(), y.cpu().numpy(), y0.cpu().numpy()
         is_out = np.zeros(yh.size, dtype=bool)
@@ -103,8 +115,8 @@ def test_symv_strided_batched(prec, uplo):
             sl = slice(b * stridey, b * stridey + exty)
             is_out[b * stridey: b * stridey + exty: abs(incy)] = True
             args = (prec, uplo, n, alpha, host[b * strideA:], xh[b * stridex: b * stridex + n], beta, y0h[sl])
-            want = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_X)
-            den = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_ABS)
+            want = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_X, complex_symmetric=csym)
+            den = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_ABS, complex_symmetric=csym)
             err = errors(prec, logical(yh[sl], n, incy), logical(want, n, incy), logical(den, n, incy), n)
             check(prec, err, f"symv/hemv_strided_batched {prec} {uplo} n={n} member {b}/{batch}")
         assert np.array_equal(yh[~is_out].view(np.uint8), y0h[~is_out].view(np.uint8)), "wrote between outputs"

@@ -384,6 +384,30 @@ def test_offset_calls_name_the_parent(prec):
         check(prec, errors(prec, got_all[off:], want, den, nb), f"symv/hemv_offset {prec} {uplo} offset {off}")
 
 
+@pytest.mark.parametrize("prec", "cz")
+def test_complex_symmetric_offset_and_device_scalars(prec):
+    """csymv / zsymv `_offset` and `_devscalars` forms run the kernels of the plain call (held against the
+    oracle above): same bits as that call on the sub-block pointer, nothing written before the offset."""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    alpha, beta = scalars(prec, 0.7, -0.4)
+    for n, lda, off, uplo in ((1300, 1408, 63, "L"), (1300, 1408, 1, "U"), (5000, 5000, 1000, "L"), (700, 701, 0, "U")):
+        parent = wl.matrix(prec, n, n, lda, seed=52, device=DEV)
+        wl.poison_triangle(parent[off:, off:], n - off, uplo, real_diag=False)
+        x = wl.vector(prec, n, 1, seed=52, which=1, device=DEV)
+        y0 = wl.vector(prec, n, 1, seed=52, which=2, device=DEV)
+        want, got, got_dev = y0.clone(), y0.clone(), y0.clone()
+        k.CSYMV[prec](uplo, n - off, alpha, parent[off:, off:], lda, x[off:], 1, beta, want[off:], 1)
+        k.CSYMV_OFFSET[prec](uplo, n, alpha, parent, lda, x, 1, beta, got, 1, off)
+        al = torch.tensor([alpha], dtype=dt, device=DEV)
+        be = torch.tensor([beta], dtype=dt, device=DEV)
+        k.CSYMV_DEVSCALARS[prec](uplo, n - off, al, parent[off:, off:], lda, x[off:], 1, be, got_dev[off:], 1)
+        torch.cuda.synchronize()
+        assert not torch.isnan(torch.view_as_real(want)).any()
+        assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), (n, off, uplo)
+        assert torch.equal(got_dev.view(torch.uint8), want.view(torch.uint8)), (n, off, uplo)
+
+
 @pytest.mark.parametrize("prec", PRECS)
 def test_scalars_in_device_memory(prec):
     """`_devscalars` entry points: alpha and beta are read from device memory by every kernel that ends a
