@@ -29,15 +29,33 @@ so that afterwards  A - V Y^T - X U^T  on the trailing block equals Q^T A P ther
 rows and columns of Q^T A P are upper bidiagonal with diagonal d and superdiagonal e.  V is stored in
 A on and below the diagonal of the first nb columns (leading ones explicit), U in A right of the diagonal
 of the first nb rows (leading ones explicit, at column i+1).  No rescaling of the norms.
+
+Complex matrices (``gebrd_panel`` accepts complex64 / complex128): the same steps with H_i = I - tauq v v^H
+applied as H_i^H from the left and G_i = I - taup u u^H from the right, so that every transpose above
+becomes a conjugate transpose and the update reads  A - V Y^H - X U^H:
+  y = tauq (A^H v - Y (V^H v) - U (X^H v)),      x = taup (A u - V (Y^H u) - X (U^H u)),
+a reflector for the complex vector (alpha, x) has beta = -sign(Re alpha) ||(alpha, x)|| real (so d and e are
+real), tau = (beta - alpha)/beta complex, and is skipped (tau = 0) only when x = 0 and alpha is real; the
+row reflector is generated from the conjugate of the updated row (that makes r G_i = beta e_1^T), and row i
+of A right of the diagonal stores u^H, the rows of U^H.
 """
 from __future__ import annotations
 
 import numpy as np
 
-_WIDE = {np.dtype(np.float32): np.float64, np.dtype(np.float64): np.longdouble}
+_WIDE = {np.dtype(np.float32): np.float64, np.dtype(np.float64): np.longdouble,
+         np.dtype(np.complex64): np.complex128, np.dtype(np.complex128): np.clongdouble}
 
 
 def _reflector(alpha, x, dt):
+    """(beta, tau, scaled x) with H^H (alpha, x) = (beta, 0), H = I - tau v v^H, v = (1, scaled x)"""
+    if np.iscomplexobj(x) or np.iscomplexobj(alpha):
+        rt = np.real(dt(0)).dtype.type
+        xnorm = np.sqrt(np.sum(x.real * x.real + x.imag * x.imag)) if x.size else rt(0)
+        if xnorm == 0 and alpha.imag == 0:
+            return alpha.real, dt(0), x
+        beta = -np.copysign(np.sqrt(alpha.real * alpha.real + alpha.imag * alpha.imag + xnorm * xnorm), alpha.real)
+        return beta, dt((beta - alpha) / beta), x / (alpha - beta)
     xnorm = np.sqrt(np.sum(x * x)) if x.size else dt(0)
     if xnorm == 0:
         return alpha, dt(0), x
@@ -56,18 +74,20 @@ def gebrd_panel(A, nb, *, wide=True):
     m, n = A.shape
     assert m >= n and 0 <= nb <= n
     dt = _WIDE[A.dtype] if wide else A.dtype.type
+    rt = np.real(dt(0)).dtype.type          # d and e are real
     W = A.astype(dt).copy()
     X = np.zeros((m, nb), dtype=dt)
     Y = np.zeros((n, nb), dtype=dt)
-    d = np.zeros(nb, dtype=dt)
-    e = np.zeros(nb, dtype=dt)
+    d = np.zeros(nb, dtype=rt)
+    e = np.zeros(nb, dtype=rt)
     tauq = np.zeros(nb, dtype=dt)
     taup = np.zeros(nb, dtype=dt)
+    H = lambda M: M.conj().T                # (conjugate) transpose
     for i in range(nb):
         # 1. column i
         a = W[i:, i].copy()
         if i:
-            a = a - W[i:, :i] @ Y[i, :i] - X[i:, :i] @ W[:i, i]
+            a = a - W[i:, :i] @ Y[i, :i].conj() - X[i:, :i] @ W[:i, i]
         # 2. column reflector
         beta, tq, tail = _reflector(a[0], a[1:].copy(), dt)
         d[i], tauq[i] = beta, tq
@@ -76,23 +96,23 @@ def gebrd_panel(A, nb, *, wide=True):
         if i >= n - 1:
             continue
         # 3. y
-        y = W[i:, i + 1:].T @ v
+        y = H(W[i:, i + 1:]) @ v
         if i:
-            y = y - Y[i + 1:, :i] @ (W[i:, :i].T @ v) - W[:i, i + 1:].T @ (X[i:, :i].T @ v)
+            y = y - Y[i + 1:, :i] @ (H(W[i:, :i]) @ v) - H(W[:i, i + 1:]) @ (H(X[i:, :i]) @ v)
         y = tq * y
         Y[i + 1:, i] = y
-        # row i
+        # row i (W[i, :i+1] ends with the explicit one of v)
         r = W[i, i + 1:].copy()
-        r = r - Y[i + 1:, :i + 1] @ W[i, :i + 1]
+        r = r - Y[i + 1:, :i + 1].conj() @ W[i, :i + 1]
         if i:
-            r = r - W[:i, i + 1:].T @ X[i, :i]
-        beta, tp, tail = _reflector(r[0], r[1:].copy(), dt)
+            r = r - X[i, :i] @ W[:i, i + 1:]
+        beta, tp, tail = _reflector(r[0].conj(), r[1:].conj().copy(), dt)
         e[i], taup[i] = beta, tp
         u = np.concatenate(([dt(1)], tail))
-        W[i, i + 1:] = u
+        W[i, i + 1:] = u.conj()
         # x
         x = W[i + 1:, i + 1:] @ u
-        x = x - W[i + 1:, :i + 1] @ (Y[i + 1:, :i + 1].T @ u)
+        x = x - W[i + 1:, :i + 1] @ (H(Y[i + 1:, :i + 1]) @ u)
         if i:
             x = x - X[i + 1:, :i] @ (W[:i, i + 1:] @ u)
         x = tp * x
