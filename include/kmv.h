@@ -265,8 +265,8 @@ size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
 
 /* ---- Panel step of the bidiagonal reduction (Section 10: GEMV on the trailing
  * block and on the accumulated panels, on sub-blocks at arbitrary row and
- * column offsets, with strided vectors).  For s and d, m >= n, upper
- * bidiagonal.  For the first nb columns and rows of the m x n matrix A
+ * column offsets, with strided vectors).  m >= n, upper bidiagonal; the
+ * description is for s and d, the complex forms follow it.  For the first nb columns and rows of the m x n matrix A
  * (device): column i is brought up to date, a reflector H_i = I - tauq_i v_i
  * v_i^T annihilates it below the diagonal, y_i is formed from the trailing
  * block (transposed product); row i is brought up to date, a reflector G_i =
@@ -291,6 +291,18 @@ int kmv_sgebrd_panel(int64_t m, int64_t n, int64_t nb, float* A, int64_t lda, fl
 int kmv_dgebrd_panel(int64_t m, int64_t n, int64_t nb, double* A, int64_t lda, double* d, double* e, double* tauq,
                      double* taup, double* X, int64_t ldx, double* Y, int64_t ldy, void* workspace,
                      size_t workspace_bytes, void* stream);
+/* Complex matrices: H_i = I - tauq_i v_i v_i^H is applied as H_i^H from the
+ * left and G_i = I - taup_i u_i u_i^H from the right, A - V Y^H - X U^H on
+ * the trailing block is Q^H A P there.  A reflector for the vector (alpha, x)
+ * has the real beta = -sign(Re alpha) * ||(alpha, x)||, so d and e are REAL
+ * arrays; tauq and taup are complex; row i of A right of the diagonal holds
+ * u_i^H (the conjugated vector, A[i][i+1] = 1).  Everything else as above. */
+int kmv_cgebrd_panel(int64_t m, int64_t n, int64_t nb, kmv_complex64* A, int64_t lda, float* d, float* e,
+                     kmv_complex64* tauq, kmv_complex64* taup, kmv_complex64* X, int64_t ldx, kmv_complex64* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+int kmv_zgebrd_panel(int64_t m, int64_t n, int64_t nb, kmv_complex128* A, int64_t lda, double* d, double* e,
+                     kmv_complex128* tauq, kmv_complex128* taup, kmv_complex128* X, int64_t ldx, kmv_complex128* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 size_t kmv_gebrd_panel_workspace_bytes(char prec, int64_t m, int64_t n, int64_t nb);
 
 /* ---- Strided batches: `batch` products of one shape in one call; member b

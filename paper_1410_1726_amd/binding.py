@@ -65,7 +65,7 @@ def _load() -> ctypes.CDLL:
     for name in ("ssytrd_panel", "dsytrd_panel", "chetrd_panel", "zhetrd_panel"):
         f = getattr(lib, f"kmv_{name}")
         f.argtypes, f.restype = [ch, i64, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp], ci
-    for p_ in "sd":
+    for p_ in "sdcz":
         f = getattr(lib, f"kmv_{p_}gebrd_panel")
         f.argtypes, f.restype = [i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, i64, vp, i64, vp, sz, vp], ci
     lib.kmv_gebrd_panel_workspace_bytes.argtypes, lib.kmv_gebrd_panel_workspace_bytes.restype = [ch, i64, i64, i64], sz
@@ -406,10 +406,12 @@ def gebrd_panel_workspace_bytes(prec, m, n, nb) -> int:
 
 
 def _gebrd_panel(prec):
+    rprec = {"s": "s", "d": "d", "c": "s", "z": "d"}[prec]      # d and e are real
+
     def call(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: gebrd_panel_workspace_bytes(prec, max(m, 0), max(n, 0), max(nb, 0)), A)
         rc = getattr(lib, f"kmv_{prec}gebrd_panel")(
-            m, n, nb, _ptr(A, prec), lda, _ptr(d, prec), _ptr(e, prec), _ptr(tauq, prec), _ptr(taup, prec),
+            m, n, nb, _ptr(A, prec), lda, _ptr(d, rprec), _ptr(e, rprec), _ptr(tauq, prec), _ptr(taup, prec),
             _ptr(X, prec), ldx, _ptr(Y, prec), ldy, ctypes.c_void_p(wsp), wsb, _stream(stream))
         if check and rc != 0:
             raise KmvError(f"{prec}gebrd_panel", rc)
@@ -419,8 +421,8 @@ def _gebrd_panel(prec):
     return call
 
 
-GEBRD_PANEL = {p_: _gebrd_panel(p_) for p_ in "sd"}
-sgebrd_panel, dgebrd_panel = GEBRD_PANEL["s"], GEBRD_PANEL["d"]
+GEBRD_PANEL = {p_: _gebrd_panel(p_) for p_ in "sdcz"}
+sgebrd_panel, dgebrd_panel, cgebrd_panel, zgebrd_panel = (GEBRD_PANEL[p_] for p_ in "sdcz")
 SYTRD_PANEL = {p_: _sytrd_panel(p_) for p_ in "sdcz"}      # HETRD for the complex precisions
 ssytrd_panel, dsytrd_panel, chetrd_panel, zhetrd_panel = (SYTRD_PANEL[p_] for p_ in "sdcz")
 GEMV_DEVSCALARS = {p_: _gemv_devscalars(p_) for p_ in "sdcz"}

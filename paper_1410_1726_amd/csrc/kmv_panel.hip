@@ -87,16 +87,21 @@ __global__ __launch_bounds__(PT) void reflector_kernel(int64_t m, T* head, T* ta
     }
 }
 
-// dst[k*dinc] = src[k*sinc]: a row of a column-major matrix to a contiguous vector and back
-template <class T> __global__ void strided_copy_kernel(int64_t len, const T* src, int64_t sinc, T* dst, int64_t dinc) {
+// dst[k*dinc] = src[k*sinc] (conjugated with CONJ): a row of a column-major matrix to a contiguous vector and back
+template <class T, bool CONJ = false>
+__global__ void strided_copy_kernel(int64_t len, const T* src, int64_t sinc, T* dst, int64_t dinc) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < len) dst[k * dinc] = src[k * sinc];
+    if (k < len) {
+        T v = src[k * sinc];
+        if constexpr (CONJ && Traits<T>::cplx) v.im = -v.im;
+        dst[k * dinc] = v;
+    }
 }
 
 // v <- (*s) v, the scalar in device memory
 template <class T> __global__ void scale_kernel(int64_t len, const T* s, T* v) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < len) v[k] *= *s;
+    if (k < len) v[k] = mul_of(*s, v[k]);
 }
 
 // w <- tau w - (tau/2) ((tau w).v) v.  Then, for the next column's update, the first `cnt` entries of the
@@ -145,8 +150,8 @@ __global__ __launch_bounds__(PT) void finish_w_kernel(int64_t m, const T* tau, c
 // ---- the same two kernels for complex vectors (C = cf32 / cf64, R its real type) ----
 // Reflector for (alpha, x), alpha at *head, x at tail[0..m-2]: beta = -sign(Re alpha) ||(alpha, x)|| is real,
 // tau = (beta - alpha) / beta, x <- x / (alpha - beta), *head = 1; x = 0 with a real alpha gives tau = 0,
-// beta = alpha.  The diagonal element above the head (*diag, the d_i of this column) loses its imaginary
-// part here: it is real for a Hermitian matrix and was only carried along by the column update.
+// beta = alpha.  The diagonal element above the head (*diag, the d_i of this column; may be null) loses its
+// imaginary part here: it is real for a Hermitian matrix and was only carried along by the column update.
 template <class C, class R>
 __global__ __launch_bounds__(PT) void reflector_kernel_c(int64_t m, C* diag, C* head, C* tail, R* e, C* tau) {
     __shared__ R red[PT / WAVE];
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(PT) void reflector_kernel_c(int64_t m, C* diag, C* 
     }
     if (threadIdx.x == 0) {
         *head = C{1, 0};
-        diag->im = 0;
+        if (diag) diag->im = 0;
         *e = beta;
         *tau = t;
     }
@@ -256,9 +261,9 @@ template <class C, class R> __global__ void no_reflector_kernel_c(C* diag, R* e,
 
 // e and tau of a column that has no reflector (a fill kernel rather than a memset node, so that a
 // captured panel holds kernels only)
-template <class T> __global__ void no_reflector_kernel(T* e, T* tau) {
+template <class R, class T> __global__ void no_reflector_kernel(R* e, T* tau) {
     *e = 0;
-    *tau = 0;
+    *tau = zero_of<T>();
 }
 
 template <class T> inline T from_real(double v) {
@@ -366,7 +371,7 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
         }
         if (i >= n - 1) {   // last column of the matrix: no reflector; its slots are defined all the same
             if constexpr (CPLX) hipLaunchKernelGGL((no_reflector_kernel_c<T, R>), dim3(1), dim3(1), 0, s, col, e + i, tau + i);
-            else hipLaunchKernelGGL((no_reflector_kernel<T>), dim3(1), dim3(1), 0, s, e + i, tau + i);
+            else hipLaunchKernelGGL((no_reflector_kernel<T, T>), dim3(1), dim3(1), 0, s, e + i, tau + i);
             const hipError_t he = hipGetLastError();
             if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
             continue;
@@ -407,6 +412,11 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
 // bytes at the front of the workspace for the contiguous copy of the current row
 template <class T> size_t row_bytes(int64_t n) { return (size_t)((n * sizeof(T) + 255) / 256) * 256; }
 
+// complex panels: three conjugated copies of short strided rows (at most nb elements each)
+template <class T> size_t short_rows_bytes(int64_t nb) {
+    return Traits<T>::cplx ? (size_t)((3 * nb * sizeof(T) + 255) / 256) * 256 : 0;
+}
+
 // the row copy plus the largest workspace any product of the bidiagonal panel asks for
 template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
     if (m <= 0 || n <= 0 || nb <= 0 || m < n) return 0;
@@ -426,7 +436,7 @@ template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
         need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi - 1, i + 1));
         need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', i, ni));
     }
-    return row_bytes<T>(n) + need;
+    return row_bytes<T>(n) + short_rows_bytes<T>(nb) + need;
 }
 
 // Panel step of the bidiagonal reduction (m >= n, upper bidiagonal): the published "labrd" step written
@@ -436,9 +446,17 @@ template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
 // tau; everything on the device and on the caller's stream.  The row that becomes u_i is worked on in a
 // contiguous copy (one strided gather before, one scatter after): a reflector along a row of stride lda took
 // 36 us on average at n = 16384, and the three products that take u_i as x need no packing this way.
+// Complex T: H_i = I - tauq v v^H is applied as H_i^H, G_i = I - taup u u^H from the right, the update is
+// A - V Y^H - X U^H, so every transposed product is a conjugate-transposed one.  Row i of A stores u_i^H;
+// the row is updated and reflected as its conjugate (the contiguous copy holds conj(row), then u_i), and
+// the three short strided rows that enter products conjugated (row i of Y, of V and of X) are copied
+// conjugated into the workspace first; d and e are real.
 template <class T>
-int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, T* d, T* e, T* tauq, T* taup, T* X, int64_t ldx,
-                T* Y, int64_t ldy, void* ws, size_t wsb, void* stream) {
+int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, typename Traits<T>::real* d,
+                typename Traits<T>::real* e, T* tauq, T* taup, T* X, int64_t ldx, T* Y, int64_t ldy, void* ws,
+                size_t wsb, void* stream) {
+    using R = typename Traits<T>::real;
+    constexpr bool CPLX = Traits<T>::cplx;
     if (m < 0) return -1;
     if (n < 0 || n > m) return -2;
     if (nb < 0 || nb > n) return -3;
@@ -451,62 +469,94 @@ int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, T* d, T* e,
     T* urow = static_cast<T*>(ws);            // row i right of the diagonal, contiguous
     ws = static_cast<char*>(ws) + row_bytes<T>(n);
     wsb -= row_bytes<T>(n);
+    T* yrow = static_cast<T*>(ws);            // complex only: conj of row i of Y, of V (= A), of X
+    T* vrow = yrow + nb;
+    T* xrow = vrow + nb;
+    ws = static_cast<char*>(ws) + short_rows_bytes<T>(nb);
+    wsb -= short_rows_bytes<T>(nb);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const T one = 1, zero = 0, minus = -1;
-    const auto gemv = Calls<T>::gemv;
+    const T one = from_real<T>(1), zero = from_real<T>(0), minus = from_real<T>(-1);
+    const char TR = CPLX ? 'C' : 'T';
     auto a_ = [&](int64_t i, int64_t j) { return A + i + j * lda; };
     auto x_ = [&](int64_t i, int64_t j) { return X + i + j * ldx; };
     auto y_ = [&](int64_t i, int64_t j) { return Y + i + j * ldy; };
     int rc = KMV_OK;
-#define KMV_GEMV(...)                                   \
-    do {                                                \
-        rc = gemv(__VA_ARGS__, ws, wsb, stream);        \
-        if (rc) return rc;                              \
+    hipError_t he = hipSuccess;
+#define KMV_GEMV(...)                                          \
+    do {                                                       \
+        rc = Calls<T>::gemv(__VA_ARGS__, ws, wsb, stream);     \
+        if (rc) return rc;                                     \
     } while (0)
+#define KMV_LAUNCHED()                                         \
+    do {                                                       \
+        he = hipGetLastError();                                \
+        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;    \
+    } while (0)
+    // conjugated copy of `len` elements with stride `inc` (complex panels only)
+    auto conj_row = [&](int64_t len, const T* src, int64_t inc, T* dst) {
+        hipLaunchKernelGGL((strided_copy_kernel<T, true>), dim3((unsigned)ceil_div(len, (int64_t)256)), dim3(256), 0, s,
+                           len, src, inc, dst, (int64_t)1);
+    };
+    auto reflector = [&](int64_t len, T* head, R* beta, T* tau) {
+        if constexpr (CPLX)
+            hipLaunchKernelGGL((reflector_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, len, (T*)nullptr, head, head + 1, beta, tau);
+        else
+            hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, len, head, head + 1, (int64_t)1, beta, tau);
+    };
     for (int64_t i = 0; i < nb; ++i) {
         const int64_t mi = m - i, ni = n - i - 1;
         if (i > 0) {   // column i catches up with the panels
-            KMV_GEMV('N', mi, i, &minus, a_(i, 0), lda, y_(i, 0), ldy, &one, a_(i, i), (int64_t)1);
+            if constexpr (CPLX) {
+                conj_row(i, y_(i, 0), ldy, yrow);
+                KMV_LAUNCHED();
+                KMV_GEMV('N', mi, i, &minus, a_(i, 0), lda, yrow, (int64_t)1, &one, a_(i, i), (int64_t)1);
+            } else {
+                KMV_GEMV('N', mi, i, &minus, a_(i, 0), lda, y_(i, 0), ldy, &one, a_(i, i), (int64_t)1);
+            }
             KMV_GEMV('N', mi, i, &minus, x_(i, 0), ldx, a_(0, i), (int64_t)1, &one, a_(i, i), (int64_t)1);
         }
-        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, mi, a_(i, i), a_(i, i) + 1, (int64_t)1,
-                           d + i, tauq + i);
-        hipError_t he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        reflector(mi, a_(i, i), d + i, tauq + i);
+        KMV_LAUNCHED();
         if (ni <= 0) {     // last column of the matrix: no row reflector
-            hipLaunchKernelGGL((no_reflector_kernel<T>), dim3(1), dim3(1), 0, s, e + i, taup + i);
-            he = hipGetLastError();
-            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+            hipLaunchKernelGGL((no_reflector_kernel<R, T>), dim3(1), dim3(1), 0, s, e + i, taup + i);
+            KMV_LAUNCHED();
             continue;
         }
-        // y = tauq * (trailing block^T v - corrections)
-        KMV_GEMV('T', mi, ni, &one, a_(i, i + 1), lda, a_(i, i), (int64_t)1, &zero, y_(i + 1, i), (int64_t)1);
+        // y = tauq * (trailing block^H v - corrections)
+        KMV_GEMV(TR, mi, ni, &one, a_(i, i + 1), lda, a_(i, i), (int64_t)1, &zero, y_(i + 1, i), (int64_t)1);
         if (i > 0) {
-            KMV_GEMV('T', mi, i, &one, a_(i, 0), lda, a_(i, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
+            KMV_GEMV(TR, mi, i, &one, a_(i, 0), lda, a_(i, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
             KMV_GEMV('N', ni, i, &minus, y_(i + 1, 0), ldy, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
-            KMV_GEMV('T', mi, i, &one, x_(i, 0), ldx, a_(i, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
-            KMV_GEMV('T', i, ni, &minus, a_(0, i + 1), lda, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
+            KMV_GEMV(TR, mi, i, &one, x_(i, 0), ldx, a_(i, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
+            KMV_GEMV(TR, i, ni, &minus, a_(0, i + 1), lda, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
         }
         hipLaunchKernelGGL((scale_kernel<T>), dim3((unsigned)ceil_div(ni, (int64_t)256)), dim3(256), 0, s, ni, tauq + i,
                            y_(i + 1, i));
-        he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        KMV_LAUNCHED();
         // row i catches up and gets its reflector, in a contiguous copy that then goes back into the row
         const dim3 cgrid((unsigned)ceil_div(ni, (int64_t)256));
-        hipLaunchKernelGGL((strided_copy_kernel<T>), cgrid, dim3(256), 0, s, ni, a_(i, i + 1), lda, urow, (int64_t)1);
-        he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
-        KMV_GEMV('N', ni, i + 1, &minus, y_(i + 1, 0), ldy, a_(i, 0), lda, &one, urow, (int64_t)1);
-        if (i > 0) KMV_GEMV('T', i, ni, &minus, a_(0, i + 1), lda, x_(i, 0), ldx, &one, urow, (int64_t)1);
-        hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, ni, urow, urow + 1, (int64_t)1, e + i, taup + i);
-        he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
-        hipLaunchKernelGGL((strided_copy_kernel<T>), cgrid, dim3(256), 0, s, ni, urow, (int64_t)1, a_(i, i + 1), lda);
-        he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        hipLaunchKernelGGL((strided_copy_kernel<T, CPLX>), cgrid, dim3(256), 0, s, ni, a_(i, i + 1), lda, urow, (int64_t)1);
+        KMV_LAUNCHED();
+        if constexpr (CPLX) {
+            conj_row(i + 1, a_(i, 0), lda, vrow);
+            KMV_LAUNCHED();
+            KMV_GEMV('N', ni, i + 1, &minus, y_(i + 1, 0), ldy, vrow, (int64_t)1, &one, urow, (int64_t)1);
+            if (i > 0) {
+                conj_row(i, x_(i, 0), ldx, xrow);
+                KMV_LAUNCHED();
+                KMV_GEMV('C', i, ni, &minus, a_(0, i + 1), lda, xrow, (int64_t)1, &one, urow, (int64_t)1);
+            }
+        } else {
+            KMV_GEMV('N', ni, i + 1, &minus, y_(i + 1, 0), ldy, a_(i, 0), lda, &one, urow, (int64_t)1);
+            if (i > 0) KMV_GEMV('T', i, ni, &minus, a_(0, i + 1), lda, x_(i, 0), ldx, &one, urow, (int64_t)1);
+        }
+        reflector(ni, urow, e + i, taup + i);
+        KMV_LAUNCHED();
+        hipLaunchKernelGGL((strided_copy_kernel<T, CPLX>), cgrid, dim3(256), 0, s, ni, urow, (int64_t)1, a_(i, i + 1), lda);
+        KMV_LAUNCHED();
         // x = taup * (trailing block u - corrections)
         KMV_GEMV('N', mi - 1, ni, &one, a_(i + 1, i + 1), lda, urow, (int64_t)1, &zero, x_(i + 1, i), (int64_t)1);
-        KMV_GEMV('T', ni, i + 1, &one, y_(i + 1, 0), ldy, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
+        KMV_GEMV(TR, ni, i + 1, &one, y_(i + 1, 0), ldy, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
         KMV_GEMV('N', mi - 1, i + 1, &minus, a_(i + 1, 0), lda, x_(0, i), (int64_t)1, &one, x_(i + 1, i), (int64_t)1);
         if (i > 0) {
             KMV_GEMV('N', i, ni, &one, a_(0, i + 1), lda, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
@@ -514,10 +564,10 @@ int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, T* d, T* e,
         }
         hipLaunchKernelGGL((scale_kernel<T>), dim3((unsigned)ceil_div(mi - 1, (int64_t)256)), dim3(256), 0, s, mi - 1,
                            taup + i, x_(i + 1, i));
-        he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        KMV_LAUNCHED();
     }
 #undef KMV_GEMV
+#undef KMV_LAUNCHED
     return KMV_OK;
 }
 
@@ -544,9 +594,23 @@ int kmv_dgebrd_panel(int64_t m, int64_t n, int64_t nb, double* A, int64_t lda, d
                      size_t workspace_bytes, void* stream) {
     return kmv::gebrd_panel<double>(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, workspace, workspace_bytes, stream);
 }
+int kmv_cgebrd_panel(int64_t m, int64_t n, int64_t nb, kmv_complex64* A, int64_t lda, float* d, float* e,
+                     kmv_complex64* tauq, kmv_complex64* taup, kmv_complex64* X, int64_t ldx, kmv_complex64* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    return kmv::gebrd_panel<kmv::cf32>(m, n, nb, (kmv::cf32*)A, lda, d, e, (kmv::cf32*)tauq, (kmv::cf32*)taup, (kmv::cf32*)X,
+                                       ldx, (kmv::cf32*)Y, ldy, workspace, workspace_bytes, stream);
+}
+int kmv_zgebrd_panel(int64_t m, int64_t n, int64_t nb, kmv_complex128* A, int64_t lda, double* d, double* e,
+                     kmv_complex128* tauq, kmv_complex128* taup, kmv_complex128* X, int64_t ldx, kmv_complex128* Y,
+                     int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+    return kmv::gebrd_panel<kmv::cf64>(m, n, nb, (kmv::cf64*)A, lda, d, e, (kmv::cf64*)tauq, (kmv::cf64*)taup, (kmv::cf64*)X,
+                                       ldx, (kmv::cf64*)Y, ldy, workspace, workspace_bytes, stream);
+}
 size_t kmv_gebrd_panel_workspace_bytes(char prec, int64_t m, int64_t n, int64_t nb) {
     if (prec == 's') return kmv::gebrd_workspace<float>(m, n, nb);
     if (prec == 'd') return kmv::gebrd_workspace<double>(m, n, nb);
+    if (prec == 'c') return kmv::gebrd_workspace<kmv::cf32>(m, n, nb);
+    if (prec == 'z') return kmv::gebrd_workspace<kmv::cf64>(m, n, nb);
     return 0;
 }
 int kmv_chetrd_panel(char uplo, int64_t n, int64_t nb, kmv_complex64* A, int64_t lda, float* e, kmv_complex64* tau,

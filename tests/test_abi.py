@@ -266,7 +266,7 @@ def test_strided_batched_argument_errors(prec):
     assert symv(A=None) == kmv.ERR_NULL
 
 
-@pytest.mark.parametrize("prec", "sd")
+@pytest.mark.parametrize("prec", "sdcz")
 def test_gebrd_panel_argument_errors(prec):
     f = kmv.GEBRD_PANEL[prec]
 
@@ -282,4 +282,7 @@ def test_gebrd_panel_argument_errors(prec):
     assert call() == kmv.ERR_WORKSPACE
     need = kmv.gebrd_panel_workspace_bytes(prec, 4096, 4096, 64)
     assert need >= kmv.gemv_workspace_bytes(prec, "T", 4096, 4095)
-    assert kmv.gebrd_panel_workspace_bytes("c", 64, 64, 8) == 0 and kmv.gebrd_panel_workspace_bytes(prec, 8, 9, 2) == 0
+    assert kmv.gebrd_panel_workspace_bytes("q", 64, 64, 8) == 0 and kmv.gebrd_panel_workspace_bytes(prec, 8, 9, 2) == 0
+    if prec in "cz":      # room for the row copy and the three conjugated short rows besides the products' workspace
+        esz = {"c": 8, "z": 16}[prec]
+        assert need >= kmv.gemv_workspace_bytes(prec, "C", 4096, 4095) + (4096 + 3 * 64) * esz

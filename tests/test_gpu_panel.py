@@ -248,3 +248,57 @@ def test_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     touched[off:off + n, off:off + nb] = True                      # first nb rows of the block
     assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
     assert np.all(np.isnan(X.cpu().numpy()[:, m:])) and np.all(np.isnan(Y.cpu().numpy()[:, n:]))
+
+
+@pytest.mark.parametrize("prec", "cz")
+@pytest.mark.parametrize("m,n,nb,pad,off", [(1, 1, 1, 0, 0), (2, 2, 2, 0, 0), (5, 3, 3, 1, 0), (100, 100, 16, 0, 0),
+                                            (700, 500, 32, 36, 0), (1500, 1500, 64, 0, 0), (1300, 900, 24, 52, 17),
+                                            (900, 800, 8, 3, 1)])
+def test_complex_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
+    """kmv_{c,z}gebrd_panel: reflector vectors (rows stored as u^H), the real d and e, the complex tauq and
+    taup, X and Y element by element; everything outside the first nb rows and columns bit-unchanged"""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    rdt = torch.float32 if prec == "c" else torch.float64
+    lda, ldx, ldy = m + off + pad, m + pad // 2, n + pad // 3
+    parent = wl.matrix(prec, m + off, n + off, lda, seed=m + n + nb + 1, device=DEV)
+    before = parent.clone()
+    A = parent[off:, off:] if off else parent
+    nanv = float("nan")
+    X = torch.full((nb, ldx), nanv, dtype=dt, device=DEV)
+    Y = torch.full((nb, ldy), nanv, dtype=dt, device=DEV)
+    d, e = (torch.full((nb,), nanv, dtype=rdt, device=DEV) for _ in range(2))
+    tauq, taup = (torch.full((nb,), nanv, dtype=dt, device=DEV) for _ in range(2))
+    k.GEBRD_PANEL[prec](m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy)
+    torch.cuda.synchronize()
+    A0 = before[off:off + n, off:off + m].cpu().numpy().T.copy()
+    A1 = parent[off:off + n, off:off + m].cpu().numpy().T.copy()
+    want = go.gebrd_panel(A0, nb)
+
+    def relc(got, ref):
+        ref = np.asarray(ref, dtype=np.complex128)
+        nrm = np.linalg.norm(ref)
+        return float(np.linalg.norm(np.asarray(got, dtype=np.complex128) - ref) / (nrm if nrm else 1.0))
+
+    tol = TOLC[prec]
+    panel = np.zeros((m, n), dtype=bool)
+    panel[:, :nb] = True
+    panel[:nb, :] = True
+    assert relc(A1[panel], np.asarray(want["A"])[panel]) <= tol
+    for name, got in (("d", d), ("e", e), ("tauq", tauq), ("taup", taup)):
+        assert relc(got.cpu().numpy(), want[name]) <= tol, name
+    Xh, Yh = X.cpu().numpy().T[:m], Y.cpu().numpy().T[:n]
+    dx = np.zeros((m, nb), dtype=bool)
+    dy = np.zeros((n, nb), dtype=bool)
+    for i in range(min(nb, n - 1)):
+        dx[i + 1:, i] = True
+        dy[i + 1:, i] = True
+    assert np.all(np.isfinite(Xh[dx])) and np.all(np.isfinite(Yh[dy]))
+    assert relc(Xh[dx], np.asarray(want["X"])[dx]) <= tol
+    assert relc(Yh[dy], np.asarray(want["Y"])[dy]) <= tol
+    pb, pa = before.cpu().numpy(), parent.cpu().numpy()
+    touched = np.zeros(pb.shape, dtype=bool)
+    touched[off:off + nb, off:off + m] = True
+    touched[off:off + n, off:off + nb] = True
+    assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
+    assert np.all(np.isnan(X.cpu().numpy()[:, m:].real)) and np.all(np.isnan(Y.cpu().numpy()[:, n:].real))
