@@ -897,9 +897,9 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 namespace {
 constexpr int BAL_NC = 4;   // balanced kernel: columns per wave
 constexpr int SMALL_NC = 8;            // small-matrix kernel: outputs per workgroup
-// largest n the small-matrix kernel is chosen for (measured against the two-launch path at n = 1280 .. 3072:
-// it wins up to 2048 in s and d, up to about 1792 in c and z, and loses by 20-50% from 2560 on)
-template <class T> constexpr int64_t small_n() { return Traits<T>::cplx ? 1792 : 2048; }
+// largest n the small-matrix kernel is chosen for (measured against the two-launch path at n = 1024 .. 3072:
+// it wins up to 2048 in d, up to about 1792 in s, c and z, and loses by 20-50% from 2560 on)
+template <class T> constexpr int64_t small_n() { return sizeof(T) == 8 && !Traits<T>::cplx ? 2048 : 1792; }
 // Row tiles per unit (KT) and workgroups per compute unit that go with it, measured
 // with the settings alternating in one process: two tiles (8 loads per lane and
 // buffer) with two workgroups per compute unit for 16-byte elements from n = 16384

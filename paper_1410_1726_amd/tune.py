@@ -21,6 +21,12 @@ grid: a coarse stage over the routine's kernel-shape keys, then a fine stage
 around the best coarse point over its split / workgroup counts, and reports
 the best setting next to the library's own choice (optionally as JSON that
 `apply(json.load(...))` turns back into tuning values).
+
+  python -m paper_1410_1726_amd.tune table [routine,routine,...] [n,n,...]
+
+runs the automatic mode over routines x square sizes and prints one line per case:
+the library's choice, the best setting found and what it would gain (the per-size
+table that says where the planners' defaults leave time on the floor).
 """
 from __future__ import annotations
 
@@ -134,7 +140,32 @@ def auto(routine: str, m: int, n: int, rounds: int = 3, reps: int = 8):
     return best, best_us, default_us, stages
 
 
+TABLE_ROUTINES = ("sgemv_N", "sgemv_T", "dgemv_N", "dgemv_T", "zgemv_N", "zgemv_C", "ssymv_L", "dsymv_L", "dsymv_U",
+                  "chemv_L", "zhemv_L")
+TABLE_SIZES = (2048, 4096, 8192, 12288, 16384, 24576, 32768)
+
+
+def table(routines=TABLE_ROUTINES, sizes=TABLE_SIZES, out=sys.stdout):
+    """One line per (routine, n): library's choice vs the best setting the automatic mode finds."""
+    op_of = {"gemv": lambda r: "gemv_" + ("n" if r[-1] == "N" else "t"), "symv": lambda r: "symv_l", "hemv": lambda r: "hemv_l"}
+    print(f"{'routine':9s} {'n':>6s} {'library us':>11s} {'GB/s':>8s} {'best us':>9s} {'gain':>6s}  best settings", file=out)
+    for routine in routines:
+        for n in sizes:
+            if routine[0] == "z" and n > 24576:      # 32768^2 complex doubles are 17 GB: skipped to keep the run short
+                continue
+            best, best_us, default_us, _ = auto(routine, n, n)
+            nbytes = acc.algorithmic_bytes(op_of[routine[1:5]](routine), routine[0], n, n)
+            text = " ".join(f"{key}={v}" for key, v in best.items()) or "(defaults)"
+            print(f"{routine:9s} {n:6d} {default_us:11.1f} {nbytes / default_us / 1e3:8.1f} {best_us:9.1f} "
+                  f"{100 * (default_us / best_us - 1):+5.1f}%  {text}", file=out, flush=True)
+
+
 def main(argv):
+    if argv and argv[0] == "table":
+        routines = tuple(argv[1].split(",")) if len(argv) > 1 else TABLE_ROUTINES
+        sizes = tuple(int(v) for v in argv[2].split(",")) if len(argv) > 2 else TABLE_SIZES
+        table(routines, sizes)
+        return 0
     if len(argv) < 2:
         print(__doc__)
         return 2

@@ -136,7 +136,7 @@ def test_symv_kernel_variant_query():
         for uplo in "LU":
             assert kmv.symv_kernel_variant(prec, uplo, 5000, DUMMY, 5000) in (1, 2)
             assert kmv.symv_kernel_variant(prec, uplo, 500, DUMMY, 500) == 3
-            edge = 1792 if prec in "cz" else 2048          # largest n of the single-launch kernel
+            edge = 2048 if prec == "d" else 1792             # largest n of the single-launch kernel
             assert kmv.symv_kernel_variant(prec, uplo, edge, DUMMY, edge) == 3
             assert kmv.symv_kernel_variant(prec, uplo, edge + 1, DUMMY, edge + 1) in (1, 2)
     try:
