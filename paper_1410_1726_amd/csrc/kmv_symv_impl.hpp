@@ -1034,7 +1034,10 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
     p.wst_off = p.wsn_off + round_up(wsn_bytes, WS_ALIGN);
-    p.tab_off = p.wst_off + round_up((size_t)p.npanels * p.nchunks * C * sizeof(T), WS_ALIGN);
+    // column sums: one slot per column of every panel and chunk; the bound counts the columns padded to the
+    // widest panel (every panel width divides it)
+    const size_t wst_cols = sizing ? (size_t)ceil_div(n, (int64_t)128) * 128 : (size_t)p.npanels * C;
+    p.tab_off = p.wst_off + round_up(wst_cols * p.nchunks * sizeof(T), WS_ALIGN);
     p.total_bytes = p.tab_off + round_up((size_t)p.nchunks * 2 * sizeof(int), WS_ALIGN);
     return p;
 }

@@ -660,3 +660,62 @@ def test_shrinking_trailing_blocks(prec):
                     check(prec, err, f"symv/hemv {prec} {uplo} trailing block at {o}, variant {variant}")
             finally:
                 kmv().set_tuning("symv_variant", 0)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_workspace_bound_is_enough_and_respected(prec):
+    """A workspace of exactly the queried size serves every pointer alignment, increment and tuning value:
+    the call is accepted, the bytes behind the workspace keep their pattern, and the result has the bits of
+    the call that lets the binding provide the workspace."""
+    k = kmv()
+    alpha, beta = scalars(prec, 0.9, 0.2)
+    guard = 4096
+    tunings = [{}, {"gemv_n_splits": 256, "gemv_t_splits": 256}, {"gemv_n_splits": 1, "gemv_t_splits": 1},
+               {"gemv_n_row_tiles": 4, "wg_target": 1 << 20}, {"gemv_short": 1}, {"gemv_short": 2},
+               {"symv_variant": 1, "symv_classes": 256, "symv_panel_cols": 16},
+               {"symv_variant": 1, "symv_panel_cols": 128, "symv_tiles_per_wave": 2},
+               {"symv_variant": 2, "wg_target": 1 << 20, "symv_unit_tiles": 1},
+               {"symv_variant": 2, "wg_target": 1, "symv_unit_tiles": 2, "symv_tiles_per_wave": 2},
+               {"symv_variant": 3}]
+    try:
+        for tune in tunings:
+            for key, v in tune.items():
+                k.set_tuning(key, v)
+            for m, n, off, incx in ((2500, 1900, 0, 1), (1900, 2500, 1, -2), (100, 7000, 3, 3), (6000, 130, 2, 1)):
+                lda = m + off + 5
+                parent = wl.matrix(prec, m + off, n, lda, seed=61, device=DEV)
+                A = parent[:, off:]
+                for trans in "NT":
+                    lenx, leny = (n, m) if trans == "N" else (m, n)
+                    x = wl.vector(prec, lenx, incx, seed=61, which=1, device=DEV)
+                    y0 = wl.vector(prec, leny, 1, seed=61, which=2, device=DEV)
+                    nbytes = k.gemv_workspace_bytes(prec, trans, m, n)
+                    ws = torch.full((nbytes + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+                    want, got = y0.clone(), y0.clone()
+                    k.GEMV[prec](trans, m, n, alpha, A, lda, x, incx, beta, want, 1)
+                    rc = k.GEMV[prec](trans, m, n, alpha, A, lda, x, incx, beta, got, 1, workspace=ws[:nbytes], check=False)
+                    assert rc == 0, (tune, trans, m, n, rc)
+                    torch.cuda.synchronize()
+                    assert bool((ws[nbytes:] == 0xA5).all()), ("wrote behind the workspace", tune, trans, m, n)
+                    assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+            for n, off, incx in ((2300, 0, 1), (3001, 1, 2), (700, 3, -1), (5200, 2, 1)):
+                lda = n + off + 3
+                parent = wl.matrix(prec, n + off, n, lda, seed=62, device=DEV)
+                A = parent[:, off:]
+                for uplo in "LU":
+                    x = wl.vector(prec, n, incx, seed=62, which=1, device=DEV)
+                    y0 = wl.vector(prec, n, 1, seed=62, which=2, device=DEV)
+                    nbytes = k.symv_workspace_bytes(prec, uplo, n)
+                    ws = torch.full((nbytes + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+                    want, got = y0.clone(), y0.clone()
+                    k.SYMV[prec](uplo, n, alpha, A, lda, x, incx, beta, want, 1)
+                    rc = k.SYMV[prec](uplo, n, alpha, A, lda, x, incx, beta, got, 1, workspace=ws[:nbytes], check=False)
+                    assert rc == 0, (tune, uplo, n, rc)
+                    torch.cuda.synchronize()
+                    assert bool((ws[nbytes:] == 0xA5).all()), ("wrote behind the workspace", tune, uplo, n)
+                    assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+            for key in tune:
+                k.set_tuning(key, 0)
+    finally:
+        for key in k.tuning_keys():
+            k.set_tuning(key, 0)
