@@ -148,3 +148,71 @@ def hetrd_panel(A, nb, *, wide=True):
         w = w - (t / 2) * (np.conj(w) @ v) * v
         W[i + 1:, i] = w
     return dict(A=out, e=e, tau=tau, W=W)
+
+
+def trd_panel_upper(A, nb, *, wide=True):
+    """The panel step for UPPER storage, real symmetric or complex Hermitian (decided by the dtype): the
+    mirror image of the steps above.  The LAST nb columns are reduced, from column n-1 down to n-nb; with
+    iw = i - (n - nb) the slot of column i in e, tau and W, and J the slots of the columns already done:
+
+      1. a = A[:i+1, i] - V[:i+1, J] conj(W[i, J]) - W[:i+1, J] conj(V[i, J])     (a[i] = d_i is final, real)
+      2. reflector for a[:i]: alpha = a[i-1] (its LAST element), x = a[:i-1]; beta, tau and the scaled x as
+         above; e[iw] = beta; v = [x, 1] is stored in A[:i, i] (the one explicitly, at row i-1)
+      3. w = A[:i, :i] v - V[:i, J] (W[:i, J]^H v) - W[:i, J] (V[:i, J]^H v);  w <- tau w;
+         w <- w - (tau/2) (w^H v) v;   W[:i, iw] = w  (rows i+1.. of that column hold the last small product)
+
+    so that  A - V W^H - W V^H  on the leading (n-nb) x (n-nb) block is Q^H A Q there and the last nb columns
+    are tridiagonal with diagonal d and superdiagonal e.  Column 0 has no reflector (e = tau = 0; only when
+    nb = n).  Only the upper triangle of ``A`` is read (and not the imaginary part of a complex diagonal).
+    Returns ``dict(A=..., e=..., tau=..., W=...)`` with ``e`` real, all of length / width ``nb``.
+    """
+    A = np.asarray(A)
+    n = A.shape[0]
+    assert A.shape == (n, n) and 0 <= nb <= n
+    cplx = np.iscomplexobj(A)
+    dt = _WIDE[A.dtype] if wide else A.dtype.type
+    rt = np.real(dt(0)).dtype.type
+    U = np.triu(A).astype(dt)
+    if cplx:
+        U[np.arange(n), np.arange(n)] = U[np.arange(n), np.arange(n)].real
+    S = U + np.conj(np.triu(U, 1)).T
+    out = U.copy()
+    V = np.zeros((n, nb), dtype=dt)
+    W = np.zeros((n, nb), dtype=dt)
+    e = np.zeros(nb, dtype=rt)
+    tau = np.zeros(nb, dtype=dt)
+    for i in range(n - 1, n - nb - 1, -1):
+        iw = i - (n - nb)
+        J = slice(iw + 1, nb)
+        a = S[:i + 1, i].copy()
+        if i < n - 1:
+            a = a - V[:i + 1, J] @ np.conj(W[i, J]) - W[:i + 1, J] @ np.conj(V[i, J])
+        if cplx:
+            a[i] = a[i].real
+        out[:i + 1, i] = a
+        if i == 0:
+            continue
+        alpha = a[i - 1]
+        x = a[:i - 1].copy()
+        xnorm = np.sqrt(np.sum((x * np.conj(x)).real)) if x.size else rt(0)
+        if xnorm == 0 and (not cplx or alpha.imag == 0):
+            beta, t = (alpha.real if cplx else alpha), dt(0)
+        else:
+            are = alpha.real if cplx else alpha
+            beta = -np.copysign(np.sqrt((alpha * np.conj(alpha)).real + xnorm * xnorm), are)
+            t = dt((beta - alpha) / beta)
+            x = x / (alpha - beta)
+        e[iw], tau[iw] = beta, t
+        v = np.concatenate((x, [dt(1)]))
+        V[:i, iw] = v
+        out[:i, i] = v
+        w = S[:i, :i] @ v
+        if i < n - 1:
+            W[i + 1:, iw] = np.conj(W[:i, J]).T @ v
+            w = w - V[:i, J] @ W[i + 1:, iw]
+            W[i + 1:, iw] = np.conj(V[:i, J]).T @ v
+            w = w - W[:i, J] @ W[i + 1:, iw]
+        w = t * w
+        w = w - (t / 2) * (np.conj(w) @ v) * v
+        W[:i, iw] = w
+    return dict(A=out, e=e, tau=tau, W=W)

@@ -1,6 +1,7 @@
 """Pins of the panel-step oracle (`oracle/panel_oracle.py`) against things it does not compute itself:
 a hand-worked 3 x 3 case, and numpy linear algebra on the explicitly formed reflectors (orthogonality,
-tridiagonal leading columns, the trailing-block identity, eigenvalues of a full reduction)."""
+tridiagonal leading columns, the trailing-block identity, eigenvalues of a full reduction); the upper-storage
+panel additionally against the lower-storage one on the matrix with rows and columns reversed."""
 import numpy as np
 import pytest
 
@@ -179,3 +180,96 @@ def test_hermitian_similarity_identities(dtype, n, nb):
     if nb == n:
         Tm = np.diag(d.real) + np.diag(e[: n - 1], -1) + np.diag(e[: n - 1], 1)
         assert np.allclose(np.linalg.eigvalsh(Tm), np.linalg.eigvalsh(S), atol=1e-12)
+
+
+# ---------------------------------------------------------------- upper storage ----
+def upper_input(rng, n, dtype):
+    if np.issubdtype(dtype, np.complexfloating):
+        A = (rng.uniform(-1, 1, (n, n)) + 1j * rng.uniform(-1, 1, (n, n))).astype(dtype)
+    else:
+        A = rng.uniform(-1, 1, (n, n)).astype(dtype)
+    A[np.tril_indices(n, -1)] = np.nan       # the strict lower triangle is never read
+    return A
+
+
+def completed_upper(A):
+    U = np.triu(A).astype(np.complex128 if np.iscomplexobj(A) else np.float64)
+    if np.iscomplexobj(A):
+        U[np.arange(len(U)), np.arange(len(U))] = U.diagonal().real
+    return U + np.conj(np.triu(U, 1)).T
+
+
+def test_upper_hand_worked_three_by_three():
+    # last column a = (4, 3, 4) from the top: d = 4 (bottom), alpha = a[1] = 3, x = (a[0]) = (4), beta = -5,
+    # tau = 8/5, v = (1/2, 1): the mirror image of the lower 3 x 3 case, so w = (2.88, -1.44) from the top
+    A = np.array([[5.0, 1.0, 4.0], [np.nan, 2.0, 3.0], [np.nan, np.nan, 4.0]])
+    r = po.trd_panel_upper(A, 1)
+    assert float(r["e"][0]) == -5.0 and abs(float(r["tau"][0]) - 1.6) < 1e-18
+    assert float(r["A"][2, 2]) == 4.0 and float(r["A"][1, 2]) == 1.0 and float(r["A"][0, 2]) == 0.5
+    assert np.allclose(np.asarray(r["W"][:, 0], dtype=np.float64), [2.88, -1.44, 0.0], rtol=0, atol=1e-15)
+    assert float(r["A"][0, 0]) == 5.0 and float(r["A"][0, 1]) == 1.0 and float(r["A"][1, 1]) == 2.0
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64, np.complex64, np.complex128])
+@pytest.mark.parametrize("n,nb", [(1, 1), (2, 1), (2, 2), (5, 2), (40, 8), (97, 32), (48, 48)])
+def test_upper_panel_is_the_mirror_image_of_the_lower_one(dtype, n, nb):
+    """Reversing the order of rows and columns turns the upper triangle into the lower one and the last nb
+    columns into the first nb: the lower-storage oracle on the reversed matrix must give the reversed results."""
+    rng = np.random.default_rng(n * 100 + nb + 3)
+    A = upper_input(rng, n, dtype)
+    cplx = np.iscomplexobj(A)
+    up = po.trd_panel_upper(A, nb)
+    lo = (po.hetrd_panel if cplx else po.sytrd_panel)(A[::-1, ::-1].copy(), nb)
+    wt = np.complex128 if cplx else np.float64
+    assert np.allclose(np.asarray(up["e"], dtype=np.float64), np.asarray(lo["e"], dtype=np.float64)[::-1], atol=1e-13)
+    assert np.allclose(np.asarray(up["tau"], dtype=wt), np.asarray(lo["tau"], dtype=wt)[::-1], atol=1e-13)
+    Au, Al = np.asarray(up["A"], dtype=wt), np.asarray(lo["A"], dtype=wt)[::-1, ::-1]
+    iu = np.triu_indices(n)
+    assert np.allclose(Au[iu], Al[iu], atol=1e-13)
+    Wu, Wl = np.asarray(up["W"], dtype=wt), np.asarray(lo["W"], dtype=wt)[::-1, ::-1]
+    for iw in range(nb):
+        i = n - nb + iw
+        assert np.allclose(Wu[:i, iw], Wl[:i, iw], atol=1e-13)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.complex128])
+@pytest.mark.parametrize("n,nb", [(5, 2), (40, 8), (33, 33)])
+def test_upper_similarity_identities(dtype, n, nb):
+    rng = np.random.default_rng(n * 100 + nb + 4)
+    A = upper_input(rng, n, dtype)
+    S = completed_upper(A)
+    r = po.trd_panel_upper(A, nb)
+    wt = S.dtype
+    W = np.asarray(r["W"], dtype=wt).copy()
+    assert np.all(np.isfinite(W)), "the NaN triangle was read"
+    tau = np.asarray(r["tau"], dtype=wt)
+    e = np.asarray(r["e"], dtype=np.float64)
+    out = np.asarray(r["A"], dtype=wt)
+    V = np.zeros((n, nb), dtype=wt)
+    Q = np.eye(n, dtype=wt)
+    for iw in range(nb - 1, -1, -1):
+        i = n - nb + iw
+        W[i:, iw] = 0                          # rows i.. of that column are scratch
+        if i > 0:
+            V[:i, iw] = out[:i, i]
+            assert V[i - 1, iw] == 1.0
+        Hi = np.eye(n, dtype=wt) - tau[iw] * np.outer(V[:, iw], np.conj(V[:, iw]))
+        assert np.allclose(np.conj(Hi).T @ Hi, np.eye(n), atol=1e-13), "H_i is not unitary"
+        Q = Q @ Hi
+    T = np.conj(Q).T @ S @ Q
+    scale = np.linalg.norm(S)
+    for iw in range(nb):
+        i = n - nb + iw
+        assert abs(T[i, i] - out[i, i]) < 1e-13 * scale and out[i, i].imag == 0
+        if i > 0:
+            assert abs(T[i - 1, i] - e[iw]) < 1e-13 * scale, "superdiagonal is not the real e"
+            assert np.all(np.abs(T[:i - 1, i]) < 1e-13 * scale), "column is not reduced"
+    upd = S - V @ np.conj(W).T - W @ np.conj(V).T
+    m = n - nb
+    assert np.allclose(upd[:m, :m], T[:m, :m], atol=1e-12 * scale)
+    # columns before the panel keep their input values (of a complex diagonal the real part: the rest is not read)
+    iu = np.triu_indices(n)
+    keep = iu[1] < m
+    ref = np.triu(A).astype(wt)
+    ref[np.arange(n), np.arange(n)] = ref.diagonal().real
+    assert np.array_equal(out[iu][keep], ref[iu][keep])
