@@ -229,8 +229,8 @@ int kmv_zsymv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, cons
  * two-sided reductions are where these products are spent; SYMV on the
  * trailing block and GEMV on the reflector panels, all on sub-blocks at
  * arbitrary offsets, Section 6.6).  A second workload built on the entry
- * points above, for s and d (and c, z: see the Hermitian form below), lower
- * storage only (uplo 'L').
+ * points above, for s and d (and c, z: see the Hermitian form below).  The
+ * description is for lower storage (uplo 'L'); 'U' follows it.
  * For the first nb columns of the symmetric n x n matrix A (device, lower
  * triangle referenced, never the strict upper one): column i is brought up to
  * date with the reflectors before it, a Householder reflector H_i = I - tau_i
@@ -243,6 +243,14 @@ int kmv_zsymv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, cons
  * below the subdiagonal gets tau = 0 (e = the subdiagonal entry as it stands;
  * both 0 for the last column of the matrix).  Norms are formed without
  * rescaling against underflow or overflow.
+ * uplo 'U' (upper triangle referenced, never the strict lower one) is the
+ * mirror image: the LAST nb columns are reduced, from column n-1 down to n-nb;
+ * column i = n-nb+k uses slot k of e, tau and W; its reflector annihilates
+ * A[0..i-2][i], so on exit A[i][i] = d_i, A[i-1][i] = 1, A[0..i-2][i] = the
+ * rest of v_i, e[k] the superdiagonal entry, W[0..i-1][k] = w_i (rows i.. of
+ * that column are scratch); columns 0..n-nb-1 of A are not modified and
+ * A - V W^T - W V^T on the LEADING (n-nb) x (n-nb) block is the transformed
+ * block; column 0 of the matrix has no reflector (e = tau = 0).
  * Only enqueues kernels on `stream` (about nine per column; tau and the inner
  * products stay on the device), so a panel can be captured in a graph.
  * Workspace: kmv_sytrd_panel_workspace_bytes(prec, n, nb), 256-byte aligned.

@@ -340,7 +340,8 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
     using R = typename Traits<T>::real;
     constexpr bool CPLX = Traits<T>::cplx;
     constexpr char TC = CPLX ? 'C' : 'T';
-    if (uplo != 'L' && uplo != 'l') return -1;      // lower storage only
+    const bool lower = (uplo == 'L' || uplo == 'l');
+    if (!lower && uplo != 'U' && uplo != 'u') return -1;
     if (n < 0) return -2;
     if (nb < 0 || nb > n) return -3;
     if (lda < (n > 1 ? n : 1)) return -5;
@@ -359,6 +360,60 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
     const auto gemv = Calls<T>::gemv;
     const auto symv = Calls<T>::symv;
     int rc = KMV_OK;
+    if (!lower) {
+        // Upper storage: the mirror image.  The LAST nb columns are reduced, from column n-1 down to n-nb; column
+        // i has slot iw = i - (n - nb) in e, tau and W; its reflector annihilates A[0:i-1, i], v = A[0:i, i] with
+        // the one at row i-1; the k = n-1-i columns to its right are the reflectors and W columns done before.
+        const int64_t first = n - nb;
+        for (int64_t i = n - 1; i >= first; --i) {
+            const int64_t iw = i - first, k = n - 1 - i;
+            T* col = A + i * lda;                    // A[0:i+1, i]
+            if (k > 0) {
+                rc = gemv('N', i + 1, k, &minus, A + (i + 1) * lda, lda, wrow, 1, &one, col, 1, ws, wsb, stream);
+                if (rc) return rc;
+                rc = gemv('N', i + 1, k, &minus, W + (iw + 1) * ldw, ldw, vrow, 1, &one, col, 1, ws, wsb, stream);
+                if (rc) return rc;
+            }
+            if (i == 0) {   // first column of the matrix: no reflector
+                if constexpr (CPLX) hipLaunchKernelGGL((no_reflector_kernel_c<T, R>), dim3(1), dim3(1), 0, s, col, e + iw, tau + iw);
+                else hipLaunchKernelGGL((no_reflector_kernel<T, T>), dim3(1), dim3(1), 0, s, e + iw, tau + iw);
+                const hipError_t he = hipGetLastError();
+                if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+                continue;
+            }
+            const int64_t m = i;                     // length of v
+            T* head = col + (i - 1);                 // A[i-1, i]
+            T* w = W + iw * ldw;                     // W[0:i, iw]
+            T* small = W + (i + 1) + iw * ldw;       // W[i+1:, iw]: the k-vector of the corrections
+            if constexpr (CPLX) hipLaunchKernelGGL((reflector_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, col + i, head, col, e + iw, tau + iw);
+            else hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, head, col, (int64_t)1, e + iw, tau + iw);
+            hipError_t he = hipGetLastError();
+            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+            rc = symv('U', m, &one, A, lda, col, 1, &zero, w, 1, ws, wsb, stream);
+            if (rc) return rc;
+            if (k > 0) {
+                rc = gemv(TC, m, k, &one, W + (iw + 1) * ldw, ldw, col, 1, &zero, small, 1, ws, wsb, stream);
+                if (rc) return rc;
+                rc = gemv('N', m, k, &minus, A + (i + 1) * lda, lda, small, 1, &one, w, 1, ws, wsb, stream);
+                if (rc) return rc;
+                rc = gemv(TC, m, k, &one, A + (i + 1) * lda, lda, col, 1, &zero, small, 1, ws, wsb, stream);
+                if (rc) return rc;
+                rc = gemv('N', m, k, &minus, W + (iw + 1) * ldw, ldw, small, 1, &one, w, 1, ws, wsb, stream);
+                if (rc) return rc;
+            }
+            // w finished; row i-1 of W (slots iw..) and of V (columns i..) packed for column i-1
+            if constexpr (CPLX)
+                hipLaunchKernelGGL((finish_w_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, tau + iw, col, w, W + (i - 1) + iw * ldw,
+                                   ldw, A + (i - 1) + i * lda, lda, (int)(k + 1), wrow, vrow,
+                                   i - 1 >= first ? A + (i - 1) + (i - 1) * lda : (T*)nullptr);
+            else
+                hipLaunchKernelGGL((finish_w_kernel<T>), dim3(1), dim3(PT), 0, s, m, tau + iw, col, w, W + (i - 1) + iw * ldw, ldw,
+                                   A + (i - 1) + i * lda, lda, (int)(k + 1), wrow, vrow);
+            he = hipGetLastError();
+            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        }
+        return KMV_OK;
+    }
     for (int64_t i = 0; i < nb; ++i) {
         T* col = A + i + i * lda;               // A[i:, i]
         if (i > 0) {

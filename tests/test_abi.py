@@ -231,7 +231,7 @@ def test_sytrd_panel_argument_errors(prec):
     def call(uplo="L", n=8, nb=4, lda=8, ldw=8, A=DUMMY, W=DUMMY):
         return f(uplo, n, nb, A, lda, DUMMY, DUMMY, W, ldw, workspace=NOWS, stream=0, check=False)
 
-    assert call(uplo="U") == -1                 # lower storage only
+    assert call(uplo="X") == -1 and call(uplo="U") == kmv.ERR_WORKSPACE
     assert call(n=-1) == -2
     assert call(nb=-1) == -3 and call(nb=9) == -3
     assert call(lda=7) == -5 and call(ldw=7) == -9

@@ -302,3 +302,81 @@ def test_complex_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     touched[off:off + n, off:off + nb] = True
     assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
     assert np.all(np.isnan(X.cpu().numpy()[:, m:].real)) and np.all(np.isnan(Y.cpu().numpy()[:, n:].real))
+
+
+# ------------------------------------------------------------ upper storage ----
+@pytest.mark.parametrize("prec", "sdcz")
+@pytest.mark.parametrize("n,nb,pad,off", [(1, 1, 0, 0), (2, 2, 0, 0), (3, 1, 1, 0), (100, 16, 0, 0), (700, 32, 36, 0),
+                                          (1500, 64, 0, 0), (1100, 24, 52, 17), (60, 60, 4, 1)])
+def test_upper_storage_panel_against_oracle(prec, n, nb, pad, off):
+    """uplo = 'U': the last nb columns are reduced (SYMV / HEMV 'U' on the leading block, GEMV on the columns to
+    the right).  Reflectors, e, tau, W and the diagonal element by element; the strict lower triangle (and the
+    imaginary parts of a complex diagonal) are NaN on entry; everything outside the panel's columns bit-unchanged."""
+    k = kmv()
+    cplx = prec in "cz"
+    dt = wl.TORCH_DTYPES[prec]
+    rdt = {"s": torch.float32, "d": torch.float64, "c": torch.float32, "z": torch.float64}[prec]
+    lda, ldw = n + off + pad, n + (pad // 2)
+    parent = wl.matrix(prec, n + off, n + off, lda, seed=n + nb + 2, device=DEV)
+    A = parent[off:, off:] if off else parent
+    wl.poison_triangle(A, n, "U", real_diag=False)
+    host0 = parent.clone()
+    if cplx:
+        dd = torch.arange(n, device=DEV)
+        torch.view_as_real(A)[dd, dd, 1] = float("nan")
+    before = parent.clone()
+    nanv = float("nan")
+    W = torch.full((nb, ldw), nanv, dtype=dt, device=DEV)
+    e = torch.full((nb,), nanv, dtype=rdt, device=DEV)
+    tau = torch.full((nb,), nanv, dtype=dt, device=DEV)
+    k.SYTRD_PANEL[prec]("U", n, nb, A, lda, e, tau, W, ldw)
+    torch.cuda.synchronize()
+    A0 = host_matrix(host0, off, n)
+    want = po.trd_panel_upper(A0, nb)
+    A1 = host_matrix(parent, off, n)
+    tol = (TOLC if cplx else TOL)[prec]
+
+    def relc(got, ref):
+        ref = np.asarray(ref, dtype=np.complex128)
+        nrm = np.linalg.norm(ref)
+        return float(np.linalg.norm(np.asarray(got, dtype=np.complex128) - ref) / (nrm if nrm else 1.0))
+
+    first = n - nb
+    up = np.triu(np.ones((n, n), dtype=bool))
+    up[:, :first] = False                                  # upper part of the last nb columns
+    got_cols = A1[up]
+    assert np.all(np.isfinite(np.asarray(got_cols, dtype=np.complex128).view(np.float64))), "a NaN was read"
+    for i in range(first, n):
+        assert np.asarray(A1[i, i]).imag == 0
+        if i > 0:
+            assert A1[i - 1, i] == 1.0
+    Wh = W.cpu().numpy().T[:n]
+    defined = np.zeros((n, nb), dtype=bool)
+    for iw in range(nb):
+        defined[:first + iw, iw] = True
+    assert np.all(np.isfinite(np.asarray(Wh[defined], dtype=np.complex128).view(np.float64)))
+    if nb < n:
+        assert relc(got_cols, np.asarray(want["A"])[up]) <= tol
+        assert relc(e.cpu().numpy(), want["e"]) <= tol
+        assert relc(tau.cpu().numpy(), want["tau"]) <= tol
+        assert relc(Wh[defined], np.asarray(want["W"])[defined]) <= tol
+    else:
+        # a full reduction is a long chain of dependent columns: single reflector entries of the late (small)
+        # columns are not determined to working accuracy, the factorisation as a whole is: the tridiagonal
+        # matrix of the device's d and e has the eigenvalues of the input
+        U0 = np.triu(A0).astype(np.complex128)
+        U0[np.arange(n), np.arange(n)] = U0.diagonal().real
+        S = U0 + np.conj(np.triu(U0, 1)).T
+        d = np.real(np.diag(A1)).astype(np.float64)
+        eh = e.cpu().numpy().astype(np.float64)[1:]          # slot 0 belongs to column 0: no reflector
+        Tg = np.diag(d) + np.diag(eh, 1) + np.diag(eh, -1)
+        assert np.allclose(np.linalg.eigvalsh(Tg), np.linalg.eigvalsh(S), atol=50 * tol * np.linalg.norm(S, 2))
+        assert relc(d, np.real(np.diag(np.asarray(want["A"], dtype=np.complex128)))) <= 1e3 * tol
+    pb, pa = before.cpu().numpy(), parent.cpu().numpy()    # (column, row)
+    touched = np.zeros(pb.shape, dtype=bool)
+    for i in range(first, n):
+        touched[off + i, off:off + i + 1] = True
+    assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
+    if cplx:       # the diagonal before the panel keeps its real part and its (NaN) imaginary part
+        for i in range(first):
+            assert A1[i, i].real == A0[i, i].real and np.isnan(A1[i, i].imag)
