@@ -12,6 +12,8 @@
 //              w  = A[i+1:,i+1:] v                                            (SYMV, trailing block)
 //              w -= V[i+1:,:i] (W[i+1:,:i]^T v) + W[i+1:,:i] (V[i+1:,:i]^T v) (2 GEMV-T, 2 GEMV-N)
 //              w  = tau w;  w -= (tau/2)(w.v) v                               (one small kernel)
+// Upper storage runs the mirror image (last nb columns, from the right), complex types the Hermitian form
+// (conjugated transposes, real e); the bidiagonal step further down exists for all four precisions as well.
 // Everything stays on the device and on the caller's stream: tau and the dot
 // product never visit the host, so a whole panel is one uninterrupted sequence of
 // launches (and can be captured in a graph).  The matrix-vector products go
