@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "gebrd", "batched", "csymv", "rect", "tiny"])
+    ap.add_argument("--prec", default="d", choices=list("sdcz"), help="precision of the sytrd / gebrd workloads")
+    ap.add_argument("--uplo", default="L", choices=["L", "U"], help="stored triangle of the sytrd workload")
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
@@ -216,17 +218,22 @@ def tiny_latency(k, torch, wl):
 
 
 # ------------------------------------------------------------ CPU baseline ----
+DTYPE_NAMES = {"s": "f32", "d": "f64", "c": "c64", "z": "c128"}
+
+
 def sytrd_panel_bench(args, k, torch, wl, acc):
     """One step = the panel step of the tridiagonal reduction (kmv_dsytrd_panel) on the first 64 columns of a
     16384 x 16384 fp64 matrix: per column one DSYMV on the trailing block, two DGEMV-N with strided x, two
     DGEMV-T and two DGEMV-N on the reflector panels and two small vector kernels, all enqueued without a host
     round trip.  The matrix is restored from a copy before every step, outside the timed brackets."""
-    n, nb, prec = 16384, 64, "d"
+    n, nb, prec, uplo = 16384, 64, args.prec, args.uplo
     A0 = wl.matrix(prec, n, n, n, seed=0, device="cuda")
     A = A0.clone()
     dt = wl.TORCH_DTYPES[prec]
+    rdt = wl.TORCH_DTYPES[{"c": "s", "z": "d"}.get(prec, prec)]      # e is real
+    esz = A0.element_size()
     W = torch.zeros((nb, n), dtype=dt, device="cuda")
-    e = torch.zeros(nb, dtype=dt, device="cuda")
+    e = torch.zeros(nb, dtype=rdt, device="cuda")
     tau = torch.zeros(nb, dtype=dt, device="cuda")
     ws = k.workspace(k.sytrd_panel_workspace_bytes(prec, n, nb))
     stream = torch.cuda.current_stream()
@@ -238,7 +245,7 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
         for op, mm, nn in ops:
             nbytes += acc.algorithmic_bytes(op, prec, mm, nn)
             nflops += acc.flops(op, prec, mm, nn)
-        nbytes += 6 * m * 8            # the two vector kernels: v read and written, then w and v read, w written
+        nbytes += 6 * m * esz          # the two vector kernels: v read and written, then w and v read, w written
     times = []
     for step in range(args.warmup + args.steps):
         A.copy_(A0)
@@ -246,7 +253,7 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record(stream)
-        k.dsytrd_panel("L", n, nb, A, n, e, tau, W, n, workspace=ws)
+        k.SYTRD_PANEL[prec](uplo, n, nb, A, n, e, tau, W, n, workspace=ws)
         e1.record(stream)
         host_ms = (time.perf_counter() - t0) * 1e3
         torch.cuda.synchronize()
@@ -260,9 +267,10 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
         "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
-        "config": {"workload": "panel step of the tridiagonal reduction (kmv_dsytrd_panel), n=16384, nb=64, lda=n, "
-                               "U[-1,1]: 64 DSYMV on trailing blocks + 378 DGEMV on reflector panels + 128 vector kernels",
+        "dtype": DTYPE_NAMES[prec], "data": "synthetic",
+        "config": {"workload": f"panel step of the tridiagonal reduction (kmv_{prec}{'hetrd' if prec in 'cz' else 'sytrd'}_panel, "
+                               f"uplo {uplo}), n=16384, nb=64, lda=n, U[-1,1]: 64 SYMV/HEMV on trailing blocks + 378 GEMV on "
+                               "reflector panels + 128 vector kernels",
                    "products_per_step": nb + 6 * (nb - 1)},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "gflops": round(nflops / (step_ms * 1e-3) / 1e9, 1),
@@ -278,13 +286,15 @@ def gebrd_panel_bench(args, k, torch, wl, acc):
     a 16384 x 16384 fp64 matrix: per column DGEMV-T and DGEMV-N on the whole trailing block (the latter with a
     strided x, a row of A) and eleven DGEMV on the accumulated panels, two reflectors, two scalings."""
     m = n = 16384
-    nb, prec = 64, "d"
+    nb, prec = 64, args.prec
     A0 = wl.matrix(prec, m, n, m, seed=0, device="cuda")
     A = A0.clone()
     dt = wl.TORCH_DTYPES[prec]
+    rdt = wl.TORCH_DTYPES[{"c": "s", "z": "d"}.get(prec, prec)]      # d and e are real
     X = torch.zeros((nb, m), dtype=dt, device="cuda")
     Y = torch.zeros((nb, n), dtype=dt, device="cuda")
-    d, e, tauq, taup = (torch.zeros(nb, dtype=dt, device="cuda") for _ in range(4))
+    d, e = (torch.zeros(nb, dtype=rdt, device="cuda") for _ in range(2))
+    tauq, taup = (torch.zeros(nb, dtype=dt, device="cuda") for _ in range(2))
     ws = k.workspace(k.gebrd_panel_workspace_bytes(prec, m, n, nb))
     stream = torch.cuda.current_stream()
     nbytes = nflops = big = 0
@@ -306,7 +316,7 @@ def gebrd_panel_bench(args, k, torch, wl, acc):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record(stream)
-        k.dgebrd_panel(m, n, nb, A, m, d, e, tauq, taup, X, m, Y, n, workspace=ws)
+        k.GEBRD_PANEL[prec](m, n, nb, A, m, d, e, tauq, taup, X, m, Y, n, workspace=ws)
         e1.record(stream)
         host_ms = (time.perf_counter() - t0) * 1e3
         torch.cuda.synchronize()
@@ -319,9 +329,9 @@ def gebrd_panel_bench(args, k, torch, wl, acc):
         "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
-        "config": {"workload": "panel step of the bidiagonal reduction (kmv_dgebrd_panel), m=n=16384, nb=64, lda=m, "
-                               "U[-1,1]: 128 DGEMV on trailing blocks + about 690 DGEMV on the panels",
+        "dtype": DTYPE_NAMES[prec], "data": "synthetic",
+        "config": {"workload": f"panel step of the bidiagonal reduction (kmv_{prec}gebrd_panel), m=n=16384, nb=64, lda=m, "
+                               "U[-1,1]: 128 GEMV on trailing blocks + about 690 GEMV on the panels",
                    "products_per_step": 2 * nb + 11 * (nb - 1)},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "gflops": round(nflops / (step_ms * 1e-3) / 1e9, 1),
