@@ -16,7 +16,8 @@
 // first design, still chosen for large matrices whose columns are not 16-byte
 // aligned), symv_balanced_kernel (equal shares of the triangle's pieces for one
 // resident round of workgroups, the default) and symv_small_kernel (one launch,
-// no workspace, for small matrices).  What the first one does differently from
+// no workspace, for small matrices); strided batches of small matrices have
+// symv_member_kernel (one workgroup per matrix).  What the first one does differently from
 // the paper, to fit wave64 and what was measured on the MI355X (small writes
 // scattered through a read stream cost far more than their bytes; a workgroup
 // that reads a few columns over several KiB of consecutive rows streams at full
