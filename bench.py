@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "gebrd", "batched", "csymv", "rect", "tiny"])
-    ap.add_argument("--prec", default="d", choices=list("sdcz"), help="precision of the sytrd / gebrd workloads")
+    ap.add_argument("--prec", default="d", choices=list("sdcz"), help="precision of the sytrd / gebrd / batched workloads")
     ap.add_argument("--uplo", default="L", choices=["L", "U"], help="stored triangle of the sytrd workload")
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -343,31 +343,36 @@ def gebrd_panel_bench(args, k, torch, wl, acc):
 
 
 def batched_bench(args, k, torch, wl, acc):
-    """One step = strided batches of small fp64 products, 1 GiB of matrices per batch: DGEMV N and T and DSYMV L at
-    n = 64 .. 1024, one call (one launch) per batch.  For comparison the same products as a loop of single calls
-    (prepared, so a call is one foreign call) are timed on the first 256 members."""
-    dt = wl.TORCH_DTYPES["d"]
-    total = 1 << 27                      # elements of matrix storage per batch (1 GiB)
+    """One step = strided batches of small products (--prec, default fp64), 1 GiB of matrices per batch: GEMV N and
+    T and SYMV/HEMV L at n = 64 .. 1024, one call (one launch) per batch.  For comparison the same products as a
+    loop of single calls (prepared, so a call is one foreign call) are timed on the first 256 members."""
+    prec = args.prec
+    dt = wl.TORCH_DTYPES[prec]
+    esz = torch.empty(0, dtype=dt).element_size()
+    total = (1 << 30) // esz             # elements of matrix storage per batch (1 GiB)
     flat = torch.empty(total, dtype=dt, device="cuda")
     g = torch.Generator(device="cuda")
     g.manual_seed(0)
     wl.fill_random(flat, "uniform", g)
     stream = torch.cuda.current_stream()
     rows, tot_bytes, tot_ms = [], 0, 0.0
-    t_all0 = None
-    cases = [(kind, n) for n in (64, 128, 256, 512, 1024) for kind in ("gemv_n", "gemv_t", "symv_l")]
-    xs = wl.vector("d", total // 64, 1, seed=0, which=1, device="cuda")
-    ys = wl.vector("d", total // 64, 1, seed=0, which=2, device="cuda")
+    sizes = (64, 128, 256, 512, 1024)
+    cases = [(kind, n) for n in sizes for kind in ("gemv_n", "gemv_t", "symv_l")]
+    xs = wl.vector(prec, total // min(sizes), 1, seed=0, which=1, device="cuda")     # batch * n elements at most
+    ys = wl.vector(prec, total // min(sizes), 1, seed=0, which=2, device="cuda")
+    symv_name = prec + ("hemv" if prec in "cz" else "symv")
 
     def run(kind, n, batch):
         if kind == "symv_l":
-            k.dsymv_strided_batched("L", n, 1.0, flat, n, n * n, xs, 1, n, 0.0, ys, 1, n, batch)
+            k.SYMV_STRIDED_BATCHED[prec]("L", n, 1.0, flat, n, n * n, xs, 1, n, 0.0, ys, 1, n, batch)
         else:
-            k.dgemv_strided_batched("N" if kind == "gemv_n" else "T", n, n, 1.0, flat, n, n * n, xs, 1, n, 1.0, ys, 1, n, batch)
+            k.GEMV_STRIDED_BATCHED[prec]("N" if kind == "gemv_n" else "T", n, n, 1.0, flat, n, n * n, xs, 1, n, 1.0, ys, 1, n,
+                                         batch)
 
     for kind, n in cases:
         batch = total // (n * n)
-        nbytes = batch * acc.algorithmic_bytes(kind, "d", n, n)
+        assert batch * n <= xs.numel() and batch * n * n <= flat.numel()
+        nbytes = batch * acc.algorithmic_bytes(kind, prec, n, n)
         for _ in range(args.warmup):
             run(kind, n, batch)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -381,9 +386,9 @@ def batched_bench(args, k, torch, wl, acc):
         # the same members one call at a time (first 256 only)
         nloop = min(batch, 256)
         if kind == "symv_l":
-            calls = [k.prepare_symv("d", "L", n, 1.0, flat[b * n * n:], n, xs[b * n:], 1, 0.0, ys[b * n:], 1) for b in range(nloop)]
+            calls = [k.prepare_symv(prec, "L", n, 1.0, flat[b * n * n:], n, xs[b * n:], 1, 0.0, ys[b * n:], 1) for b in range(nloop)]
         else:
-            calls = [k.prepare_gemv("d", "N" if kind == "gemv_n" else "T", n, n, 1.0, flat[b * n * n:], n, xs[b * n:], 1, 1.0,
+            calls = [k.prepare_gemv(prec, "N" if kind == "gemv_n" else "T", n, n, 1.0, flat[b * n * n:], n, xs[b * n:], 1, 1.0,
                                     ys[b * n:], 1) for b in range(nloop)]
         for c in calls:
             c()
@@ -393,7 +398,7 @@ def batched_bench(args, k, torch, wl, acc):
             c()
         torch.cuda.synchronize()
         loop_us = (time.perf_counter() - t0) * 1e6 / nloop
-        rows.append({"routine": "d" + kind, "n": n, "batch": batch, "ms": round(ms, 4),
+        rows.append({"routine": symv_name + "_L" if kind == "symv_l" else prec + kind, "n": n, "batch": batch, "ms": round(ms, 4),
                      "us_per_member": round(ms * 1e3 / batch, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                      "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "single_call_loop_us_per_member": round(loop_us, 3)})
@@ -408,9 +413,9 @@ def batched_bench(args, k, torch, wl, acc):
         "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(tot_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
-        "config": {"workload": "strided batches of DGEMV N,T and DSYMV L, n = 64..1024, 1 GiB of fp64 matrices per batch "
-                               "(32768 .. 128 members), one call per batch", "products_per_step": len(cases)},
+        "dtype": DTYPE_NAMES[prec], "data": "synthetic",
+        "config": {"workload": f"strided batches of {prec}gemv N,T and {symv_name} L, n = 64..1024, 1 GiB of matrices per batch, "
+                               "one call per batch", "products_per_step": len(cases)},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "per_shape": rows,
         "roofline": None,
