@@ -408,7 +408,9 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *                                 SYMV variant 2 the number of workgroups
  *   symv_member_rows              strided batches: largest n that gets one
  *                                 workgroup per member (up to 1024; 512 for z)
- *   symv_member_waves             waves of that workgroup (4, 8) */
+ *   symv_member_waves             waves of that workgroup (4, 8; a value
+ *                                 also keeps the smallest members away from
+ *                                 the one-wave-per-member kernel) */
 int kmv_set_tuning(const char* key, int64_t value);
 int64_t kmv_get_tuning(const char* key);
 const char* kmv_tuning_keys(void);

@@ -843,6 +843,160 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
     }
 }
 
+// Members of a batch that are at most half a row tile tall (n <= 32 * VEC): one WAVE per matrix, and the wave
+// loads CPL = 64 / L columns at a time, L lanes (L * VEC >= n rows) on each.  The per-column work of the kernel
+// above (address arithmetic, masks for the diagonal, the reduction of the column sum) is what bounds it when a
+// column is shorter than a wave's 1 KiB load; here it is shared by CPL columns.  Lane (sub, cl) = (lane % L,
+// lane / L) owns rows sub*VEC .. sub*VEC+VEC-1 in the columns j = cl, cl + CPL, ...: it adds a_ij x_j to its
+// row sums and collects op(a_ij) x_i, which a reduction over the L lanes of the column (DPP, plus one
+// cross-lane move for L = 32) turns into the column sum; the lane that owns row j takes it into its row sums.
+// At the end the row sums of the CPL lane groups are added (rotations inside the rows of 16 lanes, cross-lane
+// moves between them) and the lanes of group 0 write y.  No LDS, no barrier; loads run three column groups
+// ahead, clamped into the stored part as above, and the short columns at the end of the triangle go to the
+// epilogue in the same way.
+template <int M> __device__ __forceinline__ int xor_lane_i32(int v) {
+    const int lane = (int)(threadIdx.x & (WAVE - 1));
+    return __builtin_amdgcn_ds_bpermute((lane ^ M) << 2, v);
+}
+template <int M> __device__ __forceinline__ float xor_lane(float v) {
+    return __builtin_bit_cast(float, xor_lane_i32<M>(__builtin_bit_cast(int, v)));
+}
+template <int M> __device__ __forceinline__ double xor_lane(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)xor_lane_i32<M>((int)(uint32_t)u), hi = (uint32_t)xor_lane_i32<M>((int)(uint32_t)(u >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+// sum over the aligned group of L consecutive lanes (L = 8 .. 64), the same value in each of them
+template <int L, class R> __device__ __forceinline__ R seg_sum_real(R v) {
+    v += dpp_move<0xB1>(v);                           // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);                           // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);                          // row_half_mirror: 8 lanes
+    if constexpr (L >= 16) v += dpp_move<0x140>(v);   // row_mirror: 16 lanes
+    if constexpr (L >= 32) v += xor_lane<16>(v);
+    if constexpr (L >= 64) v += xor_lane<32>(v);
+    return v;
+}
+// sum over the 64 / L lanes that hold the same position in their group of L, the same value in each of them
+template <int L, class R> __device__ __forceinline__ R cross_sum_real(R v) {
+    if constexpr (L <= 8) v += dpp_move<0x128>(v);    // row_ror 8: the other group of 8 in the row
+    if constexpr (L <= 16) v += xor_lane<16>(v);
+    if constexpr (L <= 32) v += xor_lane<32>(v);
+    return v;
+}
+template <int L> __device__ __forceinline__ float seg_sum(float v) { return seg_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ double seg_sum(double v) { return seg_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ cf32 seg_sum(cf32 v) { return cf32{seg_sum_real<L>(v.re), seg_sum_real<L>(v.im)}; }
+template <int L> __device__ __forceinline__ cf64 seg_sum(cf64 v) { return cf64{seg_sum_real<L>(v.re), seg_sum_real<L>(v.im)}; }
+template <int L> __device__ __forceinline__ float cross_sum(float v) { return cross_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ double cross_sum(double v) { return cross_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ cf32 cross_sum(cf32 v) { return cf32{cross_sum_real<L>(v.re), cross_sum_real<L>(v.im)}; }
+template <int L> __device__ __forceinline__ cf64 cross_sum(cf64 v) { return cf64{cross_sum_real<L>(v.re), cross_sum_real<L>(v.im)}; }
+
+constexpr int TINY_NW = 4;   // members (waves) per workgroup
+
+template <class T, bool HERM, bool LOWER, int L>
+__global__ __launch_bounds__(TINY_NW * WAVE) void symv_tiny_kernel(SymvArgs<T> a, int batch) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int CPL = WAVE / L;
+    constexpr int DEPTH = 4;
+    static_assert(L == 8 || L == 16 || L == 32 || L == 64, "lanes per column");
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int member = (int)blockIdx.x * TINY_NW + __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    if (member >= batch) return;     // the whole wave leaves; nothing below waits for another wave
+    const int n = (int)a.n;
+    const int64_t lda = a.lda;
+    const T* __restrict__ x = a.x + (int64_t)member * a.batch_x;
+    const T* __restrict__ A = a.A + (int64_t)member * a.batch_A;
+    T* y = a.y + (int64_t)member * a.batch_y;
+    const int sub = lane % L, cl = lane / L;
+    const int r = sub * VEC;         // first row of this lane
+
+    T xr[VEC], acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        xr[e] = x[r + e < n ? r + e : 0];
+        acc[e] = zero_of<T>();
+    }
+    // columns with at least VEC stored rows: [jlo, jhi)
+    const int jlo = LOWER ? 0 : VEC - 1;
+    const int jhi = LOWER ? n - VEC + 1 : n;
+    if (jhi > jlo) {
+        const int ngroups = (jhi - jlo + CPL - 1) / CPL;
+        // position of the lane's vector in column j: the stored rows are [slo, shi), at least VEC of them
+        auto vec_row = [&](int j) {
+            const int slo = LOWER ? j : 0, shi = LOWER ? n : j + 1;
+            const int rc = r < slo ? slo : r;
+            return rc > shi - VEC ? shi - VEC : rc;
+        };
+        auto column = [&](int g) {     // this lane's column of group g; past the end the last column (loaded, not used)
+            const int j = jlo + g * CPL + cl;
+            return j < jhi ? j : jhi - 1;
+        };
+        Vec<T> buf[DEPTH];
+        T xj[DEPTH];
+        auto load_group = [&](int d, int g) {
+            const int j = column(g);
+            buf[d] = load_stream(A + (int64_t)j * lda + vec_row(j));
+            xj[d] = x[j];
+        };
+        auto compute_group = [&](int d, int g) {
+            const int j = column(g);
+            const bool valid = jlo + g * CPL + cl < jhi;
+            const int slo = LOWER ? j : 0, shi = LOWER ? n : j + 1;
+            const Vec<T> sv = shift_elems(buf[d], r - vec_row(j));
+            T tsum = zero_of<T>();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int row = r + e;
+                const bool stored = valid && row >= slo && row < shi;
+                const bool dia = row == j;
+                const T av = sv.e[e];
+                T nt = acc[e];
+                fma_acc(nt, select_of(HERM && dia, real_part_only(av), av), xj[d]);
+                acc[e] = select_of(stored, nt, acc[e]);
+                T tt = tsum;
+                fma_op<HERM>(tt, av, xr[e]);
+                tsum = select_of(stored && !dia, tt, tsum);
+            }
+            const T cs = seg_sum<L>(tsum);      // column sum of column j, in all L lanes of the column
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = select_of(valid && j == r + e, add_of(acc[e], cs), acc[e]);
+        };
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d) load_group(d, d);
+        for (int g = 0; g < ngroups; g += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                load_group((d + DEPTH - 1) % DEPTH, g + d + DEPTH - 1);
+                if (g + d < ngroups) compute_group(d, g + d);
+            }
+        }
+    }
+    // rows of the CPL lane groups added; group 0 finishes its rows
+    T sum[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sum[e] = cross_sum<L>(acc[e]);
+    if (cl != 0) return;
+    const T alpha = scalar_of(a.alpha, a.alpha_dev), beta = scalar_of(a.beta, a.beta_dev);
+    const int clo = LOWER ? (jhi > 0 ? jhi : 0) : 0, chi = LOWER ? n : (jlo < n ? jlo : n);   // the short columns
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int i = r + e;
+        if (i >= n) continue;
+        T s = sum[e];
+        if (VEC > 1 && i >= clo && i < chi) {
+            for (int k = clo; k < chi; ++k) {
+                const bool own = LOWER ? i >= k : i <= k;      // a_ik itself is stored (else a_ki)
+                const T av = own ? A[i + (int64_t)k * lda] : A[k + (int64_t)i * lda];
+                if (own) fma_acc(s, select_of(HERM && i == k, real_part_only(av), av), x[k]);
+                else fma_op<HERM>(s, av, x[k]);
+            }
+        }
+        T* yp = y + (int64_t)i * a.incy;
+        *yp = epilogue(alpha, s, beta, yp);
+    }
+}
+
 // y_i = alpha * ( sum over classes of wsn[class][i] + sum over chunks of
 // wst[panel(i)][chunk][i] ) + beta*y_i.  blockDim = (RED_ROWS, RED_PARTS): part g
 // adds the classes g, g+RED_PARTS, ... and then the chunks kbeg+g, kbeg+g+
@@ -1081,6 +1235,11 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
 }  // namespace
 
 namespace {
+template <class T, bool HERM, int L>
+void launch_tiny(const SymvArgs<T>& a, bool lower, dim3 grid, dim3 block, int batch, hipStream_t s) {
+    if (lower) hipLaunchKernelGGL((symv_tiny_kernel<T, HERM, true, L>), grid, block, 0, s, a, batch);
+    else hipLaunchKernelGGL((symv_tiny_kernel<T, HERM, false, L>), grid, block, 0, s, a, batch);
+}
 template <class T, bool HERM, int MAXT>
 void launch_member(const SymvArgs<T>& a, bool lower, unsigned batch, hipStream_t s) {
     const dim3 grid(batch);
@@ -1104,6 +1263,20 @@ hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int
     static_assert(!HERM || Traits<T>::cplx, "Hermitian kernels exist for complex types only");
     if (batch < 1 || batch > 65535 || (batch > 1 && a.plan.variant < 3)) return hipErrorInvalidValue;
     if (a.plan.variant == 4) {   // members of a batch: one workgroup per matrix
+        constexpr int VEC = Traits<T>::VEC;
+        // One wave per member, several columns per load when they are short: measured on 1 GiB batches against
+        // the workgroup-per-member kernel it is 1.5-3x faster up to half a row tile and 6-25% faster up to three
+        // quarters of a tile for 8- and 16-byte elements (a whole tile for 16-byte ones), 3-10% slower beyond.
+        constexpr int tiny_rows = sizeof(T) == 4 ? 32 * VEC : (sizeof(T) == 8 ? 48 * VEC : 64 * VEC);
+        if (a.n <= tiny_rows && tuning().symv_member_waves != 4 && tuning().symv_member_waves != 8) {
+            const dim3 grid((unsigned)ceil_div(batch, (int64_t)TINY_NW)), block(TINY_NW * WAVE);
+            const int b = (int)batch;
+            if (a.n <= 8 * VEC) launch_tiny<T, HERM, 8>(a, lower, grid, block, b, s);
+            else if (a.n <= 16 * VEC) launch_tiny<T, HERM, 16>(a, lower, grid, block, b, s);
+            else if (a.n <= 32 * VEC) launch_tiny<T, HERM, 32>(a, lower, grid, block, b, s);
+            else launch_tiny<T, HERM, 64>(a, lower, grid, block, b, s);
+            return hipGetLastError();
+        }
         const int64_t tiles = ceil_div(a.n, (int64_t)tile_rows<T>());
         constexpr int M = member_max_tiles<T>();
         if (tiles < 1 || tiles > M) return hipErrorInvalidValue;

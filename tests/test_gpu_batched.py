@@ -87,7 +87,8 @@ def test_complex_symmetric_strided_batched(prec, uplo):
 def _symv_batched_case(prec, uplo, csym):
     k = kmv()
     alpha, beta = scal(prec, -1.1, 0.4)
-    for n, batch, pad, incy in [(1, 1, 0, 1), (2, 3, 0, 1), (3, 2, 1, 1), (4, 2, 0, -1), (5, 2, 2, 1), (8, 4, 0, 1), (9, 3, 1, -1), (63, 5, 16, 2), (64, 2, 0, 1), (65, 3, 2, 1),
+    for n, batch, pad, incy in [(1, 1, 0, 1), (2, 3, 0, 1), (3, 2, 1, 1), (4, 2, 0, -1), (5, 2, 2, 1), (8, 4, 0, 1), (9, 3, 1, -1), (16, 5, 0, 1), (17, 3, 1, 1), (31, 2, 0, 1), (32, 6, 3, -1),
+                                 (33, 2, 0, 1), (63, 5, 16, 2), (64, 2, 0, 1), (65, 3, 2, 1), (100, 3, 1, 1), (127, 2, 0, 1), (128, 9, 0, 1),
                                  (129, 4, 0, -2), (200, 6, 3, 1), (257, 2, 5, 1), (511, 2, 0, 1), (512, 3, 0, 1),
                                  (513, 2, 1, 1), (640, 2, 0, 1), (777, 2, 0, 1), (1024, 2, 0, 1), (1100, 3, 0, 1)]:   # small members: one workgroup each; beyond: small-matrix kernel
         lda = n + (pad % 4)
