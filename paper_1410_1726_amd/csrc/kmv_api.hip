@@ -277,6 +277,7 @@ const Key KEYS[] = {
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
     {"symv_member_rows", &Tuning::symv_member_rows, 0, 1024},
     {"symv_member_waves", &Tuning::symv_member_waves, 0, 8},
+    {"symv_small_waves", &Tuning::symv_small_waves, 0, 16},
 };
 
 }  // namespace
@@ -462,6 +463,7 @@ int kmv_set_tuning(const char* key, int64_t value) {
             if (value < k.lo || value > k.hi) return -1;
             if (k.field == &Tuning::gemv_n_row_tiles && value == 3) return -1;
             if (k.field == &Tuning::symv_member_waves && value != 0 && value != 4 && value != 8) return -1;
+            if (k.field == &Tuning::symv_small_waves && value != 0 && value != 4 && value != 8 && value != 16) return -1;
             if (k.field == &Tuning::symv_panel_cols && value != 0 && value != 16 && value != 32 && value != 64 &&
                 value != 128)
                 return -1;
@@ -476,7 +478,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target,symv_member_rows,symv_member_waves"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target,symv_member_rows,symv_member_waves,symv_small_waves"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

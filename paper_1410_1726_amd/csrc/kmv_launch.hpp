@@ -25,6 +25,7 @@ struct Tuning {
     int64_t wg_target = 0;         // workgroups the heuristics aim for
     int64_t symv_member_rows = 0;     // batches: largest n for the one-workgroup-per-member kernel
     int64_t symv_member_waves = 0;    // batches: waves of that kernel's workgroup (4 or 8)
+    int64_t symv_small_waves = 0;     // small-matrix kernel: waves per workgroup (4, 8 or 16)
 };
 Tuning& tuning();
 
