@@ -36,9 +36,9 @@ HBM_PEAK_GBS = 8000.0
 # from the two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE, each scaled by the
 # reading of the library's copy kernel) summarised in profiles/sweep_hbm_traffic.txt
 MEASURED_TRAFFIC_SWEEP = {
-    "gemv_n_kernel<float>": 1411891093, "gemv_t_kernel<float>": 1410137885,
-    "gemv_n_kernel<double>": 2822079557, "gemv_t_kernel<double>": 2819138210,
-    "symv_balanced_kernel<double>": 1556587100, "symv_balanced_kernel<kmv::cf64>": 3109922465,
+    "gemv_n_kernel<float>": 1411868258, "gemv_t_kernel<float>": 1409497219,
+    "gemv_n_kernel<double>": 2822087116, "gemv_t_kernel<double>": 2818829902,
+    "symv_balanced_kernel<double>": 1607847445, "symv_balanced_kernel<kmv::cf64>": 3109920319,
 }
 
 

@@ -14,7 +14,9 @@ from gpu_util import DEV, kmv
 pytestmark = pytest.mark.gpu
 
 # normwise tolerance of a panel: nb columns that depend on each other, each a handful of length-n sums
-TOL = {"s": 1e-5, "d": 1e-12}
+# nb dependent columns, each within the single-product bound (1e-5 / 1e-13): the errors add up along the chain,
+# typically like sqrt(nb) (8e-5 at nb = 64 in single precision); five and ten single-product tolerances
+TOL = {"s": 5e-5, "d": 1e-12}
 
 
 def run_panel(prec, n, nb, lda, ldw, off=0, seed=0):
@@ -136,7 +138,7 @@ def test_panel_is_deterministic_and_capturable(prec):
         assert torch.equal(W[defined], ref[1][defined])
 
 
-TOLC = {"c": 1e-5, "z": 1e-12}
+TOLC = {"c": 5e-5, "z": 1e-12}
 
 
 @pytest.mark.parametrize("prec", "cz")
