@@ -411,7 +411,9 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *   symv_member_waves             waves of that workgroup (4, 8; a value
  *                                 also keeps the smallest members away from
  *                                 the one-wave-per-member kernel)
- *   symv_small_waves              variant 3: waves per workgroup (4, 8, 16) */
+ *   symv_small_waves              variant 3: waves per workgroup (4, 8, 16)
+ *   gemv_tiny_rows                strided batches: members with fewer rows
+ *                                 than this get one wave each (1 = never) */
 int kmv_set_tuning(const char* key, int64_t value);
 int64_t kmv_get_tuning(const char* key);
 const char* kmv_tuning_keys(void);

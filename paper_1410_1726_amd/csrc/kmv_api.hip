@@ -189,6 +189,11 @@ int gemv_batched_entry(char trans, int64_t m, int64_t n, const T* alpha, const T
             continue;
         }
         a.A = A + b0 * strideA; a.x = x + b0 * stridex; a.y = yb + b0 * stridey;
+        if (m >= Traits<T>::VEC && m <= gemv_tiny_rows<T>(notrans)) {   // short columns: one wave per member
+            const hipError_t e = launch_gemv_tiny<T>(a, notrans ? 0 : (ct ? 2 : 1), s, nb);
+            if (e != hipSuccess) return hip_code(e);
+            continue;
+        }
         GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, a.A, lda);
         // the members share one tile grid: keep the pointer's alignment shift only if every member has it
         if (nb > 1 && ((uint64_t)strideA * sizeof(T)) % 128 != 0) {
@@ -278,6 +283,7 @@ const Key KEYS[] = {
     {"symv_member_rows", &Tuning::symv_member_rows, 0, 1024},
     {"symv_member_waves", &Tuning::symv_member_waves, 0, 8},
     {"symv_small_waves", &Tuning::symv_small_waves, 0, 16},
+    {"gemv_tiny_rows", &Tuning::gemv_tiny_rows, 0, 1024},
 };
 
 }  // namespace
@@ -478,7 +484,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target,symv_member_rows,symv_member_waves,symv_small_waves"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

@@ -200,6 +200,47 @@ __device__ __forceinline__ double wave_sum(double v) { return wave_sum_real(v); 
 __device__ __forceinline__ cf32 wave_sum(cf32 v) { return cf32{wave_sum_real(v.re), wave_sum_real(v.im)}; }
 __device__ __forceinline__ cf64 wave_sum(cf64 v) { return cf64{wave_sum_real(v.re), wave_sum_real(v.im)}; }
 
+// ---- sums over groups of lanes, for kernels that put several short columns on one wave: lane = cl * L + sub
+// (L lanes per column, 64 / L columns side by side)
+template <int M> __device__ __forceinline__ int xor_lane_i32(int v) {
+    const int lane = (int)(threadIdx.x & (WAVE - 1));
+    return __builtin_amdgcn_ds_bpermute((lane ^ M) << 2, v);
+}
+template <int M> __device__ __forceinline__ float xor_lane(float v) {
+    return __builtin_bit_cast(float, xor_lane_i32<M>(__builtin_bit_cast(int, v)));
+}
+template <int M> __device__ __forceinline__ double xor_lane(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)xor_lane_i32<M>((int)(uint32_t)u), hi = (uint32_t)xor_lane_i32<M>((int)(uint32_t)(u >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+// sum over the aligned group of L consecutive lanes (L = 8 .. 64), the same value in each of them
+template <int L, class R> __device__ __forceinline__ R seg_sum_real(R v) {
+    v += dpp_move<0xB1>(v);                           // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);                           // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);                          // row_half_mirror: 8 lanes
+    if constexpr (L >= 16) v += dpp_move<0x140>(v);   // row_mirror: 16 lanes
+    if constexpr (L >= 32) v += xor_lane<16>(v);
+    if constexpr (L >= 64) v += xor_lane<32>(v);
+    return v;
+}
+// sum over the 64 / L lanes that hold the same position in their group of L, the same value in each of them
+template <int L, class R> __device__ __forceinline__ R cross_sum_real(R v) {
+    if constexpr (L <= 8) v += dpp_move<0x128>(v);    // row_ror 8: the other group of 8 in the row
+    if constexpr (L <= 16) v += xor_lane<16>(v);
+    if constexpr (L <= 32) v += xor_lane<32>(v);
+    return v;
+}
+template <int L> __device__ __forceinline__ float seg_sum(float v) { return seg_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ double seg_sum(double v) { return seg_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ cf32 seg_sum(cf32 v) { return cf32{seg_sum_real<L>(v.re), seg_sum_real<L>(v.im)}; }
+template <int L> __device__ __forceinline__ cf64 seg_sum(cf64 v) { return cf64{seg_sum_real<L>(v.re), seg_sum_real<L>(v.im)}; }
+template <int L> __device__ __forceinline__ float cross_sum(float v) { return cross_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ double cross_sum(double v) { return cross_sum_real<L>(v); }
+template <int L> __device__ __forceinline__ cf32 cross_sum(cf32 v) { return cf32{cross_sum_real<L>(v.re), cross_sum_real<L>(v.im)}; }
+template <int L> __device__ __forceinline__ cf64 cross_sum(cf64 v) { return cf64{cross_sum_real<L>(v.re), cross_sum_real<L>(v.im)}; }
+
+
 // ---- balanced contiguous partition (Section 6.2, Eqs. local_workload and
 // starting_point with W for the misprinted d): worker y of Y gets w items
 // starting at s; shares differ by at most one and tile the range [0, W).

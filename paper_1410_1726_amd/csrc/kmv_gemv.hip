@@ -577,10 +577,124 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
     return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, 0, a.n, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
 }
 
+// ---- strided batches of matrices at most one row tile tall: one WAVE per member --------------
+// Below a row tile the general kernels leave most lanes of a wave idle and spend their time on the
+// per-column instructions.  Here a member is one wave's work and the wave loads CPL = 64 / L columns at a
+// time, L lanes (L * VEC >= m rows) on each: lane (sub, cl) = (lane % L, lane / L) owns rows sub*VEC ..
+// sub*VEC+VEC-1 in the columns cl, cl + CPL, ...  'N': a_ij x_j goes into the lane's row sums, the lane
+// groups are added at the end and group 0 writes y.  'T' / 'C': op(a_ij) x_i is summed over the L lanes of
+// the column (DPP) and lane 0 of the group writes y_j.  No LDS, no barrier, loads three column groups ahead;
+// a lane whose rows straddle the last row loads at m - VEC and moves the elements into place (needs m >= VEC).
+constexpr int GTINY_NW = 4;   // members (waves) per workgroup
+template <class T, int MODE, int L>   // MODE 0: N, 1: T, 2: C
+__global__ __launch_bounds__(GTINY_NW * WAVE) void gemv_tiny_kernel(GemvArgs<T> a, int batch) {
+    constexpr int VEC = Traits<T>::VEC;
+    constexpr int CPL = WAVE / L;
+    constexpr int DEPTH = 4;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int member = (int)blockIdx.x * GTINY_NW + __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
+    if (member >= batch) return;     // the whole wave leaves; nothing below waits for another wave
+    const int m = (int)a.m, n = (int)a.n;
+    const int64_t lda = a.lda;
+    const T* __restrict__ x = a.x + (int64_t)member * a.batch_x;
+    const T* __restrict__ A = a.A + (int64_t)member * a.batch_A;
+    T* y = a.y + (int64_t)member * a.batch_y;
+    const int sub = lane % L, cl = lane / L;
+    const int r = sub * VEC;                               // first row of this lane
+    const int rc = r + VEC <= m ? r : m - VEC;             // where its vector is loaded (m >= VEC)
+    const T alpha = scalar_of(a.alpha, a.alpha_dev), beta = scalar_of(a.beta, a.beta_dev);
+    T xr[VEC], acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        xr[e] = MODE == 0 ? zero_of<T>() : x[r + e < m ? r + e : 0];
+        acc[e] = zero_of<T>();
+    }
+    const int ngroups = (n + CPL - 1) / CPL;
+    auto column = [&](int g) {     // this lane's column of group g; past the end the last column (loaded, not used)
+        const int j = g * CPL + cl;
+        return j < n ? j : n - 1;
+    };
+    Vec<T> buf[DEPTH];
+    T xj[DEPTH];
+    auto load_group = [&](int d, int g) {
+        const int j = column(g);
+        buf[d] = load_stream(A + (int64_t)j * lda + rc);
+        if (MODE == 0) xj[d] = x[j];
+    };
+    auto compute_group = [&](int d, int g) {
+        const int j = g * CPL + cl;
+        const bool valid = j < n;
+        const Vec<T> sv = shift_elems(buf[d], r - rc);
+        if (MODE == 0) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                T nt = acc[e];
+                fma_acc(nt, sv.e[e], xj[d]);
+                acc[e] = select_of(valid && r + e < m, nt, acc[e]);
+            }
+        } else {
+            T t = zero_of<T>();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                T tt = t;
+                fma_op<MODE == 2>(tt, sv.e[e], xr[e]);
+                t = select_of(r + e < m, tt, t);
+            }
+            const T cs = seg_sum<L>(t);
+            if (valid && sub == 0) {
+                T* yp = y + (int64_t)j * a.incy;
+                *yp = epilogue(alpha, cs, beta, yp);
+            }
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d) load_group(d, d);
+    for (int g = 0; g < ngroups; g += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            load_group((d + DEPTH - 1) % DEPTH, g + d + DEPTH - 1);
+            if (g + d < ngroups) compute_group(d, g + d);
+        }
+    }
+    if (MODE == 0) {
+        T sum[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum[e] = cross_sum<L>(acc[e]);
+        if (cl != 0) return;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            if (r + e >= m) continue;
+            T* yp = y + (int64_t)(r + e) * a.incy;
+            *yp = epilogue(alpha, sum[e], beta, yp);
+        }
+    }
+}
+
+template <class T, int MODE>
+void launch_gemv_tiny_mode(const GemvArgs<T>& a, hipStream_t s, int batch) {
+    constexpr int VEC = Traits<T>::VEC;
+    const dim3 grid((unsigned)ceil_div((int64_t)batch, (int64_t)GTINY_NW)), block(GTINY_NW * WAVE);
+    if (a.m <= 8 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 8>), grid, block, 0, s, a, batch);
+    else if (a.m <= 16 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 16>), grid, block, 0, s, a, batch);
+    else if (a.m <= 32 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 32>), grid, block, 0, s, a, batch);
+    else hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 64>), grid, block, 0, s, a, batch);
+}
+
+// mode 0: N, 1: T, 2: C (complex T only).  Requires VEC <= m <= one row tile, n >= 1, batch <= 65535.
+template <class T> hipError_t launch_gemv_tiny(const GemvArgs<T>& a, int mode, hipStream_t s, int64_t batch) {
+    constexpr int VEC = Traits<T>::VEC;
+    if (batch < 1 || batch > 65535 || a.m < VEC || a.m > WAVE * VEC || a.n < 1 || a.n > (int64_t)1 << 30) return hipErrorInvalidValue;
+    if (mode == 0) launch_gemv_tiny_mode<T, 0>(a, s, (int)batch);
+    else if (mode == 2 && Traits<T>::cplx) launch_gemv_tiny_mode<T, 2>(a, s, (int)batch);
+    else launch_gemv_tiny_mode<T, 1>(a, s, (int)batch);
+    return hipGetLastError();
+}
+
 #define KMV_INSTANTIATE_GEMV(T)                                                              \
     template GemvPlan<T> plan_gemv<T>(bool, int64_t, int64_t, const void*, int64_t);         \
     template hipError_t launch_gemv_n<T>(const GemvArgs<T>&, hipStream_t, int64_t);          \
-    template hipError_t launch_gemv_t<T>(const GemvArgs<T>&, bool, hipStream_t, int64_t);
+    template hipError_t launch_gemv_t<T>(const GemvArgs<T>&, bool, hipStream_t, int64_t);          \
+    template hipError_t launch_gemv_tiny<T>(const GemvArgs<T>&, int, hipStream_t, int64_t);
 KMV_INSTANTIATE_GEMV(float)
 KMV_INSTANTIATE_GEMV(double)
 KMV_INSTANTIATE_GEMV(cf32)

@@ -26,6 +26,7 @@ struct Tuning {
     int64_t symv_member_rows = 0;     // batches: largest n for the one-workgroup-per-member kernel
     int64_t symv_member_waves = 0;    // batches: waves of that kernel's workgroup (4 or 8)
     int64_t symv_small_waves = 0;     // small-matrix kernel: waves per workgroup (4, 8 or 16)
+    int64_t gemv_tiny_rows = 0;       // batches: one wave per member for m < this value (1 = never)
 };
 Tuning& tuning();
 
@@ -96,6 +97,19 @@ template <class T> struct GemvArgs {
 // batch > 1: a strided batch in one launch (requires plan.splits == 1 and the general kernels)
 template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s, int64_t batch = 1);
 template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s, int64_t batch = 1);
+// strided batches of matrices with VEC <= m <= gemv_tiny_rows<T>(notrans): one wave per member, several columns per
+// load (mode 0: N, 1: T, 2: C); uses none of the plan
+template <class T> hipError_t launch_gemv_tiny(const GemvArgs<T>& a, int mode, hipStream_t s, int64_t batch);
+// Largest m it is chosen for.  Measured on 1 GiB batches of square members against the general kernels: 'N' wins
+// up to 256 bytes per column (384 for 4-byte elements: 1.1-3.6x), 'T' / 'C' up to half a row tile (a whole one for
+// 16-byte elements: 1.1-4.8x); beyond, the general kernels are 2-25% faster.
+template <class T> inline int64_t gemv_tiny_rows(bool notrans) {
+    constexpr int64_t VEC = Traits<T>::VEC;
+    const int64_t cap = 64 * VEC;
+    if (tuning().gemv_tiny_rows > 0) return tuning().gemv_tiny_rows - 1 < cap ? tuning().gemv_tiny_rows - 1 : cap;
+    if (notrans) return sizeof(T) == 4 ? 24 * VEC : 16 * VEC;
+    return sizeof(T) == 16 ? 64 * VEC : 32 * VEC;
+}
 
 // ----------------------------------------------------------- SYMV/HEMV ----
 template <class T> struct SymvPlan {

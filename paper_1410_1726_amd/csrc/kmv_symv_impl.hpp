@@ -854,44 +854,6 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
 // moves between them) and the lanes of group 0 write y.  No LDS, no barrier; loads run three column groups
 // ahead, clamped into the stored part as above, and the short columns at the end of the triangle go to the
 // epilogue in the same way.
-template <int M> __device__ __forceinline__ int xor_lane_i32(int v) {
-    const int lane = (int)(threadIdx.x & (WAVE - 1));
-    return __builtin_amdgcn_ds_bpermute((lane ^ M) << 2, v);
-}
-template <int M> __device__ __forceinline__ float xor_lane(float v) {
-    return __builtin_bit_cast(float, xor_lane_i32<M>(__builtin_bit_cast(int, v)));
-}
-template <int M> __device__ __forceinline__ double xor_lane(double v) {
-    const uint64_t u = __builtin_bit_cast(uint64_t, v);
-    const uint32_t lo = (uint32_t)xor_lane_i32<M>((int)(uint32_t)u), hi = (uint32_t)xor_lane_i32<M>((int)(uint32_t)(u >> 32));
-    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-}
-// sum over the aligned group of L consecutive lanes (L = 8 .. 64), the same value in each of them
-template <int L, class R> __device__ __forceinline__ R seg_sum_real(R v) {
-    v += dpp_move<0xB1>(v);                           // quad_perm [1,0,3,2]
-    v += dpp_move<0x4E>(v);                           // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);                          // row_half_mirror: 8 lanes
-    if constexpr (L >= 16) v += dpp_move<0x140>(v);   // row_mirror: 16 lanes
-    if constexpr (L >= 32) v += xor_lane<16>(v);
-    if constexpr (L >= 64) v += xor_lane<32>(v);
-    return v;
-}
-// sum over the 64 / L lanes that hold the same position in their group of L, the same value in each of them
-template <int L, class R> __device__ __forceinline__ R cross_sum_real(R v) {
-    if constexpr (L <= 8) v += dpp_move<0x128>(v);    // row_ror 8: the other group of 8 in the row
-    if constexpr (L <= 16) v += xor_lane<16>(v);
-    if constexpr (L <= 32) v += xor_lane<32>(v);
-    return v;
-}
-template <int L> __device__ __forceinline__ float seg_sum(float v) { return seg_sum_real<L>(v); }
-template <int L> __device__ __forceinline__ double seg_sum(double v) { return seg_sum_real<L>(v); }
-template <int L> __device__ __forceinline__ cf32 seg_sum(cf32 v) { return cf32{seg_sum_real<L>(v.re), seg_sum_real<L>(v.im)}; }
-template <int L> __device__ __forceinline__ cf64 seg_sum(cf64 v) { return cf64{seg_sum_real<L>(v.re), seg_sum_real<L>(v.im)}; }
-template <int L> __device__ __forceinline__ float cross_sum(float v) { return cross_sum_real<L>(v); }
-template <int L> __device__ __forceinline__ double cross_sum(double v) { return cross_sum_real<L>(v); }
-template <int L> __device__ __forceinline__ cf32 cross_sum(cf32 v) { return cf32{cross_sum_real<L>(v.re), cross_sum_real<L>(v.im)}; }
-template <int L> __device__ __forceinline__ cf64 cross_sum(cf64 v) { return cf64{cross_sum_real<L>(v.re), cross_sum_real<L>(v.im)}; }
-
 constexpr int TINY_NW = 4;   // members (waves) per workgroup
 
 template <class T, bool HERM, bool LOWER, int L>

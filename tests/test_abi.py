@@ -112,7 +112,7 @@ def test_tuning_keys_roundtrip():
     assert "symv_panel_cols" in keys
     for k in keys:
         old = kmv.get_tuning(k)
-        val = {"symv_panel_cols": 64, "symv_member_waves": 8, "symv_small_waves": 8}.get(k, 2)
+        val = {"symv_panel_cols": 64, "symv_member_waves": 8, "symv_small_waves": 8, "gemv_tiny_rows": 100}.get(k, 2)
         kmv.set_tuning(k, val)
         assert kmv.get_tuning(k) == val
         kmv.set_tuning(k, old)

@@ -38,11 +38,24 @@ def y_buffer(prec, leny, incy, stridey, batch, seed):
 
 @pytest.mark.parametrize("prec", PRECS)
 @pytest.mark.parametrize("trans", "NTC")
-def test_gemv_strided_batched(prec, trans):
+@pytest.mark.parametrize("tiny_rows", [0, 1, 1024])     # the library's choice, never, up to a whole row tile
+def test_gemv_strided_batched(prec, trans, tiny_rows):
     k = kmv()
+    k.set_tuning("gemv_tiny_rows", tiny_rows)
+    try:
+        _gemv_batched_cases(k, prec, trans)
+    finally:
+        k.set_tuning("gemv_tiny_rows", 0)
+
+
+def _gemv_batched_cases(k, prec, trans):
     alpha, beta = scal(prec, 0.7, -0.3)
-    cases = [(1, 1, 1, 0, 1), (7, 5, 3, 1, 1), (64, 64, 4, 0, 2), (100, 300, 5, 3, -1), (513, 129, 17, 0, 1),
-             (1000, 40, 2, 8, 1), (300, 700, 3, 16, -2)]
+    # up to one row tile (256 / 128 / 128 / 64 rows): one wave per member with 8, 16, 32 or 64 lanes per column
+    cases = [(1, 1, 1, 0, 1), (2, 9, 3, 0, 1), (3, 3, 2, 1, 1), (4, 1, 5, 0, 1), (5, 17, 2, 2, -1), (7, 5, 3, 1, 1),
+             (8, 8, 9, 0, 1), (9, 40, 3, 1, 1), (16, 16, 6, 0, 1), (17, 3, 2, 0, 2), (31, 33, 3, 3, 1), (32, 100, 5, 0, 1),
+             (33, 7, 2, 1, 1), (63, 64, 3, 0, 1), (64, 64, 4, 0, 2), (65, 200, 7, 16, 1), (100, 300, 5, 3, -1),
+             (127, 50, 2, 0, 1), (128, 128, 3, 0, 1), (129, 31, 2, 1, 1), (255, 20, 3, 0, 1), (256, 256, 2, 0, 1),
+             (257, 9, 2, 0, 1), (513, 129, 17, 0, 1), (1000, 40, 2, 8, 1), (300, 700, 3, 16, -2)]
     for m, n, batch, pad, incy in cases:
         lda = m + (pad % 5)
         strideA = lda * n + pad                       # pad = 0 or 16: members equally aligned; else not
