@@ -1241,7 +1241,7 @@ hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int
             if (a.n <= 8 * VEC) launch_tiny<T, HERM, 8>(a, lower, grid, block, b, s);
             else if (a.n <= 16 * VEC) launch_tiny<T, HERM, 16>(a, lower, grid, block, b, s);
             else if (a.n <= 32 * VEC) launch_tiny<T, HERM, 32>(a, lower, grid, block, b, s);
-            else launch_tiny<T, HERM, 64>(a, lower, grid, block, b, s);
+            else if constexpr (tiny_rows > 32 * VEC) launch_tiny<T, HERM, 64>(a, lower, grid, block, b, s);
             return hipGetLastError();
         }
         const int64_t tiles = ceil_div(a.n, (int64_t)tile_rows<T>());
