@@ -6,6 +6,8 @@ bitwise; random inputs must match the extended-accumulation oracle within a
 normwise relative error of 1e-5 (s, c) / 1e-13 (d, z), and every component
 within the order-independent bound gamma_{n+2} * (|alpha||A||x| + |beta||y|).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -574,10 +576,11 @@ def test_gemv_short_matrix_kernels(prec):
 @pytest.mark.parametrize("prec", PRECS)
 def test_random_shapes_against_oracle(prec):
     """seeded random shapes, leading dimensions, offsets, increments and scalars for every
-    routine: whatever combination of kernels and edge cases they hit must match the oracle"""
-    rng = np.random.default_rng({"s": 11, "d": 12, "c": 13, "z": 14}[prec])
+    routine: whatever combination of kernels and edge cases they hit must match the oracle
+    (KMV_FUZZ_CASES / KMV_FUZZ_SEED in the environment lengthen or reseed the series)"""
+    rng = np.random.default_rng({"s": 11, "d": 12, "c": 13, "z": 14}[prec] + 100 * int(os.environ.get("KMV_FUZZ_SEED", "0")))
     incs = (1, 1, 1, 2, -1, 3, -2)
-    for case in range(24):
+    for case in range(int(os.environ.get("KMV_FUZZ_CASES", "24"))):
         m = int(rng.choice([1, 7, 64, 300, 1000, 2500]) + rng.integers(0, 130))
         n = int(rng.choice([1, 5, 96, 500, 1500, 3000]) + rng.integers(0, 130))
         off = int(rng.choice([0, 0, 1, 3, 16, 33]))
