@@ -2,6 +2,8 @@
 the reflectors, tau, e, the diagonal and W, on matrices that span several tiles, with ragged sizes, padded
 leading dimensions and sub-block pointers; the strict upper triangle is NaN and must stay unread and
 unwritten, the trailing columns must stay bit-unchanged."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -16,7 +18,8 @@ pytestmark = pytest.mark.gpu
 # normwise tolerance of a panel: nb columns that depend on each other, each a handful of length-n sums
 # nb dependent columns, each within the single-product bound (1e-5 / 1e-13): the errors add up along the chain,
 # typically like sqrt(nb) (8e-5 at nb = 64 in single precision); five and ten single-product tolerances
-TOL = {"s": 5e-5, "d": 1e-12}
+_SCALE = float(os.environ.get("KMV_TOL_SCALE", "1"))      # < 1 tightens the tolerances to show how much room the cases leave
+TOL = {"s": 5e-5 * _SCALE, "d": 1e-12 * _SCALE}
 
 
 def run_panel(prec, n, nb, lda, ldw, off=0, seed=0):
@@ -138,7 +141,7 @@ def test_panel_is_deterministic_and_capturable(prec):
         assert torch.equal(W[defined], ref[1][defined])
 
 
-TOLC = {"c": 5e-5, "z": 1e-12}
+TOLC = {"c": 5e-5 * _SCALE, "z": 1e-12 * _SCALE}
 
 
 @pytest.mark.parametrize("prec", "cz")
