@@ -14,6 +14,8 @@
 // applied in the same pass instead of a separate SCAL launch, Section 6.4);
 // row tiles start on the 128-byte boundary below the first element and the
 // leading slots are masked (Section 6.6) without a separate interface.
+// Strided batches run the same kernels with the member in the grid's third dimension; members with short
+// columns have a kernel of their own at the end of this file (one wave per member).
 #include "kmv_launch.hpp"
 
 namespace kmv {
