@@ -118,3 +118,71 @@ def gebrd_panel(A, nb, *, wide=True):
         x = tp * x
         X[i + 1:, i] = x
     return dict(A=W, d=d, e=e, tauq=tauq, taup=taup, X=X, Y=Y)
+
+
+def gebrd_panel_wide(A, nb, *, wide=True):
+    """The panel step for m < n (more columns than rows): the reduction is to LOWER bidiagonal form, with the
+    roles of rows and columns exchanged.  For i = 0 .. nb-1 (0 <= nb <= m), with the update A - V Y^H - X U^H of
+    the reflectors so far (V: column reflectors v_k, support rows k+1.., stored in A[k+1:, k]; U: row reflectors
+    u_k, support columns k.., stored conjugated in A[k, k:]):
+
+      1. row i up to date:      r = A[i, i:] - V[i, :i] Y[i:, :i]^H - X[i, :i] U^H[:i, i:]
+      2. row reflector from conj(r): beta = d_i, taup_i, u_i (one at column i); A[i, i:] = u_i^H
+      3. if i < m-1:
+           x = taup (A[i+1:, i:] u - V[i+1:, :i] (Y[i:, :i]^H u) - X[i+1:, :i] (U^H[:i, i:] u));   X[i+1:, i] = x
+           column i up to date:  c = A[i+1:, i] - V[i+1:, :i] conj(Y[i, :i]) - X[i+1:, :i+1] U^H[:i+1, i]
+           column reflector from c: beta = e_i, tauq_i, v_i (one at row i+1); A[i+1:, i] = v_i
+           y = tauq (A[i+1:, i+1:]^H v - Y[i+1:, :i] (V[i+1:, :i]^H v) - U[i+1:, :i+1] (X[i+1:, :i+1]^H v));  Y[i+1:, i] = y
+
+    so that the first nb rows and columns of Q^H A P are lower bidiagonal (diagonal d, subdiagonal e) and
+    A - V Y^H - X U^H on the trailing block equals Q^H A P there.  The last row of the matrix has no column
+    reflector (e = tauq = 0).  Returns the same dictionary as ``gebrd_panel``; X is m x nb, Y is n x nb.
+    """
+    A = np.asarray(A)
+    m, n = A.shape
+    assert m < n and 0 <= nb <= m
+    dt = _WIDE[A.dtype] if wide else A.dtype.type
+    rt = np.real(dt(0)).dtype.type
+    W = A.astype(dt).copy()
+    X = np.zeros((m, nb), dtype=dt)
+    Y = np.zeros((n, nb), dtype=dt)
+    d = np.zeros(nb, dtype=rt)
+    e = np.zeros(nb, dtype=rt)
+    tauq = np.zeros(nb, dtype=dt)
+    taup = np.zeros(nb, dtype=dt)
+    H = lambda M: M.conj().T
+    for i in range(nb):
+        # 1. row i (W[i, :i] holds the entries of v_0 .. v_{i-1} in row i; W[:i, i:] the rows u_k^H)
+        r = W[i, i:].copy()
+        if i:
+            r = r - Y[i:, :i].conj() @ W[i, :i] - X[i, :i] @ W[:i, i:]
+        # 2. row reflector
+        beta, tp, tail = _reflector(r[0].conj(), r[1:].conj().copy(), dt)
+        d[i], taup[i] = beta, tp
+        u = np.concatenate(([dt(1)], tail))
+        W[i, i:] = u.conj()
+        if i >= m - 1:
+            continue
+        # 3. x
+        x = W[i + 1:, i:] @ u
+        if i:
+            x = x - W[i + 1:, :i] @ (H(Y[i:, :i]) @ u) - X[i + 1:, :i] @ (W[:i, i:] @ u)
+        x = tp * x
+        X[i + 1:, i] = x
+        # column i
+        c = W[i + 1:, i].copy()
+        if i:
+            c = c - W[i + 1:, :i] @ Y[i, :i].conj()
+        c = c - X[i + 1:, :i + 1] @ W[:i + 1, i]
+        beta, tq, tail = _reflector(c[0], c[1:].copy(), dt)
+        e[i], tauq[i] = beta, tq
+        v = np.concatenate(([dt(1)], tail))
+        W[i + 1:, i] = v
+        # y
+        y = H(W[i + 1:, i + 1:]) @ v
+        if i:
+            y = y - Y[i + 1:, :i] @ (H(W[i + 1:, :i]) @ v)
+        y = y - H(W[:i + 1, i + 1:]) @ (H(X[i + 1:, :i + 1]) @ v)
+        y = tq * y
+        Y[i + 1:, i] = y
+    return dict(A=W, d=d, e=e, tauq=tauq, taup=taup, X=X, Y=Y)

@@ -180,3 +180,80 @@ def test_complex_panel_reduces_to_the_real_one_on_real_data():
         got = np.asarray(rc[key], dtype=np.complex128)
         assert np.max(np.abs(got.imag)) == 0
         assert np.allclose(got.real, np.asarray(rr[key], dtype=np.float64), atol=1e-14)
+
+
+# ---- more columns than rows: lower bidiagonal form
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64, np.complex64, np.complex128])
+@pytest.mark.parametrize("m,n,nb", [(1, 2, 1), (2, 3, 2), (3, 5, 2), (40, 41, 8), (61, 97, 32), (33, 50, 33)])
+def test_wide_matrices_lower_bidiagonal_identities(dtype, m, n, nb):
+    rng = np.random.default_rng(m * 1000 + n * 10 + nb + 11)
+    A0 = rng.uniform(-1, 1, (m, n))
+    if np.issubdtype(dtype, np.complexfloating):
+        A0 = A0 + 1j * rng.uniform(-1, 1, (m, n))
+    A0 = A0.astype(dtype)
+    r = go.gebrd_panel_wide(A0, nb)
+    Aw = A0.astype(np.complex128)
+    out = np.asarray(r["A"], dtype=np.complex128)
+    tauq = np.asarray(r["tauq"], dtype=np.complex128)
+    taup = np.asarray(r["taup"], dtype=np.complex128)
+    d = np.asarray(r["d"], dtype=np.float64)
+    e = np.asarray(r["e"], dtype=np.float64)
+    X = np.asarray(r["X"], dtype=np.complex128)
+    Y = np.asarray(r["Y"], dtype=np.complex128)
+    assert np.isrealobj(r["d"]) and np.isrealobj(r["e"])
+    V = np.zeros((m, nb), dtype=np.complex128)
+    U = np.zeros((n, nb), dtype=np.complex128)
+    Q, P = np.eye(m, dtype=np.complex128), np.eye(n, dtype=np.complex128)
+    for i in range(nb):
+        U[i:, i] = out[i, i:].conj()             # the row stores u^H
+        assert U[i, i] == 1.0
+        if i < m - 1:
+            V[i + 1:, i] = out[i + 1:, i]
+            assert V[i + 1, i] == 1.0
+        Gi = np.eye(n) - taup[i] * np.outer(U[:, i], U[:, i].conj())
+        Hi = np.eye(m) - tauq[i] * np.outer(V[:, i], V[:, i].conj())
+        assert np.allclose(Gi.conj().T @ Gi, np.eye(n), atol=1e-13) and np.allclose(Hi.conj().T @ Hi, np.eye(m), atol=1e-13)
+        P, Q = P @ Gi, Q @ Hi
+    B = Q.conj().T @ Aw @ P
+    scale = np.linalg.norm(Aw)
+    for i in range(nb):
+        assert abs(B[i, i] - d[i]) < 1e-13 * scale, "diagonal is not the real d"
+        assert np.all(np.abs(B[i, i + 1:]) < 1e-13 * scale), "row not reduced"
+        if i < m - 1:
+            assert abs(B[i + 1, i] - e[i]) < 1e-13 * scale, "subdiagonal is not the real e"
+            assert np.all(np.abs(B[i + 2:, i]) < 1e-13 * scale), "column not reduced"
+        assert np.all(np.abs(B[:i, i]) < 1e-13 * scale)
+    upd = Aw - V @ Y.conj().T - X @ U.conj().T
+    assert np.allclose(upd[nb:, nb:], B[nb:, nb:], atol=1e-12 * scale)
+    assert np.array_equal(out[nb:, nb:], Aw[nb:, nb:])
+
+
+def test_wide_panel_is_the_tall_panel_of_the_conjugate_transpose():
+    """lower bidiagonal reduction of A (m < n) = upper bidiagonal reduction of A^H, with the roles of the
+    row and the column reflectors (and of X and Y) exchanged"""
+    rng = np.random.default_rng(21)
+    m, n, nb = 30, 45, 9
+    A0 = rng.uniform(-1, 1, (m, n)) + 1j * rng.uniform(-1, 1, (m, n))
+    w, t = go.gebrd_panel_wide(A0, nb), go.gebrd_panel(A0.conj().T.copy(), nb)
+    c = lambda a: np.asarray(a, dtype=np.complex128)
+    assert np.allclose(c(w["d"]), c(t["d"]), atol=1e-13) and np.allclose(c(w["e"]), c(t["e"]), atol=1e-13)
+    # row i of A is the conjugate of column i of A^H, and the row reflector is generated from the conjugated row:
+    # the same vector, the same tau; what differs is the storage (a row holds u^H, a column holds v)
+    assert np.allclose(c(w["taup"]), c(t["tauq"]), atol=1e-13) and np.allclose(c(w["tauq"]), c(t["taup"]), atol=1e-13)
+    wa, ta = c(w["A"]), c(t["A"])
+    for i in range(nb):
+        assert np.allclose(wa[i, i:], ta[i:, i].conj(), atol=1e-13)
+        assert np.allclose(wa[i + 1:, i], ta[i, i + 1:].conj(), atol=1e-13)
+    assert np.allclose(c(w["X"]), c(t["Y"]), atol=1e-12) and np.allclose(c(w["Y"]), c(t["X"]), atol=1e-12)
+
+
+def test_wide_full_reduction_keeps_singular_values():
+    rng = np.random.default_rng(22)
+    m, n = 30, 45
+    A0 = rng.uniform(-1, 1, (m, n))
+    r = go.gebrd_panel_wide(A0, m)
+    d = np.asarray(r["d"], dtype=np.float64)
+    e = np.asarray(r["e"], dtype=np.float64)[: m - 1]
+    B = np.diag(d) + np.diag(e, -1)
+    assert np.allclose(np.linalg.svd(B, compute_uv=False), np.linalg.svd(A0, compute_uv=False), atol=1e-12)
