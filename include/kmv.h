@@ -273,8 +273,8 @@ size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
 
 /* ---- Panel step of the bidiagonal reduction (Section 10: GEMV on the trailing
  * block and on the accumulated panels, on sub-blocks at arbitrary row and
- * column offsets, with strided vectors).  m >= n, upper bidiagonal; the
- * description is for s and d, the complex forms follow it.  For the first nb columns and rows of the m x n matrix A
+ * column offsets, with strided vectors).  The description is for m >= n
+ * (upper bidiagonal) in s and d; m < n and the complex forms follow it.  For the first nb columns and rows of the m x n matrix A
  * (device): column i is brought up to date, a reflector H_i = I - tauq_i v_i
  * v_i^T annihilates it below the diagonal, y_i is formed from the trailing
  * block (transposed product); row i is brought up to date, a reflector G_i =
@@ -289,9 +289,16 @@ size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
  * beyond the panel are not modified.  The last column of the matrix has no
  * row reflector (e = taup = 0).  Norms are formed without rescaling.
  * Only enqueues kernels on `stream` (about twenty per column), capturable.
+ * m < n reduces to LOWER bidiagonal form with the roles of rows and columns
+ * exchanged: row i is brought up to date and reflected first (G_i annihilates
+ * A[i][i+1..n-1]; A[i][i..n-1] = u_i with A[i][i] = 1, d[i] the diagonal
+ * entry), x_i follows, then column i below the diagonal (H_i annihilates
+ * A[i+2..m-1][i]; A[i+1..m-1][i] = v_i with A[i+1][i] = 1, e[i] the
+ * subdiagonal entry) and y_i; X[i+1..m-1][i] = x_i, Y[i+1..n-1][i] = y_i; the
+ * last row of the matrix has no column reflector (e = tauq = 0).
  * Workspace: kmv_gebrd_panel_workspace_bytes(prec, m, n, nb), 256-byte
- * aligned.  Errors: negated argument number (m 1, n 2 (0 <= n <= m), nb 3
- * (0 <= nb <= n), lda 5, ldx 11, ldy 13), KMV_ERR_NULL, KMV_ERR_WORKSPACE, or
+ * aligned.  Errors: negated argument number (m 1, n 2, nb 3
+ * (0 <= nb <= min(m, n)), lda 5, ldx 11, ldy 13), KMV_ERR_NULL, KMV_ERR_WORKSPACE, or
  * the code of a failing launch (the columns before it are done). */
 int kmv_sgebrd_panel(int64_t m, int64_t n, int64_t nb, float* A, int64_t lda, float* d, float* e, float* tauq,
                      float* taup, float* X, int64_t ldx, float* Y, int64_t ldy, void* workspace,

@@ -476,10 +476,28 @@ template <class T> size_t short_rows_bytes(int64_t nb) {
 
 // the row copy plus the largest workspace any product of the bidiagonal panel asks for
 template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
-    if (m <= 0 || n <= 0 || nb <= 0 || m < n) return 0;
-    if (nb > n) nb = n;
+    if (m <= 0 || n <= 0 || nb <= 0) return 0;
+    const int64_t mn = m < n ? m : n;
+    if (nb > mn) nb = mn;
     const char p = Calls<T>::prec;
     size_t need = 0;
+    if (m < n) {     // lower bidiagonal: rows first
+        for (int64_t i = 0; i < nb; ++i) {
+            const int64_t mi = m - i - 1, ni = n - i;
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', ni, i));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', i, ni));
+            if (mi <= 0) continue;
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi, ni));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', ni, i));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi, i + 1));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', i, ni));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', mi, ni - 1));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', mi, i + 1));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', ni - 1, i));
+            need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', i + 1, ni - 1));
+        }
+        return row_bytes<T>(n) + short_rows_bytes<T>(nb) + need;
+    }
     for (int64_t i = 0; i < nb; ++i) {
         const int64_t mi = m - i, ni = n - i - 1;
         need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi, i));
@@ -496,7 +514,8 @@ template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
     return row_bytes<T>(n) + short_rows_bytes<T>(nb) + need;
 }
 
-// Panel step of the bidiagonal reduction (m >= n, upper bidiagonal): the published "labrd" step written
+// Panel step of the bidiagonal reduction (m >= n: upper bidiagonal; m < n: lower bidiagonal, see the branch
+// below): the published "labrd" step written
 // from its definition on top of the GEMV entry points.  Per column two products with the whole trailing
 // block (transposed from the left, plain from the right, the latter with a strided x: a row of A) and
 // eleven with the tall or wide panels of vectors accumulated so far, two reflectors and two scalings by
@@ -515,12 +534,12 @@ int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
     using R = typename Traits<T>::real;
     constexpr bool CPLX = Traits<T>::cplx;
     if (m < 0) return -1;
-    if (n < 0 || n > m) return -2;
-    if (nb < 0 || nb > n) return -3;
+    if (n < 0) return -2;
+    if (nb < 0 || nb > (m < n ? m : n)) return -3;
     if (lda < (m > 1 ? m : 1)) return -5;
     if (ldx < (m > 1 ? m : 1)) return -11;
     if (ldy < (n > 1 ? n : 1)) return -13;
-    if (n == 0 || nb == 0) return KMV_OK;
+    if (m == 0 || n == 0 || nb == 0) return KMV_OK;
     if (!A || !d || !e || !tauq || !taup || !X || !Y) return KMV_ERR_NULL;
     if (!ws || wsb < gebrd_workspace<T>(m, n, nb) || ((uintptr_t)ws % 256) != 0) return KMV_ERR_WORKSPACE;
     T* urow = static_cast<T*>(ws);            // row i right of the diagonal, contiguous
@@ -560,6 +579,75 @@ int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
         else
             hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, len, head, head + 1, (int64_t)1, beta, tau);
     };
+    if (m < n) {
+        // More columns than rows: lower bidiagonal form, the roles of rows and columns exchanged.  Row i is
+        // brought up to date and reflected first (in its contiguous, conjugated copy), x_i follows from the
+        // trailing block; then column i below the diagonal, its reflector (the one at row i+1) and y_i.
+        for (int64_t i = 0; i < nb; ++i) {
+            const int64_t mi = m - i - 1, ni = n - i;       // rows below row i, columns from column i on
+            const dim3 cgrid((unsigned)ceil_div(ni, (int64_t)256));
+            hipLaunchKernelGGL((strided_copy_kernel<T, CPLX>), cgrid, dim3(256), 0, s, ni, a_(i, i), lda, urow, (int64_t)1);
+            KMV_LAUNCHED();
+            if (i > 0) {
+                if constexpr (CPLX) {
+                    conj_row(i, a_(i, 0), lda, vrow);
+                    KMV_LAUNCHED();
+                    conj_row(i, x_(i, 0), ldx, xrow);
+                    KMV_LAUNCHED();
+                    KMV_GEMV('N', ni, i, &minus, y_(i, 0), ldy, vrow, (int64_t)1, &one, urow, (int64_t)1);
+                    KMV_GEMV('C', i, ni, &minus, a_(0, i), lda, xrow, (int64_t)1, &one, urow, (int64_t)1);
+                } else {
+                    KMV_GEMV('N', ni, i, &minus, y_(i, 0), ldy, a_(i, 0), lda, &one, urow, (int64_t)1);
+                    KMV_GEMV('T', i, ni, &minus, a_(0, i), lda, x_(i, 0), ldx, &one, urow, (int64_t)1);
+                }
+            }
+            reflector(ni, urow, d + i, taup + i);
+            KMV_LAUNCHED();
+            hipLaunchKernelGGL((strided_copy_kernel<T, CPLX>), cgrid, dim3(256), 0, s, ni, urow, (int64_t)1, a_(i, i), lda);
+            KMV_LAUNCHED();
+            if (mi <= 0) {     // last row of the matrix: no column reflector
+                hipLaunchKernelGGL((no_reflector_kernel<R, T>), dim3(1), dim3(1), 0, s, e + i, tauq + i);
+                KMV_LAUNCHED();
+                continue;
+            }
+            // x = taup * (trailing block u - corrections)
+            KMV_GEMV('N', mi, ni, &one, a_(i + 1, i), lda, urow, (int64_t)1, &zero, x_(i + 1, i), (int64_t)1);
+            if (i > 0) {
+                KMV_GEMV(TR, ni, i, &one, y_(i, 0), ldy, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
+                KMV_GEMV('N', mi, i, &minus, a_(i + 1, 0), lda, x_(0, i), (int64_t)1, &one, x_(i + 1, i), (int64_t)1);
+                KMV_GEMV('N', i, ni, &one, a_(0, i), lda, urow, (int64_t)1, &zero, x_(0, i), (int64_t)1);
+                KMV_GEMV('N', mi, i, &minus, x_(i + 1, 0), ldx, x_(0, i), (int64_t)1, &one, x_(i + 1, i), (int64_t)1);
+            }
+            hipLaunchKernelGGL((scale_kernel<T>), dim3((unsigned)ceil_div(mi, (int64_t)256)), dim3(256), 0, s, mi, taup + i,
+                               x_(i + 1, i));
+            KMV_LAUNCHED();
+            // column i below the diagonal catches up (x_i just computed takes part) and gets its reflector
+            if (i > 0) {
+                if constexpr (CPLX) {
+                    conj_row(i, y_(i, 0), ldy, yrow);
+                    KMV_LAUNCHED();
+                    KMV_GEMV('N', mi, i, &minus, a_(i + 1, 0), lda, yrow, (int64_t)1, &one, a_(i + 1, i), (int64_t)1);
+                } else {
+                    KMV_GEMV('N', mi, i, &minus, a_(i + 1, 0), lda, y_(i, 0), ldy, &one, a_(i + 1, i), (int64_t)1);
+                }
+            }
+            KMV_GEMV('N', mi, i + 1, &minus, x_(i + 1, 0), ldx, a_(0, i), (int64_t)1, &one, a_(i + 1, i), (int64_t)1);
+            reflector(mi, a_(i + 1, i), e + i, tauq + i);
+            KMV_LAUNCHED();
+            // y = tauq * (trailing block^H v - corrections)
+            KMV_GEMV(TR, mi, ni - 1, &one, a_(i + 1, i + 1), lda, a_(i + 1, i), (int64_t)1, &zero, y_(i + 1, i), (int64_t)1);
+            if (i > 0) {
+                KMV_GEMV(TR, mi, i, &one, a_(i + 1, 0), lda, a_(i + 1, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
+                KMV_GEMV('N', ni - 1, i, &minus, y_(i + 1, 0), ldy, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
+            }
+            KMV_GEMV(TR, mi, i + 1, &one, x_(i + 1, 0), ldx, a_(i + 1, i), (int64_t)1, &zero, y_(0, i), (int64_t)1);
+            KMV_GEMV(TR, i + 1, ni - 1, &minus, a_(0, i + 1), lda, y_(0, i), (int64_t)1, &one, y_(i + 1, i), (int64_t)1);
+            hipLaunchKernelGGL((scale_kernel<T>), dim3((unsigned)ceil_div(ni - 1, (int64_t)256)), dim3(256), 0, s, ni - 1,
+                               tauq + i, y_(i + 1, i));
+            KMV_LAUNCHED();
+        }
+        return KMV_OK;
+    }
     for (int64_t i = 0; i < nb; ++i) {
         const int64_t mi = m - i, ni = n - i - 1;
         if (i > 0) {   // column i catches up with the panels

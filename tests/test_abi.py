@@ -274,15 +274,16 @@ def test_gebrd_panel_argument_errors(prec):
         return f(m, n, nb, A, lda, DUMMY, DUMMY, DUMMY, DUMMY, X, ldx, DUMMY, ldy, workspace=NOWS, stream=0, check=False)
 
     assert call(m=-1) == -1
-    assert call(n=-1) == -2 and call(n=9) == -2            # m >= n only
-    assert call(nb=-1) == -3 and call(nb=7) == -3
+    assert call(n=-1) == -2
+    assert call(nb=-1) == -3 and call(nb=7) == -3 and call(m=5, n=9, lda=8, ldx=8, ldy=9, nb=6) == -3   # nb <= min(m, n)
+    assert call(m=5, n=9, ldy=9, nb=5) == kmv.ERR_WORKSPACE    # more columns than rows: lower bidiagonal form
     assert call(lda=7) == -5 and call(ldx=7) == -11 and call(ldy=5) == -13
     assert call(nb=0) == 0 and call(m=0, n=0, nb=0, lda=1, ldx=1, ldy=1) == 0
     assert call(A=None) == kmv.ERR_NULL and call(X=None) == kmv.ERR_NULL
     assert call() == kmv.ERR_WORKSPACE
     need = kmv.gebrd_panel_workspace_bytes(prec, 4096, 4096, 64)
     assert need >= kmv.gemv_workspace_bytes(prec, "T", 4096, 4095)
-    assert kmv.gebrd_panel_workspace_bytes("q", 64, 64, 8) == 0 and kmv.gebrd_panel_workspace_bytes(prec, 8, 9, 2) == 0
+    assert kmv.gebrd_panel_workspace_bytes("q", 64, 64, 8) == 0 and kmv.gebrd_panel_workspace_bytes(prec, 8, 9, 2) > 0
     if prec in "cz":      # room for the row copy and the three conjugated short rows besides the products' workspace
         esz = {"c": 8, "z": 16}[prec]
         assert need >= kmv.gemv_workspace_bytes(prec, "C", 4096, 4095) + (4096 + 3 * 64) * esz

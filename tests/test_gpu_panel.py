@@ -385,3 +385,57 @@ def test_upper_storage_panel_against_oracle(prec, n, nb, pad, off):
     if cplx:       # the diagonal before the panel keeps its real part and its (NaN) imaginary part
         for i in range(first):
             assert A1[i, i].real == A0[i, i].real and np.isnan(A1[i, i].imag)
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+@pytest.mark.parametrize("m,n,nb,pad,off", [(1, 2, 1, 0, 0), (2, 3, 2, 0, 0), (3, 5, 3, 1, 0), (100, 101, 16, 0, 0),
+                                            (500, 700, 32, 36, 0), (900, 1300, 24, 52, 17), (800, 900, 8, 3, 1)])
+def test_wide_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
+    """m < n: lower bidiagonal form (row reflectors first).  Reflector vectors, the real d and e, tauq, taup, X
+    and Y element by element; everything outside the first nb rows and columns bit-unchanged"""
+    k = kmv()
+    cplx = prec in "cz"
+    dt = wl.TORCH_DTYPES[prec]
+    rdt = {"s": torch.float32, "d": torch.float64, "c": torch.float32, "z": torch.float64}[prec]
+    lda, ldx, ldy = m + off + pad, m + pad // 2, n + pad // 3
+    parent = wl.matrix(prec, m + off, n + off, lda, seed=m + n + nb + 5, device=DEV)
+    before = parent.clone()
+    A = parent[off:, off:] if off else parent
+    nanv = float("nan")
+    X = torch.full((nb, ldx), nanv, dtype=dt, device=DEV)
+    Y = torch.full((nb, ldy), nanv, dtype=dt, device=DEV)
+    d, e = (torch.full((nb,), nanv, dtype=rdt, device=DEV) for _ in range(2))
+    tauq, taup = (torch.full((nb,), nanv, dtype=dt, device=DEV) for _ in range(2))
+    k.GEBRD_PANEL[prec](m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy)
+    torch.cuda.synchronize()
+    A0 = before[off:off + n, off:off + m].cpu().numpy().T.copy()
+    A1 = parent[off:off + n, off:off + m].cpu().numpy().T.copy()
+    want = go.gebrd_panel_wide(A0, nb)
+
+    def relc(got, ref):
+        ref = np.asarray(ref, dtype=np.complex128)
+        nrm = np.linalg.norm(ref)
+        return float(np.linalg.norm(np.asarray(got, dtype=np.complex128) - ref) / (nrm if nrm else 1.0))
+
+    tol = (TOLC if cplx else TOL)[prec]
+    panel = np.zeros((m, n), dtype=bool)
+    panel[:, :nb] = True
+    panel[:nb, :] = True
+    assert relc(A1[panel], np.asarray(want["A"])[panel]) <= tol
+    for name, got in (("d", d), ("e", e), ("tauq", tauq), ("taup", taup)):
+        assert relc(got.cpu().numpy(), want[name]) <= tol, name
+    Xh, Yh = X.cpu().numpy().T[:m], Y.cpu().numpy().T[:n]
+    dx = np.zeros((m, nb), dtype=bool)
+    dy = np.zeros((n, nb), dtype=bool)
+    for i in range(min(nb, m - 1)):
+        dx[i + 1:, i] = True
+        dy[i + 1:, i] = True
+    assert np.all(np.isfinite(np.asarray(Xh[dx], dtype=np.complex128).view(np.float64)))
+    assert np.all(np.isfinite(np.asarray(Yh[dy], dtype=np.complex128).view(np.float64)))
+    assert relc(Xh[dx], np.asarray(want["X"])[dx]) <= tol
+    assert relc(Yh[dy], np.asarray(want["Y"])[dy]) <= tol
+    pb, pa = before.cpu().numpy(), parent.cpu().numpy()
+    touched = np.zeros(pb.shape, dtype=bool)
+    touched[off:off + nb, off:off + m] = True
+    touched[off:off + n, off:off + nb] = True
+    assert np.array_equal(pb[~touched].view(np.uint8), pa[~touched].view(np.uint8)), "wrote outside the panel"
