@@ -287,3 +287,21 @@ def test_gebrd_panel_argument_errors(prec):
     if prec in "cz":      # room for the row copy and the three conjugated short rows besides the products' workspace
         esz = {"c": 8, "z": 16}[prec]
         assert need >= kmv.gemv_workspace_bytes(prec, "C", 4096, 4095) + (4096 + 3 * 64) * esz
+
+
+def test_plain_c_program_links_and_calls_the_library(tmp_path):
+    """the header is C99 and the symbols have C linkage: a C program built with gcc runs the host-only calls"""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_1410_1726_amd")
+    exe = str(tmp_path / "abi_check")
+    build = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(root, "include"),
+                            os.path.join(root, "tests", "c", "abi_check.c"), "-o", exe, "-L", libdir, "-lkmv",
+                            f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and run.stdout.strip().endswith("ok"), run.stdout + run.stderr
