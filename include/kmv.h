@@ -61,7 +61,7 @@
  * "_devscalars" forms (alpha, beta in device memory) - both also for the
  * complex symmetric product (kmv_csymv_*, kmv_zsymv_*); panel steps of the
  * tridiagonal and the bidiagonal reduction built on these calls; strided
- * batches; workspace sizes; the work partition; the bandwidth probe; tuning.
+ * batches; pointer-array batches; workspace sizes; the work partition; the bandwidth probe; tuning.
  *
  * Determinism: for fixed arguments (including the alignment of A modulo 128
  * bytes) and fixed tuning values the result is bitwise reproducible; partial
@@ -366,6 +366,52 @@ int kmv_csymv_strided_batched(char uplo, int64_t n, const kmv_complex64* alpha, 
 int kmv_zsymv_strided_batched(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* A, int64_t lda, int64_t strideA,
                               const kmv_complex128* x, int64_t incx, int64_t stridex, const kmv_complex128* beta, kmv_complex128* y,
                               int64_t incy, int64_t stridey, int64_t batch, void* stream);
+
+/* ---- Pointer-array batches: `batch` products of one shape; member b uses the
+ * matrix A[b], the vectors x[b] and y[b].  A, x and y are arrays of `batch`
+ * DEVICE pointers that themselves live in DEVICE memory (the kernels read
+ * them; the host never does, so the arrays may be filled by an earlier kernel
+ * on the stream).  For callers whose members do not lie at a constant stride;
+ * everything else as for the strided batches above: one launch per 65535
+ * members, single-launch kernels (in instances of their own that fetch the
+ * operand pointers from the arrays), no workspace, alpha and beta on the host,
+ * incx = 1, the outputs of two members must not overlap.  The members'
+ * alignment is not known at enqueue time: the tile grids start at row 0 and
+ * columns that are not 16-byte aligned are read with unaligned 16-byte loads.
+ * Errors: negated argument number (GEMV: trans 1, m 2, n 3, lda 6, incx 8,
+ * incy 11, batch 12; SYMV/HEMV: uplo 1, n 2, lda 5, incx 7, incy 10, batch
+ * 11), KMV_ERR_NULL (also for a NULL array; the pointers inside the arrays
+ * are not looked at), KMV_ERR_HIP + code. */
+int kmv_sgemv_batched(char trans, int64_t m, int64_t n, const float* alpha, const float* const* A, int64_t lda,
+                      const float* const* x, int64_t incx, const float* beta, float* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_dgemv_batched(char trans, int64_t m, int64_t n, const double* alpha, const double* const* A, int64_t lda,
+                      const double* const* x, int64_t incx, const double* beta, double* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_cgemv_batched(char trans, int64_t m, int64_t n, const kmv_complex64* alpha, const kmv_complex64* const* A, int64_t lda,
+                      const kmv_complex64* const* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_zgemv_batched(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, const kmv_complex128* const* A, int64_t lda,
+                      const kmv_complex128* const* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_ssymv_batched(char uplo, int64_t n, const float* alpha, const float* const* A, int64_t lda,
+                      const float* const* x, int64_t incx, const float* beta, float* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_dsymv_batched(char uplo, int64_t n, const double* alpha, const double* const* A, int64_t lda,
+                      const double* const* x, int64_t incx, const double* beta, double* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_chemv_batched(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* const* A, int64_t lda,
+                      const kmv_complex64* const* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_zhemv_batched(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* const* A, int64_t lda,
+                      const kmv_complex128* const* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_csymv_batched(char uplo, int64_t n, const kmv_complex64* alpha, const kmv_complex64* const* A, int64_t lda,
+                      const kmv_complex64* const* x, int64_t incx, const kmv_complex64* beta, kmv_complex64* const* y, int64_t incy,
+                      int64_t batch, void* stream);
+int kmv_zsymv_batched(char uplo, int64_t n, const kmv_complex128* alpha, const kmv_complex128* const* A, int64_t lda,
+                      const kmv_complex128* const* x, int64_t incx, const kmv_complex128* beta, kmv_complex128* const* y, int64_t incy,
+                      int64_t batch, void* stream);
 
 /* ---- Workspace sizes (bytes; an upper bound valid for every pointer
  * alignment, every increment and every tuning value).  prec is 's','d','c'

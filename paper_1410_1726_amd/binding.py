@@ -79,6 +79,14 @@ def _load() -> ctypes.CDLL:
         f.argtypes, f.restype = symv_b_args, ci
     for p_ in "cz":
         getattr(lib, f"kmv_{p_}symv_strided_batched").argtypes = symv_b_args
+    gemv_p_args = [ch, i64, i64, vp, vp, i64, vp, i64, vp, vp, i64, i64, vp]
+    symv_p_args = [ch, i64, vp, vp, i64, vp, i64, vp, vp, i64, i64, vp]
+    for p_ in "sdcz":
+        f = getattr(lib, f"kmv_{p_}gemv_batched")
+        f.argtypes, f.restype = gemv_p_args, ci
+    for name in ("ssymv", "dsymv", "chemv", "zhemv", "csymv", "zsymv"):
+        f = getattr(lib, f"kmv_{name}_batched")
+        f.argtypes, f.restype = symv_p_args, ci
     lib.kmv_gemv_workspace_bytes.argtypes, lib.kmv_gemv_workspace_bytes.restype = [ch, ch, i64, i64], sz
     lib.kmv_symv_workspace_bytes.argtypes, lib.kmv_symv_workspace_bytes.restype = [ch, ch, i64], sz
     lib.kmv_partition.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -372,6 +380,61 @@ def _symv_strided_batched(prec, complex_symmetric=False):
     return call
 
 
+def pointer_array(tensors_or_addresses, device=None) -> torch.Tensor:
+    """Device array of device addresses (int64) for the `_batched` calls: one entry per member, taken from
+    tensors (their `data_ptr()`) or given as integers."""
+    addrs = [t if isinstance(t, int) else t.data_ptr() for t in tensors_or_addresses]
+    if device is None:
+        device = next((t.device for t in tensors_or_addresses if not isinstance(t, int)), "cuda")
+    return torch.tensor(addrs, dtype=torch.int64, device=device)
+
+
+def _ptr_array(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    if t.dtype != torch.int64:
+        raise TypeError(f"expected an int64 tensor of device addresses, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError("the pointer arrays live in device memory")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _gemv_batched(prec):
+    def call(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, batch, stream=None, check=True):
+        rc = getattr(lib, f"kmv_{prec}gemv_batched")(
+            trans.encode(), m, n, _scalar(prec, alpha), _ptr_array(A), lda, _ptr_array(x), incx, _scalar(prec, beta),
+            _ptr_array(y), incy, batch, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(f"{prec}gemv_batched", rc)
+        return rc
+    call.__name__ = f"{prec}gemv_batched"
+    call.__doc__ = "`batch` GEMVs of one shape; A, x, y are int64 device tensors of device addresses (see pointer_array)."
+    return call
+
+
+def _symv_batched(prec, complex_symmetric=False):
+    name = f"{prec}{'hemv' if prec in 'cz' and not complex_symmetric else 'symv'}_batched"
+
+    def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, batch, stream=None, check=True):
+        rc = getattr(lib, f"kmv_{name}")(
+            uplo.encode(), n, _scalar(prec, alpha), _ptr_array(A), lda, _ptr_array(x), incx, _scalar(prec, beta),
+            _ptr_array(y), incy, batch, _stream(stream))
+        if check and rc != 0:
+            raise KmvError(name, rc)
+        return rc
+    call.__name__ = name
+    call.__doc__ = "`batch` SYMV / HEMV products of one shape; A, x, y are int64 device tensors of device addresses."
+    return call
+
+
+GEMV_BATCHED = {p_: _gemv_batched(p_) for p_ in "sdcz"}
+SYMV_BATCHED = {p_: _symv_batched(p_) for p_ in "sdcz"}          # HEMV for the complex precisions
+CSYMV_BATCHED = {p_: _symv_batched(p_, True) for p_ in "cz"}
+sgemv_batched, dgemv_batched, cgemv_batched, zgemv_batched = (GEMV_BATCHED[p_] for p_ in "sdcz")
+ssymv_batched, dsymv_batched, chemv_batched, zhemv_batched = (SYMV_BATCHED[p_] for p_ in "sdcz")
+csymv_batched, zsymv_batched = (CSYMV_BATCHED[p_] for p_ in "cz")
 GEMV_STRIDED_BATCHED = {p_: _gemv_strided_batched(p_) for p_ in "sdcz"}
 SYMV_STRIDED_BATCHED = {p_: _symv_strided_batched(p_) for p_ in "sdcz"}
 sgemv_strided_batched, dgemv_strided_batched, cgemv_strided_batched, zgemv_strided_batched = (

@@ -258,6 +258,105 @@ int symv_batched_entry(bool herm, char uplo, int64_t n, const T* alpha, const T*
     return KMV_OK;
 }
 
+// Pointer-array batches: member b uses A[b], x[b], y[b], arrays of device pointers in device memory (they are
+// read by the kernels, never by the host).  The same single-launch kernels as for strided batches, in
+// instances of their own that fetch the operand pointers from the arrays; the members' alignment is unknown,
+// so the tile grids start at row 0.
+inline const void* some_aligned_address() { return reinterpret_cast<const void*>(uintptr_t(WS_ALIGN)); }
+
+template <class T>
+int gemv_ptr_batched_entry(char trans, int64_t m, int64_t n, const T* alpha, const T* const* A, int64_t lda,
+                           const T* const* x, int64_t incx, const T* beta, T* const* y, int64_t incy, int64_t batch,
+                           void* stream) {
+    const bool notrans = (trans == 'N' || trans == 'n');
+    const bool tr = (trans == 'T' || trans == 't');
+    const bool ct = (trans == 'C' || trans == 'c');
+    if (!notrans && !tr && !ct) return -1;
+    if (m < 0) return -2;
+    if (n < 0) return -3;
+    if (lda < (m > 1 ? m : 1)) return -6;
+    if (incx != 1) return -8;
+    if (incy == 0) return -11;
+    if (batch < 0) return -12;
+    if (!alpha || !beta) return KMV_ERR_NULL;
+    const T al = *alpha, be = *beta;
+    if (m == 0 || n == 0 || batch == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    if (!y || (!is_zero(al) && (!A || !x))) return KMV_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t leny = notrans ? m : n;
+    GemvArgs<T> a;
+    a.m = m; a.n = n; a.lda = lda;
+    a.A = nullptr; a.x = nullptr; a.y = nullptr;
+    a.incy = incy; a.alpha = al; a.beta = be;
+    a.partial = nullptr;
+    a.y_shift = incy < 0 ? (1 - leny) * incy : 0;
+    for (int64_t b0 = 0; b0 < batch; b0 += MAX_GRID_BATCH) {
+        const int64_t nb = batch - b0 < MAX_GRID_BATCH ? batch - b0 : MAX_GRID_BATCH;
+        if (is_zero(al)) {
+            const hipError_t e = launch_scal_ptrs<T>(leny, be, y + b0, a.y_shift, incy, s, nb);
+            if (e != hipSuccess) return hip_code(e);
+            continue;
+        }
+        a.A_ptrs = A + b0; a.x_ptrs = x + b0; a.y_ptrs = y + b0;
+        if (m >= Traits<T>::VEC && m <= gemv_tiny_rows<T>(notrans)) {
+            const hipError_t e = launch_gemv_tiny<T>(a, notrans ? 0 : (ct ? 2 : 1), s, nb);
+            if (e != hipSuccess) return hip_code(e);
+            continue;
+        }
+        GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, some_aligned_address(), lda);
+        plan.shift = 0;
+        plan.ntiles = ceil_div(m, (int64_t)tile_rows<T>());
+        plan.splits = 1;
+        plan.short_form = (!notrans && plan.ntiles <= 2) ? 1 : 0;
+        plan.row_tiles = 1;
+        a.plan = plan;
+        const hipError_t e = notrans ? launch_gemv_n<T>(a, s, nb) : launch_gemv_t<T>(a, ct, s, nb);
+        if (e != hipSuccess) return hip_code(e);
+    }
+    return KMV_OK;
+}
+
+template <class T>
+int symv_ptr_batched_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* const* A, int64_t lda,
+                           const T* const* x, int64_t incx, const T* beta, T* const* y, int64_t incy, int64_t batch,
+                           void* stream) {
+    const bool lower = (uplo == 'L' || uplo == 'l');
+    const bool upper = (uplo == 'U' || uplo == 'u');
+    if (!lower && !upper) return -1;
+    if (n < 0) return -2;
+    if (lda < (n > 1 ? n : 1)) return -5;
+    if (incx != 1) return -7;
+    if (incy == 0) return -10;
+    if (batch < 0) return -11;
+    if (!alpha || !beta) return KMV_ERR_NULL;
+    const T al = *alpha, be = *beta;
+    if (n == 0 || batch == 0 || (is_zero(al) && is_one(be))) return KMV_OK;
+    if (!y || (!is_zero(al) && (!A || !x))) return KMV_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    SymvArgs<T> a;
+    a.n = n; a.lda = lda;
+    a.A = nullptr; a.x = nullptr; a.y = nullptr;
+    a.incy = incy; a.alpha = al; a.beta = be;
+    a.wsn = nullptr; a.wst = nullptr; a.wtab = nullptr;
+    a.y_shift = incy < 0 ? (1 - n) * incy : 0;
+    for (int64_t b0 = 0; b0 < batch; b0 += MAX_GRID_BATCH) {
+        const int64_t nb = batch - b0 < MAX_GRID_BATCH ? batch - b0 : MAX_GRID_BATCH;
+        if (is_zero(al)) {
+            const hipError_t e = launch_scal_ptrs<T>(n, be, y + b0, a.y_shift, incy, s, nb);
+            if (e != hipSuccess) return hip_code(e);
+            continue;
+        }
+        a.A_ptrs = A + b0; a.x_ptrs = x + b0; a.y_ptrs = y + b0;
+        SymvPlan<T> plan = plan_symv<T>(lower, n, some_aligned_address(), lda);
+        plan.shift = 0;
+        plan.variant = n <= member_rows<T>() ? 4 : 3;
+        a.plan = plan;
+        const hipError_t e = launch_symv<T>(a, lower, herm, s, nb);
+        if (e != hipSuccess) return hip_code(e);
+    }
+    return KMV_OK;
+}
+
 template <class T> size_t gemv_ws(char trans, int64_t m, int64_t n) {
     const bool notrans = (trans == 'N' || trans == 'n');
     if (m <= 0 || n <= 0) return 0;   // an empty product returns before it would use a workspace
@@ -429,6 +528,36 @@ KMV_SYMV_BATCHED(kmv_zhemv_strided_batched, kmv_complex128, cf64, true)
 KMV_SYMV_BATCHED(kmv_csymv_strided_batched, kmv_complex64, cf32, false)
 KMV_SYMV_BATCHED(kmv_zsymv_strided_batched, kmv_complex128, cf64, false)
 #undef KMV_SYMV_BATCHED
+
+// pointer-array batches
+#define KMV_GEMV_PTR_BATCHED(NAME, CT, T)                                                                         \
+    int NAME(char trans, int64_t m, int64_t n, const CT* alpha, const CT* const* A, int64_t lda,                  \
+             const CT* const* x, int64_t incx, const CT* beta, CT* const* y, int64_t incy, int64_t batch,         \
+             void* stream) {                                                                                      \
+        return gemv_ptr_batched_entry<T>(trans, m, n, (const T*)alpha, (const T* const*)A, lda,                   \
+                                         (const T* const*)x, incx, (const T*)beta, (T* const*)y, incy, batch,     \
+                                         stream);                                                                 \
+    }
+KMV_GEMV_PTR_BATCHED(kmv_sgemv_batched, float, float)
+KMV_GEMV_PTR_BATCHED(kmv_dgemv_batched, double, double)
+KMV_GEMV_PTR_BATCHED(kmv_cgemv_batched, kmv_complex64, cf32)
+KMV_GEMV_PTR_BATCHED(kmv_zgemv_batched, kmv_complex128, cf64)
+#undef KMV_GEMV_PTR_BATCHED
+
+#define KMV_SYMV_PTR_BATCHED(NAME, CT, T, HERM)                                                                   \
+    int NAME(char uplo, int64_t n, const CT* alpha, const CT* const* A, int64_t lda, const CT* const* x,          \
+             int64_t incx, const CT* beta, CT* const* y, int64_t incy, int64_t batch, void* stream) {             \
+        return symv_ptr_batched_entry<T>(HERM, uplo, n, (const T*)alpha, (const T* const*)A, lda,                 \
+                                         (const T* const*)x, incx, (const T*)beta, (T* const*)y, incy, batch,     \
+                                         stream);                                                                 \
+    }
+KMV_SYMV_PTR_BATCHED(kmv_ssymv_batched, float, float, false)
+KMV_SYMV_PTR_BATCHED(kmv_dsymv_batched, double, double, false)
+KMV_SYMV_PTR_BATCHED(kmv_chemv_batched, kmv_complex64, cf32, true)
+KMV_SYMV_PTR_BATCHED(kmv_zhemv_batched, kmv_complex128, cf64, true)
+KMV_SYMV_PTR_BATCHED(kmv_csymv_batched, kmv_complex64, cf32, false)
+KMV_SYMV_PTR_BATCHED(kmv_zsymv_batched, kmv_complex128, cf64, false)
+#undef KMV_SYMV_PTR_BATCHED
 
 size_t kmv_gemv_workspace_bytes(char prec, char trans, int64_t m, int64_t n) {
     switch (prec) {

@@ -20,6 +20,15 @@ template <class T> __global__ void scal_kernel(int64_t len, T beta, T* y, int64_
     }
 }
 
+// the same for the members of a pointer-array batch: member blockIdx.y scales y_ptrs[blockIdx.y] + shift
+template <class T> __global__ void scal_ptrs_kernel(int64_t len, T beta, T* const* y_ptrs, int64_t shift, int64_t incy) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < len) {
+        T* yp = y_ptrs[blockIdx.y] + shift + k * incy;
+        *yp = is_zero(beta) ? zero_of<T>() : mul_of(beta, *yp);
+    }
+}
+
 // blockDim = 256 = 32 outputs x 8 groups: group g adds the partial vectors
 // g, g+8, ... in ascending order, the eight group sums meet in LDS and are
 // added in group order, so the result does not depend on scheduling.
@@ -63,6 +72,14 @@ hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s, i
     return hipGetLastError();
 }
 template <class T>
+hipError_t launch_scal_ptrs(int64_t len, T beta, T* const* y_ptrs, int64_t shift, int64_t incy, hipStream_t s, int64_t batch) {
+    if (len <= 0 || batch <= 0) return hipSuccess;
+    if (batch > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((scal_ptrs_kernel<T>), dim3((unsigned)ceil_div(len, 256), (unsigned)batch), dim3(256), 0, s, len, beta,
+                       y_ptrs, shift, incy);
+    return hipGetLastError();
+}
+template <class T>
 hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off, int64_t len, T alpha, T beta,
                          const T* alpha_dev, const T* beta_dev, T* y, int64_t incy, hipStream_t s) {
     if (len <= 0) return hipSuccess;
@@ -74,6 +91,7 @@ hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64
 #define KMV_INSTANTIATE_AUX(T)                                                                              \
     template hipError_t launch_pack<T>(const T*, int64_t, int64_t, T*, hipStream_t);                        \
     template hipError_t launch_scal<T>(int64_t, T, T*, int64_t, hipStream_t, int64_t, int64_t);             \
+    template hipError_t launch_scal_ptrs<T>(int64_t, T, T* const*, int64_t, int64_t, hipStream_t, int64_t); \
     template hipError_t launch_reduce<T>(const T*, int64_t, int64_t, int64_t, int64_t, T, T, const T*, const T*, T*, \
                                          int64_t, hipStream_t);
 KMV_INSTANTIATE_AUX(float)

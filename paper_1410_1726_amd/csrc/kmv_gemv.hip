@@ -114,7 +114,7 @@ __device__ __forceinline__ void gemv_n_few_rows(const GemvArgs<T>& a, const int6
     }
 }
 
-template <class T, int NW, int U, int RT>
+template <class T, int NW, int U, int RT, bool PTRS = false>
 __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
@@ -124,9 +124,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     // the rows and differ in the columns), grid.y = block of row tiles
     const int64_t tbase = (int64_t)blockIdx.y * (NW * RT) + w;   // tiles tbase + NW*t, t < RT
     if (tbase >= a.plan.ntiles) return;
-    a.A += (int64_t)blockIdx.z * a.batch_A;   // member of a strided batch (all zero otherwise)
-    a.x += (int64_t)blockIdx.z * a.batch_x;
-    a.y += (int64_t)blockIdx.z * a.batch_y;
+    select_member<PTRS>(a, blockIdx.z);   // member of a batch (strides all zero for a single product)
 
     int64_t cw, c0;
     partition(a.n, a.plan.splits, blockIdx.x, cw, c0);
@@ -230,7 +228,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_short_kernel(GemvArgs<T> a) 
 // step across the waves at the very end.
 // WCOLS (short matrices, a few row tiles only): every wave owns NC columns of its
 // own and walks all tiles of the split alone; nothing crosses waves.
-template <class T, bool CONJ, int NC, int NW_, bool WCOLS>
+template <class T, bool CONJ, int NC, int NW_, bool WCOLS, bool PTRS = false>
 __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
@@ -242,9 +240,8 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     if (WCOLS && j0 >= a.n) return;   // a whole wave past the last column (no barrier in this form)
     const int64_t ntiles = a.plan.ntiles;
     const int shift = a.plan.shift;
-    a.A += (int64_t)blockIdx.z * a.batch_A;   // member of a strided batch (all zero otherwise)
-    a.y += (int64_t)blockIdx.z * a.batch_y;
-    const T* __restrict__ x = a.x + (int64_t)blockIdx.z * a.batch_x;
+    select_member<PTRS>(a, blockIdx.z);   // member of a batch (strides all zero for a single product)
+    const T* __restrict__ x = a.x;
 
     int64_t tw, ts;
     partition(ntiles, a.plan.splits, blockIdx.y, tw, ts);
@@ -550,6 +547,11 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s,
     const int64_t rt = a.plan.row_tiles;
     const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt), (unsigned)batch);
     const dim3 block(GN_NW * WAVE);
+    if (a.A_ptrs) {     // pointer-array batch: one instance (one row tile per wave, no column splits)
+        if (rt != 1 || a.plan.splits != 1) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS, 1, true>), grid, block, 0, s, a);
+        return hipGetLastError();
+    }
     if (rt == 1) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS, 1>), grid, block, 0, s, a);
     else if (rt == 2) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS / 2, 2>), grid, block, 0, s, a);
     else if (rt == 4) hipLaunchKernelGGL((gemv_n_kernel<T, GN_NW, GN_LOADS / 4, 4>), grid, block, 0, s, a);
@@ -561,6 +563,20 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s,
 
 template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s, int64_t batch) {
     if (batch < 1 || batch > 65535 || (batch > 1 && a.plan.splits != 1)) return hipErrorInvalidValue;
+    if (a.A_ptrs) {     // pointer-array batch: the instances without row splits
+        if (a.plan.splits != 1) return hipErrorInvalidValue;
+        const bool cj = conj && Traits<T>::cplx;
+        if (a.plan.short_form) {
+            const dim3 grid((unsigned)ceil_div(a.n, GT_NC * GT_NW), 1, (unsigned)batch);
+            if (cj) hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, true, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+            else hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, true, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        } else {
+            const dim3 grid((unsigned)ceil_div(a.n, GT_NC), 1, (unsigned)batch);
+            if (cj) hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+            else hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, false, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        }
+        return hipGetLastError();
+    }
     if (a.plan.short_form) {
         const dim3 grid((unsigned)ceil_div(a.n, GT_NC * GT_NW), (unsigned)a.plan.splits, (unsigned)batch);
         if (conj && Traits<T>::cplx)
@@ -588,7 +604,7 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
 // the column (DPP) and lane 0 of the group writes y_j.  No LDS, no barrier, loads three column groups ahead;
 // a lane whose rows straddle the last row loads at m - VEC and moves the elements into place (needs m >= VEC).
 constexpr int GTINY_NW = 4;   // members (waves) per workgroup
-template <class T, int MODE, int L>   // MODE 0: N, 1: T, 2: C
+template <class T, int MODE, int L, bool PTRS>   // MODE 0: N, 1: T, 2: C
 __global__ __launch_bounds__(GTINY_NW * WAVE) void gemv_tiny_kernel(GemvArgs<T> a, int batch) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int CPL = WAVE / L;
@@ -598,9 +614,10 @@ __global__ __launch_bounds__(GTINY_NW * WAVE) void gemv_tiny_kernel(GemvArgs<T> 
     if (member >= batch) return;     // the whole wave leaves; nothing below waits for another wave
     const int m = (int)a.m, n = (int)a.n;
     const int64_t lda = a.lda;
-    const T* __restrict__ x = a.x + (int64_t)member * a.batch_x;
-    const T* __restrict__ A = a.A + (int64_t)member * a.batch_A;
-    T* y = a.y + (int64_t)member * a.batch_y;
+    select_member<PTRS>(a, member);
+    const T* __restrict__ x = a.x;
+    const T* __restrict__ A = a.A;
+    T* y = a.y;
     const int sub = lane % L, cl = lane / L;
     const int r = sub * VEC;                               // first row of this lane
     const int rc = r + VEC <= m ? r : m - VEC;             // where its vector is loaded (m >= VEC)
@@ -672,23 +689,28 @@ __global__ __launch_bounds__(GTINY_NW * WAVE) void gemv_tiny_kernel(GemvArgs<T> 
     }
 }
 
-template <class T, int MODE>
+template <class T, int MODE, bool PTRS>
 void launch_gemv_tiny_mode(const GemvArgs<T>& a, hipStream_t s, int batch) {
     constexpr int VEC = Traits<T>::VEC;
     const dim3 grid((unsigned)ceil_div((int64_t)batch, (int64_t)GTINY_NW)), block(GTINY_NW * WAVE);
-    if (a.m <= 8 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 8>), grid, block, 0, s, a, batch);
-    else if (a.m <= 16 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 16>), grid, block, 0, s, a, batch);
-    else if (a.m <= 32 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 32>), grid, block, 0, s, a, batch);
-    else hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 64>), grid, block, 0, s, a, batch);
+    if (a.m <= 8 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 8, PTRS>), grid, block, 0, s, a, batch);
+    else if (a.m <= 16 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 16, PTRS>), grid, block, 0, s, a, batch);
+    else if (a.m <= 32 * VEC) hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 32, PTRS>), grid, block, 0, s, a, batch);
+    else hipLaunchKernelGGL((gemv_tiny_kernel<T, MODE, 64, PTRS>), grid, block, 0, s, a, batch);
+}
+template <class T, bool PTRS>
+void launch_gemv_tiny_ptrs(const GemvArgs<T>& a, int mode, hipStream_t s, int batch) {
+    if (mode == 0) launch_gemv_tiny_mode<T, 0, PTRS>(a, s, batch);
+    else if (mode == 2 && Traits<T>::cplx) launch_gemv_tiny_mode<T, 2, PTRS>(a, s, batch);
+    else launch_gemv_tiny_mode<T, 1, PTRS>(a, s, batch);
 }
 
 // mode 0: N, 1: T, 2: C (complex T only).  Requires VEC <= m <= one row tile, n >= 1, batch <= 65535.
 template <class T> hipError_t launch_gemv_tiny(const GemvArgs<T>& a, int mode, hipStream_t s, int64_t batch) {
     constexpr int VEC = Traits<T>::VEC;
     if (batch < 1 || batch > 65535 || a.m < VEC || a.m > WAVE * VEC || a.n < 1 || a.n > (int64_t)1 << 30) return hipErrorInvalidValue;
-    if (mode == 0) launch_gemv_tiny_mode<T, 0>(a, s, (int)batch);
-    else if (mode == 2 && Traits<T>::cplx) launch_gemv_tiny_mode<T, 2>(a, s, (int)batch);
-    else launch_gemv_tiny_mode<T, 1>(a, s, (int)batch);
+    if (a.A_ptrs) launch_gemv_tiny_ptrs<T, true>(a, mode, s, (int)batch);
+    else launch_gemv_tiny_ptrs<T, false>(a, mode, s, (int)batch);
     return hipGetLastError();
 }
 

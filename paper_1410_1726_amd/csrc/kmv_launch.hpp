@@ -91,6 +91,12 @@ template <class T> struct GemvArgs {
     // strided batches: workgroups with blockIdx.z = b work on A + b*batch_A, x + b*batch_x, y + b*batch_y
     // (elements); all zero for a single product
     int64_t batch_A = 0, batch_x = 0, batch_y = 0;
+    // pointer-array batches (kernel instances with PTRS): member b works on A_ptrs[b], x_ptrs[b] and
+    // y_ptrs[b] + y_shift (the shift moves the base for incy < 0); arrays of device pointers in device memory
+    const T* const* A_ptrs = nullptr;
+    const T* const* x_ptrs = nullptr;
+    T* const* y_ptrs = nullptr;
+    int64_t y_shift = 0;
     T* partial;       // [splits][part_stride]
     GemvPlan<T> plan;
 };
@@ -141,11 +147,28 @@ template <class T> struct SymvArgs {
     // strided batches: workgroups with blockIdx.z = b work on A + b*batch_A, x + b*batch_x, y + b*batch_y
     // (elements); all zero for a single product
     int64_t batch_A = 0, batch_x = 0, batch_y = 0;
+    const T* const* A_ptrs = nullptr;   // pointer-array batches, as in GemvArgs
+    const T* const* x_ptrs = nullptr;
+    T* const* y_ptrs = nullptr;
+    int64_t y_shift = 0;
     T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
     int* wtab;        // variant 2: [nchunks][2] first and last workgroup whose share touches the chunk
     SymvPlan<T> plan;
 };
+// Operands of member b of a batch, inside a kernel: strided (base + b*stride; all strides zero for a single
+// product) or, in the kernel instances for pointer-array batches, read from the arrays.
+template <bool PTRS, class Args> __device__ __forceinline__ void select_member(Args& a, int64_t b) {
+    if constexpr (PTRS) {
+        a.A = a.A_ptrs[b];
+        a.x = a.x_ptrs[b];
+        a.y = a.y_ptrs[b] + a.y_shift;
+    } else {
+        a.A += b * a.batch_A;
+        a.x += b * a.batch_x;
+        a.y += b * a.batch_y;
+    }
+}
 // HERM selects the Hermitian rule (conjugated mirror image, real diagonal); it exists for
 // complex T only.  Each (T, HERM) pair is instantiated in exactly one translation unit.
 // Row tiles of the largest matrix the one-workgroup-per-member kernel (plan.variant == 4, batches only)
@@ -176,6 +199,9 @@ template <class T> hipError_t launch_pack(const T* src, int64_t inc, int64_t len
 // (`batch` vectors, `stride` elements apart)
 template <class T>
 hipError_t launch_scal(int64_t len, T beta, T* y, int64_t incy, hipStream_t s, int64_t batch = 1, int64_t stride = 0);
+// y <- beta*y for the members of a pointer-array batch (member b: y_ptrs[b] + shift)
+template <class T>
+hipError_t launch_scal_ptrs(int64_t len, T beta, T* const* y_ptrs, int64_t shift, int64_t incy, hipStream_t s, int64_t batch);
 // y[k*incy] = alpha * sum_s partial[s*stride + off + k] + beta*y[k*incy], s ascending
 template <class T> hipError_t launch_reduce(const T* partial, int64_t splits, int64_t stride, int64_t off,
                                             int64_t len, T alpha, T beta, const T* alpha_dev, const T* beta_dev, T* y,

@@ -572,7 +572,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
 // affordable while the triangle stays in cache, and there is no workspace and
 // no second kernel: below a few thousand rows the two launches of the kernels
 // above cost more than the traffic.
-template <class T, bool HERM, bool LOWER, int NC, int NW>
+template <class T, bool HERM, bool LOWER, int NC, int NW, bool PTRS = false>
 __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
@@ -583,9 +583,9 @@ __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
     const int shift = a.plan.shift;
     const int64_t j0 = (int64_t)blockIdx.x * NC;
     const int64_t jend = j0 + NC < n ? j0 + NC : n;   // one past the last existing output
-    const T* __restrict__ x = a.x + (int64_t)blockIdx.y * a.batch_x;   // member of a strided batch (all zero otherwise)
-    const T* __restrict__ A = a.A + (int64_t)blockIdx.y * a.batch_A;
-    a.y += (int64_t)blockIdx.y * a.batch_y;
+    select_member<PTRS>(a, blockIdx.y);   // member of a batch (strides all zero for a single product)
+    const T* __restrict__ x = a.x;
+    const T* __restrict__ A = a.A;
     T acc[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) acc[c] = zero_of<T>();
@@ -708,7 +708,7 @@ __global__ __launch_bounds__(NW * WAVE) void symv_small_kernel(SymvArgs<T> a) {
 // lies inside the stored part and moves the elements into place afterwards, so the other triangle is never
 // loaded here either.  That needs VEC stored rows in the column; the VEC - 1 columns at the short end of
 // the triangle (at most 6 elements) are left to the epilogue, which adds them to the outputs they belong to.
-template <class T, bool HERM, bool LOWER, int MAXT, int NW>
+template <class T, bool HERM, bool LOWER, int MAXT, int NW, bool PTRS>
 __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
@@ -716,9 +716,10 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int n = (int)a.n;
     const int64_t lda = a.lda;
-    const T* __restrict__ x = a.x + (int64_t)blockIdx.x * a.batch_x;
-    const T* __restrict__ A = a.A + (int64_t)blockIdx.x * a.batch_A;
-    T* y = a.y + (int64_t)blockIdx.x * a.batch_y;
+    select_member<PTRS>(a, blockIdx.x);
+    const T* __restrict__ x = a.x;
+    const T* __restrict__ A = a.A;
+    T* y = a.y;
     const int ntiles = (n + TR - 1) / TR;
 
     __shared__ T rowsum[MAXT * TR];   // N parts, all waves
@@ -753,13 +754,15 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
             const int rc = r < slo ? slo : r;
             return rc > shi - VEC ? shi - VEC : rc;
         };
-        auto load_col = [&](Vec<T>(&buf)[MAXT], int j) {
+        // x_j travels with the column's buffer: fetched at compute time it would be a load in the critical path
+        // of every column in the pointer-array instances, where x is not known to be read-only kernel input
+        auto load_col = [&](Vec<T>(&buf)[MAXT], T& xj, int j) {
             const T* __restrict__ col = A + (int64_t)j * lda;
 #pragma unroll
             for (int t = 0; t < MAXT; ++t) buf[t] = load_stream(col + vec_row(t, j));
+            xj = x[j];
         };
-        auto compute_col = [&](const Vec<T>(&buf)[MAXT], int j) {
-            const T xj = x[j];
+        auto compute_col = [&](const Vec<T>(&buf)[MAXT], const T xj, int j) {
             const int slo = LOWER ? j : 0, shi = LOWER ? n : j + 1;
             const int tlo = slo / TR, thi = (shi - 1) / TR + 1;
             T tsum = zero_of<T>();
@@ -800,13 +803,14 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
         // small members, whose columns are short; deeper settings measured the same or 1-4% slower)
         constexpr int DEPTH = MAXT == 1 ? 4 : (MAXT == 2 ? 3 : 2);
         Vec<T> b[DEPTH][MAXT];
+        T xb[DEPTH];
 #pragma unroll
-        for (int d = 0; d < DEPTH - 1; ++d) load_col(b[d], column(d));
+        for (int d = 0; d < DEPTH - 1; ++d) load_col(b[d], xb[d], column(d));
         for (int k = 0; k < cnt; k += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                load_col(b[(d + DEPTH - 1) % DEPTH], column(k + d + DEPTH - 1));
-                if (k + d < cnt) compute_col(b[d], jlo + w + (k + d) * NW);
+                load_col(b[(d + DEPTH - 1) % DEPTH], xb[(d + DEPTH - 1) % DEPTH], column(k + d + DEPTH - 1));
+                if (k + d < cnt) compute_col(b[d], xb[d], jlo + w + (k + d) * NW);
             }
         }
     }
@@ -856,7 +860,7 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
 // epilogue in the same way.
 constexpr int TINY_NW = 4;   // members (waves) per workgroup
 
-template <class T, bool HERM, bool LOWER, int L>
+template <class T, bool HERM, bool LOWER, int L, bool PTRS>
 __global__ __launch_bounds__(TINY_NW * WAVE) void symv_tiny_kernel(SymvArgs<T> a, int batch) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int CPL = WAVE / L;
@@ -867,9 +871,10 @@ __global__ __launch_bounds__(TINY_NW * WAVE) void symv_tiny_kernel(SymvArgs<T> a
     if (member >= batch) return;     // the whole wave leaves; nothing below waits for another wave
     const int n = (int)a.n;
     const int64_t lda = a.lda;
-    const T* __restrict__ x = a.x + (int64_t)member * a.batch_x;
-    const T* __restrict__ A = a.A + (int64_t)member * a.batch_A;
-    T* y = a.y + (int64_t)member * a.batch_y;
+    select_member<PTRS>(a, member);
+    const T* __restrict__ x = a.x;
+    const T* __restrict__ A = a.A;
+    T* y = a.y;
     const int sub = lane % L, cl = lane / L;
     const int r = sub * VEC;         // first row of this lane
 
@@ -1199,26 +1204,41 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
 namespace {
 template <class T, bool HERM, int NW>
 void launch_small(const SymvArgs<T>& a, bool lower, dim3 grid, hipStream_t s) {
+    if (a.A_ptrs) {
+        if (lower) hipLaunchKernelGGL((symv_small_kernel<T, HERM, true, SMALL_NC, NW, true>), grid, dim3(NW * WAVE), 0, s, a);
+        else hipLaunchKernelGGL((symv_small_kernel<T, HERM, false, SMALL_NC, NW, true>), grid, dim3(NW * WAVE), 0, s, a);
+        return;
+    }
     if (lower) hipLaunchKernelGGL((symv_small_kernel<T, HERM, true, SMALL_NC, NW>), grid, dim3(NW * WAVE), 0, s, a);
     else hipLaunchKernelGGL((symv_small_kernel<T, HERM, false, SMALL_NC, NW>), grid, dim3(NW * WAVE), 0, s, a);
 }
+template <class T, bool HERM, int L, bool PTRS>
+void launch_tiny_ptrs(const SymvArgs<T>& a, bool lower, dim3 grid, dim3 block, int batch, hipStream_t s) {
+    if (lower) hipLaunchKernelGGL((symv_tiny_kernel<T, HERM, true, L, PTRS>), grid, block, 0, s, a, batch);
+    else hipLaunchKernelGGL((symv_tiny_kernel<T, HERM, false, L, PTRS>), grid, block, 0, s, a, batch);
+}
 template <class T, bool HERM, int L>
 void launch_tiny(const SymvArgs<T>& a, bool lower, dim3 grid, dim3 block, int batch, hipStream_t s) {
-    if (lower) hipLaunchKernelGGL((symv_tiny_kernel<T, HERM, true, L>), grid, block, 0, s, a, batch);
-    else hipLaunchKernelGGL((symv_tiny_kernel<T, HERM, false, L>), grid, block, 0, s, a, batch);
+    if (a.A_ptrs) launch_tiny_ptrs<T, HERM, L, true>(a, lower, grid, block, batch, s);
+    else launch_tiny_ptrs<T, HERM, L, false>(a, lower, grid, block, batch, s);
+}
+template <class T, bool HERM, int MAXT, int NW, bool PTRS>
+void launch_member_ptrs(const SymvArgs<T>& a, bool lower, unsigned batch, hipStream_t s) {
+    const dim3 grid(batch);
+    if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, NW, PTRS>), grid, dim3(NW * WAVE), 0, s, a);
+    else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, NW, PTRS>), grid, dim3(NW * WAVE), 0, s, a);
 }
 template <class T, bool HERM, int MAXT>
 void launch_member(const SymvArgs<T>& a, bool lower, unsigned batch, hipStream_t s) {
-    const dim3 grid(batch);
     // eight waves from 2 KB per column on (measured on 1 GiB batches: 3-10% faster there, up to 45% for the
     // largest members, 3-10% slower below)
     const bool eight = tuning().symv_member_waves ? tuning().symv_member_waves == 8 : a.n * (int64_t)sizeof(T) >= 2048;
-    if (eight) {
-        if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, 8>), grid, dim3(8 * WAVE), 0, s, a);
-        else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, 8>), grid, dim3(8 * WAVE), 0, s, a);
+    if (a.A_ptrs) {
+        if (eight) launch_member_ptrs<T, HERM, MAXT, 8, true>(a, lower, batch, s);
+        else launch_member_ptrs<T, HERM, MAXT, 4, true>(a, lower, batch, s);
     } else {
-        if (lower) hipLaunchKernelGGL((symv_member_kernel<T, HERM, true, MAXT, 4>), grid, dim3(4 * WAVE), 0, s, a);
-        else hipLaunchKernelGGL((symv_member_kernel<T, HERM, false, MAXT, 4>), grid, dim3(4 * WAVE), 0, s, a);
+        if (eight) launch_member_ptrs<T, HERM, MAXT, 8, false>(a, lower, batch, s);
+        else launch_member_ptrs<T, HERM, MAXT, 4, false>(a, lower, batch, s);
     }
 }
 }  // namespace

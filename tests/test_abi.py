@@ -305,3 +305,22 @@ def test_plain_c_program_links_and_calls_the_library(tmp_path):
     assert build.returncode == 0, build.stderr
     run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert run.returncode == 0 and run.stdout.strip().endswith("ok"), run.stdout + run.stderr
+
+
+@pytest.mark.parametrize("prec", "sdcz")
+def test_pointer_array_batched_argument_errors(prec):
+    g, sv = kmv.GEMV_BATCHED[prec], kmv.SYMV_BATCHED[prec]
+
+    def gemv(trans="N", m=8, n=6, lda=8, incx=1, incy=1, batch=2, A=DUMMY, y=DUMMY):
+        return g(trans, m, n, 1.0, A, lda, DUMMY, incx, 0.0, y, incy, batch, stream=0, check=False)
+
+    def symv(uplo="L", n=8, lda=8, incx=1, incy=1, batch=2, A=DUMMY):
+        return sv(uplo, n, 1.0, A, lda, DUMMY, incx, 0.0, DUMMY, incy, batch, stream=0, check=False)
+
+    assert gemv(trans="X") == -1 and gemv(m=-1) == -2 and gemv(n=-1) == -3 and gemv(lda=7) == -6
+    assert gemv(incx=2) == -8 and gemv(incy=0) == -11 and gemv(batch=-1) == -12
+    assert gemv(batch=0) == 0 and gemv(m=0, lda=1) == 0
+    assert gemv(A=None) == kmv.ERR_NULL and gemv(y=None) == kmv.ERR_NULL
+    assert symv(uplo="X") == -1 and symv(n=-1) == -2 and symv(lda=7) == -5
+    assert symv(incx=-1) == -7 and symv(incy=0) == -10 and symv(batch=-1) == -11
+    assert symv(batch=0) == 0 and symv(n=0, lda=1) == 0 and symv(A=None) == kmv.ERR_NULL

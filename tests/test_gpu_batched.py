@@ -167,3 +167,128 @@ def test_batch_longer_than_one_launch_and_special_scalars():
     k.dgemv_strided_batched("N", m, n, 2.0, A, m, m * n, x, 1, n, 0.5, y, 1, m, 0)
     k.dsymv_strided_batched("L", 3, 0.0, A, 3, 9, x, 1, 3, 1.0, y, 1, 3, 100)
     assert torch.equal(y, y0)
+
+
+# ------------------------------------------------------------ pointer-array batches ----
+def _member_offsets(batch, extent, rng):
+    """start offsets of `batch` members of `extent` elements in one buffer, in shuffled order and with gaps
+    of 0..5 elements, so that the members are neither equally spaced nor equally aligned"""
+    gaps = rng.integers(0, 6, size=batch)
+    starts = np.concatenate(([0], np.cumsum(extent + gaps)[:-1])) + 1      # +1: the first one is unaligned too
+    order = rng.permutation(batch)
+    return [int(starts[i]) for i in order], int(starts[-1] + extent + 8)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "NTC")
+def test_gemv_pointer_array_batched(prec, trans):
+    k = kmv()
+    alpha, beta = scal(prec, 0.7, -0.3)
+    rng = np.random.default_rng(5)
+    for m, n, batch, pad, incy in [(1, 1, 1, 0, 1), (3, 9, 4, 0, 1), (8, 8, 9, 1, -1), (31, 33, 3, 3, 1), (64, 64, 4, 0, 2),
+                                   (100, 300, 5, 3, -1), (129, 31, 2, 1, 1), (256, 256, 3, 0, 1), (257, 9, 2, 0, 1),
+                                   (513, 129, 7, 0, 1), (1000, 40, 2, 8, 1), (300, 700, 3, 16, -2)]:
+        lda = m + (pad % 5)
+        lenx, leny = (n, m) if trans == "N" else (m, n)
+        exty = 1 + (leny - 1) * abs(incy)
+        offA, sizeA = _member_offsets(batch, lda * n, rng)
+        offy, sizey = _member_offsets(batch, exty, rng)
+        A = rand(prec, sizeA, 31 + m)
+        x = rand(prec, lenx * batch + 1, 32 + m)
+        y0 = torch.full((sizey,), NAN, dtype=wl.TORCH_DTYPES[prec], device=DEV)
+        vals = rand(prec, batch * leny, 33 + m).view(batch, leny)
+        for b in range(batch):
+            y0[offy[b]: offy[b] + exty: abs(incy)] = vals[b]
+        y = y0.clone()
+        offx = [0 if b % 2 else 1 + b * lenx - lenx * (b > 0) for b in range(batch)]        # odd members share one x
+        offx = [min(o, x.numel() - lenx) for o in offx]
+        Ap = k.pointer_array([A[o:] for o in offA])
+        xp = k.pointer_array([x[o:] for o in offx])
+        yp = k.pointer_array([y[o:] for o in offy])
+        k.GEMV_BATCHED[prec](trans, m, n, alpha, Ap, lda, xp, 1, beta, yp, incy, batch)
+        torch.cuda.synchronize()
+        Ah, xh, yh, y0h = A.cpu().numpy(), x.cpu().numpy(), y.cpu().numpy(), y0.cpu().numpy()
+        is_out = np.zeros(yh.size, dtype=bool)
+        for b in range(batch):
+            sl = slice(offy[b], offy[b] + exty)
+            is_out[offy[b]: offy[b] + exty: abs(incy)] = True
+            kw = dict(lda=lda, incy=incy)
+            args = (prec, trans, m, n, alpha, Ah[offA[b]:], xh[offx[b]: offx[b] + lenx], beta, y0h[sl])
+            want = oracle.gemv(*args, mode=oracle.MODE_X, **kw)
+            den = oracle.gemv(*args, mode=oracle.MODE_ABS, **kw)
+            err = errors(prec, logical(yh[sl], leny, incy), logical(want, leny, incy), logical(den, leny, incy), lenx)
+            check(prec, err, f"{prec}gemv_batched {trans} {m}x{n} member {b}/{batch}")
+        assert np.array_equal(yh[~is_out].view(np.uint8), y0h[~is_out].view(np.uint8)), "wrote between outputs"
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+@pytest.mark.parametrize("csym", [False, True])
+def test_symv_pointer_array_batched(prec, uplo, csym):
+    if csym and prec not in "cz":
+        pytest.skip("complex symmetric exists for c and z")
+    k = kmv()
+    alpha, beta = scal(prec, -1.1, 0.4)
+    rng = np.random.default_rng(6)
+    for n, batch, pad, incy in [(1, 2, 0, 1), (3, 3, 1, 1), (9, 3, 1, -1), (17, 3, 1, 1), (33, 4, 0, 1), (64, 2, 0, 2),
+                                (100, 3, 1, 1), (129, 4, 0, -2), (257, 2, 5, 1), (512, 3, 0, 1), (640, 2, 0, 1),
+                                (1024, 2, 0, 1), (1100, 3, 0, 1)]:
+        lda = n + (pad % 4)
+        exty = 1 + (n - 1) * abs(incy)
+        offA, sizeA = _member_offsets(batch, lda * n, rng)
+        offy, sizey = _member_offsets(batch, exty, rng)
+        A = rand(prec, sizeA, 41 + n)
+        host = A.cpu().numpy()
+        for b in range(batch):
+            blk = A[offA[b]: offA[b] + lda * n].view(n, lda)
+            wl.poison_triangle(blk, n, uplo, real_diag=False)
+            if prec in "cz" and not csym:
+                d = torch.arange(n, device=DEV)
+                torch.view_as_real(blk)[d, d, 1] = NAN
+        x = rand(prec, n * batch, 42 + n)
+        y0 = torch.full((sizey,), NAN, dtype=wl.TORCH_DTYPES[prec], device=DEV)
+        vals = rand(prec, batch * n, 43 + n).view(batch, n)
+        for b in range(batch):
+            y0[offy[b]: offy[b] + exty: abs(incy)] = vals[b]
+        y = y0.clone()
+        Ap = k.pointer_array([A[o:] for o in offA])
+        xp = k.pointer_array([x[b * n:] for b in range(batch)])
+        yp = k.pointer_array([y[o:] for o in offy])
+        (k.CSYMV_BATCHED if csym else k.SYMV_BATCHED)[prec](uplo, n, alpha, Ap, lda, xp, 1, beta, yp, incy, batch)
+        torch.cuda.synchronize()
+        xh, yh, y0h = x.cpu().numpy(), y.cpu().numpy(), y0.cpu().numpy()
+        is_out = np.zeros(yh.size, dtype=bool)
+        for b in range(batch):
+            sl = slice(offy[b], offy[b] + exty)
+            is_out[offy[b]: offy[b] + exty: abs(incy)] = True
+            args = (prec, uplo, n, alpha, host[offA[b]:], xh[b * n: b * n + n], beta, y0h[sl])
+            want = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_X, complex_symmetric=csym)
+            den = oracle.symv(*args, lda=lda, incy=incy, mode=oracle.MODE_ABS, complex_symmetric=csym)
+            err = errors(prec, logical(yh[sl], n, incy), logical(want, n, incy), logical(den, n, incy), n)
+            check(prec, err, f"symv/hemv_batched {prec} {uplo} n={n} member {b}/{batch}")
+        assert np.array_equal(yh[~is_out].view(np.uint8), y0h[~is_out].view(np.uint8)), "wrote between outputs"
+
+
+def test_pointer_array_batch_longer_than_one_launch_and_special_scalars():
+    k = kmv()
+    m, n, batch = 4, 3, 70000
+    A = rand("d", batch * m * n, 1)
+    x = rand("d", batch * n, 2)
+    y0 = rand("d", batch * m, 3)
+    y = y0.clone()
+    base = torch.arange(batch, dtype=torch.int64, device=DEV)
+    Ap = A.data_ptr() + base * (m * n * 8)
+    xp = x.data_ptr() + base * (n * 8)
+    yp = y.data_ptr() + base * (m * 8)
+    k.dgemv_batched("N", m, n, 2.0, Ap, m, xp, 1, -1.0, yp, 1, batch)
+    torch.cuda.synchronize()
+    Ah = A.cpu().numpy().reshape(batch, n, m)
+    want = 2.0 * np.einsum("bji,bj->bi", Ah, x.cpu().numpy().reshape(batch, n)) - y0.cpu().numpy().reshape(batch, m)
+    assert np.max(np.abs(y.cpu().numpy().reshape(batch, m) - want)) <= 1e-14
+    # alpha = 0: y <- beta*y, the arrays of A and x are not looked at
+    y.copy_(y0)
+    k.dgemv_batched("T", n, m, 0.0, None, n, None, 1, 3.0, yp, 1, batch)
+    assert torch.equal(y, 3.0 * y0)
+    k.dsymv_batched("L", 2, 0.0, None, 2, None, 1, 1.0, yp, 1, batch)          # alpha = 0, beta = 1: nothing happens
+    k.dsymv_batched("U", 2, 1.0, Ap, 2, xp, 1, 0.0, yp, 1, 0)                  # empty batch
+    assert torch.equal(y, 3.0 * y0)
