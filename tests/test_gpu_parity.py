@@ -607,12 +607,14 @@ def test_calls_can_be_captured_in_a_graph():
     n = 1800
     A = wl.matrix("d", n, n, seed=41, device=DEV)
     x = wl.vector("d", n, seed=41, device=DEV)
-    y1, y2, y3, y4, y5, y6 = (torch.zeros(n, dtype=torch.float64, device=DEV) for _ in range(6))
+    y1, y2, y3, y4, y5, y6, y7 = (torch.zeros(n, dtype=torch.float64, device=DEV) for _ in range(7))
     ws = torch.empty(max(k.gemv_workspace_bytes("d", "N", n, n), k.symv_workspace_bytes("d", "L", n)),
                      dtype=torch.uint8, device=DEV)
     dev_alpha = torch.zeros(1, dtype=torch.float64, device=DEV)
     dev_beta = torch.zeros(1, dtype=torch.float64, device=DEV)
     nb, bn = 9, 200                              # a batch of nine 200 x 200 blocks inside A's buffer
+    idx = torch.arange(nb, dtype=torch.int64, device=DEV)
+    Ap, xp, yp = A.data_ptr() + idx * (bn * bn * 8), x.data_ptr() + idx * (bn * 8), y7.data_ptr() + idx * (bn * 8)
 
     def run():
         k.dgemv("N", n, n, 0.7, A, n, x, 1, 0.0, y1, 1, workspace=ws)
@@ -623,6 +625,7 @@ def test_calls_can_be_captured_in_a_graph():
         dev_alpha.copy_(y1[:1])                  # device-side producer of alpha
         k.dsymv_devscalars("U", n, dev_alpha, A, n, x, 1, dev_beta, y5, 1, workspace=ws)
         k.dgemv_strided_batched("T", bn, bn, 1.0, A, bn, bn * bn, x, 1, bn, 0.0, y6, 1, bn, nb)
+        k.dsymv_batched("L", bn, 1.0, Ap, bn, xp, 1, 0.0, yp, 1, nb)       # the same members through pointer arrays
 
     run()                                   # warm up outside the capture (occupancy queries, module load)
     torch.cuda.synchronize()
@@ -633,11 +636,11 @@ def test_calls_can_be_captured_in_a_graph():
         x.copy_(wl.vector("d", n, seed=50 + rep, device=DEV))
         g.replay()
         torch.cuda.synchronize()
-        got = [t.clone() for t in (y1, y2, y3, y4, y5, y6)]
+        got = [t.clone() for t in (y1, y2, y3, y4, y5, y6, y7)]
         run()
         torch.cuda.synchronize()
-        assert float(y5.abs().sum()) > 0 and float(y6.abs().sum()) > 0
-        for a_, b_ in zip(got, (y1, y2, y3, y4, y5, y6)):
+        assert float(y5.abs().sum()) > 0 and float(y6.abs().sum()) > 0 and float(y7.abs().sum()) > 0
+        for a_, b_ in zip(got, (y1, y2, y3, y4, y5, y6, y7)):
             assert torch.equal(a_, b_), f"replay {rep} differs from the eager calls"
 
 
