@@ -48,10 +48,10 @@ def test_gemv_strided_batched(prec, trans, tiny_rows):
         k.set_tuning("gemv_tiny_rows", 0)
 
 
-def _gemv_batched_cases(k, prec, trans):
+def _gemv_batched_cases(k, prec, trans, cases=None):
     alpha, beta = scal(prec, 0.7, -0.3)
     # up to one row tile (256 / 128 / 128 / 64 rows): one wave per member with 8, 16, 32 or 64 lanes per column
-    cases = [(1, 1, 1, 0, 1), (2, 9, 3, 0, 1), (3, 3, 2, 1, 1), (4, 1, 5, 0, 1), (5, 17, 2, 2, -1), (7, 5, 3, 1, 1),
+    cases = cases or [(1, 1, 1, 0, 1), (2, 9, 3, 0, 1), (3, 3, 2, 1, 1), (4, 1, 5, 0, 1), (5, 17, 2, 2, -1), (7, 5, 3, 1, 1),
              (8, 8, 9, 0, 1), (9, 40, 3, 1, 1), (16, 16, 6, 0, 1), (17, 3, 2, 0, 2), (31, 33, 3, 3, 1), (32, 100, 5, 0, 1),
              (33, 7, 2, 1, 1), (63, 64, 3, 0, 1), (64, 64, 4, 0, 2), (65, 200, 7, 16, 1), (100, 300, 5, 3, -1),
              (127, 50, 2, 0, 1), (128, 128, 3, 0, 1), (129, 31, 2, 1, 1), (255, 20, 3, 0, 1), (256, 256, 2, 0, 1),
@@ -97,10 +97,10 @@ def test_complex_symmetric_strided_batched(prec, uplo):
     _symv_batched_case(prec, uplo, True)
 
 
-def _symv_batched_case(prec, uplo, csym):
+def _symv_batched_case(prec, uplo, csym, cases=None):
     k = kmv()
     alpha, beta = scal(prec, -1.1, 0.4)
-    for n, batch, pad, incy in [(1, 1, 0, 1), (2, 3, 0, 1), (3, 2, 1, 1), (4, 2, 0, -1), (5, 2, 2, 1), (8, 4, 0, 1), (9, 3, 1, -1), (16, 5, 0, 1), (17, 3, 1, 1), (31, 2, 0, 1), (32, 6, 3, -1),
+    for n, batch, pad, incy in cases or [(1, 1, 0, 1), (2, 3, 0, 1), (3, 2, 1, 1), (4, 2, 0, -1), (5, 2, 2, 1), (8, 4, 0, 1), (9, 3, 1, -1), (16, 5, 0, 1), (17, 3, 1, 1), (31, 2, 0, 1), (32, 6, 3, -1),
                                  (33, 2, 0, 1), (63, 5, 16, 2), (64, 2, 0, 1), (65, 3, 2, 1), (100, 3, 1, 1), (127, 2, 0, 1), (128, 9, 0, 1),
                                  (129, 4, 0, -2), (200, 6, 3, 1), (257, 2, 5, 1), (511, 2, 0, 1), (512, 3, 0, 1),
                                  (513, 2, 1, 1), (640, 2, 0, 1), (777, 2, 0, 1), (1024, 2, 0, 1), (1100, 3, 0, 1)]:   # small members: one workgroup each; beyond: small-matrix kernel
@@ -292,3 +292,26 @@ def test_pointer_array_batch_longer_than_one_launch_and_special_scalars():
     k.dsymv_batched("L", 2, 0.0, None, 2, None, 1, 1.0, yp, 1, batch)          # alpha = 0, beta = 1: nothing happens
     k.dsymv_batched("U", 2, 1.0, Ap, 2, xp, 1, 0.0, yp, 1, 0)                  # empty batch
     assert torch.equal(y, 3.0 * y0)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_random_batched_shapes(prec):
+    """seeded random member sizes, batch counts, paddings and increments through the strided forms
+    (KMV_FUZZ_CASES / KMV_FUZZ_SEED in the environment lengthen or reseed the series)"""
+    import os
+    rng = np.random.default_rng({"s": 21, "d": 22, "c": 23, "z": 24}[prec] + 100 * int(os.environ.get("KMV_FUZZ_SEED", "0")))
+    count = int(os.environ.get("KMV_FUZZ_CASES", "12"))
+    k = kmv()
+    sizes = [1, 2, 3, 5, 8, 13, 16, 24, 32, 47, 64, 96, 128, 200, 256, 300, 511, 700, 1030]
+    gemv_cases, symv_cases = [], []
+    for _ in range(count):
+        m = int(rng.choice(sizes) + rng.integers(0, 3))
+        n = int(rng.choice(sizes) + rng.integers(0, 3))
+        gemv_cases.append((m, n, int(rng.integers(1, 6)), int(rng.choice([0, 1, 3, 16])), int(rng.choice([1, 1, 2, -1]))))
+        symv_cases.append((n, int(rng.integers(1, 5)), int(rng.choice([0, 1, 2, 16])), int(rng.choice([1, 1, 2, -1]))))
+    for trans in "NTC":
+        _gemv_batched_cases(k, prec, trans, gemv_cases)
+    for uplo in "LU":
+        _symv_batched_case(prec, uplo, False, symv_cases)
+        if prec in "cz":
+            _symv_batched_case(prec, uplo, True, symv_cases)
