@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--prec", default="d", choices=list("sdcz"), help="precision of the sytrd / gebrd / batched workloads")
     ap.add_argument("--uplo", default="L", choices=["L", "U"], help="stored triangle of the sytrd workload")
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
+    ap.add_argument("--only", default=None, help="regular expression on 'routine:n' (e.g. 'dsymv_L:16384|dgemv_N:'): time only "
+                                                 "the matching products of the workload (for profiles)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
     return ap.parse_args()
@@ -512,6 +514,12 @@ def main():
     # products at the end of a step are already queued when their turn comes
     probe = stream_probe(k, torch)
     prods = sorted(products(args.workload), key=lambda p: -p["n"] * p.get("m", p["n"]))
+    if args.only:
+        import re
+        prods = [p for p in prods if re.search(args.only, f"{routine_name(p)}:{p['n']}")]
+        if not prods:
+            print(f"bench.py: --only {args.only!r} matches no product of workload {args.workload}", file=sys.stderr)
+            sys.exit(2)
     inputs = Inputs(prods, torch, wl)
     stream = torch.cuda.current_stream()
     calls = [make_call(p, k, *inputs.views(p)) for p in prods]

@@ -482,6 +482,22 @@ const char* kmv_tuning_keys(void);
  * and profiles that have to name the kernel they time. */
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda);
 
+/* The balanced SYMV/HEMV kernel deals the pieces (row chunk x panel of 16
+ * columns) of the stored triangle to its workgroups in contiguous shares of a
+ * work line (Section 6.2, Eqs. local_workload / starting_point), on which a
+ * piece weighs the row tiles it really holds (`unit_tiles` at a time) plus
+ * `fixed`.  This call returns the table the planner computes for such a call:
+ * start[y] = (chunk << 20) | piece inside the chunk for y = 0 .. workers (the
+ * last entry is (number of chunks, 0)); first[k] / last[k] = the workers that
+ * hold the first and the last piece of chunk k (arrays of 160 entries); *work
+ * = length of the line.  Host arrays owned by the caller, any of them may be
+ * NULL.  shift = leading masked slots of row tile 0 (0 .. rows per tile - 1),
+ * chunk_tiles 4 or 8, unit_tiles 1 or 2, slots = workgroups wanted (at most
+ * 800 are used).  Returns the number of workers, -1 for arguments out of
+ * range.  Nothing is launched; exported for the tests of the host logic. */
+int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots,
+                    int fixed, uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work);
+
 const char* kmv_version(void);
 
 #ifdef __cplusplus

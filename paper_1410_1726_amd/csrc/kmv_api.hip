@@ -98,7 +98,6 @@ int symv_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int6
     if (dev_scalars) { a.alpha_dev = alpha; a.beta_dev = beta; }
     a.wsn = reinterpret_cast<T*>(ws + plan.wsn_off);
     a.wst = reinterpret_cast<T*>(ws + plan.wst_off);
-    a.wtab = reinterpret_cast<int*>(ws + plan.tab_off);
     a.plan = plan;
     if (incx != 1) {
         T* xp = reinterpret_cast<T*>(ws + plan.xpack_off);
@@ -236,7 +235,7 @@ int symv_batched_entry(bool herm, char uplo, int64_t n, const T* alpha, const T*
     SymvArgs<T> a;
     a.n = n; a.lda = lda;
     a.incy = incy; a.alpha = al; a.beta = be;
-    a.wsn = nullptr; a.wst = nullptr; a.wtab = nullptr;
+    a.wsn = nullptr; a.wst = nullptr;
     a.batch_A = strideA; a.batch_x = stridex; a.batch_y = stridey;
     for (int64_t b0 = 0; b0 < batch; b0 += MAX_GRID_BATCH) {
         const int64_t nb = batch - b0 < MAX_GRID_BATCH ? batch - b0 : MAX_GRID_BATCH;
@@ -337,7 +336,7 @@ int symv_ptr_batched_entry(bool herm, char uplo, int64_t n, const T* alpha, cons
     a.n = n; a.lda = lda;
     a.A = nullptr; a.x = nullptr; a.y = nullptr;
     a.incy = incy; a.alpha = al; a.beta = be;
-    a.wsn = nullptr; a.wst = nullptr; a.wtab = nullptr;
+    a.wsn = nullptr; a.wst = nullptr;
     a.y_shift = incy < 0 ? (1 - n) * incy : 0;
     for (int64_t b0 = 0; b0 < batch; b0 += MAX_GRID_BATCH) {
         const int64_t nb = batch - b0 < MAX_GRID_BATCH ? batch - b0 : MAX_GRID_BATCH;
@@ -378,6 +377,7 @@ const Key KEYS[] = {
     {"symv_classes", &Tuning::symv_classes, 0, 256},
     {"symv_variant", &Tuning::symv_variant, 0, 3},
     {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
+    {"symv_piece_fixed", &Tuning::symv_piece_fixed, 0, 17},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
     {"symv_member_rows", &Tuning::symv_member_rows, 0, 1024},
     {"symv_member_waves", &Tuning::symv_member_waves, 0, 8},
@@ -613,7 +613,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,symv_piece_fixed,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
@@ -627,6 +627,36 @@ int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int6
         case 'z': return plan_symv<cf64>(lower, n, base, lda).variant;
     }
     return 0;
+}
+
+int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed,
+                    uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work) {
+    const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
+    if ((!lower && !upper) || n < 1 || n > ((int64_t)1 << 30) || shift < 0 || (chunk_tiles != 4 && chunk_tiles != 8) ||
+        (unit_tiles != 1 && unit_tiles != 2) || slots < 1 || fixed < 0 || fixed > 16)
+        return -1;
+    const SymvBalanced* b = nullptr;
+    int tr = 0;
+    switch (prec) {
+        case 's': tr = tile_rows<float>(); break;
+        case 'd': tr = tile_rows<double>(); break;
+        case 'c': tr = tile_rows<cf32>(); break;
+        case 'z': tr = tile_rows<cf64>(); break;
+        default: return -1;
+    }
+    if (shift >= tr || ceil_div(ceil_div(n + shift, tr), chunk_tiles) > SHARE_MAX_CHUNKS) return -1;
+    switch (prec) {
+        case 's': b = symv_shares<float>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
+        case 'd': b = symv_shares<double>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
+        case 'c': b = symv_shares<cf32>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
+        case 'z': b = symv_shares<cf64>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
+    }
+    if (!b) return -1;
+    if (start) memcpy(start, b->shares.start, sizeof(uint32_t) * (size_t)(b->workers + 1));
+    if (first) memcpy(first, b->owners.first, sizeof(b->owners.first));
+    if (last) memcpy(last, b->owners.last, sizeof(b->owners.last));
+    if (work) *work = b->work;
+    return b->workers;
 }
 
 const char* kmv_version(void) { return "kmv 0.1 (gfx950)"; }

@@ -184,6 +184,8 @@ __device__ __forceinline__ double read_lane(double v, int lane) {
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
+__device__ __forceinline__ cf32 read_lane(cf32 v, int lane) { return cf32{read_lane(v.re, lane), read_lane(v.im, lane)}; }
+__device__ __forceinline__ cf64 read_lane(cf64 v, int lane) { return cf64{read_lane(v.re, lane), read_lane(v.im, lane)}; }
 template <class R> __device__ __forceinline__ R wave_sum_real(R v) {
     v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
     v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]

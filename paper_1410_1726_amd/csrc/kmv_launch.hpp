@@ -22,6 +22,7 @@ struct Tuning {
     int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
     int64_t symv_variant = 0;         // SYMV main kernel: 1 = chains, 2 = balanced shares
     int64_t symv_unit_tiles = 0;      // balanced kernel: row tiles per prefetch unit (1 or 2)
+    int64_t symv_piece_fixed = 0;     // balanced kernel: fixed part of a piece's weight on the work line, plus one
     int64_t wg_target = 0;         // workgroups the heuristics aim for
     int64_t symv_member_rows = 0;     // batches: largest n for the one-workgroup-per-member kernel
     int64_t symv_member_waves = 0;    // batches: waves of that kernel's workgroup (4 or 8)
@@ -118,6 +119,27 @@ template <class T> inline int64_t gemv_tiny_rows(bool notrans) {
 }
 
 // ----------------------------------------------------------- SYMV/HEMV ----
+// Shares of the balanced kernel's work line, computed on the host and handed to the kernels as arguments
+// (Section 6.2 deals equal contiguous shares to the workers; here the shares are cut where pieces start and a
+// piece weighs what it holds).  start[y] = (row chunk << SHARE_PIECE_BITS) | piece inside the chunk: the first
+// piece of worker y; start[workers] = (number of chunks, 0).  first / last: the workers that hold the first and
+// the last piece of a chunk, which is all the final pass needs to find the chunk's row-sum vectors.
+constexpr int SHARE_MAX_WORKERS = 800;      // 3204 bytes of kernel arguments
+constexpr int SHARE_PIECE_BITS = 20;
+constexpr int SHARE_MAX_CHUNKS = 160;
+struct SymvShares { uint32_t start[SHARE_MAX_WORKERS + 1]; };
+struct SymvOwners { uint16_t first[SHARE_MAX_CHUNKS], last[SHARE_MAX_CHUNKS]; };
+struct SymvBalanced {
+    // what the table was computed for
+    int64_t n;
+    int shift, lower, chunk_tiles, unit_tiles, slots, fixed;
+    // the table
+    int64_t work;     // length of the work line
+    int workers;      // shares (workgroups of the main kernel)
+    SymvShares shares;
+    SymvOwners owners;
+};
+
 template <class T> struct SymvPlan {
     int shift;
     int variant;           // main kernel: 1 = chains of panels per row chunk, 2 = balanced shares of pieces
@@ -129,11 +151,15 @@ template <class T> struct SymvPlan {
     int64_t nchunks;       // row chunks
     int64_t classes;       // a chain takes every classes-th panel of its row chunk
     int64_t rows_padded;   // distance between two row-sum vectors (variant 1: >= ntiles * tile_rows; 2: >= chunk rows)
-    int64_t work;          // variant 2: length of the work line (row tiles x panels that hold stored elements)
+    int64_t work;          // variant 2: length of the work line (stored row tiles of all pieces plus a fixed part per piece)
     int64_t workers;       // variant 2: workgroups of the main kernel
-    size_t xpack_off, wsn_off, wst_off, tab_off, total_bytes;
+    const SymvBalanced* bal;   // variant 2: the shares (host memory of the planner, valid until the thread's next few plans)
+    size_t xpack_off, wsn_off, wst_off, total_bytes;
 };
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
+// the table of shares for given settings (what plan_symv looks up for the balanced kernel; exported for tests)
+template <class T>
+const SymvBalanced* symv_shares(bool lower, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed);
 
 template <class T> struct SymvArgs {
     int64_t n, lda;
@@ -153,7 +179,6 @@ template <class T> struct SymvArgs {
     int64_t y_shift = 0;
     T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
-    int* wtab;        // variant 2: [nchunks][2] first and last workgroup whose share touches the chunk
     SymvPlan<T> plan;
 };
 // Operands of member b of a batch, inside a kernel: strided (base + b*stride; all strides zero for a single

@@ -290,47 +290,50 @@ __global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
     }
 }
 
-// panels whose stored part touches row chunk k (chunks of CT tiles): first panel
-// plo and their number; tk = row tiles of the chunk (the last chunk may be short)
+// Groups of KT row tiles of the row chunk [tbeg, tend) that hold stored elements of panel p (C columns):
+// [glo, ghi).  Inside a chunk's own panel range (chunk_panels) the range is never empty.
 template <bool LOWER>
-__host__ __device__ __forceinline__ int64_t chunk_pieces(int64_t k, int64_t CT, int64_t C, int shift, int64_t TR,
-                                                         int64_t ntiles, int64_t npanels, int64_t& plo, int64_t& tk) {
-    const int64_t tbeg = k * CT;
-    const int64_t tend = tbeg + CT < ntiles ? tbeg + CT : ntiles;
-    int64_t phi;
-    chunk_panels<LOWER>(tbeg, tend, C, shift, TR, npanels, plo, phi);
-    tk = tend - tbeg;
-    return phi > plo ? phi - plo : 0;
+__host__ __device__ __forceinline__ void piece_groups(int p, int C, int n, int shift, int TR, int KT, int tbeg, int tend,
+                                                      int& glo, int& ghi) {
+    const int gk = (tend - tbeg + KT - 1) / KT;
+    if (LOWER) {
+        const int tlo = (p * C + shift) / TR;
+        glo = tlo > tbeg ? (tlo - tbeg) / KT : 0;
+        ghi = gk;
+    } else {
+        const int jend = p * C + C < n ? p * C + C : n;
+        const int thi = (jend - 1 + shift) / TR + 1;
+        glo = 0;
+        ghi = thi < tend ? (thi - tbeg + KT - 1) / KT : gk;
+    }
 }
-// Length of a piece on the work line: its row tiles plus a fixed part (measured:
-// a piece of a short last chunk costs clearly more than its share of the rows).
-#ifndef KMV_PIECE_FIXED
-#define KMV_PIECE_FIXED 3
-#endif
-__host__ __device__ __forceinline__ int64_t piece_weight(int64_t tk) { return tk + KMV_PIECE_FIXED; }
 
 // Balanced form: the pieces (row chunk k, panel p) of the stored triangle are
-// laid chunk by chunk on a work line (piece_weight units each) that is dealt to
-// the workgroups in equal contiguous shares by the partition of Section 6.2 (a
-// piece goes to the share that holds its first unit), and the grid is exactly
-// one resident round (compute units x occupancy): every workgroup starts at
-// once, reads about the same number of bytes and ends at once, and at any
-// moment the resident workgroups cover all row chunks, so the load on memory
-// channels does not depend on the leading dimension.  A workgroup's share lies
-// in one chunk, rarely two or more.
-// Inside a piece wave w owns the columns [w*NC, (w+1)*NC) of the panel over ALL
-// CT = KT*G row tiles (G units of KT tiles, visited in a per-wave rotated order
-// so that the waves read different KiB of their columns at any moment).  The
+// laid chunk by chunk on a work line, each with the weight of the row tiles it
+// really holds plus a fixed part, and the line is dealt to the workgroups in
+// equal contiguous shares by the partition of Section 6.2 (a piece goes to the
+// share that holds its first unit).  The host computes where every share starts
+// and passes the table in the kernel arguments, so a workgroup begins to load
+// after two scalar reads.  The grid is exactly one resident round (compute
+// units x occupancy): every workgroup starts at once, reads about the same
+// number of bytes and ends at once, and at any moment the resident workgroups
+// cover all row chunks, so the load on memory channels does not depend on the
+// leading dimension.  A workgroup's share lies in one chunk, rarely two or more.
+// Inside a piece wave w owns the columns [w*NC, (w+1)*NC) of the panel over the
+// piece's stored groups of KT row tiles, visited in a per-wave rotated order so
+// that the waves read different KiB of their columns at any moment.  The
 // transposed column sums are private to the wave: one DPP reduction per column
 // and panel, no barrier inside the walk, and the diagonal tiles' element-wise
 // work is spread over all waves.  The row sums of a wave live in a wave-private
 // LDS array (each lane touches only its own slots, no synchronisation) and meet
 // the other waves' when the share leaves a chunk: one row-sum vector per
-// (workgroup, chunk), stored at index workgroup + chunk; the owners of a
-// chunk's first and last piece leave their numbers in a small table for the
-// final pass.  x over the chunk's rows is staged in LDS.
+// (workgroup, chunk), stored at index workgroup + chunk.  x over the chunk's
+// rows is staged in LDS; the x_j of a unit's columns travel with the unit's
+// matrix vectors (one load, spread to the lanes' multiply-adds by readlane when
+// the unit is used), so nothing between issuing a unit's loads and using the
+// unit before it waits for memory.
 template <class T, bool HERM, bool LOWER, int NC, int KT, int G, int NW>
-__global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kernel(SymvArgs<T> a) {
+__global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kernel(SymvArgs<T> a, SymvShares sh) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     constexpr int C = NC * NW;
@@ -345,112 +348,139 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
     const int shift = a.plan.shift;
     const int ntiles = (int)a.plan.ntiles, nchunks = (int)a.plan.nchunks, npanels = (int)a.plan.npanels;
     const T* __restrict__ x = a.x;
+    // long columns [jlo, jhi): at least VEC stored rows, so that any lane finds 16 stored bytes in them.  The
+    // VEC - 1 short columns at the tip of the triangle (at most six elements) are left to the final pass.
+    const int jlo = LOWER ? 0 : VEC - 1, jhi = LOWER ? n - VEC + 1 : n;
 
     __shared__ __align__(16) T xs[R];       // x over the chunk's rows (zeros outside [0, n))
     __shared__ __align__(16) T rs[NW][R];   // row sums of each wave
 
-    // this workgroup's share [wlo, whi) of the work line
-    int64_t wlo, whi;
-    {
-        int64_t wcnt;
-        partition(a.plan.work, (int64_t)gridDim.x, (int64_t)blockIdx.x, wcnt, wlo);
-        if (wcnt <= 0) return;
-        whi = wlo + wcnt;
-    }
+    // this workgroup's share: from piece j0 of chunk k0 up to (not including) piece j1 of chunk k1
+    const uint32_t e0 = sh.start[blockIdx.x], e1 = sh.start[blockIdx.x + 1];
+    constexpr uint32_t PIECE_MASK = (1u << SHARE_PIECE_BITS) - 1;
+    const int k0 = (int)(e0 >> SHARE_PIECE_BITS), j0 = (int)(e0 & PIECE_MASK);
+    const int k1 = (int)(e1 >> SHARE_PIECE_BITS), j1 = (int)(e1 & PIECE_MASK);
 
     Vec<T> b0[KT][NC], b1[KT][NC];
-    T xj0[NC], xj1[NC];
+    T xr0 = zero_of<T>(), xr1 = zero_of<T>();
     T accT[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) accT[c] = zero_of<T>();
 
-    int64_t wb = 0;   // work before chunk k
-    for (int k = 0; k < nchunks && wb < whi; ++k) {
-        int64_t plo64, tk, len;
-        len = chunk_pieces<LOWER>(k, CT, C, shift, TR, ntiles, npanels, plo64, tk);
-        const int64_t wb0 = wb, pw = piece_weight(tk);
-        wb += len * pw;
-        if (wb <= wlo) continue;   // the share starts in a later chunk
-        // pieces of this chunk whose first unit of the line lies in the share (there
-        // may be none: the row-sum vector is then all zeros)
-        const int64_t lo = (wlo > wb0 ? wlo : wb0) - wb0, hi = (whi < wb ? whi : wb) - wb0;
-        const int j0 = (int)((lo + pw - 1) / pw), j1 = (int)((hi + pw - 1) / pw);
-        // the owners of a chunk's first and last piece tell the final pass which
-        // row-sum vectors exist for the chunk
-        if (threadIdx.x == 0 && j1 > j0) {
-            if (j0 == 0) a.wtab[2 * k] = (int)blockIdx.x;
-            if (j1 == (int)len) a.wtab[2 * k + 1] = (int)blockIdx.x;
-        }
-        // piece, panel and unit counts fit 32 bits (n < 2^31 * 16 columns)
-        const int pfirst = (int)plo64 + j0;
-        const int gk = ((int)tk + KT - 1) / KT;   // units per piece: a short last chunk has fewer
-        const int units = (j1 - j0) * gk;
+    for (int k = k0; k <= k1 && k < nchunks; ++k) {
         const int tbeg = k * CT;
         const int tend = tbeg + CT < ntiles ? tbeg + CT : ntiles;
+        int64_t plo64, phi64;
+        chunk_panels<LOWER>(tbeg, tend, C, shift, TR, npanels, plo64, phi64);
+        const int ja = k == k0 ? j0 : 0, jb = k == k1 ? j1 : (int)(phi64 - plo64);
+        if (jb <= ja) continue;               // the share ends where this chunk begins
+        const int pfirst = (int)plo64 + ja, npieces = jb - ja;
         const int row0 = tbeg * TR - shift;   // row of slot 0 of the chunk
 
-        // flags of row tile tt (0..CT-1 inside the chunk) against the wave's column
-        // group starting at column jg: valid = holds stored elements, fast = all rows
-        // exist, all NC columns exist, every pair strictly inside the triangle
-        auto tile_flags = [&](int jg, int tt, bool& valid, bool& fast) {
-            const int t = tbeg + tt;
-            const int r0 = t * TR - shift;
-            const bool inrange = t < tend && jg < n;
-            const bool rowfull = r0 >= 0 && r0 + TR <= n;
-            const int jl = (jg + NC < n ? jg + NC : n) - 1;   // last existing column
-            valid = inrange && (LOWER ? (r0 + TR - 1 >= jg) : (r0 <= jl));
-            fast = valid && rowfull && jg + NC <= n && (LOWER ? (r0 >= jg + NC) : (r0 + TR - 1 < jg));
+        // row tiles of the chunk (numbered from 0) whose TR rows all exist: [tf_lo, tf_hi)
+        const int tf_lo = row0 < 0 ? 1 : 0;
+        const int tf_hi = (n - row0) / TR < tend - tbeg ? (n - row0) / TR : tend - tbeg;
+
+        // Position of the share's walk through this chunk: piece pp, step ss of the piece's nu stored
+        // groups [glo, glo + nu), at group gg (the waves start at different groups).  What depends on
+        // the piece only is worked out once per piece: the wave's first column jg, its NC columns as
+        // they are loaded (cj: a column that does not exist or is a short one stands in as the nearest
+        // long column), the lane's address of row 0 of each (col), the lane's element of x, and the
+        // tiles [fa, fb) in which every pair of the wave's columns is an ordinary off-diagonal element.
+        struct Walk {
+            int pp, ss, gg, glo, nu, fa, fb;
+            int cj[NC];
+            const T* col[NC];
+            const T* xcol;
         };
-        // one unit = the wave's NC columns of one panel over KT row tiles; the next
-        // unit's matrix vectors and x_j scalars are in flight while this one is used
-        // (pp, g) = (piece of the share, group of KT row tiles); the waves take the
-        // groups in rotated order so that they read different KiB at any moment
-        auto load_unit = [&](Vec<T>(&b)[KT][NC], T(&xjb)[NC], int pp, int g) {
-            const int jg = (pfirst + pp) * C + w * NC;
+        auto enter = [&](Walk& it) {
+            const int p = pfirst + it.pp;
+            int glo, ghi;
+            piece_groups<LOWER>(p, C, n, shift, TR, KT, tbeg, tend, glo, ghi);
+            it.glo = glo;
+            it.nu = ghi - glo;
+            int r = w;
 #pragma unroll
-            for (int q = 0; q < KT; ++q) {
-                bool valid, fast;
-                tile_flags(jg, g * KT + q, valid, fast);
-                const int rq = row0 + (g * KT + q) * TR + lane * VEC;
-                if (fast) {
-                    const T* src = a.A + (int64_t)jg * lda + rq;
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) b[q][c] = load_stream(src + (int64_t)c * lda);
-                } else if (valid) {
-                    // edge / diagonal tile: element loads into the same buffer; a pair
-                    // outside the stored triangle loads the (always stored) diagonal
-                    // element of its column instead and is skipped at use
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        const int row = rq + v;
-                        const bool rowok = row >= 0 && row < n;
-#pragma unroll
-                        for (int c = 0; c < NC; ++c) {
-                            const int j = jg + c;
-                            const int jc = j < n ? j : n - 1;
-                            const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
-                            b[q][c].e[v] = load_elem_stream(a.A + (ins ? row : jc) + (int64_t)jc * lda);
-                        }
-                    }
+            for (int i = 1; i < NW; ++i) r = r >= it.nu ? r - it.nu : r;
+            it.gg = glo + r;
+            it.ss = 0;
+            const int jg = p * C + w * NC;
+            if (jg >= jlo && jg + NC <= jhi) {
+                if (LOWER) {
+                    const int f = (jg + NC + shift + TR - 1) / TR - tbeg;   // first tile that starts at or below row jg + NC
+                    it.fa = f > tf_lo ? f : tf_lo;
+                    it.fb = tf_hi;
+                } else {
+                    const int f = (jg + shift) / TR - tbeg;                 // tiles before f end above row jg
+                    it.fa = tf_lo;
+                    it.fb = f < tf_hi ? f : tf_hi;
                 }
+            } else {
+                it.fa = it.fb = 0;
             }
 #pragma unroll
-            for (int c = 0; c < NC; ++c)
-                xjb[c] = select_of(jg + c < n, x[jg + c < n ? jg + c : n - 1], zero_of<T>());
+            for (int c = 0; c < NC; ++c) {
+                const int j = jg + c;
+                it.cj[c] = j < jlo ? jlo : (j >= jhi ? jhi - 1 : j);
+                it.col[c] = a.A + (int64_t)it.cj[c] * lda;
+            }
+            const int jx = jg + (lane & (NC - 1));
+            it.xcol = x + (jx < jlo ? jlo : (jx >= jhi ? jhi - 1 : jx));
         };
-        auto compute_unit = [&](const Vec<T>(&b)[KT][NC], const T(&xjb)[NC], int pp, int g, bool last) {
-            const int p = pfirst + pp;
-            const int jg = p * C + w * NC;
+        auto advance = [&](Walk& it) {
+            if (it.pp >= npieces) return;   // the walk is over
+            if (++it.ss == it.nu) {
+                if (++it.pp < npieces) enter(it);
+            } else if (++it.gg == it.glo + it.nu) {
+                it.gg = it.glo;
+            }
+        };
+
+        // One unit = the wave's NC columns of one panel over KT row tiles; the next unit's matrix vectors
+        // and x_j are in flight while this one is used.  A unit is always 1 + KT*NC loads, whatever it
+        // holds, so the number of loads in flight is known at every point of the walk: a lane whose VEC
+        // rows are not all stored in the column (the diagonal crosses them, they lie beyond the matrix,
+        // the tile lies on the other side of the diagonal) loads the nearest 16 bytes of the column's
+        // stored part instead and moves the elements into place when the unit is used.  What the use
+        // needs to know travels with the buffer: the first tile gt, the panel p, and flags (bit q: tile
+        // q is fast; LAST: the piece ends with this unit; PAST: the walk is over, the loads are cheap
+        // stand-ins that keep the pipeline's shape, every lane reading the first stored vector of its
+        // column, and the use changes nothing).
+        constexpr int F_LAST = 1 << 8, F_PAST = 1 << 9;
+        struct Unit { int gt, p, fl; };
+        Walk it;
+        const int lane_row = lane * VEC;
+        auto issue = [&](Vec<T>(&b)[KT][NC], T& xr, Unit& u) {
+            const bool past = it.pp >= npieces;
+            u.gt = it.gg * KT;
+            u.p = pfirst + it.pp;
+            u.fl = past ? F_PAST : (it.ss == it.nu - 1 ? F_LAST : 0);
+            xr = *it.xcol;
 #pragma unroll
             for (int q = 0; q < KT; ++q) {
-                bool valid, fast;
-                tile_flags(jg, g * KT + q, valid, fast);
-                if (!valid) continue;
-                const int slot = (g * KT + q) * TR + lane * VEC;
+                if (!past && u.gt + q >= it.fa && u.gt + q < it.fb) u.fl |= 1 << q;
+                const int r = (past ? -(1 << 30) : row0 + (u.gt + q) * TR) + lane_row;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const int slo = LOWER ? it.cj[c] : 0, top = LOWER ? n - VEC : it.cj[c] + 1 - VEC;
+                    const int rc = max(min(r, top), slo);   // slo <= top: the column holds VEC stored rows
+                    b[q][c] = load_stream(it.col[c] + rc);
+                }
+            }
+            advance(it);
+        };
+        auto use = [&](const Vec<T>(&b)[KT][NC], const T& xr, const Unit& u) {
+            const int jg = u.p * C + w * NC;
+            T xjb[NC];   // wave-uniform
+#pragma unroll
+            for (int c = 0; c < NC; ++c) xjb[c] = read_lane(xr, c);
+#pragma unroll
+            for (int q = 0; q < KT; ++q) {
+                const int slot = (u.gt + q) * TR + lane_row;
                 Vec<T> xi, an;
                 __builtin_memcpy(&xi, &xs[slot], sizeof(xi));
                 __builtin_memcpy(&an, &rs[w][slot], sizeof(an));
-                if (fast) {
+                if (u.fl & (1 << q)) {
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -461,17 +491,22 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
                 } else {
                     // pairs outside the stored triangle are skipped, the diagonal feeds
                     // only the row sum and HEMV takes its real part
-                    const int rq = row0 + slot;
+                    const int r = row0 + slot;
+                    const bool past = (u.fl & F_PAST) != 0;
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        const int row = rq + v;
-                        const bool rowok = row >= 0 && row < n;
+                    for (int c = 0; c < NC; ++c) {
+                        const int j = jg + c;
+                        const bool exists = !past && j >= jlo && j < jhi;
+                        const int jc = j < jlo ? jlo : (j >= jhi ? jhi - 1 : j);
+                        const int slo = LOWER ? jc : 0, shi = LOWER ? n : jc + 1;
+                        const int rc = r < slo ? slo : (r > shi - VEC ? shi - VEC : r);
+                        const Vec<T> sv = shift_elems(b[q][c], r - rc);
 #pragma unroll
-                        for (int c = 0; c < NC; ++c) {
-                            const int j = jg + c;
-                            const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
+                        for (int v = 0; v < VEC; ++v) {
+                            const int row = r + v;
+                            const bool ins = exists && row >= slo && row < shi;
                             const bool dia = (row == j);
-                            const T av = b[q][c].e[v];
+                            const T av = sv.e[v];
                             const T ad = select_of(HERM && dia, real_part_only(av), av);
                             T nn = an.e[v], nt = accT[c];
                             fma_acc(nn, ad, xjb[c]);
@@ -483,8 +518,8 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
                 }
                 __builtin_memcpy(&rs[w][slot], &an, sizeof(an));
             }
-            if (last) {
-                // panel finished: column sums of this wave's NC columns, lane c keeps column c
+            if (u.fl & F_LAST) {
+                // piece finished: column sums of this wave's NC columns, lane c keeps column c
                 T mine = zero_of<T>();
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
@@ -492,25 +527,15 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
                     mine = select_of(lane == c, sum, mine);
                     accT[c] = zero_of<T>();
                 }
-                if (lane < NC) a.wst[((int64_t)p * nchunks + k) * C + w * NC + lane] = mine;
+                if (lane < NC) a.wst[((int64_t)u.p * nchunks + k) * C + w * NC + lane] = mine;
             }
         };
 
         // the first matrix vectors are on their way while x is staged
-        // next unit to load / to use: piece, step inside the piece, rotated tile group
-        const int g0 = w % gk;
-        int lp = 0, ls = 0, lg = g0, cp = 0, cs = 0, cg = g0;
-        auto step = [&](int& pp, int& ss, int& gg) {
-            if (++gg == gk) gg = 0;
-            if (++ss == gk) {
-                ss = 0;
-                ++pp;
-            }
-        };
-        if (units > 0) {
-            load_unit(b0, xj0, lp, lg);
-            step(lp, ls, lg);
-        }
+        Unit u0, u1;
+        it.pp = 0;
+        enter(it);
+        issue(b0, xr0, u0);
         for (int i = threadIdx.x; i < R; i += NW * WAVE) {
             const int row = row0 + i;
             const int rc = row < 0 ? 0 : (row >= n ? n - 1 : row);
@@ -521,25 +546,21 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
 #pragma unroll
             for (int v = 0; v < VEC; ++v) z.e[v] = zero_of<T>();
 #pragma unroll
-            for (int t = 0; t < CT; ++t) __builtin_memcpy(&rs[w][t * TR + lane * VEC], &z, sizeof(z));
+            for (int t = 0; t < CT; ++t) __builtin_memcpy(&rs[w][t * TR + lane_row], &z, sizeof(z));
         }
         __syncthreads();
-        for (int u = 0; u < units; u += 2) {
-            if (u + 1 < units) {
-                load_unit(b1, xj1, lp, lg);
-                step(lp, ls, lg);
-            }
-            compute_unit(b0, xj0, cp, cg, cs == gk - 1);
-            step(cp, cs, cg);
-            if (u + 1 < units) {
-                if (u + 2 < units) {
-                    load_unit(b0, xj0, lp, lg);
-                    step(lp, ls, lg);
-                }
-                compute_unit(b1, xj1, cp, cg, cs == gk - 1);
-                step(cp, cs, cg);
-            }
-        }
+        // Every pass of the loop issues two units' loads and uses two units, unconditionally, and the only
+        // exit is at the bottom: no path through the loop holds fewer loads in flight than another, so the
+        // waits in front of a unit's first use cover exactly the loads issued before it.
+        do {
+            issue(b1, xr1, u1);
+            use(b0, xr0, u0);
+            issue(b0, xr0, u0);
+            use(b1, xr1, u1);
+        } while (!(u0.fl & F_PAST));
+        // the stand-in loads issued past the end are never used; waiting for them here (vmcnt(0), the other
+        // counters left alone) tells the compiler that no load is in flight when the next chunk's walk starts
+        __builtin_amdgcn_s_waitcnt(0x0F70);
 
         // leaving the chunk: the NW waves' row sums are added in wave order and
         // stored as row-sum vector number workgroup + chunk
@@ -969,8 +990,8 @@ __global__ __launch_bounds__(TINY_NW * WAVE) void symv_tiny_kernel(SymvArgs<T> a
 // adds the classes g, g+RED_PARTS, ... and then the chunks kbeg+g, kbeg+g+
 // RED_PARTS, ... in ascending order; the parts meet in LDS and are added in
 // part order, so the result does not depend on scheduling.
-template <class T, bool LOWER, bool BAL>
-__global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a) {
+template <class T, bool HERM, bool LOWER, bool BAL>
+__global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a, SymvOwners owners) {
     constexpr int TR = tile_rows<T>();
     const int lx = threadIdx.x, g = threadIdx.y;
     const int64_t i = (int64_t)blockIdx.x * RED_ROWS + lx;
@@ -981,12 +1002,10 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
     if (i < a.n) {
         if (BAL) {
             // row-sum vectors of the workgroups whose share touches the chunk of row i:
-            // numbers ylo..yhi (left by the main kernel), vector y + k each
+            // numbers ylo..yhi (from the host's table of shares), vector y + k each
             const int64_t CT = a.plan.chunk_tiles, slot = i + shift;
             const int64_t k = slot / (CT * TR);
-            int64_t ylo = a.wtab[2 * k], yhi = a.wtab[2 * k + 1];
-            if (ylo < 0) ylo = 0;
-            if (yhi >= a.plan.workers) yhi = a.plan.workers - 1;
+            const int64_t ylo = owners.first[k], yhi = owners.last[k];
             const T* __restrict__ wsn = a.wsn + (slot - k * CT * TR);
 #pragma unroll 4
             for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
@@ -1003,6 +1022,21 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
         const T* __restrict__ wst = a.wst + pi * a.plan.nchunks * C + (i - pi * C);
 #pragma unroll 4
         for (int64_t k = kbeg + g; k < kend; k += RED_PARTS) s = add_of(s, wst[k * C]);
+        // the balanced kernel leaves out the VEC - 1 columns at the tip of the triangle that hold fewer
+        // than VEC stored rows; their few elements are added here, to the outputs they belong to
+        constexpr int VEC = Traits<T>::VEC;
+        if (BAL && VEC > 1 && g == 0) {
+            const int64_t clo = LOWER ? (a.n - VEC + 1 > 0 ? a.n - VEC + 1 : 0) : 0;
+            const int64_t chi = LOWER ? a.n : (VEC - 1 < a.n ? VEC - 1 : a.n);
+            if (i >= clo && i < chi) {
+                for (int64_t k = clo; k < chi; ++k) {
+                    const bool own = LOWER ? i >= k : i <= k;      // a_ik itself is stored (else a_ki)
+                    const T av = own ? a.A[i + k * a.lda] : a.A[k + i * a.lda];
+                    if (own) fma_acc(s, select_of(HERM && i == k, real_part_only(av), av), a.x[k]);
+                    else fma_op<HERM>(s, av, a.x[k]);
+                }
+            }
+        }
     }
     part[g][lx] = s;
     __syncthreads();
@@ -1031,7 +1065,9 @@ template <class T> inline int default_unit_tiles(int64_t n) {
     return (sizeof(T) == 16 && n >= 16384) || (sizeof(T) == 8 && n >= 28672) ? 2 : 1;
 }
 inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }
-constexpr int64_t MAX_WORKERS = 2048;
+// fixed part of a piece's weight on the work line, in row tiles (the column sums and their store, the
+// change of panel): measured, see the tuning key symv_piece_fixed
+constexpr int DEFAULT_PIECE_FIXED = 1;
 // compute units x min(occupancy, wanted workgroups per compute unit), queried once per instance
 template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     constexpr bool HERM = Traits<T>::cplx;
@@ -1063,6 +1099,114 @@ template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
 }
 }  // namespace
 
+// Walks the work line of the balanced kernel in runs of pieces of equal weight: f(chunk, first piece of
+// the run inside the chunk, pieces in the run, weight of each).  Within a chunk the number of stored
+// groups of a piece changes only where the diagonal crosses a group boundary, so a chunk has at most
+// chunk_tiles / unit_tiles + 1 runs and the walk costs a few operations per run.
+template <class T, class F>
+inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int fixed, F&& f) {
+    constexpr int TR = tile_rows<T>();
+    constexpr int C = BAL_NC * SY_NW;
+    const int ntiles = (int)ceil_div(n + shift, TR), nchunks = (int)ceil_div(ntiles, ct), npanels = (int)ceil_div(n, C);
+    for (int k = 0; k < nchunks; ++k) {
+        const int tbeg = k * ct, tend = tbeg + ct < ntiles ? tbeg + ct : ntiles;
+        int64_t plo, phi;
+        if (lower) chunk_panels<true>(tbeg, tend, C, shift, TR, npanels, plo, phi);
+        else chunk_panels<false>(tbeg, tend, C, shift, TR, npanels, plo, phi);
+        int64_t p = plo;
+        while (p < phi) {
+            int glo, ghi;
+            int64_t q;   // first panel after p with another number of stored groups
+            if (lower) {
+                piece_groups<true>((int)p, C, (int)n, shift, TR, kt, tbeg, tend, glo, ghi);
+                // one group fewer from the panel whose first column lies at or below row (tbeg + (glo + 1) kt) TR - shift
+                q = ceil_div((int64_t)(tbeg + (glo + 1) * kt) * TR - shift, C);
+            } else {
+                piece_groups<false>((int)p, C, (int)n, shift, TR, kt, tbeg, tend, glo, ghi);
+                // one group more from the panel whose last column lies at or beyond row (tbeg + ghi kt) TR - shift
+                const int gk = (tend - tbeg + kt - 1) / kt;
+                q = ghi >= gk ? phi : ceil_div((int64_t)(tbeg + ghi * kt) * TR - shift + 1, C) - 1;
+            }
+            if (q > phi) q = phi;
+            if (q <= p) q = p + 1;   // cannot happen (see the two conditions above); keeps the walk finite regardless
+            f(k, (int)(p - plo), (int)(q - p), (ghi - glo) * kt + fixed);
+            p = q;
+        }
+    }
+}
+
+// The shares for one (shape, alignment, tuning): looked up in a small per-thread cache, else computed.
+// `slots` = workgroups wanted (one resident round).  Every share holds at least one piece: the worker
+// count is capped so that a share is at least as long as the heaviest piece.
+template <class T>
+inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int ct, int kt, int64_t slots, int fixed) {
+    constexpr int NCACHE = 8;
+    thread_local SymvBalanced cache[NCACHE];
+    thread_local int used = 0, next = 0;
+    if (slots > SHARE_MAX_WORKERS) slots = SHARE_MAX_WORKERS;
+    if (slots < 1) slots = 1;
+    for (int i = 0; i < used; ++i) {
+        const SymvBalanced& e = cache[i];
+        if (e.n == n && e.shift == shift && e.lower == (int)lower && e.chunk_tiles == ct && e.unit_tiles == kt &&
+            e.slots == (int)slots && e.fixed == fixed)
+            return &e;
+    }
+    SymvBalanced& b = cache[next];
+    next = (next + 1) % NCACHE;
+    if (used < NCACHE) ++used;
+    b.n = n; b.shift = shift; b.lower = lower; b.chunk_tiles = ct; b.unit_tiles = kt; b.slots = (int)slots; b.fixed = fixed;
+    int64_t W = 0, pieces = 0;
+    walk_work_line<T>(lower, n, shift, ct, kt, fixed, [&](int, int, int cnt, int wt) {
+        W += (int64_t)cnt * wt;
+        pieces += cnt;
+    });
+    int64_t Y = slots;
+    const int64_t wmax = ct + fixed;
+    if (Y > W / wmax) Y = W / wmax;
+    if (Y > pieces) Y = pieces;
+    if (Y < 1) Y = 1;
+    b.work = W;
+    b.workers = (int)Y;
+    constexpr int TR = tile_rows<T>();
+    const int nchunks = (int)ceil_div(ceil_div(n + shift, TR), ct);
+    // worker y starts at the first piece whose first unit lies at or after partition's starting point s(y)
+    int64_t pos = 0, y = 0, wy, sy;
+    partition(W, Y, 0, wy, sy);
+    walk_work_line<T>(lower, n, shift, ct, kt, fixed, [&](int k, int j, int cnt, int wt) {
+        const int64_t last_start = pos + (int64_t)(cnt - 1) * wt;
+        while (y < Y && sy <= last_start) {
+            const int64_t idx = sy <= pos ? 0 : (sy - pos + wt - 1) / wt;
+            b.shares.start[y] = ((uint32_t)k << SHARE_PIECE_BITS) | (uint32_t)(j + idx);
+            ++y;
+            if (y < Y) partition(W, Y, y, wy, sy);
+        }
+        pos += (int64_t)cnt * wt;
+    });
+    b.shares.start[Y] = (uint32_t)nchunks << SHARE_PIECE_BITS;
+    for (int64_t i = Y + 1; i <= SHARE_MAX_WORKERS; ++i) b.shares.start[i] = b.shares.start[Y];
+    // owners of every chunk's first and last piece
+    for (int k = 0; k < SHARE_MAX_CHUNKS; ++k) { b.owners.first[k] = 0; b.owners.last[k] = 0; }
+    constexpr uint32_t PIECE_MASK = (1u << SHARE_PIECE_BITS) - 1;
+    for (int64_t yy = Y - 1; yy >= 0; --yy) {
+        const uint32_t e0 = b.shares.start[yy], e1 = b.shares.start[yy + 1];
+        const int ka = (int)(e0 >> SHARE_PIECE_BITS);
+        const int kb = (e1 & PIECE_MASK) ? (int)(e1 >> SHARE_PIECE_BITS) : (int)(e1 >> SHARE_PIECE_BITS) - 1;
+        for (int k = ka; k <= kb && k < SHARE_MAX_CHUNKS; ++k) b.owners.first[k] = (uint16_t)yy;
+    }
+    for (int64_t yy = 0; yy < Y; ++yy) {
+        const uint32_t e0 = b.shares.start[yy], e1 = b.shares.start[yy + 1];
+        const int ka = (int)(e0 >> SHARE_PIECE_BITS);
+        const int kb = (e1 & PIECE_MASK) ? (int)(e1 >> SHARE_PIECE_BITS) : (int)(e1 >> SHARE_PIECE_BITS) - 1;
+        for (int k = ka; k <= kb && k < SHARE_MAX_CHUNKS; ++k) b.owners.last[k] = (uint16_t)yy;
+    }
+    return &b;
+}
+
+template <class T>
+const SymvBalanced* symv_shares(bool lower, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed) {
+    return balanced_shares<T>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed);
+}
+
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda) {
     constexpr int TR = tile_rows<T>();
     SymvPlan<T> p;
@@ -1079,7 +1223,6 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
         const bool drifting = n >= 12000 && ((uint64_t)lda * sizeof(T)) % 16 != 0;
         p.variant = n <= small_n<T>() ? 3 : (drifting ? 1 : 2);
     }
-    if (n > (int64_t)1 << 30 && p.variant == 2) p.variant = 1;   // the balanced kernel keeps row and column numbers in 32 bits
     int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
     if (p.variant == 2) C = BAL_NC * SY_NW;
     // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
@@ -1087,6 +1230,13 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     if (ktw <= 0) {
         if (p.variant == 1) ktw = sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE;
         else ktw = n < (sizeof(T) < 16 ? 16384 : 10000) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay below that
+    }
+    // the balanced kernel loads 16-byte vectors from columns with at least VEC stored rows: it needs some
+    if (p.variant == 2 && n < 4 * Traits<T>::VEC) p.variant = 3;
+    if (p.variant == 2) {
+        // the balanced kernel keeps row and column numbers in 32 bits and its tables hold SHARE_MAX_CHUNKS chunks
+        if (ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ktw = 2;
+        if (n > (int64_t)1 << 30 || ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) p.variant = 1;
     }
     if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
     p.panel_cols = C;
@@ -1107,48 +1257,33 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.work = 0;
     p.unit_tiles = 1;
     p.workers = 0;
+    p.bal = nullptr;
     size_t wsn_bytes;
     if (sizing) {
         // room for either variant: MAX_CLASSES row-sum vectors of all rows, or one
         // vector of the tallest chunk per workgroup and chunk
         p.rows_padded = partial_stride<T>(p.ntiles * TR);
         const size_t chains = (size_t)Q * p.rows_padded * sizeof(T);
-        // workgroups <= pieces: the largest piece count over both triangles, both
-        // chunk heights and all alignments
-        int64_t entries = 0;
-        const int64_t C2 = BAL_NC * SY_NW;
-        for (int64_t kt = 1; kt <= 2; ++kt)
-            for (int sh = 0; sh <= max_row_shift<T>(); ++sh) {
-                const int64_t nt = ceil_div(n + sh, TR), ct = SY_NW * kt, nc = ceil_div(nt, ct), npan = ceil_div(n, C2);
-                int64_t lo = 0, up = 0, plo, tk;
-                for (int64_t k = 0; k < nc; ++k) {
-                    lo += chunk_pieces<true>(k, ct, C2, sh, TR, nt, npan, plo, tk);
-                    up += chunk_pieces<false>(k, ct, C2, sh, TR, nt, npan, plo, tk);
-                }
-                if (lo > entries) entries = lo;
-                if (up > entries) entries = up;
-            }
-        if (entries > MAX_WORKERS) entries = MAX_WORKERS;
-        entries += p.nchunks + 1;
-        const size_t balanced = (size_t)entries * partial_stride<T>(2 * SY_NW * TR) * sizeof(T);
+        // workgroups <= pieces <= chunks x panels, for either chunk height
+        size_t balanced = 0;
+        for (int64_t kw = 1; kw <= 2; ++kw) {
+            const int64_t nc = ceil_div(p.ntiles, SY_NW * kw), npan = ceil_div(n, (int64_t)BAL_NC * SY_NW);
+            int64_t entries = nc * npan < SHARE_MAX_WORKERS ? nc * npan : SHARE_MAX_WORKERS;
+            entries += nc + 1;
+            const size_t bytes = (size_t)entries * partial_stride<T>(kw * SY_NW * TR) * sizeof(T);
+            if (bytes > balanced) balanced = bytes;
+        }
         wsn_bytes = chains > balanced ? chains : balanced;
     } else if (p.variant == 2) {
-        int64_t plo, tk, pieces = 0;
-        for (int64_t k = 0; k < p.nchunks; ++k) {
-            const int64_t len = lower ? chunk_pieces<true>(k, p.chunk_tiles, C, p.shift, TR, p.ntiles, p.npanels, plo, tk)
-                                      : chunk_pieces<false>(k, p.chunk_tiles, C, p.shift, TR, p.ntiles, p.npanels, plo, tk);
-            pieces += len;
-            p.work += len * piece_weight(tk);
-        }
         p.unit_tiles = tuning().symv_unit_tiles > 0 ? (int)tuning().symv_unit_tiles : default_unit_tiles<T>(n);
         int64_t Y = tuning().wg_target > 0 ? tuning().wg_target : balanced_slots<T>(lower, (int)ktw, p.unit_tiles);
         if (Y <= 0) Y = 256 * wgs_per_cu(p.unit_tiles);
-        if (Y > MAX_WORKERS) Y = MAX_WORKERS;
-        if (Y > pieces) Y = pieces;
-        if (Y < 1) Y = 1;
-        p.workers = Y;
+        const int fixed = tuning().symv_piece_fixed > 0 ? (int)tuning().symv_piece_fixed - 1 : DEFAULT_PIECE_FIXED;
+        p.bal = balanced_shares<T>(lower, n, p.shift, (int)p.chunk_tiles, p.unit_tiles, Y, fixed);
+        p.work = p.bal->work;
+        p.workers = p.bal->workers;
         p.rows_padded = partial_stride<T>(p.chunk_tiles * TR);
-        wsn_bytes = (size_t)(Y + p.nchunks) * p.rows_padded * sizeof(T);
+        wsn_bytes = (size_t)(p.workers + p.nchunks) * p.rows_padded * sizeof(T);
     } else {
         p.rows_padded = partial_stride<T>(p.ntiles * TR);
         wsn_bytes = (size_t)Q * p.rows_padded * sizeof(T);
@@ -1159,8 +1294,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     // column sums: one slot per column of every panel and chunk; the bound counts the columns padded to the
     // widest panel (every panel width divides it)
     const size_t wst_cols = sizing ? (size_t)ceil_div(n, (int64_t)128) * 128 : (size_t)p.npanels * C;
-    p.tab_off = p.wst_off + round_up(wst_cols * p.nchunks * sizeof(T), WS_ALIGN);
-    p.total_bytes = p.tab_off + round_up((size_t)p.nchunks * 2 * sizeof(int), WS_ALIGN);
+    p.total_bytes = p.wst_off + round_up(wst_cols * p.nchunks * sizeof(T), WS_ALIGN);
     return p;
 }
 
@@ -1174,13 +1308,14 @@ void launch_main(const SymvArgs<T>& a, hipStream_t s) {
 template <class T, bool HERM, bool LOWER, int KT, int G>
 void launch_balanced(const SymvArgs<T>& a, hipStream_t s) {
     const dim3 grid((unsigned)a.plan.workers);
-    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a);
+    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a,
+                       a.plan.bal->shares);
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
     const int cols = (int)a.plan.panel_cols, ktw = (int)(a.plan.chunk_tiles / SY_NW);
     if (a.plan.variant == 2) {
         const int kt = a.plan.unit_tiles;
-        if (cols != BAL_NC * SY_NW || a.plan.workers < 1) return false;
+        if (cols != BAL_NC * SY_NW || a.plan.workers < 1 || !a.plan.bal) return false;
         if (ktw == 1 && kt == 1) launch_balanced<T, HERM, LOWER, 1, SY_NW>(a, s);
         else if (ktw == 2 && kt == 1) launch_balanced<T, HERM, LOWER, 1, 2 * SY_NW>(a, s);
         else if (ktw == 1 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW / 2>(a, s);
@@ -1291,11 +1426,12 @@ hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int
     const dim3 rgrid((unsigned)ceil_div(a.n, RED_ROWS));
     const dim3 rblock(RED_ROWS, RED_PARTS);
     if (a.plan.variant == 2) {
-        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, true, true>), rgrid, rblock, 0, s, a);
-        else hipLaunchKernelGGL((symv_reduce_kernel<T, false, true>), rgrid, rblock, 0, s, a);
+        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, true, true>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
+        else hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, false, true>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
     } else {
-        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, true, false>), rgrid, rblock, 0, s, a);
-        else hipLaunchKernelGGL((symv_reduce_kernel<T, false, false>), rgrid, rblock, 0, s, a);
+        const SymvOwners none = {};
+        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, true, false>), rgrid, rblock, 0, s, a, none);
+        else hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, false, false>), rgrid, rblock, 0, s, a, none);
     }
     return hipGetLastError();
 }
