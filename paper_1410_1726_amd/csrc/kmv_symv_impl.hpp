@@ -389,6 +389,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
         // tiles [fa, fb) in which every pair of the wave's columns is an ordinary off-diagonal element.
         struct Walk {
             int pp, ss, gg, glo, nu, fa, fb;
+            bool longcols;   // the wave's NC columns all exist and are long ones
             int cj[NC];
             const T* col[NC];
             const T* xcol;
@@ -405,7 +406,8 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
             it.gg = glo + r;
             it.ss = 0;
             const int jg = p * C + w * NC;
-            if (jg >= jlo && jg + NC <= jhi) {
+            it.longcols = jg >= jlo && jg + NC <= jhi;
+            if (it.longcols) {
                 if (LOWER) {
                     const int f = (jg + NC + shift + TR - 1) / TR - tbeg;   // first tile that starts at or below row jg + NC
                     it.fa = f > tf_lo ? f : tf_lo;
@@ -446,7 +448,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
         // q is fast; LAST: the piece ends with this unit; PAST: the walk is over, the loads are cheap
         // stand-ins that keep the pipeline's shape, every lane reading the first stored vector of its
         // column, and the use changes nothing).
-        constexpr int F_LAST = 1 << 8, F_PAST = 1 << 9;
+        constexpr int F_WHOLE = 1 << 4, F_LAST = 1 << 8, F_PAST = 1 << 9;
         struct Unit { int gt, p, fl; };
         Walk it;
         const int lane_row = lane * VEC;
@@ -459,6 +461,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
 #pragma unroll
             for (int q = 0; q < KT; ++q) {
                 if (!past && u.gt + q >= it.fa && u.gt + q < it.fb) u.fl |= 1 << q;
+                else if (!past && it.longcols && u.gt + q >= tf_lo && u.gt + q < tf_hi) u.fl |= F_WHOLE << q;
                 const int r = (past ? -(1 << 30) : row0 + (u.gt + q) * TR) + lane_row;
 #pragma unroll
                 for (int c = 0; c < NC; ++c) {
@@ -488,9 +491,30 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
                             fma_acc(an.e[v], b[q][c].e[v], xjb[c]);
                             fma_op<HERM>(accT[c], b[q][c].e[v], xi.e[v]);
                         }
+                } else if (u.fl & (F_WHOLE << q)) {
+                    // the diagonal crosses the tile, all its rows and the wave's columns exist: a lane's vector
+                    // is used whole when it lies strictly on the stored side of the column's diagonal element
+                    // and not at all otherwise (the vector that holds the diagonal element belongs to the
+                    // final pass), so nothing has to be moved or masked element by element
+                    const int r = row0 + slot;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const int j = jg + c;
+                        const bool whole = LOWER ? r > j : r + VEC - 1 < j;
+                        T nt = accT[c];
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            T nn = an.e[v];
+                            fma_acc(nn, b[q][c].e[v], xjb[c]);
+                            an.e[v] = select_of(whole, nn, an.e[v]);
+                            fma_op<HERM>(nt, b[q][c].e[v], xi.e[v]);
+                        }
+                        accT[c] = select_of(whole, nt, accT[c]);
+                    }
                 } else {
-                    // pairs outside the stored triangle are skipped, the diagonal feeds
-                    // only the row sum and HEMV takes its real part
+                    // edge tiles (rows before the first or beyond the last one, short or missing columns):
+                    // pairs outside the stored triangle are skipped, and so are the pairs whose row lies in
+                    // the same aligned group of VEC rows as the column's diagonal element (final pass)
                     const int r = row0 + slot;
                     const bool past = (u.fl & F_PAST) != 0;
 #pragma unroll
@@ -504,15 +528,13 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) {
                             const int row = r + v;
-                            const bool ins = exists && row >= slo && row < shi;
-                            const bool dia = (row == j);
+                            const bool ins = exists && row >= slo && row < shi && (row + shift) / VEC != (j + shift) / VEC;
                             const T av = sv.e[v];
-                            const T ad = select_of(HERM && dia, real_part_only(av), av);
                             T nn = an.e[v], nt = accT[c];
-                            fma_acc(nn, ad, xjb[c]);
+                            fma_acc(nn, av, xjb[c]);
                             fma_op<HERM>(nt, av, xi.e[v]);
                             an.e[v] = select_of(ins, nn, an.e[v]);
-                            accT[c] = select_of(ins && !dia, nt, accT[c]);
+                            accT[c] = select_of(ins, nt, accT[c]);
                         }
                     }
                 }
@@ -1022,19 +1044,27 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
         const T* __restrict__ wst = a.wst + pi * a.plan.nchunks * C + (i - pi * C);
 #pragma unroll 4
         for (int64_t k = kbeg + g; k < kend; k += RED_PARTS) s = add_of(s, wst[k * C]);
-        // the balanced kernel leaves out the VEC - 1 columns at the tip of the triangle that hold fewer
-        // than VEC stored rows; their few elements are added here, to the outputs they belong to
+        // The balanced kernel leaves two kinds of pairs to this pass: those whose row lies in the same aligned
+        // group of VEC rows as the column's diagonal element (the groups of the lanes' 16-byte vectors: rows
+        // m*VEC - shift ...), and the VEC - 1 columns at the tip of the triangle that hold fewer than VEC stored
+        // rows.  Both are a handful of elements per output.
         constexpr int VEC = Traits<T>::VEC;
-        if (BAL && VEC > 1 && g == 0) {
-            const int64_t clo = LOWER ? (a.n - VEC + 1 > 0 ? a.n - VEC + 1 : 0) : 0;
-            const int64_t chi = LOWER ? a.n : (VEC - 1 < a.n ? VEC - 1 : a.n);
-            if (i >= clo && i < chi) {
-                for (int64_t k = clo; k < chi; ++k) {
-                    const bool own = LOWER ? i >= k : i <= k;      // a_ik itself is stored (else a_ki)
-                    const T av = own ? a.A[i + k * a.lda] : a.A[k + i * a.lda];
-                    if (own) fma_acc(s, select_of(HERM && i == k, real_part_only(av), av), a.x[k]);
-                    else fma_op<HERM>(s, av, a.x[k]);
-                }
+        if (BAL && g == 0) {
+            auto add_pair = [&](int64_t k) {
+                const bool own = LOWER ? i >= k : i <= k;      // a_ik itself is stored (else a_ki)
+                const T av = own ? a.A[i + k * a.lda] : a.A[k + i * a.lda];
+                if (own) fma_acc(s, select_of(HERM && i == k, real_part_only(av), av), a.x[k]);
+                else fma_op<HERM>(s, av, a.x[k]);
+            };
+            const int64_t glo = (i + shift) / VEC * VEC - shift;
+            const int64_t gbeg = glo > 0 ? glo : 0, gend = glo + VEC < a.n ? glo + VEC : a.n;
+            for (int64_t k = gbeg; k < gend; ++k) add_pair(k);
+            if (VEC > 1) {
+                const int64_t clo = LOWER ? (a.n - VEC + 1 > 0 ? a.n - VEC + 1 : 0) : 0;
+                const int64_t chi = LOWER ? a.n : (VEC - 1 < a.n ? VEC - 1 : a.n);
+                if (i >= clo && i < chi)
+                    for (int64_t k = clo; k < chi; ++k)
+                        if (k < gbeg || k >= gend) add_pair(k);
             }
         }
     }
