@@ -50,8 +50,14 @@
  *                        reference BLAS numbers them
  *                          GEMV     : trans 1, m 2, n 3, lda 6, incx 8, incy 11
  *                          SYMV/HEMV: uplo 1, n 2, lda 5, incx 7, incy 10
- *   KMV_ERR_WORKSPACE    workspace is NULL or smaller than the size the
- *                        matching *_workspace_bytes call reports
+ *   KMV_ERR_WORKSPACE    the call needs its workspace and it is NULL, not
+ *                        256-byte aligned or smaller than the size the
+ *                        matching *_workspace_bytes call reports.  A call
+ *                        needs it when x is strided (incx != 1) or when its
+ *                        kernels exchange partial sums: GEMV with split
+ *                        columns or rows, SYMV/HEMV beyond the size of the
+ *                        one-launch kernel (kmv_symv_kernel_variant == 2);
+ *                        otherwise workspace may be NULL
  *   KMV_ERR_NULL         A, x, y, alpha or beta is NULL
  *   KMV_ERR_HIP + e      the HIP runtime reported error e at launch
  *   On any error nothing is enqueued and y is untouched.
@@ -108,7 +114,11 @@ int kmv_zgemv(char trans, int64_t m, int64_t n, const kmv_complex128* alpha, con
  * its `uplo` triangle ('L' or 'U', lower case accepted) is read (Section 6.1
  * kernel 3, Section 6.5 for the diagonal blocks, Algorithm "Upper/Lower
  * SYMV/HEMV").  Each stored off-diagonal element is read once and used for
- * both a_ij*x_j and op(a_ij)*x_i. */
+ * both a_ij*x_j and op(a_ij)*x_i (matrices of at most about 2000 rows go to a
+ * one-launch kernel that reads the cache-resident triangle twice instead).
+ * n beyond what the kernels' tables index (about 139000 rows of 16-byte
+ * elements, more for the others: more than fits the device) is refused with
+ * KMV_ERR_HIP + hipErrorInvalidValue. */
 int kmv_ssymv(char uplo, int64_t n, const float* alpha, const float* A, int64_t lda,
               const float* x, int64_t incx, const float* beta, float* y, int64_t incy,
               void* workspace, size_t workspace_bytes, void* stream);
@@ -452,11 +462,13 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *   gemv_n_row_tiles              row tiles per wave of GEMV-N (1, 2, 4)
  *   gemv_short                    kernels for matrices of a few row tiles:
  *                                 1 = never, 2 = whenever they apply
- *   symv_variant                  SYMV/HEMV main kernel, see below (1, 2, 3)
- *   symv_panel_cols               panel width of variant 1 (16, 32, 64, 128)
+ *   symv_variant                  SYMV/HEMV main kernel, see below (2, 3)
  *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)
- *   symv_classes                  variant 1: chains per row chunk (1..256)
  *   symv_unit_tiles               variant 2: row tiles per prefetch unit (1, 2)
+ *   symv_piece_fixed              variant 2: fixed part of a piece's weight on
+ *                                 the work line, plus one (1..17)
+ *   symv_edge_weight              variant 2: extra weight per edge tile of a
+ *                                 piece, plus one (1..17)
  *   wg_target                     workgroups the split heuristics aim for; for
  *                                 SYMV variant 2 the number of workgroups
  *   symv_member_rows              strided batches: largest n that gets one
@@ -472,11 +484,11 @@ int64_t kmv_get_tuning(const char* key);
 const char* kmv_tuning_keys(void);
 
 /* Which main kernel a kmv_<prec>symv / hemv call with these arguments would
- * launch under the current tuning values: 1 = chains of column panels per row
- * chunk, 2 = balanced shares of (row chunk, panel) pieces (the balanced
- * partition of Section 6.2 applied to the stored triangle), 3 = the
- * single-launch kernel for small matrices (no workspace traffic, every stored
- * element read twice).  Only the address
+ * launch under the current tuning values: 2 = balanced shares of (row chunk,
+ * panel) pieces (the balanced partition of Section 6.2 applied to the stored
+ * triangle), 3 = the single-launch kernel for small matrices (no workspace
+ * traffic; every stored element is read twice, which only pays while the
+ * triangle stays in cache, hence its size limit of about 2000 rows).  Only the address
  * of A is used (its alignment decides), nothing is read or launched.  Returns
  * 0 for an unknown prec or uplo, n < 0 or lda < max(1, n).  For benchmarks
  * and profiles that have to name the kernel they time. */
@@ -486,17 +498,18 @@ int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int6
  * columns) of the stored triangle to its workgroups in contiguous shares of a
  * work line (Section 6.2, Eqs. local_workload / starting_point), on which a
  * piece weighs the row tiles it really holds (`unit_tiles` at a time) plus
- * `fixed`.  This call returns the table the planner computes for such a call:
+ * `fixed`, plus `edge` for every edge tile among them (a tile with rows
+ * before row 0, when shift > 0, or beyond row n - 1).  This call returns the table the planner computes for such a call:
  * start[y] = (chunk << 20) | piece inside the chunk for y = 0 .. workers (the
  * last entry is (number of chunks, 0)); first[k] / last[k] = the workers that
- * hold the first and the last piece of chunk k (arrays of 160 entries); *work
+ * hold the first and the last piece of chunk k (arrays of 272 entries); *work
  * = length of the line.  Host arrays owned by the caller, any of them may be
  * NULL.  shift = leading masked slots of row tile 0 (0 .. rows per tile - 1),
  * chunk_tiles 4 or 8, unit_tiles 1 or 2, slots = workgroups wanted (at most
  * 800 are used).  Returns the number of workers, -1 for arguments out of
  * range.  Nothing is launched; exported for the tests of the host logic. */
 int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots,
-                    int fixed, uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work);
+                    int fixed, int edge, uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work);
 
 const char* kmv_version(void);
 

@@ -97,7 +97,7 @@ def _load() -> ctypes.CDLL:
     lib.kmv_tuning_keys.restype = ctypes.c_char_p
     lib.kmv_symv_kernel_variant.argtypes = [ctypes.c_char, ctypes.c_char, i64, ctypes.c_void_p, i64]
     lib.kmv_symv_kernel_variant.restype = ctypes.c_int
-    lib.kmv_symv_shares.argtypes = [ctypes.c_char, ctypes.c_char, i64, ci, ci, ci, i64, ci, ctypes.c_void_p,
+    lib.kmv_symv_shares.argtypes = [ctypes.c_char, ctypes.c_char, i64, ci, ci, ci, i64, ci, ci, ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(i64)]
     lib.kmv_symv_shares.restype = ci
     lib.kmv_version.restype = ctypes.c_char_p
@@ -537,19 +537,19 @@ def tuning_keys():
 
 
 def symv_kernel_variant(prec, uplo, n, A, lda):
-    """1 (chains) or 2 (balanced shares): the main kernel a symv/hemv call with these
+    """2 (balanced shares) or 3 (one launch): the main kernel a symv/hemv call with these
     arguments launches; A may be a tensor or an integer address"""
     addr = A if isinstance(A, int) else A.data_ptr()
     return int(lib.kmv_symv_kernel_variant(prec.encode(), uplo.encode(), n, ctypes.c_void_p(addr), lda))
 
 
-def symv_shares(prec, uplo, n, shift, chunk_tiles, unit_tiles, slots, fixed):
+def symv_shares(prec, uplo, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge=0):
     """Table of shares of the balanced SYMV/HEMV kernel for these settings: (workers, work,
-    [(chunk, piece)] * (workers + 1), first[160], last[160]); None for arguments out of range."""
+    [(chunk, piece)] * (workers + 1), first[272], last[272]); None for arguments out of range."""
     start = (ctypes.c_uint32 * 801)()
-    first, last = (ctypes.c_uint16 * 160)(), (ctypes.c_uint16 * 160)()
+    first, last = (ctypes.c_uint16 * 272)(), (ctypes.c_uint16 * 272)()
     work = ctypes.c_int64(0)
-    y = int(lib.kmv_symv_shares(prec.encode(), uplo.encode(), n, shift, chunk_tiles, unit_tiles, slots, fixed, start, first,
+    y = int(lib.kmv_symv_shares(prec.encode(), uplo.encode(), n, shift, chunk_tiles, unit_tiles, slots, fixed, edge, start, first,
                                 last, ctypes.byref(work)))
     if y < 0:
         return None

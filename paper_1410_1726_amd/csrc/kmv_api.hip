@@ -89,15 +89,18 @@ int symv_entry(bool herm, char uplo, int64_t n, const T* alpha, const T* A, int6
     if (!dev_scalars && is_zero(al)) return hip_code(launch_scal<T>(n, be, yb, incy, s));
 
     const SymvPlan<T> plan = plan_symv<T>(lower, n, A, lda);
-    if (!workspace || workspace_bytes < plan.total_bytes || ((uintptr_t)workspace % WS_ALIGN) != 0)
+    if (plan.variant == 0) return KMV_ERR_HIP + (int)hipErrorInvalidValue;   // beyond what the kernels index
+    // the one-launch kernel with a contiguous x touches no workspace
+    const bool need_ws = plan.variant == 2 || incx != 1;
+    if (need_ws && (!workspace || workspace_bytes < plan.total_bytes || ((uintptr_t)workspace % WS_ALIGN) != 0))
         return KMV_ERR_WORKSPACE;
     char* ws = static_cast<char*>(workspace);
     SymvArgs<T> a;
     a.n = n; a.lda = lda; a.A = A;
     a.y = yb; a.incy = incy; a.alpha = al; a.beta = be;
     if (dev_scalars) { a.alpha_dev = alpha; a.beta_dev = beta; }
-    a.wsn = reinterpret_cast<T*>(ws + plan.wsn_off);
-    a.wst = reinterpret_cast<T*>(ws + plan.wst_off);
+    a.wsn = plan.variant == 2 ? reinterpret_cast<T*>(ws + plan.wsn_off) : nullptr;
+    a.wst = plan.variant == 2 ? reinterpret_cast<T*>(ws + plan.wst_off) : nullptr;
     a.plan = plan;
     if (incx != 1) {
         T* xp = reinterpret_cast<T*>(ws + plan.xpack_off);
@@ -372,12 +375,11 @@ const Key KEYS[] = {
     {"gemv_t_splits", &Tuning::gemv_t_splits, 0, 256},
     {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
     {"gemv_short", &Tuning::gemv_short, 0, 2},
-    {"symv_panel_cols", &Tuning::symv_panel_cols, 0, 128},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
-    {"symv_classes", &Tuning::symv_classes, 0, 256},
     {"symv_variant", &Tuning::symv_variant, 0, 3},
     {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
     {"symv_piece_fixed", &Tuning::symv_piece_fixed, 0, 17},
+    {"symv_edge_weight", &Tuning::symv_edge_weight, 0, 17},
     {"wg_target", &Tuning::wg_target, 0, 1 << 20},
     {"symv_member_rows", &Tuning::symv_member_rows, 0, 1024},
     {"symv_member_waves", &Tuning::symv_member_waves, 0, 8},
@@ -599,9 +601,7 @@ int kmv_set_tuning(const char* key, int64_t value) {
             if (k.field == &Tuning::gemv_n_row_tiles && value == 3) return -1;
             if (k.field == &Tuning::symv_member_waves && value != 0 && value != 4 && value != 8) return -1;
             if (k.field == &Tuning::symv_small_waves && value != 0 && value != 4 && value != 8 && value != 16) return -1;
-            if (k.field == &Tuning::symv_panel_cols && value != 0 && value != 16 && value != 32 && value != 64 &&
-                value != 128)
-                return -1;
+            if (k.field == &Tuning::symv_variant && value == 1) return -1;
             tuning().*(k.field) = value;
             return 0;
         }
@@ -613,7 +613,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_panel_cols,symv_tiles_per_wave,symv_classes,symv_variant,symv_unit_tiles,symv_piece_fixed,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
@@ -630,10 +630,10 @@ int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int6
 }
 
 int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed,
-                    uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work) {
+                    int edge, uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
     if ((!lower && !upper) || n < 1 || n > ((int64_t)1 << 30) || shift < 0 || (chunk_tiles != 4 && chunk_tiles != 8) ||
-        (unit_tiles != 1 && unit_tiles != 2) || slots < 1 || fixed < 0 || fixed > 16)
+        (unit_tiles != 1 && unit_tiles != 2) || slots < 1 || fixed < 0 || fixed > 16 || edge < 0 || edge > 16)
         return -1;
     const SymvBalanced* b = nullptr;
     int tr = 0;
@@ -646,10 +646,10 @@ int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles,
     }
     if (shift >= tr || ceil_div(ceil_div(n + shift, tr), chunk_tiles) > SHARE_MAX_CHUNKS) return -1;
     switch (prec) {
-        case 's': b = symv_shares<float>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
-        case 'd': b = symv_shares<double>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
-        case 'c': b = symv_shares<cf32>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
-        case 'z': b = symv_shares<cf64>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed); break;
+        case 's': b = symv_shares<float>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge); break;
+        case 'd': b = symv_shares<double>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge); break;
+        case 'c': b = symv_shares<cf32>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge); break;
+        case 'z': b = symv_shares<cf64>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge); break;
     }
     if (!b) return -1;
     if (start) memcpy(start, b->shares.start, sizeof(uint32_t) * (size_t)(b->workers + 1));

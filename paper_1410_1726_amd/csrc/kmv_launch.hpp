@@ -17,12 +17,11 @@ struct Tuning {
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
     int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
     int64_t gemv_short = 0;        // kernels for matrices of a few row tiles: 1 = never, 2 = whenever possible
-    int64_t symv_panel_cols = 0;      // SYMV panel width: 16, 32, 64 or 128 columns
-    int64_t symv_tiles_per_wave = 0;  // SYMV row tiles per wave: 1 or 2
-    int64_t symv_classes = 0;         // SYMV panel classes (chains per row chunk): 1..256
-    int64_t symv_variant = 0;         // SYMV main kernel: 1 = chains, 2 = balanced shares
+    int64_t symv_tiles_per_wave = 0;  // SYMV row-chunk height in units of 4 row tiles: 1 or 2
+    int64_t symv_variant = 0;         // SYMV main kernel: 2 = balanced shares, 3 = one launch
     int64_t symv_unit_tiles = 0;      // balanced kernel: row tiles per prefetch unit (1 or 2)
     int64_t symv_piece_fixed = 0;     // balanced kernel: fixed part of a piece's weight on the work line, plus one
+    int64_t symv_edge_weight = 0;     // balanced kernel: extra weight of a piece per edge tile it holds, plus one
     int64_t wg_target = 0;         // workgroups the heuristics aim for
     int64_t symv_member_rows = 0;     // batches: largest n for the one-workgroup-per-member kernel
     int64_t symv_member_waves = 0;    // batches: waves of that kernel's workgroup (4 or 8)
@@ -126,13 +125,13 @@ template <class T> inline int64_t gemv_tiny_rows(bool notrans) {
 // the last piece of a chunk, which is all the final pass needs to find the chunk's row-sum vectors.
 constexpr int SHARE_MAX_WORKERS = 800;      // 3204 bytes of kernel arguments
 constexpr int SHARE_PIECE_BITS = 20;
-constexpr int SHARE_MAX_CHUNKS = 160;
+constexpr int SHARE_MAX_CHUNKS = 272;
 struct SymvShares { uint32_t start[SHARE_MAX_WORKERS + 1]; };
 struct SymvOwners { uint16_t first[SHARE_MAX_CHUNKS], last[SHARE_MAX_CHUNKS]; };
 struct SymvBalanced {
     // what the table was computed for
     int64_t n;
-    int shift, lower, chunk_tiles, unit_tiles, slots, fixed;
+    int shift, lower, chunk_tiles, unit_tiles, slots, fixed, edge;
     // the table
     int64_t work;     // length of the work line
     int workers;      // shares (workgroups of the main kernel)
@@ -142,15 +141,14 @@ struct SymvBalanced {
 
 template <class T> struct SymvPlan {
     int shift;
-    int variant;           // main kernel: 1 = chains of panels per row chunk, 2 = balanced shares of pieces
+    int variant;           // main kernel: 2 = balanced shares of pieces, 3 = one launch (4: batches, one workgroup per member; 0: refused)
     int unit_tiles;        // variant 2: row tiles per prefetch unit
     int64_t ntiles;        // row tiles covering [-shift, n)
     int64_t panel_cols;    // columns per panel
     int64_t npanels;       // column panels
     int64_t chunk_tiles;   // row tiles per workgroup
     int64_t nchunks;       // row chunks
-    int64_t classes;       // a chain takes every classes-th panel of its row chunk
-    int64_t rows_padded;   // distance between two row-sum vectors (variant 1: >= ntiles * tile_rows; 2: >= chunk rows)
+    int64_t rows_padded;   // distance between two row-sum vectors (>= chunk rows)
     int64_t work;          // variant 2: length of the work line (stored row tiles of all pieces plus a fixed part per piece)
     int64_t workers;       // variant 2: workgroups of the main kernel
     const SymvBalanced* bal;   // variant 2: the shares (host memory of the planner, valid until the thread's next few plans)
@@ -159,7 +157,8 @@ template <class T> struct SymvPlan {
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
 // the table of shares for given settings (what plan_symv looks up for the balanced kernel; exported for tests)
 template <class T>
-const SymvBalanced* symv_shares(bool lower, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed);
+const SymvBalanced* symv_shares(bool lower, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed,
+                                int edge);
 
 template <class T> struct SymvArgs {
     int64_t n, lda;
@@ -177,7 +176,7 @@ template <class T> struct SymvArgs {
     const T* const* x_ptrs = nullptr;
     T* const* y_ptrs = nullptr;
     int64_t y_shift = 0;
-    T* wsn;           // row sums ("N part"): [classes][rows_padded], or [workgroup + chunk][rows_padded]
+    T* wsn;           // row sums ("N part"): [workgroup + chunk][rows_padded]
     T* wst;           // [npanels][nchunks][panel_cols]  column sums ("T part")
     SymvPlan<T> plan;
 };

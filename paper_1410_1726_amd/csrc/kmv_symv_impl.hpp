@@ -11,36 +11,17 @@
 // to a separate kernel that mirrors them in shared memory (Section 6.5).
 //
 // Kept: the dual use of each element, the register double buffer, blocks of
-// the stored triangle as the unit of work.  Three main kernels follow, each
-// with its own description: symv_kernel (chains of panels per row chunk, the
-// first design, still chosen for large matrices whose columns are not 16-byte
-// aligned), symv_balanced_kernel (equal shares of the triangle's pieces for one
-// resident round of workgroups, the default) and symv_small_kernel (one launch,
-// no workspace, for small matrices); strided batches of small matrices have
-// symv_member_kernel (one workgroup per matrix).  What the first one does differently from
-// the paper, to fit wave64 and what was measured on the MI355X (small writes
-// scattered through a read stream cost far more than their bytes; a workgroup
-// that reads a few columns over several KiB of consecutive rows streams at full
-// speed; each of the 8 XCDs has its own L2):
-//  * lanes map to 16-byte row vectors, a wave streams 1 KiB of a column per
-//    instruction;
-//  * a workgroup owns a chunk of NW*KTW row tiles and walks HORIZONTALLY over
-//    a chain of column panels (every Q-th panel that the chunk's rows touch),
-//    each wave keeping the non-transposed row sums of its own KTW tiles in
-//    registers for the whole chain: they are stored once per chain into a
-//    workspace indexed [class][row], instead of once per block;
-//  * inside a panel the workgroup sweeps groups of NC columns, so at any
-//    moment it reads NC columns over NW consecutive KiB; the next group is in
-//    flight (registers) while the current one is used, across panel borders;
-//  * the transposed column sums are reduced across the wave once per column
-//    group (DPP), meet the other waves' in LDS once per panel (one barrier per
-//    panel, none inside) and go to a workspace indexed [panel][chunk][column];
-//  * diagonal and edge tiles are handled in the same kernel and the same
-//    prefetch pipeline by element loads that never touch the other triangle,
-//    so the mirrored copy of Section 6.5 is never built;
-//  * consecutive workgroup ids differ in the class, so every XCD sees all row
-//    offsets (with a power-of-two leading dimension the lines of one row range
-//    in all columns share few L2 sets), and long chains are dispatched first.
+// the stored triangle as the unit of work, the balanced partition of Section
+// 6.2.  Two main kernels follow, each with its own description:
+// symv_balanced_kernel (equal shares of the triangle's pieces for one resident
+// round of workgroups) and symv_small_kernel (one launch, no workspace, for
+// small matrices); strided batches of small matrices have symv_member_kernel
+// (one workgroup per matrix) and symv_tiny_kernel (one wave per matrix).  What
+// was measured on the MI355X and shaped them: lanes map to 16-byte row vectors,
+// a wave streams 1 KiB of a column per instruction; small writes scattered
+// through a read stream cost far more than their bytes, so row sums stay on
+// chip for a whole share; each of the 8 XCDs has its own L2; the other
+// triangle is never loaded, so the mirrored copy of Section 6.5 is never built.
 // A second kernel adds, in a fixed order, all row sums and column sums that
 // belong to y_i and applies alpha and beta (no atomics anywhere).
 //
@@ -55,13 +36,6 @@ namespace kmv {
 
 namespace {
 constexpr int SY_NW = 4;    // waves per workgroup
-// columns per column group (with two tiles per wave: 8 loads in flight per lane
-// and buffer, three workgroups per compute unit)
-template <class T> constexpr int sy_nc() { return 4; }
-constexpr int DEFAULT_PANEL_COLS = 16;
-constexpr int64_t TARGET_CHAINS = 2048;   // chains (workgroups) the class count aims at
-constexpr int DEFAULT_TILES_PER_WAVE = 2;
-constexpr int MAX_CLASSES = 256;
 constexpr int RED_ROWS = 16, RED_PARTS = 16;
 }  // namespace
 
@@ -90,203 +64,6 @@ __host__ __device__ __forceinline__ void chunk_panels(int64_t tbeg, int64_t tend
         const int64_t need = tbeg * TR - shift + 1;
         plo = need > 0 ? (need + C - 1) / C - 1 : 0;
         phi = npanels;
-    }
-}
-
-template <class T, bool HERM, bool LOWER, int NC, int CGS, int KTW, int NW>
-__global__ __launch_bounds__(NW * WAVE, 3) void symv_kernel(SymvArgs<T> a) {
-    constexpr int VEC = Traits<T>::VEC;
-    constexpr int TR = WAVE * VEC;
-    constexpr int C = NC * CGS;
-    constexpr int CT = NW * KTW;
-    const int lane = threadIdx.x & (WAVE - 1);
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
-    const int64_t n = a.n, lda = a.lda;
-    const int shift = a.plan.shift;
-    const int64_t ntiles = a.plan.ntiles;
-    const T* __restrict__ x = a.x;
-
-    // chain = (chunk k, class cls); long chains first: the bottom chunks for
-    // 'L', the top chunks for 'U'
-    const int64_t Q = a.plan.classes;
-    const int64_t cls = (int64_t)blockIdx.x % Q, kord = (int64_t)blockIdx.x / Q;
-    const int64_t k = LOWER ? (a.plan.nchunks - 1 - kord) : kord;
-    const int64_t tbeg = k * CT;
-    int64_t tend = tbeg + CT;
-    if (tend > ntiles) tend = ntiles;
-    int64_t plo, phi;
-    chunk_panels<LOWER>(tbeg, tend, C, shift, TR, a.plan.npanels, plo, phi);
-    const int64_t p0 = plo + ((cls - plo) % Q + Q) % Q;            // first panel of the class
-    const int64_t np = p0 < phi ? (phi - p0 + Q - 1) / Q : 0;      // panels of this chain
-    const int64_t units = np * CGS;
-
-    // this wave's row tiles, their x segment and their row-sum accumulators
-    int64_t tq[KTW], rq[KTW];
-    bool inrange[KTW], rowfull[KTW];
-    Vec<T> xi[KTW];
-    T accN[KTW][VEC];
-#pragma unroll
-    for (int q = 0; q < KTW; ++q) {
-        tq[q] = tbeg + w + (int64_t)NW * q;
-        inrange[q] = tq[q] < tend;
-        const int64_t r0 = tq[q] * TR - shift;
-        rowfull[q] = inrange[q] && r0 >= 0 && r0 + TR <= n;
-        rq[q] = r0 + (int64_t)lane * VEC;
-        if (rowfull[q]) {
-            xi[q] = load_cached(x + rq[q]);
-        } else {
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                const int64_t row = rq[q] + v;
-                const int64_t rc = row < 0 ? 0 : (row >= n ? n - 1 : row);
-                xi[q].e[v] = select_of(inrange[q] && row >= 0 && row < n, x[rc], zero_of<T>());
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) accN[q][v] = zero_of<T>();
-    }
-
-    __shared__ T tpart[2][NW][C];
-
-    // per panel: which of this wave's tiles carry stored elements at all (valid)
-    // and which are "fast": all rows exist, the panel is full width and every
-    // (row, column) pair lies strictly inside the stored triangle
-    auto tile_flags = [&](int64_t p, bool(&valid)[KTW], bool(&fast)[KTW]) {
-        const int64_t J0 = p * C;
-        int64_t tlo, thi;
-        panel_tiles<LOWER>(J0, C, n, shift, TR, ntiles, tlo, thi);
-        const bool ragged = (J0 + C > n);
-#pragma unroll
-        for (int q = 0; q < KTW; ++q) {
-            const int64_t r0 = tq[q] * TR - shift;
-            valid[q] = inrange[q] && tq[q] >= tlo && tq[q] < thi;
-            fast[q] = valid[q] && rowfull[q] && !ragged && (LOWER ? (r0 > J0 + C - 1) : (r0 + TR - 1 < J0));
-        }
-    };
-
-    // one unit of work = one column group (NC columns) of one panel over all KTW
-    // tiles of the wave; the next unit's matrix vectors and x_j scalars are in
-    // flight while the current one is being used
-    Vec<T> b0[KTW][NC], b1[KTW][NC];
-    T xj0[NC], xj1[NC];
-    auto load_unit = [&](Vec<T>(&buf)[KTW][NC], T(&xjb)[NC], int64_t u) {
-        const int64_t p = p0 + Q * (u / CGS);
-        const int64_t jg = p * C + (u % CGS) * NC;
-        bool valid[KTW], fast[KTW];
-        tile_flags(p, valid, fast);
-#pragma unroll
-        for (int q = 0; q < KTW; ++q) {
-            if (fast[q]) {
-                const T* src = a.A + jg * lda + rq[q];
-#pragma unroll
-                for (int c = 0; c < NC; ++c) buf[q][c] = load_stream(src + (int64_t)c * lda);
-            } else if (valid[q]) {
-                // edge / diagonal tile: element loads into the same buffer; a pair
-                // outside the stored triangle loads the (always stored) diagonal
-                // element of its column instead and is skipped at use
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    const int64_t row = rq[q] + v;
-                    const bool rowok = row >= 0 && row < n;
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        const int64_t j = jg + c;
-                        const int64_t jc = j < n ? j : n - 1;
-                        const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
-                        buf[q][c].e[v] = load_elem_stream(a.A + (ins ? row : jc) + jc * lda);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < NC; ++c) xjb[c] = select_of(jg + c < n, x[jg + c < n ? jg + c : n - 1], zero_of<T>());
-    };
-    auto compute_unit = [&](const Vec<T>(&buf)[KTW][NC], const T(&xjb)[NC], int64_t u) {
-        const int64_t pi = u / CGS;
-        const int cg = (int)(u % CGS);
-        const int64_t p = p0 + Q * pi;
-        const int64_t jg = p * C + (int64_t)cg * NC;
-        bool valid[KTW], fast[KTW];
-        tile_flags(p, valid, fast);
-        T accT[NC];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) accT[c] = zero_of<T>();
-#pragma unroll
-        for (int q = 0; q < KTW; ++q) {
-            if (fast[q]) {
-#pragma unroll
-                for (int c = 0; c < NC; ++c)
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        fma_acc(accN[q][v], buf[q][c].e[v], xjb[c]);
-                        fma_op<HERM>(accT[c], buf[q][c].e[v], xi[q].e[v]);
-                    }
-            } else if (valid[q]) {
-                // edge / diagonal tile (element-loaded above): pairs outside the
-                // stored triangle are skipped, the diagonal feeds only the row sum
-                // and HEMV takes its real part
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    const int64_t row = rq[q] + v;
-                    const bool rowok = row >= 0 && row < n;
-#pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        const int64_t j = jg + c;
-                        const bool ins = rowok && j < n && (LOWER ? row >= j : row <= j);
-                        const bool dia = (row == j);
-                        const T av = buf[q][c].e[v];
-                        const T an = select_of(HERM && dia, real_part_only(av), av);
-                        T nn = accN[q][v], nt = accT[c];
-                        fma_acc(nn, an, xjb[c]);
-                        fma_op<HERM>(nt, av, xi[q].e[v]);
-                        accN[q][v] = select_of(ins, nn, accN[q][v]);
-                        accT[c] = select_of(ins && !dia, nt, accT[c]);
-                    }
-                }
-            }
-        }
-        T(&tp)[NW][C] = tpart[pi & 1];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const T s = wave_sum(accT[c]);
-            if (lane == 0) tp[w][cg * NC + c] = s;
-        }
-        if (cg == CGS - 1) {
-            // panel finished: the column sums of the NW waves meet in LDS and are
-            // added in wave order.  tpart alternates between two copies, so one
-            // barrier per panel is enough.
-            __syncthreads();
-            if (threadIdx.x < C) {
-                const int c = threadIdx.x;
-                T s = tp[0][c];
-#pragma unroll
-                for (int ww = 1; ww < NW; ++ww) s = add_of(s, tp[ww][c]);
-                a.wst[(p * a.plan.nchunks + k) * C + c] = s;
-            }
-        }
-    };
-
-    if (units > 0) load_unit(b0, xj0, 0);
-    for (int64_t u = 0; u < units; u += 2) {
-        if (u + 1 < units) load_unit(b1, xj1, u + 1);
-        compute_unit(b0, xj0, u);
-        if (u + 1 < units) {
-            if (u + 2 < units) load_unit(b0, xj0, u + 2);
-            compute_unit(b1, xj1, u + 1);
-        }
-    }
-
-    // row sums of the whole chain: one 16-byte store per lane and tile into
-    // wsn[class][row slot] (zeros where the chain had nothing to add)
-    T* __restrict__ wsn = a.wsn + cls * a.plan.rows_padded + shift;
-#pragma unroll
-    for (int q = 0; q < KTW; ++q) {
-        if (inrange[q]) {
-            Vec<T> o;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) o.e[v] = accN[q][v];
-            store_vec_stream(wsn + rq[q], o);
-        }
     }
 }
 
@@ -1007,12 +784,12 @@ __global__ __launch_bounds__(TINY_NW * WAVE) void symv_tiny_kernel(SymvArgs<T> a
     }
 }
 
-// y_i = alpha * ( sum over classes of wsn[class][i] + sum over chunks of
-// wst[panel(i)][chunk][i] ) + beta*y_i.  blockDim = (RED_ROWS, RED_PARTS): part g
-// adds the classes g, g+RED_PARTS, ... and then the chunks kbeg+g, kbeg+g+
-// RED_PARTS, ... in ascending order; the parts meet in LDS and are added in
-// part order, so the result does not depend on scheduling.
-template <class T, bool HERM, bool LOWER, bool BAL>
+// y_i = alpha * ( sum over the workgroups whose share touches the chunk of row i of their row-sum
+// vectors + sum over chunks of wst[panel(i)][chunk][i] + the pairs left to this pass ) + beta*y_i.
+// blockDim = (RED_ROWS, RED_PARTS): part g adds the vectors g, g+RED_PARTS, ... and then the chunks
+// kbeg+g, kbeg+g+RED_PARTS, ... in ascending order; the parts meet in LDS and are added in part
+// order, so the result does not depend on scheduling.
+template <class T, bool HERM, bool LOWER>
 __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a, SymvOwners owners) {
     constexpr int TR = tile_rows<T>();
     const int lx = threadIdx.x, g = threadIdx.y;
@@ -1022,7 +799,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
     __shared__ T part[RED_PARTS][RED_ROWS];
     T s = zero_of<T>();
     if (i < a.n) {
-        if (BAL) {
+        {
             // row-sum vectors of the workgroups whose share touches the chunk of row i:
             // numbers ylo..yhi (from the host's table of shares), vector y + k each
             const int64_t CT = a.plan.chunk_tiles, slot = i + shift;
@@ -1031,10 +808,6 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
             const T* __restrict__ wsn = a.wsn + (slot - k * CT * TR);
 #pragma unroll 4
             for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
-        } else {
-            const T* __restrict__ wsn = a.wsn + i + shift;
-#pragma unroll 4
-            for (int64_t q = g; q < a.plan.classes; q += RED_PARTS) s = add_of(s, wsn[q * a.plan.rows_padded]);
         }
         // chunks whose row tiles intersect the tile range of the panel of column i
         const int64_t pi = i / C;
@@ -1049,7 +822,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
         // m*VEC - shift ...), and the VEC - 1 columns at the tip of the triangle that hold fewer than VEC stored
         // rows.  Both are a handful of elements per output.
         constexpr int VEC = Traits<T>::VEC;
-        if (BAL && g == 0) {
+        if (g == 0) {
             auto add_pair = [&](int64_t k) {
                 const bool own = LOWER ? i >= k : i <= k;      // a_ik itself is stored (else a_ki)
                 const T av = own ? a.A[i + k * a.lda] : a.A[k + i * a.lda];
@@ -1086,19 +859,31 @@ constexpr int SMALL_NC = 8;            // small-matrix kernel: outputs per workg
 // largest n the small-matrix kernel is chosen for (measured against the two-launch path at n = 1024 .. 3072:
 // it wins up to 2048 in d, up to about 1792 in s, c and z, and loses by 20-50% from 2560 on)
 template <class T> constexpr int64_t small_n() { return sizeof(T) == 8 && !Traits<T>::cplx ? 2048 : 1792; }
-// Row tiles per unit (KT) and workgroups per compute unit that go with it, measured
-// with the settings alternating in one process: two tiles (8 loads per lane and
-// buffer) with two workgroups per compute unit for 16-byte elements from n = 16384
-// and 8-byte elements from n = 28672 on (1-3% faster there, 3-5% slower at
-// n = 8192), otherwise one tile (4 loads) with three workgroups per compute unit.
-template <class T> inline int default_unit_tiles(int64_t n) {
-    return (sizeof(T) == 16 && n >= 16384) || (sizeof(T) == 8 && n >= 28672) ? 2 : 1;
+// Row tiles per unit (KT), chunk height and workgroups per compute unit, measured with the settings
+// alternating in one process over n = 2560 .. 32768 in all four precisions: one tile per unit (4 matrix
+// loads and one of x per lane and buffer) is never slower than two; ONE workgroup per compute unit is
+// fastest from a few hundred megabytes of triangle on (the kernel's loads are pipelined by the wave itself,
+// and more resident workgroups only lengthen the queues in front of the memory channels: DSYMV 16384
+// 164 us against 176-178 us with two or three per compute unit), two below; chunks of 8 row tiles pay for
+// 16-byte elements from n = 8192 and for 8-byte elements from about n = 20000 (2-10%), 4 tiles elsewhere.
+template <class T> inline int default_unit_tiles(int64_t) { return 1; }
+inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }   // the most the kernel instances are built for
+template <class T> inline int default_wgs_per_cu(int64_t n) {
+    const double bytes = 0.5 * (double)n * (double)n * sizeof(T);
+    return bytes >= (sizeof(T) == 16 ? 600e6 : 200e6) ? 1 : 2;
 }
-inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }
+template <class T> inline int64_t default_tiles_per_wave(int64_t n) {
+    if (sizeof(T) == 4) return 1;
+    return n >= (sizeof(T) == 16 ? 8192 : 20480) ? 2 : 1;
+}
 // fixed part of a piece's weight on the work line, in row tiles (the column sums and their store, the
 // change of panel): measured, see the tuning key symv_piece_fixed
 constexpr int DEFAULT_PIECE_FIXED = 1;
-// compute units x min(occupancy, wanted workgroups per compute unit), queried once per instance
+// what an edge tile costs on top of an ordinary one, in row tiles (tuning key symv_edge_weight)
+// measured at n = 17001 (one ragged tile at the bottom of every column): one tile's worth for 8- and 16-byte
+// elements, three for 4-byte ones (four elements per lane to move into place)
+template <class T> constexpr int default_edge_weight() { return sizeof(T) == 4 ? 3 : 1; }
+// compute units and min(occupancy, most workgroups wanted per compute unit), queried once per instance
 template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     constexpr bool HERM = Traits<T>::cplx;
     int dev = 0, cus = 0, nb = 0;
@@ -1109,7 +894,7 @@ template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
                                                          SY_NW * WAVE, 0);
     (void)hipGetLastError();
     if (e != hipSuccess || cus <= 0 || nb <= 0) return -1;
-    return (int64_t)cus * (nb < wgs_per_cu(KT) ? nb : wgs_per_cu(KT));
+    return ((int64_t)cus << 8) | (nb < wgs_per_cu(KT) ? nb : wgs_per_cu(KT));   // compute units, workgroups that fit on one
 }
 template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
     static int64_t cache[MAX_CACHED_DEVICES][2][3][3] = {};
@@ -1134,7 +919,7 @@ template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
 // groups of a piece changes only where the diagonal crosses a group boundary, so a chunk has at most
 // chunk_tiles / unit_tiles + 1 runs and the walk costs a few operations per run.
 template <class T, class F>
-inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int fixed, F&& f) {
+inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int fixed, int edge, F&& f) {
     constexpr int TR = tile_rows<T>();
     constexpr int C = BAL_NC * SY_NW;
     const int ntiles = (int)ceil_div(n + shift, TR), nchunks = (int)ceil_div(ntiles, ct), npanels = (int)ceil_div(n, C);
@@ -1143,6 +928,10 @@ inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int
         int64_t plo, phi;
         if (lower) chunk_panels<true>(tbeg, tend, C, shift, TR, npanels, plo, phi);
         else chunk_panels<false>(tbeg, tend, C, shift, TR, npanels, plo, phi);
+        // groups of the chunk that hold an edge tile (rows before row 0 or beyond row n - 1): their pairs are
+        // masked and moved element by element, which costs `edge` row tiles' worth of time on top
+        const int ge0 = (k == 0 && shift > 0) ? 0 : -1;
+        const int ge1 = (tend == ntiles && (int64_t)ntiles * TR - shift > n) ? (tend - 1 - tbeg) / kt : -1;
         int64_t p = plo;
         while (p < phi) {
             int glo, ghi;
@@ -1159,7 +948,8 @@ inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int
             }
             if (q > phi) q = phi;
             if (q <= p) q = p + 1;   // cannot happen (see the two conditions above); keeps the walk finite regardless
-            f(k, (int)(p - plo), (int)(q - p), (ghi - glo) * kt + fixed);
+            const int edges = (ge0 >= glo && ge0 < ghi ? 1 : 0) + (ge1 >= glo && ge1 < ghi && ge1 != ge0 ? 1 : 0);
+            f(k, (int)(p - plo), (int)(q - p), (ghi - glo) * kt + fixed + edges * edge);
             p = q;
         }
     }
@@ -1169,7 +959,7 @@ inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int
 // `slots` = workgroups wanted (one resident round).  Every share holds at least one piece: the worker
 // count is capped so that a share is at least as long as the heaviest piece.
 template <class T>
-inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int ct, int kt, int64_t slots, int fixed) {
+inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int ct, int kt, int64_t slots, int fixed, int edge) {
     constexpr int NCACHE = 8;
     thread_local SymvBalanced cache[NCACHE];
     thread_local int used = 0, next = 0;
@@ -1178,20 +968,20 @@ inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int
     for (int i = 0; i < used; ++i) {
         const SymvBalanced& e = cache[i];
         if (e.n == n && e.shift == shift && e.lower == (int)lower && e.chunk_tiles == ct && e.unit_tiles == kt &&
-            e.slots == (int)slots && e.fixed == fixed)
+            e.slots == (int)slots && e.fixed == fixed && e.edge == edge)
             return &e;
     }
     SymvBalanced& b = cache[next];
     next = (next + 1) % NCACHE;
     if (used < NCACHE) ++used;
-    b.n = n; b.shift = shift; b.lower = lower; b.chunk_tiles = ct; b.unit_tiles = kt; b.slots = (int)slots; b.fixed = fixed;
+    b.n = n; b.shift = shift; b.lower = lower; b.chunk_tiles = ct; b.unit_tiles = kt; b.slots = (int)slots; b.fixed = fixed; b.edge = edge;
     int64_t W = 0, pieces = 0;
-    walk_work_line<T>(lower, n, shift, ct, kt, fixed, [&](int, int, int cnt, int wt) {
+    walk_work_line<T>(lower, n, shift, ct, kt, fixed, edge, [&](int, int, int cnt, int wt) {
         W += (int64_t)cnt * wt;
         pieces += cnt;
     });
     int64_t Y = slots;
-    const int64_t wmax = ct + fixed;
+    const int64_t wmax = ct + fixed + 2 * edge;
     if (Y > W / wmax) Y = W / wmax;
     if (Y > pieces) Y = pieces;
     if (Y < 1) Y = 1;
@@ -1202,7 +992,7 @@ inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int
     // worker y starts at the first piece whose first unit lies at or after partition's starting point s(y)
     int64_t pos = 0, y = 0, wy, sy;
     partition(W, Y, 0, wy, sy);
-    walk_work_line<T>(lower, n, shift, ct, kt, fixed, [&](int k, int j, int cnt, int wt) {
+    walk_work_line<T>(lower, n, shift, ct, kt, fixed, edge, [&](int k, int j, int cnt, int wt) {
         const int64_t last_start = pos + (int64_t)(cnt - 1) * wt;
         while (y < Y && sy <= last_start) {
             const int64_t idx = sy <= pos ? 0 : (sy - pos + wt - 1) / wt;
@@ -1233,108 +1023,85 @@ inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int
 }
 
 template <class T>
-const SymvBalanced* symv_shares(bool lower, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed) {
-    return balanced_shares<T>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed);
+const SymvBalanced* symv_shares(bool lower, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed,
+                                int edge) {
+    return balanced_shares<T>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge);
 }
 
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda) {
     constexpr int TR = tile_rows<T>();
+    constexpr int64_t C = BAL_NC * SY_NW;
     SymvPlan<T> p;
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
-    // Main kernel.  Measured with the two kernels alternating in one process: the
-    // balanced kernel is faster (by up to 10-30% below n = 8192 and for 16-byte
-    // elements, 3-8% when all columns start at the same offset inside an 8 KiB
-    // stretch) or equal, except for large matrices whose columns are not 16-byte
-    // aligned, where the chain kernel's longer runs per column win 2-3%.
+    // main kernel: the one-launch kernel up to small_n, the balanced kernel beyond
     p.variant = (int)tuning().symv_variant;
-    if (p.variant <= 0) {
-        const bool drifting = n >= 12000 && ((uint64_t)lda * sizeof(T)) % 16 != 0;
-        p.variant = n <= small_n<T>() ? 3 : (drifting ? 1 : 2);
-    }
-    int64_t C = tuning().symv_panel_cols > 0 ? tuning().symv_panel_cols : DEFAULT_PANEL_COLS;
-    if (p.variant == 2) C = BAL_NC * SY_NW;
-    // chunks of about 1024 rows (512 for 16-byte elements): one 256-row tile per wave in single precision
-    int64_t ktw = tuning().symv_tiles_per_wave;
-    if (ktw <= 0) {
-        if (p.variant == 1) ktw = sizeof(T) == 4 ? 1 : DEFAULT_TILES_PER_WAVE;
-        else ktw = n < (sizeof(T) < 16 ? 16384 : 10000) ? 1 : DEFAULT_TILES_PER_WAVE;   // measured: finer pieces pay below that
-    }
+    if (p.variant <= 0) p.variant = n <= small_n<T>() ? 3 : 2;
     // the balanced kernel loads 16-byte vectors from columns with at least VEC stored rows: it needs some
     if (p.variant == 2 && n < 4 * Traits<T>::VEC) p.variant = 3;
-    if (p.variant == 2) {
-        // the balanced kernel keeps row and column numbers in 32 bits and its tables hold SHARE_MAX_CHUNKS chunks
-        if (ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ktw = 2;
-        if (n > (int64_t)1 << 30 || ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) p.variant = 1;
-    }
-    if (sizing) { C = 16; ktw = 1; }   // sizing takes the settings that need the most room
+    // chunk height in units of 4 row tiles
+    int64_t ktw = tuning().symv_tiles_per_wave;
+    if (ktw <= 0) ktw = default_tiles_per_wave<T>(n);
+    // the balanced kernel's tables hold SHARE_MAX_CHUNKS chunks (enough for every matrix that fits the device's
+    // memory when the chunks are 8 tiles high)
+    if (ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ktw = 2;
+    if (sizing) ktw = 1;   // sizing takes the settings that need the most room
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
     p.chunk_tiles = SY_NW * ktw;
     p.nchunks = ceil_div(p.ntiles, p.chunk_tiles);
-    // classes: a power of two between 32 and 128 that gives about TARGET_CHAINS
-    // chains (measured: fewer chains leave compute units idle at the end, more
-    // only add row-sum vectors), never more than there are panels
-    int64_t Q = tuning().symv_classes;
-    if (Q <= 0) {
-        Q = 32;
-        while (Q < 128 && Q * p.nchunks < TARGET_CHAINS) Q *= 2;
-    }
-    if (sizing) Q = MAX_CLASSES;
-    else if (Q > p.npanels) Q = p.npanels;
-    p.classes = Q;
     p.work = 0;
     p.unit_tiles = 1;
     p.workers = 0;
     p.bal = nullptr;
-    size_t wsn_bytes;
+    size_t wsn_bytes = 0;
     if (sizing) {
-        // room for either variant: MAX_CLASSES row-sum vectors of all rows, or one
-        // vector of the tallest chunk per workgroup and chunk
-        p.rows_padded = partial_stride<T>(p.ntiles * TR);
-        const size_t chains = (size_t)Q * p.rows_padded * sizeof(T);
-        // workgroups <= pieces <= chunks x panels, for either chunk height
-        size_t balanced = 0;
+        // one row-sum vector of the chunk's height per workgroup and chunk; workgroups <= pieces <= chunks x
+        // panels, for either chunk height
+        p.rows_padded = partial_stride<T>(2 * SY_NW * TR);
         for (int64_t kw = 1; kw <= 2; ++kw) {
-            const int64_t nc = ceil_div(p.ntiles, SY_NW * kw), npan = ceil_div(n, (int64_t)BAL_NC * SY_NW);
-            int64_t entries = nc * npan < SHARE_MAX_WORKERS ? nc * npan : SHARE_MAX_WORKERS;
+            const int64_t nc = ceil_div(p.ntiles, SY_NW * kw);
+            int64_t entries = nc * p.npanels < SHARE_MAX_WORKERS ? nc * p.npanels : SHARE_MAX_WORKERS;
             entries += nc + 1;
             const size_t bytes = (size_t)entries * partial_stride<T>(kw * SY_NW * TR) * sizeof(T);
-            if (bytes > balanced) balanced = bytes;
+            if (bytes > wsn_bytes) wsn_bytes = bytes;
         }
-        wsn_bytes = chains > balanced ? chains : balanced;
     } else if (p.variant == 2) {
+        if (n > (int64_t)1 << 30 || p.nchunks > SHARE_MAX_CHUNKS) {
+            p.variant = 0;   // beyond what the kernel's 32-bit row numbers and tables hold: the launch is refused
+            p.total_bytes = 0;
+            return p;
+        }
         p.unit_tiles = tuning().symv_unit_tiles > 0 ? (int)tuning().symv_unit_tiles : default_unit_tiles<T>(n);
-        int64_t Y = tuning().wg_target > 0 ? tuning().wg_target : balanced_slots<T>(lower, (int)ktw, p.unit_tiles);
-        if (Y <= 0) Y = 256 * wgs_per_cu(p.unit_tiles);
+        int64_t Y = tuning().wg_target;
+        if (Y <= 0) {
+            // one resident round: compute units x workgroups per compute unit (never more than fit)
+            const int64_t q = balanced_slots<T>(lower, (int)ktw, p.unit_tiles);
+            const int64_t cus = q > 0 ? q >> 8 : 256, fit = q > 0 ? q & 255 : wgs_per_cu(p.unit_tiles);
+            const int64_t want = default_wgs_per_cu<T>(n);
+            Y = cus * (want < fit ? want : fit);
+        }
         const int fixed = tuning().symv_piece_fixed > 0 ? (int)tuning().symv_piece_fixed - 1 : DEFAULT_PIECE_FIXED;
-        p.bal = balanced_shares<T>(lower, n, p.shift, (int)p.chunk_tiles, p.unit_tiles, Y, fixed);
+        const int edge = tuning().symv_edge_weight > 0 ? (int)tuning().symv_edge_weight - 1 : default_edge_weight<T>();
+        p.bal = balanced_shares<T>(lower, n, p.shift, (int)p.chunk_tiles, p.unit_tiles, Y, fixed, edge);
         p.work = p.bal->work;
         p.workers = p.bal->workers;
         p.rows_padded = partial_stride<T>(p.chunk_tiles * TR);
         wsn_bytes = (size_t)(p.workers + p.nchunks) * p.rows_padded * sizeof(T);
     } else {
-        p.rows_padded = partial_stride<T>(p.ntiles * TR);
-        wsn_bytes = (size_t)Q * p.rows_padded * sizeof(T);
+        p.rows_padded = 0;   // the one-launch kernels use no partial sums
     }
     p.xpack_off = 0;
     p.wsn_off = round_up((size_t)n * sizeof(T), WS_ALIGN);
     p.wst_off = p.wsn_off + round_up(wsn_bytes, WS_ALIGN);
-    // column sums: one slot per column of every panel and chunk; the bound counts the columns padded to the
-    // widest panel (every panel width divides it)
-    const size_t wst_cols = sizing ? (size_t)ceil_div(n, (int64_t)128) * 128 : (size_t)p.npanels * C;
-    p.total_bytes = p.wst_off + round_up(wst_cols * p.nchunks * sizeof(T), WS_ALIGN);
+    // column sums: one slot per column of every panel and chunk
+    const size_t wst_bytes = (sizing || p.variant == 2) ? (size_t)p.npanels * C * p.nchunks * sizeof(T) : 0;
+    p.total_bytes = p.wst_off + round_up(wst_bytes, WS_ALIGN);
     return p;
 }
 
 namespace {
-template <class T, bool HERM, bool LOWER, int C, int KTW>
-void launch_main(const SymvArgs<T>& a, hipStream_t s) {
-    const dim3 grid((unsigned)(a.plan.nchunks * a.plan.classes));
-    hipLaunchKernelGGL((symv_kernel<T, HERM, LOWER, sy_nc<T>(), C / sy_nc<T>(), KTW, SY_NW>), grid, dim3(SY_NW * WAVE),
-                       0, s, a);
-}
 template <class T, bool HERM, bool LOWER, int KT, int G>
 void launch_balanced(const SymvArgs<T>& a, hipStream_t s) {
     const dim3 grid((unsigned)a.plan.workers);
@@ -1353,16 +1120,7 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
         else return false;
         return true;
     }
-    if (cols == 16 && ktw == 1) launch_main<T, HERM, LOWER, 16, 1>(a, s);
-    else if (cols == 16 && ktw == 2) launch_main<T, HERM, LOWER, 16, 2>(a, s);
-    else if (cols == 32 && ktw == 1) launch_main<T, HERM, LOWER, 32, 1>(a, s);
-    else if (cols == 32 && ktw == 2) launch_main<T, HERM, LOWER, 32, 2>(a, s);
-    else if (cols == 64 && ktw == 1) launch_main<T, HERM, LOWER, 64, 1>(a, s);
-    else if (cols == 64 && ktw == 2) launch_main<T, HERM, LOWER, 64, 2>(a, s);
-    else if (cols == 128 && ktw == 1) launch_main<T, HERM, LOWER, 128, 1>(a, s);
-    else if (cols == 128 && ktw == 2) launch_main<T, HERM, LOWER, 128, 2>(a, s);
-    else return false;
-    return true;
+    return false;
 }
 }  // namespace
 
@@ -1413,7 +1171,7 @@ void launch_member(const SymvArgs<T>& a, bool lower, unsigned batch, hipStream_t
 template <class T, bool HERM>
 hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int64_t batch) {
     static_assert(!HERM || Traits<T>::cplx, "Hermitian kernels exist for complex types only");
-    if (batch < 1 || batch > 65535 || (batch > 1 && a.plan.variant < 3)) return hipErrorInvalidValue;
+    if (batch < 1 || batch > 65535 || a.plan.variant < 2 || (batch > 1 && a.plan.variant < 3)) return hipErrorInvalidValue;
     if (a.plan.variant == 4) {   // members of a batch: one workgroup per matrix
         constexpr int VEC = Traits<T>::VEC;
         // One wave per member, several columns per load when they are short: measured on 1 GiB batches against
@@ -1455,14 +1213,8 @@ hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int
     if (e != hipSuccess) return e;
     const dim3 rgrid((unsigned)ceil_div(a.n, RED_ROWS));
     const dim3 rblock(RED_ROWS, RED_PARTS);
-    if (a.plan.variant == 2) {
-        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, true, true>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
-        else hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, false, true>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
-    } else {
-        const SymvOwners none = {};
-        if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, true, false>), rgrid, rblock, 0, s, a, none);
-        else hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, false, false>), rgrid, rblock, 0, s, a, none);
-    }
+    if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, true>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
+    else hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, false>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
     return hipGetLastError();
 }
 

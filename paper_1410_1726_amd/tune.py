@@ -98,7 +98,7 @@ def _coarse_grid(routine: str, m: int, n: int) -> dict:
         return {"gemv_n_row_tiles": [1, 2, 4], "gemv_n_splits": [0, 8, 32, 128]}
     if name == "gemv":
         return {"gemv_t_splits": [0, 1, 2, 4, 8, 16]}
-    variants = [1, 2] + ([3] if n <= 4096 else [])
+    variants = [2] + ([3] if n <= 4096 else [])
     return {"symv_variant": variants, "symv_tiles_per_wave": [1, 2], "symv_unit_tiles": [1, 2]}
 
 
@@ -115,10 +115,7 @@ def _fine_grid(routine: str, best: dict) -> dict:
     if name == "gemv":
         return {}
     if best.get("symv_variant") == 2:
-        fixed["wg_target"] = [0, 512, 768, 1024]
-        return fixed
-    if best.get("symv_variant") == 1:
-        fixed["symv_classes"] = [0, 32, 64, 128]
+        fixed["wg_target"] = [0, 256, 512, 768]
         return fixed
     return {}
 

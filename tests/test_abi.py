@@ -66,7 +66,9 @@ def test_symv_argument_errors(prec):
     assert call(incy=0) == -10
     assert call(A=None) == kmv.ERR_NULL
     assert call(n=0, lda=1) == 0
-    assert call() == kmv.ERR_WORKSPACE          # SYMV always needs its workspace
+    # the two-kernel path and a strided x need the workspace (the one-launch kernel with a contiguous x does not)
+    assert call(n=5000, lda=5000) == kmv.ERR_WORKSPACE
+    assert call(incx=2) == kmv.ERR_WORKSPACE
     assert f("u", 4, 0.0, DUMMY, 4, DUMMY, 1, 1.0, DUMMY, 1, workspace=NOWS, stream=0, check=False) == 0
 
 
@@ -109,10 +111,10 @@ def test_workspace_sizes():
 
 def test_tuning_keys_roundtrip():
     keys = kmv.tuning_keys()
-    assert "symv_panel_cols" in keys
+    assert "symv_tiles_per_wave" in keys
     for k in keys:
         old = kmv.get_tuning(k)
-        val = {"symv_panel_cols": 64, "symv_member_waves": 8, "symv_small_waves": 8, "gemv_tiny_rows": 100}.get(k, 2)
+        val = {"symv_member_waves": 8, "symv_small_waves": 8, "gemv_tiny_rows": 100}.get(k, 2)
         kmv.set_tuning(k, val)
         assert kmv.get_tuning(k) == val
         kmv.set_tuning(k, old)
@@ -121,7 +123,7 @@ def test_tuning_keys_roundtrip():
     with pytest.raises(ValueError):
         kmv.set_tuning("gemv_n_splits", 100000)
     with pytest.raises(ValueError):
-        kmv.set_tuning("symv_panel_cols", 96)
+        kmv.set_tuning("symv_variant", 1)           # the value of a kernel that no longer exists
     with pytest.raises(ValueError):
         kmv.set_tuning("symv_member_waves", 6)
     assert "kmv" in kmv.version()
@@ -134,13 +136,13 @@ def test_symv_kernel_variant_query():
     assert kmv.symv_kernel_variant("d", "L", 100, DUMMY, 99) == 0
     for prec in "sdcz":
         for uplo in "LU":
-            assert kmv.symv_kernel_variant(prec, uplo, 5000, DUMMY, 5000) in (1, 2)
+            assert kmv.symv_kernel_variant(prec, uplo, 5000, DUMMY, 5000) == 2
             assert kmv.symv_kernel_variant(prec, uplo, 500, DUMMY, 500) == 3
             edge = 2048 if prec == "d" else 1792             # largest n of the single-launch kernel
             assert kmv.symv_kernel_variant(prec, uplo, edge, DUMMY, edge) == 3
-            assert kmv.symv_kernel_variant(prec, uplo, edge + 1, DUMMY, edge + 1) in (1, 2)
+            assert kmv.symv_kernel_variant(prec, uplo, edge + 1, DUMMY, edge + 1) == 2
     try:
-        for v in (1, 2, 3):
+        for v in (2, 3):
             kmv.set_tuning("symv_variant", v)
             assert kmv.symv_kernel_variant("s", "L", 5000, DUMMY, 5000) == v
     finally:
@@ -198,7 +200,7 @@ def test_offset_argument_errors(prec):
     assert symv(off=-1) == -11 and symv(off=9) == -11
     assert symv(off=8) == 0
     assert symv(A=None) == kmv.ERR_NULL
-    assert symv() == kmv.ERR_WORKSPACE
+    assert symv(n=5008, lda=5008, off=8) == kmv.ERR_WORKSPACE      # the two-kernel path needs its workspace
 
 
 @pytest.mark.parametrize("prec", "sdcz")
@@ -221,7 +223,7 @@ def test_devscalars_argument_errors(prec):
     assert symv(uplo="N") == -1 and symv(n=-1) == -2 and symv(lda=7) == -5 and symv(incx=0) == -7
     assert symv(alpha=None) == kmv.ERR_NULL and symv(A=None) == kmv.ERR_NULL
     assert symv(n=0, lda=1) == 0
-    assert symv() == kmv.ERR_WORKSPACE
+    assert symv(n=5000, lda=5000) == kmv.ERR_WORKSPACE
 
 
 @pytest.mark.parametrize("prec", "sdcz")

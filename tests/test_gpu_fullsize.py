@@ -128,27 +128,12 @@ def test_rectangular_panels(prec):
         free()
 
 
-# ---- the chain kernel (chosen only for large matrices with drifting column alignment
-# by default) at a large size, forced through the tuning key, and the size that selects it
-def test_symv_chain_kernel_large():
+# ---- a large size whose columns are not 16-byte aligned against each other (lda = n odd): unaligned 16-byte
+# loads and a ragged last row tile in every column
+def test_symv_drifting_alignment_large():
     from paper_1410_1726_amd import binding as k
-    n = 24576
-    host = None
-    try:
-        k.set_tuning("symv_variant", 1)
-        for uplo in "LU":
-            parent = wl.matrix("d", n, n, n, seed=7, device=DEV)
-            _, err, ex = symv_case("d", uplo, n, 1.0, 0.0, lda=n, seed=7, parent=parent, parent_host=host,
-                                   sample=samples(n, 7))
-            host = ex["parent_host"]
-            check("d", err, f"dsymv {uplo} n={n} chain kernel")
-            del parent
-            free()
-    finally:
-        k.set_tuning("symv_variant", 0)
-    del host
-    n = 17001   # lda = n: columns not 16-byte aligned, the default picks the chain kernel
-    assert k.symv_kernel_variant("d", "L", n, 256, n) == 1
+    n = 17001
+    assert k.symv_kernel_variant("d", "L", n, 256, n) == 2
     for uplo in "LU":
         _, err, _ = symv_case("d", uplo, n, 1.0, 0.0, lda=n, seed=8, sample=samples(n, 8))
         check("d", err, f"dsymv {uplo} n={n}")

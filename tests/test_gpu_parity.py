@@ -237,23 +237,25 @@ def test_split_variants_agree_with_oracle():
                 k.set_tuning(key, s)
                 _, err, _ = gemv_case("d", trans, 2100, 1900, 0.7, 0.3, seed=15)
                 check("d", err, f"{key}={s}")
-        for cols, tpw, classes in ((64, 1, 1), (64, 2, 3), (128, 1, 8), (128, 2, 5), (64, 2, 256), (64, 1, 16)):
-            k.set_tuning("symv_panel_cols", cols)
+        k.set_tuning("symv_variant", 2)
+        for tpw, workers, fixed, edge in ((1, 1, 1, 1), (2, 3, 4, 1), (1, 8, 1, 9), (2, 5, 17, 17), (2, 256, 2, 3), (1, 16, 3, 2)):
             k.set_tuning("symv_tiles_per_wave", tpw)
-            k.set_tuning("symv_classes", classes)
+            k.set_tuning("wg_target", workers)
+            k.set_tuning("symv_piece_fixed", fixed)
+            k.set_tuning("symv_edge_weight", edge)
             for prec, n in (("z", 1500), ("s", 2300), ("d", 3001)):
                 for uplo in "LU":
                     _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, seed=16)
-                    check(prec, err, f"symv panel_cols={cols} tiles_per_wave={tpw} classes={classes} {prec} {uplo}")
+                    check(prec, err, f"symv tiles_per_wave={tpw} workers={workers} fixed={fixed} edge={edge} {prec} {uplo}")
     finally:
         for key in k.tuning_keys():
             k.set_tuning(key, 0)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [2, 3])
 @pytest.mark.parametrize("prec", list("sdcz"))
 def test_symv_main_kernel_variants(prec, variant):
-    """the SYMV/HEMV main kernels (chains of panels; balanced shares of pieces; one launch for small matrices), forced
+    """the SYMV/HEMV main kernels (balanced shares of pieces; one launch for small matrices), forced
     through the tuning key, over ragged sizes, sub-block offsets, chunk heights and
     workgroup counts that make one share span several row chunks"""
     k = kmv()
@@ -261,7 +263,6 @@ def test_symv_main_kernel_variants(prec, variant):
         k.set_tuning("symv_variant", variant)
         for tpw, target, unit in ((0, 0, 0), (1, 3, 1), (2, 1, 2), (1, 256, 2), (2, 7, 1)):
             k.set_tuning("symv_tiles_per_wave", tpw)
-            k.set_tuning("symv_classes", target)
             k.set_tuning("wg_target", target)
             k.set_tuning("symv_unit_tiles", unit)
             for n, off, lda in ((1, 0, None), (63, 0, None), (257, 0, 300), (1500, 17, 1792), (2048, 0, 2048),
@@ -290,7 +291,7 @@ def test_complex_symmetric_symv(prec, uplo):
     got_h, _, _ = symv_case(prec, uplo, 300, 1.0, 0.0, dist="smallint", seed=5)
     assert not np.array_equal(got_s, got_h)
     try:
-        for variant, unit in ((0, 0), (1, 0), (2, 1), (2, 2), (3, 0)):
+        for variant, unit in ((0, 0), (2, 1), (2, 2), (3, 0)):
             k.set_tuning("symv_variant", variant)
             k.set_tuning("symv_unit_tiles", unit)
             for n, off, lda, incx, incy in ((1000, 0, None, 1, 1), (1500, 17, 1792, -2, 1), (2048, 0, 2048, 1, 3),
@@ -465,7 +466,7 @@ def test_scalars_in_device_memory(prec):
             assert torch.equal(got.view(torch.uint8), y0.view(torch.uint8))
             for key in tune:
                 k.set_tuning(key, 0)
-        for variant, n in ((3, 700), (2, 2500), (1, 2500)):
+        for variant, n in ((3, 700), (2, 2500)):
             k.set_tuning("symv_variant", variant)
             for uplo in "LU":
                 A = wl.poison_triangle(wl.matrix(prec, n, n, n + 5, seed=8, device=DEV), n, uplo)
@@ -678,8 +679,7 @@ def test_workspace_bound_is_enough_and_respected(prec):
     guard = 4096
     tunings = [{}, {"gemv_n_splits": 256, "gemv_t_splits": 256}, {"gemv_n_splits": 1, "gemv_t_splits": 1},
                {"gemv_n_row_tiles": 4, "wg_target": 1 << 20}, {"gemv_short": 1}, {"gemv_short": 2},
-               {"symv_variant": 1, "symv_classes": 256, "symv_panel_cols": 16},
-               {"symv_variant": 1, "symv_panel_cols": 128, "symv_tiles_per_wave": 2},
+               {"symv_variant": 2, "symv_tiles_per_wave": 1, "wg_target": 800},
                {"symv_variant": 2, "wg_target": 1 << 20, "symv_unit_tiles": 1},
                {"symv_variant": 2, "wg_target": 1, "symv_unit_tiles": 2, "symv_tiles_per_wave": 2},
                {"symv_variant": 3}]

@@ -13,7 +13,7 @@ TILE_ROWS = {"s": 256, "d": 128, "c": 128, "z": 64}
 C = 16
 
 
-def enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed):
+def enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed, edge=0):
     """[(chunk, piece in chunk, weight)] in line order, from the definition: piece (k, p) exists when some
     stored element (i, j), j in panel p, has its row slot i + shift in chunk k; its weight counts the groups
     of kt row tiles of the chunk that hold such an element, times kt, plus `fixed`."""
@@ -27,7 +27,7 @@ def enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed):
         j = 0
         for p in range(npanels):
             c0, c1 = p * C, min(p * C + C, n) - 1           # columns of the panel
-            groups = 0
+            groups = edges = 0
             for g in range(-(-(tend - tbeg) // kt)):
                 t0, t1 = tbeg + g * kt, min(tbeg + g * kt + kt, tend)
                 r0, r1 = max(t0 * tr - shift, 0), min(t1 * tr - shift, n) - 1      # rows of the group
@@ -36,25 +36,28 @@ def enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed):
                 # lower: some row >= some column of the panel; upper: some row <= some column
                 stored = (r1 >= c0) if uplo == "L" else (r0 <= c1)
                 groups += stored
+                first_tile_cut = (k == 0 and g == 0 and shift > 0)
+                last_tile_cut = (tend == ntiles and g == (tend - 1 - tbeg) // kt and ntiles * tr - shift > n)
+                edges += stored and (first_tile_cut or last_tile_cut)
             if groups:
-                out.append((k, j, groups * kt + fixed))
+                out.append((k, j, groups * kt + fixed + edges * edge))
                 j += 1
     return out, nchunks
 
 
-CASES = [(prec, uplo, n, shift, ct, kt, slots, fixed)
+CASES = [(prec, uplo, n, shift, ct, kt, slots, fixed, edge)
          for prec in "sdcz" for uplo in "LU"
          for n, shift in ((2049, 0), (2600, 5), (4099, 0), (5000, 15), (8192, 1), (12289, 7))
          for ct, kt in ((4, 1), (8, 1), (8, 2), (4, 2))
-         for slots, fixed in ((768, 1), (512, 3), (100, 0))]
+         for slots, fixed, edge in ((768, 1, 2), (512, 3, 0), (100, 0, 1))]
 
 
-@pytest.mark.parametrize("prec,uplo,n,shift,ct,kt,slots,fixed", CASES[::7] + CASES[3::11])
-def test_shares_tile_the_pieces(prec, uplo, n, shift, ct, kt, slots, fixed):
+@pytest.mark.parametrize("prec,uplo,n,shift,ct,kt,slots,fixed,edge", CASES[::7] + CASES[3::11])
+def test_shares_tile_the_pieces(prec, uplo, n, shift, ct, kt, slots, fixed, edge):
     if shift >= TILE_ROWS[prec]:
         shift = TILE_ROWS[prec] - 1
-    pieces, nchunks = enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed)
-    got = kmv.symv_shares(prec, uplo, n, shift, ct, kt, slots, fixed)
+    pieces, nchunks = enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed, edge)
+    got = kmv.symv_shares(prec, uplo, n, shift, ct, kt, slots, fixed, edge)
     assert got is not None
     workers, work, start, first, last = got
     assert work == sum(w for _, _, w in pieces)
