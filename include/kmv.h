@@ -511,6 +511,25 @@ int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int6
 int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots,
                     int fixed, int edge, uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work);
 
+/* kmv_dsymv for callers that cannot allocate or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and errors as kmv_dsymv without the workspace pair:
+ * the partial sums (and the packed copy of a strided x) go to a device array
+ * of KMV_STATIC_SCRATCH_BYTES that is part of the library's code object (each
+ * device the library runs on holds its copy until the process ends).  The
+ * call allocates nothing and frees nothing.  A product whose plan needs more
+ * than the array holds is refused with KMV_ERR_WORKSPACE before anything is
+ * enqueued: with the default tuning DSYMV fits up to about n = 38000
+ * (kmv_symv_workspace_bytes('d', uplo, n) is an upper bound of the need).
+ * The first call on a device looks up the array's address (make it outside a
+ * graph capture).  All calls on a device share the one array: two calls whose
+ * kernels may overlap in time (different streams, or graph branches) race
+ * and give wrong results; calls on one stream are safe.  Nothing in the array
+ * has to be cleared between calls: every slot is written before it is read. */
+#define KMV_STATIC_SCRATCH_BYTES (16u << 20)
+int kmv_dsymv_static(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x,
+                     int64_t incx, const double* beta, double* y, int64_t incy, void* stream);
+
 const char* kmv_version(void);
 
 #ifdef __cplusplus

@@ -100,6 +100,9 @@ def _load() -> ctypes.CDLL:
     lib.kmv_symv_shares.argtypes = [ctypes.c_char, ctypes.c_char, i64, ci, ci, ci, i64, ci, ci, ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(i64)]
     lib.kmv_symv_shares.restype = ci
+    lib.kmv_dsymv_static.argtypes = [ctypes.c_char, i64, ctypes.c_void_p, ctypes.c_void_p, i64, ctypes.c_void_p, i64,
+                                     ctypes.c_void_p, ctypes.c_void_p, i64, ctypes.c_void_p]
+    lib.kmv_dsymv_static.restype = ci
     lib.kmv_version.restype = ctypes.c_char_p
     return lib
 
@@ -225,6 +228,16 @@ def ssymv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream
 
 def dsymv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
     return _symv("dsymv", "d", uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace, stream, check)
+
+
+def dsymv_static(uplo, n, alpha, A, lda, x, incx, beta, y, incy, stream=None, check=True):
+    """kmv_dsymv_static: DSYMV with the library's own static device array as workspace (no allocation anywhere, not
+    even in this wrapper); products that need more than the array holds are refused with ERR_WORKSPACE."""
+    rc = lib.kmv_dsymv_static(uplo.encode(), n, _scalar("d", alpha), _ptr(A, "d"), lda, _ptr(x, "d"), incx,
+                              _scalar("d", beta), _ptr(y, "d"), incy, _stream(stream))
+    if check and rc != 0:
+        raise KmvError("dsymv_static", rc)
+    return rc
 
 
 def chemv(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):

@@ -5,10 +5,22 @@
 // routines do (Section 5.2), with the stream of its "_async" variants.
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/kmv.h"
 #include "kmv_launch.hpp"
 
+// Scratch memory of kmv_dsymv_static: partial sums and the packed x of one product, in place of the caller's
+// workspace.  Every device the library runs on holds its own copy at its own address until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress; the kernels get the looked-up address.
+static __device__ __align__(256) unsigned char static_scratch[KMV_STATIC_SCRATCH_BYTES];
+
 namespace kmv {
+
+namespace {
+std::mutex static_scratch_mutex;
+void* static_scratch_ptr[MAX_CACHED_DEVICES] = {};
+}  // namespace
 
 Tuning& tuning() {
     static Tuning t;
@@ -657,6 +669,30 @@ int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles,
     if (last) memcpy(last, b->owners.last, sizeof(b->owners.last));
     if (work) *work = b->work;
     return b->workers;
+}
+
+int kmv_dsymv_static(char uplo, int64_t n, const double* alpha, const double* A, int64_t lda, const double* x,
+                     int64_t incx, const double* beta, double* y, int64_t incy, void* stream) {
+    // the device address of this device's copy of the array, looked up once per device
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_code(e);
+    if (dev < 0 || dev >= MAX_CACHED_DEVICES) return KMV_ERR_HIP + (int)hipErrorInvalidDevice;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(static_scratch_mutex);
+        if (!static_scratch_ptr[dev]) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+            if (e != hipSuccess) return hip_code(e);
+            if (!p) return KMV_ERR_HIP + (int)hipErrorInvalidSymbol;
+            static_scratch_ptr[dev] = p;
+        }
+        ptr = static_scratch_ptr[dev];
+    }
+    // sizes whose partial sums do not fit the array are refused before anything is enqueued
+    // (symv_entry compares the plan's need with the size given here)
+    return symv_entry<double>(false, uplo, n, alpha, A, lda, x, incx, beta, y, incy, ptr, KMV_STATIC_SCRATCH_BYTES, stream);
 }
 
 const char* kmv_version(void) { return "kmv 0.1 (gfx950)"; }
