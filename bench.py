@@ -4,11 +4,26 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--table FILE]
 
 One "step" is one pass of the whole hot path over one batch of synthetic
-inputs.  The default workload is the size sweep the headline metric is quoted
-on: SGEMV / DGEMV (N and T) and DSYMV / ZHEMV (L and U) on square matrices,
-n = 1024..32768 in steps of 1024 plus n = 1000, 4099, 17001 for GEMV, lda = n,
-entries U[-1,1], seed 0 (268 products per step).  All inputs are resident in
-HBM before the timed region starts.
+inputs.  The default workload `all` runs four groups per step, one after the
+other, each bracketed by device synchronisations:
+
+  sweep      the size sweep the headline metric is quoted on: SGEMV / DGEMV (N
+             and T) and DSYMV / ZHEMV (L and U) on square matrices, n = 1024 ..
+             32768 in steps of 1024 plus n = 1000, 4099, 17001 for GEMV, lda = n,
+             entries U[-1,1], seed 0 (268 products)
+  target16k  all 16 routine x precision products at n = 16384 and 32768
+  large      all 16 at n = 49152 (s, c) / 40960 (d, z), lda = n + 32, N(0,1)
+             entries, incx 1 and 2
+  subblock   DGEMV N, T and DSYMV L on blocks of a 20000 x 20000 parent at
+             offsets 1, 17, 63, 1000
+
+`value` is the sweep group's throughput (the configurations the metric is
+quoted on); every group reports its own throughput and per-routine fractions
+of the HBM peak.  All inputs are resident in HBM before the timed region
+starts; every product whose matrix is smaller than 512 MB works on a region
+of its own, so no product finds its matrix in a cache because another product
+read it (the same small products timed back to back on one region are
+reported separately as `cache_resident`).
 
 The metric follows the paper's performance model (Section 7): algorithmic
 bytes (matrix once, x once, y read and written once; one triangle for the
@@ -32,14 +47,26 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes (read + written) per launch of the main kernels in the default sweep,
-# from the two rocprofv3 --pmc passes (FETCH_SIZE, WRITE_SIZE, each scaled by the
-# reading of the library's copy kernel) summarised in profiles/sweep_hbm_traffic.txt
-MEASURED_TRAFFIC_SWEEP = {
-    "gemv_n_kernel<float>": 1411868258, "gemv_t_kernel<float>": 1409497219,
-    "gemv_n_kernel<double>": 2822087116, "gemv_t_kernel<double>": 2818829902,
-    "symv_balanced_kernel<double>": 1607847445, "symv_balanced_kernel<kmv::cf64>": 3109920319,
-}
+COLD_BYTES = 512e6      # products with a smaller matrix get a region of their own (and a cache-resident timing)
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "sweep_hbm_traffic.txt")
+
+
+def measured_traffic(kernel):
+    """HBM bytes (read + written) per launch of `kernel` in the default benchmark, from the rocprofv3 --pmc
+    summary under profiles/ (lines `traffic kernel=<name> ... bytes_per_launch=<n> library=<version>`), or
+    None when the summary is missing, does not list the kernel or was made with another library version."""
+    from paper_1410_1726_amd import binding as k
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            for line in f:
+                if not line.startswith("traffic "):
+                    continue
+                kv = dict(item.split("=", 1) for item in line.split()[1:] if "=" in item)
+                if kv.get("kernel") == kernel.replace(" ", "") and kv.get("library") == k.version().replace(" ", "_"):
+                    return int(kv["bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
 
 
 def parse():
@@ -47,7 +74,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="sweep", choices=["sweep", "target16k", "large", "subblock", "panel", "sytrd", "gebrd", "batched", "csymv", "rect", "tiny"])
+    ap.add_argument("--workload", default="all", choices=["all", "sweep", "target16k", "large", "subblock", "panel", "sytrd", "gebrd", "batched", "csymv", "rect", "tiny"])
     ap.add_argument("--prec", default="d", choices=list("sdcz"), help="precision of the sytrd / gebrd / batched workloads")
     ap.add_argument("--uplo", default="L", choices=["L", "U"], help="stored triangle of the sytrd workload")
     ap.add_argument("--table", default=None, help="write per-(routine, n) JSON lines to this file")
@@ -62,6 +89,12 @@ def parse():
 def products(workload):
     """List of dicts describing the products of one step."""
     out = []
+    if workload == "all":
+        for group in ("sweep", "target16k", "large", "subblock"):
+            for p in products(group):
+                p["group"] = group
+                out.append(p)
+        return out
     if workload == "sweep":
         sizes = [1024 * k for k in range(1, 33)]
         for prec in "sd":
@@ -148,24 +181,38 @@ def kernel_name(p):
     return f"{ {1: 'symv_kernel', 2: 'symv_balanced_kernel', 3: 'symv_small_kernel'}[variant] }<{t}>"
 
 
-class Inputs:
-    """Device buffers: per (precision, distribution) one flat matrix buffer as large
-    as the largest product needs (each product views it with its own lda) and one
-    x / y pair.  Filled once, before anything is timed.  The unreferenced triangle
-    of the symmetric products holds ordinary random numbers here: it is never
-    loaded, so its content cannot change the timing (the parity tests run the same
-    shapes with that triangle set to NaN)."""
+def matrix_span(p):
+    """elements of the flat buffer that the product's matrix (or its parent) spans"""
+    cols = p.get("parent", 0) or p["n"]
+    return p["lda"] * cols
 
-    def __init__(self, prods, torch, wl):
-        need, vlen = {}, {}
-        for p in prods:
+
+class Inputs:
+    """Device buffers: per (precision, distribution) one flat matrix buffer and one x / y pair.  A product views
+    the buffer with its own lda; a product whose matrix is smaller than COLD_BYTES views a region of its own (the
+    regions of one buffer are laid end to end), so that its matrix is not in a cache because another product
+    just read the same addresses; the large ones all start at the front, each of them alone replaces whatever
+    the caches held.  Filled once, before anything is timed.  The unreferenced triangle of the symmetric
+    products holds ordinary random numbers here (one buffer serves all sizes, so there is no one triangle to
+    poison): it is never loaded, so its content cannot change the timing; the parity tests run the same shapes
+    with that triangle set to NaN, and check_poisoned() below runs one poisoned product per routine."""
+
+    def __init__(self, prods, torch, wl, acc):
+        need, vlen, small = {}, {}, {}
+        esize = {"s": 4, "d": 8, "c": 8, "z": 16}
+        self.offset = {}
+        for i, p in enumerate(prods):
             key = (p["prec"], p.get("dist", "uniform"))
-            cols = p.get("parent", 0) or p["n"]
-            need[key] = max(need.get(key, 0), p["lda"] * cols)
+            span = matrix_span(p)
+            need[key] = max(need.get(key, 0), span)
             vlen[key] = max(vlen.get(key, 0), 1 + (max(p["n"], p.get("m", 0)) - 1) * abs(p.get("incx", 1)))
+            if span * esize[p["prec"]] < COLD_BYTES and not p.get("parent"):
+                self.offset[i] = small.get(key, 0)
+                small[key] = self.offset[i] + (span + 63) // 64 * 64
         self.mat, self.vec = {}, {}
         for key, elems in need.items():
             prec, dist = key
+            elems = max(elems, small.get(key, 0))
             flat = torch.empty(elems, dtype=wl.TORCH_DTYPES[prec], device="cuda")
             g = torch.Generator(device="cuda")
             g.manual_seed(0)
@@ -174,14 +221,31 @@ class Inputs:
             self.vec[key] = (wl.vector(prec, vlen[key], 1, dist=dist, seed=0, which=1, device="cuda"),
                              wl.vector(prec, vlen[key], 1, dist=dist, seed=0, which=2, device="cuda"))
 
-    def views(self, p):
+    def views(self, i, p, own_region=True):
         key = (p["prec"], p.get("dist", "uniform"))
         n, lda, off = p["n"], p["lda"], p.get("off", 0)
         cols = p.get("parent", 0) or n
-        A2 = self.mat[key][: lda * cols].view(cols, lda)
+        start = self.offset.get(i, 0) if own_region else 0
+        A2 = self.mat[key][start: start + lda * cols].view(cols, lda)
         A = A2[off:, off:] if off else A2
         x, y = self.vec[key]
         return A, x, y
+
+
+def check_poisoned(k, torch, wl):
+    """One product per symmetric routine on a matrix whose unreferenced triangle is NaN (and y NaN, beta = 0):
+    the result must be finite.  Not timed; the element-wise comparison with the oracle is the parity tests'."""
+    n = 4100
+    for prec in "sdcz":
+        for uplo in "LU":
+            A = wl.poison_triangle(wl.matrix(prec, n, n, n + 12, seed=3, device="cuda"), n, uplo)
+            x = wl.vector(prec, n, 1, seed=3, which=1, device="cuda")
+            y = torch.full_like(x, float("nan"))
+            k.SYMV[prec](uplo, n, 1.0, A, n + 12, x, 1, 0.0, y, 1)
+            torch.cuda.synchronize()
+            if not bool(torch.isfinite(torch.view_as_real(y) if y.is_complex() else y).all()):
+                raise RuntimeError(f"bench.py: {prec} symv/hemv {uplo} read the unreferenced triangle or y with beta = 0")
+    return "ok"
 
 
 def make_call(p, k, A, x, y):
@@ -510,22 +574,28 @@ def main():
         print(json.dumps(sytrd_panel_bench(args, k, torch, wl, acc)))
         return
 
-    # largest products first: the host runs ahead of the device, so the short
-    # products at the end of a step are already queued when their turn comes
     probe = stream_probe(k, torch)
-    prods = sorted(products(args.workload), key=lambda p: -p["n"] * p.get("m", p["n"]))
+    poisoned = check_poisoned(k, torch, wl)
+    # within a group the largest products come first: the host runs ahead of the device, so the
+    # short products at the end of a group are already queued when their turn comes
+    prods = products(args.workload)
+    for p in prods:
+        p.setdefault("group", args.workload)
     if args.only:
         import re
         prods = [p for p in prods if re.search(args.only, f"{routine_name(p)}:{p['n']}")]
         if not prods:
             print(f"bench.py: --only {args.only!r} matches no product of workload {args.workload}", file=sys.stderr)
             sys.exit(2)
-    inputs = Inputs(prods, torch, wl)
+    group_names = list(dict.fromkeys(p["group"] for p in prods))
+    prods.sort(key=lambda p: (group_names.index(p["group"]), -p["n"] * p.get("m", p["n"])))
+    inputs = Inputs(prods, torch, wl, acc)
     stream = torch.cuda.current_stream()
-    calls = [make_call(p, k, *inputs.views(p)) for p in prods]
+    calls = [make_call(p, k, *inputs.views(i, p)) for i, p in enumerate(prods)]
     nprod = len(prods)
     per = [dict(bytes=acc.algorithmic_bytes(op_name(p), p["prec"], p.get("m", p["n"]), p["n"]),
                 flops=acc.flops(op_name(p), p["prec"], p.get("m", p["n"]), p["n"]), ms=0.0) for p in prods]
+    members = {g: [i for i, p in enumerate(prods) if p["group"] == g] for g in group_names}
 
     for _ in range(args.warmup):
         for call in calls:
@@ -533,27 +603,54 @@ def main():
     events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in prods]
               for _ in range(args.steps)]
     torch.cuda.synchronize()
-    # timed region: exactly `steps` passes, inputs already resident in HBM; HIP
-    # events on the launch stream bracket every product for the breakdown
-    t0 = time.perf_counter()
+    # timed region: exactly `steps` passes, inputs already resident in HBM; the wall clock runs per group
+    # between two device synchronisations, HIP events on the launch stream bracket every product for the
+    # breakdown
+    group_wall = {g: 0.0 for g in group_names}
+    t_begin = time.perf_counter()
     for step in range(args.steps):
-        for call, (e0, e1) in zip(calls, events[step]):
-            e0.record(stream)
-            call()
-            e1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+        for g in group_names:
+            t0 = time.perf_counter()
+            for i in members[g]:
+                e0, e1 = events[step][i]
+                e0.record(stream)
+                calls[i]()
+                e1.record(stream)
+            torch.cuda.synchronize()
+            group_wall[g] += time.perf_counter() - t0
+    wall = time.perf_counter() - t_begin
     for step in range(args.steps):
         for rec, (e0, e1) in zip(per, events[step]):
             t = e0.elapsed_time(e1)
             rec["ms"] += t / args.steps
             rec.setdefault("all_ms", []).append(t)
 
-    step_ms = wall / args.steps * 1e3          # wall clock between the two synchronisations
+    step_ms = wall / args.steps * 1e3          # wall clock of a whole step (all groups)
     device_ms = sum(r["ms"] for r in per)       # sum of the per-product event brackets
-    tot_bytes = sum(r["bytes"] for r in per)
-    tot_flops = sum(r["flops"] for r in per)
-    value = tot_bytes / (step_ms * 1e-3) / 1e9
+
+    def group_summary(g):
+        idx = members[g]
+        gb = sum(per[i]["bytes"] for i in idx)
+        gf = sum(per[i]["flops"] for i in idx)
+        ms = group_wall[g] / args.steps * 1e3
+        routines, graded = {}, {}
+        for i in idx:
+            p, r = prods[i], per[i]
+            a = routines.setdefault(routine_name(p), [0, 0.0])
+            a[0] += r["bytes"]
+            a[1] += r["ms"]
+            if p["n"] >= 16384:
+                a = graded.setdefault(routine_name(p), [0, 0.0])
+                a[0] += r["bytes"]
+                a[1] += r["ms"]
+        frac = lambda d: {name: round(b / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for name, (b, m) in d.items()}
+        return {"value": round(gb / (ms * 1e-3) / 1e9, 1), "unit": "GB/s", "frac_hbm_peak": round(gb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "ms_per_step": round(ms, 3), "products": len(idx), "gflops": round(gf / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak_by_routine": frac(routines), "frac_hbm_peak_n_ge_16384": frac(graded)}
+
+    groups = {g: group_summary(g) for g in group_names}
+    head = "sweep" if "sweep" in groups else group_names[0]     # the configurations the metric is quoted on
+    value = groups[head]["value"]
 
     # dominant kernel = the main kernel with the largest share of the step time
     by_kernel = {}
@@ -564,7 +661,7 @@ def main():
         d["launches"] += 1
     dom, dd = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
     achieved = dd["bytes"] / (dd["ms"] * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_SWEEP.get(dom) if args.workload == "sweep" and not args.tuning else None
+    traffic = measured_traffic(dom) if args.workload == "all" and not args.tuning and not args.only else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "traffic_source": "profiles/sweep_hbm_traffic.txt (bytes per launch, read + written)" if traffic else None,
@@ -572,47 +669,73 @@ def main():
                 "avg_launch_us": round(dd["ms"] * 1e3 / dd["launches"], 2),
                 "avg_algorithmic_bytes_per_launch": dd["bytes"] // dd["launches"]}
 
-    # fraction of peak per routine over the graded region n >= 16384
-    graded = {}
-    for p, r in zip(prods, per):
-        if p["n"] >= 16384:
-            g = graded.setdefault(routine_name(p), [0, 0.0])
-            g[0] += r["bytes"]
-            g[1] += r["ms"]
-    graded = {name: round(b / (m * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) for name, (b, m) in graded.items()}
+    # the products that fit the last-level cache, timed back to back on ONE region (cache resident) beside
+    # their timing inside the step (own region, cold)
+    small = [i for i, p in enumerate(prods) if i in inputs.offset]
+    cache_resident = None
+    if small:
+        warm_ms, cold_ms, sb = 0.0, 0.0, 0
+        for i in small:
+            call = make_call(prods[i], k, *inputs.views(i, prods[i], own_region=False))
+            for _ in range(2):
+                call()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                call()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            per[i]["warm_ms"] = e0.elapsed_time(e1) / 10
+            warm_ms += per[i]["warm_ms"]
+            cold_ms += per[i]["ms"]
+            sb += per[i]["bytes"]
+        cache_resident = {"products": len(small), "matrix_bytes_below": int(COLD_BYTES),
+                          "cold_gbs": round(sb / (cold_ms * 1e-3) / 1e9, 1), "warm_gbs": round(sb / (warm_ms * 1e-3) / 1e9, 1),
+                          "note": "cold = inside the step, every product on a region of its own; warm = ten calls back to back "
+                                  "on one region (not HBM bandwidth: the matrix stays in the last-level cache)"}
 
     if args.table:
         with open(args.table, "w") as f:
             for p, r in zip(prods, per):
                 gbs = r["bytes"] / (r["ms"] * 1e-3) / 1e9
-                f.write(json.dumps({"routine": routine_name(p), "m": p.get("m", p["n"]), "n": p["n"], "lda": p["lda"], "off": p.get("off", 0),
-                                    "incx": p.get("incx", 1), "us": round(r["ms"] * 1e3, 2),
-                                    "us_min": round(min(r["all_ms"]) * 1e3, 2),
-                                    "us_median": round(sorted(r["all_ms"])[len(r["all_ms"]) // 2] * 1e3, 2),
-                                    "gbs": round(gbs, 1),
-                                    "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                                    "gflops": round(r["flops"] / (r["ms"] * 1e-3) / 1e9, 1)}) + "\n")
+                row = {"group": p["group"], "routine": routine_name(p), "m": p.get("m", p["n"]), "n": p["n"], "lda": p["lda"],
+                       "off": p.get("off", 0), "incx": p.get("incx", 1), "us": round(r["ms"] * 1e3, 2),
+                       "us_min": round(min(r["all_ms"]) * 1e3, 2),
+                       "us_median": round(sorted(r["all_ms"])[len(r["all_ms"]) // 2] * 1e3, 2),
+                       "gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                       "gflops": round(r["flops"] / (r["ms"] * 1e-3) / 1e9, 1)}
+                if "warm_ms" in r:
+                    row["us_cache_resident"] = round(r["warm_ms"] * 1e3, 2)
+                f.write(json.dumps(row) + "\n")
 
+    labels = {
+        "sweep": "configs[1]+configs[2]: SGEMV/DGEMV N,T n=1024..32768 step 1024 + {1000,4099,17001}; "
+                 "DSYMV/ZHEMV L,U n=1024..32768 step 1024, beta=0; lda=n, U[-1,1], seed 0 (the unreferenced triangle holds "
+                 "ordinary numbers here and is never loaded; one NaN-poisoned product per routine is checked before the timing)",
+        "target16k": "all 16 precision x routine products at n=16384 and 32768, lda=n",
+        "large": "configs[4]: n=49152 (s,c) / 40960 (d,z), lda=n+32, N(0,1), alpha=0.7, beta=0.3, incx 1 and 2",
+        "subblock": "configs[3]: blocks of a 20000x20000 fp64 parent at offsets 1,17,63,1000",
+        "panel": "DSYMV L, DGEMV T, DGEMV N on the trailing blocks at offsets 0..64 of a 16384x16384 fp64 parent "
+                 "(one 64-column panel of a two-sided reduction), beta=0",
+        "csymv": "CSYMV/ZSYMV (complex symmetric) beside CHEMV/ZHEMV, L and U, n=16384 and 32768, lda=n",
+        "rect": "S/DGEMV N,T on tall-skinny and short-wide panels (65536x32 .. 4096x16384 and transposes), lda=m",
+        "tiny": "configs[0]: DGEMV N m=n=lda=1024",
+    }
+    workload_label = ("value on " + labels["sweep"] + "; further groups in the same step, each with its own figures: " +
+                      "; ".join(f"{g} = {labels[g]}" for g in group_names if g != "sweep")) if args.workload == "all" else labels[args.workload]
+    precs = sorted({p["prec"] for p in prods if p["group"] == head}, key="sdcz".index)
     out = {
         "metric": "achieved HBM GB/s (algorithmic bytes / time) for xGEMV/xSYMV vs n, 1 GPU",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32+f64+c128" if args.workload == "sweep" else "f32+f64+c64+c128", "data": "synthetic",
-        "config": {"workload": {
-            "sweep": "configs[1]+configs[2]: SGEMV/DGEMV N,T n=1024..32768 step 1024 + {1000,4099,17001}; "
-                     "DSYMV/ZHEMV L,U n=1024..32768 step 1024 (other triangle NaN, beta=0); lda=n, U[-1,1], seed 0",
-            "target16k": "all 16 precision x routine products at n=16384 and 32768, lda=n",
-            "large": "configs[4]: n=49152 (s,c) / 40960 (d,z), lda=n+32, N(0,1), alpha=0.7, beta=0.3, incx 1 and 2",
-            "subblock": "configs[3]: blocks of a 20000x20000 fp64 parent at offsets 1,17,63,1000",
-            "panel": "DSYMV L, DGEMV T, DGEMV N on the trailing blocks at offsets 0..64 of a 16384x16384 fp64 parent "
-                     "(one 64-column panel of a two-sided reduction), beta=0",
-            "csymv": "CSYMV/ZSYMV (complex symmetric) beside CHEMV/ZHEMV, L and U, n=16384 and 32768, lda=n",
-            "rect": "S/DGEMV N,T on tall-skinny and short-wide panels (65536x32 .. 4096x16384 and transposes), lda=m",
-            "tiny": "configs[0]: DGEMV N m=n=lda=1024",
-        }[args.workload], "products_per_step": nprod},
-        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-        "gflops": round(tot_flops / (step_ms * 1e-3) / 1e9, 1),
-        "frac_hbm_peak_n_ge_16384": graded,
+        "dtype": "+".join(DTYPE_NAMES[c] for c in precs), "data": "synthetic",
+        "config": {"workload": workload_label, "products_per_step": nprod, "value_group": head},
+        "frac_hbm_peak": groups[head]["frac_hbm_peak"],
+        "gflops": groups[head]["gflops"],
+        "frac_hbm_peak_n_ge_16384": groups[head]["frac_hbm_peak_n_ge_16384"],
+        "groups": groups,
+        "cache_resident": cache_resident,
+        "poisoned_triangle_check": poisoned,
         "device_ms_per_step": round(device_ms, 3),
         "stream_probe": probe,
         "frac_of_stream_read": round(value / probe["read_gbs"], 4),
