@@ -66,7 +66,7 @@ def check(prec, err: Errors, what=""):
 
 
 def gemv_case(prec, trans, m, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uniform", seed=0,
-              row_off=0, col_off=0, parent=None, sample=None, poison_outside=True):
+              row_off=0, col_off=0, parent=None, sample=None, poison_outside=True, call=None):
     """Run kmv_<prec>gemv and the oracle on one seeded problem.
 
     The matrix is the m x n block at (row_off, col_off) of a parent stored with
@@ -87,7 +87,10 @@ def gemv_case(prec, trans, m, n, alpha, beta, *, lda=None, incx=1, incy=1, dist=
     x = wl.vector(prec, lenx, incx, dist=dist, seed=seed, which=1, device=DEV, gap_value=float("nan"))
     y0 = wl.vector(prec, leny, incy, dist=dist, seed=seed, which=2, device=DEV, gap_value=float("nan"))
     y = y0.clone()
-    k.GEMV[prec](trans, m, n, alpha, A, lda, x, incx, beta, y, incy)
+    if call is not None:
+        call(trans, m, n, alpha, A, lda, x, incx, beta, y, incy)
+    else:
+        k.GEMV[prec](trans, m, n, alpha, A, lda, x, incx, beta, y, incy)
     torch.cuda.synchronize()
     yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
     # positions of y that are not outputs must be bit-unchanged (NaN canaries)
@@ -123,16 +126,18 @@ def gemv_case(prec, trans, m, n, alpha, beta, *, lda=None, incx=1, incy=1, dist=
 
 def symv_case(prec, uplo, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uniform", seed=0,
               off=0, sample=None, nan_imag_diag=False, parent=None, parent_host=None, poison=True,
-              complex_symmetric=False):
+              complex_symmetric=False, oracle_sees_poison=False, call=None):
     """Run kmv symv/hemv (csymv/zsymv with `complex_symmetric`) and the oracle; with `poison` the unreferenced triangle
     and everything outside the block of the parent are NaN on the device (the
     host copy handed to the oracle is taken before: the oracle indexes the
-    stored triangle only)."""
+    stored triangle only; with `oracle_sees_poison` the host copy is taken AFTER the poisoning, so an oracle
+    that indexed the wrong triangle or left the block would return NaN).  `call(uplo, n, alpha, A, lda, x, incx,
+    beta, y, incy)` replaces the plain entry point (other entry points with the same result)."""
     k = kmv()
     lda = max(n + off if lda is None else lda, 1)
     if parent is None:
         parent = wl.matrix(prec, n + off, n + off, lda, dist=dist, seed=seed, device=DEV)
-    if parent_host is None:
+    if parent_host is None and not oracle_sees_poison:
         parent_host = parent.cpu().numpy().reshape(-1)     # before poisoning: the oracle reads only the triangle
     A = parent[off:, off:] if off else parent
     if poison:
@@ -145,13 +150,19 @@ def symv_case(prec, uplo, n, alpha, beta, *, lda=None, incx=1, incy=1, dist="uni
     if nan_imag_diag and prec in "cz":
         d = torch.arange(n, device=DEV)
         torch.view_as_real(A)[d, d, 1] = float("nan")
+    if oracle_sees_poison:
+        assert poison and parent_host is None
+        parent_host = parent.cpu().numpy().reshape(-1)     # NaN everywhere the product must not look
     x = wl.vector(prec, n, incx, dist=dist, seed=seed, which=1, device=DEV, gap_value=float("nan"))
     y0 = wl.vector(prec, n, incy, dist=dist, seed=seed, which=2, device=DEV, gap_value=float("nan"))
     if beta == 0:
         y0.fill_(float("nan"))      # beta = 0: y must not be read
     y = y0.clone()
     assert not (complex_symmetric and nan_imag_diag), "the symmetric product uses the whole diagonal entry"
-    (k.CSYMV if complex_symmetric else k.SYMV)[prec](uplo, n, alpha, A, lda, x, incx, beta, y, incy)
+    if call is not None:
+        call(uplo, n, alpha, A, lda, x, incx, beta, y, incy)
+    else:
+        (k.CSYMV if complex_symmetric else k.SYMV)[prec](uplo, n, alpha, A, lda, x, incx, beta, y, incy)
     torch.cuda.synchronize()
     yh, y0h, xh = y.cpu().numpy(), y0.cpu().numpy(), x.cpu().numpy()
     if abs(incy) > 1 and n:

@@ -58,6 +58,34 @@ def test_symv_sweep_largest(prec):
         free()
 
 
+# ---- EVERY output element at the largest sweep size, in the launch configuration the benchmark times: a
+# mistake confined to one workgroup's share of the work (one row chunk, one 16-column panel) cannot hide
+# between samples
+def test_gemv_every_output_at_32768():
+    n = 32768
+    parent = wl.matrix("d", n, n, n, seed=0, device=DEV)
+    for trans in "NT":
+        _, err, _ = gemv_case("d", trans, n, n, 1.0, 1.0, lda=n, seed=0, parent=parent, poison_outside=False)
+        check("d", err, f"dgemv {trans} n={n}, all outputs")
+    del parent
+    free()
+
+
+@pytest.mark.parametrize("prec", "dz")
+def test_symv_every_output_at_32768(prec):
+    n = 32768
+    host = None
+    for uplo in "LU":
+        parent = wl.matrix(prec, n, n, n, seed=0, device=DEV)      # regenerated: the run poisons it
+        _, err, ex = symv_case(prec, uplo, n, 1.0, 0.0, lda=n, seed=0, parent=parent, parent_host=host, nan_imag_diag=True)
+        host = ex["parent_host"]
+        check(prec, err, f"symv/hemv {prec} {uplo} n={n}, all outputs")
+        del parent
+        free()
+    del host
+    free()
+
+
 # ---- sub-blocks of a 20000 x 20000 fp64 parent, alpha = -1, beta = 1 -----------
 PARENT_N = 20000
 _parent_host = {}
@@ -85,6 +113,23 @@ def test_subblocks_of_20000_parent(off):
         check("d", err, f"dsymv L block n={n} at offset {off}")
         del parent
         free()
+
+
+def test_subblock_every_output():
+    """the largest block at offset 17 of the 20000 x 20000 parent, every output element, and the oracle is handed
+    the parent as the device sees it: NaN outside the block (and in the unreferenced triangle for DSYMV)"""
+    off, n = 17, 19000 - 17
+    for trans in "NT":
+        parent, _ = parent20k()
+        _, err, _ = gemv_case("d", trans, n, n, -1.0, 1.0, lda=PARENT_N, row_off=off, col_off=off, seed=4, parent=parent)
+        check("d", err, f"dgemv {trans} block n={n} at offset {off}, all outputs")
+        del parent
+        free()
+    parent, _ = parent20k()
+    _, err, _ = symv_case("d", "L", n, -1.0, 1.0, lda=PARENT_N, off=off, seed=4, parent=parent, oracle_sees_poison=True)
+    check("d", err, f"dsymv L block n={n} at offset {off}, all outputs")
+    del parent
+    free()
 
 
 def test_release_parent_host_copy():

@@ -252,6 +252,64 @@ def test_split_variants_agree_with_oracle():
             k.set_tuning(key, 0)
 
 
+@pytest.mark.parametrize("prec", list("sdcz"))
+def test_oracle_is_handed_the_poisoned_matrix(prec):
+    """medium sizes with the host copy for the oracle taken AFTER the poisoning: NaN in the unreferenced triangle,
+    in the lda padding and everywhere outside the block, so an oracle loop that left the stored triangle would
+    return NaN and fail the comparison (the GPU result is checked against it element by element as usual)"""
+    for n, off, lda in ((3001, 0, 3008), (4099, 5, 4200), (2500, 17, 2600)):
+        for uplo in "LU":
+            _, err, _ = symv_case(prec, uplo, n, 0.7, 0.3, lda=lda, off=off, seed=n, oracle_sees_poison=True)
+            check(prec, err, f"symv/hemv {prec} {uplo} n={n} off={off}, oracle on the poisoned copy")
+            if prec in "cz":
+                _, err, _ = symv_case(prec, uplo, n, 0.7 - 0.2j, 0.3j, lda=lda, off=off, seed=n, oracle_sees_poison=True,
+                                      complex_symmetric=True)
+                check(prec, err, f"complex symmetric symv {prec} {uplo} n={n} off={off}, oracle on the poisoned copy")
+
+
+@pytest.mark.parametrize("prec", list("sdcz"))
+def test_other_entry_points_against_the_oracle(prec):
+    """the entry points that share kernels with the plain calls, each compared with the ORACLE (not with the
+    plain GPU call): scalars in device memory, the parent + offset forms, also for the complex symmetric product"""
+    k = kmv()
+    dt = wl.TORCH_DTYPES[prec]
+    al_v, be_v = (0.7 - 0.2j, 0.3 + 0.1j) if prec in "cz" else (0.7, 0.3)
+    al = torch.tensor([al_v], dtype=dt, device=DEV)
+    be = torch.tensor([be_v], dtype=dt, device=DEV)
+
+    def dev_gemv(trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
+        k.GEMV_DEVSCALARS[prec](trans, m, n, al, A, lda, x, incx, be, y, incy)
+
+    def dev_symv(uplo, n, alpha, A, lda, x, incx, beta, y, incy):
+        k.SYMV_DEVSCALARS[prec](uplo, n, al, A, lda, x, incx, be, y, incy)
+
+    for trans in "NTC":
+        _, err, _ = gemv_case(prec, trans, 2100, 1900, al_v, be_v, lda=2111, seed=41, call=dev_gemv)
+        check(prec, err, f"{prec}gemv_devscalars {trans}")
+    for n in (900, 3001):            # one-launch kernel and the two-kernel path
+        for uplo in "LU":
+            _, err, _ = symv_case(prec, uplo, n, al_v, be_v, lda=n + 7, seed=42, call=dev_symv)
+            check(prec, err, f"{prec} symv/hemv_devscalars {uplo} n={n}")
+    # parent + offset: the call names the parent (size n + off) and the offset; the oracle gets the block
+    off = 37
+    for n in (800, 2900):
+        def off_symv(uplo, nn, alpha, A, lda, x, incx, beta, y, incy, csym=False):
+            # A, x, y as symv_case passes them describe the block; step back to the parent's first element
+            Ap = A.as_strided((1,), (1,), A.storage_offset() - off * lda - off)
+            xp, yp = torch.zeros(nn + off, dtype=dt, device=DEV), torch.zeros(nn + off, dtype=dt, device=DEV)
+            xp[off:], yp[off:] = x, y
+            (k.CSYMV_OFFSET if csym else k.SYMV_OFFSET)[prec](uplo, nn + off, alpha, Ap, lda, xp, 1, beta, yp, 1, off)
+            assert torch.equal(yp[:off], torch.zeros(off, dtype=dt, device=DEV)), "wrote before the offset"
+            y.copy_(yp[off:])
+        for uplo in "LU":
+            _, err, _ = symv_case(prec, uplo, n, al_v, be_v, lda=n + off + 3, off=off, seed=43, call=off_symv)
+            check(prec, err, f"{prec} symv/hemv_offset {uplo} n={n}")
+            if prec in "cz":
+                _, err, _ = symv_case(prec, uplo, n, al_v, be_v, lda=n + off + 3, off=off, seed=44, complex_symmetric=True,
+                                      call=lambda *a: off_symv(*a, csym=True))
+                check(prec, err, f"{prec} complex symmetric symv_offset {uplo} n={n}")
+
+
 @pytest.mark.parametrize("variant", [2, 3])
 @pytest.mark.parametrize("prec", list("sdcz"))
 def test_symv_main_kernel_variants(prec, variant):

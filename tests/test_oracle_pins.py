@@ -394,6 +394,48 @@ def test_abs_mode_and_sampling(prec):
     assert np.array_equal(parts[idx], fulls[idx])
 
 
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("trans", "TC")
+def test_abs_mode_of_transposed_gemv(prec, trans):
+    """|alpha| (|A|^T |x|) + |beta| |y| from numpy on a rectangular matrix with a padded leading dimension and
+    strided vectors: an ABS loop that walked rows for columns, or used the wrong vector lengths, fails"""
+    rng = np.random.default_rng(17)
+    m, n = 37, 22
+    A, x, y = rnd(rng, prec, (m, n)), rnd(rng, prec, m), rnd(rng, prec, n)
+    alpha, beta = (-0.7 + 0.4j, 0.3 - 0.2j) if prec in "cz" else (-0.7, 0.3)
+    Af, lda = colmajor(A, lda=m + 5)
+    got = logical(oracle.gemv(prec, trans, m, n, alpha, Af, strided(x, 2), beta, strided(y, -3), lda=lda, incx=2, incy=-3,
+                              mode=MODE_ABS), n, -3)
+    want = abs(alpha) * (np.abs(A).astype(np.float64).T @ np.abs(x).astype(np.float64)) + abs(beta) * np.abs(y).astype(np.float64)
+    assert np.allclose(got.real, want, rtol=1e-6) and np.all(np.isfinite(got.real))
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("uplo", "LU")
+def test_abs_mode_of_symv_on_the_completed_matrix(prec, uplo):
+    """ABS mode of SYMV / HEMV (and of the complex symmetric product) against numpy on |S|, S completed from the
+    stored triangle, with the OTHER triangle and the padding NaN in what the oracle sees: a loop that indexed the
+    wrong triangle returns NaN, one that dropped the mirrored part or counted the diagonal twice misses the
+    value; HEMV takes |Re a_ii| on the diagonal, the symmetric product |a_ii|"""
+    rng = np.random.default_rng(19)
+    n = 61
+    A, x, y = rnd(rng, prec, (n, n)), rnd(rng, prec, n), rnd(rng, prec, n)
+    alpha, beta = (0.6 - 0.8j, -0.5j) if prec in "cz" else (-1.25, 0.5)
+    Af, lda = colmajor(poison(A, uplo), lda=n + 3)
+    variants = [(False, prec in "cz")] + ([(True, False)] if prec in "cz" else [])
+    for csym, herm in variants:
+        S = complete(A, uplo, herm)
+        want = abs(alpha) * (np.abs(S).astype(np.float64) @ np.abs(x).astype(np.float64)) + abs(beta) * np.abs(y).astype(np.float64)
+        got = oracle.symv(prec, uplo, n, alpha, Af, x, beta, y, lda=lda, mode=MODE_ABS, complex_symmetric=csym)
+        assert np.all(np.isfinite(got.real)), "the ABS loop touched the unreferenced triangle or the padding"
+        assert np.allclose(got.real, want, rtol=1e-6), (csym, np.max(np.abs(got.real - want)))
+    if prec in "cz":
+        # the two diagonal rules differ when the diagonal has an imaginary part
+        h = oracle.symv(prec, uplo, n, alpha, Af, x, beta, y, lda=lda, mode=MODE_ABS)
+        c = oracle.symv(prec, uplo, n, alpha, Af, x, beta, y, lda=lda, mode=MODE_ABS, complex_symmetric=True)
+        assert np.all(c.real >= h.real) and np.any(c.real > h.real)
+
+
 # --------------------------------------------------------------------------
 # 8. complex symmetric SYMV (prec c,z): the s,d rule applied to complex data.
 #    Pinned apart from HEMV so that a conjugation left in, or the diagonal's
