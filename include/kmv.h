@@ -462,6 +462,9 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *   gemv_n_row_tiles              row tiles per wave of GEMV-N (1, 2, 4)
  *   gemv_short                    kernels for matrices of a few row tiles:
  *                                 1 = never, 2 = whenever they apply
+ *   gemv_align_classes            GEMV with a leading dimension that is no
+ *                                 multiple of 128 bytes: columns grouped by
+ *                                 their alignment (1 = never, 2 = always)
  *   symv_variant                  SYMV/HEMV main kernel, see below (2, 3)
  *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)
  *   symv_unit_tiles               variant 2: row tiles per prefetch unit (1, 2)

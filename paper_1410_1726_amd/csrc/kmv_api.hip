@@ -208,7 +208,7 @@ int gemv_batched_entry(char trans, int64_t m, int64_t n, const T* alpha, const T
             if (e != hipSuccess) return hip_code(e);
             continue;
         }
-        GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, a.A, lda);
+        GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, a.A, lda, false);
         // the members share one tile grid: keep the pointer's alignment shift only if every member has it
         if (nb > 1 && ((uint64_t)strideA * sizeof(T)) % 128 != 0) {
             plan.shift = 0;
@@ -317,7 +317,7 @@ int gemv_ptr_batched_entry(char trans, int64_t m, int64_t n, const T* alpha, con
             if (e != hipSuccess) return hip_code(e);
             continue;
         }
-        GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, some_aligned_address(), lda);
+        GemvPlan<T> plan = plan_gemv<T>(notrans, m, n, some_aligned_address(), lda, false);
         plan.shift = 0;
         plan.ntiles = ceil_div(m, (int64_t)tile_rows<T>());
         plan.splits = 1;
@@ -387,6 +387,7 @@ const Key KEYS[] = {
     {"gemv_t_splits", &Tuning::gemv_t_splits, 0, 256},
     {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
     {"gemv_short", &Tuning::gemv_short, 0, 2},
+    {"gemv_align_classes", &Tuning::gemv_align_classes, 0, 2},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 2},
     {"symv_variant", &Tuning::symv_variant, 0, 3},
     {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
@@ -625,7 +626,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,gemv_align_classes,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

@@ -31,8 +31,9 @@ namespace kmv {
 // Edge tiles (rows before the first or after the last row) run the same
 // pipeline with the lanes' load positions clamped into the column: the lanes
 // outside compute sums of rows that do not exist, which are dropped.
+// The workgroup's columns are c0, c0 + cs, ..., cw of them (cs > 1: the columns of one alignment class).
 template <class T, int U, int RT, int NW, bool EDGE>
-__device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t (&r)[RT], int64_t c0, int64_t cw,
+__device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t (&r)[RT], int64_t c0, int64_t cw, int64_t cs,
                                             T (&acc)[RT][Traits<T>::VEC]) {
     constexpr int VEC = Traits<T>::VEC;
     const int64_t lda = a.lda;
@@ -54,14 +55,15 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
     }
     Vec<T> b0[U][RT], b1[U][RT];
     T xb0[U], xb1[U];
+    const int64_t cstride = cs * lda;
     auto load_blk = [&](Vec<T>(&buf)[U][RT], T(&xb)[U], int64_t j) {
         const T* q = A + j * lda;
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int t = 0; t < RT; ++t) buf[u][t] = load_stream(q + (int64_t)u * lda + rl[t]);
+            for (int t = 0; t < RT; ++t) buf[u][t] = load_stream(q + (int64_t)u * cstride + rl[t]);
 #pragma unroll
-        for (int u = 0; u < U; ++u) xb[u] = x[j + u];
+        for (int u = 0; u < U; ++u) xb[u] = x[j + u * cs];
     };
     auto compute_blk = [&](const Vec<T>(&buf)[U][RT], const T(&xb)[U]) {
 #pragma unroll
@@ -76,15 +78,16 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
     const int64_t nblk = cw / U;
     if (nblk > 0) load_blk(b0, xb0, c0);
     for (int64_t b = 0; b < nblk; b += 2) {
-        const int64_t j = c0 + b * U;
-        if (b + 1 < nblk) load_blk(b1, xb1, j + U);
+        const int64_t j = c0 + b * U * cs;
+        if (b + 1 < nblk) load_blk(b1, xb1, j + U * cs);
         compute_blk(b0, xb0);
         if (b + 1 < nblk) {
-            if (b + 2 < nblk) load_blk(b0, xb0, j + 2 * U);
+            if (b + 2 < nblk) load_blk(b0, xb0, j + 2 * U * cs);
             compute_blk(b1, xb1);
         }
     }
-    for (int64_t j = c0 + nblk * U; j < c0 + cw; ++j) {
+    for (int64_t i = nblk * U; i < cw; ++i) {
+        const int64_t j = c0 + i * cs;
         const T xj = x[j];
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
@@ -126,13 +129,29 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
     if (tbase >= a.plan.ntiles) return;
     select_member<PTRS>(a, blockIdx.z);   // member of a batch (strides all zero for a single product)
 
-    int64_t cw, c0;
-    partition(a.n, a.plan.splits, blockIdx.x, cw, c0);
+    int64_t cw, c0, cs = 1;
+    int shift = a.plan.shift;
+    int64_t ntiles = a.plan.ntiles, part_off = a.plan.part_off;
+    if (a.plan.period > 1) {
+        // columns of one alignment class: class, class + period, ...; the row tiles start on the
+        // 128-byte boundary below the class's first element
+        const int64_t P = a.plan.period, cls = (int64_t)blockIdx.x % P, q = (int64_t)blockIdx.x / P;
+        const int64_t ncls = cls < a.n ? (a.n - cls + P - 1) / P : 0;
+        int64_t k0;
+        partition(ncls, a.plan.splits / P, q, cw, k0);
+        c0 = cls + P * k0;
+        cs = P;
+        shift = (int)((uintptr_t)(a.A + cls * a.lda) % 128 / sizeof(T));
+        ntiles = ceil_div(a.m + shift, (int64_t)TR);
+        if (tbase >= ntiles) return;
+    } else {
+        partition(a.n, a.plan.splits, blockIdx.x, cw, c0);
+    }
     int64_t r[RT];          // first row slot of this lane in each tile (may be outside [0, m))
     bool interior = true;   // all RT tiles fully inside the matrix (wave uniform)
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        const int64_t r0 = (tbase + (int64_t)NW * t) * TR - a.plan.shift;
+        const int64_t r0 = (tbase + (int64_t)NW * t) * TR - shift;
         r[t] = r0 + (int64_t)lane * VEC;
         interior = interior && (r0 >= 0) && (r0 + TR <= a.m);
     }
@@ -142,13 +161,13 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[t][v] = zero_of<T>();
 
-    if (interior) gemv_n_walk<T, U, RT, NW, false>(a, r, c0, cw, acc);
-    else if (a.m >= VEC) gemv_n_walk<T, U, RT, NW, true>(a, r, c0, cw, acc);
+    if (interior) gemv_n_walk<T, U, RT, NW, false>(a, r, c0, cw, cs, acc);
+    else if (a.m >= VEC) gemv_n_walk<T, U, RT, NW, true>(a, r, c0, cw, cs, acc);
     else gemv_n_few_rows<T, RT>(a, r, c0, cw, acc);
 
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-        if (tbase + (int64_t)NW * t >= a.plan.ntiles) continue;   // tile beyond the matrix: nothing to store
+        if (tbase + (int64_t)NW * t >= ntiles) continue;   // tile beyond the matrix: nothing to store
         if (a.plan.splits == 1) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
@@ -162,7 +181,7 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_kernel(GemvArgs<T> a) {
             Vec<T> out;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) out.e[v] = acc[t][v];
-            store_vec(a.partial + (int64_t)blockIdx.x * a.plan.part_stride + (r[t] + a.plan.shift), out);
+            store_vec(a.partial + (int64_t)blockIdx.x * a.plan.part_stride + (r[t] + part_off), out);
         }
     }
 }
@@ -191,8 +210,8 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_short_kernel(GemvArgs<T> a) 
     T acc[1][VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[0][v] = zero_of<T>();
-    if (interior) gemv_n_walk<T, U, 1, NW, false>(a, r, c0 + c0s, cws, acc);
-    else if (a.m >= VEC) gemv_n_walk<T, U, 1, NW, true>(a, r, c0 + c0s, cws, acc);
+    if (interior) gemv_n_walk<T, U, 1, NW, false>(a, r, c0 + c0s, cws, 1, acc);
+    else if (a.m >= VEC) gemv_n_walk<T, U, 1, NW, true>(a, r, c0 + c0s, cws, 1, acc);
     else gemv_n_few_rows<T, 1>(a, r, c0 + c0s, cws, acc);
 
     __shared__ T red[NW][TR];
@@ -236,12 +255,23 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int w = WCOLS ? 0 : wv;
-    const int64_t j0 = WCOLS ? ((int64_t)blockIdx.x * NW_ + wv) * NC : (int64_t)blockIdx.x * NC;
+    int64_t j0 = WCOLS ? ((int64_t)blockIdx.x * NW_ + wv) * NC : (int64_t)blockIdx.x * NC;
     if (WCOLS && j0 >= a.n) return;   // a whole wave past the last column (no barrier in this form)
-    const int64_t ntiles = a.plan.ntiles;
-    const int shift = a.plan.shift;
+    int64_t ntiles = a.plan.ntiles;
+    int shift = a.plan.shift;
     select_member<PTRS>(a, blockIdx.z);   // member of a batch (strides all zero for a single product)
     const T* __restrict__ x = a.x;
+    // the workgroup's columns are j0, j0 + js, ...; with alignment classes (period > 1) they are columns of
+    // one class, and the row tiles start on the 128-byte boundary below that class's first element
+    int64_t js = 1, jlast = a.n - 1;
+    if (!WCOLS && a.plan.period > 1) {
+        const int64_t P = a.plan.period, cls = (int64_t)blockIdx.x % P;
+        j0 = cls + P * ((int64_t)blockIdx.x / P) * NC;
+        js = P;
+        jlast = cls < a.n ? cls + (a.n - 1 - cls) / P * P : 0;    // last column of the class (column 0 if it has none)
+        shift = (int)((uintptr_t)(a.A + (cls < a.n ? cls : 0) * a.lda) % 128 / sizeof(T));
+        ntiles = ceil_div(a.m + shift, (int64_t)TR);
+    }
 
     int64_t tw, ts;
     partition(ntiles, a.plan.splits, blockIdx.y, tw, ts);
@@ -250,7 +280,7 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     const T* __restrict__ col[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int64_t j = (j0 + c < a.n) ? (j0 + c) : (a.n - 1);
+        const int64_t j = (j0 + c * js < a.n) ? (j0 + c * js) : jlast;
         col[c] = a.A + j * a.lda;
     }
     T acc[NC];
@@ -361,7 +391,7 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     if (!WCOLS) __syncthreads();
     if (WCOLS ? lane < NC : threadIdx.x < NC) {
         const int c = WCOLS ? lane : threadIdx.x;
-        const int64_t j = j0 + c;
+        const int64_t j = j0 + c * js;
         if (j < a.n) {
             T s = WCOLS ? mine : red[0][c];
             for (int ww = 1; ww < NW; ++ww) s = add_of(s, red[ww][c]);
@@ -447,13 +477,30 @@ inline int64_t choose_splits(int64_t rb, int64_t slots, int64_t cap) {
     return best;
 }
 
-template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda) {
+template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda, bool classes) {
     constexpr int TR = tile_rows<T>();
     GemvPlan<T> p;
     p.row_tiles = 1;
     const bool sizing = (A == nullptr);
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(m + p.shift, TR);
+    // alignment classes: worth it when the columns are long and there are several workgroups' worth per class
+    // (measured: a stream of 1 KiB loads that start 8 .. 64 bytes off a 128-byte boundary runs 4-9% slower,
+    // nine lines per load instead of eight)
+    p.period = 1;
+    const uint64_t step = ((uint64_t)lda * sizeof(T)) % 128;
+    if (classes && !sizing && step != 0 && tuning().gemv_align_classes != 1) {
+        uint64_t g = step, h = 128;
+        while (h) { const uint64_t t = g % h; g = h; h = t; }
+        const int64_t P = (int64_t)(128 / g);
+        // by default for the transposed product only (SGEMV/DGEMV/CGEMV-T at n = 17001, lda = n: 6-7% faster; the
+        // non-transposed kernel gains 0-3% at best, its split counts have to be multiples of the period)
+        if (tuning().gemv_align_classes == 2 || (!notrans && (double)m * sizeof(T) >= 16384.0 && n >= 64 * P)) {
+            p.period = P;
+            p.shift = max_row_shift<T>();
+            p.ntiles = ceil_div(m + p.shift, TR);
+        }
+    }
     const int64_t target = tuning().wg_target > 0 ? tuning().wg_target : DEFAULT_WG_TARGET;
     int64_t s;
     const int64_t max_splits = MAX_SPLITS;
@@ -495,7 +542,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
             if (s4 > cap) s4 = 0;
             const bool big = (double)m * (double)n * sizeof(T) >= 256.0 * 1024 * 1024;
             const bool rows_even = sizeof(T) == 4 ? p.ntiles % (GN_NW * 4) == 0 : p.ntiles * 100 >= rb4 * GN_NW * 4 * 85;
-            if (big && rows_even && s4 >= 1 && rb4 * s4 * 100 >= cus * 85) {
+            if (p.period == 1 && big && rows_even && s4 >= 1 && rb4 * s4 * 100 >= cus * 85) {
                 p.row_tiles = 4;
                 s = s4;
             }
@@ -504,7 +551,12 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
         if (s <= 0 && tuning().wg_target <= 0 && !sizing) s = choose_splits(rb, gemv_n_slots<T>(p.row_tiles), cap);
         if (s <= 0) s = ceil_div(target, rb);
         if (s > cap) s = cap;
-        p.part_stride = partial_stride<T>(p.ntiles * TR);
+        if (p.period > 1) {     // every split lies in one class: a multiple of the period (n >= 64 columns per class)
+            s = s / p.period * p.period;
+            if (s < p.period) s = p.period;
+            if (s > MAX_SPLITS) s = MAX_SPLITS / p.period * p.period;
+        }
+        p.part_stride = partial_stride<T>(p.ntiles * TR + TR);
     } else {
         const int64_t g = n > 0 ? ceil_div(n, GT_NC) : 1;
         // Row splits (and the second kernel that adds the pieces) pay only when the column groups
@@ -526,7 +578,15 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     }
     if (s > max_splits) s = max_splits;
     if (s < 1) s = 1;
+    if (p.short_form) {     // the kernels for short matrices take the columns as they come
+        if (p.period > 1) {
+            p.shift = 0;
+            p.ntiles = ceil_div(m, TR);
+        }
+        p.period = 1;
+    }
     p.splits = s;
+    p.part_off = p.period > 1 ? max_row_shift<T>() : p.shift;
     const int64_t lenx = notrans ? n : m;
     p.xpack_off = 0;
     p.partial_off = round_up((size_t)lenx * sizeof(T), WS_ALIGN);
@@ -558,7 +618,7 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s,
     else return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.plan.splits == 1) return e;
-    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
+    return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.part_off, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
 }
 
 template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hipStream_t s, int64_t batch) {
@@ -584,7 +644,9 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
         else
             hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
     } else {
-        const dim3 grid((unsigned)ceil_div(a.n, GT_NC), (unsigned)a.plan.splits, (unsigned)batch);
+        // with alignment classes every class gets its own column groups
+        const int64_t P = a.plan.period > 1 ? a.plan.period : 1;
+        const dim3 grid((unsigned)(P * ceil_div(ceil_div(a.n, P), GT_NC)), (unsigned)a.plan.splits, (unsigned)batch);
         if (conj && Traits<T>::cplx)
             hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
         else
@@ -715,7 +777,7 @@ template <class T> hipError_t launch_gemv_tiny(const GemvArgs<T>& a, int mode, h
 }
 
 #define KMV_INSTANTIATE_GEMV(T)                                                              \
-    template GemvPlan<T> plan_gemv<T>(bool, int64_t, int64_t, const void*, int64_t);         \
+    template GemvPlan<T> plan_gemv<T>(bool, int64_t, int64_t, const void*, int64_t, bool);         \
     template hipError_t launch_gemv_n<T>(const GemvArgs<T>&, hipStream_t, int64_t);          \
     template hipError_t launch_gemv_t<T>(const GemvArgs<T>&, bool, hipStream_t, int64_t);          \
     template hipError_t launch_gemv_tiny<T>(const GemvArgs<T>&, int, hipStream_t, int64_t);

@@ -17,6 +17,7 @@ struct Tuning {
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
     int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
     int64_t gemv_short = 0;        // kernels for matrices of a few row tiles: 1 = never, 2 = whenever possible
+    int64_t gemv_align_classes = 0;   // columns grouped by their alignment when lda is no multiple of 128 bytes: 1 = never, 2 = always
     int64_t symv_tiles_per_wave = 0;  // SYMV row-chunk height in units of 4 row tiles: 1 or 2
     int64_t symv_variant = 0;         // SYMV main kernel: 2 = balanced shares, 3 = one launch
     int64_t symv_unit_tiles = 0;      // balanced kernel: row tiles per prefetch unit (1 or 2)
@@ -73,11 +74,19 @@ template <class T> struct GemvPlan {
     int64_t splits;       // N: column splits; T: row splits
     int64_t row_tiles;    // N: row tiles per wave
     int short_form;       // kernels for matrices of a few row tiles (waves split columns instead of rows)
+    // Alignment classes (Section 6.6 carried to leading dimensions that are no multiple of 128 bytes): the
+    // misalignment of column j is (A + j*lda) mod 128, which repeats every `period` columns.  With period > 1
+    // a workgroup takes columns of ONE class (j = class, class + period, ...), all equally aligned, and starts
+    // its row tiles on THEIR 128-byte boundary (the kernel works the shift out from the class's first column);
+    // shift and ntiles above then describe the class with the largest shift.  1 = all columns alike.
+    int64_t period;
+    int64_t part_off;     // slot of row 0 in a partial vector of GEMV-N
     int64_t part_stride;  // elements between consecutive partial vectors
     size_t xpack_off, partial_off, total_bytes;   // workspace layout
 };
 // plan for a concrete call (A != nullptr) or the worst case over alignments
-template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda);
+// (classes = false: never group the columns by alignment; the batched forms, whose members share one grid)
+template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, const void* A, int64_t lda, bool classes = true);
 
 template <class T> struct GemvArgs {
     int64_t m, n, lda;

@@ -237,6 +237,22 @@ def test_split_variants_agree_with_oracle():
                 k.set_tuning(key, s)
                 _, err, _ = gemv_case("d", trans, 2100, 1900, 0.7, 0.3, seed=15)
                 check("d", err, f"{key}={s}")
+        # columns grouped by alignment class (leading dimension no multiple of 128 bytes), forced on for small
+        # and ragged shapes, with few and many splits, classes with no column at all (n below the period)
+        k.set_tuning("gemv_align_classes", 2)
+        for prec, m, n, lda in (("d", 2100, 1900, 2111), ("s", 700, 45, 701), ("z", 300, 9, 333), ("c", 4099, 260, 4100),
+                                ("d", 3, 50, 5), ("s", 1, 7, 3)):
+            for key, trans, splits in (("gemv_n_splits", "N", 0), ("gemv_n_splits", "N", 64), ("gemv_t_splits", "T", 0),
+                                       ("gemv_t_splits", "C", 3)):
+                k.set_tuning(key, splits)
+                _, err, _ = gemv_case(prec, trans, m, n, 0.7, 0.3, lda=lda, row_off=1, col_off=2, seed=19)
+                check(prec, err, f"alignment classes {prec}gemv {trans} {m}x{n} lda={lda} splits={splits}")
+                k.set_tuning(key, 0)
+        k.set_tuning("gemv_align_classes", 1)
+        for trans in "NT":
+            _, err, _ = gemv_case("d", trans, 4099, 4099, 0.7, 0.3, lda=4099, seed=20)
+            check("d", err, f"dgemv {trans} without alignment classes")
+        k.set_tuning("gemv_align_classes", 0)
         k.set_tuning("symv_variant", 2)
         for tpw, workers, fixed, edge in ((1, 1, 1, 1), (2, 3, 4, 1), (1, 8, 1, 9), (2, 5, 17, 17), (2, 256, 2, 3), (1, 16, 3, 2)):
             k.set_tuning("symv_tiles_per_wave", tpw)
