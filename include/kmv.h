@@ -481,10 +481,29 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *                                 the one-wave-per-member kernel)
  *   symv_small_waves              variant 3: waves per workgroup (4, 8, 16)
  *   gemv_tiny_rows                strided batches: members with fewer rows
- *                                 than this get one wave each (1 = never) */
+ *                                 than this get one wave each (1 = never)
+ *   tuned_table                   1 = ignore the compiled-in table of measured
+ *                                 per-size settings (see kmv_tuned_settings) */
 int kmv_set_tuning(const char* key, int64_t value);
 int64_t kmv_get_tuning(const char* key);
 const char* kmv_tuning_keys(void);
+
+/* The table of measured per-size settings (Section 9: the best tuning
+ * parameters of every routine, precision and size found by a coarse and a
+ * fine sweep, kept apart from the kernels).  The tuning tool writes its rows
+ * (python -m paper_1410_1726_amd.tune table --save), the build compiles them
+ * in, and the planners of the single-product entry points consult them for
+ * square products (m == n) whose leading dimension is a whole number of
+ * 128-byte lines: a row fills the tuning keys that the caller left at 0, for
+ * that one call.  This query returns 1 and the row's values if a row applies
+ * to routine op ('N'; 'T' for both transposed forms; 'L' or 'U' for
+ * SYMV/HEMV) in precision prec at size n under the current tuning values, 0
+ * if none does (the planner's rules decide), -1 for an unknown op or prec, a
+ * negative n or a null pointer.  values (host, 7 entries, written only when
+ * 1 is returned) = gemv_n_splits, gemv_n_row_tiles, gemv_t_splits,
+ * symv_variant, symv_tiles_per_wave, symv_unit_tiles, wg_target; 0 = left to
+ * the planner.  Host only: nothing is read from the device or launched. */
+int kmv_tuned_settings(char prec, char op, int64_t n, int64_t* values);
 
 /* Which main kernel a kmv_<prec>symv / hemv call with these arguments would
  * launch under the current tuning values: 2 = balanced shares of (row chunk,

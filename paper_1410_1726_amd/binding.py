@@ -95,6 +95,8 @@ def _load() -> ctypes.CDLL:
     lib.kmv_set_tuning.argtypes, lib.kmv_set_tuning.restype = [ctypes.c_char_p, i64], ci
     lib.kmv_get_tuning.argtypes, lib.kmv_get_tuning.restype = [ctypes.c_char_p], i64
     lib.kmv_tuning_keys.restype = ctypes.c_char_p
+    lib.kmv_tuned_settings.argtypes = [ctypes.c_char, ctypes.c_char, i64, ctypes.POINTER(ctypes.c_int64)]
+    lib.kmv_tuned_settings.restype = ctypes.c_int
     lib.kmv_symv_kernel_variant.argtypes = [ctypes.c_char, ctypes.c_char, i64, ctypes.c_void_p, i64]
     lib.kmv_symv_kernel_variant.restype = ctypes.c_int
     lib.kmv_symv_shares.argtypes = [ctypes.c_char, ctypes.c_char, i64, ci, ci, ci, i64, ci, ci, ctypes.c_void_p,
@@ -547,6 +549,20 @@ def get_tuning(key):
 
 def tuning_keys():
     return lib.kmv_tuning_keys().decode().split(",")
+
+
+TUNED_FIELDS = ("gemv_n_splits", "gemv_n_row_tiles", "gemv_t_splits", "symv_variant", "symv_tiles_per_wave",
+                "symv_unit_tiles", "wg_target")
+
+
+def tuned_settings(prec, op, n):
+    """Row of the compiled-in table of measured settings that the planners apply to a square product of
+    routine op ('N', 'T', 'L', 'U') at size n, as {key: value} without the zero fields; None if no row applies."""
+    vals = (ctypes.c_int64 * 7)()
+    rc = int(lib.kmv_tuned_settings(prec.encode(), op.encode(), n, vals))
+    if rc < 0:
+        raise ValueError(f"bad arguments ({prec!r}, {op!r}, {n})")
+    return {f: int(v) for f, v in zip(TUNED_FIELDS, vals) if v} if rc == 1 else None
 
 
 def symv_kernel_variant(prec, uplo, n, A, lda):

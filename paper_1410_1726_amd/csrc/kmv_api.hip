@@ -28,6 +28,35 @@ Tuning& tuning() {
 }
 
 namespace {
+const TunedRow TUNED_ROWS[] = {
+#include "kmv_tuned_table.inc"
+    {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0},   // end mark
+};
+}  // namespace
+
+Tuning tuned(char op, char prec, int64_t m, int64_t n, int64_t lda_bytes) {
+    Tuning t = tuning();
+    if (t.tuned_table == 1 || m != n || lda_bytes % 128 != 0) return t;
+    for (const TunedRow* r = TUNED_ROWS; r->op; ++r) {
+        if (r->op != op || r->prec != prec || n < r->n_lo || n >= r->n_hi) continue;
+        if (op == 'N' && t.gemv_n_splits == 0 && t.gemv_n_row_tiles == 0 && t.wg_target == 0) {
+            t.gemv_n_splits = r->gemv_n_splits;
+            t.gemv_n_row_tiles = r->gemv_n_row_tiles;
+        }
+        if (op == 'T' && t.gemv_t_splits == 0 && t.wg_target == 0) t.gemv_t_splits = r->gemv_t_splits;
+        if ((op == 'L' || op == 'U') && t.symv_variant == 0 && t.symv_tiles_per_wave == 0 && t.symv_unit_tiles == 0 &&
+            t.wg_target == 0) {
+            t.symv_variant = r->symv_variant;
+            t.symv_tiles_per_wave = r->symv_tiles_per_wave;
+            t.symv_unit_tiles = r->symv_unit_tiles;
+            t.wg_target = r->wg_target;
+        }
+        break;
+    }
+    return t;
+}
+
+namespace {
 
 inline int hip_code(hipError_t e) { return e == hipSuccess ? KMV_OK : KMV_ERR_HIP + (int)e; }
 
@@ -398,6 +427,7 @@ const Key KEYS[] = {
     {"symv_member_waves", &Tuning::symv_member_waves, 0, 8},
     {"symv_small_waves", &Tuning::symv_small_waves, 0, 16},
     {"gemv_tiny_rows", &Tuning::gemv_tiny_rows, 0, 1024},
+    {"tuned_table", &Tuning::tuned_table, 0, 1},
 };
 
 }  // namespace
@@ -626,7 +656,20 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,gemv_align_classes,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,gemv_align_classes,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows,tuned_table"; }
+
+int kmv_tuned_settings(char prec, char op, int64_t n, int64_t* values) {
+    if (!values || n < 0 || !strchr("sdcz", prec) || prec == 0 || !strchr("NTLU", op) || op == 0) return -1;
+    if (tuning().tuned_table == 1) return 0;
+    for (const TunedRow* r = TUNED_ROWS; r->op; ++r)
+        if (r->op == op && r->prec == prec && n >= r->n_lo && n < r->n_hi) {
+            const int64_t v[7] = {r->gemv_n_splits, r->gemv_n_row_tiles, r->gemv_t_splits, r->symv_variant,
+                                  r->symv_tiles_per_wave, r->symv_unit_tiles, r->wg_target};
+            for (int i = 0; i < 7; ++i) values[i] = v[i];
+            return 1;
+        }
+    return 0;
+}
 
 int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int64_t lda) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');

@@ -482,6 +482,8 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     GemvPlan<T> p;
     p.row_tiles = 1;
     const bool sizing = (A == nullptr);
+    // the caller's tuning values, plus the measured settings of this size where the caller left the choice open
+    const Tuning tn = sizing || !classes ? tuning() : tuned(notrans ? 'N' : 'T', prec_char<T>(), m, n, lda * (int64_t)sizeof(T));
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(m + p.shift, TR);
     // alignment classes: worth it when the columns are long and there are several workgroups' worth per class
@@ -489,29 +491,29 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     // nine lines per load instead of eight)
     p.period = 1;
     const uint64_t step = ((uint64_t)lda * sizeof(T)) % 128;
-    if (classes && !sizing && step != 0 && tuning().gemv_align_classes != 1) {
+    if (classes && !sizing && step != 0 && tn.gemv_align_classes != 1) {
         uint64_t g = step, h = 128;
         while (h) { const uint64_t t = g % h; g = h; h = t; }
         const int64_t P = (int64_t)(128 / g);
         // by default for the transposed product only (SGEMV/DGEMV/CGEMV-T at n = 17001, lda = n: 6-7% faster; the
         // non-transposed kernel gains 0-3% at best, its split counts have to be multiples of the period)
-        if (tuning().gemv_align_classes == 2 || (!notrans && (double)m * sizeof(T) >= 16384.0 && n >= 64 * P)) {
+        if (tn.gemv_align_classes == 2 || (!notrans && (double)m * sizeof(T) >= 16384.0 && n >= 64 * P)) {
             p.period = P;
             p.shift = max_row_shift<T>();
             p.ntiles = ceil_div(m + p.shift, TR);
         }
     }
-    const int64_t target = tuning().wg_target > 0 ? tuning().wg_target : DEFAULT_WG_TARGET;
+    const int64_t target = tn.wg_target > 0 ? tn.wg_target : DEFAULT_WG_TARGET;
     int64_t s;
     const int64_t max_splits = MAX_SPLITS;
     p.short_form = 0;
-    const int64_t short_mode = tuning().gemv_short;   // 0 = automatic, 1 = never, 2 = whenever the kernels allow
+    const int64_t short_mode = tn.gemv_short;   // 0 = automatic, 1 = never, 2 = whenever the kernels allow
     if (notrans && !sizing && short_mode != 1 && p.ntiles <= 2) {
         // one or two row tiles: NW/ntiles waves per tile split the columns once more
         p.short_form = 1;
         const int64_t ws = GN_NW / p.ntiles;
         int64_t cap = n / (GN_LOADS * ws) > 1 ? n / (GN_LOADS * ws) : 1;   // a block of columns per wave at least
-        s = tuning().gemv_n_splits > 0 ? tuning().gemv_n_splits : (tuning().wg_target > 0 ? tuning().wg_target : 256);   // measured best
+        s = tn.gemv_n_splits > 0 ? tn.gemv_n_splits : (tn.wg_target > 0 ? tn.wg_target : 256);   // measured best
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(p.ntiles * TR);
     } else if (!notrans && !sizing && short_mode != 1 && (p.ntiles <= SHORT_T_TILES || (short_mode == 2 && p.ntiles <= 64))) {
@@ -522,9 +524,9 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     } else if (notrans) {
         int64_t cap = n / 32 > 1 ? n / 32 : 1;   // at least 32 columns per split
         if (cap > MAX_SPLITS) cap = MAX_SPLITS;
-        s = tuning().gemv_n_splits;
-        p.row_tiles = tuning().gemv_n_row_tiles > 0 ? tuning().gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
-        if (tuning().gemv_n_row_tiles <= 0 && s <= 0 && tuning().wg_target <= 0 && !sizing) {
+        s = tn.gemv_n_splits;
+        p.row_tiles = tn.gemv_n_row_tiles > 0 ? tn.gemv_n_row_tiles : DEFAULT_GN_ROW_TILES;
+        if (tn.gemv_n_row_tiles <= 0 && s <= 0 && tn.wg_target <= 0 && !sizing) {
             // Large matrices: ONE workgroup per compute unit, each over 16 row tiles (four per wave, two
             // columns per prefetch block).  Measured with the settings alternating in one process this
             // is 3-7% faster than two workgroups per compute unit from about 256 MB of matrix on (the
@@ -548,7 +550,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
             }
         }
         const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
-        if (s <= 0 && tuning().wg_target <= 0 && !sizing) s = choose_splits(rb, gemv_n_slots<T>(p.row_tiles), cap);
+        if (s <= 0 && tn.wg_target <= 0 && !sizing) s = choose_splits(rb, gemv_n_slots<T>(p.row_tiles), cap);
         if (s <= 0) s = ceil_div(target, rb);
         if (s > cap) s = cap;
         if (p.period > 1) {     // every split lies in one class: a multiple of the period (n >= 64 columns per class)
@@ -570,8 +572,8 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
             sa = ceil_div(512, g);
             if (sa < 4) sa = 4;
         }
-        s = tuning().gemv_t_splits > 0 ? tuning().gemv_t_splits
-                                       : (tuning().wg_target > 0 ? ceil_div(tuning().wg_target, g) : sa);
+        s = tn.gemv_t_splits > 0 ? tn.gemv_t_splits
+                                       : (tn.wg_target > 0 ? ceil_div(tn.wg_target, g) : sa);
         const int64_t cap = p.ntiles / (2 * GT_NW) > 1 ? p.ntiles / (2 * GT_NW) : 1;   // two tiles per wave at least
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(n);

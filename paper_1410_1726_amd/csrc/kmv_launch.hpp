@@ -28,8 +28,25 @@ struct Tuning {
     int64_t symv_member_waves = 0;    // batches: waves of that kernel's workgroup (4 or 8)
     int64_t symv_small_waves = 0;     // small-matrix kernel: waves per workgroup (4, 8 or 16)
     int64_t gemv_tiny_rows = 0;       // batches: one wave per member for m < this value (1 = never)
+    int64_t tuned_table = 0;          // measured per-size settings: 1 = ignore them (the planners' rules alone)
 };
 Tuning& tuning();
+
+// Measured per-size settings (Section 9: tuning parameters found by a coarse and a fine sweep, kept apart from the
+// kernels).  The rows are written by the tuning tool (`tune table --save`) into kmv_tuned_table.inc and compiled
+// in.  A row applies to the square products of its routine ('N', 'T' for both transposed forms, 'L', 'U') and
+// precision whose size lies in [n_lo, n_hi) and whose leading dimension is a whole number of 128-byte lines (what
+// the tool measures); a zero field leaves that choice to the planner's rule.  tuned() returns the caller's
+// tuning values with the matching row filled into the keys the caller left at 0: an explicit key always wins.
+struct TunedRow {
+    char op, prec;
+    int32_t n_lo, n_hi;
+    int16_t gemv_n_splits, gemv_n_row_tiles, gemv_t_splits, symv_variant, symv_tiles_per_wave, symv_unit_tiles, wg_target;
+};
+Tuning tuned(char op, char prec, int64_t m, int64_t n, int64_t lda_bytes);
+template <class T> constexpr char prec_char() {
+    return sizeof(T) == 4 ? 's' : (sizeof(T) == 16 ? 'z' : (Traits<T>::cplx ? 'c' : 'd'));
+}
 
 // Index of the current device for the per-device caches of the planners
 // (occupancy and compute-unit counts differ between devices), -1 if it cannot

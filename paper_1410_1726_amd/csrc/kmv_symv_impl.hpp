@@ -856,9 +856,10 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
 namespace {
 constexpr int BAL_NC = 4;   // balanced kernel: columns per wave
 constexpr int SMALL_NC = 8;            // small-matrix kernel: outputs per workgroup
-// largest n the small-matrix kernel is chosen for (measured against the two-launch path at n = 1024 .. 3072:
-// it wins up to 2048 in d, up to about 1792 in s, c and z, and loses by 20-50% from 2560 on)
-template <class T> constexpr int64_t small_n() { return sizeof(T) == 8 && !Traits<T>::cplx ? 2048 : 1792; }
+// largest n the small-matrix kernel is chosen for (measured against the two-launch path at n = 1536 .. 3072 in
+// steps of 128 .. 256, both triangles: it wins up to 2176 in s (10-15 us against 15-16), up to 2048 in d and c,
+// up to about 1600 in z, and loses by 20-70% from 2560 on)
+template <class T> constexpr int64_t small_n() { return sizeof(T) == 4 ? 2176 : (sizeof(T) == 16 ? 1664 : 2048); }
 // Row tiles per unit (KT), chunk height and workgroups per compute unit, measured with the settings
 // alternating in one process over n = 2560 .. 32768 in all four precisions: one tile per unit (4 matrix
 // loads and one of x per lane and buffer) is never slower than two; ONE workgroup per compute unit is
@@ -1033,15 +1034,17 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     constexpr int64_t C = BAL_NC * SY_NW;
     SymvPlan<T> p;
     const bool sizing = (A == nullptr);
+    // the caller's tuning values, plus the measured settings of this size where the caller left the choice open
+    const Tuning tn = sizing ? tuning() : tuned(lower ? 'L' : 'U', prec_char<T>(), n, n, lda * (int64_t)sizeof(T));
     p.shift = sizing ? max_row_shift<T>() : row_shift<T>(A, lda);
     p.ntiles = ceil_div(n + p.shift, TR);
     // main kernel: the one-launch kernel up to small_n, the balanced kernel beyond
-    p.variant = (int)tuning().symv_variant;
+    p.variant = (int)tn.symv_variant;
     if (p.variant <= 0) p.variant = n <= small_n<T>() ? 3 : 2;
     // the balanced kernel loads 16-byte vectors from columns with at least VEC stored rows: it needs some
     if (p.variant == 2 && n < 4 * Traits<T>::VEC) p.variant = 3;
     // chunk height in units of 4 row tiles
-    int64_t ktw = tuning().symv_tiles_per_wave;
+    int64_t ktw = tn.symv_tiles_per_wave;
     if (ktw <= 0) ktw = default_tiles_per_wave<T>(n);
     // the balanced kernel's tables hold SHARE_MAX_CHUNKS chunks (enough for every matrix that fits the device's
     // memory when the chunks are 8 tiles high)
@@ -1073,8 +1076,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             p.total_bytes = 0;
             return p;
         }
-        p.unit_tiles = tuning().symv_unit_tiles > 0 ? (int)tuning().symv_unit_tiles : default_unit_tiles<T>(n);
-        int64_t Y = tuning().wg_target;
+        p.unit_tiles = tn.symv_unit_tiles > 0 ? (int)tn.symv_unit_tiles : default_unit_tiles<T>(n);
+        int64_t Y = tn.wg_target;
         if (Y <= 0) {
             // one resident round: compute units x workgroups per compute unit (never more than fit)
             const int64_t q = balanced_slots<T>(lower, (int)ktw, p.unit_tiles);
@@ -1082,8 +1085,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             const int64_t want = default_wgs_per_cu<T>(n);
             Y = cus * (want < fit ? want : fit);
         }
-        const int fixed = tuning().symv_piece_fixed > 0 ? (int)tuning().symv_piece_fixed - 1 : DEFAULT_PIECE_FIXED;
-        const int edge = tuning().symv_edge_weight > 0 ? (int)tuning().symv_edge_weight - 1 : default_edge_weight<T>();
+        const int fixed = tn.symv_piece_fixed > 0 ? (int)tn.symv_piece_fixed - 1 : DEFAULT_PIECE_FIXED;
+        const int edge = tn.symv_edge_weight > 0 ? (int)tn.symv_edge_weight - 1 : default_edge_weight<T>();
         p.bal = balanced_shares<T>(lower, n, p.shift, (int)p.chunk_tiles, p.unit_tiles, Y, fixed, edge);
         p.work = p.bal->work;
         p.workers = p.bal->workers;

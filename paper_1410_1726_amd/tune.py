@@ -27,6 +27,14 @@ the best setting next to the library's own choice (optionally as JSON that
 runs the automatic mode over routines x square sizes and prints one line per case:
 the library's choice, the best setting found and what it would gain (the per-size
 table that says where the planners' defaults leave time on the floor).
+
+  python -m paper_1410_1726_amd.tune table --save [routine,...] [n,...]
+
+does the same with the saved table switched off, measures every gain of 3% or more a
+second time against the planners' rule, and writes the settings that held up as rows
+of csrc/kmv_tuned_table.inc.  The rows are compiled into the library (build again
+afterwards): the planners look a square product's size up there before they
+fall back on their rules.
 """
 from __future__ import annotations
 
@@ -57,14 +65,19 @@ def _time(call, reps, warm=2):
 def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int = 10):
     """routine like 'dgemv_T', 'zhemv_U', 'ssymv_L'; grid: {key: [values]}.  Returns
     [(settings dict, median microseconds)], in grid order."""
+    keys = list(grid)
+    combos = [dict(zip(keys, vals)) for vals in itertools.product(*(grid[key] for key in keys))] or [{}]
+    return sweep_settings(routine, m, n, combos, rounds, reps)
+
+
+def sweep_settings(routine: str, m: int, n: int, combos: list, rounds: int = 5, reps: int = 10):
+    """The same over an explicit list of settings dicts ({} = the library's own choice, saved table included)."""
     prec, name, mode = routine[0], routine[1:5], routine[-1]
     sym = name in ("symv", "hemv")
     A = wl.matrix(prec, m, n, m, device="cuda")
     lenx, leny = (n, n) if sym else ((n, m) if mode == "N" else (m, n))
     x = wl.vector(prec, lenx, device="cuda")
     y = wl.vector(prec, leny, which=2, device="cuda")
-    keys = list(grid)
-    combos = [dict(zip(keys, vals)) for vals in itertools.product(*(grid[key] for key in keys))] or [{}]
     times = [[] for _ in combos]
     saved = {key: k.get_tuning(key) for key in k.tuning_keys()}
     try:
@@ -74,6 +87,8 @@ def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int =
                     k.set_tuning(key, 0)
                 for key, v in combo.items():
                     k.set_tuning(key, v)
+                if combo:       # an explicit setting is measured against the planners' rules, not the saved table
+                    k.set_tuning("tuned_table", 1)
                 # the plan (kernel, splits, workspace layout) is fixed when the call is prepared
                 call = (k.prepare_symv(prec, mode, n, 1.0, A, m, x, 1, 0.0, y, 1) if sym
                         else k.prepare_gemv(prec, mode, m, n, 1.0, A, m, x, 1, 1.0, y, 1))
@@ -137,31 +152,107 @@ def auto(routine: str, m: int, n: int, rounds: int = 3, reps: int = 8):
     return best, best_us, default_us, stages
 
 
-TABLE_ROUTINES = ("sgemv_N", "sgemv_T", "dgemv_N", "dgemv_T", "zgemv_N", "zgemv_C", "ssymv_L", "dsymv_L", "dsymv_U",
-                  "chemv_L", "zhemv_L")
+TABLE_ROUTINES = tuple(f"{p}gemv_{t}" for p in "sdcz" for t in ("N", "C" if p in "cz" else "T")) + \
+    tuple(f"{p}{'hemv' if p in 'cz' else 'symv'}_{u}" for p in "sdcz" for u in "LU")
 TABLE_SIZES = (2048, 4096, 8192, 12288, 16384, 24576, 32768)
+SAVE_GAIN = 0.03           # a setting enters the saved table when it beats the planner's rule by this much, twice
+TABLE_FILE = "csrc/kmv_tuned_table.inc"
+ROW_FIELDS = ("gemv_n_splits", "gemv_n_row_tiles", "gemv_t_splits", "symv_variant", "symv_tiles_per_wave", "symv_unit_tiles",
+              "wg_target")
 
 
-def table(routines=TABLE_ROUTINES, sizes=TABLE_SIZES, out=sys.stdout):
-    """One line per (routine, n): library's choice vs the best setting the automatic mode finds."""
+CLASS_WIDTHS = (16, 64)    # a row serves n -+ n/16 if it holds up at both ends, else n -+ n/64, else n alone
+
+
+def _size_class(n, width):
+    """[lo, hi) around the measured size n."""
+    return n - n // width, n + n // width + 1
+
+
+def _op(routine):
+    return routine[-1] if routine[1:5] in ("symv", "hemv") else ("N" if routine[-1] == "N" else "T")
+
+
+def _row_text(routine, n, width, settings):
+    op = _op(routine)
+    lo, hi = _size_class(n, width)
+    vals = ", ".join(str(int(settings.get(f, 0))) for f in ROW_FIELDS)
+    return f"    {{'{op}', '{routine[0]}', {lo}, {hi}, {vals}}},   // {routine} n = {n}"
+
+
+def table(routines=TABLE_ROUTINES, sizes=TABLE_SIZES, out=sys.stdout, save=False):
+    """One line per (routine, n): library's choice vs the best setting the automatic mode finds.  With `save` the
+    library's choice is taken with the saved table off, and the settings that beat it twice become table rows."""
     op_of = {"gemv": lambda r: "gemv_" + ("n" if r[-1] == "N" else "t"), "symv": lambda r: "symv_l", "hemv": lambda r: "hemv_l"}
     print(f"{'routine':9s} {'n':>6s} {'library us':>11s} {'GB/s':>8s} {'best us':>9s} {'gain':>6s}  best settings", file=out)
+    rows = []
+    rule = {"tuned_table": 1}
     for routine in routines:
         for n in sizes:
             if routine[0] == "z" and n > 24576:      # 32768^2 complex doubles are 17 GB: skipped to keep the run short
                 continue
             best, best_us, default_us, _ = auto(routine, n, n)
+            if save:
+                default_us = sweep_settings(routine, n, n, [rule], 3, 8)[0][1]
+            note = ""
+            if save and best and default_us / best_us - 1 >= SAVE_GAIN:
+                # second measurement, rule and candidate alternating
+                (_, r_us), (_, b_us) = sweep_settings(routine, n, n, [{"tuned_table": 1}, best], 5, 8)
+                if r_us / b_us - 1 >= SAVE_GAIN:
+                    # the row will serve a class of sizes: it must not lose at the ends of the class
+                    note = ""
+                    for width in CLASS_WIDTHS:
+                        lo, hi = _size_class(n, width)
+                        ends = []
+                        for ne in (lo, hi - 1):
+                            (_, re_us), (_, be_us) = sweep_settings(routine, ne, ne, [{"tuned_table": 1}, best], 3, 8)
+                            ends.append(100 * (re_us / be_us - 1))
+                        note += f" ends {lo}: {ends[0]:+.1f}% {hi - 1}: {ends[1]:+.1f}%"
+                        if min(ends) >= -1.0:
+                            rows.append(_row_text(routine, n, width, best))
+                            note = f"  saved for [{lo}, {hi}) (second measurement {100 * (r_us / b_us - 1):+.1f}%,{note})"
+                            break
+                    else:
+                        # the split and tile counts that win depend on how the size divides into tiles
+                        rows.append(f"    {{'{_op(routine)}', '{routine[0]}', {n}, {n + 1}, "
+                                    + ", ".join(str(int(best.get(f, 0))) for f in ROW_FIELDS) + f"}},   // {routine} n = {n}")
+                        note = f"  saved for n = {n} alone (second measurement {100 * (r_us / b_us - 1):+.1f}%,{note})"
+                else:
+                    note = f"  not saved (second measurement {100 * (r_us / b_us - 1):+.1f}%)"
             nbytes = acc.algorithmic_bytes(op_of[routine[1:5]](routine), routine[0], n, n)
             text = " ".join(f"{key}={v}" for key, v in best.items()) or "(defaults)"
             print(f"{routine:9s} {n:6d} {default_us:11.1f} {nbytes / default_us / 1e3:8.1f} {best_us:9.1f} "
-                  f"{100 * (default_us / best_us - 1):+5.1f}%  {text}", file=out, flush=True)
+                  f"{100 * (default_us / best_us - 1):+5.1f}%  {text}{note}", file=out, flush=True)
+    return rows
+
+
+def write_rows(rows, path=None):
+    import os
+    path = path or os.path.join(os.path.dirname(os.path.abspath(__file__)), TABLE_FILE)
+    with open(path, "w") as f:
+        f.write("// Written by: python -m paper_1410_1726_amd.tune table --save\n")
+        f.write("// {routine, precision, n_lo, n_hi, " + ", ".join(ROW_FIELDS) + "}; 0 = the planner's rule\n")
+        for r in rows:
+            f.write(r + "\n")
+    return path
 
 
 def main(argv):
     if argv and argv[0] == "table":
-        routines = tuple(argv[1].split(",")) if len(argv) > 1 else TABLE_ROUTINES
+        save = "--save" in argv
+        out_path = None
+        if save:
+            i = argv.index("--save")
+            del argv[i]
+        if "--out" in argv:
+            i = argv.index("--out")
+            out_path = argv[i + 1]
+            del argv[i:i + 2]
+        routines = tuple(argv[1].split(",")) if len(argv) > 1 and argv[1] else TABLE_ROUTINES
         sizes = tuple(int(v) for v in argv[2].split(",")) if len(argv) > 2 else TABLE_SIZES
-        table(routines, sizes)
+        rows = table(routines, sizes, save=save)
+        if save:
+            print(f"{len(rows)} rows written to {write_rows(rows, out_path)}; build the library again to compile them in")
         return 0
     if len(argv) < 2:
         print(__doc__)

@@ -114,7 +114,7 @@ def test_tuning_keys_roundtrip():
     assert "symv_tiles_per_wave" in keys
     for k in keys:
         old = kmv.get_tuning(k)
-        val = {"symv_member_waves": 8, "symv_small_waves": 8, "gemv_tiny_rows": 100}.get(k, 2)
+        val = {"symv_member_waves": 8, "symv_small_waves": 8, "gemv_tiny_rows": 100, "tuned_table": 1}.get(k, 2)
         kmv.set_tuning(k, val)
         assert kmv.get_tuning(k) == val
         kmv.set_tuning(k, old)
@@ -138,7 +138,7 @@ def test_symv_kernel_variant_query():
         for uplo in "LU":
             assert kmv.symv_kernel_variant(prec, uplo, 5000, DUMMY, 5000) == 2
             assert kmv.symv_kernel_variant(prec, uplo, 500, DUMMY, 500) == 3
-            edge = 2048 if prec == "d" else 1792             # largest n of the single-launch kernel
+            edge = {"s": 2176, "d": 2048, "c": 2048, "z": 1664}[prec]   # largest n of the single-launch kernel
             assert kmv.symv_kernel_variant(prec, uplo, edge, DUMMY, edge) == 3
             assert kmv.symv_kernel_variant(prec, uplo, edge + 1, DUMMY, edge + 1) == 2
     try:
@@ -147,6 +147,42 @@ def test_symv_kernel_variant_query():
             assert kmv.symv_kernel_variant("s", "L", 5000, DUMMY, 5000) == v
     finally:
         kmv.set_tuning("symv_variant", 0)
+
+
+def test_table_of_measured_settings():
+    """host-only: every row of the compiled-in table is what the query returns inside its size range, holds legal
+    tuning values, and the tuned_table key switches the table off"""
+    text = open(os.path.join(ROOT, "paper_1410_1726_amd", "csrc", "kmv_tuned_table.inc")).read()
+    rows = re.findall(r"\{'(\w)', '(\w)', (\d+), (\d+), ([-\d, ]+)\}", text)
+    seen = set()
+    for op, prec, lo, hi, vals in rows:
+        lo, hi, vals = int(lo), int(hi), [int(v) for v in vals.split(",")]
+        assert op in "NTLU" and prec in "sdcz" and 0 < lo < hi and len(vals) == len(kmv.TUNED_FIELDS)
+        want = {f: v for f, v in zip(kmv.TUNED_FIELDS, vals) if v}
+        assert want, "a row that sets nothing"
+        for n in (lo, hi - 1):
+            assert kmv.tuned_settings(prec, op, n) == want
+        for r in range(lo, hi, max(1, (hi - lo) // 4)):          # ranges of one routine do not overlap
+            assert (op, prec, r) not in seen
+            seen.add((op, prec, r))
+        try:
+            for key, v in want.items():
+                kmv.set_tuning(key, v)                            # raises on an illegal value
+        finally:
+            for key in want:
+                kmv.set_tuning(key, 0)
+    assert kmv.tuned_settings("d", "N", 7) is None                # far below every measured size
+    with pytest.raises(ValueError):
+        kmv.tuned_settings("q", "N", 4096)
+    with pytest.raises(ValueError):
+        kmv.tuned_settings("d", "X", 4096)
+    if rows:
+        op, prec, lo = rows[0][0], rows[0][1], int(rows[0][2])
+        kmv.set_tuning("tuned_table", 1)
+        try:
+            assert kmv.tuned_settings(prec, op, lo) is None
+        finally:
+            kmv.set_tuning("tuned_table", 0)
 
 
 def test_tuning_tool_grids_and_apply():
