@@ -289,9 +289,12 @@ DTYPE_NAMES = {"s": "f32", "d": "f64", "c": "c64", "z": "c128"}
 
 def sytrd_panel_bench(args, k, torch, wl, acc):
     """One step = the panel step of the tridiagonal reduction (kmv_dsytrd_panel) on the first 64 columns of a
-    16384 x 16384 fp64 matrix: per column one DSYMV on the trailing block, two DGEMV-N with strided x, two
-    DGEMV-T and two DGEMV-N on the reflector panels and two small vector kernels, all enqueued without a host
-    round trip.  The matrix is restored from a copy before every step, outside the timed brackets."""
+    16384 x 16384 fp64 matrix: per column one DSYMV on the trailing block and the products with the two
+    reflector panels (two N products with a row of the other panel, two T and two N products with v) plus the
+    reflector and the scaling of w, which the library runs as three kernels of its own, all enqueued without a
+    host round trip.  The bytes counted are those of the algorithm's products, each panel product as a GEMV of
+    its own (what the step costs when built from BLAS calls), so that the figure compares across
+    implementations.  The matrix is restored from a copy before every step, outside the timed brackets."""
     n, nb, prec, uplo = 16384, 64, args.prec, args.uplo
     A0 = wl.matrix(prec, n, n, n, seed=0, device="cuda")
     A = A0.clone()
@@ -335,8 +338,8 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAMES[prec], "data": "synthetic",
         "config": {"workload": f"panel step of the tridiagonal reduction (kmv_{prec}{'hetrd' if prec in 'cz' else 'sytrd'}_panel, "
-                               f"uplo {uplo}), n=16384, nb=64, lda=n, U[-1,1]: 64 SYMV/HEMV on trailing blocks + 378 GEMV on "
-                               "reflector panels + 128 vector kernels",
+                               f"uplo {uplo}), n=16384, nb=64, lda=n, U[-1,1]: 64 SYMV/HEMV on trailing blocks + 378 products "
+                               "with the reflector panels + 128 vector steps (three fused kernels per column)",
                    "products_per_step": nb + 6 * (nb - 1)},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "gflops": round(nflops / (step_ms * 1e-3) / 1e9, 1),

@@ -261,8 +261,9 @@ int kmv_zsymv_devscalars(char uplo, int64_t n, const kmv_complex128* alpha, cons
  * that column are scratch); columns 0..n-nb-1 of A are not modified and
  * A - V W^T - W V^T on the LEADING (n-nb) x (n-nb) block is the transformed
  * block; column 0 of the matrix has no reflector (e = tau = 0).
- * Only enqueues kernels on `stream` (about nine per column; tau and the inner
- * products stay on the device), so a panel can be captured in a graph.
+ * Only enqueues kernels on `stream` (five per column: the symmetric product's
+ * two and three of the panel's own; tau, the norms and the inner products stay
+ * on the device), so a panel can be captured in a graph.
  * Workspace: kmv_sytrd_panel_workspace_bytes(prec, n, nb), 256-byte aligned.
  * Errors: negated argument number (uplo 1, n 2, nb 3 (0 <= nb <= min(n, 1024)), lda 5,
  * ldw 9), KMV_ERR_NULL, KMV_ERR_WORKSPACE, or the code of a failing launch,

@@ -1,24 +1,27 @@
 // Panel steps of the two-sided reductions - symmetric tridiagonal (below) and
-// bidiagonal (further down) - built on the library's own
-// SYMV and GEMV calls (paper, Section 10: the two-sided reductions spend their
+// bidiagonal (further down) (paper, Section 10: the two-sided reductions spend their
 // memory-bound time in exactly these products - SYMV on the trailing block once
 // per column, GEMV on the tall panels of accumulated reflectors - and always on
 // sub-blocks that start at arbitrary offsets inside the matrix, Section 6.6).
 //
-// The step is the published "latrd" panel of the blocked Householder
+// The tridiagonal step is the published "latrd" panel of the blocked Householder
 // tridiagonalisation, lower storage, written from its definition:
-//   column i:  a  = A[i:,i] - V[i:,:i] W[i,:i]^T - W[i:,:i] V[i,:i]^T        (2 GEMV-N, strided x)
-//              reflector (beta, tau, v) that annihilates a[2:]                (one small kernel)
+//   column i:  a  = A[i:,i] - V[i:,:i] W[i,:i]^T - W[i:,:i] V[i,:i]^T
+//              reflector (beta, tau, v) that annihilates a[2:]
 //              w  = A[i+1:,i+1:] v                                            (SYMV, trailing block)
-//              w -= V[i+1:,:i] (W[i+1:,:i]^T v) + W[i+1:,:i] (V[i+1:,:i]^T v) (2 GEMV-T, 2 GEMV-N)
-//              w  = tau w;  w -= (tau/2)(w.v) v                               (one small kernel)
+//              w -= V[i+1:,:i] (W[i+1:,:i]^T v) + W[i+1:,:i] (V[i+1:,:i]^T v)
+//              w  = tau w;  w -= (tau/2)(w.v) v
+// The symmetric product, which holds 97% of the bytes, goes through the public entry point (the same
+// argument checks, planner and kernels as any other caller's).  The products with the two tall panels
+// (at most nb columns wide) and the vector steps between them are three kernels of this file per column:
+// as six GEMV launches, their second-stage sums and two vector kernels they were eleven launches of 4-11 us
+// each, a quarter of the panel's time for 3% of its bytes.
 // Upper storage runs the mirror image (last nb columns, from the right), complex types the Hermitian form
-// (conjugated transposes, real e); the bidiagonal step further down exists for all four precisions as well.
-// Everything stays on the device and on the caller's stream: tau and the dot
-// product never visit the host, so a whole panel is one uninterrupted sequence of
-// launches (and can be captured in a graph).  The matrix-vector products go
-// through the public entry points, i.e. through the same argument checks,
-// planners and kernels as any other caller's.
+// (conjugated transposes, real e).  The bidiagonal step further down is built on the public GEMV entry
+// points and exists for all four precisions as well.
+// Everything stays on the device and on the caller's stream: tau, the norms and the inner
+// products never visit the host, so a whole panel is one uninterrupted sequence of
+// launches (and can be captured in a graph).
 #include "../../include/kmv.h"
 #include "kmv_common.hpp"
 
@@ -106,50 +109,7 @@ template <class T> __global__ void scale_kernel(int64_t len, const T* s, T* v) {
     if (k < len) v[k] = mul_of(*s, v[k]);
 }
 
-// w <- tau w - (tau/2) ((tau w).v) v.  Then, for the next column's update, the first `cnt` entries of the
-// next row of W and of V (element j at wnext[j*ldw], vnext[j*ldv]; the last one of W is w[0], just written)
-// are copied to the contiguous wrow / vrow, which spares that column two launches for packing strided rows.
-template <class T>
-__global__ __launch_bounds__(PT) void finish_w_kernel(int64_t m, const T* tau, const T* v, T* w, const T* wnext,
-                                                      int64_t ldw, const T* vnext, int64_t ldv, int cnt, T* wrow,
-                                                      T* vrow) {
-    __shared__ T red[PT / WAVE];
-    const T t = *tau;
-    T part = 0;
-    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
-        T wv[PU], vv[PU];
-#pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int64_t k = base + (int64_t)u * PT;
-            wv[u] = k < m ? w[k] : T(0);
-            vv[u] = k < m ? v[k] : T(0);
-        }
-#pragma unroll
-        for (int u = 0; u < PU; ++u) part += (t * wv[u]) * vv[u];
-    }
-    const T c = T(-0.5) * t * block_sum(part, red);
-    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
-        T wv[PU], vv[PU];
-#pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int64_t k = base + (int64_t)u * PT;
-            wv[u] = k < m ? w[k] : T(0);
-            vv[u] = k < m ? v[k] : T(0);
-        }
-#pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int64_t k = base + (int64_t)u * PT;
-            if (k < m) w[k] = t * wv[u] + c * vv[u];
-        }
-    }
-    __syncthreads();     // w[0] is in place for every thread of the workgroup
-    if ((int)threadIdx.x < cnt) {
-        wrow[threadIdx.x] = wnext[threadIdx.x * ldw];
-        vrow[threadIdx.x] = vnext[threadIdx.x * ldv];
-    }
-}
-
-// ---- the same two kernels for complex vectors (C = cf32 / cf64, R its real type) ----
+// ---- the reflector kernel for complex vectors (C = cf32 / cf64, R its real type) ----
 // Reflector for (alpha, x), alpha at *head, x at tail[0..m-2]: beta = -sign(Re alpha) ||(alpha, x)|| is real,
 // tau = (beta - alpha) / beta, x <- x / (alpha - beta), *head = 1; x = 0 with a real alpha gives tau = 0,
 // beta = alpha.  The diagonal element above the head (*diag, the d_i of this column; may be null) loses its
@@ -200,58 +160,272 @@ __global__ __launch_bounds__(PT) void reflector_kernel_c(int64_t m, C* diag, C* 
     }
 }
 
-// w <- tau w - (tau/2) ((tau w)^H v) v, then the conjugated next rows of W and V packed for the next column.
-// The next diagonal element (*diag_next) loses its imaginary part before that column's update reads it: the
-// caller need not have set it, and a product with it would carry whatever it holds into the real part
-// (null for the last column of the panel: the element after it is not the panel's).
-template <class C, class R>
-__global__ __launch_bounds__(PT) void finish_w_kernel_c(int64_t m, const C* tau, const C* v, C* w, const C* wnext,
-                                                        int64_t ldw, const C* vnext, int64_t ldv, int cnt, C* wrow,
-                                                        C* vrow, C* diag_next) {
-    __shared__ R red[PT / WAVE];
-    const C t = *tau;
-    R pr = 0, pi = 0;       // sum of conj(t w_k) v_k
-    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
-        C wv[PU], vv[PU];
+// ---- The tridiagonal panel's own kernels ------------------------------------------------------------------
+// Everything of a column except the symmetric product runs in three launches over row chunks, each launch
+// ending where the next step needs a sum over all rows; the sums travel as one partial per workgroup and are
+// added up in workgroup order by every consumer, so the result does not depend on scheduling:
+//   panel_reflector_kernel  norm of the column from the partials -> beta, tau; scales the reflector's tail;
+//                           partial products  W^H v, V^H v  of its chunk with the panels of earlier columns
+//   (SYMV / HEMV            w = A22 v, the public entry point)
+//   panel_correct_kernel    W^H v, V^H v from the partials;  w <- tau (w - V (W^H v) - W (V^H v)),  partial w^H v
+//   panel_column_kernel     w <- w - (tau/2)(w^H v) v;  the next column catches up with all reflectors so far,
+//                           a <- a - V conj(W[d,:]) - W conj(V[d,:])  (d = its diagonal row), its diagonal
+//                           entry made real, partial sums of squares of its entries beyond the subdiagonal
+// The two tall panels V (in A) and W are read three times per column instead of being the operands of six
+// matrix-vector launches with two vector kernels in between.  All three are bound by the latency of the panel
+// loads, so their shapes aim at many loads in flight: the correct and column kernels run one workgroup per 64
+// rows (up to FG_MAX workgroups), its four waves taking every fourth column of the panels and adding their
+// parts through LDS; the reflector kernel, whose output is 2k sums PER WORKGROUP that every workgroup of the
+// next launch has to add up, runs at most DG_MAX workgroups of 16 waves over 256 rows, the waves again
+// splitting the columns.
+// Row space: the kernels of one column see the rows of its reflector vector v (m rows) and everything that is
+// row-aligned with it; the next column `a` has the same rows, its diagonal entry in row d = 0 (lower storage,
+// HEAD_FIRST) or d = m-1 (upper), its subdiagonal entry next to it.
+constexpr int FT = 256;        // correct / column kernels: threads,
+constexpr int FR = WAVE;       //   rows per pass (one per lane),
+constexpr int FG_MAX = 256;    //   most workgroups
+constexpr int DT = 1024;       // reflector kernel: threads,
+constexpr int DR = 256;        //   rows per pass,
+constexpr int DG_MAX = 64;     //   most workgroups
+constexpr int NB_MAX = 1024;
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int64_t thin_rows(int64_t m) { return FR * ceil_div(m > 0 ? m : 1, (int64_t)FR * FG_MAX); }
+inline unsigned thin_chunks(int64_t m) { return (unsigned)ceil_div(m > 0 ? m : 1, thin_rows(m)); }
+inline int64_t fat_rows(int64_t m) { return DR * ceil_div(m > 0 ? m : 1, (int64_t)DR * DG_MAX); }
+inline unsigned fat_chunks(int64_t m) { return (unsigned)ceil_div(m > 0 ? m : 1, fat_rows(m)); }
+
+template <class T> __device__ __forceinline__ T conj_of(T a) {
+    if constexpr (Traits<T>::cplx) return T{a.re, -a.im};
+    else return a;
+}
+template <class T> __device__ __forceinline__ T from_one() {
+    if constexpr (Traits<T>::cplx) return T{1, 0};
+    else return T(1);
+}
+template <class T> __device__ __forceinline__ T neg_of(T a) {
+    if constexpr (Traits<T>::cplx) return T{-a.re, -a.im};
+    else return -a;
+}
+template <class T> __device__ __forceinline__ typename Traits<T>::real abs2_of(T a) {
+    if constexpr (Traits<T>::cplx) return a.re * a.re + a.im * a.im;
+    else return a * a;
+}
+template <class T> __device__ __forceinline__ T half_neg_of(T a) {      // -a/2
+    if constexpr (Traits<T>::cplx) return T{(typename Traits<T>::real)(-0.5) * a.re, (typename Traits<T>::real)(-0.5) * a.im};
+    else return T(-0.5) * a;
+}
+// sum over the NT threads of the workgroup in a fixed order (lanes by DPP, then the waves in wave order);
+// red holds one slot per wave
+template <int NT, class T> __device__ __forceinline__ T group_sum(T v, T* red) {
+    const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE;
+    const T s = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) red[w] = s;
+    __syncthreads();
+    T tot = red[0];
 #pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int64_t k = base + (int64_t)u * PT;
-            wv[u] = k < m ? w[k] : C{0, 0};
-            vv[u] = k < m ? v[k] : C{0, 0};
-        }
-#pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const R sr = t.re * wv[u].re - t.im * wv[u].im, si = t.re * wv[u].im + t.im * wv[u].re;   // t w
-            pr += sr * vv[u].re + si * vv[u].im;
-            pi += sr * vv[u].im - si * vv[u].re;
+    for (int q = 1; q < NT / WAVE; ++q) tot = add_of(tot, red[q]);
+    return tot;
+}
+
+template <class T, bool HEAD_FIRST>
+__global__ __launch_bounds__(FT) void panel_column_kernel(int64_t m, int64_t rpw, int k, const T* __restrict__ Vp, int64_t ldv,
+                                                          const T* __restrict__ Wp, int64_t ldw, const T* __restrict__ v, T* w,
+                                                          const T* tau, const T* wdot, int gw, const T* whead, T* a,
+                                                          typename Traits<T>::real* normpart, T* alpha_out, int finalize,
+                                                          int has_next) {
+    using R = typename Traits<T>::real;
+    __shared__ T wr[NB_MAX + 1], vr[NB_MAX + 1];
+    __shared__ T part[FT / WAVE][FR];
+    __shared__ T red[FT / WAVE];
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    const int64_t rd = HEAD_FIRST ? 0 : m - 1, ra = HEAD_FIRST ? 1 : m - 2;
+    const bool update = finalize && has_next;
+    T c = zero_of<T>();
+    if (finalize) {
+        T d = zero_of<T>();
+        for (int g = threadIdx.x; g < gw; g += FT) d = add_of(d, wdot[g]);
+        c = mul_of(half_neg_of(*tau), group_sum<FT>(d, red));
+        if (has_next) {
+            for (int j = threadIdx.x; j < k; j += FT) {
+                wr[j] = conj_of(Wp[rd + j * ldw]);
+                vr[j] = conj_of(Vp[rd + j * ldv]);
+            }
+            if (threadIdx.x == 0) {
+                T wf = *whead;
+                fma_acc(wf, c, v[rd]);
+                wr[k] = conj_of(wf);
+                vr[k] = conj_of(v[rd]);
+            }
+            __syncthreads();
         }
     }
-    const R dr = block_sum(pr, red), di = block_sum(pi, red);
-    // c = -(t/2) * dot
-    const C c{R(-0.5) * (t.re * dr - t.im * di), R(-0.5) * (t.re * di + t.im * dr)};
-    for (int64_t base = threadIdx.x; base < m; base += (int64_t)PU * PT) {
-        C wv[PU], vv[PU];
-#pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int64_t k = base + (int64_t)u * PT;
-            wv[u] = k < m ? w[k] : C{0, 0};
-            vv[u] = k < m ? v[k] : C{0, 0};
+    R nrm = 0;
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
+    for (int64_t rb = r0; rb < r1; rb += FR) {
+        const int64_t r = rb + lane;
+        const bool in = r < r1;
+        if (update) {
+            T sub = zero_of<T>();
+            if (in) {
+#pragma unroll 8
+                for (int j = wv; j < k; j += FT / WAVE) {
+                    fma_acc(sub, Vp[r + j * ldv], wr[j]);
+                    fma_acc(sub, Wp[r + j * ldw], vr[j]);
+                }
+            }
+            part[wv][lane] = sub;
+            __syncthreads();
         }
+        if (wv == 0 && in) {
+            T vv = zero_of<T>(), wf = zero_of<T>();
+            if (finalize) {
+                vv = v[r];
+                wf = w[r];
+                fma_acc(wf, c, vv);
+                w[r] = wf;
+            }
+            if (has_next) {
+                T acc = a[r];
+                if (finalize) {
+                    T sub = part[0][lane];
 #pragma unroll
-        for (int u = 0; u < PU; ++u) {
-            const int64_t k = base + (int64_t)u * PT;
-            if (k < m)
-                w[k] = C{t.re * wv[u].re - t.im * wv[u].im + c.re * vv[u].re - c.im * vv[u].im,
-                         t.re * wv[u].im + t.im * wv[u].re + c.re * vv[u].im + c.im * vv[u].re};
+                    for (int q = 1; q < FT / WAVE; ++q) sub = add_of(sub, part[q][lane]);
+                    fma_acc(sub, vv, wr[k]);
+                    fma_acc(sub, wf, vr[k]);
+                    acc = add_of(acc, neg_of(sub));
+                }
+                if (r == rd) acc = real_part_only(acc);
+                a[r] = acc;
+                if (r == ra) *alpha_out = acc;
+                if (r != rd && r != ra) nrm += abs2_of(acc);
+            }
         }
+        if (update) __syncthreads();     // part is written again in the next pass
+    }
+    if (has_next && wv == 0) {
+        nrm = wave_sum(nrm);
+        if (lane == 0) normpart[blockIdx.x] = nrm;
+    }
+}
+
+// Reflector of the column `a` (m rows, diagonal entry in row rd, alpha next to it, x the rest): beta = -sign(Re alpha)
+// ||(alpha, x)||, tau = (beta - alpha) / beta, x <- x / (alpha - beta), a[ra] = 1; x = 0 (and a real alpha) gives
+// tau = 0, beta = alpha.  alpha and ||x||^2 come from the launch before (every workgroup overwrites its part of
+// the column, so none may read another's).  Then the chunk's share of  W^H v  and  V^H v  for the kp columns of
+// the panels: dots[g][j] and dots[g][kp + j].
+template <class T, bool HEAD_FIRST>
+__global__ __launch_bounds__(DT) void panel_reflector_kernel(int64_t m, int64_t rpw, int kp, const T* __restrict__ Vp, int64_t ldv,
+                                                             const T* __restrict__ Wp, int64_t ldw, T* a,
+                                                             const typename Traits<T>::real* normpart, int gn, const T* alpha_in,
+                                                             typename Traits<T>::real* e, T* tau, T* dots) {
+    using R = typename Traits<T>::real;
+    __shared__ R red[DT / WAVE];
+    const int64_t rd = HEAD_FIRST ? 0 : m - 1, ra = HEAD_FIRST ? 1 : m - 2;
+    R x2 = 0;
+    for (int g = threadIdx.x; g < gn; g += DT) x2 += normpart[g];
+    const R xn2 = group_sum<DT>(x2, red);
+    const T alpha = *alpha_in;
+    R beta, are, aim = 0;
+    if constexpr (Traits<T>::cplx) { are = alpha.re; aim = alpha.im; }
+    else are = alpha;
+    beta = are;
+    T t = zero_of<T>(), scale = zero_of<T>();
+    const bool have = xn2 != 0 || aim != 0;
+    if (have) {
+        beta = -copysign(sqrt(are * are + aim * aim + xn2), are);
+        const R dr = are - beta, den = dr * dr + aim * aim;      // 1 / (alpha - beta)
+        if constexpr (Traits<T>::cplx) {
+            t = T{(beta - are) / beta, -aim / beta};
+            scale = T{dr / den, -aim / den};
+        } else {
+            t = (beta - are) / beta;
+            scale = R(1) / dr;
+        }
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
+    for (int64_t r = r0 + threadIdx.x; r < r1; r += DT) {
+        if (r == rd) continue;
+        if (r == ra) a[r] = from_one<T>();
+        else if (have) a[r] = mul_of(a[r], scale);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *e = beta;
+        *tau = t;
+    }
+    if (kp == 0) return;
+    __syncthreads();     // the chunk of v is in place for all waves of the workgroup
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    for (int j = wv; j < kp; j += DT / WAVE) {
+        T aw = zero_of<T>(), av = zero_of<T>();
+#pragma unroll 4
+        for (int64_t r = r0 + lane; r < r1; r += WAVE) {
+            const T x = r == rd ? zero_of<T>() : a[r];
+            fma_acc_conj(aw, Wp[r + j * ldw], x);
+            fma_acc_conj(av, Vp[r + j * ldv], x);
+        }
+        aw = wave_sum(aw);
+        av = wave_sum(av);
+        if (lane == 0) {
+            dots[(int64_t)blockIdx.x * 2 * kp + j] = aw;
+            dots[(int64_t)blockIdx.x * 2 * kp + kp + j] = av;
+        }
+    }
+}
+
+// w <- tau (w - V s1 - W s2) with s1 = W^H v, s2 = V^H v summed from the gd partial rows of `dots`; the chunk's
+// share of w^H v goes to wdot[g], the entry of w in row rd (the next column's diagonal row) to *whead as well:
+// the next launch rewrites w, and all its workgroups need that one entry as it is now.
+template <class T>
+__global__ __launch_bounds__(FT) void panel_correct_kernel(int64_t m, int64_t rpw, int k, const T* __restrict__ Vp, int64_t ldv,
+                                                           const T* __restrict__ Wp, int64_t ldw, const T* __restrict__ v, T* w,
+                                                           const T* tau, const T* __restrict__ dots, int gd, int64_t rd, T* wdot,
+                                                           T* whead) {
+    __shared__ T s1[NB_MAX], s2[NB_MAX];
+    __shared__ T part[FT / WAVE][FR];
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    for (int j = threadIdx.x; j < 2 * k; j += FT) {
+        T s = zero_of<T>();
+#pragma unroll 8
+        for (int g = 0; g < gd; ++g) s = add_of(s, dots[(int64_t)g * 2 * k + j]);
+        if (j < k) s1[j] = s;
+        else s2[j - k] = s;
     }
     __syncthreads();
-    if ((int)threadIdx.x < cnt) {
-        const C a = wnext[threadIdx.x * ldw], b = vnext[threadIdx.x * ldv];
-        wrow[threadIdx.x] = C{a.re, -a.im};
-        vrow[threadIdx.x] = C{b.re, -b.im};
+    const T t = *tau;
+    T dot = zero_of<T>();
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
+    for (int64_t rb = r0; rb < r1; rb += FR) {
+        const int64_t r = rb + lane;
+        const bool in = r < r1;
+        T sub = zero_of<T>();
+        if (in) {
+#pragma unroll 8
+            for (int j = wv; j < k; j += FT / WAVE) {
+                fma_acc(sub, Vp[r + j * ldv], s1[j]);
+                fma_acc(sub, Wp[r + j * ldw], s2[j]);
+            }
+        }
+        part[wv][lane] = sub;
+        __syncthreads();
+        if (wv == 0 && in) {
+            T tot = part[0][lane];
+#pragma unroll
+            for (int q = 1; q < FT / WAVE; ++q) tot = add_of(tot, part[q][lane]);
+            const T wn = mul_of(t, add_of(w[r], neg_of(tot)));
+            w[r] = wn;
+            if (r == rd) *whead = wn;
+            fma_acc_conj(dot, wn, v[r]);
+        }
+        __syncthreads();     // part is written again in the next pass
     }
-    if (threadIdx.x == 0 && diag_next) diag_next->im = 0;
+    if (wv == 0) {
+        dot = wave_sum(dot);
+        if (lane == 0) wdot[blockIdx.x] = dot;
+    }
 }
 
 // a column without a reflector: e = tau = 0, the diagonal element real
@@ -314,25 +488,38 @@ template <> struct Calls<cf64> {
 
 inline size_t max_of(size_t a, size_t b) { return a > b ? a : b; }
 
-// bytes at the front of the workspace for the two packed rows (nb elements each)
-template <class T> size_t rows_bytes(int64_t nb) {
-    return (size_t)((2 * nb * sizeof(T) + 255) / 256) * 256;
-}
+// Front of the workspace: what the panel's own kernels hand to each other.  alpha and the entry of w in the
+// next diagonal row (256 bytes), then one partial per workgroup of the norms and of w^H v, then the partial
+// products with the panels (2 nb per workgroup of the reflector kernel).
+template <class T> struct PanelScratch {
+    using R = typename Traits<T>::real;
+    T* alpha;
+    T* whead;
+    R* normpart;
+    T* wdot;
+    T* dots;
+    static size_t bytes(int64_t nb) {
+        return 256 + round_up(FG_MAX * sizeof(R), 256) + round_up(FG_MAX * sizeof(T), 256) +
+               round_up((size_t)DG_MAX * 2 * (size_t)nb * sizeof(T), 256);
+    }
+    explicit PanelScratch(void* base) {
+        char* p = static_cast<char*>(base);
+        alpha = reinterpret_cast<T*>(p);
+        whead = alpha + 1;
+        normpart = reinterpret_cast<R*>(p + 256);
+        wdot = reinterpret_cast<T*>(p + 256 + round_up(FG_MAX * sizeof(R), 256));
+        dots = reinterpret_cast<T*>(p + 256 + round_up(FG_MAX * sizeof(R), 256) + round_up(FG_MAX * sizeof(T), 256));
+    }
+};
 
-// the packed rows plus the largest workspace any product of the panel asks for
+// the panel's own scratch plus the largest workspace a symmetric product of the panel asks for
 template <class T> size_t panel_workspace(int64_t n, int64_t nb) {
     if (n <= 0 || nb <= 0) return 0;
     if (nb > n) nb = n;
     size_t need = 0;
-    for (int64_t i = 0; i < nb; ++i) {
-        need = max_of(need, kmv_gemv_workspace_bytes(Calls<T>::prec, 'N', n - i, i));
-        if (i < n - 1) {
-            need = max_of(need, kmv_symv_workspace_bytes(Calls<T>::prec, 'L', n - i - 1));
-            need = max_of(need, kmv_gemv_workspace_bytes(Calls<T>::prec, 'T', n - i - 1, i));
-            need = max_of(need, kmv_gemv_workspace_bytes(Calls<T>::prec, 'N', n - i - 1, i));
-        }
-    }
-    return rows_bytes<T>(nb) + need;
+    for (int64_t i = 0; i < nb && i < n - 1; ++i)
+        need = max_of(need, kmv_symv_workspace_bytes(Calls<T>::prec, 'L', n - i - 1));
+    return PanelScratch<T>::bytes(nb) + need;
 }
 
 // T real: SYTRD panel; T complex (cf32 / cf64): HETRD panel, e real, transposes conjugated
@@ -351,119 +538,90 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
     if (n == 0 || nb == 0) return KMV_OK;
     if (!A || !e || !tau || !W) return KMV_ERR_NULL;
     if (!ws || wsb < panel_workspace<T>(n, nb) || ((uintptr_t)ws % 256) != 0) return KMV_ERR_WORKSPACE;
-    static_assert(PT >= 1024, "the row copy at the end of finish_w_kernel uses one thread per column of the panel");
-    if (nb > PT) return -3;
-    T* wrow = static_cast<T*>(ws);           // row i of W and of V, packed by the column before
-    T* vrow = wrow + nb;
-    ws = static_cast<char*>(ws) + rows_bytes<T>(nb);
-    wsb -= rows_bytes<T>(nb);
+    if (nb > NB_MAX) return -3;
+    const PanelScratch<T> sc(ws);
+    ws = static_cast<char*>(ws) + PanelScratch<T>::bytes(nb);
+    wsb -= PanelScratch<T>::bytes(nb);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const T one = from_real<T>(1), zero = from_real<T>(0), minus = from_real<T>(-1);
-    const auto gemv = Calls<T>::gemv;
+    const T one = from_real<T>(1), zero = from_real<T>(0);
     const auto symv = Calls<T>::symv;
-    int rc = KMV_OK;
+    const T* nullc = nullptr;
+    T* nullm = nullptr;
+#define KMV_PANEL_CHECK()                                        \
+    do {                                                         \
+        const hipError_t he_ = hipGetLastError();                \
+        if (he_ != hipSuccess) return KMV_ERR_HIP + (int)he_;    \
+    } while (0)
     if (!lower) {
         // Upper storage: the mirror image.  The LAST nb columns are reduced, from column n-1 down to n-nb; column
         // i has slot iw = i - (n - nb) in e, tau and W; its reflector annihilates A[0:i-1, i], v = A[0:i, i] with
         // the one at row i-1; the k = n-1-i columns to its right are the reflectors and W columns done before.
         const int64_t first = n - nb;
+        // norm and alpha of the first column to go (it has nothing to catch up with)
+        hipLaunchKernelGGL((panel_column_kernel<T, false>), dim3(thin_chunks(n)), dim3(FT), 0, s, n, thin_rows(n), 0, nullc,
+                           (int64_t)0, nullc, (int64_t)0, nullc, nullm, nullc, nullc, 0, nullc, A + (n - 1) * lda, sc.normpart,
+                           sc.alpha, 0, 1);
+        KMV_PANEL_CHECK();
         for (int64_t i = n - 1; i >= first; --i) {
-            const int64_t iw = i - first, k = n - 1 - i;
-            T* col = A + i * lda;                    // A[0:i+1, i]
-            if (k > 0) {
-                rc = gemv('N', i + 1, k, &minus, A + (i + 1) * lda, lda, wrow, 1, &one, col, 1, ws, wsb, stream);
-                if (rc) return rc;
-                rc = gemv('N', i + 1, k, &minus, W + (iw + 1) * ldw, ldw, vrow, 1, &one, col, 1, ws, wsb, stream);
-                if (rc) return rc;
-            }
+            const int64_t iw = i - first, k = n - 1 - i, mp = i + 1;
+            T* col = A + i * lda;                    // A[0:i+1, i], the diagonal entry last
             if (i == 0) {   // first column of the matrix: no reflector
                 if constexpr (CPLX) hipLaunchKernelGGL((no_reflector_kernel_c<T, R>), dim3(1), dim3(1), 0, s, col, e + iw, tau + iw);
                 else hipLaunchKernelGGL((no_reflector_kernel<T, T>), dim3(1), dim3(1), 0, s, e + iw, tau + iw);
-                const hipError_t he = hipGetLastError();
-                if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+                KMV_PANEL_CHECK();
                 continue;
             }
-            const int64_t m = i;                     // length of v
-            T* head = col + (i - 1);                 // A[i-1, i]
+            const T* Vp = A + (i + 1) * lda;         // the k columns to the right: reflectors ...
+            const T* Wp = W + (iw + 1) * ldw;        // ... and their companions
+            hipLaunchKernelGGL((panel_reflector_kernel<T, false>), dim3(fat_chunks(mp)), dim3(DT), 0, s, mp, fat_rows(mp), (int)k,
+                               Vp, lda, Wp, ldw, col, sc.normpart, (int)thin_chunks(mp), sc.alpha, e + iw, tau + iw, sc.dots);
+            KMV_PANEL_CHECK();
+            const int64_t m = i;                     // length of v = A[0:i, i]
             T* w = W + iw * ldw;                     // W[0:i, iw]
-            T* small = W + (i + 1) + iw * ldw;       // W[i+1:, iw]: the k-vector of the corrections
-            if constexpr (CPLX) hipLaunchKernelGGL((reflector_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, col + i, head, col, e + iw, tau + iw);
-            else hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, head, col, (int64_t)1, e + iw, tau + iw);
-            hipError_t he = hipGetLastError();
-            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
-            rc = symv('U', m, &one, A, lda, col, 1, &zero, w, 1, ws, wsb, stream);
+            const int rc = symv('U', m, &one, A, lda, col, 1, &zero, w, 1, ws, wsb, stream);
             if (rc) return rc;
-            if (k > 0) {
-                rc = gemv(TC, m, k, &one, W + (iw + 1) * ldw, ldw, col, 1, &zero, small, 1, ws, wsb, stream);
-                if (rc) return rc;
-                rc = gemv('N', m, k, &minus, A + (i + 1) * lda, lda, small, 1, &one, w, 1, ws, wsb, stream);
-                if (rc) return rc;
-                rc = gemv(TC, m, k, &one, A + (i + 1) * lda, lda, col, 1, &zero, small, 1, ws, wsb, stream);
-                if (rc) return rc;
-                rc = gemv('N', m, k, &minus, W + (iw + 1) * ldw, ldw, small, 1, &one, w, 1, ws, wsb, stream);
-                if (rc) return rc;
-            }
-            // w finished; row i-1 of W (slots iw..) and of V (columns i..) packed for column i-1
-            if constexpr (CPLX)
-                hipLaunchKernelGGL((finish_w_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, tau + iw, col, w, W + (i - 1) + iw * ldw,
-                                   ldw, A + (i - 1) + i * lda, lda, (int)(k + 1), wrow, vrow,
-                                   i - 1 >= first ? A + (i - 1) + (i - 1) * lda : (T*)nullptr);
-            else
-                hipLaunchKernelGGL((finish_w_kernel<T>), dim3(1), dim3(PT), 0, s, m, tau + iw, col, w, W + (i - 1) + iw * ldw, ldw,
-                                   A + (i - 1) + i * lda, lda, (int)(k + 1), wrow, vrow);
-            he = hipGetLastError();
-            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+            hipLaunchKernelGGL((panel_correct_kernel<T>), dim3(thin_chunks(m)), dim3(FT), 0, s, m, thin_rows(m), (int)k, Vp, lda, Wp,
+                               ldw, col, w, tau + iw, sc.dots, (int)fat_chunks(mp), m - 1, sc.wdot, sc.whead);
+            KMV_PANEL_CHECK();
+            hipLaunchKernelGGL((panel_column_kernel<T, false>), dim3(thin_chunks(m)), dim3(FT), 0, s, m, thin_rows(m), (int)k, Vp, lda,
+                               Wp, ldw, col, w, tau + iw, sc.wdot, (int)thin_chunks(m), sc.whead, A + (i - 1) * lda, sc.normpart,
+                               sc.alpha, 1, i - 1 >= first ? 1 : 0);
+            KMV_PANEL_CHECK();
         }
         return KMV_OK;
     }
+    hipLaunchKernelGGL((panel_column_kernel<T, true>), dim3(thin_chunks(n)), dim3(FT), 0, s, n, thin_rows(n), 0, nullc, (int64_t)0,
+                       nullc, (int64_t)0, nullc, nullm, nullc, nullc, 0, nullc, A, sc.normpart, sc.alpha, 0, 1);
+    KMV_PANEL_CHECK();
     for (int64_t i = 0; i < nb; ++i) {
-        T* col = A + i + i * lda;               // A[i:, i]
-        if (i > 0) {
-            // column i catches up with the reflectors before it; x is row i of W, then row i of V (= of A),
-            // both packed (and conjugated in the complex case) by the last kernel of column i-1
-            rc = gemv('N', n - i, i, &minus, A + i, lda, wrow, 1, &one, col, 1, ws, wsb, stream);
-            if (rc) return rc;
-            rc = gemv('N', n - i, i, &minus, W + i, ldw, vrow, 1, &one, col, 1, ws, wsb, stream);
-            if (rc) return rc;
-        }
+        T* col = A + i + i * lda;               // A[i:, i], up to date: the diagonal entry first
+        const int64_t mp = n - i;
         if (i >= n - 1) {   // last column of the matrix: no reflector; its slots are defined all the same
             if constexpr (CPLX) hipLaunchKernelGGL((no_reflector_kernel_c<T, R>), dim3(1), dim3(1), 0, s, col, e + i, tau + i);
             else hipLaunchKernelGGL((no_reflector_kernel<T, T>), dim3(1), dim3(1), 0, s, e + i, tau + i);
-            const hipError_t he = hipGetLastError();
-            if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+            KMV_PANEL_CHECK();
             continue;
         }
+        hipLaunchKernelGGL((panel_reflector_kernel<T, true>), dim3(fat_chunks(mp)), dim3(DT), 0, s, mp, fat_rows(mp), (int)i, A + i,
+                           lda, W + i, ldw, col, sc.normpart, (int)thin_chunks(mp), sc.alpha, e + i, tau + i, sc.dots);
+        KMV_PANEL_CHECK();
         const int64_t m = n - i - 1;
         T* v = col + 1;                         // A[i+1:, i]
         T* w = W + (i + 1) + i * ldw;           // W[i+1:, i]
-        T* small = W + i * ldw;                 // W[:i, i]: the i-vector of the corrections
-        if constexpr (CPLX) hipLaunchKernelGGL((reflector_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, col, v, v + 1, e + i, tau + i);
-        else hipLaunchKernelGGL((reflector_kernel<T>), dim3(1), dim3(PT), 0, s, m, v, v + 1, (int64_t)1, e + i, tau + i);
-        hipError_t he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
-        rc = symv('L', m, &one, A + (i + 1) + (i + 1) * lda, lda, v, 1, &zero, w, 1, ws, wsb, stream);
+        const int rc = symv('L', m, &one, A + (i + 1) + (i + 1) * lda, lda, v, 1, &zero, w, 1, ws, wsb, stream);
         if (rc) return rc;
-        if (i > 0) {
-            rc = gemv(TC, m, i, &one, W + i + 1, ldw, v, 1, &zero, small, 1, ws, wsb, stream);
-            if (rc) return rc;
-            rc = gemv('N', m, i, &minus, A + i + 1, lda, small, 1, &one, w, 1, ws, wsb, stream);
-            if (rc) return rc;
-            rc = gemv(TC, m, i, &one, A + i + 1, lda, v, 1, &zero, small, 1, ws, wsb, stream);
-            if (rc) return rc;
-            rc = gemv('N', m, i, &minus, W + i + 1, ldw, small, 1, &one, w, 1, ws, wsb, stream);
-            if (rc) return rc;
-        }
-        if constexpr (CPLX)
-            hipLaunchKernelGGL((finish_w_kernel_c<T, R>), dim3(1), dim3(PT), 0, s, m, tau + i, v, w, W + (i + 1), ldw,
-                               A + (i + 1), lda, (int)(i + 1), wrow, vrow,
-                               i + 1 < nb ? A + (i + 1) + (i + 1) * lda : (T*)nullptr);
-        else
-            hipLaunchKernelGGL((finish_w_kernel<T>), dim3(1), dim3(PT), 0, s, m, tau + i, v, w, W + (i + 1), ldw,
-                               A + (i + 1), lda, (int)(i + 1), wrow, vrow);
-        he = hipGetLastError();
-        if (he != hipSuccess) return KMV_ERR_HIP + (int)he;
+        const T* Vp = A + i + 1;                // rows i+1.. of the i reflectors before ...
+        const T* Wp = W + i + 1;                // ... and of their companions
+        hipLaunchKernelGGL((panel_correct_kernel<T>), dim3(thin_chunks(m)), dim3(FT), 0, s, m, thin_rows(m), (int)i, Vp, lda, Wp, ldw,
+                           v, w, tau + i, sc.dots, (int)fat_chunks(mp), (int64_t)0, sc.wdot, sc.whead);
+        KMV_PANEL_CHECK();
+        hipLaunchKernelGGL((panel_column_kernel<T, true>), dim3(thin_chunks(m)), dim3(FT), 0, s, m, thin_rows(m), (int)i, Vp, lda, Wp,
+                           ldw, v, w, tau + i, sc.wdot, (int)thin_chunks(m), sc.whead, A + (i + 1) + (i + 1) * lda, sc.normpart,
+                           sc.alpha, 1, i + 1 < nb ? 1 : 0);
+        KMV_PANEL_CHECK();
     }
     return KMV_OK;
+#undef KMV_PANEL_CHECK
 }
 
 // bytes at the front of the workspace for the contiguous copy of the current row
