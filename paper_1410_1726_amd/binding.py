@@ -16,8 +16,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# KMV_LIBRARY selects another build of the same library (tuning experiments)
-LIB_PATH = os.environ.get("KMV_LIBRARY") or os.path.join(_HERE, "libkmv.so")
+LIB_PATH = os.path.join(_HERE, "libkmv.so")
 
 ERR_WORKSPACE = 1001
 ERR_NULL = 1002
@@ -138,13 +137,25 @@ def _ptr(t, prec=None):
 _ws_cache: dict = {}
 
 
-def workspace(nbytes: int, device=None) -> torch.Tensor:
-    """Grow-only per-device byte buffer (torch owns the memory)."""
+def _stream_handle(stream, device=None) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    return int(stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+def workspace(nbytes: int, device=None, stream=None) -> torch.Tensor:
+    """Grow-only byte buffer per (device, stream) (torch owns the memory).  Products enqueued on different
+    streams run concurrently and must not share partial sums, so each stream gets a buffer of its own; a
+    buffer that has to grow is replaced only after the device has finished the work that may still use it.
+    A caller that passes its own workspace must keep to the same rule: one workspace per stream."""
     dev = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
-    buf = _ws_cache.get(dev)
+    key = (dev, _stream_handle(stream, dev))
+    buf = _ws_cache.get(key)
     if buf is None or buf.numel() < nbytes:
+        if buf is not None:
+            torch.cuda.synchronize(dev)
         buf = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
-        _ws_cache[dev] = buf
+        _ws_cache[key] = buf
     return buf
 
 
@@ -176,11 +187,11 @@ def symv_workspace_bytes(prec, uplo, n) -> int:
     return v
 
 
-def _ws_args(workspace_, need, y):
-    """(pointer, bytes) of the workspace: None -> cached torch buffer of `need()`
+def _ws_args(workspace_, need, y, stream=None):
+    """(pointer, bytes) of the workspace: None -> the stream's cached torch buffer of `need()`
     bytes, a tensor -> its storage, a (pointer, bytes) tuple -> as given."""
     if workspace_ is None:
-        workspace_ = workspace(need(), None if isinstance(y, int) else y.device)
+        workspace_ = workspace(need(), None if isinstance(y, int) else y.device, stream)
     if isinstance(workspace_, tuple):
         return workspace_
     return workspace_.data_ptr(), workspace_.numel() * workspace_.element_size()
@@ -188,7 +199,7 @@ def _ws_args(workspace_, need, y):
 
 def _gemv(prec, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace_=None, stream=None, check=True):
     wsp, wsb = _ws_args(workspace_, lambda: gemv_workspace_bytes(
-        prec, trans if trans in tuple("NnTtCc") else "N", max(m, 0), max(n, 0)), y)
+        prec, trans if trans in tuple("NnTtCc") else "N", max(m, 0), max(n, 0)), y, stream)
     al, be = _scalar(prec, alpha), _scalar(prec, beta)
     rc = getattr(lib, f"kmv_{prec}gemv")(trans.encode(), m, n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be,
                                          _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -199,7 +210,7 @@ def _gemv(prec, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace_=N
 
 def _symv(name, prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace_=None, stream=None, check=True):
     wsp, wsb = _ws_args(workspace_, lambda: symv_workspace_bytes(
-        prec, uplo if uplo in tuple("LlUu") else "L", max(n, 0)), y)
+        prec, uplo if uplo in tuple("LlUu") else "L", max(n, 0)), y, stream)
     al, be = _scalar(prec, alpha), _scalar(prec, beta)
     rc = getattr(lib, f"kmv_{name}")(uplo.encode(), n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be,
                                      _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -271,8 +282,8 @@ class Prepared:
 def prepare_gemv(prec, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None) -> Prepared:
     if workspace is None:
         workspace = _cached_workspace(gemv_workspace_bytes(prec, trans, max(m, 0), max(n, 0)),
-                                           None if isinstance(y, int) else y.device)
-    wsp, wsb = _ws_args(workspace, None, y)
+                                      None if isinstance(y, int) else y.device, stream)
+    wsp, wsb = _ws_args(workspace, None, y, stream)
     al, be = _scalar(prec, alpha), _scalar(prec, beta)
     args = (trans.encode(), m, n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be, _ptr(y, prec), incy,
             ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -287,8 +298,8 @@ def prepare_symv(prec, uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace
     name = f"{prec}{'hemv' if prec in 'cz' and not complex_symmetric else 'symv'}"
     if workspace is None:
         workspace = _cached_workspace(symv_workspace_bytes(prec, uplo, max(n, 0)),
-                                           None if isinstance(y, int) else y.device)
-    wsp, wsb = _ws_args(workspace, None, y)
+                                      None if isinstance(y, int) else y.device, stream)
+    wsp, wsb = _ws_args(workspace, None, y, stream)
     al, be = _scalar(prec, alpha), _scalar(prec, beta)
     args = (uplo.encode(), n, al, _ptr(A, prec), lda, _ptr(x, prec), incx, be, _ptr(y, prec), incy,
             ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -307,7 +318,7 @@ def _gemv_offset(prec):
     def call(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, offset_r, offset_c, workspace=None, stream=None,
              check=True):
         wsp, wsb = _ws_args(workspace, lambda: gemv_workspace_bytes(
-            prec, trans if trans in tuple("NnTtCc") else "N", max(m - offset_r, 0), max(n - offset_c, 0)), y)
+            prec, trans if trans in tuple("NnTtCc") else "N", max(m - offset_r, 0), max(n - offset_c, 0)), y, stream)
         rc = getattr(lib, f"kmv_{prec}gemv_offset")(
             trans.encode(), m, n, _scalar(prec, alpha), _ptr(A, prec), lda, _ptr(x, prec), incx, _scalar(prec, beta),
             _ptr(y, prec), incy, offset_r, offset_c, ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -324,7 +335,7 @@ def _symv_offset(prec, complex_symmetric=False):
 
     def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, offset, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: symv_workspace_bytes(
-            prec, uplo if uplo in tuple("LlUu") else "L", max(n - offset, 0)), y)
+            prec, uplo if uplo in tuple("LlUu") else "L", max(n - offset, 0)), y, stream)
         rc = getattr(lib, f"kmv_{name}")(
             uplo.encode(), n, _scalar(prec, alpha), _ptr(A, prec), lda, _ptr(x, prec), incx, _scalar(prec, beta),
             _ptr(y, prec), incy, offset, ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -339,7 +350,7 @@ def _symv_offset(prec, complex_symmetric=False):
 def _gemv_devscalars(prec):
     def call(trans, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: gemv_workspace_bytes(
-            prec, trans if trans in tuple("NnTtCc") else "N", max(m, 0), max(n, 0)), y)
+            prec, trans if trans in tuple("NnTtCc") else "N", max(m, 0), max(n, 0)), y, stream)
         rc = getattr(lib, f"kmv_{prec}gemv_devscalars")(
             trans.encode(), m, n, _ptr(alpha, prec), _ptr(A, prec), lda, _ptr(x, prec), incx, _ptr(beta, prec),
             _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -356,7 +367,7 @@ def _symv_devscalars(prec, complex_symmetric=False):
 
     def call(uplo, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None, check=True):
         wsp, wsb = _ws_args(workspace, lambda: symv_workspace_bytes(
-            prec, uplo if uplo in tuple("LlUu") else "L", max(n, 0)), y)
+            prec, uplo if uplo in tuple("LlUu") else "L", max(n, 0)), y, stream)
         rc = getattr(lib, f"kmv_{name}")(
             uplo.encode(), n, _ptr(alpha, prec), _ptr(A, prec), lda, _ptr(x, prec), incx, _ptr(beta, prec),
             _ptr(y, prec), incy, ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -470,7 +481,7 @@ def _sytrd_panel(prec):
     eprec = {"s": "s", "d": "d", "c": "s", "z": "d"}[prec]      # e is real
 
     def call(uplo, n, nb, A, lda, e, tau, W, ldw, workspace=None, stream=None, check=True):
-        wsp, wsb = _ws_args(workspace, lambda: sytrd_panel_workspace_bytes(prec, max(n, 0), max(min(nb, n), 0)), A)
+        wsp, wsb = _ws_args(workspace, lambda: sytrd_panel_workspace_bytes(prec, max(n, 0), max(min(nb, n), 0)), A, stream)
         rc = getattr(lib, f"kmv_{name}")(
             uplo.encode(), n, nb, _ptr(A, prec), lda, _ptr(e, eprec), _ptr(tau, prec), _ptr(W, prec), ldw,
             ctypes.c_void_p(wsp), wsb, _stream(stream))
@@ -490,7 +501,7 @@ def _gebrd_panel(prec):
     rprec = {"s": "s", "d": "d", "c": "s", "z": "d"}[prec]      # d and e are real
 
     def call(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, workspace=None, stream=None, check=True):
-        wsp, wsb = _ws_args(workspace, lambda: gebrd_panel_workspace_bytes(prec, max(m, 0), max(n, 0), max(nb, 0)), A)
+        wsp, wsb = _ws_args(workspace, lambda: gebrd_panel_workspace_bytes(prec, max(m, 0), max(n, 0), max(nb, 0)), A, stream)
         rc = getattr(lib, f"kmv_{prec}gebrd_panel")(
             m, n, nb, _ptr(A, prec), lda, _ptr(d, rprec), _ptr(e, rprec), _ptr(tauq, prec), _ptr(taup, prec),
             _ptr(X, prec), ldx, _ptr(Y, prec), ldy, ctypes.c_void_p(wsp), wsb, _stream(stream))

@@ -549,6 +549,8 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
                 s = s4;
             }
         }
+        // row blocks are the grid's second dimension (at most 65535): very tall matrices take more tiles per wave
+        while (p.row_tiles < 4 && ceil_div(p.ntiles, GN_NW * p.row_tiles) > 65535) p.row_tiles *= 2;
         const int64_t rb = ceil_div(p.ntiles, GN_NW * p.row_tiles);
         if (s <= 0 && tn.wg_target <= 0 && !sizing) s = choose_splits(rb, gemv_n_slots<T>(p.row_tiles), cap);
         if (s <= 0) s = ceil_div(target, rb);
@@ -607,6 +609,7 @@ template <class T> hipError_t launch_gemv_n(const GemvArgs<T>& a, hipStream_t s,
         return launch_reduce<T>(a.partial, a.plan.splits, a.plan.part_stride, a.plan.shift, a.m, a.alpha, a.beta, a.alpha_dev, a.beta_dev, a.y, a.incy, s);
     }
     const int64_t rt = a.plan.row_tiles;
+    if (rt < 1 || ceil_div(a.plan.ntiles, GN_NW * rt) > 65535) return hipErrorInvalidValue;   // beyond the grid's second dimension
     const dim3 grid((unsigned)a.plan.splits, (unsigned)ceil_div(a.plan.ntiles, GN_NW * rt), (unsigned)batch);
     const dim3 block(GN_NW * WAVE);
     if (a.A_ptrs) {     // pointer-array batch: one instance (one row tile per wave, no column splits)
