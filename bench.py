@@ -48,7 +48,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 COLD_BYTES = 512e6      # products with a smaller matrix get a region of their own (and a cache-resident timing)
-TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "sweep_hbm_traffic.txt")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "default_step_hbm_traffic.txt")
 
 
 def measured_traffic(kernel):
@@ -81,6 +81,9 @@ def parse():
     ap.add_argument("--only", default=None, help="regular expression on 'routine:n' (e.g. 'dsymv_L:16384|dgemv_N:'): time only "
                                                  "the matching products of the workload (for profiles)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cache-resident", action="store_true",
+                    help="skip the back-to-back calls of the cache-sized products after the timed steps (for profiles: every "
+                         "launch of the run then belongs to a step)")
     ap.add_argument("--tuning", action="append", default=[], help="key=value for kmv_set_tuning")
     return ap.parse_args()
 
@@ -667,14 +670,14 @@ def main():
     traffic = measured_traffic(dom) if args.workload == "all" and not args.tuning and not args.only else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "traffic_source": "profiles/sweep_hbm_traffic.txt (bytes per launch, read + written)" if traffic else None,
+                "traffic_source": "profiles/default_step_hbm_traffic.txt (bytes per launch, read + written)" if traffic else None,
                 "launches_per_step": dd["launches"],
                 "avg_launch_us": round(dd["ms"] * 1e3 / dd["launches"], 2),
                 "avg_algorithmic_bytes_per_launch": dd["bytes"] // dd["launches"]}
 
     # the products that fit the last-level cache, timed back to back on ONE region (cache resident) beside
     # their timing inside the step (own region, cold)
-    small = [i for i, p in enumerate(prods) if i in inputs.offset]
+    small = [] if args.no_cache_resident else [i for i, p in enumerate(prods) if i in inputs.offset]
     cache_resident = None
     if small:
         warm_ms, cold_ms, sb = 0.0, 0.0, 0
