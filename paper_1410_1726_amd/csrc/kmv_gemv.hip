@@ -562,7 +562,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
                     if (st > cap) st = cap;
                     const double fill = (double)(rbt * st) / (double)cus;
                     const double full = (double)p.ntiles / (double)(rbt * GN_NW * rt);
-                    const double pref = sizeof(T) == 4 ? (rt == 2 ? 1.0 : (rt == 1 ? 0.97 : 0.93))
+                    const double pref = sizeof(T) == 4 ? (rt == 2 ? 1.0 : 0.93)
                                                        : (rt == 4 ? 1.0 : (rt == 2 ? 0.98 : 0.95));
                     if (fill * full >= 0.80 && fill * full * pref > best) {
                         best = fill * full * pref;
