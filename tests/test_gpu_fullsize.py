@@ -32,7 +32,7 @@ def free():
 
 # ---- size sweep: SGEMV / DGEMV, N and T, lda = n, alpha = beta = 1 ------------
 @pytest.mark.parametrize("prec", "sd")
-@pytest.mark.parametrize("n", [16384, 17001, 32768])
+@pytest.mark.parametrize("n", [16384, 17001, 20001, 32768])     # 17001, 20001: leading dimension off the 128-byte grid
 def test_gemv_sweep_sizes(prec, n):
     parent = wl.matrix(prec, n, n, n, seed=0, device=DEV)
     for trans in "NT":
