@@ -467,7 +467,8 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *                                 multiple of 128 bytes: columns grouped by
  *                                 their alignment (1 = never, 2 = always)
  *   symv_variant                  SYMV/HEMV main kernel, see below (2, 3)
- *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2)
+ *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2,
+ *                                 3; 3 with one-tile units only)
  *   symv_unit_tiles               variant 2: row tiles per prefetch unit (1, 2)
  *   symv_piece_fixed              variant 2: fixed part of a piece's weight on
  *                                 the work line, plus one (1..17)

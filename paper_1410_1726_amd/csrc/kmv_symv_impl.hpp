@@ -866,7 +866,9 @@ template <class T> constexpr int64_t small_n() { return sizeof(T) == 4 ? 2176 : 
 // fastest from a few hundred megabytes of triangle on (the kernel's loads are pipelined by the wave itself,
 // and more resident workgroups only lengthen the queues in front of the memory channels: DSYMV 16384
 // 164 us against 176-178 us with two or three per compute unit), two below; chunks of 8 row tiles pay for
-// 16-byte elements from n = 8192 and for 8-byte elements from about n = 20000 (2-10%), 4 tiles elsewhere.
+// 8-byte elements from about n = 20000 (2%), for 16-byte elements from about n = 8400 (10% at 24576) and 12 tiles
+// from about 10000 (another 1-2.5%; no gain for the other types; 12 tiles are what 64 KB of LDS hold), 4 tiles
+// elsewhere.
 template <class T> inline int default_unit_tiles(int64_t) { return 1; }
 inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }   // the most the kernel instances are built for
 template <class T> inline int default_wgs_per_cu(int64_t n) {
@@ -875,7 +877,8 @@ template <class T> inline int default_wgs_per_cu(int64_t n) {
 }
 template <class T> inline int64_t default_tiles_per_wave(int64_t n) {
     if (sizeof(T) == 4) return 1;
-    return n >= (sizeof(T) == 16 ? 8192 : 20480) ? 2 : 1;
+    if (sizeof(T) == 16) return n >= 10240 ? 3 : (n >= 8448 ? 2 : 1);
+    return n >= 20480 ? 2 : 1;
 }
 // fixed part of a piece's weight on the work line, in row tiles (the column sums and their store, the
 // change of panel): measured, see the tuning key symv_piece_fixed
@@ -898,16 +901,18 @@ template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     return ((int64_t)cus << 8) | (nb < wgs_per_cu(KT) ? nb : wgs_per_cu(KT));   // compute units, workgroups that fit on one
 }
 template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
-    static int64_t cache[MAX_CACHED_DEVICES][2][3][3] = {};
+    static int64_t cache[MAX_CACHED_DEVICES][2][4][3] = {};
     const int di = cached_device_index();
-    if (ktw < 1 || ktw > 2 || kt < 1 || kt > 2 || di < 0) return -1;
+    if (ktw < 1 || ktw > 3 || kt < 1 || kt > 2 || (ktw == 3 && kt != 1) || di < 0) return -1;
     int64_t& c = cache[di][lower ? 1 : 0][ktw][kt];
     if (c == 0) {
         if (lower) {
-            if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, true, 1, SY_NW>() : balanced_slots_of<T, true, 1, 2 * SY_NW>();
+            if (ktw == 3) c = balanced_slots_of<T, true, 1, 3 * SY_NW>();
+            else if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, true, 1, SY_NW>() : balanced_slots_of<T, true, 1, 2 * SY_NW>();
             else c = ktw == 1 ? balanced_slots_of<T, true, 2, SY_NW / 2>() : balanced_slots_of<T, true, 2, SY_NW>();
         } else {
-            if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, false, 1, SY_NW>() : balanced_slots_of<T, false, 1, 2 * SY_NW>();
+            if (ktw == 3) c = balanced_slots_of<T, false, 1, 3 * SY_NW>();
+            else if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, false, 1, SY_NW>() : balanced_slots_of<T, false, 1, 2 * SY_NW>();
             else c = ktw == 1 ? balanced_slots_of<T, false, 2, SY_NW / 2>() : balanced_slots_of<T, false, 2, SY_NW>();
         }
     }
@@ -1047,8 +1052,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     int64_t ktw = tn.symv_tiles_per_wave;
     if (ktw <= 0) ktw = default_tiles_per_wave<T>(n);
     // the balanced kernel's tables hold SHARE_MAX_CHUNKS chunks (enough for every matrix that fits the device's
-    // memory when the chunks are 8 tiles high)
-    if (ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ktw = 2;
+    // memory when the chunks are 8 or 12 tiles high)
+    while (ktw < 3 && ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ++ktw;
     if (sizing) ktw = 1;   // sizing takes the settings that need the most room
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
@@ -1062,8 +1067,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     if (sizing) {
         // one row-sum vector of the chunk's height per workgroup and chunk; workgroups <= pieces <= chunks x
         // panels, for either chunk height
-        p.rows_padded = partial_stride<T>(2 * SY_NW * TR);
-        for (int64_t kw = 1; kw <= 2; ++kw) {
+        p.rows_padded = partial_stride<T>(3 * SY_NW * TR);
+        for (int64_t kw = 1; kw <= 3; ++kw) {
             const int64_t nc = ceil_div(p.ntiles, SY_NW * kw);
             int64_t entries = nc * p.npanels < SHARE_MAX_WORKERS ? nc * p.npanels : SHARE_MAX_WORKERS;
             entries += nc + 1;
@@ -1077,6 +1082,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             return p;
         }
         p.unit_tiles = tn.symv_unit_tiles > 0 ? (int)tn.symv_unit_tiles : default_unit_tiles<T>(n);
+        if (ktw == 3) p.unit_tiles = 1;   // the 12-tile chunks exist with one-tile units only
         int64_t Y = tn.wg_target;
         if (Y <= 0) {
             // one resident round: compute units x workgroups per compute unit (never more than fit)
@@ -1120,6 +1126,7 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
         else if (ktw == 2 && kt == 1) launch_balanced<T, HERM, LOWER, 1, 2 * SY_NW>(a, s);
         else if (ktw == 1 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW / 2>(a, s);
         else if (ktw == 2 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW>(a, s);
+        else if (ktw == 3 && kt == 1) launch_balanced<T, HERM, LOWER, 1, 3 * SY_NW>(a, s);
         else return false;
         return true;
     }
