@@ -10,6 +10,7 @@ interleaved rounds are (the defaults in the planners were chosen this way).
 
   python -m paper_1410_1726_amd.tune dsymv_L 16384 symv_unit_tiles=1,2 wg_target=512,768
   python -m paper_1410_1726_amd.tune sgemv_N 8192x65536 gemv_n_splits=0,32,64,128
+  python -m paper_1410_1726_amd.tune zhemv_L 40960 lda_pad=32 symv_tiles_per_wave=2,3     (lda = n + 32)
 
 A value 0 means "let the library choose".  Prints the median time of every
 combination (microseconds, GB/s of algorithmic bytes) and marks the fastest.
@@ -62,19 +63,20 @@ def _time(call, reps, warm=2):
     return e0.elapsed_time(e1) / reps * 1e3
 
 
-def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int = 10):
-    """routine like 'dgemv_T', 'zhemv_U', 'ssymv_L'; grid: {key: [values]}.  Returns
+def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int = 10, lda_pad: int = 0):
+    """routine like 'dgemv_T', 'zhemv_U', 'ssymv_L'; grid: {key: [values]}; lda = m + lda_pad.  Returns
     [(settings dict, median microseconds)], in grid order."""
     keys = list(grid)
     combos = [dict(zip(keys, vals)) for vals in itertools.product(*(grid[key] for key in keys))] or [{}]
-    return sweep_settings(routine, m, n, combos, rounds, reps)
+    return sweep_settings(routine, m, n, combos, rounds, reps, lda_pad)
 
 
-def sweep_settings(routine: str, m: int, n: int, combos: list, rounds: int = 5, reps: int = 10):
+def sweep_settings(routine: str, m: int, n: int, combos: list, rounds: int = 5, reps: int = 10, lda_pad: int = 0):
     """The same over an explicit list of settings dicts ({} = the library's own choice, saved table included)."""
     prec, name, mode = routine[0], routine[1:5], routine[-1]
     sym = name in ("symv", "hemv")
-    A = wl.matrix(prec, m, n, m, device="cuda")
+    lda = m + lda_pad
+    A = wl.matrix(prec, m, n, lda, device="cuda")
     lenx, leny = (n, n) if sym else ((n, m) if mode == "N" else (m, n))
     x = wl.vector(prec, lenx, device="cuda")
     y = wl.vector(prec, leny, which=2, device="cuda")
@@ -90,8 +92,8 @@ def sweep_settings(routine: str, m: int, n: int, combos: list, rounds: int = 5, 
                 if combo:       # an explicit setting is measured against the planners' rules, not the saved table
                     k.set_tuning("tuned_table", 1)
                 # the plan (kernel, splits, workspace layout) is fixed when the call is prepared
-                call = (k.prepare_symv(prec, mode, n, 1.0, A, m, x, 1, 0.0, y, 1) if sym
-                        else k.prepare_gemv(prec, mode, m, n, 1.0, A, m, x, 1, 1.0, y, 1))
+                call = (k.prepare_symv(prec, mode, n, 1.0, A, lda, x, 1, 0.0, y, 1) if sym
+                        else k.prepare_gemv(prec, mode, m, n, 1.0, A, lda, x, 1, 1.0, y, 1))
                 times[i].append(_time(call, reps))
     finally:
         for key, v in saved.items():
@@ -279,11 +281,14 @@ def main(argv):
         return 0
     routine, shape = argv[0], argv[1]
     m, n = (int(v) for v in shape.split("x")) if "x" in shape else (int(shape), int(shape))
-    grid = {}
+    grid, lda_pad = {}, 0
     for spec in argv[2:]:
         key, vals = spec.split("=")
+        if key == "lda_pad":          # not a tuning key: the matrix gets the leading dimension m + lda_pad
+            lda_pad = int(vals)
+            continue
         grid[key] = [int(v) for v in vals.split(",")]
-    res = sweep(routine, m, n, grid)
+    res = sweep(routine, m, n, grid, lda_pad=lda_pad)
     op = {"gemv": "gemv_" + routine[-1].lower(), "symv": "symv_l", "hemv": "hemv_l"}[routine[1:5]]
     nbytes = acc.algorithmic_bytes(op, routine[0], m, n)
     best = min(us for _, us in res)
