@@ -467,8 +467,8 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  *                                 multiple of 128 bytes: columns grouped by
  *                                 their alignment (1 = never, 2 = always)
  *   symv_variant                  SYMV/HEMV main kernel, see below (2, 3)
- *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1, 2,
- *                                 3; 3 with one-tile units only)
+ *   symv_tiles_per_wave           row-chunk height, in units of 4 row tiles (1 .. 4;
+ *                                 3 and 4 with one-tile units only)
  *   symv_unit_tiles               variant 2: row tiles per prefetch unit (1, 2)
  *   symv_piece_fixed              variant 2: fixed part of a piece's weight on
  *                                 the work line, plus one (1..17)
@@ -543,7 +543,7 @@ int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles,
  * device the library runs on holds its copy until the process ends).  The
  * call allocates nothing and frees nothing.  A product whose plan needs more
  * than the array holds is refused with KMV_ERR_WORKSPACE before anything is
- * enqueued: with the default tuning DSYMV fits up to about n = 38000
+ * enqueued: with the default tuning DSYMV fits up to about n = 54000
  * (kmv_symv_workspace_bytes('d', uplo, n) is an upper bound of the need).
  * The first call on a device looks up the array's address (make it outside a
  * graph capture).  All calls on a device share the one array: two calls whose

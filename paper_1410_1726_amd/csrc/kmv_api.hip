@@ -417,7 +417,7 @@ const Key KEYS[] = {
     {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
     {"gemv_short", &Tuning::gemv_short, 0, 2},
     {"gemv_align_classes", &Tuning::gemv_align_classes, 0, 2},
-    {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 3},
+    {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 4},
     {"symv_variant", &Tuning::symv_variant, 0, 3},
     {"symv_unit_tiles", &Tuning::symv_unit_tiles, 0, 2},
     {"symv_piece_fixed", &Tuning::symv_piece_fixed, 0, 17},
@@ -688,7 +688,7 @@ int kmv_symv_kernel_variant(char prec, char uplo, int64_t n, const void* A, int6
 int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles, int unit_tiles, int64_t slots, int fixed,
                     int edge, uint32_t* start, uint16_t* first, uint16_t* last, int64_t* work) {
     const bool lower = (uplo == 'L' || uplo == 'l'), upper = (uplo == 'U' || uplo == 'u');
-    if ((!lower && !upper) || n < 1 || n > ((int64_t)1 << 30) || shift < 0 || (chunk_tiles != 4 && chunk_tiles != 8 && chunk_tiles != 12) ||
+    if ((!lower && !upper) || n < 1 || n > ((int64_t)1 << 30) || shift < 0 || (chunk_tiles != 4 && chunk_tiles != 8 && chunk_tiles != 12 && chunk_tiles != 16) ||
         (unit_tiles != 1 && unit_tiles != 2) || slots < 1 || fixed < 0 || fixed > 16 || edge < 0 || edge > 16)
         return -1;
     const SymvBalanced* b = nullptr;

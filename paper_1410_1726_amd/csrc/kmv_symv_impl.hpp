@@ -129,8 +129,14 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
     // VEC - 1 short columns at the tip of the triangle (at most six elements) are left to the final pass.
     const int jlo = LOWER ? 0 : VEC - 1, jhi = LOWER ? n - VEC + 1 : n;
 
-    __shared__ __align__(16) T xs[R];       // x over the chunk's rows (zeros outside [0, n))
-    __shared__ __align__(16) T rs[NW][R];   // row sums of each wave
+    // x over the chunk's rows (zeros outside [0, n)) and the row sums of each wave: static LDS up to 64 KB, the
+    // tallest chunks take dynamic LDS (the launch passes balanced_lds_bytes)
+    constexpr bool DYN_LDS = (size_t)(NW + 1) * R * sizeof(T) > 65536;
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
+    __shared__ __align__(16) T xs_static[DYN_LDS ? 1 : R];
+    __shared__ __align__(16) T rs_static[DYN_LDS ? 1 : NW][DYN_LDS ? 1 : R];
+    T* const xs = DYN_LDS ? reinterpret_cast<T*>(dyn_lds) : xs_static;
+    T(*const rs)[R] = DYN_LDS ? reinterpret_cast<T(*)[R]>(dyn_lds + (size_t)R * sizeof(T)) : reinterpret_cast<T(*)[R]>(&rs_static[0][0]);
 
     // this workgroup's share: from piece j0 of chunk k0 up to (not including) piece j1 of chunk k1
     const uint32_t e0 = sh.start[blockIdx.x], e1 = sh.start[blockIdx.x + 1];
@@ -866,9 +872,10 @@ template <class T> constexpr int64_t small_n() { return sizeof(T) == 4 ? 2176 : 
 // fastest from a few hundred megabytes of triangle on (the kernel's loads are pipelined by the wave itself,
 // and more resident workgroups only lengthen the queues in front of the memory channels: DSYMV 16384
 // 164 us against 176-178 us with two or three per compute unit), two below; chunks of 8 row tiles pay for
-// 8-byte elements from about n = 20000 (2%), for 16-byte elements from about n = 8400 (10% at 24576) and 12 tiles
-// from about 10000 (another 1-2.5%; no gain for the other types; 12 tiles are what 64 KB of LDS hold), 4 tiles
-// elsewhere.
+// 8-byte elements from about n = 20000 (2%), for 16-byte elements from about n = 8400 (10% at 24576); 12 tiles
+// (what 64 KB of static LDS hold) add 1-2.5% for 16-byte elements from about 10000, and 16 tiles (80 KB of dynamic
+// LDS) another 0.7-4% from 16384 (ZHEMV 32768: 1314 -> 1271 us) and 1.7% for 8-byte elements at 40960; 4 tiles
+// elsewhere and always for 4-byte elements.
 template <class T> inline int default_unit_tiles(int64_t) { return 1; }
 inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }   // the most the kernel instances are built for
 template <class T> inline int default_wgs_per_cu(int64_t n) {
@@ -877,8 +884,8 @@ template <class T> inline int default_wgs_per_cu(int64_t n) {
 }
 template <class T> inline int64_t default_tiles_per_wave(int64_t n) {
     if (sizeof(T) == 4) return 1;
-    if (sizeof(T) == 16) return n >= 10240 ? 3 : (n >= 8448 ? 2 : 1);
-    return n >= 20480 ? 2 : 1;
+    if (sizeof(T) == 16) return n >= 16384 ? 4 : (n >= 10240 ? 3 : (n >= 8448 ? 2 : 1));
+    return n >= 36864 ? 4 : (n >= 20480 ? 2 : 1);
 }
 // fixed part of a piece's weight on the work line, in row tiles (the column sums and their store, the
 // change of panel): measured, see the tuning key symv_piece_fixed
@@ -888,6 +895,21 @@ constexpr int DEFAULT_PIECE_FIXED = 1;
 // elements, three for 4-byte ones (four elements per lane to move into place)
 template <class T> constexpr int default_edge_weight() { return sizeof(T) == 4 ? 3 : 1; }
 // compute units and min(occupancy, most workgroups wanted per compute unit), queried once per instance
+// Dynamic LDS of an instance: 0 while its arrays fit the 64 KB of static LDS, else their size; such an instance
+// is allowed the larger amount once per device (the symmetric and the Hermitian instance are different kernels).
+template <class T, bool HERM, bool LOWER, int KT, int G> size_t balanced_dynamic_lds() {
+    constexpr size_t bytes = (size_t)(SY_NW + 1) * KT * G * tile_rows<T>() * sizeof(T);
+    if (bytes <= 65536) return 0;
+    static bool allowed[MAX_CACHED_DEVICES] = {};
+    const int di = cached_device_index();
+    if (di < 0 || !allowed[di]) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        (void)hipGetLastError();
+        if (di >= 0) allowed[di] = true;
+    }
+    return bytes;
+}
 template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     constexpr bool HERM = Traits<T>::cplx;
     int dev = 0, cus = 0, nb = 0;
@@ -895,23 +917,25 @@ template <class T, bool LOWER, int KT, int G> int64_t balanced_slots_of() {
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
         e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>,
-                                                         SY_NW * WAVE, 0);
+                                                         SY_NW * WAVE, balanced_dynamic_lds<T, HERM, LOWER, KT, G>());
     (void)hipGetLastError();
     if (e != hipSuccess || cus <= 0 || nb <= 0) return -1;
     return ((int64_t)cus << 8) | (nb < wgs_per_cu(KT) ? nb : wgs_per_cu(KT));   // compute units, workgroups that fit on one
 }
 template <class T> int64_t balanced_slots(bool lower, int ktw, int kt) {
-    static int64_t cache[MAX_CACHED_DEVICES][2][4][3] = {};
+    static int64_t cache[MAX_CACHED_DEVICES][2][5][3] = {};
     const int di = cached_device_index();
-    if (ktw < 1 || ktw > 3 || kt < 1 || kt > 2 || (ktw == 3 && kt != 1) || di < 0) return -1;
+    if (ktw < 1 || ktw > 4 || kt < 1 || kt > 2 || (ktw >= 3 && kt != 1) || di < 0) return -1;
     int64_t& c = cache[di][lower ? 1 : 0][ktw][kt];
     if (c == 0) {
         if (lower) {
-            if (ktw == 3) c = balanced_slots_of<T, true, 1, 3 * SY_NW>();
+            if (ktw == 4) c = balanced_slots_of<T, true, 1, 4 * SY_NW>();
+            else if (ktw == 3) c = balanced_slots_of<T, true, 1, 3 * SY_NW>();
             else if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, true, 1, SY_NW>() : balanced_slots_of<T, true, 1, 2 * SY_NW>();
             else c = ktw == 1 ? balanced_slots_of<T, true, 2, SY_NW / 2>() : balanced_slots_of<T, true, 2, SY_NW>();
         } else {
-            if (ktw == 3) c = balanced_slots_of<T, false, 1, 3 * SY_NW>();
+            if (ktw == 4) c = balanced_slots_of<T, false, 1, 4 * SY_NW>();
+            else if (ktw == 3) c = balanced_slots_of<T, false, 1, 3 * SY_NW>();
             else if (kt == 1) c = ktw == 1 ? balanced_slots_of<T, false, 1, SY_NW>() : balanced_slots_of<T, false, 1, 2 * SY_NW>();
             else c = ktw == 1 ? balanced_slots_of<T, false, 2, SY_NW / 2>() : balanced_slots_of<T, false, 2, SY_NW>();
         }
@@ -1052,8 +1076,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     int64_t ktw = tn.symv_tiles_per_wave;
     if (ktw <= 0) ktw = default_tiles_per_wave<T>(n);
     // the balanced kernel's tables hold SHARE_MAX_CHUNKS chunks (enough for every matrix that fits the device's
-    // memory when the chunks are 8 or 12 tiles high)
-    while (ktw < 3 && ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ++ktw;
+    // memory when the chunks are 8 to 16 tiles high)
+    while (ktw < 4 && ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ++ktw;
     if (sizing) ktw = 1;   // sizing takes the settings that need the most room
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
@@ -1067,8 +1091,8 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     if (sizing) {
         // one row-sum vector of the chunk's height per workgroup and chunk; workgroups <= pieces <= chunks x
         // panels, for either chunk height
-        p.rows_padded = partial_stride<T>(3 * SY_NW * TR);
-        for (int64_t kw = 1; kw <= 3; ++kw) {
+        p.rows_padded = partial_stride<T>(4 * SY_NW * TR);
+        for (int64_t kw = 1; kw <= 4; ++kw) {
             const int64_t nc = ceil_div(p.ntiles, SY_NW * kw);
             int64_t entries = nc * p.npanels < SHARE_MAX_WORKERS ? nc * p.npanels : SHARE_MAX_WORKERS;
             entries += nc + 1;
@@ -1082,7 +1106,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             return p;
         }
         p.unit_tiles = tn.symv_unit_tiles > 0 ? (int)tn.symv_unit_tiles : default_unit_tiles<T>(n);
-        if (ktw == 3) p.unit_tiles = 1;   // the 12-tile chunks exist with one-tile units only
+        if (ktw >= 3) p.unit_tiles = 1;   // the 12- and 16-tile chunks exist with one-tile units only
         int64_t Y = tn.wg_target;
         if (Y <= 0) {
             // one resident round: compute units x workgroups per compute unit (never more than fit)
@@ -1114,7 +1138,8 @@ namespace {
 template <class T, bool HERM, bool LOWER, int KT, int G>
 void launch_balanced(const SymvArgs<T>& a, hipStream_t s) {
     const dim3 grid((unsigned)a.plan.workers);
-    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>), grid, dim3(SY_NW * WAVE), 0, s, a,
+    const size_t dyn = balanced_dynamic_lds<T, HERM, LOWER, KT, G>();
+    hipLaunchKernelGGL((symv_balanced_kernel<T, HERM, LOWER, BAL_NC, KT, G, SY_NW>), grid, dim3(SY_NW * WAVE), dyn, s, a,
                        a.plan.bal->shares);
 }
 template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& a, hipStream_t s) {
@@ -1127,6 +1152,7 @@ template <class T, bool HERM, bool LOWER> bool dispatch_main(const SymvArgs<T>& 
         else if (ktw == 1 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW / 2>(a, s);
         else if (ktw == 2 && kt == 2) launch_balanced<T, HERM, LOWER, 2, SY_NW>(a, s);
         else if (ktw == 3 && kt == 1) launch_balanced<T, HERM, LOWER, 1, 3 * SY_NW>(a, s);
+        else if (ktw == 4 && kt == 1) launch_balanced<T, HERM, LOWER, 1, 4 * SY_NW>(a, s);
         else return false;
         return true;
     }

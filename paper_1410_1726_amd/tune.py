@@ -116,7 +116,7 @@ def _coarse_grid(routine: str, m: int, n: int) -> dict:
     if name == "gemv":
         return {"gemv_t_splits": [0, 1, 2, 4, 8, 16]}
     variants = [2] + ([3] if n <= 4096 else [])
-    return {"symv_variant": variants, "symv_tiles_per_wave": [1, 2, 3], "symv_unit_tiles": [1, 2]}
+    return {"symv_variant": variants, "symv_tiles_per_wave": [1, 2, 3, 4], "symv_unit_tiles": [1, 2]}
 
 
 def _fine_grid(routine: str, best: dict) -> dict:

@@ -255,7 +255,7 @@ def test_split_variants_agree_with_oracle():
         k.set_tuning("gemv_align_classes", 0)
         k.set_tuning("symv_variant", 2)
         for tpw, workers, fixed, edge in ((1, 1, 1, 1), (2, 3, 4, 1), (1, 8, 1, 9), (2, 5, 17, 17), (2, 256, 2, 3), (1, 16, 3, 2),
-                                          (3, 1, 1, 1), (3, 7, 2, 3), (3, 256, 0, 0)):
+                                          (3, 1, 1, 1), (3, 7, 2, 3), (3, 256, 0, 0), (4, 1, 1, 1), (4, 6, 3, 2), (4, 256, 0, 0)):
             k.set_tuning("symv_tiles_per_wave", tpw)
             k.set_tuning("wg_target", workers)
             k.set_tuning("symv_piece_fixed", fixed)
@@ -336,7 +336,7 @@ def test_symv_main_kernel_variants(prec, variant):
     k = kmv()
     try:
         k.set_tuning("symv_variant", variant)
-        for tpw, target, unit in ((0, 0, 0), (1, 3, 1), (2, 1, 2), (1, 256, 2), (2, 7, 1), (3, 5, 1), (3, 256, 0)):
+        for tpw, target, unit in ((0, 0, 0), (1, 3, 1), (2, 1, 2), (1, 256, 2), (2, 7, 1), (3, 5, 1), (3, 256, 0), (4, 3, 1), (4, 256, 0)):
             k.set_tuning("symv_tiles_per_wave", tpw)
             k.set_tuning("wg_target", target)
             k.set_tuning("symv_unit_tiles", unit)
