@@ -700,7 +700,7 @@ int kmv_symv_shares(char prec, char uplo, int64_t n, int shift, int chunk_tiles,
         case 'z': tr = tile_rows<cf64>(); break;
         default: return -1;
     }
-    if (shift >= tr || ceil_div(ceil_div(n + shift, tr), chunk_tiles) > SHARE_MAX_CHUNKS) return -1;
+    if (shift >= tr || ceil_div(ceil_div(n + shift, tr), chunk_tiles) + 1 > SHARE_MAX_CHUNKS) return -1;
     switch (prec) {
         case 's': b = symv_shares<float>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge); break;
         case 'd': b = symv_shares<double>(lower, n, shift, chunk_tiles, unit_tiles, slots, fixed, edge); break;

@@ -172,7 +172,8 @@ template <class T> struct SymvPlan {
     int64_t ntiles;        // row tiles covering [-shift, n)
     int64_t panel_cols;    // columns per panel
     int64_t npanels;       // column panels
-    int64_t chunk_tiles;   // row tiles per workgroup
+    int64_t chunk_tiles;   // row tiles per row chunk
+    int64_t chunk_off;     // row chunk k covers the row tiles [k*chunk_tiles - chunk_off, (k+1)*chunk_tiles - chunk_off)
     int64_t nchunks;       // row chunks
     int64_t rows_padded;   // distance between two row-sum vectors (>= chunk rows)
     int64_t work;          // variant 2: length of the work line (stored row tiles of all pieces plus a fixed part per piece)
@@ -180,6 +181,15 @@ template <class T> struct SymvPlan {
     const SymvBalanced* bal;   // variant 2: the shares (host memory of the planner, valid until the thread's next few plans)
     size_t xpack_off, wsn_off, wst_off, total_bytes;
 };
+// Where the row chunks start.  The tiles rarely divide into whole chunks, and a short chunk is made of short pieces,
+// for which the per-piece work (column sums, change of panel) and an edge tile weigh most.  It therefore goes
+// where the triangle is narrow: lower storage starts with it (its rows hold the fewest stored columns), upper storage
+// ends with it.  Returns the number of tiles by which the chunk grid starts before tile 0: a multiple of the unit's
+// tiles, so that only the matrix's last chunk can end inside a unit (whose rows beyond n are masked anyway).
+__host__ __device__ __forceinline__ int64_t symv_chunk_offset(bool lower, int64_t ntiles, int64_t chunk_tiles, int64_t unit_tiles) {
+    const int64_t c = (chunk_tiles - ntiles % chunk_tiles) % chunk_tiles;
+    return lower ? c - c % unit_tiles : 0;
+}
 template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, int64_t lda);
 // the table of shares for given settings (what plan_symv looks up for the balanced kernel; exported for tests)
 template <class T>

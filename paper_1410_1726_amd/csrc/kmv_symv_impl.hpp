@@ -150,9 +150,10 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
 #pragma unroll
     for (int c = 0; c < NC; ++c) accT[c] = zero_of<T>();
 
+    const int coff = (int)a.plan.chunk_off;
     for (int k = k0; k <= k1 && k < nchunks; ++k) {
-        const int tbeg = k * CT;
-        const int tend = tbeg + CT < ntiles ? tbeg + CT : ntiles;
+        const int tbeg = k * CT - coff > 0 ? k * CT - coff : 0;
+        const int tend = (k + 1) * CT - coff < ntiles ? (k + 1) * CT - coff : ntiles;
         int64_t plo64, phi64;
         chunk_panels<LOWER>(tbeg, tend, C, shift, TR, npanels, plo64, phi64);
         const int ja = k == k0 ? j0 : 0, jb = k == k1 ? j1 : (int)(phi64 - plo64);
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
         // long column), the lane's address of row 0 of each (col), the lane's element of x, and the
         // tiles [fa, fb) in which every pair of the wave's columns is an ordinary off-diagonal element.
         struct Walk {
-            int pp, ss, gg, glo, nu, fa, fb;
+            int pp, ss, gg, glo, nu, fa, fb, ra, rb;
             bool longcols;   // the wave's NC columns all exist and are long ones
             int cj[NC];
             const T* col[NC];
@@ -191,17 +192,24 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
             const int jg = p * C + w * NC;
             it.longcols = jg >= jlo && jg + NC <= jhi;
             if (it.longcols) {
+                // [ra, rb): tiles cut by the matrix's first or last row whose existing rows are all ordinary
+                // off-diagonal elements of the wave's columns (the ragged last tile of the columns far above it
+                // in lower storage, the shifted first tile of the columns far to its right in upper storage)
                 if (LOWER) {
                     const int f = (jg + NC + shift + TR - 1) / TR - tbeg;   // first tile that starts at or below row jg + NC
                     it.fa = f > tf_lo ? f : tf_lo;
                     it.fb = tf_hi;
+                    it.ra = f > tf_hi ? f : tf_hi;
+                    it.rb = tend - tbeg;
                 } else {
                     const int f = (jg + shift) / TR - tbeg;                 // tiles before f end above row jg
                     it.fa = tf_lo;
                     it.fb = f < tf_hi ? f : tf_hi;
+                    it.ra = 0;
+                    it.rb = f < tf_lo ? f : tf_lo;
                 }
             } else {
-                it.fa = it.fb = 0;
+                it.fa = it.fb = it.ra = it.rb = 0;
             }
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
@@ -231,7 +239,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
         // q is fast; LAST: the piece ends with this unit; PAST: the walk is over, the loads are cheap
         // stand-ins that keep the pipeline's shape, every lane reading the first stored vector of its
         // column, and the use changes nothing).
-        constexpr int F_WHOLE = 1 << 4, F_LAST = 1 << 8, F_PAST = 1 << 9;
+        constexpr int F_WHOLE = 1 << 4, F_LAST = 1 << 8, F_PAST = 1 << 9, F_RAG = 1 << 12;
         struct Unit { int gt, p, fl; };
         Walk it;
         const int lane_row = lane * VEC;
@@ -244,6 +252,7 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
 #pragma unroll
             for (int q = 0; q < KT; ++q) {
                 if (!past && u.gt + q >= it.fa && u.gt + q < it.fb) u.fl |= 1 << q;
+                else if (!past && u.gt + q >= it.ra && u.gt + q < it.rb) u.fl |= F_RAG << q;
                 else if (!past && it.longcols && u.gt + q >= tf_lo && u.gt + q < tf_hi) u.fl |= F_WHOLE << q;
                 const int r = (past ? -(1 << 30) : row0 + (u.gt + q) * TR) + lane_row;
 #pragma unroll
@@ -274,6 +283,25 @@ __global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kern
                             fma_acc(an.e[v], b[q][c].e[v], xjb[c]);
                             fma_op<HERM>(accT[c], b[q][c].e[v], xi.e[v]);
                         }
+                } else if (u.fl & (F_RAG << q)) {
+                    // the tile is cut by the first or the last row of the matrix and lies away from the diagonal:
+                    // a lane whose vector was loaded at a clamped position moves its elements into place, rows
+                    // that do not exist are skipped, everything else is an ordinary pair
+                    const int r = row0 + slot;
+                    const int rc = LOWER ? (r < n - VEC ? r : n - VEC) : (r > 0 ? r : 0);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        const Vec<T> sv = shift_elems(b[q][c], r - rc);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) {
+                            const bool ins = LOWER ? r + v < n : r + v >= 0;
+                            T nn = an.e[v], nt = accT[c];
+                            fma_acc(nn, sv.e[v], xjb[c]);
+                            fma_op<HERM>(nt, sv.e[v], xi.e[v]);
+                            an.e[v] = select_of(ins, nn, an.e[v]);
+                            accT[c] = select_of(ins, nt, accT[c]);
+                        }
+                    }
                 } else if (u.fl & (F_WHOLE << q)) {
                     // the diagonal crosses the tile, all its rows and the wave's columns exist: a lane's vector
                     // is used whole when it lies strictly on the stored side of the column's diagonal element
@@ -809,9 +837,10 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
             // row-sum vectors of the workgroups whose share touches the chunk of row i:
             // numbers ylo..yhi (from the host's table of shares), vector y + k each
             const int64_t CT = a.plan.chunk_tiles, slot = i + shift;
-            const int64_t k = slot / (CT * TR);
+            const int64_t k = (slot + a.plan.chunk_off * TR) / (CT * TR);
+            const int64_t tbeg = k * CT - a.plan.chunk_off > 0 ? k * CT - a.plan.chunk_off : 0;   // the chunk's first tile
             const int64_t ylo = owners.first[k], yhi = owners.last[k];
-            const T* __restrict__ wsn = a.wsn + (slot - k * CT * TR);
+            const T* __restrict__ wsn = a.wsn + (slot - tbeg * TR);
 #pragma unroll 4
             for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
         }
@@ -819,7 +848,8 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
         const int64_t pi = i / C;
         int64_t tlo, thi;
         panel_tiles<LOWER>(pi * C, C, a.n, shift, TR, a.plan.ntiles, tlo, thi);
-        const int64_t kbeg = tlo / a.plan.chunk_tiles, kend = (thi - 1) / a.plan.chunk_tiles + 1;
+        const int64_t kbeg = (tlo + a.plan.chunk_off) / a.plan.chunk_tiles;
+        const int64_t kend = (thi - 1 + a.plan.chunk_off) / a.plan.chunk_tiles + 1;
         const T* __restrict__ wst = a.wst + pi * a.plan.nchunks * C + (i - pi * C);
 #pragma unroll 4
         for (int64_t k = kbeg + g; k < kend; k += RED_PARTS) s = add_of(s, wst[k * C]);
@@ -872,7 +902,9 @@ template <class T> constexpr int64_t small_n() { return sizeof(T) == 4 ? 2176 : 
 // fastest from a few hundred megabytes of triangle on (the kernel's loads are pipelined by the wave itself,
 // and more resident workgroups only lengthen the queues in front of the memory channels: DSYMV 16384
 // 164 us against 176-178 us with two or three per compute unit), two below; chunks of 8 row tiles pay for
-// 8-byte elements from about n = 20000 (2%), for 16-byte elements from about n = 8400 (10% at 24576); 12 tiles
+// real 8-byte elements from about n = 17400 (1-2%; not at 16384: -4%), for complex 8-byte elements from about 9000
+// (2-5%), for 16-byte elements from about n = 8400 (10% at 24576) - the complex types spend more on the column
+// sums of a piece, which a taller piece amortises; 12 tiles
 // (what 64 KB of static LDS hold) add 1-2.5% for 16-byte elements from about 10000, and 16 tiles (80 KB of dynamic
 // LDS) another 0.7-4% from 16384 (ZHEMV 32768: 1314 -> 1271 us) and 1.7% for 8-byte elements at 40960; 4 tiles
 // elsewhere and always for 4-byte elements.
@@ -885,7 +917,7 @@ template <class T> inline int default_wgs_per_cu(int64_t n) {
 template <class T> inline int64_t default_tiles_per_wave(int64_t n) {
     if (sizeof(T) == 4) return 1;
     if (sizeof(T) == 16) return n >= 16384 ? 4 : (n >= 10240 ? 3 : (n >= 8448 ? 2 : 1));
-    return n >= 36864 ? 4 : (n >= 20480 ? 2 : 1);
+    return n >= 36864 ? 4 : (n >= (Traits<T>::cplx ? 9216 : 17408) ? 2 : 1);
 }
 // fixed part of a piece's weight on the work line, in row tiles (the column sums and their store, the
 // change of panel): measured, see the tuning key symv_piece_fixed
@@ -952,9 +984,10 @@ template <class T, class F>
 inline void walk_work_line(bool lower, int64_t n, int shift, int ct, int kt, int fixed, int edge, F&& f) {
     constexpr int TR = tile_rows<T>();
     constexpr int C = BAL_NC * SY_NW;
-    const int ntiles = (int)ceil_div(n + shift, TR), nchunks = (int)ceil_div(ntiles, ct), npanels = (int)ceil_div(n, C);
+    const int ntiles = (int)ceil_div(n + shift, TR), npanels = (int)ceil_div(n, C);
+    const int coff = (int)symv_chunk_offset(lower, ntiles, ct, kt), nchunks = (int)ceil_div(ntiles + coff, ct);
     for (int k = 0; k < nchunks; ++k) {
-        const int tbeg = k * ct, tend = tbeg + ct < ntiles ? tbeg + ct : ntiles;
+        const int tbeg = k * ct - coff > 0 ? k * ct - coff : 0, tend = (k + 1) * ct - coff < ntiles ? (k + 1) * ct - coff : ntiles;
         int64_t plo, phi;
         if (lower) chunk_panels<true>(tbeg, tend, C, shift, TR, npanels, plo, phi);
         else chunk_panels<false>(tbeg, tend, C, shift, TR, npanels, plo, phi);
@@ -1018,7 +1051,8 @@ inline const SymvBalanced* balanced_shares(bool lower, int64_t n, int shift, int
     b.work = W;
     b.workers = (int)Y;
     constexpr int TR = tile_rows<T>();
-    const int nchunks = (int)ceil_div(ceil_div(n + shift, TR), ct);
+    const int64_t ntiles_all = ceil_div(n + shift, TR);
+    const int nchunks = (int)ceil_div(ntiles_all + symv_chunk_offset(lower, ntiles_all, ct, kt), ct);
     // worker y starts at the first piece whose first unit lies at or after partition's starting point s(y)
     int64_t pos = 0, y = 0, wy, sy;
     partition(W, Y, 0, wy, sy);
@@ -1082,9 +1116,11 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     p.panel_cols = C;
     p.npanels = ceil_div(n, C);
     p.chunk_tiles = SY_NW * ktw;
-    p.nchunks = ceil_div(p.ntiles, p.chunk_tiles);
+    p.unit_tiles = tn.symv_unit_tiles > 0 ? (int)tn.symv_unit_tiles : default_unit_tiles<T>(n);
+    if (ktw >= 3 || sizing || p.variant != 2) p.unit_tiles = 1;   // the 12- and 16-tile chunks exist with one-tile units only
+    p.chunk_off = sizing ? 0 : symv_chunk_offset(lower, p.ntiles, p.chunk_tiles, p.unit_tiles);
+    p.nchunks = sizing ? ceil_div(p.ntiles, p.chunk_tiles) + 1 : ceil_div(p.ntiles + p.chunk_off, p.chunk_tiles);
     p.work = 0;
-    p.unit_tiles = 1;
     p.workers = 0;
     p.bal = nullptr;
     size_t wsn_bytes = 0;
@@ -1093,7 +1129,7 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
         // panels, for either chunk height
         p.rows_padded = partial_stride<T>(4 * SY_NW * TR);
         for (int64_t kw = 1; kw <= 4; ++kw) {
-            const int64_t nc = ceil_div(p.ntiles, SY_NW * kw);
+            const int64_t nc = ceil_div(p.ntiles, SY_NW * kw) + 1;   // the chunk grid may start before tile 0
             int64_t entries = nc * p.npanels < SHARE_MAX_WORKERS ? nc * p.npanels : SHARE_MAX_WORKERS;
             entries += nc + 1;
             const size_t bytes = (size_t)entries * partial_stride<T>(kw * SY_NW * TR) * sizeof(T);
@@ -1105,8 +1141,6 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
             p.total_bytes = 0;
             return p;
         }
-        p.unit_tiles = tn.symv_unit_tiles > 0 ? (int)tn.symv_unit_tiles : default_unit_tiles<T>(n);
-        if (ktw >= 3) p.unit_tiles = 1;   // the 12- and 16-tile chunks exist with one-tile units only
         int64_t Y = tn.wg_target;
         if (Y <= 0) {
             // one resident round: compute units x workgroups per compute unit (never more than fit)

@@ -101,10 +101,11 @@ def test_workspace_sizes():
         big = kmv.gemv_workspace_bytes(prec, "N", 4096, 4096)
         assert 0 < small <= big
         assert small >= 1024 * b                      # room for a packed x
-        n = 2048
+        n = 8192
         s = kmv.symv_workspace_bytes(prec, "L", n)
         assert s >= n * b and s == kmv.symv_workspace_bytes(prec, "U", n)
         assert s < 0.2 * n * n * b                    # partial sums stay a small share of the matrix
+        assert kmv.symv_workspace_bytes(prec, "L", 2048) < 32 << 20   # bounded by the most workgroups x the tallest chunk
     assert kmv.gemv_workspace_bytes("q", "N", 8, 8) == 0
     assert kmv.symv_workspace_bytes("d", "L", -1) == 0
 

@@ -16,14 +16,18 @@ C = 16
 def enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed, edge=0):
     """[(chunk, piece in chunk, weight)] in line order, from the definition: piece (k, p) exists when some
     stored element (i, j), j in panel p, has its row slot i + shift in chunk k; its weight counts the groups
-    of kt row tiles of the chunk that hold such an element, times kt, plus `fixed`."""
+    of kt row tiles of the chunk that hold such an element, times kt, plus `fixed`.  The tiles rarely divide into
+    whole chunks: the short chunk is the FIRST one for lower storage (the chunk grid starts `coff` tiles before
+    tile 0) and the last one for upper storage - where the triangle is narrow."""
     tr = TILE_ROWS[prec]
     ntiles = -(-(n + shift) // tr)
-    nchunks = -(-ntiles // ct)
+    coff = (ct - ntiles % ct) % ct if uplo == "L" else 0
+    coff -= coff % kt                    # a multiple of the unit's tiles: only the matrix's last chunk ends inside a unit
+    nchunks = -(-(ntiles + coff) // ct)
     npanels = -(-n // C)
     out = []
     for k in range(nchunks):
-        tbeg, tend = k * ct, min(k * ct + ct, ntiles)
+        tbeg, tend = max(k * ct - coff, 0), min((k + 1) * ct - coff, ntiles)
         j = 0
         for p in range(npanels):
             c0, c1 = p * C, min(p * C + C, n) - 1           # columns of the panel
@@ -48,7 +52,7 @@ def enumerate_pieces(prec, uplo, n, shift, ct, kt, fixed, edge=0):
 CASES = [(prec, uplo, n, shift, ct, kt, slots, fixed, edge)
          for prec in "sdcz" for uplo in "LU"
          for n, shift in ((2049, 0), (2600, 5), (4099, 0), (5000, 15), (8192, 1), (12289, 7))
-         for ct, kt in ((4, 1), (8, 1), (8, 2), (4, 2))
+         for ct, kt in ((4, 1), (8, 1), (8, 2), (4, 2), (12, 1), (16, 1))
          for slots, fixed, edge in ((768, 1, 2), (512, 3, 0), (100, 0, 1))]
 
 
