@@ -11,6 +11,7 @@ interleaved rounds are (the defaults in the planners were chosen this way).
   python -m paper_1410_1726_amd.tune dsymv_L 16384 symv_unit_tiles=1,2 wg_target=512,768
   python -m paper_1410_1726_amd.tune sgemv_N 8192x65536 gemv_n_splits=0,32,64,128
   python -m paper_1410_1726_amd.tune zhemv_L 40960 lda_pad=32 symv_tiles_per_wave=2,3     (lda = n + 32)
+  python -m paper_1410_1726_amd.tune dsymv_L 18999 off=1 lda_pad=1000                     (block at (1, 1), lda = 20000)
 
 A value 0 means "let the library choose".  Prints the median time of every
 combination (microseconds, GB/s of algorithmic bytes) and marks the fastest.
@@ -63,20 +64,24 @@ def _time(call, reps, warm=2):
     return e0.elapsed_time(e1) / reps * 1e3
 
 
-def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int = 10, lda_pad: int = 0):
-    """routine like 'dgemv_T', 'zhemv_U', 'ssymv_L'; grid: {key: [values]}; lda = m + lda_pad.  Returns
+def sweep(routine: str, m: int, n: int, grid: dict, rounds: int = 5, reps: int = 10, lda_pad: int = 0, off: int = 0):
+    """routine like 'dgemv_T', 'zhemv_U', 'ssymv_L'; grid: {key: [values]}; lda = m + off + lda_pad, the matrix is
+    the block at (off, off) of its parent.  Returns
     [(settings dict, median microseconds)], in grid order."""
     keys = list(grid)
     combos = [dict(zip(keys, vals)) for vals in itertools.product(*(grid[key] for key in keys))] or [{}]
-    return sweep_settings(routine, m, n, combos, rounds, reps, lda_pad)
+    return sweep_settings(routine, m, n, combos, rounds, reps, lda_pad, off)
 
 
-def sweep_settings(routine: str, m: int, n: int, combos: list, rounds: int = 5, reps: int = 10, lda_pad: int = 0):
+def sweep_settings(routine: str, m: int, n: int, combos: list, rounds: int = 5, reps: int = 10, lda_pad: int = 0,
+                   off: int = 0):
     """The same over an explicit list of settings dicts ({} = the library's own choice, saved table included)."""
     prec, name, mode = routine[0], routine[1:5], routine[-1]
     sym = name in ("symv", "hemv")
-    lda = m + lda_pad
-    A = wl.matrix(prec, m, n, lda, device="cuda")
+    lda = m + off + lda_pad
+    A = wl.matrix(prec, m + off, n + off, lda, device="cuda")
+    if off:
+        A = A[off:, off:]        # a sub-block pointer: same leading dimension, any alignment
     lenx, leny = (n, n) if sym else ((n, m) if mode == "N" else (m, n))
     x = wl.vector(prec, lenx, device="cuda")
     y = wl.vector(prec, leny, which=2, device="cuda")
@@ -281,14 +286,17 @@ def main(argv):
         return 0
     routine, shape = argv[0], argv[1]
     m, n = (int(v) for v in shape.split("x")) if "x" in shape else (int(shape), int(shape))
-    grid, lda_pad = {}, 0
+    grid, lda_pad, off = {}, 0, 0
     for spec in argv[2:]:
         key, vals = spec.split("=")
-        if key == "lda_pad":          # not a tuning key: the matrix gets the leading dimension m + lda_pad
+        if key == "lda_pad":          # not a tuning key: the matrix gets the leading dimension m + off + lda_pad
             lda_pad = int(vals)
             continue
+        if key == "off":              # not a tuning key: the matrix is the block at (off, off) of its parent
+            off = int(vals)
+            continue
         grid[key] = [int(v) for v in vals.split(",")]
-    res = sweep(routine, m, n, grid, lda_pad=lda_pad)
+    res = sweep(routine, m, n, grid, lda_pad=lda_pad, off=off)
     op = {"gemv": "gemv_" + routine[-1].lower(), "symv": "symv_l", "hemv": "hemv_l"}[routine[1:5]]
     nbytes = acc.algorithmic_bytes(op, routine[0], m, n)
     best = min(us for _, us in res)
