@@ -920,8 +920,10 @@ template <class T> inline int64_t default_tiles_per_wave(int64_t n) {
     return n >= 36864 ? 4 : (n >= (Traits<T>::cplx ? 9216 : 17408) ? 2 : 1);
 }
 // fixed part of a piece's weight on the work line, in row tiles (the column sums and their store, the
-// change of panel): measured, see the tuning key symv_piece_fixed
-constexpr int DEFAULT_PIECE_FIXED = 1;
+// change of panel): measured over s, d, c, z at n = 16384 and 32768 with the key symv_piece_fixed: three tiles' worth is
+// never slower than one and 2-4% faster for SSYMV at 16384 and ZHEMV with tall chunks (whose pieces on the diagonal
+// are the most lopsided); beyond that nothing changes
+constexpr int DEFAULT_PIECE_FIXED = 3;
 // what an edge tile costs on top of an ordinary one, in row tiles (tuning key symv_edge_weight)
 // measured at n = 17001 (one ragged tile at the bottom of every column): one tile's worth for 8- and 16-byte
 // elements, three for 4-byte ones (four elements per lane to move into place)
