@@ -364,3 +364,23 @@ def test_pointer_array_batched_argument_errors(prec):
     assert symv(uplo="X") == -1 and symv(n=-1) == -2 and symv(lda=7) == -5
     assert symv(incx=-1) == -7 and symv(incy=0) == -10 and symv(batch=-1) == -11
     assert symv(batch=0) == 0 and symv(n=0, lda=1) == 0 and symv(A=None) == kmv.ERR_NULL
+
+
+def test_tuning_tool_table_rows():
+    """host-only: the size classes of the table-saving mode and the text of a saved row"""
+    from paper_1410_1726_amd import tune
+    assert tune._size_class(16384, 16) == (15360, 17409) and tune._size_class(4096, 64) == (4032, 4161)
+    row = tune._row_text("zhemv_U", 8192, 64, {"symv_variant": 2, "symv_tiles_per_wave": 1, "wg_target": 256})
+    assert row.strip().startswith("{'U', 'z', 8064, 8321, 0, 0, 0, 2, 1, 0, 256}")
+    assert tune._row_text("cgemv_C", 4096, 16, {"gemv_t_splits": 16}).strip().startswith("{'T', 'c', 3840, 4353, 0, 0, 16, 0, 0, 0, 0}")
+    assert tune._op("dgemv_N") == "N" and tune._op("sgemv_T") == "T" and tune._op("dsymv_L") == "L"
+    assert len(tune.ROW_FIELDS) == len(kmv.TUNED_FIELDS) and tuple(tune.ROW_FIELDS) == tuple(kmv.TUNED_FIELDS)
+    assert len(tune.TABLE_ROUTINES) == 16 and len(set(tune.TABLE_ROUTINES)) == 16
+
+
+def test_tuning_tool_writes_rows(tmp_path):
+    from paper_1410_1726_amd import tune
+    rows = [tune._row_text("sgemv_N", 4096, 64, {"gemv_n_row_tiles": 2})]
+    path = tune.write_rows(rows, str(tmp_path / "table.inc"))
+    text = open(path).read()
+    assert text.startswith("// Written by") and "{'N', 's', 4032, 4161, 0, 2, 0, 0, 0, 0, 0}" in text
