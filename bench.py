@@ -355,8 +355,9 @@ def sytrd_panel_bench(args, k, torch, wl, acc):
 
 def gebrd_panel_bench(args, k, torch, wl, acc):
     """One step = the panel step of the bidiagonal reduction (kmv_dgebrd_panel) on the first 64 columns and rows of
-    a 16384 x 16384 fp64 matrix: per column DGEMV-T and DGEMV-N on the whole trailing block (the latter with a
-    strided x, a row of A) and eleven DGEMV on the accumulated panels, two reflectors, two scalings."""
+    a 16384 x 16384 matrix: per column GEMV-T and GEMV-N on the whole trailing block and eleven products with the
+    accumulated panels, two reflectors, two scalings (the panel products and vector steps run in four fused
+    launches per column; the bytes counted are those of the algorithm's products, each as a GEMV of its own)."""
     m = n = 16384
     nb, prec = 64, args.prec
     A0 = wl.matrix(prec, m, n, m, seed=0, device="cuda")
@@ -403,7 +404,7 @@ def gebrd_panel_bench(args, k, torch, wl, acc):
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAMES[prec], "data": "synthetic",
         "config": {"workload": f"panel step of the bidiagonal reduction (kmv_{prec}gebrd_panel), m=n=16384, nb=64, lda=m, "
-                               "U[-1,1]: 128 GEMV on trailing blocks + about 690 GEMV on the panels",
+                               "U[-1,1]: 128 GEMV on trailing blocks + about 690 products with the panels (four fused kernels per column)",
                    "products_per_step": 2 * nb + 11 * (nb - 1)},
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "gflops": round(nflops / (step_ms * 1e-3) / 1e9, 1),

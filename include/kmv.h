@@ -299,7 +299,10 @@ size_t kmv_sytrd_panel_workspace_bytes(char prec, int64_t n, int64_t nb);
  * (rows 0..i of column i of X and Y are scratch).  Rows and columns nb.. of A
  * beyond the panel are not modified.  The last column of the matrix has no
  * row reflector (e = taup = 0).  Norms are formed without rescaling.
- * Only enqueues kernels on `stream` (about twenty per column), capturable.
+ * Only enqueues kernels on `stream` (eight per column for nb <= 256: the two
+ * products with the trailing block, their second stages and four launches of
+ * the panel's own kernels, which do not write the scratch rows of X and Y;
+ * about twenty GEMV-sized launches per column beyond), capturable.
  * m < n reduces to LOWER bidiagonal form with the roles of rows and columns
  * exchanged: row i is brought up to date and reflected first (G_i annihilates
  * A[i][i+1..n-1]; A[i][i..n-1] = u_i with A[i][i] = 1, d[i] the diagonal

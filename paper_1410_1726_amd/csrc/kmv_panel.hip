@@ -17,8 +17,10 @@
 // as six GEMV launches, their second-stage sums and two vector kernels they were eleven launches of 4-11 us
 // each, a quarter of the panel's time for 3% of its bytes.
 // Upper storage runs the mirror image (last nb columns, from the right), complex types the Hermitian form
-// (conjugated transposes, real e).  The bidiagonal step further down is built on the public GEMV entry
-// points and exists for all four precisions as well.
+// (conjugated transposes, real e).  The bidiagonal step further down follows the same plan in all four
+// precisions: the two products with the trailing block per column go through the public GEMV entry points,
+// everything else of a column is four launches of two kernels of this file (a panel wider than 256 columns
+// runs the step built from GEMV calls alone, about twenty launches per column).
 // Everything stays on the device and on the caller's stream: tau, the norms and the inner
 // products never visit the host, so a whole panel is one uninterrupted sequence of
 // launches (and can be captured in a graph).
@@ -442,6 +444,182 @@ template <class R, class T> __global__ void no_reflector_kernel(R* e, T* tau) {
     *tau = zero_of<T>();
 }
 
+// ---- The bidiagonal panel's own kernels -------------------------------------------------------------------
+// A column of the bidiagonal step has two halves of the same shape, one along the rows of the matrix (the
+// column reflector v_i, then x_i) and one along its columns (the row reflector u_i, then y_i).  Each half is a
+// long vector index r and two tall panels that are contiguous in r:
+//     along the rows:     V = A[:, :i] (the column reflectors) and X
+//     along the columns:  Y and U, where U[j][k] = u_k[j] is a contiguous copy of the row reflectors kept in the
+//                         workspace (row k of A holds u_k^H with stride lda, which no wave can read coalesced)
+// and runs as  update -> reflector -> product with the trailing block (the public GEMV entry point) -> the
+// other half's update, ...: two launches of this file per half, four per column, where the step built from
+// GEMV calls took about twenty.
+//   bd_update_kernel      finishes the vector z the product before it left behind,
+//                             z <- tau (z - P s1 - Q s2),   s1 = P^H w, s2 = Q^H w summed from the partials of the
+//                             reflector kernel before (w = the reflector the product was formed with),
+//                         and brings the next vector to reflect up to date with all reflectors so far,
+//                             t <- t - P c1 - Q c2 - z cz   (c1, c2, cz: the entries of the other half's panels
+//                             in the row or column of t, conjugated as the update A - V Y^H - X U^H asks),
+//                         reading both panels once for the two sums; t is taken from a strided, conjugated
+//                         row of A (GATHER) or updated in place; its first entry goes to *alpha_out, the
+//                         partial sums of squares of the others to normpart (one per workgroup)
+//   bd_reflector_kernel   beta, tau and the scaling from alpha and the partial norms; scales the vector in
+//                         place (first entry = 1), optionally scatters its conjugate into the row of A, and
+//                         leaves the partial products P^H w, Q^H w of its row chunk in `dots`
+// Partial sums are added in workgroup order by every consumer, so results do not depend on scheduling.
+constexpr int BD_NB = 256;     // widest panel the two kernels hold coefficients for; wider panels take the GEMV-built step
+
+template <class T, bool GATHER>
+__global__ __launch_bounds__(FT) void bd_update_kernel(int64_t len, int64_t rpw, int kp, const T* __restrict__ P, int64_t ldp, int kq,
+                                                       const T* __restrict__ Q, int64_t ldq, T* z, const T* tau,
+                                                       const T* __restrict__ dots, int gd, const T* c1src, int64_t c1inc,
+                                                       const T* c2src, int64_t c2inc, int conj2, const T* czsrc, const T* src,
+                                                       int64_t sinc, T* dst, typename Traits<T>::real* normpart, T* alpha_out,
+                                                       int fin, int has_next) {
+    using R = typename Traits<T>::real;
+    __shared__ T s1[BD_NB], s2[BD_NB], c1[BD_NB], c2[BD_NB];
+    __shared__ T partf[FT / WAVE][FR], partu[FT / WAVE][FR];
+    __shared__ T czs;
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    const bool update = fin && has_next;
+    if (fin) {
+        const int kk = kp + kq;
+        for (int j = threadIdx.x; j < kk; j += FT) {
+            T s = zero_of<T>();
+#pragma unroll 8
+            for (int g = 0; g < gd; ++g) s = add_of(s, dots[(int64_t)g * kk + j]);
+            if (j < kp) s1[j] = s;
+            else s2[j - kp] = s;
+        }
+        if (has_next) {
+            for (int j = threadIdx.x; j < kp; j += FT) c1[j] = conj_of(c1src[j * c1inc]);
+            for (int j = threadIdx.x; j < kq; j += FT) c2[j] = conj2 ? conj_of(c2src[j * c2inc]) : c2src[j * c2inc];
+            if (threadIdx.x == 0) czs = conj2 ? conj_of(*czsrc) : *czsrc;
+        }
+        __syncthreads();
+    }
+    const T t = fin ? *tau : zero_of<T>();
+    const T cz = update ? czs : zero_of<T>();
+    R nrm = 0;
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < len ? r0 + rpw : len;
+    for (int64_t rb = r0; rb < r1; rb += FR) {
+        const int64_t r = rb + lane;
+        const bool in = r < r1;
+        if (fin) {
+            T sf = zero_of<T>(), su = zero_of<T>();
+            if (in) {
+#pragma unroll 8
+                for (int j = wv; j < kp; j += FT / WAVE) {
+                    const T p = P[r + j * ldp];
+                    fma_acc(sf, p, s1[j]);
+                    if (update) fma_acc(su, p, c1[j]);
+                }
+#pragma unroll 8
+                for (int j = wv; j < kq; j += FT / WAVE) {
+                    const T q = Q[r + j * ldq];
+                    fma_acc(sf, q, s2[j]);
+                    if (update) fma_acc(su, q, c2[j]);
+                }
+            }
+            partf[wv][lane] = sf;
+            partu[wv][lane] = su;
+            __syncthreads();
+        }
+        if (wv == 0 && in) {
+            T zf = zero_of<T>();
+            if (fin) {
+                T tot = partf[0][lane];
+#pragma unroll
+                for (int q = 1; q < FT / WAVE; ++q) tot = add_of(tot, partf[q][lane]);
+                zf = mul_of(t, add_of(z[r], neg_of(tot)));
+                z[r] = zf;
+            }
+            if (has_next) {
+                T acc = src[r * sinc];
+                if constexpr (GATHER) acc = conj_of(acc);
+                if (fin) {
+                    T sub = partu[0][lane];
+#pragma unroll
+                    for (int q = 1; q < FT / WAVE; ++q) sub = add_of(sub, partu[q][lane]);
+                    fma_acc(sub, zf, cz);
+                    acc = add_of(acc, neg_of(sub));
+                }
+                dst[r] = acc;
+                if (r == 0) *alpha_out = acc;
+                else nrm += abs2_of(acc);
+            }
+        }
+        if (fin) __syncthreads();     // the part arrays are written again in the next pass
+    }
+    if (has_next && wv == 0) {
+        nrm = wave_sum(nrm);
+        if (lane == 0) normpart[blockIdx.x] = nrm;
+    }
+}
+
+// Reflector of the vector a (len entries, alpha = a[0], x the rest), alpha and ||x||^2 from the update kernel
+// before: beta = -sign(Re alpha) ||(alpha, x)||, tau = (beta - alpha) / beta, x <- x / (alpha - beta), a[0] = 1;
+// x = 0 (and a real alpha) gives tau = 0, beta = alpha.  With `scat` the conjugate of the finished vector goes to
+// scat[r * scinc] as well (the row of A).  Then the chunk's share of P^H a (kp sums) and Q^H a (kq sums):
+// dots[g][0 .. kp) and dots[g][kp .. kp + kq).
+template <class T>
+__global__ __launch_bounds__(DT) void bd_reflector_kernel(int64_t len, int64_t rpw, int kp, const T* __restrict__ P, int64_t ldp, int kq,
+                                                          const T* __restrict__ Q, int64_t ldq, T* a,
+                                                          const typename Traits<T>::real* normpart, int gn, const T* alpha_in,
+                                                          typename Traits<T>::real* e, T* tau, T* scat, int64_t scinc, T* dots) {
+    using R = typename Traits<T>::real;
+    __shared__ R red[DT / WAVE];
+    R x2 = 0;
+    for (int g = threadIdx.x; g < gn; g += DT) x2 += normpart[g];
+    const R xn2 = group_sum<DT>(x2, red);
+    const T alpha = *alpha_in;
+    R beta, are, aim = 0;
+    if constexpr (Traits<T>::cplx) { are = alpha.re; aim = alpha.im; }
+    else are = alpha;
+    beta = are;
+    T t = zero_of<T>(), scale = zero_of<T>();
+    const bool have = xn2 != 0 || aim != 0;
+    if (have) {
+        beta = -copysign(sqrt(are * are + aim * aim + xn2), are);
+        const R dr = are - beta, den = dr * dr + aim * aim;      // 1 / (alpha - beta)
+        if constexpr (Traits<T>::cplx) {
+            t = T{(beta - are) / beta, -aim / beta};
+            scale = T{dr / den, -aim / den};
+        } else {
+            t = (beta - are) / beta;
+            scale = R(1) / dr;
+        }
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < len ? r0 + rpw : len;
+    for (int64_t r = r0 + threadIdx.x; r < r1; r += DT) {
+        T x = from_one<T>();
+        if (r != 0) {
+            x = a[r];
+            if (have) x = mul_of(x, scale);
+        }
+        a[r] = x;
+        if (scat) scat[r * scinc] = conj_of(x);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *e = beta;
+        *tau = t;
+    }
+    const int kk = kp + kq;
+    if (kk == 0) return;
+    __syncthreads();     // the chunk of the vector is in place for all waves of the workgroup
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    for (int j = wv; j < kk; j += DT / WAVE) {
+        const T* col = j < kp ? P + j * ldp : Q + (j - kp) * ldq;
+        T acc = zero_of<T>();
+#pragma unroll 4
+        for (int64_t r = r0 + lane; r < r1; r += WAVE) fma_acc_conj(acc, col[r], a[r]);
+        acc = wave_sum(acc);
+        if (lane == 0) dots[(int64_t)blockIdx.x * kk + j] = acc;
+    }
+}
+
 template <class T> inline T from_real(double v) {
     if constexpr (Traits<T>::cplx) return T{(typename Traits<T>::real)v, 0};
     else return (T)v;
@@ -632,13 +810,33 @@ template <class T> size_t short_rows_bytes(int64_t nb) {
     return Traits<T>::cplx ? (size_t)((3 * nb * sizeof(T) + 255) / 256) * 256 : 0;
 }
 
-// the row copy plus the largest workspace any product of the bidiagonal panel asks for
+// the contiguous copy U of the row reflectors (n x nb, U[j][k] = u_k[j]) that the fused step keeps
+inline int64_t bd_ldu(int64_t n) { return (n + 31) / 32 * 32; }
+template <class T> size_t bd_u_bytes(int64_t n, int64_t nb) { return round_up((size_t)bd_ldu(n) * (size_t)nb * sizeof(T), 256); }
+
+// Workspace of the bidiagonal panel.  Panels of at most BD_NB columns run the fused step: the hand-over scratch
+// of its kernels, U, and the largest workspace of the two products with the trailing block; wider panels the
+// step built from GEMV calls: the row copy plus the largest workspace any of its products asks for.
 template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
     if (m <= 0 || n <= 0 || nb <= 0) return 0;
     const int64_t mn = m < n ? m : n;
     if (nb > mn) nb = mn;
     const char p = Calls<T>::prec;
     size_t need = 0;
+    if (nb <= BD_NB) {
+        for (int64_t i = 0; i < nb; ++i) {
+            const int64_t mi = m < n ? m - i - 1 : m - i, ni = m < n ? n - i : n - i - 1;
+            if (mi <= 0 || ni <= 0) continue;
+            if (m < n) {
+                need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi, ni));
+                need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', mi, ni - 1));
+            } else {
+                need = max_of(need, kmv_gemv_workspace_bytes(p, 'T', mi, ni));
+                need = max_of(need, kmv_gemv_workspace_bytes(p, 'N', mi - 1, ni));
+            }
+        }
+        return PanelScratch<T>::bytes(nb) + bd_u_bytes<T>(n, nb) + need;
+    }
     if (m < n) {     // lower bidiagonal: rows first
         for (int64_t i = 0; i < nb; ++i) {
             const int64_t mi = m - i - 1, ni = n - i;
@@ -672,9 +870,130 @@ template <class T> size_t gebrd_workspace(int64_t m, int64_t n, int64_t nb) {
     return row_bytes<T>(n) + short_rows_bytes<T>(nb) + need;
 }
 
+// The bidiagonal panel step with the kernels above (panels of at most BD_NB columns): per column
+//   m >= n:  reflector of column i (d, tauq; partial V^H v, X^H v) - y_i = A22^H v (GEMV) - update along the columns
+//            (y_i finished; row i gathered, conjugated, brought up to date into U[:, i]) - reflector of the row (e,
+//            taup; scattered back into A; partial Y^H u, U^H u) - x_i = A22 u (GEMV) - update along the rows (x_i
+//            finished; column i+1 brought up to date)
+//   m <  n:  the same with rows and columns exchanged, the row first.
+// Arguments are checked by the caller.
+template <class T>
+int gebrd_panel_fused(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, typename Traits<T>::real* d,
+                      typename Traits<T>::real* e, T* tauq, T* taup, T* X, int64_t ldx, T* Y, int64_t ldy, void* ws, size_t wsb,
+                      void* stream) {
+    using R = typename Traits<T>::real;
+    constexpr bool CPLX = Traits<T>::cplx;
+    const PanelScratch<T> sc(ws);
+    T* U = reinterpret_cast<T*>(static_cast<char*>(ws) + PanelScratch<T>::bytes(nb));
+    const int64_t ldu = bd_ldu(n);
+    const size_t front = PanelScratch<T>::bytes(nb) + bd_u_bytes<T>(n, nb);
+    ws = static_cast<char*>(ws) + front;
+    wsb -= front;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const T one = from_real<T>(1), zero = from_real<T>(0);
+    const char TR = CPLX ? 'C' : 'T';
+    auto a_ = [&](int64_t i, int64_t j) { return A + i + j * lda; };
+    auto x_ = [&](int64_t i, int64_t j) { return X + i + j * ldx; };
+    auto y_ = [&](int64_t i, int64_t j) { return Y + i + j * ldy; };
+    auto u_ = [&](int64_t j, int64_t k) { return U + j + k * ldu; };
+    const T* nullc = nullptr;
+    T* nullm = nullptr;
+    int rc = KMV_OK;
+#define KMV_BD_CHECK()                                           \
+    do {                                                         \
+        const hipError_t he_ = hipGetLastError();                \
+        if (he_ != hipSuccess) return KMV_ERR_HIP + (int)he_;    \
+    } while (0)
+    // update along the rows of A: finishes x (column kq of X, `fin`) and brings column c of A up to date (`next`),
+    // both from row r0 on; kp = columns of V, kq = columns of X in the sums
+    auto rows_update = [&](int64_t r0, int64_t c, int kp, int kq, const T* tau, int gd, int fin, int next) {
+        const int64_t len = m - r0;
+        hipLaunchKernelGGL((bd_update_kernel<T, false>), dim3(thin_chunks(len)), dim3(FT), 0, s, len, thin_rows(len), kp, a_(r0, 0), lda,
+                           kq, x_(r0, 0), ldx, fin ? x_(r0, kq) : nullm, tau, sc.dots, gd, next && fin ? y_(c, 0) : nullc, ldy,
+                           next && fin ? a_(0, c) : nullc, (int64_t)1, 0, next && fin ? a_(kq, c) : nullc,
+                           next ? a_(r0, c) : nullc, (int64_t)1, next ? a_(r0, c) : nullm, sc.normpart, sc.alpha, fin, next);
+    };
+    // update along the columns of A: finishes y (column yc of Y, `fin`) and gathers row r of A from column j0 on,
+    // conjugated and brought up to date, into U[j0:, r] (`next`); P and Q are (Y, U) or (U, Y), see the callers
+    auto cols_update = [&](int64_t j0, int64_t r, int kp, const T* P, int64_t ldp, int kq, const T* Q, int64_t ldq, T* z,
+                           const T* tau, int gd, const T* c1src, int64_t c1inc, const T* c2src, int64_t c2inc, const T* czsrc, int fin,
+                           int next) {
+        const int64_t len = n - j0;
+        hipLaunchKernelGGL((bd_update_kernel<T, true>), dim3(thin_chunks(len)), dim3(FT), 0, s, len, thin_rows(len), kp, P, ldp, kq, Q,
+                           ldq, z, tau, sc.dots, gd, c1src, c1inc, c2src, c2inc, 1, czsrc, next ? a_(r, j0) : nullc, lda,
+                           next ? u_(j0, r) : nullm, sc.normpart, sc.alpha, fin, next);
+    };
+    auto reflect = [&](int64_t len, int kp, const T* P, int64_t ldp, int kq, const T* Q, int64_t ldq, T* a, R* beta, T* tau, T* scat) {
+        hipLaunchKernelGGL((bd_reflector_kernel<T>), dim3(fat_chunks(len)), dim3(DT), 0, s, len, fat_rows(len), kp, P, ldp, kq, Q, ldq, a,
+                           sc.normpart, (int)thin_chunks(len), sc.alpha, beta, tau, scat, lda, sc.dots);
+    };
+    if (m < n) {
+        // lower bidiagonal: the row first
+        cols_update(0, 0, 0, nullc, 0, 0, nullc, 0, nullm, nullc, 0, nullc, 0, nullc, 0, nullc, 0, 1);
+        KMV_BD_CHECK();
+        for (int64_t i = 0; i < nb; ++i) {
+            const int64_t mi = m - i - 1, ni = n - i;       // rows below row i, columns from column i on
+            const int k = (int)i;
+            reflect(ni, k, y_(i, 0), ldy, k, u_(i, 0), ldu, u_(i, i), d + i, taup + i, a_(i, i));
+            KMV_BD_CHECK();
+            if (mi <= 0) {     // last row of the matrix: no column reflector
+                hipLaunchKernelGGL((no_reflector_kernel<R, T>), dim3(1), dim3(1), 0, s, e + i, tauq + i);
+                KMV_BD_CHECK();
+                continue;
+            }
+            rc = Calls<T>::gemv('N', mi, ni, &one, a_(i + 1, i), lda, u_(i, i), (int64_t)1, &zero, x_(i + 1, i), (int64_t)1, ws, wsb,
+                                stream);
+            if (rc) return rc;
+            // x_i = taup (x - V (Y^H u) - X (U^H u)); column i below the diagonal catches up, x_i taking part
+            rows_update(i + 1, i, k, k, taup + i, (int)fat_chunks(ni), 1, 1);
+            KMV_BD_CHECK();
+            reflect(mi, k + 1, x_(i + 1, 0), ldx, k, a_(i + 1, 0), lda, a_(i + 1, i), e + i, tauq + i, nullm);
+            KMV_BD_CHECK();
+            rc = Calls<T>::gemv(TR, mi, ni - 1, &one, a_(i + 1, i + 1), lda, a_(i + 1, i), (int64_t)1, &zero, y_(i + 1, i), (int64_t)1,
+                                ws, wsb, stream);
+            if (rc) return rc;
+            // y_i = tauq (y - U (X^H v) - Y (V^H v)); row i+1 catches up, y_i taking part
+            cols_update(i + 1, i + 1, k + 1, u_(i + 1, 0), ldu, k, y_(i + 1, 0), ldy, y_(i + 1, i), tauq + i, (int)fat_chunks(mi),
+                        x_(i + 1, 0), ldx, a_(i + 1, 0), lda, a_(i + 1, i), 1, i + 1 < nb ? 1 : 0);
+            KMV_BD_CHECK();
+        }
+        return KMV_OK;
+    }
+    rows_update(0, 0, 0, 0, nullc, 0, 0, 1);
+    KMV_BD_CHECK();
+    for (int64_t i = 0; i < nb; ++i) {
+        const int64_t mi = m - i, ni = n - i - 1;
+        const int k = (int)i;
+        reflect(mi, k, a_(i, 0), lda, k, x_(i, 0), ldx, a_(i, i), d + i, tauq + i, nullm);
+        KMV_BD_CHECK();
+        if (ni <= 0) {     // last column of the matrix: no row reflector
+            hipLaunchKernelGGL((no_reflector_kernel<R, T>), dim3(1), dim3(1), 0, s, e + i, taup + i);
+            KMV_BD_CHECK();
+            continue;
+        }
+        rc = Calls<T>::gemv(TR, mi, ni, &one, a_(i, i + 1), lda, a_(i, i), (int64_t)1, &zero, y_(i + 1, i), (int64_t)1, ws, wsb, stream);
+        if (rc) return rc;
+        // y_i = tauq (y - Y (V^H v) - U (X^H v)); row i right of the diagonal catches up, y_i taking part
+        cols_update(i + 1, i, k, y_(i + 1, 0), ldy, k, u_(i + 1, 0), ldu, y_(i + 1, i), tauq + i, (int)fat_chunks(mi), a_(i, 0), lda,
+                    x_(i, 0), ldx, a_(i, i), 1, 1);
+        KMV_BD_CHECK();
+        reflect(ni, k + 1, y_(i + 1, 0), ldy, k, u_(i + 1, 0), ldu, u_(i + 1, i), e + i, taup + i, a_(i, i + 1));
+        KMV_BD_CHECK();
+        rc = Calls<T>::gemv('N', mi - 1, ni, &one, a_(i + 1, i + 1), lda, u_(i + 1, i), (int64_t)1, &zero, x_(i + 1, i), (int64_t)1, ws,
+                            wsb, stream);
+        if (rc) return rc;
+        // x_i = taup (x - V (Y^H u) - X (U^H u)); column i+1 catches up, x_i taking part
+        rows_update(i + 1, i + 1, k + 1, k, taup + i, (int)fat_chunks(ni), 1, i + 1 < nb ? 1 : 0);
+        KMV_BD_CHECK();
+    }
+#undef KMV_BD_CHECK
+    return KMV_OK;
+}
+
 // Panel step of the bidiagonal reduction (m >= n: upper bidiagonal; m < n: lower bidiagonal, see the branch
-// below): the published "labrd" step written
-// from its definition on top of the GEMV entry points.  Per column two products with the whole trailing
+// below): the published "labrd" step written from its definition.  Argument checks, then the fused step above
+// for panels of at most BD_NB columns; beyond that the step on top of the GEMV entry points that follows,
+// which is also the plain statement of what the fused kernels compute.  Per column two products with the whole trailing
 // block (transposed from the left, plain from the right, the latter with a strided x: a row of A) and
 // eleven with the tall or wide panels of vectors accumulated so far, two reflectors and two scalings by
 // tau; everything on the device and on the caller's stream.  The row that becomes u_i is worked on in a
@@ -700,6 +1019,7 @@ int gebrd_panel(int64_t m, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
     if (m == 0 || n == 0 || nb == 0) return KMV_OK;
     if (!A || !d || !e || !tauq || !taup || !X || !Y) return KMV_ERR_NULL;
     if (!ws || wsb < gebrd_workspace<T>(m, n, nb) || ((uintptr_t)ws % 256) != 0) return KMV_ERR_WORKSPACE;
+    if (nb <= BD_NB) return gebrd_panel_fused<T>(m, n, nb, A, lda, d, e, tauq, taup, X, ldx, Y, ldy, ws, wsb, stream);
     T* urow = static_cast<T*>(ws);            // row i right of the diagonal, contiguous
     ws = static_cast<char*>(ws) + row_bytes<T>(n);
     wsb -= row_bytes<T>(n);

@@ -191,7 +191,7 @@ from oracle import gebrd_panel_oracle as go   # noqa: E402
 @pytest.mark.parametrize("prec", "sd")
 @pytest.mark.parametrize("m,n,nb,pad,off", [(1, 1, 1, 0, 0), (2, 2, 2, 0, 0), (5, 3, 3, 1, 0), (100, 100, 16, 0, 0),
                                             (700, 500, 32, 36, 0), (1500, 1500, 64, 0, 0), (1300, 900, 24, 52, 17),
-                                            (900, 1500 - 700, 8, 3, 1)])
+                                            (900, 1500 - 700, 8, 3, 1), (900, 700, 260, 4, 0)])
 def test_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     """kmv_{s,d}gebrd_panel on a block at (off, off) of a parent with padded leading dimension: reflector
     vectors, d, e, tauq, taup, X and Y element by element; everything outside the first nb rows and columns
@@ -244,10 +244,54 @@ def test_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     assert np.all(np.isnan(X.cpu().numpy()[:, m:])) and np.all(np.isnan(Y.cpu().numpy()[:, n:]))
 
 
+@pytest.mark.parametrize("prec,m,n", [("d", 900, 700), ("c", 500, 800)])
+def test_gebrd_panel_is_deterministic_and_capturable(prec, m, n):
+    """the bidiagonal panel (fused kernels plus the two products per column) is launches only: captured in a
+    graph and replayed on restored inputs, every replay reproduces the eager result bit for bit"""
+    k = kmv()
+    nb = 32
+    dt = wl.TORCH_DTYPES[prec]
+    rdt = {"d": torch.float64, "c": torch.float32}[prec]
+    A0 = wl.matrix(prec, m, n, m, seed=5, device=DEV)
+    A = A0.clone()
+    X = torch.zeros((nb, m), dtype=dt, device=DEV)
+    Y = torch.zeros((nb, n), dtype=dt, device=DEV)
+    d, e = (torch.zeros(nb, dtype=rdt, device=DEV) for _ in range(2))
+    tauq, taup = (torch.zeros(nb, dtype=dt, device=DEV) for _ in range(2))
+    ws = k.workspace(k.gebrd_panel_workspace_bytes(prec, m, n, nb))
+    k.GEBRD_PANEL[prec](m, n, nb, A, m, d, e, tauq, taup, X, m, Y, n, workspace=ws)
+    torch.cuda.synchronize()
+    outs = (A, d, e, tauq, taup)
+    ref = [t.clone() for t in outs]
+    refX, refY = X.clone(), Y.clone()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    A.copy_(A0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            k.GEBRD_PANEL[prec](m, n, nb, A, m, d, e, tauq, taup, X, m, Y, n, workspace=ws, stream=side)
+    cols = torch.arange(nb, device=DEV).unsqueeze(1)
+    for _ in range(3):
+        A.copy_(A0)
+        for t in (d, e, tauq, taup, X, Y):
+            t.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs, ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+        for got, want, rows in ((X, refX, m), (Y, refY, n)):
+            defined = torch.arange(rows, device=DEV).unsqueeze(0) > cols
+            assert torch.equal(torch.view_as_real(got[defined]) if got.is_complex() else got[defined],
+                               torch.view_as_real(want[defined]) if want.is_complex() else want[defined])
+
+
 @pytest.mark.parametrize("prec", "cz")
 @pytest.mark.parametrize("m,n,nb,pad,off", [(1, 1, 1, 0, 0), (2, 2, 2, 0, 0), (5, 3, 3, 1, 0), (100, 100, 16, 0, 0),
                                             (700, 500, 32, 36, 0), (1500, 1500, 64, 0, 0), (1300, 900, 24, 52, 17),
-                                            (900, 800, 8, 3, 1)])
+                                            (900, 800, 8, 3, 1), (600, 500, 260, 4, 0)])
 def test_complex_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     """kmv_{c,z}gebrd_panel: reflector vectors (rows stored as u^H), the real d and e, the complex tauq and
     taup, X and Y element by element; everything outside the first nb rows and columns bit-unchanged"""
@@ -375,7 +419,8 @@ def test_upper_storage_panel_against_oracle(prec, n, nb, pad, off):
 
 @pytest.mark.parametrize("prec", "sdcz")
 @pytest.mark.parametrize("m,n,nb,pad,off", [(1, 2, 1, 0, 0), (2, 3, 2, 0, 0), (3, 5, 3, 1, 0), (100, 101, 16, 0, 0),
-                                            (500, 700, 32, 36, 0), (900, 1300, 24, 52, 17), (800, 900, 8, 3, 1)])
+                                            (500, 700, 32, 36, 0), (900, 1300, 24, 52, 17), (800, 900, 8, 3, 1),
+                                            (500, 700, 260, 4, 0)])
 def test_wide_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     """m < n: lower bidiagonal form (row reflectors first).  Reflector vectors, the real d and e, tauq, taup, X
     and Y element by element; everything outside the first nb rows and columns bit-unchanged"""
