@@ -903,7 +903,9 @@ template <class T> constexpr int64_t small_n() { return sizeof(T) == 4 ? 2176 : 
 // and more resident workgroups only lengthen the queues in front of the memory channels: DSYMV 16384
 // 164 us against 176-178 us with two or three per compute unit), two below; chunks of 8 row tiles pay for
 // real 8-byte elements from about n = 17400 (1-2%; not at 16384: -4%), for complex 8-byte elements from about 9000
-// (2-5%), for 16-byte elements from about n = 8400 (10% at 24576) - the complex types spend more on the column
+// (2-5%; except where the column stride is a multiple of 32 KB, n = 12288 and 16384 with lda = n: there 8-tile chunks
+// are 2-3% SLOWER than 4-tile ones and 12-tile chunks as fast or faster, while 11264, 13312, 15360 gain 1.5-4% from 8
+// tiles and lose with 12 - the plan takes 12 tiles for such strides below 18432), for 16-byte elements from about n = 8400 (10% at 24576) - the complex types spend more on the column
 // sums of a piece, which a taller piece amortises; 12 tiles
 // (what 64 KB of static LDS hold) add 1-2.5% for 16-byte elements from about 10000, and 16 tiles (80 KB of dynamic
 // LDS) another 0.7-4% from 16384 (ZHEMV 32768: 1314 -> 1271 us) and 1.7% for 8-byte elements at 40960; 4 tiles
@@ -1110,7 +1112,10 @@ template <class T> SymvPlan<T> plan_symv(bool lower, int64_t n, const void* A, i
     if (p.variant == 2 && n < 4 * Traits<T>::VEC) p.variant = 3;
     // chunk height in units of 4 row tiles
     int64_t ktw = tn.symv_tiles_per_wave;
-    if (ktw <= 0) ktw = default_tiles_per_wave<T>(n);
+    if (ktw <= 0) {
+        ktw = default_tiles_per_wave<T>(n);
+        if (Traits<T>::cplx && sizeof(T) == 8 && ktw == 2 && n < 18432 && (lda * (int64_t)sizeof(T)) % 32768 == 0) ktw = 3;
+    }
     // the balanced kernel's tables hold SHARE_MAX_CHUNKS chunks (enough for every matrix that fits the device's
     // memory when the chunks are 8 to 16 tiles high)
     while (ktw < 4 && ceil_div(p.ntiles, SY_NW * ktw) > SHARE_MAX_CHUNKS) ++ktw;
