@@ -190,6 +190,10 @@ constexpr int DT = 1024;       // reflector kernel: threads,
 constexpr int DR = 256;        //   rows per pass,
 constexpr int DG_MAX = 64;     //   most workgroups
 constexpr int NB_MAX = 1024;
+// reflector kernels: panel columns a wave works on at a time (16 waves per workgroup leave 128 registers per lane: two
+// columns for 16-byte elements, four otherwise),
+template <class T> constexpr int rc_of() { return sizeof(T) == 16 ? 2 : 4; }
+constexpr int RQ = DR / WAVE; //   rows per lane in the first DR rows of a chunk (what is fetched ahead)
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t thin_rows(int64_t m) { return FR * ceil_div(m > 0 ? m : 1, (int64_t)FR * FG_MAX); }
 inline unsigned thin_chunks(int64_t m) { return (unsigned)ceil_div(m > 0 ? m : 1, thin_rows(m)); }
@@ -230,6 +234,49 @@ template <int NT, class T> __device__ __forceinline__ T group_sum(T v, T* red) {
     return tot;
 }
 
+// s1[0 .. kp), s2[0 .. kk - kp) <- the column sums of the gd partial rows of `dots` (kk entries each), for a workgroup
+// of FT threads: wave w adds the rows g = w, w + 4, ... of 64 columns at a time (all its loads in flight at once), the
+// four waves' sums are added in wave order through tmp - a fixed order, whatever the scheduling.
+template <class T>
+__device__ __forceinline__ void sum_partial_rows(const T* __restrict__ dots, int gd, int kk, int kp, T* s1, T* s2, T (*tmp)[FR]) {
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    for (int jb = 0; jb < kk; jb += WAVE) {
+        const int j = jb + lane;
+        T s = zero_of<T>();
+        if (j < kk) {
+#pragma unroll 16
+            for (int g = wv; g < gd; g += FT / WAVE) s = add_of(s, dots[(int64_t)g * kk + j]);
+        }
+        tmp[wv][lane] = s;
+        __syncthreads();
+        if (wv == 0 && j < kk) {
+            T tot = tmp[0][lane];
+#pragma unroll
+            for (int q = 1; q < FT / WAVE; ++q) tot = add_of(tot, tmp[q][lane]);
+            if (j < kp) s1[j] = tot;
+            else s2[j - kp] = tot;
+        }
+        __syncthreads();
+    }
+}
+
+// The update kernel of the bidiagonal panel starts with a prologue (sums of partials, coefficients, barriers) that
+// the panel entries themselves do not depend on, and a barrier keeps the compiler from moving loads across it: so the
+// first PF columns a wave takes of each panel are fetched by hand before the prologue, for the lane's row of the
+// workgroup's first pass (its only one up to 16384 rows), and used in the same order as the loop would have used
+// them (10.8 -> 8.9 us per launch at 16384 rows, nb = 64).  The same in the correct and column kernels of the
+// tridiagonal panel, which follow the symmetric product's final pass, measured slower (6.1 -> 10.2 us) and is not done.
+constexpr int PF = 16;
+template <class T>
+__device__ __forceinline__ void fetch_ahead(T (&pre)[PF], const T* __restrict__ P, int64_t ld, int k, int64_t r, bool in) {
+    const int wv = threadIdx.x / WAVE;
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+        const int j = wv + u * (FT / WAVE);
+        pre[u] = in && j < k ? P[r + j * ld] : zero_of<T>();
+    }
+}
+
 template <class T, bool HEAD_FIRST>
 __global__ __launch_bounds__(FT) void panel_column_kernel(int64_t m, int64_t rpw, int k, const T* __restrict__ Vp, int64_t ldv,
                                                           const T* __restrict__ Wp, int64_t ldw, const T* __restrict__ v, T* w,
@@ -243,6 +290,8 @@ __global__ __launch_bounds__(FT) void panel_column_kernel(int64_t m, int64_t rpw
     const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
     const int64_t rd = HEAD_FIRST ? 0 : m - 1, ra = HEAD_FIRST ? 1 : m - 2;
     const bool update = finalize && has_next;
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
     T c = zero_of<T>();
     if (finalize) {
         T d = zero_of<T>();
@@ -263,8 +312,6 @@ __global__ __launch_bounds__(FT) void panel_column_kernel(int64_t m, int64_t rpw
         }
     }
     R nrm = 0;
-    const int64_t r0 = (int64_t)blockIdx.x * rpw;
-    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
     for (int64_t rb = r0; rb < r1; rb += FR) {
         const int64_t r = rb + lane;
         const bool in = r < r1;
@@ -323,8 +370,26 @@ __global__ __launch_bounds__(DT) void panel_reflector_kernel(int64_t m, int64_t 
                                                              const typename Traits<T>::real* normpart, int gn, const T* alpha_in,
                                                              typename Traits<T>::real* e, T* tau, T* dots) {
     using R = typename Traits<T>::real;
+    constexpr int RC = rc_of<T>();
     __shared__ R red[DT / WAVE];
+    __shared__ T xs[DT];       // the finished vector, first DT rows of the chunk (all of it up to 65536 rows)
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
     const int64_t rd = HEAD_FIRST ? 0 : m - 1, ra = HEAD_FIRST ? 1 : m - 2;
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
+    // the panel entries of the wave's first group of columns do not depend on the norm: fetched ahead of it
+    T pw[RC / 2][RQ], pv[RC / 2][RQ];
+#pragma unroll
+    for (int c = 0; c < RC / 2; ++c) {
+        const int j = wv + c * (DT / WAVE);
+#pragma unroll
+        for (int q = 0; q < RQ; ++q) {
+            const int64_t r = r0 + lane + q * WAVE;
+            const bool in = j < kp && r < r1;
+            pw[c][q] = in ? Wp[r + j * ldw] : zero_of<T>();
+            pv[c][q] = in ? Vp[r + j * ldv] : zero_of<T>();
+        }
+    }
     R x2 = 0;
     for (int g = threadIdx.x; g < gn; g += DT) x2 += normpart[g];
     const R xn2 = group_sum<DT>(x2, red);
@@ -346,12 +411,19 @@ __global__ __launch_bounds__(DT) void panel_reflector_kernel(int64_t m, int64_t 
             scale = R(1) / dr;
         }
     }
-    const int64_t r0 = (int64_t)blockIdx.x * rpw;
-    const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
     for (int64_t r = r0 + threadIdx.x; r < r1; r += DT) {
-        if (r == rd) continue;
-        if (r == ra) a[r] = from_one<T>();
-        else if (have) a[r] = mul_of(a[r], scale);
+        T x = zero_of<T>();          // the diagonal row is not part of v
+        if (r == ra) {
+            x = from_one<T>();
+            a[r] = x;
+        } else if (r != rd) {
+            x = a[r];
+            if (have) {
+                x = mul_of(x, scale);
+                a[r] = x;
+            }
+        }
+        if (r - r0 < DT) xs[r - r0] = x;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *e = beta;
@@ -359,20 +431,49 @@ __global__ __launch_bounds__(DT) void panel_reflector_kernel(int64_t m, int64_t 
     }
     if (kp == 0) return;
     __syncthreads();     // the chunk of v is in place for all waves of the workgroup
-    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
-    for (int j = wv; j < kp; j += DT / WAVE) {
-        T aw = zero_of<T>(), av = zero_of<T>();
-#pragma unroll 4
-        for (int64_t r = r0 + lane; r < r1; r += WAVE) {
-            const T x = r == rd ? zero_of<T>() : a[r];
-            fma_acc_conj(aw, Wp[r + j * ldw], x);
-            fma_acc_conj(av, Vp[r + j * ldv], x);
+    // a wave takes RC / 2 columns of each panel at a time, so that their loads are in flight together (a column past
+    // the end repeats the wave's first one and is not stored)
+    for (int jb = wv; jb < kp; jb += (RC / 2) * (DT / WAVE)) {
+        const T *cw[RC / 2], *cv[RC / 2];
+        T aw[RC / 2], av[RC / 2];
+#pragma unroll
+        for (int c = 0; c < RC / 2; ++c) {
+            const int j = jb + c * (DT / WAVE) < kp ? jb + c * (DT / WAVE) : jb;
+            cw[c] = Wp + j * ldw;
+            cv[c] = Vp + j * ldv;
+            aw[c] = av[c] = zero_of<T>();
         }
-        aw = wave_sum(aw);
-        av = wave_sum(av);
-        if (lane == 0) {
-            dots[(int64_t)blockIdx.x * 2 * kp + j] = aw;
-            dots[(int64_t)blockIdx.x * 2 * kp + kp + j] = av;
+        int64_t r = r0 + lane;
+        if (jb == wv) {      // the group fetched ahead
+#pragma unroll
+            for (int q = 0; q < RQ; ++q, r += WAVE) {
+                if (r < r1) {
+                    const T x = xs[r - r0];
+#pragma unroll
+                    for (int c = 0; c < RC / 2; ++c) {
+                        fma_acc_conj(aw[c], pw[c][q], x);
+                        fma_acc_conj(av[c], pv[c][q], x);
+                    }
+                }
+            }
+        }
+#pragma unroll 4
+        for (; r < r1; r += WAVE) {
+            const T x = r - r0 < DT ? xs[r - r0] : (r == rd ? zero_of<T>() : a[r]);
+#pragma unroll
+            for (int c = 0; c < RC / 2; ++c) {
+                fma_acc_conj(aw[c], cw[c][r], x);
+                fma_acc_conj(av[c], cv[c][r], x);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < RC / 2; ++c) {
+            const T sw = wave_sum(aw[c]), sv = wave_sum(av[c]);
+            const int j = jb + c * (DT / WAVE);
+            if (lane == 0 && j < kp) {
+                dots[(int64_t)blockIdx.x * 2 * kp + j] = sw;
+                dots[(int64_t)blockIdx.x * 2 * kp + kp + j] = sv;
+            }
         }
     }
 }
@@ -388,18 +489,11 @@ __global__ __launch_bounds__(FT) void panel_correct_kernel(int64_t m, int64_t rp
     __shared__ T s1[NB_MAX], s2[NB_MAX];
     __shared__ T part[FT / WAVE][FR];
     const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
-    for (int j = threadIdx.x; j < 2 * k; j += FT) {
-        T s = zero_of<T>();
-#pragma unroll 8
-        for (int g = 0; g < gd; ++g) s = add_of(s, dots[(int64_t)g * 2 * k + j]);
-        if (j < k) s1[j] = s;
-        else s2[j - k] = s;
-    }
-    __syncthreads();
-    const T t = *tau;
-    T dot = zero_of<T>();
     const int64_t r0 = (int64_t)blockIdx.x * rpw;
     const int64_t r1 = r0 + rpw < m ? r0 + rpw : m;
+    sum_partial_rows(dots, gd, 2 * k, k, s1, s2, part);
+    const T t = *tau;
+    T dot = zero_of<T>();
     for (int64_t rb = r0; rb < r1; rb += FR) {
         const int64_t r = rb + lane;
         const bool in = r < r1;
@@ -482,15 +576,13 @@ __global__ __launch_bounds__(FT) void bd_update_kernel(int64_t len, int64_t rpw,
     __shared__ T czs;
     const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
     const bool update = fin && has_next;
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < len ? r0 + rpw : len;
+    T pp[PF], pq[PF];
+    fetch_ahead(pp, P, ldp, kp, r0 + lane, fin && r0 + lane < r1);
+    fetch_ahead(pq, Q, ldq, kq, r0 + lane, fin && r0 + lane < r1);
     if (fin) {
-        const int kk = kp + kq;
-        for (int j = threadIdx.x; j < kk; j += FT) {
-            T s = zero_of<T>();
-#pragma unroll 8
-            for (int g = 0; g < gd; ++g) s = add_of(s, dots[(int64_t)g * kk + j]);
-            if (j < kp) s1[j] = s;
-            else s2[j - kp] = s;
-        }
+        sum_partial_rows(dots, gd, kp + kq, kp, s1, s2, partf);
         if (has_next) {
             for (int j = threadIdx.x; j < kp; j += FT) c1[j] = conj_of(c1src[j * c1inc]);
             for (int j = threadIdx.x; j < kq; j += FT) c2[j] = conj2 ? conj_of(c2src[j * c2inc]) : c2src[j * c2inc];
@@ -501,22 +593,40 @@ __global__ __launch_bounds__(FT) void bd_update_kernel(int64_t len, int64_t rpw,
     const T t = fin ? *tau : zero_of<T>();
     const T cz = update ? czs : zero_of<T>();
     R nrm = 0;
-    const int64_t r0 = (int64_t)blockIdx.x * rpw;
-    const int64_t r1 = r0 + rpw < len ? r0 + rpw : len;
     for (int64_t rb = r0; rb < r1; rb += FR) {
         const int64_t r = rb + lane;
         const bool in = r < r1;
         if (fin) {
             T sf = zero_of<T>(), su = zero_of<T>();
             if (in) {
-#pragma unroll 8
-                for (int j = wv; j < kp; j += FT / WAVE) {
+                int j0 = wv;
+                if (rb == r0) {
+#pragma unroll
+                    for (int u = 0; u < PF; ++u) {
+                        const int j = wv + u * (FT / WAVE);
+                        if (j < kp) {
+                            fma_acc(sf, pp[u], s1[j]);
+                            if (update) fma_acc(su, pp[u], c1[j]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < PF; ++u) {
+                        const int j = wv + u * (FT / WAVE);
+                        if (j < kq) {
+                            fma_acc(sf, pq[u], s2[j]);
+                            if (update) fma_acc(su, pq[u], c2[j]);
+                        }
+                    }
+                    j0 = wv + PF * (FT / WAVE);
+                }
+#pragma unroll 16
+                for (int j = j0; j < kp; j += FT / WAVE) {
                     const T p = P[r + j * ldp];
                     fma_acc(sf, p, s1[j]);
                     if (update) fma_acc(su, p, c1[j]);
                 }
-#pragma unroll 8
-                for (int j = wv; j < kq; j += FT / WAVE) {
+#pragma unroll 16
+                for (int j = j0; j < kq; j += FT / WAVE) {
                     const T q = Q[r + j * ldq];
                     fma_acc(sf, q, s2[j]);
                     if (update) fma_acc(su, q, c2[j]);
@@ -569,7 +679,25 @@ __global__ __launch_bounds__(DT) void bd_reflector_kernel(int64_t len, int64_t r
                                                           const typename Traits<T>::real* normpart, int gn, const T* alpha_in,
                                                           typename Traits<T>::real* e, T* tau, T* scat, int64_t scinc, T* dots) {
     using R = typename Traits<T>::real;
+    constexpr int RC = rc_of<T>();
     __shared__ R red[DT / WAVE];
+    __shared__ T xs[DT];       // the finished vector, first DT rows of the chunk (all of it up to 65536 rows)
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    const int kk = kp + kq;
+    const int64_t r0 = (int64_t)blockIdx.x * rpw;
+    const int64_t r1 = r0 + rpw < len ? r0 + rpw : len;
+    // the panel entries of the wave's first group of columns do not depend on the norm: fetched ahead of it
+    T pc[RC][RQ];
+#pragma unroll
+    for (int c = 0; c < RC; ++c) {
+        const int j = wv + c * (DT / WAVE), jc = j < kk ? j : 0;
+        const T* col = jc < kp ? P + jc * ldp : Q + (jc - kp) * ldq;
+#pragma unroll
+        for (int q = 0; q < RQ; ++q) {
+            const int64_t r = r0 + lane + q * WAVE;
+            pc[c][q] = j < kk && r < r1 ? col[r] : zero_of<T>();
+        }
+    }
     R x2 = 0;
     for (int g = threadIdx.x; g < gn; g += DT) x2 += normpart[g];
     const R xn2 = group_sum<DT>(x2, red);
@@ -591,8 +719,6 @@ __global__ __launch_bounds__(DT) void bd_reflector_kernel(int64_t len, int64_t r
             scale = R(1) / dr;
         }
     }
-    const int64_t r0 = (int64_t)blockIdx.x * rpw;
-    const int64_t r1 = r0 + rpw < len ? r0 + rpw : len;
     for (int64_t r = r0 + threadIdx.x; r < r1; r += DT) {
         T x = from_one<T>();
         if (r != 0) {
@@ -601,22 +727,48 @@ __global__ __launch_bounds__(DT) void bd_reflector_kernel(int64_t len, int64_t r
         }
         a[r] = x;
         if (scat) scat[r * scinc] = conj_of(x);
+        if (r - r0 < DT) xs[r - r0] = x;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *e = beta;
         *tau = t;
     }
-    const int kk = kp + kq;
     if (kk == 0) return;
     __syncthreads();     // the chunk of the vector is in place for all waves of the workgroup
-    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
-    for (int j = wv; j < kk; j += DT / WAVE) {
-        const T* col = j < kp ? P + j * ldp : Q + (j - kp) * ldq;
-        T acc = zero_of<T>();
+    // a wave takes RC columns at a time, so that their loads are in flight together (a column past the end repeats
+    // the wave's first one and is not stored)
+    for (int jb = wv; jb < kk; jb += RC * (DT / WAVE)) {
+        const T* col[RC];
+        T acc[RC];
+#pragma unroll
+        for (int c = 0; c < RC; ++c) {
+            const int j = jb + c * (DT / WAVE) < kk ? jb + c * (DT / WAVE) : jb;
+            col[c] = j < kp ? P + j * ldp : Q + (j - kp) * ldq;
+            acc[c] = zero_of<T>();
+        }
+        int64_t r = r0 + lane;
+        if (jb == wv) {      // the group fetched ahead
+#pragma unroll
+            for (int q = 0; q < RQ; ++q, r += WAVE) {
+                if (r < r1) {
+                    const T x = xs[r - r0];
+#pragma unroll
+                    for (int c = 0; c < RC; ++c) fma_acc_conj(acc[c], pc[c][q], x);
+                }
+            }
+        }
 #pragma unroll 4
-        for (int64_t r = r0 + lane; r < r1; r += WAVE) fma_acc_conj(acc, col[r], a[r]);
-        acc = wave_sum(acc);
-        if (lane == 0) dots[(int64_t)blockIdx.x * kk + j] = acc;
+        for (; r < r1; r += WAVE) {
+            const T x = r - r0 < DT ? xs[r - r0] : a[r];
+#pragma unroll
+            for (int c = 0; c < RC; ++c) fma_acc_conj(acc[c], col[c][r], x);
+        }
+#pragma unroll
+        for (int c = 0; c < RC; ++c) {
+            const T sum = wave_sum(acc[c]);
+            const int j = jb + c * (DT / WAVE);
+            if (lane == 0 && j < kk) dots[(int64_t)blockIdx.x * kk + j] = sum;
+        }
     }
 }
 
