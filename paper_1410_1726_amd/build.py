@@ -8,6 +8,7 @@ installed.  The library is written next to this file.
 from __future__ import annotations
 
 import os
+import re
 import shutil
 import subprocess
 import sys
@@ -26,7 +27,10 @@ HIPCC_FLAGS = [
     # compiler from forming them
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
+    # per-kernel register, LDS and scratch figures as compiler remarks: collected into RESOURCES below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+RESOURCES = os.path.join(BUILD, "resource_usage.txt")     # one line per kernel: name vgprs lds_bytes scratch_bytes_per_lane
 
 
 def _hipcc() -> str:
@@ -34,6 +38,25 @@ def _hipcc() -> str:
         if cand and os.path.exists(cand):
             return cand
     raise RuntimeError("hipcc not found: the kmv library needs the ROCm toolchain")
+
+
+def _kernel_resources(remarks: str) -> dict:
+    """{mangled kernel name: (VGPRs, LDS bytes per workgroup, scratch bytes per lane)} from the compiler's
+    kernel-resource-usage remarks.  Scratch above zero means the kernel spills registers to memory: none of the
+    library's kernels does, and tests/test_abi.py keeps it that way."""
+    out, name, cur = {}, None, {}
+    for ln in remarks.splitlines():
+        m = re.search(r"remark: (?:.*: )?Function Name: (\S+)", ln)
+        if m:
+            name, cur = m.group(1), {}
+            continue
+        m = re.search(r"remark: (?:.*: )?\s*(VGPRs|LDS Size \[bytes/block\]|ScratchSize \[bytes/lane\]): (\d+)", ln)
+        if m and name:
+            cur[m.group(1)] = int(m.group(2))
+            if len(cur) == 3:
+                out[name] = (cur["VGPRs"], cur["LDS Size [bytes/block]"], cur["ScratchSize [bytes/lane]"])
+                name = None
+    return out
 
 
 def build_library(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
@@ -49,18 +72,26 @@ def build_library(verbose: bool = False, extra_flags=(), out: str | None = None)
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
-        if verbose and r.stderr.strip():
-            print(r.stderr, file=sys.stderr)
-        return obj
+        other = [ln for ln in r.stderr.splitlines() if "remark:" not in ln and "-Rpass-analysis" not in ln]
+        if verbose and any(ln.strip() for ln in other):
+            print("\n".join(other), file=sys.stderr)
+        return obj, _kernel_resources(r.stderr)
 
     with ThreadPoolExecutor(max_workers=6) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
+        done = list(ex.map(compile_one, SOURCES))
+    objs = [d[0] for d in done]
     tmp = out + ".tmp"
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     os.replace(tmp, out)
+    if out == LIB:      # the report describes the default library
+        with open(RESOURCES + ".tmp", "w") as f:
+            for _, kernels in done:
+                for name, (vgprs, lds, scratch) in sorted(kernels.items()):
+                    f.write(f"{name} {vgprs} {lds} {scratch}\n")
+        os.replace(RESOURCES + ".tmp", RESOURCES)
     return out
 
 

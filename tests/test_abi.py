@@ -384,3 +384,20 @@ def test_tuning_tool_writes_rows(tmp_path):
     path = tune.write_rows(rows, str(tmp_path / "table.inc"))
     text = open(path).read()
     assert text.startswith("// Written by") and "{'N', 's', 4032, 4161, 0, 2, 0, 0, 0, 0, 0}" in text
+
+
+def test_no_kernel_spills_registers():
+    """the build collects the compiler's per-kernel resource figures; no kernel of the library may use scratch
+    memory (register spills: a spilling kernel still computes correctly, only several times slower), and the
+    report must cover the kernels of every source file"""
+    from paper_1410_1726_amd import build
+    if not os.path.exists(build.RESOURCES) or os.path.getmtime(build.RESOURCES) + 2 < os.path.getmtime(kmv.LIB_PATH):
+        pytest.skip("no resource report for this library (built without paper_1410_1726_amd.build)")
+    rows = [ln.split() for ln in open(build.RESOURCES)]
+    assert len(rows) > 500 and all(len(r) == 4 for r in rows)
+    for family in ("gemv_n_kernel", "gemv_t_kernel", "symv_balanced_kernel", "symv_reduce_kernel", "bd_update_kernel",
+                   "panel_reflector_kernel", "reduce_kernel"):
+        assert any(family in r[0] for r in rows), family
+    spilling = [(r[0], int(r[3])) for r in rows if int(r[3]) > 0]
+    assert not spilling, spilling
+    assert all(int(r[1]) <= 512 and int(r[2]) <= 160 * 1024 for r in rows)
