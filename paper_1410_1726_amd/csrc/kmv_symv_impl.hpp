@@ -908,8 +908,8 @@ template <class T> constexpr int64_t small_n() { return sizeof(T) == 4 ? 2176 : 
 // tiles and lose with 12 - the plan takes 12 tiles for such strides below 18432), for 16-byte elements from about n = 8400 (10% at 24576) - the complex types spend more on the column
 // sums of a piece, which a taller piece amortises; 12 tiles
 // (what 64 KB of static LDS hold) add 1-2.5% for 16-byte elements from about 10000, and 16 tiles (80 KB of dynamic
-// LDS) another 0.7-4% from 16384 (ZHEMV 32768: 1314 -> 1271 us) and 1.7% for 8-byte elements at 40960; 4 tiles
-// elsewhere and always for 4-byte elements.
+// LDS) another 0.7-4% from 16384 (ZHEMV 32768: 1314 -> 1271 us) and 1.7% for 8-byte elements at 40960; 4-byte elements
+// gain 1-2.7% from 8 tiles from about n = 36000 on (and lose 3-4% at 32768); 4 tiles elsewhere.
 template <class T> inline int default_unit_tiles(int64_t) { return 1; }
 inline int wgs_per_cu(int kt) { return kt == 1 ? 3 : 2; }   // the most the kernel instances are built for
 template <class T> inline int default_wgs_per_cu(int64_t n) {
@@ -917,7 +917,7 @@ template <class T> inline int default_wgs_per_cu(int64_t n) {
     return bytes >= (sizeof(T) == 16 ? 600e6 : 200e6) ? 1 : 2;
 }
 template <class T> inline int64_t default_tiles_per_wave(int64_t n) {
-    if (sizeof(T) == 4) return 1;
+    if (sizeof(T) == 4) return n >= 36864 ? 2 : 1;
     if (sizeof(T) == 16) return n >= 16384 ? 4 : (n >= 10240 ? 3 : (n >= 8448 ? 2 : 1));
     return n >= 36864 ? 4 : (n >= (Traits<T>::cplx ? 9216 : 17408) ? 2 : 1);
 }
