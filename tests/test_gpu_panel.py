@@ -46,6 +46,16 @@ def host_matrix(parent, off, n):
 @pytest.mark.parametrize("n,nb,pad,off", [(1, 1, 0, 0), (2, 2, 0, 0), (3, 1, 1, 0), (100, 16, 0, 0), (700, 32, 36, 0),
                                           (1500, 64, 0, 0), (1100, 24, 52, 17), (300, 300, 4, 1)])
 def test_panel_against_oracle(prec, n, nb, pad, off):
+    check_panel(prec, n, nb, pad, off)
+
+
+def test_panel_with_many_rows():
+    """more than 16384 rows: the panel's own kernels take several passes per workgroup, and the reflector kernel
+    more rows than it fetches ahead"""
+    check_panel("s", 20000, 3, 0, 0)
+
+
+def check_panel(prec, n, nb, pad, off):
     lda, ldw = n + off + pad, n + (pad // 2)
     parent, before, W, e, tau = run_panel(prec, n, nb, lda, ldw, off, seed=n + nb)
     A0 = host_matrix(before, off, n)
@@ -191,7 +201,8 @@ from oracle import gebrd_panel_oracle as go   # noqa: E402
 @pytest.mark.parametrize("prec", "sd")
 @pytest.mark.parametrize("m,n,nb,pad,off", [(1, 1, 1, 0, 0), (2, 2, 2, 0, 0), (5, 3, 3, 1, 0), (100, 100, 16, 0, 0),
                                             (700, 500, 32, 36, 0), (1500, 1500, 64, 0, 0), (1300, 900, 24, 52, 17),
-                                            (900, 1500 - 700, 8, 3, 1), (900, 700, 260, 4, 0)])
+                                            (900, 1500 - 700, 8, 3, 1), (900, 700, 260, 4, 0), (700, 520, 200, 4, 0),
+                                            (70000, 40, 8, 0, 0)])
 def test_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     """kmv_{s,d}gebrd_panel on a block at (off, off) of a parent with padded leading dimension: reflector
     vectors, d, e, tauq, taup, X and Y element by element; everything outside the first nb rows and columns
@@ -291,7 +302,8 @@ def test_gebrd_panel_is_deterministic_and_capturable(prec, m, n):
 @pytest.mark.parametrize("prec", "cz")
 @pytest.mark.parametrize("m,n,nb,pad,off", [(1, 1, 1, 0, 0), (2, 2, 2, 0, 0), (5, 3, 3, 1, 0), (100, 100, 16, 0, 0),
                                             (700, 500, 32, 36, 0), (1500, 1500, 64, 0, 0), (1300, 900, 24, 52, 17),
-                                            (900, 800, 8, 3, 1), (600, 500, 260, 4, 0)])
+                                            (900, 800, 8, 3, 1), (600, 500, 260, 4, 0), (600, 420, 200, 4, 0),
+                                            (70000, 40, 8, 0, 0)])
 def test_complex_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     """kmv_{c,z}gebrd_panel: reflector vectors (rows stored as u^H), the real d and e, the complex tauq and
     taup, X and Y element by element; everything outside the first nb rows and columns bit-unchanged"""
@@ -420,7 +432,7 @@ def test_upper_storage_panel_against_oracle(prec, n, nb, pad, off):
 @pytest.mark.parametrize("prec", "sdcz")
 @pytest.mark.parametrize("m,n,nb,pad,off", [(1, 2, 1, 0, 0), (2, 3, 2, 0, 0), (3, 5, 3, 1, 0), (100, 101, 16, 0, 0),
                                             (500, 700, 32, 36, 0), (900, 1300, 24, 52, 17), (800, 900, 8, 3, 1),
-                                            (500, 700, 260, 4, 0)])
+                                            (500, 700, 260, 4, 0), (420, 600, 256, 4, 0), (40, 70000, 8, 0, 0)])
 def test_wide_gebrd_panel_against_oracle(prec, m, n, nb, pad, off):
     """m < n: lower bidiagonal form (row reflectors first).  Reflector vectors, the real d and e, tauq, taup, X
     and Y element by element; everything outside the first nb rows and columns bit-unchanged"""
