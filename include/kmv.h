@@ -464,6 +464,9 @@ int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c,
  * automatically.  Process-wide; not thread safe against concurrent calls.
  *   gemv_n_splits, gemv_t_splits  column / row splits of the GEMV kernels
  *   gemv_n_row_tiles              row tiles per wave of GEMV-N (1, 2, 4)
+ *   gemv_t_wgs                    workgroups of the transposed kernel (each
+ *                                 takes every gemv_t_wgs-th group of columns;
+ *                                 0 or more than there are groups: one each)
  *   gemv_short                    kernels for matrices of a few row tiles:
  *                                 1 = never, 2 = whenever they apply
  *   gemv_align_classes            GEMV with a leading dimension that is no

@@ -415,6 +415,7 @@ const Key KEYS[] = {
     {"gemv_n_splits", &Tuning::gemv_n_splits, 0, 256},
     {"gemv_t_splits", &Tuning::gemv_t_splits, 0, 256},
     {"gemv_n_row_tiles", &Tuning::gemv_n_row_tiles, 0, 4},
+    {"gemv_t_wgs", &Tuning::gemv_t_wgs, 0, 65535},
     {"gemv_short", &Tuning::gemv_short, 0, 2},
     {"gemv_align_classes", &Tuning::gemv_align_classes, 0, 2},
     {"symv_tiles_per_wave", &Tuning::symv_tiles_per_wave, 0, 4},
@@ -656,7 +657,7 @@ int64_t kmv_get_tuning(const char* key) {
         if (strcmp(k.name, key) == 0) return tuning().*(k.field);
     return -1;
 }
-const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_short,gemv_align_classes,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows,tuned_table"; }
+const char* kmv_tuning_keys(void) { return "gemv_n_splits,gemv_t_splits,gemv_n_row_tiles,gemv_t_wgs,gemv_short,gemv_align_classes,symv_tiles_per_wave,symv_variant,symv_unit_tiles,symv_piece_fixed,symv_edge_weight,wg_target,symv_member_rows,symv_member_waves,symv_small_waves,gemv_tiny_rows,tuned_table"; }
 
 int kmv_tuned_settings(char prec, char op, int64_t n, int64_t* values) {
     if (!values || n < 0 || !strchr("sdcz", prec) || prec == 0 || !strchr("NTLU", op) || op == 0) return -1;

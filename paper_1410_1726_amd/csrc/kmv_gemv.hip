@@ -247,7 +247,9 @@ __global__ __launch_bounds__(NW * WAVE) void gemv_n_short_kernel(GemvArgs<T> a) 
 // step across the waves at the very end.
 // WCOLS (short matrices, a few row tiles only): every wave owns NC columns of its
 // own and walks all tiles of the split alone; nothing crosses waves.
-template <class T, bool CONJ, int NC, int NW_, bool WCOLS, bool PTRS = false>
+// BANDS: the instance with the banded main loop below (it costs about 90 registers per lane, which the launches with
+// little work per workgroup - row splits, small matrices - cannot spare: they keep the instance without it).
+template <class T, bool CONJ, int NC, int NW_, bool WCOLS, bool PTRS = false, bool BANDS = false>
 __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
@@ -255,18 +257,22 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / WAVE);
     const int w = WCOLS ? 0 : wv;
-    int64_t j0 = WCOLS ? ((int64_t)blockIdx.x * NW_ + wv) * NC : (int64_t)blockIdx.x * NC;
-    if (WCOLS && j0 >= a.n) return;   // a whole wave past the last column (no barrier in this form)
-    int64_t ntiles = a.plan.ntiles;
-    int shift = a.plan.shift;
     select_member<PTRS>(a, blockIdx.z);   // member of a batch (strides all zero for a single product)
     const T* __restrict__ x = a.x;
+    // A workgroup takes the column groups gx = blockIdx.x, blockIdx.x + gridDim.x, ...: one each in the usual launch,
+    // several when the planner starts fewer workgroups than there are groups.
+    const int64_t ngroups = (WCOLS || a.plan.t_groups <= 0) ? (int64_t)gridDim.x : a.plan.t_groups;
+    for (int64_t gx = blockIdx.x; gx < ngroups; gx += gridDim.x) {
+    int64_t j0 = WCOLS ? (gx * NW_ + wv) * NC : gx * NC;
+    if (WCOLS && j0 >= a.n) return;   // a whole wave past the last column (no barrier in this form, one group per workgroup)
+    int64_t ntiles = a.plan.ntiles;
+    int shift = a.plan.shift;
     // the workgroup's columns are j0, j0 + js, ...; with alignment classes (period > 1) they are columns of
     // one class, and the row tiles start on the 128-byte boundary below that class's first element
     int64_t js = 1, jlast = a.n - 1;
     if (!WCOLS && a.plan.period > 1) {
-        const int64_t P = a.plan.period, cls = (int64_t)blockIdx.x % P;
-        j0 = cls + P * ((int64_t)blockIdx.x / P) * NC;
+        const int64_t P = a.plan.period, cls = gx % P;
+        j0 = cls + P * (gx / P) * NC;
         js = P;
         jlast = cls < a.n ? cls + (a.n - 1 - cls) / P * P : 0;    // last column of the class (column 0 if it has none)
         shift = (int)((uintptr_t)(a.A + (cls < a.n ? cls : 0) * a.lda) % 128 / sizeof(T));
@@ -346,19 +352,81 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
     if (first_edge && w == 0) masked_tile(0);
     if (last_edge && w == NW - 1) masked_tile(ntiles - 1);
 
+    // Bands first: while NW * RT interior tiles are left, wave w takes RT CONSECUTIVE tiles (w * RT ... of the band)
+    // and walks the workgroup's columns CB at a time, x of its tiles in registers - every column is read in runs
+    // of NW * RT KiB instead of one tile per wave and eight columns at once.  Two register buffers of RT x CB
+    // vectors, the next block (or the next band's first, with its x) in flight while one is used.  The bands are
+    // taken in an order rotated by the column group, as the tiles below.
+    int64_t ilo_rest = ilo, ni_rest = ni;
+    if constexpr (BANDS && !WCOLS) {
+        constexpr int RT = 4, CB = 2, NBLK = NC / CB;
+        static_assert(NC % CB == 0 && NBLK % 2 == 0, "an even number of blocks per band keeps the buffers' roles fixed");
+        const int64_t band = (int64_t)NW * RT, nbands = ni / band;
+        if (nbands > 0) {
+            const int64_t brot = (gx * 37) % nbands;
+            auto band_row = [&](int64_t b) {
+                int64_t bi = b + brot;
+                if (bi >= nbands) bi -= nbands;
+                return (ilo + bi * band + (int64_t)w * RT) * TR - shift + (int64_t)lane * VEC;
+            };
+            Vec<T> xa[RT], xb[RT], b0[RT][CB], b1[RT][CB];
+            auto load_x = [&](Vec<T>(&xv)[RT], int64_t r) {
+#pragma unroll
+                for (int t = 0; t < RT; ++t) xv[t] = load_cached(x + r + t * TR);
+            };
+            auto load_block = [&](Vec<T>(&buf)[RT][CB], int64_t r, int blk) {
+#pragma unroll
+                for (int cc = 0; cc < CB; ++cc)
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) buf[t][cc] = load_stream(col[blk * CB + cc] + r + t * TR);
+            };
+            auto compute_block = [&](const Vec<T>(&buf)[RT][CB], const Vec<T>(&xv)[RT], int blk) {
+#pragma unroll
+                for (int cc = 0; cc < CB; ++cc)
+#pragma unroll
+                    for (int t = 0; t < RT; ++t)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) fma_op<CONJ>(acc[blk * CB + cc], buf[t][cc].e[v], xv[t].e[v]);
+            };
+            int64_t r = band_row(0);
+            load_x(xa, r);
+            load_block(b0, r, 0);
+            for (int64_t b = 0; b < nbands; ++b) {
+                const int64_t rn = b + 1 < nbands ? band_row(b + 1) : r;
+#pragma unroll
+                for (int blk = 0; blk < NBLK; blk += 2) {
+                    load_block(b1, r, blk + 1);
+                    compute_block(b0, xa, blk);
+                    if (blk + 2 < NBLK) {
+                        load_block(b0, r, blk + 2);
+                    } else if (b + 1 < nbands) {
+                        load_x(xb, rn);
+                        load_block(b0, rn, 0);
+                    }
+                    compute_block(b1, xa, blk + 1);
+                }
+#pragma unroll
+                for (int t = 0; t < RT; ++t) xa[t] = xb[t];
+                r = rn;
+            }
+            ilo_rest = ilo + nbands * band;
+            ni_rest = ni - nbands * band;
+        }
+    }
+
     // The waves take the interior tiles round robin, starting at a tile that
     // depends on the column group: workgroups that run at the same time then
     // sit at different row offsets (with a power-of-two leading dimension equal
     // row offsets of different columns share few L2 sets).  The rotation depends
     // only on the arguments, so results stay reproducible.
-    const int64_t rot = (ni > 0 && !WCOLS) ? ((int64_t)blockIdx.x * 37) % ni : 0;
-    const int64_t cnt = ni > w ? (ni - w + NW - 1) / NW : 0;   // tiles of this wave
+    const int64_t rot = (ni_rest > 0 && !WCOLS) ? (gx * 37) % ni_rest : 0;
+    const int64_t cnt = ni_rest > w ? (ni_rest - w + NW - 1) / NW : 0;   // tiles of this wave
     {
         Vec<T> x0, x1, b0[NC], b1[NC];
         auto load_tile = [&](Vec<T>& xv, Vec<T>(&buf)[NC], int64_t k) {
             int64_t i = w + k * NW + rot;
-            if (i >= ni) i -= ni;
-            const int64_t r = (ilo + i) * TR - shift + (int64_t)lane * VEC;
+            if (i >= ni_rest) i -= ni_rest;
+            const int64_t r = (ilo_rest + i) * TR - shift + (int64_t)lane * VEC;
             xv = load_cached(x + r);
 #pragma unroll
             for (int c = 0; c < NC; ++c) buf[c] = load_stream(col[c] + r);
@@ -403,6 +471,8 @@ __global__ __launch_bounds__(NW_ * WAVE) void gemv_t_kernel(GemvArgs<T> a) {
             }
         }
     }
+    if (!WCOLS && gx + gridDim.x < ngroups) __syncthreads();   // red is written again for the next group
+    }
 }
 
 // ------------------------------------------------------------- host side ----
@@ -411,6 +481,7 @@ constexpr int GN_NW = 4;                // GEMV-N: waves per workgroup
 constexpr int GN_LOADS = 8;             // GEMV-N: 16-byte loads per lane and prefetch block (columns x tiles)
 constexpr int GN_WGS_PER_CU = 2;        // GEMV-N: workgroups per compute unit the column split aims at
 constexpr int GT_NC = 8, GT_NW = 4;     // GEMV-T: columns per workgroup, waves per workgroup
+constexpr int GT_BAND = GT_NW * 4;      // GEMV-T: row tiles of a band (four consecutive tiles per wave)
 constexpr int64_t MAX_SPLITS = 256;
 constexpr int64_t SHORT_T_TILES = 2;         // GEMV-T: up to this many row tiles every wave owns its columns
 constexpr int64_t DEFAULT_WG_TARGET = 2048;   // about 8 workgroups per compute unit
@@ -481,6 +552,8 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
     constexpr int TR = tile_rows<T>();
     GemvPlan<T> p;
     p.row_tiles = 1;
+    p.t_groups = 0;
+    p.t_wgs = 0;
     const bool sizing = (A == nullptr);
     // the caller's tuning values, plus the measured settings of this size where the caller left the choice open
     const Tuning tn = sizing || !classes ? tuning() : tuned(notrans ? 'N' : 'T', prec_char<T>(), m, n, lda * (int64_t)sizeof(T));
@@ -615,11 +688,31 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
             sa = ceil_div(512, g);
             if (sa < 4) sa = 4;
         }
+        // From 192 groups on: while a group of columns holds less than about 600 KB, eight row splits (many short
+        // workgroups that start and end at different times) beat one workgroup per group or per compute unit, whose
+        // pipelines all fill and drain together: 8-19% in s for n = 5120 ... 11264, 3-8% up to 15360, 7-11% in d at
+        // 3072 ... 7168, 6% in z at 3072 (sweep over n = 2048 ... 20480 in steps of 1024, splits 1 ... 16, with and
+        // without the one-workgroup-per-compute-unit form).  Not when the column stride is 16 KB or a multiple of
+        // 32 KB: the splits then start in the same memory channels and lose up to 25%, and the unsplit form is the
+        // best there (odd multiples of 16 KB from 48 KB on behave like any other stride).
+        const double group_bytes = (double)m * GT_NC * sizeof(T);
+        const int64_t stride_bytes = lda * (int64_t)sizeof(T);
+        if (g >= 192 && !sizing && stride_bytes != 16384 && stride_bytes % 32768 != 0 && group_bytes >= 96e3 && group_bytes < 600e3)
+            sa = 8;
         s = tn.gemv_t_splits > 0 ? tn.gemv_t_splits
                                        : (tn.wg_target > 0 ? ceil_div(tn.wg_target, g) : sa);
         const int64_t cap = p.ntiles / (2 * GT_NW) > 1 ? p.ntiles / (2 * GT_NW) : 1;   // two tiles per wave at least
         if (s > cap) s = cap;
         p.part_stride = partial_stride<T>(n);
+        p.t_groups = p.period * ceil_div(ceil_div(n > 0 ? n : 1, p.period), (int64_t)GT_NC);
+        // One workgroup per compute unit, each taking every 256th group of columns, instead of one workgroup per
+        // group: never slower, 3-7% faster around n = 6000 ... 8000, 1-3% up to 16384, below 1% beyond (s, d, c at
+        // n = 6144 ... 49152; 192 workgroups, the best count of the non-transposed kernel, lose 1-4% here, 384 lose 6%).
+        p.t_wgs = tn.gemv_t_wgs;
+        if (p.t_wgs <= 0 && !sizing && s == 1) {
+            const int64_t cus = device_cus();
+            if (cus > 0 && p.t_groups >= 2 * cus) p.t_wgs = cus;
+        }
     }
     if (s > max_splits) s = max_splits;
     if (s < 1) s = 1;
@@ -692,11 +785,17 @@ template <class T> hipError_t launch_gemv_t(const GemvArgs<T>& a, bool conj, hip
     } else {
         // with alignment classes every class gets its own column groups
         const int64_t P = a.plan.period > 1 ? a.plan.period : 1;
-        const dim3 grid((unsigned)(P * ceil_div(ceil_div(a.n, P), GT_NC)), (unsigned)a.plan.splits, (unsigned)batch);
-        if (conj && Traits<T>::cplx)
-            hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
-        else
-            hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        const int64_t groups = P * ceil_div(ceil_div(a.n, P), GT_NC);
+        if (a.plan.t_groups > 0 && a.plan.t_groups != groups) return hipErrorInvalidValue;
+        const int64_t wgs = a.plan.t_groups > 0 && a.plan.t_wgs > 0 && a.plan.t_wgs < groups ? a.plan.t_wgs : groups;
+        const dim3 grid((unsigned)wgs, (unsigned)a.plan.splits, (unsigned)batch);
+        // the banded instance when a split holds a band of tiles at least
+        const bool bands = a.plan.ntiles / a.plan.splits >= GT_BAND;
+        const bool cj = conj && Traits<T>::cplx;
+        if (bands && cj) hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false, false, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        else if (bands) hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, false, false, true>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        else if (cj) hipLaunchKernelGGL((gemv_t_kernel<T, true, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
+        else hipLaunchKernelGGL((gemv_t_kernel<T, false, GT_NC, GT_NW, false>), grid, dim3(GT_NW * WAVE), 0, s, a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.plan.splits == 1) return e;

@@ -16,6 +16,7 @@ struct Tuning {
     int64_t gemv_n_splits = 0;     // column splits of GEMV-N
     int64_t gemv_t_splits = 0;     // row splits of GEMV-T
     int64_t gemv_n_row_tiles = 0;  // GEMV-N row tiles per wave: 1, 2 or 4
+    int64_t gemv_t_wgs = 0;        // GEMV-T: workgroups of the main kernel (each takes several column groups); 0 = planner
     int64_t gemv_short = 0;        // kernels for matrices of a few row tiles: 1 = never, 2 = whenever possible
     int64_t gemv_align_classes = 0;   // columns grouped by their alignment when lda is no multiple of 128 bytes: 1 = never, 2 = always
     int64_t symv_tiles_per_wave = 0;  // SYMV row-chunk height in units of 4 row tiles: 1 or 2
@@ -97,6 +98,8 @@ template <class T> struct GemvPlan {
     // its row tiles on THEIR 128-byte boundary (the kernel works the shift out from the class's first column);
     // shift and ntiles above then describe the class with the largest shift.  1 = all columns alike.
     int64_t period;
+    int64_t t_groups;     // T: column groups of the main kernel (0: one per workgroup, as launched),
+    int64_t t_wgs;        //    workgroups that share them (0 or >= t_groups: one group each)
     int64_t part_off;     // slot of row 0 in a partial vector of GEMV-N
     int64_t part_stride;  // elements between consecutive partial vectors
     size_t xpack_off, partial_off, total_bytes;   // workspace layout

@@ -237,6 +237,16 @@ def test_split_variants_agree_with_oracle():
                 k.set_tuning(key, s)
                 _, err, _ = gemv_case("d", trans, 2100, 1900, 0.7, 0.3, seed=15)
                 check("d", err, f"{key}={s}")
+        # GEMV-T with fewer workgroups than column groups (each takes several), alone, with row splits, and with
+        # alignment classes
+        for wgs, splits, lda in ((1, 0, 2100), (7, 0, 2100), (100, 3, 2100), (192, 0, 2100), (5, 2, 2111)):
+            k.set_tuning("gemv_t_wgs", wgs)
+            k.set_tuning("gemv_t_splits", splits)
+            for prec, trans in (("d", "T"), ("c", "C"), ("s", "T")):
+                _, err, _ = gemv_case(prec, trans, 2100, 1900, 0.7, 0.3, lda=lda, seed=17)
+                check(prec, err, f"gemv_t_wgs={wgs} splits={splits} lda={lda} {prec}gemv {trans}")
+        k.set_tuning("gemv_t_wgs", 0)
+        k.set_tuning("gemv_t_splits", 0)
         # columns grouped by alignment class (leading dimension no multiple of 128 bytes), forced on for small
         # and ragged shapes, with few and many splits, classes with no column at all (n below the period)
         k.set_tuning("gemv_align_classes", 2)
