@@ -635,10 +635,16 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
             if (s4 > cap) s4 = 0;
             const bool big = (double)m * (double)n * sizeof(T) >= 256.0 * 1024 * 1024;
             const bool rows_even = sizeof(T) == 4 ? p.ntiles % (GN_NW * 4) == 0 : p.ntiles * 100 >= rb4 * GN_NW * 4 * 85;
-            if (p.period == 1 && big && rows_even && s4 >= 1 && rb4 * s4 * 100 >= cus * (on_grid ? 68 : 85)) {
+            // 4-byte elements on the grid whose first or last row tile is cut (a sub-block pointer, a ragged row
+            // count): the waves that own the cut tiles pay four selects per load for every column, and with one
+            // workgroup per compute unit the round waits for them (SGEMV-N on the 16383 x 16383 block at (1, 1) of a
+            // 16384 x 16384 matrix: 192 us in this form, 160-164 us with two workgroups per compute unit; the wider
+            // types lose nothing: 307 us either way).  They take the general rule below.
+            const bool cut4 = sizeof(T) == 4 && on_grid && (p.shift != 0 || (m + p.shift) % TR != 0);
+            if (p.period == 1 && big && rows_even && !cut4 && s4 >= 1 && rb4 * s4 * 100 >= cus * (on_grid ? 68 : 85)) {
                 p.row_tiles = 4;
                 s = s4;
-            } else if (p.period == 1 && big && cus > 0) {
+            } else if (p.period == 1 && big && cus > 0 && !cut4) {
                 // The same regime for the sizes that rule leaves out (ragged row counts, leading dimensions off
                 // the 128-byte grid): still ONE workgroup per compute unit, with the tiles per wave that waste the
                 // least of the single round - score = share of the compute units that get a workgroup x share of
