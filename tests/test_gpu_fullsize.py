@@ -132,6 +132,21 @@ def test_subblock_every_output():
     free()
 
 
+@pytest.mark.parametrize("prec", "sc")
+def test_large_subblocks_on_the_grid(prec):
+    """blocks of more than 256 MB at (1, 1) and (33, 5) of a parent whose leading dimension is a multiple of 128 bytes,
+    with ragged row counts: the planner's large-matrix forms with a shifted row grid and cut first and last tiles
+    (4-byte elements leave the one-workgroup-per-compute-unit form of GEMV-N there), NaN around the block"""
+    n, lda = (9000, 9056) if prec == "s" else (6100, 6144)
+    for row_off, col_off in ((1, 1), (33, 5)):
+        m = lda - row_off - 7
+        for trans in ("N", "C" if prec == "c" else "T"):
+            _, err, _ = gemv_case(prec, trans, m, n, 0.7, 0.3, lda=lda, row_off=row_off, col_off=col_off, seed=23,
+                                  sample=samples(m if trans == "N" else n, 3))
+            check(prec, err, f"{prec}gemv {trans} {m}x{n} block at ({row_off}, {col_off}), lda={lda}")
+        free()
+
+
 def test_release_parent_host_copy():
     _parent_host.clear()
     free()
