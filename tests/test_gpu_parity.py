@@ -684,6 +684,27 @@ def test_random_shapes_against_oracle(prec):
         check(prec, err, f"case {case}: symv/hemv {prec} {uplo} n={n} off={off} pad={pad} inc={incx},{incy}")
 
 
+@pytest.mark.parametrize("prec", PRECS)
+def test_mid_size_shapes_against_oracle(prec):
+    """seeded shapes of 4000 ... 9000 rows and columns with odd leading dimensions and offsets: the sizes at which the
+    transposed kernel changes between its forms (row splits, one workgroup per compute unit, banded loop) and the
+    non-transposed one between its split rules; sampled outputs against the oracle"""
+    rng = np.random.default_rng({"s": 31, "d": 32, "c": 33, "z": 34}[prec])
+    for case in range(10):
+        m = int(rng.integers(4000, 9000))
+        n = int(rng.integers(4000, 9000))
+        off = int(rng.choice([0, 0, 1, 16, 33]))
+        pad = int(rng.choice([0, 0, 5, 32, 96]))
+        if case % 3 == 0:       # a leading dimension on the 128-byte grid
+            pad += (-(m + off + pad)) % 32
+        trans = ("N", "T", "C")[case % 3] if prec in "cz" else ("N", "T")[case % 2]
+        alpha, beta = scalars(prec, 0.7, 0.3)
+        leny = m if trans == "N" else n
+        _, err, _ = gemv_case(prec, trans, m, n, alpha, beta, lda=m + off + pad, row_off=off, col_off=off % 7, seed=300 + case,
+                              sample=wl.sample_indices(leny, 64, case).numpy())
+        check(prec, err, f"case {case}: {prec}gemv {trans} {m}x{n} off={off} pad={pad}")
+
+
 def test_calls_can_be_captured_in_a_graph():
     """the entry points only enqueue kernels (no allocation, no memset, no host
     synchronisation), so a sequence of calls can be recorded once and replayed;
