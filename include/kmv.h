@@ -451,10 +451,13 @@ void kmv_partition(int64_t W, int64_t Y, int64_t y, int64_t* w, int64_t* s);
  *   kind 0 "read"  : sum-reduce a[0..n)   (reads  n*8 bytes)
  *   kind 1 "copy"  : b[i] = a[i]          (moves 2*n*8 bytes)
  *   kind 2 "triad" : c[i] = a[i] + s*b[i] (moves 3*n*8 bytes)
+ *   kind 3 "read, few workgroups": kind 0 in the launch shape of the fastest
+ *                    matrix kernel - 192 workgroups (or the tuning value
+ *                    wg_target), 16 vector loads in flight per lane
  * over n doubles.  a, b, c: device pointers to n doubles each (b, c may be
- * NULL for kind 0; c for kind 1); `sink` a device pointer to at least 8192
- * doubles (kind 0 writes per-workgroup sums there).  Returns 0 or an error
- * code as above. */
+ * NULL for kinds 0 and 3; c for kind 1); `sink` a device pointer to at least
+ * 8192 doubles (kinds 0 and 3 write per-workgroup sums there).  Returns 0 or
+ * an error code as above. */
 int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c, double* sink, void* stream);
 
 /* ---- Tuning values for sweeps (Section 9: the tuning parameters are kept

@@ -632,8 +632,9 @@ void kmv_partition(int64_t W, int64_t Y, int64_t y, int64_t* w, int64_t* s) {
 }
 
 int kmv_stream_probe(int kind, int64_t n, const double* a, double* b, double* c, double* sink, void* stream) {
-    if (kind < 0 || kind > 2 || n < 0) return -1;
-    if (!a || (kind == 0 && !sink) || (kind >= 1 && !b) || (kind == 2 && !c)) return KMV_ERR_NULL;
+    if (kind < 0 || kind > 3 || n < 0) return -1;
+    const bool reads = kind == 0 || kind == 3;
+    if (!a || (reads && !sink) || (!reads && !b) || (kind == 2 && !c)) return KMV_ERR_NULL;
     return hip_code(launch_stream_probe(kind, n, a, b, c, sink, static_cast<hipStream_t>(stream)));
 }
 

@@ -126,6 +126,43 @@ __global__ __launch_bounds__(256) void probe_read(const d2* __restrict__ a, int6
     __syncthreads();
     if (threadIdx.x == 0) sink[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
+// the same with 16 loads in flight per lane (two sets of 8, the next set issued before the current one is summed)
+__global__ __launch_bounds__(256) void probe_read_deep(const d2* __restrict__ a, int64_t nvec, double* __restrict__ sink) {
+    int64_t w, s;
+    partition(ceil_div(nvec, 2048), gridDim.x, blockIdx.x, w, s);   // units of 2048 vectors = 32 KiB
+    const int64_t beg = s * 2048, end = (s + w) * 2048 < nvec ? (s + w) * 2048 : nvec;
+    d2 acc[8], b0[8], b1[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] = d2{0, 0};
+    int64_t i = beg + threadIdx.x;
+    auto load = [&](d2(&buf)[8], int64_t at) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) buf[u] = __builtin_nontemporal_load(a + at + u * 256);
+    };
+    auto add = [&](const d2(&buf)[8]) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u] += buf[u];
+    };
+    const int64_t nfull = (end - beg) / 2048;     // whole blocks of 2048 vectors
+    if (nfull > 0) load(b0, i);
+    for (int64_t k = 0; k < nfull; k += 2) {
+        if (k + 1 < nfull) load(b1, i + (k + 1) * 2048);
+        add(b0);
+        if (k + 1 < nfull) {
+            if (k + 2 < nfull) load(b0, i + (k + 2) * 2048);
+            add(b1);
+        }
+    }
+    for (int64_t r = i + nfull * 2048; r < end; r += 256) acc[0] += __builtin_nontemporal_load(a + r);
+    d2 t = acc[0];
+#pragma unroll
+    for (int u = 1; u < 8; ++u) t += acc[u];
+    double r = wave_sum(t.x + t.y);
+    __shared__ double red[4];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = r;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
 __global__ __launch_bounds__(256) void probe_copy(const d2* __restrict__ a, d2* __restrict__ b, int64_t nvec) {
     int64_t w, s;
     partition(ceil_div(nvec, 1024), gridDim.x, blockIdx.x, w, s);
@@ -156,6 +193,12 @@ hipError_t launch_stream_probe(int kind, int64_t n, const double* a, double* b, 
     if (nvec <= 0) return hipSuccess;
     int64_t wg = ceil_div(nvec, 1024);
     if (wg > PROBE_WG) wg = PROBE_WG;
+    if (kind == 3) {     // the read probe in the matrix kernels' best launch shape: few workgroups, deep prefetch
+        const int64_t want = tuning().wg_target > 0 ? tuning().wg_target : 192;
+        if (wg > want) wg = want;
+        hipLaunchKernelGGL(probe_read_deep, dim3((unsigned)wg), dim3(256), 0, s, reinterpret_cast<const d2*>(a), nvec, sink);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)wg), block(256);
     if (kind == 0)
         hipLaunchKernelGGL(probe_read, grid, block, 0, s, reinterpret_cast<const d2*>(a), nvec, sink);

@@ -705,6 +705,33 @@ def test_mid_size_shapes_against_oracle(prec):
         check(prec, err, f"case {case}: {prec}gemv {trans} {m}x{n} off={off} pad={pad}")
 
 
+@pytest.mark.parametrize("n", [2, 2048, 1_000_002, 40_000_000])
+def test_stream_probe_moves_what_it_says(n):
+    """the calibration kernels (STREAM read / copy / triad, and the read pass with few workgroups) really read and write
+    every element: the per-workgroup sums add up to the array's sum, the copy and the triad equal their definitions"""
+    k = kmv()
+    g = torch.Generator(device=DEV).manual_seed(n)
+    a = torch.randint(-8, 9, (n,), generator=g, device=DEV).to(torch.float64)     # sums are exact in any order
+    b = torch.full((n,), float("nan"), dtype=torch.float64, device=DEV)
+    c = torch.full((n,), float("nan"), dtype=torch.float64, device=DEV)
+    want = float(a.sum().item())
+    for kind, wgs in ((0, 0), (3, 0), (3, 7), (3, 8192)):
+        sink = torch.zeros(8192, dtype=torch.float64, device=DEV)
+        k.set_tuning("wg_target", wgs)
+        try:
+            k.stream_probe(kind, n, a, None, None, sink)
+        finally:
+            k.set_tuning("wg_target", 0)
+        torch.cuda.synchronize()
+        assert float(sink.sum().item()) == want, (kind, wgs)
+    k.stream_probe(1, n, a, b, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(b, a)
+    k.stream_probe(2, n, a, b, c, None)
+    torch.cuda.synchronize()
+    assert torch.equal(c, a + 3.0 * b)
+
+
 def test_calls_can_be_captured_in_a_graph():
     """the entry points only enqueue kernels (no allocation, no memset, no host
     synchronisation), so a sequence of calls can be recorded once and replayed;
