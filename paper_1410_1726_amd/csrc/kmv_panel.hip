@@ -858,7 +858,6 @@ int sytrd_panel(char uplo, int64_t n, int64_t nb, T* A, int64_t lda, typename Tr
                 int64_t ldw, void* ws, size_t wsb, void* stream) {
     using R = typename Traits<T>::real;
     constexpr bool CPLX = Traits<T>::cplx;
-    constexpr char TC = CPLX ? 'C' : 'T';
     const bool lower = (uplo == 'L' || uplo == 'l');
     if (!lower && uplo != 'U' && uplo != 'u') return -1;
     if (n < 0) return -2;

@@ -110,7 +110,7 @@ __host__ __device__ __forceinline__ void piece_groups(int p, int C, int n, int s
 // the unit is used), so nothing between issuing a unit's loads and using the
 // unit before it waits for memory.
 template <class T, bool HERM, bool LOWER, int NC, int KT, int G, int NW>
-__global__ __launch_bounds__(NW * WAVE, KT == 1 ? 3 : 2) void symv_balanced_kernel(SymvArgs<T> a, SymvShares sh) {
+__global__ __launch_bounds__(NW * WAVE, KT == 1 ? (G <= 8 ? 3 : (G <= 12 ? 2 : 1)) : 2) void symv_balanced_kernel(SymvArgs<T> a, SymvShares sh) {
     constexpr int VEC = Traits<T>::VEC;
     constexpr int TR = WAVE * VEC;
     constexpr int C = NC * NW;
@@ -574,7 +574,6 @@ __global__ __launch_bounds__(NW * WAVE) void symv_member_kernel(SymvArgs<T> a) {
     const T* __restrict__ x = a.x;
     const T* __restrict__ A = a.A;
     T* y = a.y;
-    const int ntiles = (n + TR - 1) / TR;
 
     __shared__ T rowsum[MAXT * TR];   // N parts, all waves
     __shared__ T colsum[MAXT * TR];   // T parts, one writer per column
