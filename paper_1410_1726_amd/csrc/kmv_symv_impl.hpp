@@ -37,6 +37,8 @@ namespace kmv {
 namespace {
 constexpr int SY_NW = 4;    // waves per workgroup
 constexpr int RED_ROWS = 16, RED_PARTS = 16;
+// final pass of the balanced kernel: rows per workgroup (a row group is read with one 128-byte access at least)
+template <class T> constexpr int red_rows() { return sizeof(T) == 4 ? 32 : 16; }
 }  // namespace
 
 // first / one-past-last row tile that a panel's stored part touches
@@ -819,17 +821,18 @@ __global__ __launch_bounds__(TINY_NW * WAVE) void symv_tiny_kernel(SymvArgs<T> a
 
 // y_i = alpha * ( sum over the workgroups whose share touches the chunk of row i of their row-sum
 // vectors + sum over chunks of wst[panel(i)][chunk][i] + the pairs left to this pass ) + beta*y_i.
-// blockDim = (RED_ROWS, RED_PARTS): part g adds the vectors g, g+RED_PARTS, ... and then the chunks
-// kbeg+g, kbeg+g+RED_PARTS, ... in ascending order; the parts meet in LDS and are added in part
-// order, so the result does not depend on scheduling.
+// blockDim = (RR, RP) with RR = 16 rows (32 for 4-byte elements, so that a row group is one 128-byte access) and
+// RP = 256 / RR parts: part g adds the vectors g, g+RP, ... and then the chunks kbeg+g, kbeg+g+RP, ... in ascending
+// order; the parts meet in LDS and are added in part order, so the result does not depend on scheduling.
 template <class T, bool HERM, bool LOWER>
-__global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvArgs<T> a, SymvOwners owners) {
+__global__ __launch_bounds__(256) void symv_reduce_kernel(SymvArgs<T> a, SymvOwners owners) {
     constexpr int TR = tile_rows<T>();
+    constexpr int RR = red_rows<T>(), RP = 256 / RR;
     const int lx = threadIdx.x, g = threadIdx.y;
-    const int64_t i = (int64_t)blockIdx.x * RED_ROWS + lx;
+    const int64_t i = (int64_t)blockIdx.x * RR + lx;
     const int shift = a.plan.shift;
     const int64_t C = a.plan.panel_cols;
-    __shared__ T part[RED_PARTS][RED_ROWS];
+    __shared__ T part[RP][RR];
     T s = zero_of<T>();
     if (i < a.n) {
         {
@@ -841,7 +844,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
             const int64_t ylo = owners.first[k], yhi = owners.last[k];
             const T* __restrict__ wsn = a.wsn + (slot - tbeg * TR);
 #pragma unroll 4
-            for (int64_t yy = ylo + g; yy <= yhi; yy += RED_PARTS) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
+            for (int64_t yy = ylo + g; yy <= yhi; yy += RP) s = add_of(s, wsn[(yy + k) * a.plan.rows_padded]);
         }
         // chunks whose row tiles intersect the tile range of the panel of column i
         const int64_t pi = i / C;
@@ -851,7 +854,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
         const int64_t kend = (thi - 1 + a.plan.chunk_off) / a.plan.chunk_tiles + 1;
         const T* __restrict__ wst = a.wst + pi * a.plan.nchunks * C + (i - pi * C);
 #pragma unroll 4
-        for (int64_t k = kbeg + g; k < kend; k += RED_PARTS) s = add_of(s, wst[k * C]);
+        for (int64_t k = kbeg + g; k < kend; k += RP) s = add_of(s, wst[k * C]);
         // The balanced kernel leaves two kinds of pairs to this pass: those whose row lies in the same aligned
         // group of VEC rows as the column's diagonal element (the groups of the lanes' 16-byte vectors: rows
         // m*VEC - shift ...), and the VEC - 1 columns at the tip of the triangle that hold fewer than VEC stored
@@ -881,7 +884,7 @@ __global__ __launch_bounds__(RED_ROWS * RED_PARTS) void symv_reduce_kernel(SymvA
     if (g == 0 && i < a.n) {
         T tot = part[0][lx];
 #pragma unroll
-        for (int gg = 1; gg < RED_PARTS; ++gg) tot = add_of(tot, part[gg][lx]);
+        for (int gg = 1; gg < RP; ++gg) tot = add_of(tot, part[gg][lx]);
         T* yp = a.y + i * a.incy;
         *yp = epilogue(scalar_of(a.alpha, a.alpha_dev), tot, scalar_of(a.beta, a.beta_dev), yp);
     }
@@ -1287,8 +1290,8 @@ hipError_t launch_symv_kind(const SymvArgs<T>& a, bool lower, hipStream_t s, int
     if (!ok) return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 rgrid((unsigned)ceil_div(a.n, RED_ROWS));
-    const dim3 rblock(RED_ROWS, RED_PARTS);
+    const dim3 rgrid((unsigned)ceil_div(a.n, (int64_t)red_rows<T>()));
+    const dim3 rblock(red_rows<T>(), 256 / red_rows<T>());
     if (lower) hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, true>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
     else hipLaunchKernelGGL((symv_reduce_kernel<T, HERM, false>), rgrid, rblock, 0, s, a, a.plan.bal->owners);
     return hipGetLastError();
