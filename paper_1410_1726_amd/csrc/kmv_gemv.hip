@@ -44,13 +44,17 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
     // moved to where the lane's existing rows expect them
     int64_t rl[RT];
     int dsh[RT];
+    int cut[RT];            // wave uniform: the tile is cut by the first or the last row (only those pay for the moves)
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
         rl[t] = r[t];
         dsh[t] = 0;
+        cut[t] = 0;
         if (EDGE) {
             rl[t] = r[t] < 0 ? 0 : (r[t] + VEC > a.m ? a.m - VEC : r[t]);
             dsh[t] = (int)(r[t] - rl[t]);
+            const int64_t r0 = r[t] - (int64_t)(threadIdx.x & (WAVE - 1)) * VEC;
+            cut[t] = __builtin_amdgcn_readfirstlane((int)(r0 < 0 || r0 + WAVE * VEC > a.m));
         }
     }
     Vec<T> b0[U][RT], b1[U][RT];
@@ -70,7 +74,8 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
-                const Vec<T> v = EDGE ? shift_elems(buf[u][t], dsh[t]) : buf[u][t];
+                Vec<T> v = buf[u][t];
+                if (EDGE && cut[t]) v = shift_elems(v, dsh[t]);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) fma_acc(acc[t][e], v.e[e], xb[u]);
             }
@@ -92,7 +97,7 @@ __device__ __forceinline__ void gemv_n_walk(const GemvArgs<T>& a, const int64_t 
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
             Vec<T> v = load_stream(A + j * lda + rl[t]);
-            if (EDGE) v = shift_elems(v, dsh[t]);
+            if (EDGE && cut[t]) v = shift_elems(v, dsh[t]);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) fma_acc(acc[t][e], v.e[e], xj);
         }
