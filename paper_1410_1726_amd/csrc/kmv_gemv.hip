@@ -643,7 +643,7 @@ template <class T> GemvPlan<T> plan_gemv(bool notrans, int64_t m, int64_t n, con
             // 4-byte elements on the grid whose first or last row tile is cut (a sub-block pointer, a ragged row
             // count): the waves that own the cut tiles pay four selects per load for every column, and with one
             // workgroup per compute unit the round waits for them (SGEMV-N on the 16383 x 16383 block at (1, 1) of a
-            // 16384 x 16384 matrix: 192 us in this form, 160-164 us with two workgroups per compute unit; the wider
+            // 16384 x 16384 matrix: 173 us in this form, 160-164 us with two workgroups per compute unit; the wider
             // types lose nothing: 307 us either way).  They take the general rule below.
             const bool cut4 = sizeof(T) == 4 && on_grid && (p.shift != 0 || (m + p.shift) % TR != 0);
             if (p.period == 1 && big && rows_even && !cut4 && s4 >= 1 && rb4 * s4 * 100 >= cus * (on_grid ? 68 : 85)) {
